@@ -1,0 +1,153 @@
+"""Seeded synthetic inputs for ReLU linear attention over video token sequences.
+
+This module serves both the CPU oracle's tests and the HIP path's tests and
+benchmarks.  It holds no arithmetic of the method itself: only the workload
+shapes, the random draw, and the storage format of the drawn values (bf16 bit
+patterns or fp32).
+
+The five workloads stand in for the paper's video resolutions (Sec. 4.1 and the
+latency tables): 480x832x81 and 720x1280x81 clips tokenised to 21x30x52 and
+21x45x80 latent tokens, and the one-minute block-autoregressive stream of
+Sec. 3.3.3.  Real activations are not available, so every tensor is i.i.d.
+Gaussian, drawn as documented in `draw_qkv`.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+
+__all__ = [
+    "Workload", "WORKLOADS", "workload", "draw_qkv", "draw_block",
+    "draw_tensors", "f32_to_bf16_bits", "bf16_bits_to_f32", "as_f32",
+]
+
+
+@dataclass(frozen=True)
+class Workload:
+    """Shape of one benchmark/parity configuration.
+
+    `n_blocks == 0` means a bidirectional layer over N tokens; otherwise the
+    sequence is `n_blocks` consecutive blocks of `N` tokens each, attended
+    block-causally with a carried state.
+    """
+    name: str
+    B: int
+    H: int
+    N: int          # tokens per head (per block when n_blocks > 0)
+    d: int
+    dtype: str      # "bf16" or "f32"
+    scale: float    # values are scale * N(0, 1)
+    seed: int
+    n_blocks: int = 0
+    per_block_seed: bool = False
+    eps: float = 1e-6
+
+    @property
+    def elem_bytes(self) -> int:
+        return 2 if self.dtype == "bf16" else 4
+
+    @property
+    def head_tokens(self) -> int:
+        """Head-tokens in one pass (one block for block workloads)."""
+        return self.B * self.H * self.N
+
+    @property
+    def algorithmic_bytes(self) -> int:
+        """Q, K, V read once and O written once (per block for block workloads)."""
+        return 4 * self.head_tokens * self.d * self.elem_bytes
+
+    @property
+    def algorithmic_flops(self) -> int:
+        """(4 d^2 + 4 d) per head-token: two d x d contractions, key sum,
+        denominator dot product and the final scale."""
+        return self.head_tokens * (4 * self.d * self.d + 4 * self.d)
+
+
+WORKLOADS = {
+    # 4 latent frames x 16 x 16 tokens, fp32 validation mode
+    "tiny_f32": Workload("tiny_f32", B=1, H=2, N=4 * 16 * 16, d=32, dtype="f32",
+                         scale=1.0, seed=1001),
+    # 480p-like bidirectional layer
+    "bidir_480p": Workload("bidir_480p", B=1, H=32, N=21 * 30 * 52, d=64,
+                           dtype="bf16", scale=0.5, seed=1002),
+    # 720p-like bidirectional layer, conditional + unconditional pair
+    "bidir_720p": Workload("bidir_720p", B=2, H=32, N=21 * 45 * 80, d=64,
+                           dtype="bf16", scale=0.5, seed=1003),
+    # block-causal, 10 blocks of 3 latent frames x 30 x 52
+    "block_480p": Workload("block_480p", B=1, H=32, N=3 * 30 * 52, d=64,
+                           dtype="bf16", scale=0.5, seed=1004, n_blocks=10),
+    # minute-length stream, 80 blocks of 3 latent frames x 45 x 80
+    "stream_720p": Workload("stream_720p", B=1, H=32, N=3 * 45 * 80, d=64,
+                            dtype="bf16", scale=0.5, seed=5000, n_blocks=80,
+                            per_block_seed=True),
+}
+
+
+def workload(name: str) -> Workload:
+    return WORKLOADS[name]
+
+
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round fp32 to bf16 (nearest, ties to even); returns the uint16 patterns.
+
+    Finite inputs only (the generators never produce NaN or Inf).
+    """
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    bias = np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))
+    return ((u + bias) >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
+    """Exact widening of bf16 bit patterns to fp32."""
+    return (np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32)
+            << np.uint32(16)).view(np.float32)
+
+
+def _store(x: np.ndarray, dtype: str) -> np.ndarray:
+    if dtype == "bf16":
+        return f32_to_bf16_bits(x)
+    if dtype == "f32":
+        return np.ascontiguousarray(x, dtype=np.float32)
+    raise ValueError(f"unknown dtype {dtype!r}")
+
+
+def draw_tensors(seed: int, shape, scale: float, dtype: str, count: int = 3):
+    """`count` tensors of `shape`, drawn one after another from one
+    `numpy.random.Generator(PCG64(seed))` as float32 standard normals in C
+    order, multiplied by `scale` in fp32, then stored as `dtype`
+    ("bf16": uint16 bit patterns, "f32": float32)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    out = []
+    for _ in range(count):
+        x = rng.standard_normal(size=shape, dtype=np.float32)
+        if scale != 1.0:
+            x *= np.float32(scale)
+        out.append(_store(x, dtype))
+    return out
+
+
+def draw_qkv(w: Workload):
+    """Q, K, V for a bidirectional workload, or for the WHOLE sequence of a
+    block workload whose blocks share one seed (shape [B][H][n_blocks*N][d];
+    block m is tokens [m*N, (m+1)*N)).  Drawn in the order Q, K, V."""
+    if w.per_block_seed:
+        raise ValueError("per-block-seed workloads are drawn with draw_block")
+    n = w.N * max(1, w.n_blocks)
+    return draw_tensors(w.seed, (w.B, w.H, n, w.d), w.scale, w.dtype)
+
+
+def draw_block(w: Workload, m: int):
+    """Q, K, V of block m ([B][H][N][d]) of a block workload."""
+    if w.n_blocks <= 0 or not 0 <= m < w.n_blocks:
+        raise ValueError("block index out of range")
+    if w.per_block_seed:
+        return draw_tensors(w.seed + m, (w.B, w.H, w.N, w.d), w.scale, w.dtype)
+    q, k, v = draw_qkv(w)
+    sl = slice(m * w.N, (m + 1) * w.N)
+    return [np.ascontiguousarray(t[:, :, sl, :]) for t in (q, k, v)]
+
+
+def as_f32(x: np.ndarray, dtype: str) -> np.ndarray:
+    """The stored values as fp32, exactly (bf16 bits are widened)."""
+    return bf16_bits_to_f32(x) if dtype == "bf16" else np.asarray(x, np.float32)
