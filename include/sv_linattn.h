@@ -1,0 +1,120 @@
+/*
+ * sv_linattn.h - C ABI of the MI355X (gfx950) ReLU linear-attention library.
+ *
+ * The library computes, per (batch, head) pair independently,
+ *
+ *     phi(x) = max(x, 0)
+ *     S[k][v] = sum_j phi(K[j][k]) * V[j][v]        (d x d attention state)
+ *     z[k]    = sum_j phi(K[j][k])                  (key sum)
+ *     O[i][v] = (sum_k phi(Q[i][k]) S[k][v]) / (sum_k phi(Q[i][k]) z[k] + eps)
+ *
+ * which is the right-hand form of the linear-attention equation of Sec. 3.2 of
+ * the SANA-Video paper (arXiv 2509.24695) without RoPE, and its block-causal
+ * re-formulation of Sec. 3.3.1 in which earlier blocks enter only through the
+ * carried S and z (the constant-memory cache of Alg. 1).  eps is not in the
+ * paper's equations; it is added to the denominator after the dot product.
+ *
+ * Conventions common to every entry point
+ *  - All data pointers (Q, K, V, O, S, z, workspace) are DEVICE pointers on the
+ *    current HIP device.  Descriptors are HOST pointers and are read before the
+ *    call returns.  The library never allocates, frees or keeps a pointer.
+ *  - Token tensors are [B][H][N][d] with d contiguous; the other three strides
+ *    are given in elements.  Pointers must be 16-byte aligned and the strides
+ *    multiples of 16 bytes.  d must be 32 or 64.
+ *  - S is [B][H][d][d] fp32, row = key feature k, column = value feature v, so
+ *    that out = phi(Q) * S.  z is [B][H][d] fp32.  Both dense.
+ *  - SV_BF16 tokens: bf16 storage, bf16 MFMA products with fp32 accumulation,
+ *    outputs rounded to bf16 (nearest even).  SV_F32: fp32 validation mode,
+ *    plain fp32 arithmetic.
+ *  - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
+ *    default stream); nothing synchronises with the host.
+ *  - Every argument is checked on the host before anything is launched: a call
+ *    that returns an error other than SV_ERR_LAUNCH has not touched S, z or O.
+ *  - For fixed arguments the results are bit-reproducible: partial sums over
+ *    token chunks are combined in a fixed order, never with float atomics.
+ *  - Inputs must be finite; O must not alias Q, K or V.
+ */
+#ifndef SV_LINATTN_H
+#define SV_LINATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SV_OK = 0,
+    SV_ERR_NULL = 1,        /* a required pointer is NULL                           */
+    SV_ERR_SHAPE = 2,       /* B, H, N <= 0, stride_n < d, or overlapping strides    */
+    SV_ERR_UNSUPPORTED = 3, /* d not in {32, 64} or unknown dtype                    */
+    SV_ERR_ALIGN = 4,       /* pointer or stride not a multiple of 16 bytes          */
+    SV_ERR_RANGE = 5,       /* token range outside [0, N], or eps negative/non-finite */
+    SV_ERR_WORKSPACE = 6,   /* workspace smaller than sv_linattn_workspace_bytes()   */
+    SV_ERR_LAUNCH = 7       /* HIP reported an error while enqueuing                  */
+} sv_status;
+
+typedef enum { SV_BF16 = 0, SV_F32 = 1 } sv_dtype;
+
+/* Describes one token tensor (Q, K, V and O of a call share one descriptor). */
+typedef struct {
+    int32_t B, H, N, d;     /* N = tokens addressable through the pointer            */
+    int64_t stride_b;       /* elements between batches                               */
+    int64_t stride_h;       /* elements between heads                                 */
+    int64_t stride_n;       /* elements between tokens (>= d)                         */
+    int32_t dtype;          /* sv_dtype                                               */
+} sv_tensor_desc;
+
+/* Bytes of device workspace that sv_linattn_state / sv_block_linattn_step need
+ * for a call over n_tokens tokens per head.  Pure host function.  The value
+ * depends on B*H and d only (it is an upper bound over n_tokens), so a stream
+ * of blocks of any length reuses one allocation: the library-attributable
+ * memory of block-causal generation is this plus S and z, independent of the
+ * video length (Sec. 3.3.1, cost table).  Returns 0 for unsupported arguments. */
+size_t sv_linattn_workspace_bytes(int32_t B, int32_t H, int32_t n_tokens, int32_t d);
+
+/* State reduction (numerator and denominator brackets of the Sec. 3.2 equation;
+ * S_j and the key sum of Sec. 3.3.1) over tokens [tok_begin, tok_end):
+ *     accumulate == 0:  S, z  = sums            (overwritten)
+ *     accumulate != 0:  S, z += sums            (carried state updated in place)
+ * An empty range zero-fills (accumulate == 0) or leaves S, z unchanged.
+ * The token range is split over workgroups; their fp32 partial sums go through
+ * `workspace` and are combined in chunk order. */
+sv_status sv_linattn_state(const void *K, const void *V, const sv_tensor_desc *kv,
+                           int32_t tok_begin, int32_t tok_end, int accumulate,
+                           float *S, float *z,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+/* Apply (Sec. 3.2 equation, right-hand form; Sec. 3.3.1 first equality):
+ *     O[b][h][i][:] = phi(Q[b][h][i][:]) S[b][h] / (phi(Q[b][h][i][:]) . z[b][h] + eps)
+ * for i in [tok_begin, tok_end); other rows of O are not written.  O has the
+ * descriptor's shape, strides and dtype.  A row whose phi(Q) is all zero gives
+ * exactly 0 (0 / eps), never NaN, for eps > 0. */
+sv_status sv_linattn_apply(const void *Q, const sv_tensor_desc *q,
+                           int32_t tok_begin, int32_t tok_end,
+                           const float *S, const float *z, float eps,
+                           void *O, void *stream);
+
+/* One block of block-causal generation (Sec. 3.3.1; the cache update and use of
+ * Alg. 1): fold the block's keys and values into the carried state,
+ *     S += phi(K_b)^T V_b,   z += sum phi(K_b),
+ * then emit O_b from the UPDATED state, so that attention is full inside the
+ * block and causal towards earlier blocks.  `blk` describes Q_b, K_b, V_b and
+ * O_b (all N tokens of the descriptor form the block).  S and z are read and
+ * written in place; starting from all-zero S, z gives the first block. */
+sv_status sv_block_linattn_step(const void *Qb, const void *Kb, const void *Vb,
+                                const sv_tensor_desc *blk,
+                                float *S, float *z, float eps, void *Ob,
+                                void *workspace, size_t workspace_bytes, void *stream);
+
+/* Human-readable name of a status code (static storage). */
+const char *sv_status_string(int status);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int sv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SV_LINATTN_H */

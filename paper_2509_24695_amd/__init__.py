@@ -1,0 +1,11 @@
+"""MI355X (gfx950) ReLU linear attention for long video token sequences.
+
+Thin Python binding over libsvlinattn.so (hand-written HIP kernels behind a C
+ABI, declared in include/sv_linattn.h).  PyTorch is used by callers for device
+memory and streams only; every step of the computation runs in the library.
+"""
+from .binding import (  # noqa: F401
+    SV_BF16, SV_F32, SvError, TensorDesc, desc_of, library_path, load_library,
+    sv_block_linattn_step, sv_linattn_apply, sv_linattn_state,
+    sv_linattn_workspace_bytes, sv_status_string, sv_version, EXPORTS,
+)

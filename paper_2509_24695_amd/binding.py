@@ -1,0 +1,160 @@
+"""ctypes binding of libsvlinattn.so: argument marshalling only.
+
+The functions carry the names and argument order of the C ABI
+(include/sv_linattn.h).  Device buffers are torch tensors (or raw integer
+device addresses); nothing here computes, and there is no fallback: if the
+shared library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+SV_BF16, SV_F32 = 0, 1
+
+EXPORTS = (
+    "sv_linattn_workspace_bytes", "sv_linattn_state", "sv_linattn_apply",
+    "sv_block_linattn_step", "sv_status_string", "sv_version",
+)
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libsvlinattn.so")
+_lib = None
+
+
+class SvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = int(status)
+        super().__init__(f"{where}: {sv_status_string(status)} (status {int(status)})")
+
+
+class _CDesc(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int32), ("d", ctypes.c_int32),
+                ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_n", ctypes.c_int64),
+                ("dtype", ctypes.c_int32)]
+
+
+@dataclass
+class TensorDesc:
+    """Mirror of sv_tensor_desc: [B][H][N][d] token tensor, strides in elements."""
+    B: int
+    H: int
+    N: int
+    d: int
+    stride_b: int
+    stride_h: int
+    stride_n: int
+    dtype: int
+
+    def _c(self) -> _CDesc:
+        return _CDesc(self.B, self.H, self.N, self.d, self.stride_b, self.stride_h, self.stride_n, self.dtype)
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libsvlinattn.so; raises if it has not been built (no fallback path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2509_24695_amd.build` "
+            "(hipcc, --offload-arch=gfx950). There is no CPU or PyTorch fallback.")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    dp = ctypes.POINTER(_CDesc)
+    lib.sv_linattn_workspace_bytes.argtypes = [i32, i32, i32, i32]
+    lib.sv_linattn_workspace_bytes.restype = sz
+    lib.sv_linattn_state.argtypes = [vp, vp, dp, i32, i32, ctypes.c_int, vp, vp, vp, sz, vp]
+    lib.sv_linattn_state.restype = ctypes.c_int
+    lib.sv_linattn_apply.argtypes = [vp, dp, i32, i32, vp, vp, ctypes.c_float, vp, vp]
+    lib.sv_linattn_apply.restype = ctypes.c_int
+    lib.sv_block_linattn_step.argtypes = [vp, vp, vp, dp, vp, vp, ctypes.c_float, vp, vp, sz, vp]
+    lib.sv_block_linattn_step.restype = ctypes.c_int
+    lib.sv_status_string.argtypes = [ctypes.c_int]
+    lib.sv_status_string.restype = ctypes.c_char_p
+    lib.sv_version.argtypes = []
+    lib.sv_version.restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def _ptr(x):
+    """Device address of a torch tensor, or an integer address / None as given."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return ctypes.c_void_p(x)
+    return ctypes.c_void_p(x.data_ptr())
+
+
+def _nbytes(x) -> int:
+    return int(x.numel() * x.element_size())
+
+
+def _stream(stream):
+    if stream is None:
+        return None
+    if isinstance(stream, int):
+        return ctypes.c_void_p(stream)
+    return ctypes.c_void_p(stream.cuda_stream)       # torch.cuda.Stream
+
+
+def desc_of(t) -> TensorDesc:
+    """Descriptor of a 4-D torch tensor [B][H][N][d] (bf16 or fp32, last dim contiguous)."""
+    import torch
+    if t.dim() != 4 or t.stride(3) != 1:
+        raise ValueError("token tensors are [B][H][N][d] with d contiguous")
+    if t.dtype == torch.bfloat16:
+        dt = SV_BF16
+    elif t.dtype == torch.float32:
+        dt = SV_F32
+    else:
+        raise ValueError(f"unsupported dtype {t.dtype}")
+    B, H, N, d = t.shape
+    return TensorDesc(B, H, N, d, t.stride(0), t.stride(1), t.stride(2), dt)
+
+
+def sv_status_string(status: int) -> str:
+    return load_library().sv_status_string(int(status)).decode()
+
+
+def sv_version() -> int:
+    return int(load_library().sv_version())
+
+
+def sv_linattn_workspace_bytes(B: int, H: int, n_tokens: int, d: int) -> int:
+    return int(load_library().sv_linattn_workspace_bytes(B, H, n_tokens, d))
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise SvError(status, where)
+
+
+def sv_linattn_state(K, V, kv: TensorDesc, tok_begin: int, tok_end: int, accumulate: int, S, z,
+                     workspace, workspace_bytes: int | None = None, stream=None) -> None:
+    d = kv._c() if kv is not None else None
+    wb = _nbytes(workspace) if workspace_bytes is None else int(workspace_bytes)
+    _check(load_library().sv_linattn_state(_ptr(K), _ptr(V), ctypes.byref(d) if d else None, tok_begin, tok_end,
+                                           int(accumulate), _ptr(S), _ptr(z), _ptr(workspace), wb,
+                                           _stream(stream)), "sv_linattn_state")
+
+
+def sv_linattn_apply(Q, q: TensorDesc, tok_begin: int, tok_end: int, S, z, eps: float, O, stream=None) -> None:
+    d = q._c() if q is not None else None
+    _check(load_library().sv_linattn_apply(_ptr(Q), ctypes.byref(d) if d else None, tok_begin, tok_end, _ptr(S),
+                                           _ptr(z), float(eps), _ptr(O), _stream(stream)), "sv_linattn_apply")
+
+
+def sv_block_linattn_step(Qb, Kb, Vb, blk: TensorDesc, S, z, eps: float, Ob, workspace,
+                          workspace_bytes: int | None = None, stream=None) -> None:
+    d = blk._c() if blk is not None else None
+    wb = _nbytes(workspace) if workspace_bytes is None else int(workspace_bytes)
+    _check(load_library().sv_block_linattn_step(_ptr(Qb), _ptr(Kb), _ptr(Vb), ctypes.byref(d) if d else None,
+                                                _ptr(S), _ptr(z), float(eps), _ptr(Ob), _ptr(workspace), wb,
+                                                _stream(stream)), "sv_block_linattn_step")

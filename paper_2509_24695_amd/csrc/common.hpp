@@ -1,0 +1,79 @@
+// Shared device-side helpers for the gfx950 linear-attention kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sv {
+
+constexpr int kWave = 64;            // CDNA wavefront width
+constexpr int kThreads = 256;        // every kernel here runs 4 waves per workgroup
+constexpr int kWavesPerWg = kThreads / kWave;
+constexpr int kMaxChunks = 32;       // upper bound on token chunks per head (workspace sizing)
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef short s16x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Element strides of a [B][H][N][d] token tensor (d contiguous).
+struct TokStrides {
+    int64_t b, h, n;
+};
+
+// ---- bf16 <-> fp32 on raw bit patterns -------------------------------------------------
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+// Round to nearest even (hardware conversion on gfx950).
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float x) {
+    return __builtin_bit_cast(uint16_t, (__bf16)x);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    f32x2 f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+}
+
+// ReLU feature map on two packed bf16 values: a negative bf16 is a negative
+// int16, so a signed 16-bit max with zero clears it (and turns -0 into +0).
+__device__ __forceinline__ uint32_t relu_bf16x2(uint32_t w) {
+    const s16x2 zero = {0, 0};
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(s16x2, w), zero));
+}
+__device__ __forceinline__ u32x4 relu_bf16x8(u32x4 v) {
+    v.x = relu_bf16x2(v.x); v.y = relu_bf16x2(v.y); v.z = relu_bf16x2(v.z); v.w = relu_bf16x2(v.w);
+    return v;
+}
+
+// ---- typed scalar access used by the generic (any dtype) kernels --------------------------
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static __device__ __forceinline__ float load(const float *p) { return *p; }
+    static __device__ __forceinline__ void store(float *p, float x) { *p = x; }
+};
+template <> struct Elem<uint16_t> {   // bf16 bit patterns
+    static __device__ __forceinline__ float load(const uint16_t *p) { return bf16_bits_to_f32(*p); }
+    static __device__ __forceinline__ void store(uint16_t *p, float x) { *p = f32_to_bf16_bits(x); }
+};
+
+// Tiles of a token range are dealt to chunks as evenly as integers allow:
+// chunk c of C owns tiles [c*T/C, (c+1)*T/C).
+__host__ __device__ __forceinline__ int chunk_tile_begin(int c, int C, int T) {
+    return (int)(((int64_t)c * T) / C);
+}
+
+// Orders this wave's LDS traffic for the compiler; the hardware already executes
+// one wave's LDS instructions in issue order, so no s_barrier is involved.
+__device__ __forceinline__ void wave_lds_fence() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+}  // namespace sv

@@ -1,0 +1,150 @@
+// Plain fp32-arithmetic kernels for every supported (dtype, d) pair, and the
+// fixed-order partial-state reduction used by all paths.
+//
+// These serve the fp32 validation mode (results within 1e-5 of a float64
+// evaluation) and the bf16 shapes that have no MFMA kernel.  Products are fp32
+// FMAs in token order inside a chunk; chunks are combined by state_reduce.
+#pragma once
+
+#include "common.hpp"
+
+namespace sv {
+
+// Partial state of one token chunk of one head:
+//   ws[(bh*C + c)][k*D + v] = sum_{j in chunk c} phi(K[j][k]) V[j][v]     (Sec. 3.2, numerator bracket)
+//   ws[(bh*C + c)][D*D + k] = sum_{j in chunk c} phi(K[j][k])             (denominator bracket)
+// grid = (C, B*H), block = 256.  Tiles hold TT tokens; chunk c owns tiles
+// [c*T/C, (c+1)*T/C) of the T tiles that cover [t0, t1).
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void state_partial_generic(
+    const T *__restrict__ K, const T *__restrict__ V, TokStrides st, int H, int t0, int t1, int C,
+    float *__restrict__ ws)
+{
+    constexpr int TT = 32;
+    constexpr int EPT = D * D / kThreads;   // S elements per thread (one row segment)
+    constexpr int TPR = D / EPT;            // threads per S row
+    __shared__ float sK[TT][D];
+    __shared__ float sV[TT][D];
+
+    const int tid = threadIdx.x;
+    const int c = blockIdx.x, bh = blockIdx.y;
+    const int b = bh / H, h = bh % H;
+    const T *Kh = K + b * st.b + h * st.h;
+    const T *Vh = V + b * st.b + h * st.h;
+
+    const int n_tiles = (t1 - t0 + TT - 1) / TT;
+    const int tile_lo = chunk_tile_begin(c, C, n_tiles);
+    const int tile_hi = chunk_tile_begin(c + 1, C, n_tiles);
+
+    const int k = tid / TPR, v0 = (tid % TPR) * EPT;
+    float acc[EPT];
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) acc[e] = 0.f;
+    float zacc = 0.f;
+
+    for (int tile = tile_lo; tile < tile_hi; ++tile) {
+        const int tok0 = t0 + tile * TT;
+        for (int idx = tid; idx < TT * D; idx += kThreads) {
+            const int j = idx / D, f = idx % D;
+            const int tok = tok0 + j;
+            float kv = 0.f, vv = 0.f;
+            if (tok < t1) {
+                kv = fmaxf(Elem<T>::load(Kh + (int64_t)tok * st.n + f), 0.f);   // phi = ReLU
+                vv = Elem<T>::load(Vh + (int64_t)tok * st.n + f);
+            }
+            sK[j][f] = kv;
+            sV[j][f] = vv;
+        }
+        __syncthreads();
+#pragma unroll 4
+        for (int j = 0; j < TT; ++j) {
+            const float a = sK[j][k];
+            zacc += a;
+#pragma unroll
+            for (int e = 0; e < EPT; ++e) acc[e] = fmaf(a, sV[j][v0 + e], acc[e]);
+        }
+        __syncthreads();
+    }
+
+    float *out = ws + ((int64_t)bh * C + c) * (D * D + D);
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) out[k * D + v0 + e] = acc[e];
+    if (tid % TPR == 0) out[D * D + k] = zacc;
+}
+
+// S, z (+)= sum over chunks of the partial states, in chunk order:
+//   x = accumulate ? old : 0;  for c = 0..C-1: x += ws[bh][c][e]
+// The fixed order makes the result bit-reproducible (no float atomics).
+// grid = (ceil((D*D+D)/256), B*H).  C == 0 zero-fills or leaves the state as is.
+template <int D>
+__global__ __launch_bounds__(kThreads) void state_reduce(
+    const float *__restrict__ ws, int C, int accumulate, float *__restrict__ S, float *__restrict__ z)
+{
+    constexpr int E = D * D + D;
+    const int e = blockIdx.x * kThreads + threadIdx.x;
+    const int bh = blockIdx.y;
+    if (e >= E) return;
+    float *dst = e < D * D ? S + (int64_t)bh * D * D + e : z + (int64_t)bh * D + (e - D * D);
+    float x = accumulate ? *dst : 0.f;
+    const float *p = ws + (int64_t)bh * C * E + e;
+    for (int c = 0; c < C; ++c) x += p[(int64_t)c * E];
+    *dst = x;
+}
+
+// O[i][v] = (sum_k phi(Q[i][k]) S[k][v]) / (sum_k phi(Q[i][k]) z[k] + eps)   (Sec. 3.2, right-hand form)
+// grid = (C, B*H), block = 256.  The head's S and z stay in LDS for the whole
+// token range of the workgroup.
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void apply_generic(
+    const T *__restrict__ Q, T *__restrict__ O, TokStrides st, int H, int t0, int t1, int C,
+    const float *__restrict__ S, const float *__restrict__ z, float eps)
+{
+    constexpr int VPT = 4;                   // outputs per thread
+    constexpr int TPT = D / VPT;             // threads per token
+    constexpr int TT = kThreads / TPT;       // tokens per tile
+    __shared__ float sS[D][D];
+    __shared__ float sz[D];
+    __shared__ float sQ[TT][D];
+
+    const int tid = threadIdx.x;
+    const int c = blockIdx.x, bh = blockIdx.y;
+    const int b = bh / H, h = bh % H;
+    const T *Qh = Q + b * st.b + h * st.h;
+    T *Oh = O + b * st.b + h * st.h;
+
+    for (int idx = tid; idx < D * D; idx += kThreads) sS[idx / D][idx % D] = S[(int64_t)bh * D * D + idx];
+    if (tid < D) sz[tid] = z[(int64_t)bh * D + tid];
+
+    const int n_tiles = (t1 - t0 + TT - 1) / TT;
+    const int tile_lo = chunk_tile_begin(c, C, n_tiles);
+    const int tile_hi = chunk_tile_begin(c + 1, C, n_tiles);
+    const int j = tid / TPT, v0 = (tid % TPT) * VPT;
+
+    for (int tile = tile_lo; tile < tile_hi; ++tile) {
+        const int tok0 = t0 + tile * TT;
+        __syncthreads();
+        for (int idx = tid; idx < TT * D; idx += kThreads) {
+            const int jj = idx / D, f = idx % D;
+            const int tok = tok0 + jj;
+            sQ[jj][f] = tok < t1 ? fmaxf(Elem<T>::load(Qh + (int64_t)tok * st.n + f), 0.f) : 0.f;
+        }
+        __syncthreads();
+        float num[VPT] = {0.f, 0.f, 0.f, 0.f};
+        float den = 0.f;
+#pragma unroll 8
+        for (int k = 0; k < D; ++k) {
+            const float q = sQ[j][k];
+            den = fmaf(q, sz[k], den);
+#pragma unroll
+            for (int e = 0; e < VPT; ++e) num[e] = fmaf(q, sS[k][v0 + e], num[e]);
+        }
+        const int tok = tok0 + j;
+        if (tok < t1) {
+            const float dd = den + eps;
+#pragma unroll
+            for (int e = 0; e < VPT; ++e) Elem<T>::store(Oh + (int64_t)tok * st.n + v0 + e, num[e] / dd);
+        }
+    }
+}
+
+}  // namespace sv

@@ -1,0 +1,247 @@
+"""GPU parity: the HIP library, called through its C ABI, against the float64
+CPU oracle on the same seeded inputs, element by element.
+
+Tolerances (written out in sv_workloads.metrics.TOL): bf16 tokens -- max
+relative error 2e-2 and relative L2 error 5e-3 on O; fp32 validation mode --
+1e-5 on both.  S and z are fp32 sums of exactly representable products in both
+modes and are held to the 1e-5 class everywhere.
+"""
+import numpy as np
+import pytest
+
+import paper_2509_24695_amd as sv
+import sv_workloads as wl
+from oracle import linattn_oracle as orc
+from sv_workloads import metrics
+from tests.gpu_util import gpu_bidirectional, new_state, new_workspace, say, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+STATE_TOL = 1e-5
+
+
+def _draw(seed, B, H, N, d, dtype, scale=0.5):
+    return wl.draw_tensors(seed, (B, H, N, d), scale, dtype)
+
+
+def _check_state(S, z, S_ref, z_ref, what):
+    for name, g, r in (("S", S, S_ref), ("z", z, z_ref)):
+        g = to_host(g)
+        assert np.isfinite(g).all(), f"{what}: non-finite {name}"
+        assert metrics.rel_l2(g, r) <= STATE_TOL, f"{what}: {name} rel_l2 {metrics.rel_l2(g, r)}"
+        assert metrics.max_rel(g, r) <= STATE_TOL, f"{what}: {name} max_rel {metrics.max_rel(g, r)}"
+
+
+# ---- configuration 1: fp32 validation mode ---------------------------------------------------
+
+def test_tiny_f32_bidirectional():
+    w = wl.workload("tiny_f32")
+    say(f"{w.name} B={w.B} H={w.H} N={w.N} d={w.d} f32")
+    Q, K, V = wl.draw_qkv(w)
+    O_ref, S_ref, z_ref = orc.bidirectional(Q, K, V, w.eps)
+    O, S, z = gpu_bidirectional(to_dev(Q), to_dev(K), to_dev(V), w.eps)
+    _check_state(S, z, S_ref, z_ref, w.name)
+    metrics.check(to_host(O), O_ref, "f32", w.name)
+
+
+# ---- small shapes: several tiles, ragged tails, both dtypes and head dims ----------------------
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 64), ("bf16", 32), ("f32", 64), ("f32", 32)])
+@pytest.mark.parametrize("B,H,N", [(1, 1, 1), (1, 2, 7), (2, 3, 33), (1, 2, 100), (1, 4, 1000), (2, 2, 4681)])
+def test_bidirectional_small(dtype, d, B, H, N):
+    say(f"bidirectional_small dtype={dtype} d={d} B={B} H={H} N={N}")
+    Q, K, V = _draw(7000 + N, B, H, N, d, dtype)
+    O_ref, S_ref, z_ref = orc.bidirectional(Q, K, V, 1e-6)
+    O, S, z = gpu_bidirectional(to_dev(Q), to_dev(K), to_dev(V), 1e-6)
+    _check_state(S, z, S_ref, z_ref, "state")
+    metrics.check(to_host(O), O_ref, dtype, "O")
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 64), ("f32", 32)])
+def test_state_range_and_accumulate(dtype, d):
+    """Token ranges and accumulate semantics; chunked sums equal the one-shot sum."""
+    import torch
+    B, H, N = 2, 3, 3000
+    say(f"state_range_and_accumulate dtype={dtype} d={d}")
+    _, K, V = _draw(7100, B, H, N, d, dtype)
+    Kd, Vd = to_dev(K), to_dev(V)
+    dsc = sv.desc_of(Kd)
+    ws = new_workspace(B, H, N, d)
+    S, z = new_state(B, H, d)
+    edges = [0, 1, 18, 18, 1500, 2999, 3000]          # includes an empty range
+    for a, b in zip(edges[:-1], edges[1:]):
+        sv.sv_linattn_state(Kd, Vd, dsc, a, b, 1, S, z, ws)
+    torch.cuda.synchronize()
+    S_ref, z_ref = orc.state(K, V)
+    _check_state(S, z, S_ref, z_ref, "accumulated")
+    # a strict sub-range, overwrite mode
+    sv.sv_linattn_state(Kd, Vd, dsc, 37, 2050, 0, S, z, ws)
+    torch.cuda.synchronize()
+    S_ref, z_ref = orc.state(K, V, 37, 2050)
+    _check_state(S, z, S_ref, z_ref, "sub-range")
+    # empty range, overwrite mode: zero fill
+    sv.sv_linattn_state(Kd, Vd, dsc, 5, 5, 0, S, z, ws)
+    torch.cuda.synchronize()
+    assert not to_host(S).any() and not to_host(z).any()
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 64), ("f32", 32)])
+def test_apply_range_leaves_other_rows_untouched(dtype, d):
+    import torch
+    B, H, N = 1, 2, 500
+    say(f"apply_range dtype={dtype} d={d}")
+    Q, K, V = _draw(7200, B, H, N, d, dtype)
+    O_ref, S_ref, z_ref = orc.bidirectional(Q, K, V, 1e-6)
+    Qd = to_dev(Q)
+    Sd = torch.from_numpy(S_ref.astype(np.float32)).cuda()
+    zd = torch.from_numpy(z_ref.astype(np.float32)).cuda()
+    O = torch.full_like(Qd, 7.0)
+    sv.sv_linattn_apply(Qd, sv.desc_of(Qd), 33, 401, Sd, zd, 1e-6, O)
+    torch.cuda.synchronize()
+    Oh = to_host(O)
+    assert (Oh[:, :, :33] == 7.0).all() and (Oh[:, :, 401:] == 7.0).all()
+    metrics.check(Oh[:, :, 33:401], O_ref[:, :, 33:401], dtype, "O range")
+
+
+def test_strided_token_layout():
+    """[B][N][H][d] memory (a projection's natural output) through the strides."""
+    import torch
+    B, H, N, d = 2, 4, 300, 64
+    say("strided_token_layout")
+    Q, K, V = _draw(7300, B, H, N, d, "bf16")
+    O_ref, S_ref, z_ref = orc.bidirectional(Q, K, V, 1e-6)
+
+    def bnhd(x):          # same logical tensor, physical layout [B][N][H][d]
+        return to_dev(x).permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+
+    Qd, Kd, Vd = bnhd(Q), bnhd(K), bnhd(V)
+    assert Qd.stride() == (N * H * d, d, H * d, 1)
+    S, z = new_state(B, H, d)
+    ws = new_workspace(B, H, N, d)
+    O = torch.zeros_like(Qd)               # preserves the permuted strides
+    assert O.stride() == Qd.stride()
+    sv.sv_linattn_state(Kd, Vd, sv.desc_of(Kd), 0, N, 0, S, z, ws)
+    sv.sv_linattn_apply(Qd, sv.desc_of(Qd), 0, N, S, z, 1e-6, O)
+    torch.cuda.synchronize()
+    _check_state(S, z, S_ref, z_ref, "strided")
+    metrics.check(to_host(O), O_ref, "bf16", "strided O")
+
+
+# ---- degenerate rows -------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 64), ("f32", 32)])
+def test_degenerate_rows(dtype, d):
+    say(f"degenerate_rows dtype={dtype} d={d}")
+    B, H, N = 1, 2, 70
+    Q, K, V = (wl.as_f32(t, dtype) for t in _draw(7400, B, H, N, d, dtype))
+    Q[0, 0, 3] = -np.abs(Q[0, 0, 3]) - 0.5          # a query with phi(Q) = 0
+    Q[0, 1, 69] = -np.abs(Q[0, 1, 69]) - 0.5
+    K[0, 1] = -np.abs(K[0, 1]) - 0.5                # a head whose keys are all negative
+    store = (lambda x: wl.f32_to_bf16_bits(x)) if dtype == "bf16" else (lambda x: x)
+    Q, K, V = store(Q), store(K), store(V)
+    O_ref, S_ref, z_ref = orc.bidirectional(Q, K, V, 1e-6)
+    O, S, z = gpu_bidirectional(to_dev(Q), to_dev(K), to_dev(V), 1e-6)
+    Oh, Sh, zh = to_host(O), to_host(S), to_host(z)
+    assert np.isfinite(Oh).all()
+    assert not Oh[0, 0, 3].any() and not Oh[0, 1].any()
+    assert not Sh[0, 1].any() and not zh[0, 1].any()
+    metrics.check(Oh, O_ref, dtype, "degenerate O")
+
+
+# ---- block-causal stream -----------------------------------------------------------------------
+
+def _gpu_stream(blocks, eps, B, H, d):
+    """Runs sv_block_linattn_step over host blocks; returns per-block O (host), final S, z."""
+    import torch
+    S, z = new_state(B, H, d)
+    ws = new_workspace(B, H, max(b[0].shape[2] for b in blocks), d)
+    outs = []
+    for (Q, K, V) in blocks:
+        Qd, Kd, Vd = to_dev(Q), to_dev(K), to_dev(V)
+        O = torch.empty_like(Qd)
+        sv.sv_block_linattn_step(Qd, Kd, Vd, sv.desc_of(Qd), S, z, eps, O, ws)
+        torch.cuda.synchronize()
+        outs.append(to_host(O))
+    return outs, S, z
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 64), ("f32", 32)])
+def test_block_stream_small(dtype, d):
+    B, H = 1, 3
+    sizes = [130, 1, 64, 333, 17]
+    say(f"block_stream_small dtype={dtype} d={d} sizes={sizes}")
+    blocks = [_draw(7500 + i, B, H, n, d, dtype) for i, n in enumerate(sizes)]
+    outs, S, z = _gpu_stream(blocks, 1e-6, B, H, d)
+    S_ref = z_ref = None
+    for i, (O_ref, S_ref, z_ref) in enumerate(orc.block_stream(blocks, 1e-6)):
+        metrics.check(outs[i], O_ref, dtype, f"block {i}")
+    _check_state(S, z, S_ref, z_ref, "final state")
+
+
+def test_single_block_equals_bidirectional_bitwise():
+    """One block from the empty cache is the bidirectional layer (same kernels, same order)."""
+    import torch
+    B, H, N, d = 1, 4, 2000, 64
+    say("single_block_equals_bidirectional")
+    Q, K, V = _draw(7600, B, H, N, d, "bf16")
+    Qd, Kd, Vd = to_dev(Q), to_dev(K), to_dev(V)
+    O1, S1, z1 = gpu_bidirectional(Qd, Kd, Vd, 1e-6)
+    S2, z2 = new_state(B, H, d)
+    O2 = torch.empty_like(Qd)
+    sv.sv_block_linattn_step(Qd, Kd, Vd, sv.desc_of(Qd), S2, z2, 1e-6, O2, new_workspace(B, H, N, d))
+    torch.cuda.synchronize()
+    assert torch.equal(S1, S2) and torch.equal(z1, z2)
+    assert torch.equal(O1.view(torch.int16), O2.view(torch.int16))
+
+
+def test_determinism_and_resume():
+    """Two runs are bit-identical; stopping, saving (S, z) to the host and resuming in fresh
+    buffers continues bit-identically (the carried state is the whole context)."""
+    import torch
+    B, H, d = 1, 8, 64
+    sizes = [700, 700, 700, 700]
+    say("determinism_and_resume")
+    blocks = [_draw(7700 + i, B, H, n, d, "bf16") for i, n in enumerate(sizes)]
+    outs1, S1, z1 = _gpu_stream(blocks, 1e-6, B, H, d)
+    outs2, S2, z2 = _gpu_stream(blocks, 1e-6, B, H, d)
+    assert torch.equal(S1, S2) and torch.equal(z1, z2)
+    assert all(np.array_equal(a, b) for a, b in zip(outs1, outs2))
+    # resume after two blocks
+    _, Sa, za = _gpu_stream(blocks[:2], 1e-6, B, H, d)
+    Sh, zh = Sa.cpu(), za.cpu()
+    del Sa, za
+    S, z = Sh.cuda(), zh.cuda()
+    ws = new_workspace(B, H, 700, d)
+    for i in (2, 3):
+        Qd, Kd, Vd = (to_dev(t) for t in blocks[i])
+        O = torch.empty_like(Qd)
+        sv.sv_block_linattn_step(Qd, Kd, Vd, sv.desc_of(Qd), S, z, 1e-6, O, ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_host(O), outs1[i])
+    assert torch.equal(S, S1) and torch.equal(z, z1)
+
+
+def test_workspace_and_state_bytes_do_not_depend_on_length():
+    sizes = {sv.sv_linattn_workspace_bytes(1, 32, n, 64) for n in (1, 4680, 10800, 864000)}
+    assert len(sizes) == 1
+
+
+# ---- error paths reach the caller before any launch ----------------------------------------------
+
+def test_errors_leave_outputs_untouched():
+    import torch
+    B, H, N, d = 1, 2, 64, 64
+    say("error paths")
+    Q, K, V = (to_dev(t) for t in _draw(7800, B, H, N, d, "bf16"))
+    S, z = new_state(B, H, d)
+    S.fill_(3.0)
+    ws = new_workspace(B, H, N, d)
+    dsc = sv.desc_of(K)
+    with pytest.raises(sv.SvError) as e:
+        sv.sv_linattn_state(K, V, dsc, 10, 65, 0, S, z, ws)
+    assert e.value.status == 5
+    with pytest.raises(sv.SvError) as e:
+        sv.sv_linattn_state(K, V, dsc, 0, N, 0, S, z, ws, workspace_bytes=16)
+    assert e.value.status == 6
+    torch.cuda.synchronize()
+    assert (S == 3.0).all()

@@ -1,0 +1,110 @@
+"""Host-side checks that need no GPU: the shared library loads, exports every
+symbol the header declares, and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2509_24695_amd as sv
+from paper_2509_24695_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "sv_linattn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sv_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    if not os.path.exists(sv.library_path()):
+        from paper_2509_24695_amd import build
+        build.build()
+    lib = ctypes.CDLL(sv.library_path())
+    declared = _declared_symbols()
+    assert set(declared) == set(sv.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert sv.sv_version() >= 100
+
+
+def test_status_strings():
+    assert sv.sv_status_string(0) == "ok"
+    assert len({sv.sv_status_string(i) for i in range(8)}) == 8
+
+
+def test_workspace_bytes():
+    assert sv.sv_linattn_workspace_bytes(1, 32, 4680, 64) == sv.sv_linattn_workspace_bytes(1, 32, 864000, 64)
+    assert sv.sv_linattn_workspace_bytes(1, 32, 100, 64) >= 32 * (64 * 64 + 64) * 4
+    assert sv.sv_linattn_workspace_bytes(1, 32, 100, 48) == 0
+    assert sv.sv_linattn_workspace_bytes(0, 32, 100, 64) == 0
+
+
+FAKE = 0x10000          # aligned, never dereferenced: every call below fails before a launch
+
+
+def _desc(**kw):
+    base = dict(B=1, H=2, N=128, d=64, stride_b=2 * 128 * 64, stride_h=128 * 64, stride_n=64, dtype=sv.SV_BF16)
+    base.update(kw)
+    return sv.TensorDesc(**base)
+
+
+@pytest.mark.parametrize("kwargs,status", [
+    (dict(d=48), 3), (dict(dtype=5), 3), (dict(N=0), 2), (dict(B=0), 2), (dict(stride_n=32), 2),
+    (dict(stride_n=68), 4), (dict(stride_h=128 * 64 + 4), 4),
+])
+def test_bad_descriptors(kwargs, status):
+    with pytest.raises(sv.SvError) as e:
+        sv.sv_linattn_state(FAKE, FAKE, _desc(**kwargs), 0, 1, 0, FAKE, FAKE, FAKE, workspace_bytes=1 << 30)
+    assert e.value.status == status
+    with pytest.raises(sv.SvError) as e:
+        sv.sv_linattn_apply(FAKE, _desc(**kwargs), 0, 1, FAKE, FAKE, 1e-6, FAKE)
+    assert e.value.status == status
+    with pytest.raises(sv.SvError) as e:
+        sv.sv_block_linattn_step(FAKE, FAKE, FAKE, _desc(**kwargs), FAKE, FAKE, 1e-6, FAKE, FAKE,
+                                 workspace_bytes=1 << 30)
+    assert e.value.status == status
+
+
+def test_null_range_alignment_workspace_eps():
+    d = _desc()
+    big = 1 << 30
+    with pytest.raises(sv.SvError) as e:
+        sv.sv_linattn_state(None, FAKE, d, 0, 1, 0, FAKE, FAKE, FAKE, workspace_bytes=big)
+    assert e.value.status == 1
+    with pytest.raises(sv.SvError) as e:
+        sv.sv_linattn_state(FAKE, FAKE, None, 0, 1, 0, FAKE, FAKE, FAKE, workspace_bytes=big)
+    assert e.value.status == 1
+    for t0, t1 in [(-1, 4), (5, 4), (0, 129)]:
+        with pytest.raises(sv.SvError) as e:
+            sv.sv_linattn_state(FAKE, FAKE, d, t0, t1, 0, FAKE, FAKE, FAKE, workspace_bytes=big)
+        assert e.value.status == 5
+        with pytest.raises(sv.SvError) as e:
+            sv.sv_linattn_apply(FAKE, d, t0, t1, FAKE, FAKE, 1e-6, FAKE)
+        assert e.value.status == 5
+    with pytest.raises(sv.SvError) as e:
+        sv.sv_linattn_state(FAKE + 8, FAKE, d, 0, 1, 0, FAKE, FAKE, FAKE, workspace_bytes=big)
+    assert e.value.status == 4
+    with pytest.raises(sv.SvError) as e:
+        sv.sv_linattn_state(FAKE, FAKE, d, 0, 1, 0, FAKE, FAKE, FAKE, workspace_bytes=1024)
+    assert e.value.status == 6
+    for eps in (-1.0, float("nan"), float("inf")):
+        with pytest.raises(sv.SvError) as e:
+            sv.sv_linattn_apply(FAKE, d, 0, 1, FAKE, FAKE, eps, FAKE)
+        assert e.value.status == 5
+        with pytest.raises(sv.SvError) as e:
+            sv.sv_block_linattn_step(FAKE, FAKE, FAKE, d, FAKE, FAKE, eps, FAKE, FAKE, workspace_bytes=big)
+        assert e.value.status == 5
+
+
+def test_product_path_does_not_import_the_oracle():
+    """The library and its binding must never reach into oracle/ (no CPU fallback)."""
+    pkg = os.path.join(ROOT, "paper_2509_24695_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), f
+    assert binding.load_library() is not None
