@@ -1,0 +1,238 @@
+#!/usr/bin/env python3
+"""Benchmark of the MI355X linear-attention hot path.
+
+One "step" is one forward pass of the attention core of one layer over all
+heads of the workload: state reduction + fixed-order reduce + apply
+(bidirectional workloads), i.e. every token of Q, K, V read once and O written
+once.  Inputs are synthetic (i.i.d. Gaussian times 0.5, bf16), generated on the
+device and resident in HBM before the timed region starts; buffer sets rotate
+so that repeats are not served from the 256 MB Infinity Cache.
+
+Prints ONE JSON line.  `value` is tokens/s of the layer (B*N / time per step).
+`roofline` refers to the slower of the two kernels of a step (state-partial or
+apply), timed with HIP events on the launch stream inside the timed region.
+`cpu_baseline` is the float64 oracle timed on the host cores on the same
+workload.  Block-causal workloads are reported under `block_stream`.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+
+
+def _parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=60)
+    ap.add_argument("--warmup", type=int, default=6)
+    ap.add_argument("--workload", default="bidir_480p", choices=["bidir_480p", "bidir_720p"])
+    ap.add_argument("--sets", type=int, default=0, help="rotating buffer sets (0 = enough for > 1.5 GB)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-block-stream", action="store_true")
+    ap.add_argument("--stream-blocks", type=int, default=80)
+    return ap.parse_args()
+
+
+def _randn_bf16(shape, gen):
+    import torch
+    return (torch.randn(shape, device="cuda", dtype=torch.float32, generator=gen) * 0.5).to(torch.bfloat16)
+
+
+def bench_bidirectional(w, steps, warmup, n_sets, sv, torch):
+    B, H, N, d = w.B, w.H, w.N, w.d
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(w.seed)
+    if n_sets <= 0:
+        n_sets = max(2, -(-int(1.5e9) // w.algorithmic_bytes))
+    sets = []
+    for _ in range(n_sets):
+        q, k, v = (_randn_bf16((B, H, N, d), gen) for _ in range(3))
+        sets.append((q, k, v, torch.empty_like(q)))
+    S = torch.empty((B, H, d, d), dtype=torch.float32, device="cuda")
+    z = torch.empty((B, H, d), dtype=torch.float32, device="cuda")
+    ws = torch.empty(sv.sv_linattn_workspace_bytes(B, H, N, d), dtype=torch.uint8, device="cuda")
+    dsc = sv.desc_of(sets[0][0])
+    stream = torch.cuda.current_stream()
+
+    def step(i, ev=None):
+        q, k, v, o = sets[i % n_sets]
+        if ev:
+            ev[0].record(stream)
+        sv.sv_linattn_state(k, v, dsc, 0, N, 0, S, z, ws, stream=stream)
+        if ev:
+            ev[1].record(stream)
+        sv.sv_linattn_apply(q, dsc, 0, N, S, z, w.eps, o, stream=stream)
+        if ev:
+            ev[2].record(stream)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i, events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    t_state = [e[0].elapsed_time(e[1]) for e in events]      # ms
+    t_apply = [e[1].elapsed_time(e[2]) for e in events]
+    t_step_ev = [e[0].elapsed_time(e[2]) for e in events]
+    return {
+        "ms_per_step": wall / steps * 1e3,
+        "ms_state": statistics.mean(t_state), "ms_apply": statistics.mean(t_apply),
+        "ms_step_events_median": statistics.median(t_step_ev),
+        "n_sets": n_sets, "sets": sets,
+    }
+
+
+def bench_block_stream(w, n_blocks, sv, torch):
+    """Whole stream enqueued back to back, one event pair per block; no host sync inside."""
+    B, H, N, d = w.B, w.H, w.N, w.d
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(w.seed)
+    blocks = []
+    for _ in range(n_blocks):
+        q, k, v = (_randn_bf16((B, H, N, d), gen) for _ in range(3))
+        blocks.append((q, k, v, torch.empty_like(q)))
+    S = torch.zeros((B, H, d, d), dtype=torch.float32, device="cuda")
+    z = torch.zeros((B, H, d), dtype=torch.float32, device="cuda")
+    ws = torch.empty(sv.sv_linattn_workspace_bytes(B, H, N, d), dtype=torch.uint8, device="cuda")
+    lib_bytes = S.numel() * 4 + z.numel() * 4 + ws.numel()
+    dsc = sv.desc_of(blocks[0][0])
+    stream = torch.cuda.current_stream()
+
+    def run(events=None):
+        S.zero_()
+        z.zero_()
+        for m, (q, k, v, o) in enumerate(blocks):
+            if events:
+                events[m][0].record(stream)
+            sv.sv_block_linattn_step(q, k, v, dsc, S, z, w.eps, o, ws, stream=stream)
+            if events:
+                events[m][1].record(stream)
+
+    run()                                           # warm-up pass over the stream
+    torch.cuda.synchronize()
+    torch.cuda.reset_peak_memory_stats()
+    mem_before = torch.cuda.memory_allocated()
+    # pass 1: one event pair around the whole stream (throughput)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    S.zero_()
+    z.zero_()
+    torch.cuda.synchronize()
+    a.record(stream)
+    for (q, k, v, o) in blocks:
+        sv.sv_block_linattn_step(q, k, v, dsc, S, z, w.eps, o, ws, stream=stream)
+    b.record(stream)
+    torch.cuda.synchronize()
+    stream_ms = a.elapsed_time(b)
+    # pass 2: per-block latency
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in blocks]
+    run(events)
+    torch.cuda.synchronize()
+    lat = [e[0].elapsed_time(e[1]) * 1e3 for e in events]            # us
+    peak_extra = torch.cuda.max_memory_allocated() - mem_before
+    tail = lat[1:] if len(lat) > 1 else lat
+    med = statistics.median(tail)
+    xs = list(range(len(tail)))
+    mx, my = statistics.mean(xs), statistics.mean(tail)
+    slope = (sum((x - mx) * (y - my) for x, y in zip(xs, tail)) / max(1e-30, sum((x - mx) ** 2 for x in xs))
+             if len(tail) > 1 else 0.0)
+    per_block_us = stream_ms * 1e3 / n_blocks
+    return {
+        "workload": w.name, "blocks": n_blocks, "tokens_per_block": N,
+        "us_per_block_stream": per_block_us,
+        "tokens_per_s": B * N / (per_block_us * 1e-6),
+        "hbm_GBps": w.algorithmic_bytes / (per_block_us * 1e-6) / 1e9,
+        "hbm_frac": w.algorithmic_bytes / (per_block_us * 1e-6) / 1e9 / HBM_PEAK_GBPS,
+        "latency_us": {"first": lat[0], "min": min(tail), "median": med, "max": max(tail),
+                       "max_over_median": max(tail) / med, "slope_us_per_block": slope},
+        "library_bytes": lib_bytes, "peak_new_device_bytes_during_stream": int(peak_extra),
+    }
+
+
+def cpu_baseline(w, sets, torch):
+    """The float64 oracle on the host cores, on the full workload (one buffer set)."""
+    import numpy as np
+    from oracle import linattn_oracle as orc
+    q, k, v, _ = sets[0]
+    host = [t.view(torch.int16).cpu().numpy().view(np.uint16) for t in (q, k, v)]
+    f32 = [(h.astype(np.uint32) << np.uint32(16)).view(np.float32) for h in host]   # exact widening
+    best = None
+    t_all = time.perf_counter()
+    passes = 0
+    while passes < 3 and (time.perf_counter() - t_all) < 30.0:
+        t0 = time.perf_counter()
+        orc.bidirectional(f32[0], f32[1], f32[2], w.eps)
+        dt = time.perf_counter() - t0
+        best = dt if best is None else min(best, dt)
+        passes += 1
+    return {"value": w.B * w.N / best, "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"full {w.name} workload (B={w.B}, H={w.H}, N={w.N}, d={w.d}), best of {passes} passes, "
+                      f"{best:.3f} s per pass, float64",
+            "seconds_per_pass": best}
+
+
+def main():
+    args = _parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (the path is one GPU's share of the layer); "
+              "run it with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2509_24695_amd as sv
+    import sv_workloads as wl
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    sv.load_library()              # fails loudly when the HIP library is missing
+    torch.cuda.set_device(0)
+
+    w = wl.workload(args.workload)
+    r = bench_bidirectional(w, args.steps, args.warmup, args.sets, sv, torch)
+    sec = r["ms_per_step"] * 1e-3
+    half = w.algorithmic_bytes / 2          # state reads K,V; apply reads Q and writes O
+    dom = "state" if r["ms_state"] >= r["ms_apply"] else "apply"
+    dom_ms = max(r["ms_state"], r["ms_apply"])
+    achieved = half / (dom_ms * 1e-3) / 1e9
+    out = {
+        "metric": "linear-attention tokens/s per layer (fwd)",
+        "value": w.B * w.N / sec, "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": r["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: bidirectional ReLU linear attention, B={w.B} H={w.H} N={w.N} d={w.d}, "
+                               "bf16 tokens, fp32 state", "B": w.B, "H": w.H, "N": w.N, "d": w.d,
+                   "buffer_sets": r["n_sets"]},
+        "tflops": w.algorithmic_flops / sec / 1e12,
+        "hbm_GBps_step": w.algorithmic_bytes / sec / 1e9,
+        "hbm_frac_step": w.algorithmic_bytes / sec / 1e9 / HBM_PEAK_GBPS,
+        "kernels_ms": {"state(partial+reduce)": r["ms_state"], "apply": r["ms_apply"],
+                       "step_events_median": r["ms_step_events_median"]},
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "algorithmic_bytes_per_launch": half, "avg_launch_ms": dom_ms},
+    }
+    if not args.no_block_stream:
+        out["block_stream"] = [
+            bench_block_stream(wl.workload("block_480p"), 10, sv, torch),
+            bench_block_stream(wl.workload("stream_720p"), args.stream_blocks, sv, torch),
+        ]
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, r["sets"], torch)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

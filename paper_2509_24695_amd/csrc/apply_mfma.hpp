@@ -9,15 +9,17 @@
 // axis lands on the lanes of the accumulator: each lane ends up with 32
 // consecutive output features of ONE token and can normalise them with that
 // token's denominator and pack them into 64 contiguous bytes.  S^T is the A
-// operand; it is converted once per workgroup from fp32 into a bf16 hi + lo
-// pair (S = hi + lo to ~2^-17), staged through LDS, and then lives in registers
-// for the workgroup's whole token range.  phi(Q)^T is the B operand: a lane
+// operand; every wave loads it once, straight from global memory, splits each
+// fp32 value into a bf16 hi + lo pair (S = hi + lo to ~2^-17) and keeps it in
+// registers for its whole token range.  The key sum z rides along as two extra
+// operand rows (hi and lo), so the denominator comes out of the same MFMA pass
+// in fp32 and only has to be handed to the lane that holds the token's other
+// 32 features (one cross-lane exchange).  phi(Q)^T is the B operand: a lane
 // needs 8 consecutive features of one token, i.e. 16 contiguous bytes of the
-// token row.  Q tiles come in with coalesced 16-byte loads and pass through a
-// wave-private LDS tile to reach that layout; O tiles go back through the same
-// tile so that stores are coalesced too.  The denominator is a per-lane fp32
-// dot product over the lane's 32 features, completed by one cross-lane exchange
-// with the lane that holds the token's other 32 features.
+// token row.  Q tiles come in with coalesced non-temporal 16-byte loads and
+// pass through a wave-private LDS tile to reach that layout; O tiles go back
+// through the same tile so that stores are coalesced too.  No workgroup
+// barrier is needed anywhere.
 #pragma once
 
 #include "common.hpp"
@@ -25,164 +27,204 @@
 
 namespace sv {
 
-template <int TILE>
+constexpr int kApplyTile = 32;   // tokens per wave tile (the N dimension of the 32x32x16 MFMA)
+
 __device__ __forceinline__ void apply_tile_load(const uint16_t *Qh, int64_t stride_n, int tok0, int t1, int lane,
-                                                u32x4 (&qreg)[TILE / 8])
+                                                u32x4 (&qreg)[kApplyTile / 8])
 {
     const int col = lane & 7;
 #pragma unroll
-    for (int i = 0; i < TILE / 8; ++i) {
+    for (int i = 0; i < kApplyTile / 8; ++i) {
         const int tok = tok0 + (lane >> 3) + 8 * i;
         u32x4 q = {0u, 0u, 0u, 0u};
-        if (tok < t1) q = *reinterpret_cast<const u32x4 *>(Qh + (int64_t)tok * stride_n + col * 8);
+        if (tok < t1) q = load_stream16(Qh + (int64_t)tok * stride_n + col * 8);
         qreg[i] = q;
     }
 }
 
-// grid = (C, B*H), block = 256 (4 waves).  Chunk c owns tiles [c*T/C, (c+1)*T/C)
-// of the T = ceil((t1-t0)/32) tiles of 32 tokens; waves take tiles round-robin.
-// HILO = false drops the low half of S (one MFMA pass instead of two).
+// The state of one head as MFMA A operands, per lane (m = lane%32, g = lane/32).
+//   S rows: MFMA row m of row block rb stands for output feature
+//     F(rb, m) = 32*((m/4)%2) + 16*rb + 4*(m/8) + m%4,
+//   chosen so that accumulator register i of a lane in half g' = lane/32 is
+//   output feature 32*g' + 16*rb + i of the lane's token.
+//   z rows: row 0 = hi(z), row 1 = lo(z), rows 2..31 = 0.
 template <bool HILO>
-__global__ __launch_bounds__(kThreads, 2) void apply_mfma_d64(
+struct ApplyOperands {
+    static constexpr int NS = HILO ? 2 : 1;
+    bf16x8 s[NS][2][4];    // [hi/lo][row block][k-step]
+    bf16x8 zrow[4];        // [k-step]
+
+    __device__ __forceinline__ void load(const float *__restrict__ Sh, const float *__restrict__ zh, int lane)
+    {
+        const int m = lane & 31, g = lane >> 5;
+        float sv_[2][4][8];
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+            const int F = 32 * ((m >> 2) & 1) + 16 * rb + 4 * (m >> 3) + (m & 3);
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) sv_[rb][ks][i] = Sh[(16 * ks + 8 * g + i) * 64 + F];
+        }
+        float zv[4][8];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) zv[ks][i] = zh[16 * ks + 8 * g + i];
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                uint32_t hi[4], lo[4];
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    const float a = sv_[rb][ks][2 * p], b = sv_[rb][ks][2 * p + 1];
+                    hi[p] = pack_bf16x2(a, b);
+                    lo[p] = pack_bf16x2(a - bf16_lo(hi[p]), b - bf16_hi(hi[p]));
+                }
+                const u32x4 h4 = {hi[0], hi[1], hi[2], hi[3]}, l4 = {lo[0], lo[1], lo[2], lo[3]};
+                s[0][rb][ks] = __builtin_bit_cast(bf16x8, h4);
+                if (HILO) s[NS - 1][rb][ks] = __builtin_bit_cast(bf16x8, l4);
+            }
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            uint32_t w[4];
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const float a = zv[ks][2 * p], b = zv[ks][2 * p + 1];
+                const uint32_t hi = pack_bf16x2(a, b);
+                const uint32_t lo = pack_bf16x2(a - bf16_lo(hi), b - bf16_hi(hi));
+                w[p] = m == 0 ? hi : (m == 1 ? lo : 0u);
+            }
+            const u32x4 w4 = {w[0], w[1], w[2], w[3]};
+            zrow[ks] = __builtin_bit_cast(bf16x8, w4);
+        }
+    }
+};
+
+// One wave's share of the token range [t0, t1): tiles first_tile, first_tile +
+// tile_step, ... below n_tiles (32 tokens each).  `tileQ` is this wave's private
+// LDS tile (kApplyTile * kRowBytes bytes).  `qreg` holds the first DEPTH tiles,
+// already requested by the caller with apply_prefetch.
+template <int DEPTH>
+__device__ __forceinline__ void apply_prefetch(const uint16_t *Qh, int64_t stride_n, int t0, int t1, int first_tile,
+                                               int tile_step, int n_tiles, int lane,
+                                               u32x4 (&qreg)[DEPTH][kApplyTile / 8])
+{
+#pragma unroll
+    for (int s = 0; s < DEPTH; ++s) {
+        const int t = first_tile + s * tile_step;
+        if (t < n_tiles) apply_tile_load(Qh, stride_n, t0 + t * kApplyTile, t1, lane, qreg[s]);
+    }
+}
+
+template <bool HILO, int DEPTH>
+__device__ __forceinline__ void apply_tiles(const uint16_t *Qh, uint16_t *Oh, int64_t stride_n, int t0, int t1,
+                                            int first_tile, int tile_step, int n_tiles, unsigned char *tileQ,
+                                            int lane, const ApplyOperands<HILO> &A, float eps,
+                                            u32x4 (&qreg)[DEPTH][kApplyTile / 8])
+{
+    constexpr int NS = HILO ? 2 : 1;
+    const int n = lane & 31, g = lane >> 5;
+    const int wr_off = (lane >> 3) * kRowBytes + (lane & 7) * 16;
+
+    int tile = first_tile;
+    while (tile < n_tiles) {
+#pragma unroll
+        for (int s = 0; s < DEPTH; ++s) {
+            if (tile < n_tiles) {
+                const int tok0 = t0 + tile * kApplyTile;
+                wave_lds_fence();
+#pragma unroll
+                for (int i = 0; i < kApplyTile / 8; ++i)
+                    *reinterpret_cast<u32x4 *>(tileQ + wr_off + 8 * i * kRowBytes) = relu_bf16x8(qreg[s][i]);   // phi(Q)
+                const int nxt = tile + DEPTH * tile_step;
+                if (nxt < n_tiles) apply_tile_load(Qh, stride_n, t0 + nxt * kApplyTile, t1, lane, qreg[s]);
+                wave_lds_fence();
+
+                // B operands: features 16*ks + 8g .. +8 of token n
+                bf16x8 Bq[4];
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+                    Bq[ks] = *reinterpret_cast<const bf16x8 *>(tileQ + n * kRowBytes + (16 * ks + 8 * g) * 2);
+
+                f32x16 acc[2], accz;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) { acc[0][i] = 0.f; acc[1][i] = 0.f; accz[i] = 0.f; }
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+                    accz = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.zrow[ks], Bq[ks], accz, 0, 0, 0);
+#pragma unroll
+                for (int p = NS - 1; p >= 0; --p)      // small (lo) terms first
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks) {
+                        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.s[p][0][ks], Bq[ks], acc[0], 0, 0, 0);
+                        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.s[p][1][ks], Bq[ks], acc[1], 0, 0, 0);
+                    }
+
+                // denominator: rows 0 (hi) and 1 (lo) of the z block sit in registers 0 and 1 of
+                // the lanes of the lower half; the upper half fetches them across the wave
+                float den = accz[1] + accz[0];
+                den = __shfl(den, n);
+                const float inv = 1.0f / (den + eps);
+
+                wave_lds_fence();
+#pragma unroll
+                for (int rb = 0; rb < 2; ++rb) {
+                    u32x4 lo4, hi4;
+                    lo4.x = pack_bf16x2(acc[rb][0] * inv, acc[rb][1] * inv);
+                    lo4.y = pack_bf16x2(acc[rb][2] * inv, acc[rb][3] * inv);
+                    lo4.z = pack_bf16x2(acc[rb][4] * inv, acc[rb][5] * inv);
+                    lo4.w = pack_bf16x2(acc[rb][6] * inv, acc[rb][7] * inv);
+                    hi4.x = pack_bf16x2(acc[rb][8] * inv, acc[rb][9] * inv);
+                    hi4.y = pack_bf16x2(acc[rb][10] * inv, acc[rb][11] * inv);
+                    hi4.z = pack_bf16x2(acc[rb][12] * inv, acc[rb][13] * inv);
+                    hi4.w = pack_bf16x2(acc[rb][14] * inv, acc[rb][15] * inv);
+                    unsigned char *row = tileQ + n * kRowBytes + (32 * g + 16 * rb) * 2;
+                    *reinterpret_cast<u32x4 *>(row) = lo4;
+                    *reinterpret_cast<u32x4 *>(row + 16) = hi4;
+                }
+                wave_lds_fence();
+#pragma unroll
+                for (int i = 0; i < kApplyTile / 8; ++i) {
+                    const int tok = tok0 + (lane >> 3) + 8 * i;
+                    const u32x4 o = *reinterpret_cast<const u32x4 *>(tileQ + wr_off + 8 * i * kRowBytes);
+                    if (tok < t1) store_stream16(Oh + (int64_t)tok * stride_n + (lane & 7) * 8, o);
+                }
+            }
+            tile += tile_step;
+        }
+    }
+}
+
+template <int WAVES>
+__host__ __device__ constexpr int apply_lds_bytes() { return WAVES * kApplyTile * kRowBytes; }
+
+// grid = (C, B*H), block = 64*WAVES.  Wave w of workgroup c owns tiles
+// WAVES*c + w + WAVES*C*i (i = 0, 1, ...) of the T = ceil((t1-t0)/32) tiles,
+// the same round-robin deal as the state kernel.
+// HILO = false drops the low half of S (one MFMA pass instead of two).
+template <bool HILO, int WAVES, int DEPTH>
+__global__ __launch_bounds__(64 * WAVES, 1) void apply_mfma_d64(
     const uint16_t *__restrict__ Q, uint16_t *__restrict__ O, TokStrides st, int H, int t0, int t1, int C,
     const float *__restrict__ S, const float *__restrict__ z, float eps)
 {
-    constexpr int D = 64;
-    constexpr int TILE = 32;
-    constexpr int NS = HILO ? 2 : 1;
-    constexpr int kTileBytes = TILE * kRowBytes;
-    constexpr int kStBytes = D * kRowBytes;                       // one transposed bf16 copy of S
-    constexpr int kPrologueBytes = NS * kStBytes;
-    constexpr int kStageBytes = kWavesPerWg * kTileBytes;
-    constexpr int kLdsBytes = kPrologueBytes > kStageBytes ? kPrologueBytes : kStageBytes;
-    __shared__ __attribute__((aligned(16))) unsigned char lds[kLdsBytes];
-    __shared__ __attribute__((aligned(16))) float sz[D];
-
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1), wave = tid >> 6;
     const int c = blockIdx.x, bh = blockIdx.y;
     const int b = bh / H, h = bh % H;
     const uint16_t *Qh = Q + b * st.b + h * st.h;
     uint16_t *Oh = O + b * st.b + h * st.h;
+    const int n_tiles = (t1 - t0 + kApplyTile - 1) / kApplyTile;
+    const int first = WAVES * c + wave, step = WAVES * C;
 
-    const int n_tiles = (t1 - t0 + TILE - 1) / TILE;
-    const int tile_lo = chunk_tile_begin(c, C, n_tiles);
-    const int tile_hi = chunk_tile_begin(c + 1, C, n_tiles);
-
-    // first Q tile is requested before the state is staged
-    u32x4 qreg[TILE / 8];
-    int tile = tile_lo + wave;
-    if (tile < tile_hi) apply_tile_load<TILE>(Qh, st.n, t0 + tile * TILE, t1, lane, qreg);
-
-    // ---- stage S^T as bf16 hi (+ lo): st[v][k], rows padded to kRowBytes --------------------
-    {
-        const float *Sh = S + (int64_t)bh * D * D;
-        for (int idx = tid; idx < D * D; idx += kThreads) {
-            const int k = idx >> 6, v = idx & 63;
-            const float s = Sh[idx];
-            const uint16_t hi = f32_to_bf16_bits(s);
-            *reinterpret_cast<uint16_t *>(lds + v * kRowBytes + k * 2) = hi;
-            if (HILO) {
-                const uint16_t lo = f32_to_bf16_bits(s - bf16_bits_to_f32(hi));
-                *reinterpret_cast<uint16_t *>(lds + kStBytes + v * kRowBytes + k * 2) = lo;
-            }
-        }
-        if (tid < D) sz[tid] = z[(int64_t)bh * D + tid];
-    }
-    __syncthreads();
-
-    // A operands: MFMA row m of row block rb stands for output feature
-    //   F(rb, m) = 32*((m/4)%2) + 16*rb + 4*(m/8) + m%4,
-    // chosen so that accumulator register i of a lane in half g' = lane/32 is
-    // output feature 32*g' + 16*rb + i of the lane's token.
-    const int n = lane & 31, g = lane >> 5;
-    bf16x8 A[NS][2][4];
-    {
-        const int m = n;
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
-            const int F = 32 * ((m >> 2) & 1) + 16 * rb + 4 * (m >> 3) + (m & 3);
-#pragma unroll
-            for (int s = 0; s < 4; ++s)
-#pragma unroll
-                for (int p = 0; p < NS; ++p)
-                    A[p][rb][s] = *reinterpret_cast<const bf16x8 *>(lds + p * kStBytes + F * kRowBytes +
-                                                                    (16 * s + 8 * g) * 2);
-        }
-    }
-    __syncthreads();   // the prologue region is reused as Q/O staging below
-
-    unsigned char *ldsQ = lds + wave * kTileBytes;
-    const int wr_off = (lane >> 3) * kRowBytes + (lane & 7) * 16;
-
-    for (; tile < tile_hi; tile += kWavesPerWg) {
-        const int tok0 = t0 + tile * TILE;
-        wave_lds_fence();
-#pragma unroll
-        for (int i = 0; i < TILE / 8; ++i)
-            *reinterpret_cast<u32x4 *>(ldsQ + wr_off + 8 * i * kRowBytes) = relu_bf16x8(qreg[i]);   // phi(Q)
-        const int next = tile + kWavesPerWg;
-        if (next < tile_hi) apply_tile_load<TILE>(Qh, st.n, t0 + next * TILE, t1, lane, qreg);
-        wave_lds_fence();
-
-        // B operands: features 16s + 8g .. +8 of token n
-        u32x4 Bq[4];
-#pragma unroll
-        for (int s = 0; s < 4; ++s)
-            Bq[s] = *reinterpret_cast<const u32x4 *>(ldsQ + n * kRowBytes + (16 * s + 8 * g) * 2);
-
-        // denominator: this lane's 32 features, then the other half of the token
-        float den = 0.f;
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const f32x4 z0 = *reinterpret_cast<const f32x4 *>(sz + 16 * s + 8 * g);
-            const f32x4 z1 = *reinterpret_cast<const f32x4 *>(sz + 16 * s + 8 * g + 4);
-            den = fmaf(bf16_lo(Bq[s].x), z0.x, den);  den = fmaf(bf16_hi(Bq[s].x), z0.y, den);
-            den = fmaf(bf16_lo(Bq[s].y), z0.z, den);  den = fmaf(bf16_hi(Bq[s].y), z0.w, den);
-            den = fmaf(bf16_lo(Bq[s].z), z1.x, den);  den = fmaf(bf16_hi(Bq[s].z), z1.y, den);
-            den = fmaf(bf16_lo(Bq[s].w), z1.z, den);  den = fmaf(bf16_hi(Bq[s].w), z1.w, den);
-        }
-        den += __shfl_xor(den, 32);
-
-        f32x16 acc[2];
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[rb][i] = 0.f;
-#pragma unroll
-            for (int p = NS - 1; p >= 0; --p)      // small (lo) terms first
-#pragma unroll
-                for (int s = 0; s < 4; ++s)
-                    acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        A[p][rb][s], __builtin_bit_cast(bf16x8, Bq[s]), acc[rb], 0, 0, 0);
-        }
-
-        // normalise, round to bf16, and send the tile back through LDS
-        const float inv = 1.0f / (den + eps);
-        wave_lds_fence();
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
-            u32x4 lo4, hi4;
-            lo4.x = pack_bf16x2(acc[rb][0] * inv, acc[rb][1] * inv);
-            lo4.y = pack_bf16x2(acc[rb][2] * inv, acc[rb][3] * inv);
-            lo4.z = pack_bf16x2(acc[rb][4] * inv, acc[rb][5] * inv);
-            lo4.w = pack_bf16x2(acc[rb][6] * inv, acc[rb][7] * inv);
-            hi4.x = pack_bf16x2(acc[rb][8] * inv, acc[rb][9] * inv);
-            hi4.y = pack_bf16x2(acc[rb][10] * inv, acc[rb][11] * inv);
-            hi4.z = pack_bf16x2(acc[rb][12] * inv, acc[rb][13] * inv);
-            hi4.w = pack_bf16x2(acc[rb][14] * inv, acc[rb][15] * inv);
-            unsigned char *row = ldsQ + n * kRowBytes + (32 * g + 16 * rb) * 2;
-            *reinterpret_cast<u32x4 *>(row) = lo4;
-            *reinterpret_cast<u32x4 *>(row + 16) = hi4;
-        }
-        wave_lds_fence();
-#pragma unroll
-        for (int i = 0; i < TILE / 8; ++i) {
-            const int tok = tok0 + (lane >> 3) + 8 * i;
-            const u32x4 o = *reinterpret_cast<const u32x4 *>(ldsQ + wr_off + 8 * i * kRowBytes);
-            if (tok < t1) *reinterpret_cast<u32x4 *>(Oh + (int64_t)tok * st.n + (lane & 7) * 8) = o;
-        }
-    }
+    u32x4 qreg[DEPTH][kApplyTile / 8];
+    apply_prefetch<DEPTH>(Qh, st.n, t0, t1, first, step, n_tiles, lane, qreg);   // in flight while S is fetched
+    ApplyOperands<HILO> A;
+    A.load(S + (size_t)bh * 64 * 64, z + (size_t)bh * 64, lane);
+    apply_tiles<HILO, DEPTH>(Qh, Oh, st.n, t0, t1, first, step, n_tiles, lds + wave * kApplyTile * kRowBytes, lane,
+                             A, eps, qreg);
 }
 
 }  // namespace sv

@@ -1,0 +1,91 @@
+// One-launch block step for d = 64 bf16 on gfx950 (Sec. 3.3.1; cache update and
+// use of Alg. 1):
+//
+//   S += phi(K_b)^T V_b,  z += sum phi(K_b),  O_b = phi(Q_b) S / (phi(Q_b) z + eps)
+//
+// with O_b computed from the UPDATED state.  The grid is sized so that every
+// workgroup is resident at once (one per compute unit).  Each workgroup first
+// reduces its round-robin share of the block's keys and values to a partial
+// state; the last workgroup of a head to arrive folds the partials into the
+// carried S, z in chunk order and publishes an epoch-tagged "ready" flag; the
+// others meanwhile have their first Q tiles in flight and poll the flag (a
+// bounded number of times, so every wave always reaches the end of the kernel).
+// Then all of them apply the new state to their share of Q_b.  The dependency
+// "all of the block's keys before any of its outputs" is per head, not grid
+// wide, so heads drift past each other and reads overlap writes.
+#pragma once
+
+#include "apply_mfma.hpp"
+#include "state_mfma.hpp"
+
+namespace sv {
+
+template <int TILE, int WAVES>
+__host__ __device__ constexpr int block_step_lds_bytes() {
+    return state_lds_bytes<TILE, WAVES>() > apply_lds_bytes<WAVES>() + 16 ? state_lds_bytes<TILE, WAVES>()
+                                                                          : apply_lds_bytes<WAVES>() + 16;
+}
+
+// grid = (C, B*H) with C*B*H <= resident workgroup capacity, block = 64*WAVES.
+template <int TILE, int WAVES, int DEPTH_S, bool HILO, int DEPTH_A>
+__global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma_d64(
+    const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
+    uint16_t *__restrict__ O, TokStrides st, int H, int N, int C, float *__restrict__ S, float *__restrict__ z,
+    float eps, void *__restrict__ ws, unsigned long long epoch, uint32_t spin_limit)
+{
+    constexpr int THREADS = 64 * WAVES;
+    constexpr int kTileBytes = TILE * kRowBytes;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    uint32_t *lds_word = reinterpret_cast<uint32_t *>(lds + block_step_lds_bytes<TILE, WAVES>() - 16);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wave = tid >> 6;
+    const int c = blockIdx.x, bh = blockIdx.y, BH = gridDim.y;
+    const int b = bh / H, h = bh % H;
+    const int64_t head_off = b * st.b + h * st.h;
+    float *Sh = S + (size_t)bh * 64 * 64, *zh = z + (size_t)bh * 64;
+
+    // ---- fold this workgroup's share of K_b, V_b ------------------------------------------------
+    {
+        const int n_tiles = (N + TILE - 1) / TILE;
+        StateAcc acc;
+        acc.clear();
+        unsigned char *tileK = lds + wave * 2 * kTileBytes;
+        state_accumulate<TILE, DEPTH_S>(K + head_off, V + head_off, st.n, 0, N, WAVES * c + wave, WAVES * C, n_tiles,
+                                        tileK, tileK + kTileBytes, lane, acc);
+        float *partials = static_cast<float *>(ws) + (size_t)bh * kMaxChunks * kStateElems;
+        state_wg_reduce_store<WAVES>(acc, reinterpret_cast<float *>(lds), wave, lane,
+                                     partials + (size_t)c * kStateElems);
+    }
+
+    // ---- first Q tiles are requested before the head's state is waited for -----------------------
+    const int n_tiles_q = (N + kApplyTile - 1) / kApplyTile;
+    const int first = WAVES * c + wave, step = WAVES * C;
+    u32x4 qreg[DEPTH_A][kApplyTile / 8];
+    apply_prefetch<DEPTH_A>(Q + head_off, st.n, 0, N, first, step, n_tiles_q, lane, qreg);
+
+    // ---- last arriver of the head updates S, z in place and publishes ----------------------------
+    unsigned long long *ready = ws_ready(ws, BH, kStateElems) + bh;
+    if (state_arrive_is_last(ws, BH, bh, C, epoch, lds_word)) {
+        const float *partials = static_cast<const float *>(ws) + (size_t)bh * kMaxChunks * kStateElems;
+        state_finalize<THREADS>(partials, C, 1, Sh, zh);
+        __threadfence();                               // release the new state (every thread its own stores)
+        __syncthreads();
+        if (tid == 0) flag_publish(ready, epoch);
+    } else {
+        if (tid == 0) {
+            const bool ok = flag_wait(ready, epoch, spin_limit);
+            if (!ok) *ws_error(ws, BH, kStateElems) = epoch;      // never expected; results are invalid then
+        }
+        __syncthreads();
+        __threadfence();                               // acquire the new state
+    }
+
+    // ---- apply the updated state to this workgroup's share of Q_b ----------------------------------
+    ApplyOperands<HILO> A;
+    A.load(Sh, zh, lane);
+    apply_tiles<HILO, DEPTH_A>(Q + head_off, O + head_off, st.n, 0, N, first, step, n_tiles_q,
+                               lds + wave * kApplyTile * kRowBytes, lane, A, eps, qreg);
+}
+
+}  // namespace sv

@@ -50,6 +50,26 @@ __device__ __forceinline__ u32x4 relu_bf16x8(u32x4 v) {
     return v;
 }
 
+// Streaming 16-byte global accesses.  Tokens are read once and outputs written
+// once, so with SV_STREAM_NT both are marked non-temporal.
+#ifndef SV_STREAM_NT
+#define SV_STREAM_NT 1
+#endif
+__device__ __forceinline__ u32x4 load_stream16(const void *p) {
+#if SV_STREAM_NT
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+#else
+    return *reinterpret_cast<const u32x4 *>(p);
+#endif
+}
+__device__ __forceinline__ void store_stream16(void *p, u32x4 v) {
+#if SV_STREAM_NT
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(p));
+#else
+    *reinterpret_cast<u32x4 *>(p) = v;
+#endif
+}
+
 // ---- typed scalar access used by the generic (any dtype) kernels --------------------------
 
 template <typename T> struct Elem;

@@ -1,33 +1,73 @@
 // bf16 MFMA state reduction for d = 64 on gfx950.
 //
-//   S_c[k][v] = sum_{j in chunk c} phi(K[j][k]) V[j][v],   z_c[k] = sum_{j in chunk c} phi(K[j][k])
+//   S[k][v] (+)= sum_j phi(K[j][k]) V[j][v],   z[k] (+)= sum_j phi(K[j][k])
 //
 // (numerator and denominator brackets of the linear-attention equation of
-// Sec. 3.2; the per-token state S_j of Sec. 3.3.1 summed over a chunk).
+// Sec. 3.2; the per-token states S_j of Sec. 3.3.1 summed over a token range).
 //
 // The contraction runs over tokens, but K and V are stored feature-contiguous,
 // so both MFMA operands need a transpose.  Each wave works alone on tiles of
-// TILE tokens: coalesced 16-byte loads (8 lanes cover one 128-byte token row),
-// ReLU on the packed bf16 pairs, a store into the wave's private LDS tile, and
-// 32-bit LDS reads down the token axis that are re-packed into operands.  A
-// 32-bit word holds features (2r, 2r+1) of one token, so lane r of a 32-row
-// MFMA block serves row "feature 2r" in block 0 and "feature 2r+1" in block 1:
-// the row/column permutation is undone when the accumulators are written out.
-// Because a wave only ever reads LDS it wrote itself, no workgroup barrier is
-// needed inside the token loop.
+// TILE tokens: coalesced non-temporal 16-byte loads (8 lanes cover one 128-byte
+// token row), ReLU on the packed bf16 pairs, a store into the wave's private
+// LDS tile, and 32-bit LDS reads down the token axis that are re-packed into
+// operands.  A 32-bit word holds features (2r, 2r+1) of one token, so lane r
+// of a 32-row MFMA block serves row "feature 2r" in block 0 and "feature 2r+1"
+// in block 1: the row/column permutation is undone when the accumulators are
+// written out.  Because a wave only ever reads LDS it wrote itself, no
+// workgroup barrier is needed inside the token loop.
+//
+// One workgroup per compute unit and a round-robin deal of tiles keep the whole
+// grid streaming through a narrow, moving window of each head's tokens, which
+// is what HBM likes best; the loads of the next DEPTH tiles are always in
+// flight.  Workgroup partials go to the workspace; the last workgroup of a head
+// to arrive adds them up in chunk order (bit-reproducible, no float atomics).
 #pragma once
 
 #include "common.hpp"
+#include "sync.hpp"
 
 namespace sv {
 
 constexpr int kRowBytes = 144;   // 128-byte token row + 16 bytes of padding (bank spread, keeps 16-byte alignment)
+constexpr int kStateElems = 64 * 64 + 64;            // S then z of one head, d = 64
+constexpr int kSlotFloats = 72 * kWave;              // one wave's accumulators laid out register-major
 
-// Registers of one lane after the loop: the 64x64 fp32 partial state as four
-// 32x32 MFMA accumulators, plus 8 key-sum lanes.
+// Workspace layout (B*H = BH heads, `elems` = d*d + d):
+//   float  partial[BH][kMaxChunks][elems]
+//   u64    arrivals[BH]      (epoch-tagged tickets)
+//   u64    ready[BH]         (epoch when the head's state is final; fused block step only)
+//   u64    error, pad        (non-zero if a bounded wait ever timed out)
+__host__ __device__ constexpr size_t ws_partial_bytes(int BH, int elems) {
+    return (size_t)BH * kMaxChunks * elems * sizeof(float);
+}
+__host__ __device__ __forceinline__ unsigned long long *ws_arrivals(void *ws, int BH, int elems) {
+    return reinterpret_cast<unsigned long long *>(static_cast<unsigned char *>(ws) + ws_partial_bytes(BH, elems));
+}
+__host__ __device__ __forceinline__ unsigned long long *ws_ready(void *ws, int BH, int elems) {
+    return ws_arrivals(ws, BH, elems) + BH;
+}
+__host__ __device__ __forceinline__ unsigned long long *ws_error(void *ws, int BH, int elems) {
+    return ws_arrivals(ws, BH, elems) + 2 * BH;
+}
+__host__ __device__ constexpr size_t ws_total_bytes(int BH, int elems) {
+    return ws_partial_bytes(BH, elems) + (size_t)(2 * BH + 2) * sizeof(unsigned long long);
+}
+
+// Registers of one lane: the 64x64 fp32 partial state as four 32x32 MFMA
+// accumulators, plus 8 key-sum lanes.
 struct StateAcc {
     f32x16 s[2][2];   // [row block = key feature parity][col block = value feature parity]
     float z[8];       // features (lane%8)*8 + e of the tokens this lane loaded
+    __device__ __forceinline__ void clear() {
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) s[rb][cb][i] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) z[e] = 0.f;
+    }
 };
 
 template <int TILE>
@@ -41,8 +81,8 @@ __device__ __forceinline__ void state_tile_load(const uint16_t *Kh, const uint16
         const int tok = tok0 + (lane >> 3) + 8 * i;
         u32x4 kk = {0u, 0u, 0u, 0u}, vv = {0u, 0u, 0u, 0u};
         if (tok < t1) {
-            kk = *reinterpret_cast<const u32x4 *>(Kh + (int64_t)tok * stride_n + col * 8);
-            vv = *reinterpret_cast<const u32x4 *>(Vh + (int64_t)tok * stride_n + col * 8);
+            kk = load_stream16(Kh + (int64_t)tok * stride_n + col * 8);
+            vv = load_stream16(Vh + (int64_t)tok * stride_n + col * 8);
         }
         kreg[i] = kk;
         vreg[i] = vv;
@@ -68,90 +108,76 @@ __device__ __forceinline__ void lds_gather_pairs(const unsigned char *tile, int 
     odd = __builtin_bit_cast(bf16x8, hi);
 }
 
-// grid = (C, B*H), block = 256 (4 waves).  Chunk c owns tiles
-// [c*T/C, (c+1)*T/C) of the T = ceil((t1-t0)/TILE) tiles; inside the chunk the
-// waves take tiles round-robin.  Tokens past t1 are loaded as zeros, which add
-// nothing to either sum.  Output: ws[(bh*C + c)][64*64 + 64] fp32, S part in
-// [k][v] order.
-template <int TILE>
-__global__ __launch_bounds__(kThreads, 2) void state_partial_mfma_d64(
-    const uint16_t *__restrict__ K, const uint16_t *__restrict__ V, TokStrides st, int H, int t0, int t1,
-    int C, float *__restrict__ ws)
+// One wave's share of the token range [t0, t1): tiles first_tile, first_tile +
+// tile_step, ... below n_tiles.  Tokens past t1 are loaded as zeros, which add
+// nothing to either sum.  `tileK`/`tileV` are this wave's private LDS tiles.
+template <int TILE, int DEPTH>
+__device__ __forceinline__ void state_accumulate(const uint16_t *Kh, const uint16_t *Vh, int64_t stride_n, int t0,
+                                                 int t1, int first_tile, int tile_step, int n_tiles,
+                                                 unsigned char *tileK, unsigned char *tileV, int lane,
+                                                 StateAcc &acc)
 {
     static_assert(TILE == 16 || TILE == 32, "tile is one or two MFMA k-steps");
-    constexpr int D = 64;
-    constexpr int kTileBytes = TILE * kRowBytes;
-    constexpr int kSlotFloats = 72 * kWave;                       // 64 S registers + 8 z registers per lane
-    constexpr int kStageBytes = kWavesPerWg * 2 * kTileBytes;
-    constexpr int kReduceBytes = 2 * kSlotFloats * 4;
-    constexpr int kLdsBytes = kStageBytes > kReduceBytes ? kStageBytes : kReduceBytes;
-    __shared__ __attribute__((aligned(16))) unsigned char lds[kLdsBytes];
-
-    const int tid = threadIdx.x;
-    const int lane = tid & (kWave - 1), wave = tid >> 6;
-    const int c = blockIdx.x, bh = blockIdx.y;
-    const int b = bh / H, h = bh % H;
-    const uint16_t *Kh = K + b * st.b + h * st.h;
-    const uint16_t *Vh = V + b * st.b + h * st.h;
-
-    const int n_tiles = (t1 - t0 + TILE - 1) / TILE;
-    const int tile_lo = chunk_tile_begin(c, C, n_tiles);
-    const int tile_hi = chunk_tile_begin(c + 1, C, n_tiles);
-
-    unsigned char *ldsK = lds + wave * 2 * kTileBytes;
-    unsigned char *ldsV = ldsK + kTileBytes;
-
-    StateAcc acc;
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-        for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc.s[rb][cb][i] = 0.f;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc.z[e] = 0.f;
-
     const int r = lane & 31, g = lane >> 5;
     const int wr_off = (lane >> 3) * kRowBytes + (lane & 7) * 16;
 
-    u32x4 kreg[TILE / 8], vreg[TILE / 8];
-    int tile = tile_lo + wave;
-    if (tile < tile_hi) state_tile_load<TILE>(Kh, Vh, st.n, t0 + tile * TILE, t1, lane, kreg, vreg);
-
-    for (; tile < tile_hi; tile += kWavesPerWg) {
-        // phi(K) on the packed pairs; key sum in fp32 from the same registers
+    u32x4 kreg[DEPTH][TILE / 8], vreg[DEPTH][TILE / 8];
 #pragma unroll
-        for (int i = 0; i < TILE / 8; ++i) {
-            kreg[i] = relu_bf16x8(kreg[i]);
-            acc.z[0] += bf16_lo(kreg[i].x);  acc.z[1] += bf16_hi(kreg[i].x);
-            acc.z[2] += bf16_lo(kreg[i].y);  acc.z[3] += bf16_hi(kreg[i].y);
-            acc.z[4] += bf16_lo(kreg[i].z);  acc.z[5] += bf16_hi(kreg[i].z);
-            acc.z[6] += bf16_lo(kreg[i].w);  acc.z[7] += bf16_hi(kreg[i].w);
-        }
-        wave_lds_fence();   // earlier reads of this tile buffer are done before it is overwritten
-#pragma unroll
-        for (int i = 0; i < TILE / 8; ++i) {
-            *reinterpret_cast<u32x4 *>(ldsK + wr_off + 8 * i * kRowBytes) = kreg[i];
-            *reinterpret_cast<u32x4 *>(ldsV + wr_off + 8 * i * kRowBytes) = vreg[i];
-        }
-        // next tile's loads fly while this one is multiplied
-        const int next = tile + kWavesPerWg;
-        if (next < tile_hi) state_tile_load<TILE>(Kh, Vh, st.n, t0 + next * TILE, t1, lane, kreg, vreg);
-        wave_lds_fence();
-#pragma unroll
-        for (int s = 0; s < TILE / 16; ++s) {
-            bf16x8 a0, a1, b0, b1;
-            lds_gather_pairs(ldsK, 16 * s + 8 * g, r, a0, a1);
-            lds_gather_pairs(ldsV, 16 * s + 8 * g, r, b0, b1);
-            acc.s[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc.s[0][0], 0, 0, 0);
-            acc.s[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc.s[0][1], 0, 0, 0);
-            acc.s[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc.s[1][0], 0, 0, 0);
-            acc.s[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc.s[1][1], 0, 0, 0);
-        }
+    for (int s = 0; s < DEPTH; ++s) {
+        const int t = first_tile + s * tile_step;
+        if (t < n_tiles) state_tile_load<TILE>(Kh, Vh, stride_n, t0 + t * TILE, t1, lane, kreg[s], vreg[s]);
     }
 
-    // ---- combine the four waves in a fixed order: (w0 + w2) + (w1 + w3) --------------------
-    float *slot = reinterpret_cast<float *>(lds);
+    int tile = first_tile;
+    while (tile < n_tiles) {
+#pragma unroll
+        for (int s = 0; s < DEPTH; ++s) {
+            if (tile < n_tiles) {
+                // phi(K) on the packed pairs; key sum in fp32 from the same registers
+#pragma unroll
+                for (int i = 0; i < TILE / 8; ++i) {
+                    const u32x4 kk = relu_bf16x8(kreg[s][i]);
+                    kreg[s][i] = kk;
+                    acc.z[0] += bf16_lo(kk.x);  acc.z[1] += bf16_hi(kk.x);
+                    acc.z[2] += bf16_lo(kk.y);  acc.z[3] += bf16_hi(kk.y);
+                    acc.z[4] += bf16_lo(kk.z);  acc.z[5] += bf16_hi(kk.z);
+                    acc.z[6] += bf16_lo(kk.w);  acc.z[7] += bf16_hi(kk.w);
+                }
+                wave_lds_fence();   // earlier reads of the tile buffer are done before it is overwritten
+#pragma unroll
+                for (int i = 0; i < TILE / 8; ++i) {
+                    *reinterpret_cast<u32x4 *>(tileK + wr_off + 8 * i * kRowBytes) = kreg[s][i];
+                    *reinterpret_cast<u32x4 *>(tileV + wr_off + 8 * i * kRowBytes) = vreg[s][i];
+                }
+                // refill this stage: DEPTH tiles ahead
+                const int nxt = tile + DEPTH * tile_step;
+                if (nxt < n_tiles)
+                    state_tile_load<TILE>(Kh, Vh, stride_n, t0 + nxt * TILE, t1, lane, kreg[s], vreg[s]);
+                wave_lds_fence();
+#pragma unroll
+                for (int ks = 0; ks < TILE / 16; ++ks) {
+                    bf16x8 a0, a1, b0, b1;
+                    lds_gather_pairs(tileK, 16 * ks + 8 * g, r, a0, a1);
+                    lds_gather_pairs(tileV, 16 * ks + 8 * g, r, b0, b1);
+                    acc.s[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc.s[0][0], 0, 0, 0);
+                    acc.s[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc.s[0][1], 0, 0, 0);
+                    acc.s[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc.s[1][0], 0, 0, 0);
+                    acc.s[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc.s[1][1], 0, 0, 0);
+                }
+            }
+            tile += tile_step;
+        }
+    }
+}
+
+// Adds the WAVES waves' accumulators in a fixed tree order through two LDS
+// slots and lets wave 0 write the workgroup's partial state, S in [k][v] order
+// followed by z, to `out` (kStateElems floats).  Must be called by all threads;
+// the staging tiles are dead afterwards.
+template <int WAVES>
+__device__ __forceinline__ void state_wg_reduce_store(StateAcc &acc, float *slot, int wave, int lane,
+                                                      float *__restrict__ out)
+{
     auto put = [&](float *dst) {
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb)
@@ -172,19 +198,21 @@ __global__ __launch_bounds__(kThreads, 2) void state_partial_mfma_d64(
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc.z[e] += src[(64 + e) * kWave + lane];
     };
-    __syncthreads();                                   // staging tiles are dead from here on
-    if (wave >= 2) put(slot + (wave - 2) * kSlotFloats);
-    __syncthreads();
-    if (wave < 2) add(slot + wave * kSlotFloats);
-    __syncthreads();
-    if (wave == 1) put(slot);
-    __syncthreads();
+    __syncthreads();                                   // all waves are done with their staging tiles
+#pragma unroll
+    for (int h = WAVES / 2; h >= 1; h /= 2) {          // wave w absorbs wave w + h
+#pragma unroll
+        for (int base = 0; base < h; base += 2) {      // two waves at a time (two slots)
+            if (wave >= h + base && wave < h + base + 2 && wave < 2 * h) put(slot + (wave - h - base) * kSlotFloats);
+            __syncthreads();
+            if (wave >= base && wave < base + 2 && wave < h) add(slot + (wave - base) * kSlotFloats);
+            __syncthreads();
+        }
+    }
     if (wave != 0) return;
-    add(slot);
 
-    // ---- wave 0 writes the chunk's partial state in [k][v] order ----------------------------
     // 32x32 accumulator layout: register i of lane l is row 8*(i/4) + 4*(l/32) + i%4, column l%32.
-    float *out = ws + ((int64_t)bh * C + c) * (D * D + D);
+    const int r = lane & 31, g = lane >> 5;
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
@@ -192,9 +220,9 @@ __global__ __launch_bounds__(kThreads, 2) void state_partial_mfma_d64(
             const int m = 8 * (i >> 2) + 4 * g + (i & 3);
             const int k = 2 * m + rb;
             f32x2 pair = {acc.s[rb][0][i], acc.s[rb][1][i]};       // value features 2r, 2r+1
-            *reinterpret_cast<f32x2 *>(out + k * D + 2 * r) = pair;
+            *reinterpret_cast<f32x2 *>(out + k * 64 + 2 * r) = pair;
         }
-    // key sum: lanes with equal lane%8 hold the same 8 features
+    // key sum: lanes with equal lane%8 hold the same 8 features (wavefront-level reduction)
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         float x = acc.z[e];
@@ -206,9 +234,89 @@ __global__ __launch_bounds__(kThreads, 2) void state_partial_mfma_d64(
     if (lane < 8) {
         f32x4 lo = {acc.z[0], acc.z[1], acc.z[2], acc.z[3]};
         f32x4 hi = {acc.z[4], acc.z[5], acc.z[6], acc.z[7]};
-        *reinterpret_cast<f32x4 *>(out + D * D + lane * 8) = lo;
-        *reinterpret_cast<f32x4 *>(out + D * D + lane * 8 + 4) = hi;
+        *reinterpret_cast<f32x4 *>(out + 64 * 64 + lane * 8) = lo;
+        *reinterpret_cast<f32x4 *>(out + 64 * 64 + lane * 8 + 4) = hi;
     }
+}
+
+// The calling workgroup has just stored partial `c` of head `bh`.  Returns true
+// in exactly one workgroup per head and call: the last one to arrive, after it
+// has made all C partials of the head visible to itself.
+__device__ __forceinline__ bool state_arrive_is_last(void *ws, int BH, int bh, int C, unsigned long long epoch,
+                                                     uint32_t *lds_word)
+{
+    __threadfence();                                    // release this thread's partial-state stores
+    __syncthreads();
+    if (threadIdx.x == 0) *lds_word = ticket_take(ws_arrivals(ws, BH, kStateElems) + bh, epoch);
+    __syncthreads();
+    const bool last = *lds_word == (uint32_t)(C - 1);
+    if (last) __threadfence();                          // acquire the other workgroups' partials
+    return last;
+}
+
+// S, z (+)= partial[0] + partial[1] + ... + partial[C-1], in that order.
+// Every thread of the workgroup takes float4 slices of the kStateElems values.
+template <int THREADS>
+__device__ __forceinline__ void state_finalize(const float *__restrict__ partials, int C, int accumulate,
+                                               float *__restrict__ S, float *__restrict__ z)
+{
+    constexpr int kVecs = kStateElems / 4;              // 1040 float4
+    for (int v = threadIdx.x; v < kVecs; v += THREADS) {
+        float *dst = v < 1024 ? S + 4 * v : z + 4 * (v - 1024);
+        f32x4 x = {0.f, 0.f, 0.f, 0.f};
+        if (accumulate) x = *reinterpret_cast<const f32x4 *>(dst);
+        int c = 0;
+        for (; c + 4 <= C; c += 4) {                    // four partials in flight, summed in order
+            const f32x4 p0 = *reinterpret_cast<const f32x4 *>(partials + (size_t)(c + 0) * kStateElems + 4 * v);
+            const f32x4 p1 = *reinterpret_cast<const f32x4 *>(partials + (size_t)(c + 1) * kStateElems + 4 * v);
+            const f32x4 p2 = *reinterpret_cast<const f32x4 *>(partials + (size_t)(c + 2) * kStateElems + 4 * v);
+            const f32x4 p3 = *reinterpret_cast<const f32x4 *>(partials + (size_t)(c + 3) * kStateElems + 4 * v);
+            x += p0; x += p1; x += p2; x += p3;
+        }
+        for (; c < C; ++c) x += *reinterpret_cast<const f32x4 *>(partials + (size_t)c * kStateElems + 4 * v);
+        *reinterpret_cast<f32x4 *>(dst) = x;
+    }
+}
+
+// Dynamic LDS of state_mfma_d64: staging tiles or reduction slots, plus one word.
+template <int TILE, int WAVES>
+__host__ __device__ constexpr int state_lds_bytes() {
+    constexpr int stage = WAVES * 2 * TILE * kRowBytes, red = 2 * kSlotFloats * 4;
+    return (stage > red ? stage : red) + 16;
+}
+
+// grid = (C, B*H), block = 64*WAVES.  Wave w of workgroup c owns tiles
+// WAVES*c + w + WAVES*C*i (i = 0, 1, ...) of the T = ceil((t1-t0)/TILE) tiles.
+template <int TILE, int WAVES, int DEPTH>
+__global__ __launch_bounds__(64 * WAVES, 1) void state_mfma_d64(
+    const uint16_t *__restrict__ K, const uint16_t *__restrict__ V, TokStrides st, int H, int t0, int t1,
+    int C, int accumulate, float *__restrict__ S, float *__restrict__ z, void *__restrict__ ws,
+    unsigned long long epoch)
+{
+    constexpr int THREADS = 64 * WAVES;
+    constexpr int kTileBytes = TILE * kRowBytes;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    uint32_t *lds_word = reinterpret_cast<uint32_t *>(lds + state_lds_bytes<TILE, WAVES>() - 16);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wave = tid >> 6;
+    const int c = blockIdx.x, bh = blockIdx.y, BH = gridDim.y;
+    const int b = bh / H, h = bh % H;
+    const uint16_t *Kh = K + b * st.b + h * st.h;
+    const uint16_t *Vh = V + b * st.b + h * st.h;
+    const int n_tiles = (t1 - t0 + TILE - 1) / TILE;
+
+    StateAcc acc;
+    acc.clear();
+    unsigned char *tileK = lds + wave * 2 * kTileBytes;
+    state_accumulate<TILE, DEPTH>(Kh, Vh, st.n, t0, t1, WAVES * c + wave, WAVES * C, n_tiles, tileK,
+                                  tileK + kTileBytes, lane, acc);
+
+    float *partials = static_cast<float *>(ws) + (size_t)bh * kMaxChunks * kStateElems;
+    state_wg_reduce_store<WAVES>(acc, reinterpret_cast<float *>(lds), wave, lane,
+                                 partials + (size_t)c * kStateElems);
+    if (state_arrive_is_last(ws, BH, bh, C, epoch, lds_word))
+        state_finalize<THREADS>(partials, C, accumulate, S + (size_t)bh * 64 * 64, z + (size_t)bh * 64);
 }
 
 }  // namespace sv

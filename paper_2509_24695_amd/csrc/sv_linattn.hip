@@ -5,7 +5,12 @@
 #include <hip/hip_runtime.h>
 #include <math.h>
 
+#include <atomic>
+#include <chrono>
+#include <mutex>
+
 #include "apply_mfma.hpp"
+#include "block_step_fused.hpp"
 #include "common.hpp"
 #include "generic_kernels.hpp"
 #include "state_mfma.hpp"
@@ -14,8 +19,13 @@ namespace {
 
 using namespace sv;
 
-constexpr int kVersion = 100;   // 0.1.0
-constexpr int kNumCUs = 256;    // MI355X
+constexpr int kVersion = 200;   // 0.2.0
+
+// Tuned launch shapes of the bf16 d = 64 kernels (one workgroup per compute unit).
+constexpr int kStateTile = 32, kStateWaves = 4, kStateDepth = 2;
+constexpr int kApplyWaves = 4, kApplyDepth = 2;
+constexpr bool kApplyHiLo = true;
+constexpr uint32_t kSpinLimit = 1u << 24;      // polls of ~100 ns: far beyond any real wait
 
 struct Shape {
     int B, H, N, d, BH;
@@ -24,25 +34,74 @@ struct Shape {
     int elem_bytes;
 };
 
-// Launch plan shared by the state and apply kernels: the token range is cut
-// into tiles of `tile` tokens and the tiles are dealt to `chunks` workgroups per
-// head.  The chunk count aims at `wgs_per_cu` workgroups per compute unit over
-// the whole grid and never exceeds kMaxChunks (which sizes the workspace).
-struct Plan {
-    int tile, chunks;
+struct Device {
+    int num_cu = 0;
+    int fused_resident_wgs = 0;     // how many block-step workgroups fit on the device at once
+    bool ok = false;
 };
 
-Plan make_plan(int BH, int n_tokens, int tile, int wgs_per_cu, int max_chunks)
+auto *const kStateKernel = state_mfma_d64<kStateTile, kStateWaves, kStateDepth>;
+auto *const kApplyKernel = apply_mfma_d64<kApplyHiLo, kApplyWaves, kApplyDepth>;
+auto *const kFusedKernel = block_step_mfma_d64<kStateTile, kStateWaves, kStateDepth, kApplyHiLo, kApplyDepth>;
+constexpr int kStateLds = state_lds_bytes<kStateTile, kStateWaves>();
+constexpr int kApplyLds = apply_lds_bytes<kApplyWaves>();
+constexpr int kFusedLds = block_step_lds_bytes<kStateTile, kStateWaves>();
+
+// Per-device facts, queried once (no device memory is touched).
+const Device &device_info()
 {
-    Plan p{tile, 0};
-    if (n_tokens <= 0) return p;
-    const int n_tiles = (n_tokens + tile - 1) / tile;
-    int chunks = (kNumCUs * wgs_per_cu + BH - 1) / BH;
-    if (chunks > max_chunks) chunks = max_chunks;
-    if (chunks > n_tiles) chunks = n_tiles;
+    static Device devs[64];
+    static std::mutex mu;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+        static Device bad;
+        return bad;
+    }
+    std::lock_guard<std::mutex> lock(mu);
+    Device &d = devs[dev];
+    if (!d.ok) {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return d;
+        d.num_cu = prop.multiProcessorCount;
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kStateKernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, kStateLds);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kApplyKernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, kApplyLds);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kFusedKernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, kFusedLds);
+        int per_cu = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(kFusedKernel),
+                                                         64 * kStateWaves, kFusedLds) != hipSuccess)
+            per_cu = 0;
+        d.fused_resident_wgs = per_cu * d.num_cu;
+        (void)hipGetLastError();
+        d.ok = d.num_cu > 0;
+    }
+    return d;
+}
+
+// Fresh 40-bit tag for the workspace's counters and flags; unique per call
+// within the process and seeded from the clock so that stale workspace
+// contents of an earlier process do not look current.
+unsigned long long next_epoch()
+{
+    static std::atomic<unsigned long long> ctr{
+        (unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count() * 2654435761ull};
+    return (ctr.fetch_add(1, std::memory_order_relaxed) & ((1ull << 40) - 1)) | 1ull << 39;
+}
+
+// Token chunks (workgroups) per head: about one workgroup per compute unit over
+// the whole grid, never more than kMaxChunks (which sizes the workspace) or
+// than there are tiles.
+int plan_chunks(int BH, int n_tokens, int tokens_per_wg_step, int num_cu)
+{
+    if (n_tokens <= 0) return 0;
+    const int steps = (n_tokens + tokens_per_wg_step - 1) / tokens_per_wg_step;
+    int chunks = num_cu / BH;
+    if (chunks > kMaxChunks) chunks = kMaxChunks;
+    if (chunks > steps) chunks = steps;
     if (chunks < 1) chunks = 1;
-    p.chunks = chunks;
-    return p;
+    return chunks;
 }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -71,48 +130,50 @@ sv_status check_range(const Shape &s, int32_t t0, int32_t t1)
     return (t0 < 0 || t1 < t0 || t1 > s.N) ? SV_ERR_RANGE : SV_OK;
 }
 
-size_t workspace_bytes(int BH, int d) { return (size_t)BH * kMaxChunks * ((size_t)d * d + d) * sizeof(float); }
+size_t workspace_bytes(int BH, int d) { return ws_total_bytes(BH, d * d + d); }
 
 sv_status launch_status() { return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_LAUNCH; }
 
-// Partial states of [t0,t1) into the workspace, then the fixed-order reduction
-// into S, z.  All arguments are already validated.
+bool eps_ok(float eps) { return isfinite(eps) && eps >= 0.f; }
+
+// S, z (+)= state of tokens [t0,t1).  All arguments are already validated.
 sv_status enqueue_state(const void *K, const void *V, const Shape &s, int t0, int t1, int accumulate, float *S,
-                        float *z, float *ws, hipStream_t stream)
+                        float *z, void *ws, hipStream_t stream)
 {
     const int n = t1 - t0;
-    const bool mfma = s.bf16 && s.d == 64;
-    const Plan plan = mfma ? make_plan(s.BH, n, n >= 8192 ? 32 : 16, 2, kMaxChunks)
-                           : make_plan(s.BH, n, 32, 2, kMaxChunks);
     if (n == 0 && accumulate) return SV_OK;
-    if (n > 0) {
-        const dim3 grid(plan.chunks, s.BH), block(kThreads);
-        if (mfma) {
-            auto *k = static_cast<const uint16_t *>(K);
-            auto *v = static_cast<const uint16_t *>(V);
-            if (plan.tile == 32)
-                state_partial_mfma_d64<32><<<grid, block, 0, stream>>>(k, v, s.st, s.H, t0, t1, plan.chunks, ws);
-            else
-                state_partial_mfma_d64<16><<<grid, block, 0, stream>>>(k, v, s.st, s.H, t0, t1, plan.chunks, ws);
-        } else if (s.bf16) {
-            auto *k = static_cast<const uint16_t *>(K);
-            auto *v = static_cast<const uint16_t *>(V);
-            state_partial_generic<uint16_t, 32><<<grid, block, 0, stream>>>(k, v, s.st, s.H, t0, t1, plan.chunks, ws);
-        } else {
-            auto *k = static_cast<const float *>(K);
-            auto *v = static_cast<const float *>(V);
-            if (s.d == 64)
-                state_partial_generic<float, 64><<<grid, block, 0, stream>>>(k, v, s.st, s.H, t0, t1, plan.chunks, ws);
-            else
-                state_partial_generic<float, 32><<<grid, block, 0, stream>>>(k, v, s.st, s.H, t0, t1, plan.chunks, ws);
-        }
-    }
+    const Device &dev = device_info();
+    if (!dev.ok) return SV_ERR_LAUNCH;
     const int E = s.d * s.d + s.d;
-    const dim3 rgrid((E + kThreads - 1) / kThreads, s.BH), rblock(kThreads);
-    if (s.d == 64)
-        state_reduce<64><<<rgrid, rblock, 0, stream>>>(ws, plan.chunks, accumulate, S, z);
-    else
-        state_reduce<32><<<rgrid, rblock, 0, stream>>>(ws, plan.chunks, accumulate, S, z);
+    const dim3 rgrid((E + kThreads - 1) / kThreads, s.BH);
+    if (n == 0) {                                   // overwrite with the empty sum
+        if (s.d == 64) state_reduce<64><<<rgrid, kThreads, 0, stream>>>(static_cast<float *>(ws), 0, 0, S, z);
+        else state_reduce<32><<<rgrid, kThreads, 0, stream>>>(static_cast<float *>(ws), 0, 0, S, z);
+        return launch_status();
+    }
+    if (s.bf16 && s.d == 64) {
+        const int C = plan_chunks(s.BH, n, kStateTile * kStateWaves, dev.num_cu);
+        kStateKernel<<<dim3(C, s.BH), 64 * kStateWaves, kStateLds, stream>>>(
+            static_cast<const uint16_t *>(K), static_cast<const uint16_t *>(V), s.st, s.H, t0, t1, C, accumulate, S, z,
+            ws, next_epoch());
+        return launch_status();
+    }
+    // fp32 validation mode and bf16 d = 32: plain-FMA partials, then the fixed-order reduction
+    const int C = plan_chunks(s.BH, n, 32, 2 * dev.num_cu);
+    const dim3 grid(C, s.BH);
+    float *wsf = static_cast<float *>(ws);
+    if (s.bf16) {
+        state_partial_generic<uint16_t, 32><<<grid, kThreads, 0, stream>>>(
+            static_cast<const uint16_t *>(K), static_cast<const uint16_t *>(V), s.st, s.H, t0, t1, C, wsf);
+    } else if (s.d == 64) {
+        state_partial_generic<float, 64><<<grid, kThreads, 0, stream>>>(
+            static_cast<const float *>(K), static_cast<const float *>(V), s.st, s.H, t0, t1, C, wsf);
+    } else {
+        state_partial_generic<float, 32><<<grid, kThreads, 0, stream>>>(
+            static_cast<const float *>(K), static_cast<const float *>(V), s.st, s.H, t0, t1, C, wsf);
+    }
+    if (s.d == 64) state_reduce<64><<<rgrid, kThreads, 0, stream>>>(wsf, C, accumulate, S, z);
+    else state_reduce<32><<<rgrid, kThreads, 0, stream>>>(wsf, C, accumulate, S, z);
     return launch_status();
 }
 
@@ -121,28 +182,35 @@ sv_status enqueue_apply(const void *Q, const Shape &s, int t0, int t1, const flo
 {
     const int n = t1 - t0;
     if (n == 0) return SV_OK;
-    const bool mfma = s.bf16 && s.d == 64;
-    // generic tiles: 256 threads / (d/4 threads per token)
-    const Plan plan = mfma ? make_plan(s.BH, n, 32, 4, 1 << 20) : make_plan(s.BH, n, kThreads / (s.d / 4), 4, 1 << 20);
-    const dim3 grid(plan.chunks, s.BH), block(kThreads);
-    if (mfma) {
-        apply_mfma_d64<true><<<grid, block, 0, stream>>>(static_cast<const uint16_t *>(Q), static_cast<uint16_t *>(O),
-                                                        s.st, s.H, t0, t1, plan.chunks, S, z, eps);
-    } else if (s.bf16) {
-        apply_generic<uint16_t, 32><<<grid, block, 0, stream>>>(static_cast<const uint16_t *>(Q),
-                                                               static_cast<uint16_t *>(O), s.st, s.H, t0, t1,
-                                                               plan.chunks, S, z, eps);
+    const Device &dev = device_info();
+    if (!dev.ok) return SV_ERR_LAUNCH;
+    if (s.bf16 && s.d == 64) {
+        int C = dev.num_cu / s.BH;
+        const int steps = (n + kApplyTile * kApplyWaves - 1) / (kApplyTile * kApplyWaves);
+        if (C > steps) C = steps;
+        if (C < 1) C = 1;
+        kApplyKernel<<<dim3(C, s.BH), 64 * kApplyWaves, kApplyLds, stream>>>(
+            static_cast<const uint16_t *>(Q), static_cast<uint16_t *>(O), s.st, s.H, t0, t1, C, S, z, eps);
+        return launch_status();
+    }
+    const int tile = kThreads / (s.d / 4);          // generic tiles: 256 threads / (d/4 threads per token)
+    int C = (4 * dev.num_cu + s.BH - 1) / s.BH;
+    const int n_tiles = (n + tile - 1) / tile;
+    if (C > n_tiles) C = n_tiles;
+    const dim3 grid(C, s.BH);
+    if (s.bf16) {
+        apply_generic<uint16_t, 32><<<grid, kThreads, 0, stream>>>(static_cast<const uint16_t *>(Q),
+                                                                  static_cast<uint16_t *>(O), s.st, s.H, t0, t1, C, S,
+                                                                  z, eps);
     } else if (s.d == 64) {
-        apply_generic<float, 64><<<grid, block, 0, stream>>>(static_cast<const float *>(Q), static_cast<float *>(O),
-                                                            s.st, s.H, t0, t1, plan.chunks, S, z, eps);
+        apply_generic<float, 64><<<grid, kThreads, 0, stream>>>(static_cast<const float *>(Q), static_cast<float *>(O),
+                                                               s.st, s.H, t0, t1, C, S, z, eps);
     } else {
-        apply_generic<float, 32><<<grid, block, 0, stream>>>(static_cast<const float *>(Q), static_cast<float *>(O),
-                                                            s.st, s.H, t0, t1, plan.chunks, S, z, eps);
+        apply_generic<float, 32><<<grid, kThreads, 0, stream>>>(static_cast<const float *>(Q), static_cast<float *>(O),
+                                                               s.st, s.H, t0, t1, C, S, z, eps);
     }
     return launch_status();
 }
-
-bool eps_ok(float eps) { return isfinite(eps) && eps >= 0.f; }
 
 }  // namespace
 
@@ -167,7 +235,7 @@ sv_status sv_linattn_state(const void *K, const void *V, const sv_tensor_desc *k
     if (!aligned16(K) || !aligned16(V) || !aligned16(S) || !aligned16(z) || !aligned16(workspace))
         return SV_ERR_ALIGN;
     if (workspace_bytes_given < workspace_bytes(s.BH, s.d)) return SV_ERR_WORKSPACE;
-    return enqueue_state(K, V, s, tok_begin, tok_end, accumulate != 0, S, z, static_cast<float *>(workspace),
+    return enqueue_state(K, V, s, tok_begin, tok_end, accumulate != 0, S, z, workspace,
                          static_cast<hipStream_t>(stream));
 }
 
@@ -198,7 +266,20 @@ sv_status sv_block_linattn_step(const void *Qb, const void *Kb, const void *Vb, 
         return SV_ERR_ALIGN;
     if (workspace_bytes_given < workspace_bytes(s.BH, s.d)) return SV_ERR_WORKSPACE;
     auto hs = static_cast<hipStream_t>(stream);
-    rc = enqueue_state(Kb, Vb, s, 0, s.N, 1, S, z, static_cast<float *>(workspace), hs);
+    if (s.bf16 && s.d == 64) {
+        const Device &dev = device_info();
+        if (!dev.ok) return SV_ERR_LAUNCH;
+        // One launch when the whole grid can be resident at once (needed by the in-kernel wait).
+        const int C = plan_chunks(s.BH, s.N, kStateTile * kStateWaves, dev.num_cu);
+        if ((int64_t)C * s.BH <= dev.fused_resident_wgs) {
+            kFusedKernel<<<dim3(C, s.BH), 64 * kStateWaves, kFusedLds, hs>>>(
+                static_cast<const uint16_t *>(Qb), static_cast<const uint16_t *>(Kb),
+                static_cast<const uint16_t *>(Vb), static_cast<uint16_t *>(Ob), s.st, s.H, s.N, C, S, z, eps,
+                workspace, next_epoch(), kSpinLimit);
+            return launch_status();
+        }
+    }
+    rc = enqueue_state(Kb, Vb, s, 0, s.N, 1, S, z, workspace, hs);
     if (rc != SV_OK) return rc;
     return enqueue_apply(Qb, s, 0, s.N, S, z, eps, Ob, hs);
 }
