@@ -24,6 +24,7 @@
 
 #include "common.hpp"
 #include "state_mfma.hpp"   // kRowBytes
+#include "sync.hpp"
 
 namespace sv {
 
@@ -54,6 +55,8 @@ struct ApplyOperands {
     bf16x8 s[NS][2][4];    // [hi/lo][row block][k-step]
     bf16x8 zrow[4];        // [k-step]
 
+    // COHERENT: the state was written by another workgroup of this same kernel.
+    template <bool COHERENT>
     __device__ __forceinline__ void load(const float *__restrict__ Sh, const float *__restrict__ zh, int lane)
     {
         const int m = lane & 31, g = lane >> 5;
@@ -64,13 +67,19 @@ struct ApplyOperands {
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-                for (int i = 0; i < 8; ++i) sv_[rb][ks][i] = Sh[(16 * ks + 8 * g + i) * 64 + F];
+                for (int i = 0; i < 8; ++i) {
+                    const float *p = Sh + (16 * ks + 8 * g + i) * 64 + F;
+                    sv_[rb][ks][i] = COHERENT ? load_coherent1(p) : *p;
+                }
         }
         float zv[4][8];
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-            for (int i = 0; i < 8; ++i) zv[ks][i] = zh[16 * ks + 8 * g + i];
+            for (int i = 0; i < 8; ++i) {
+                const float *p = zh + 16 * ks + 8 * g + i;
+                zv[ks][i] = COHERENT ? load_coherent1(p) : *p;
+            }
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
@@ -222,7 +231,7 @@ __global__ __launch_bounds__(64 * WAVES, 1) void apply_mfma_d64(
     u32x4 qreg[DEPTH][kApplyTile / 8];
     apply_prefetch<DEPTH>(Qh, st.n, t0, t1, first, step, n_tiles, lane, qreg);   // in flight while S is fetched
     ApplyOperands<HILO> A;
-    A.load(S + (size_t)bh * 64 * 64, z + (size_t)bh * 64, lane);
+    A.template load<false>(S + (size_t)bh * 64 * 64, z + (size_t)bh * 64, lane);
     apply_tiles<HILO, DEPTH>(Qh, Oh, st.n, t0, t1, first, step, n_tiles, lds + wave * kApplyTile * kRowBytes, lane,
                              A, eps, qreg);
 }

@@ -68,8 +68,8 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma_d64(
     unsigned long long *ready = ws_ready(ws, BH, kStateElems) + bh;
     if (state_arrive_is_last(ws, BH, bh, C, epoch, lds_word)) {
         const float *partials = static_cast<const float *>(ws) + (size_t)bh * kMaxChunks * kStateElems;
-        state_finalize<THREADS>(partials, C, 1, Sh, zh);
-        __threadfence();                               // release the new state (every thread its own stores)
+        state_finalize<THREADS, true>(partials, C, 1, Sh, zh);
+        coherent_stores_done();                        // every wave: its slice of the new state is performed
         __syncthreads();
         if (tid == 0) flag_publish(ready, epoch);
     } else {
@@ -77,13 +77,12 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma_d64(
             const bool ok = flag_wait(ready, epoch, spin_limit);
             if (!ok) *ws_error(ws, BH, kStateElems) = epoch;      // never expected; results are invalid then
         }
-        __syncthreads();
-        __threadfence();                               // acquire the new state
+        __syncthreads();                               // the new state is then read with coherent loads
     }
 
     // ---- apply the updated state to this workgroup's share of Q_b ----------------------------------
     ApplyOperands<HILO> A;
-    A.load(Sh, zh, lane);
+    A.template load<true>(Sh, zh, lane);
     apply_tiles<HILO, DEPTH_A>(Q + head_off, O + head_off, st.n, 0, N, first, step, n_tiles_q,
                                lds + wave * kApplyTile * kRowBytes, lane, A, eps, qreg);
 }

@@ -220,7 +220,7 @@ __device__ __forceinline__ void state_wg_reduce_store(StateAcc &acc, float *slot
             const int m = 8 * (i >> 2) + 4 * g + (i & 3);
             const int k = 2 * m + rb;
             f32x2 pair = {acc.s[rb][0][i], acc.s[rb][1][i]};       // value features 2r, 2r+1
-            *reinterpret_cast<f32x2 *>(out + k * 64 + 2 * r) = pair;
+            store_coherent(out + k * 64 + 2 * r, pair);
         }
     // key sum: lanes with equal lane%8 hold the same 8 features (wavefront-level reduction)
 #pragma unroll
@@ -232,10 +232,11 @@ __device__ __forceinline__ void state_wg_reduce_store(StateAcc &acc, float *slot
         acc.z[e] = x;
     }
     if (lane < 8) {
-        f32x4 lo = {acc.z[0], acc.z[1], acc.z[2], acc.z[3]};
-        f32x4 hi = {acc.z[4], acc.z[5], acc.z[6], acc.z[7]};
-        *reinterpret_cast<f32x4 *>(out + 64 * 64 + lane * 8) = lo;
-        *reinterpret_cast<f32x4 *>(out + 64 * 64 + lane * 8 + 4) = hi;
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+            f32x2 pair = {acc.z[e], acc.z[e + 1]};
+            store_coherent(out + 64 * 64 + lane * 8 + e, pair);
+        }
     }
 }
 
@@ -245,36 +246,61 @@ __device__ __forceinline__ void state_wg_reduce_store(StateAcc &acc, float *slot
 __device__ __forceinline__ bool state_arrive_is_last(void *ws, int BH, int bh, int C, unsigned long long epoch,
                                                      uint32_t *lds_word)
 {
-    __threadfence();                                    // release this thread's partial-state stores
+    coherent_stores_done();                             // this wave's partial-state stores are performed
     __syncthreads();
     if (threadIdx.x == 0) *lds_word = ticket_take(ws_arrivals(ws, BH, kStateElems) + bh, epoch);
     __syncthreads();
-    const bool last = *lds_word == (uint32_t)(C - 1);
-    if (last) __threadfence();                          // acquire the other workgroups' partials
-    return last;
+    return *lds_word == (uint32_t)(C - 1);              // the partials are then read with coherent loads
 }
 
 // S, z (+)= partial[0] + partial[1] + ... + partial[C-1], in that order.
-// Every thread of the workgroup takes float4 slices of the kStateElems values.
-template <int THREADS>
+// Every thread of the workgroup takes 8-byte slices of the kStateElems values.
+// Partials come in through coherent loads; the loads of up to eight chunks for
+// all of a thread's slices are issued before the first one is consumed, so the
+// whole sum costs about one memory round trip per eight chunks.
+// COHERENT_OUT: also store the result coherently (other workgroups of this
+// kernel are going to read it).
+template <int THREADS, bool COHERENT_OUT>
 __device__ __forceinline__ void state_finalize(const float *__restrict__ partials, int C, int accumulate,
                                                float *__restrict__ S, float *__restrict__ z)
 {
-    constexpr int kVecs = kStateElems / 4;              // 1040 float4
-    for (int v = threadIdx.x; v < kVecs; v += THREADS) {
-        float *dst = v < 1024 ? S + 4 * v : z + 4 * (v - 1024);
-        f32x4 x = {0.f, 0.f, 0.f, 0.f};
-        if (accumulate) x = *reinterpret_cast<const f32x4 *>(dst);
-        int c = 0;
-        for (; c + 4 <= C; c += 4) {                    // four partials in flight, summed in order
-            const f32x4 p0 = *reinterpret_cast<const f32x4 *>(partials + (size_t)(c + 0) * kStateElems + 4 * v);
-            const f32x4 p1 = *reinterpret_cast<const f32x4 *>(partials + (size_t)(c + 1) * kStateElems + 4 * v);
-            const f32x4 p2 = *reinterpret_cast<const f32x4 *>(partials + (size_t)(c + 2) * kStateElems + 4 * v);
-            const f32x4 p3 = *reinterpret_cast<const f32x4 *>(partials + (size_t)(c + 3) * kStateElems + 4 * v);
-            x += p0; x += p1; x += p2; x += p3;
+    constexpr int kVecs = kStateElems / 2;                       // 2080 float2
+    constexpr int PER = (kVecs + THREADS - 1) / THREADS;         // slices per thread
+    constexpr int GROUP = 8;                                     // chunks in flight
+    const int tid = threadIdx.x;
+    f32x2 x[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const int v = tid + i * THREADS;
+        x[i] = f32x2{0.f, 0.f};
+        if (accumulate && v < kVecs) x[i] = *reinterpret_cast<const f32x2 *>(v < 2048 ? S + 2 * v : z + 2 * (v - 2048));
+    }
+    for (int c0 = 0; c0 < C; c0 += GROUP) {
+        f32x2 p[GROUP][PER];
+#pragma unroll
+        for (int cc = 0; cc < GROUP; ++cc)
+#pragma unroll
+            for (int i = 0; i < PER; ++i) {
+                const int v = tid + i * THREADS;
+                p[cc][i] = f32x2{0.f, 0.f};
+                if (c0 + cc < C && v < kVecs)
+                    p[cc][i] = load_coherent(partials + (size_t)(c0 + cc) * kStateElems + 2 * v);
+            }
+#pragma unroll
+        for (int cc = 0; cc < GROUP; ++cc)
+            if (c0 + cc < C) {
+#pragma unroll
+                for (int i = 0; i < PER; ++i) x[i] += p[cc][i];
+            }
+    }
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const int v = tid + i * THREADS;
+        if (v < kVecs) {
+            float *dst = v < 2048 ? S + 2 * v : z + 2 * (v - 2048);
+            if (COHERENT_OUT) store_coherent(dst, x[i]);
+            else *reinterpret_cast<f32x2 *>(dst) = x[i];
         }
-        for (; c < C; ++c) x += *reinterpret_cast<const f32x4 *>(partials + (size_t)c * kStateElems + 4 * v);
-        *reinterpret_cast<f32x4 *>(dst) = x;
     }
 }
 
@@ -316,7 +342,7 @@ __global__ __launch_bounds__(64 * WAVES, 1) void state_mfma_d64(
     state_wg_reduce_store<WAVES>(acc, reinterpret_cast<float *>(lds), wave, lane,
                                  partials + (size_t)c * kStateElems);
     if (state_arrive_is_last(ws, BH, bh, C, epoch, lds_word))
-        state_finalize<THREADS>(partials, C, accumulate, S + (size_t)bh * 64 * 64, z + (size_t)bh * 64);
+        state_finalize<THREADS, false>(partials, C, accumulate, S + (size_t)bh * 64 * 64, z + (size_t)bh * 64);
 }
 
 }  // namespace sv
