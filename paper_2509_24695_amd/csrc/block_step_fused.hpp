@@ -6,11 +6,12 @@
 // with O_b computed from the UPDATED state.  The grid is sized so that every
 // workgroup is resident at once (one per compute unit).  Each workgroup first
 // reduces its round-robin share of the block's keys and values to a partial
-// state; the last workgroup of a head to arrive folds the partials into the
-// carried S, z in chunk order and publishes an epoch-tagged "ready" flag; the
-// others meanwhile have their first Q tiles in flight and poll the flag (a
-// bounded number of times, so every wave always reaches the end of the kernel).
-// Then all of them apply the new state to their share of Q_b.  The dependency
+// state and publishes it with an epoch-tagged flag; when all partials of its
+// head are there it folds one slice of them into the carried S, z in chunk
+// order, publishes again, and waits for the other slices, with its first Q
+// tiles already in flight.  Every wait polls a bounded number of times, so
+// every wave always reaches the end of the kernel.  Then all workgroups apply
+// the new state to their share of Q_b.  The dependency
 // "all of the block's keys before any of its outputs" is per head, not grid
 // wide, so heads drift past each other and reads overlap writes.
 #pragma once
@@ -22,8 +23,8 @@ namespace sv {
 
 template <int TILE, int WAVES>
 __host__ __device__ constexpr int block_step_lds_bytes() {
-    return state_lds_bytes<TILE, WAVES>() > apply_lds_bytes<WAVES>() + 16 ? state_lds_bytes<TILE, WAVES>()
-                                                                          : apply_lds_bytes<WAVES>() + 16;
+    return state_lds_bytes<TILE, WAVES>() > apply_lds_bytes<WAVES>() ? state_lds_bytes<TILE, WAVES>()
+                                                                     : apply_lds_bytes<WAVES>();
 }
 
 // grid = (C, B*H) with C*B*H <= resident workgroup capacity, block = 64*WAVES.
@@ -36,7 +37,6 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma_d64(
     constexpr int THREADS = 64 * WAVES;
     constexpr int kTileBytes = TILE * kRowBytes;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-    uint32_t *lds_word = reinterpret_cast<uint32_t *>(lds + block_step_lds_bytes<TILE, WAVES>() - 16);
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1), wave = tid >> 6;
@@ -44,6 +44,13 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma_d64(
     const int b = bh / H, h = bh % H;
     const int64_t head_off = b * st.b + h * st.h;
     float *Sh = S + (size_t)bh * 64 * 64, *zh = z + (size_t)bh * 64;
+
+    // ---- this wave's first DEPTH_A tiles of Q_b are requested right away: they arrive during the
+    //      state phase and make no later load wait behind them -----------------------------------
+    const int n_tiles_q = (N + kApplyTile - 1) / kApplyTile;
+    const int first = WAVES * c + wave, step = WAVES * C;
+    u32x4 qreg[DEPTH_A][kApplyTile / 8];
+    apply_prefetch<DEPTH_A>(Q + head_off, st.n, 0, N, first, step, n_tiles_q, lane, qreg);
 
     // ---- fold this workgroup's share of K_b, V_b ------------------------------------------------
     {
@@ -58,26 +65,13 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma_d64(
                                      partials + (size_t)c * kStateElems);
     }
 
-    // ---- first Q tiles are requested before the head's state is waited for -----------------------
-    const int n_tiles_q = (N + kApplyTile - 1) / kApplyTile;
-    const int first = WAVES * c + wave, step = WAVES * C;
-    u32x4 qreg[DEPTH_A][kApplyTile / 8];
-    apply_prefetch<DEPTH_A>(Q + head_off, st.n, 0, N, first, step, n_tiles_q, lane, qreg);
-
-    // ---- last arriver of the head updates S, z in place and publishes ----------------------------
-    unsigned long long *ready = ws_ready(ws, BH, kStateElems) + bh;
-    if (state_arrive_is_last(ws, BH, bh, C, epoch, lds_word)) {
+    // ---- once all partials of the head are there, fold this workgroup's slice into S, z in place,
+    //      then wait for the other slices -------------------------------------------------------
+    {
         const float *partials = static_cast<const float *>(ws) + (size_t)bh * kMaxChunks * kStateElems;
-        state_finalize<THREADS, true>(partials, C, 1, Sh, zh);
-        coherent_stores_done();                        // every wave: its slice of the new state is performed
-        __syncthreads();
-        if (tid == 0) flag_publish(ready, epoch);
-    } else {
-        if (tid == 0) {
-            const bool ok = flag_wait(ready, epoch, spin_limit);
-            if (!ok) *ws_error(ws, BH, kStateElems) = epoch;      // never expected; results are invalid then
-        }
-        __syncthreads();                               // the new state is then read with coherent loads
+        state_publish_and_wait(ws, BH, bh, c, C, 0, epoch, spin_limit, lane);
+        state_finalize_slice<THREADS, true>(partials, c, C, 1, Sh, zh);
+        state_publish_and_wait(ws, BH, bh, c, C, 1, epoch, spin_limit, lane);
     }
 
     // ---- apply the updated state to this workgroup's share of Q_b ----------------------------------

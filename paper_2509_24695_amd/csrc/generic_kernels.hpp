@@ -76,9 +76,11 @@ __global__ __launch_bounds__(kThreads) void state_partial_generic(
 //   x = accumulate ? old : 0;  for c = 0..C-1: x += ws[bh][c][e]
 // The fixed order makes the result bit-reproducible (no float atomics).
 // grid = (ceil((D*D+D)/256), B*H).  C == 0 zero-fills or leaves the state as is.
+// Partial c of head bh starts at ws + (bh*chunk_stride + c) * (D*D+D).
 template <int D>
 __global__ __launch_bounds__(kThreads) void state_reduce(
-    const float *__restrict__ ws, int C, int accumulate, float *__restrict__ S, float *__restrict__ z)
+    const float *__restrict__ ws, int C, int chunk_stride, int accumulate, float *__restrict__ S,
+    float *__restrict__ z)
 {
     constexpr int E = D * D + D;
     const int e = blockIdx.x * kThreads + threadIdx.x;
@@ -86,7 +88,7 @@ __global__ __launch_bounds__(kThreads) void state_reduce(
     if (e >= E) return;
     float *dst = e < D * D ? S + (int64_t)bh * D * D + e : z + (int64_t)bh * D + (e - D * D);
     float x = accumulate ? *dst : 0.f;
-    const float *p = ws + (int64_t)bh * C * E + e;
+    const float *p = ws + (int64_t)bh * chunk_stride * E + e;
     for (int c = 0; c < C; ++c) x += p[(int64_t)c * E];
     *dst = x;
 }

@@ -19,8 +19,9 @@
 // One workgroup per compute unit and a round-robin deal of tiles keep the whole
 // grid streaming through a narrow, moving window of each head's tokens, which
 // is what HBM likes best; the loads of the next DEPTH tiles are always in
-// flight.  Workgroup partials go to the workspace; the last workgroup of a head
-// to arrive adds them up in chunk order (bit-reproducible, no float atomics).
+// flight.  Workgroup partials go to the workspace; once all partials of a head
+// are published, each of its workgroups adds up one slice of them in chunk
+// order (bit-reproducible, no float atomics).
 #pragma once
 
 #include "common.hpp"
@@ -34,23 +35,21 @@ constexpr int kSlotFloats = 72 * kWave;              // one wave's accumulators 
 
 // Workspace layout (B*H = BH heads, `elems` = d*d + d):
 //   float  partial[BH][kMaxChunks][elems]
-//   u64    arrivals[BH]      (epoch-tagged tickets)
-//   u64    ready[BH]         (epoch when the head's state is final; fused block step only)
-//   u64    error, pad        (non-zero if a bounded wait ever timed out)
+//   u64    flags[BH][2][kMaxChunks]   epoch-tagged: [0] partial c stored, [1] slice c of the new state stored
+//   u64    error, pad                 non-zero if a bounded wait ever timed out
 __host__ __device__ constexpr size_t ws_partial_bytes(int BH, int elems) {
     return (size_t)BH * kMaxChunks * elems * sizeof(float);
 }
-__host__ __device__ __forceinline__ unsigned long long *ws_arrivals(void *ws, int BH, int elems) {
-    return reinterpret_cast<unsigned long long *>(static_cast<unsigned char *>(ws) + ws_partial_bytes(BH, elems));
-}
-__host__ __device__ __forceinline__ unsigned long long *ws_ready(void *ws, int BH, int elems) {
-    return ws_arrivals(ws, BH, elems) + BH;
+__host__ __device__ __forceinline__ unsigned long long *ws_flags(void *ws, int BH, int elems, int bh, int phase) {
+    return reinterpret_cast<unsigned long long *>(static_cast<unsigned char *>(ws) + ws_partial_bytes(BH, elems)) +
+           ((size_t)bh * 2 + phase) * kMaxChunks;
 }
 __host__ __device__ __forceinline__ unsigned long long *ws_error(void *ws, int BH, int elems) {
-    return ws_arrivals(ws, BH, elems) + 2 * BH;
+    return reinterpret_cast<unsigned long long *>(static_cast<unsigned char *>(ws) + ws_partial_bytes(BH, elems)) +
+           (size_t)BH * 2 * kMaxChunks;
 }
 __host__ __device__ constexpr size_t ws_total_bytes(int BH, int elems) {
-    return ws_partial_bytes(BH, elems) + (size_t)(2 * BH + 2) * sizeof(unsigned long long);
+    return ws_partial_bytes(BH, elems) + ((size_t)BH * 2 * kMaxChunks + 2) * sizeof(unsigned long long);
 }
 
 // Registers of one lane: the 64x64 fp32 partial state as four 32x32 MFMA
@@ -170,14 +169,18 @@ __device__ __forceinline__ void state_accumulate(const uint16_t *Kh, const uint1
     }
 }
 
-// Adds the WAVES waves' accumulators in a fixed tree order through two LDS
-// slots and lets wave 0 write the workgroup's partial state, S in [k][v] order
-// followed by z, to `out` (kStateElems floats).  Must be called by all threads;
-// the staging tiles are dead afterwards.
+// Adds the WAVES waves' accumulators in a fixed tree order and stores the
+// workgroup's partial state, S in [k][v] order followed by z, to `out`
+// (kStateElems floats) with coherent stores spread over all threads.  The tree
+// runs register-major through two LDS slots until two waves are left; those two
+// write their sums in [k][v] order and every thread adds and stores its share.
+// Must be called by all threads; the staging tiles are dead afterwards.
 template <int WAVES>
 __device__ __forceinline__ void state_wg_reduce_store(StateAcc &acc, float *slot, int wave, int lane,
                                                       float *__restrict__ out)
 {
+    static_assert(WAVES == 4 || WAVES == 8, "tree below assumes 4 or 8 waves");
+    constexpr int THREADS = 64 * WAVES;
     auto put = [&](float *dst) {
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb)
@@ -200,7 +203,7 @@ __device__ __forceinline__ void state_wg_reduce_store(StateAcc &acc, float *slot
     };
     __syncthreads();                                   // all waves are done with their staging tiles
 #pragma unroll
-    for (int h = WAVES / 2; h >= 1; h /= 2) {          // wave w absorbs wave w + h
+    for (int h = WAVES / 2; h >= 2; h /= 2) {          // wave w absorbs wave w + h
 #pragma unroll
         for (int base = 0; base < h; base += 2) {      // two waves at a time (two slots)
             if (wave >= h + base && wave < h + base + 2 && wave < 2 * h) put(slot + (wave - h - base) * kSlotFloats);
@@ -209,120 +212,112 @@ __device__ __forceinline__ void state_wg_reduce_store(StateAcc &acc, float *slot
             __syncthreads();
         }
     }
-    if (wave != 0) return;
-
-    // 32x32 accumulator layout: register i of lane l is row 8*(i/4) + 4*(l/32) + i%4, column l%32.
-    const int r = lane & 31, g = lane >> 5;
+    // waves 0 and 1 lay their sums out as [k][v] then z (kStateElems floats each)
+    if (wave < 2) {
+        float *dst = slot + wave * kSlotFloats;
+        // 32x32 accumulator layout: register i of lane l is row 8*(i/4) + 4*(l/32) + i%4, column l%32.
+        const int r = lane & 31, g = lane >> 5;
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
+        for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int m = 8 * (i >> 2) + 4 * g + (i & 3);
-            const int k = 2 * m + rb;
-            f32x2 pair = {acc.s[rb][0][i], acc.s[rb][1][i]};       // value features 2r, 2r+1
-            store_coherent(out + k * 64 + 2 * r, pair);
+            for (int i = 0; i < 16; ++i) {
+                const int m = 8 * (i >> 2) + 4 * g + (i & 3);
+                const int k = 2 * m + rb;
+                f32x2 pair = {acc.s[rb][0][i], acc.s[rb][1][i]};   // value features 2r, 2r+1
+                *reinterpret_cast<f32x2 *>(dst + k * 64 + 2 * r) = pair;
+            }
+        // key sum: lanes with equal lane%8 hold the same 8 features (wavefront-level reduction)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float x = acc.z[e];
+            x += __shfl_xor(x, 8);
+            x += __shfl_xor(x, 16);
+            x += __shfl_xor(x, 32);
+            acc.z[e] = x;
         }
-    // key sum: lanes with equal lane%8 hold the same 8 features (wavefront-level reduction)
+        if (lane < 8) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        float x = acc.z[e];
-        x += __shfl_xor(x, 8);
-        x += __shfl_xor(x, 16);
-        x += __shfl_xor(x, 32);
-        acc.z[e] = x;
+            for (int e = 0; e < 8; ++e) dst[64 * 64 + lane * 8 + e] = acc.z[e];
+        }
     }
-    if (lane < 8) {
-#pragma unroll
-        for (int e = 0; e < 8; e += 2) {
-            f32x2 pair = {acc.z[e], acc.z[e + 1]};
-            store_coherent(out + 64 * 64 + lane * 8 + e, pair);
-        }
+    __syncthreads();
+    for (int v = threadIdx.x; v < kStateElems / 2; v += THREADS) {
+        const f32x2 a = *reinterpret_cast<const f32x2 *>(slot + 2 * v);
+        const f32x2 b = *reinterpret_cast<const f32x2 *>(slot + kSlotFloats + 2 * v);
+        store_coherent(out + 2 * v, a + b);
     }
 }
 
-// The calling workgroup has just stored partial `c` of head `bh`.  Returns true
-// in exactly one workgroup per head and call: the last one to arrive, after it
-// has made all C partials of the head visible to itself.
-__device__ __forceinline__ bool state_arrive_is_last(void *ws, int BH, int bh, int C, unsigned long long epoch,
-                                                     uint32_t *lds_word)
-{
-    coherent_stores_done();                             // this wave's partial-state stores are performed
-    __syncthreads();
-    if (threadIdx.x == 0) *lds_word = ticket_take(ws_arrivals(ws, BH, kStateElems) + bh, epoch);
-    __syncthreads();
-    return *lds_word == (uint32_t)(C - 1);              // the partials are then read with coherent loads
-}
-
-// S, z (+)= partial[0] + partial[1] + ... + partial[C-1], in that order.
-// Every thread of the workgroup takes 8-byte slices of the kStateElems values.
-// Partials come in through coherent loads; the loads of up to eight chunks for
-// all of a thread's slices are issued before the first one is consumed, so the
-// whole sum costs about one memory round trip per eight chunks.
+// Slice c of the head's state (8-byte units [c*per, (c+1)*per) of the
+// kStateElems values, per = ceil(2080 / C)):
+//   S, z (+)= partial[0] + partial[1] + ... + partial[C-1], in that order.
+// Partials come in through coherent loads, up to eight chunks in flight.
 // COHERENT_OUT: also store the result coherently (other workgroups of this
 // kernel are going to read it).
 template <int THREADS, bool COHERENT_OUT>
-__device__ __forceinline__ void state_finalize(const float *__restrict__ partials, int C, int accumulate,
-                                               float *__restrict__ S, float *__restrict__ z)
+__device__ __forceinline__ void state_finalize_slice(const float *__restrict__ partials, int c, int C, int accumulate,
+                                                     float *__restrict__ S, float *__restrict__ z)
 {
     constexpr int kVecs = kStateElems / 2;                       // 2080 float2
-    constexpr int PER = (kVecs + THREADS - 1) / THREADS;         // slices per thread
     constexpr int GROUP = 8;                                     // chunks in flight
-    const int tid = threadIdx.x;
-    f32x2 x[PER];
+    const int per = (kVecs + C - 1) / C;
+    const int lo = c * per, hi = lo + per < kVecs ? lo + per : kVecs;
+    for (int v = lo + (int)threadIdx.x; v < hi; v += THREADS) {
+        float *dst = v < 2048 ? S + 2 * v : z + 2 * (v - 2048);
+        f32x2 x = {0.f, 0.f};
+        if (accumulate) x = *reinterpret_cast<const f32x2 *>(dst);
+        for (int c0 = 0; c0 < C; c0 += GROUP) {
+            f32x2 p[GROUP];
 #pragma unroll
-    for (int i = 0; i < PER; ++i) {
-        const int v = tid + i * THREADS;
-        x[i] = f32x2{0.f, 0.f};
-        if (accumulate && v < kVecs) x[i] = *reinterpret_cast<const f32x2 *>(v < 2048 ? S + 2 * v : z + 2 * (v - 2048));
-    }
-    for (int c0 = 0; c0 < C; c0 += GROUP) {
-        f32x2 p[GROUP][PER];
-#pragma unroll
-        for (int cc = 0; cc < GROUP; ++cc)
-#pragma unroll
-            for (int i = 0; i < PER; ++i) {
-                const int v = tid + i * THREADS;
-                p[cc][i] = f32x2{0.f, 0.f};
-                if (c0 + cc < C && v < kVecs)
-                    p[cc][i] = load_coherent(partials + (size_t)(c0 + cc) * kStateElems + 2 * v);
+            for (int cc = 0; cc < GROUP; ++cc) {
+                p[cc] = f32x2{0.f, 0.f};
+                if (c0 + cc < C) p[cc] = load_coherent(partials + (size_t)(c0 + cc) * kStateElems + 2 * v);
             }
 #pragma unroll
-        for (int cc = 0; cc < GROUP; ++cc)
-            if (c0 + cc < C) {
-#pragma unroll
-                for (int i = 0; i < PER; ++i) x[i] += p[cc][i];
-            }
-    }
-#pragma unroll
-    for (int i = 0; i < PER; ++i) {
-        const int v = tid + i * THREADS;
-        if (v < kVecs) {
-            float *dst = v < 2048 ? S + 2 * v : z + 2 * (v - 2048);
-            if (COHERENT_OUT) store_coherent(dst, x[i]);
-            else *reinterpret_cast<f32x2 *>(dst) = x[i];
+            for (int cc = 0; cc < GROUP; ++cc)
+                if (c0 + cc < C) x += p[cc];
         }
+        if (COHERENT_OUT) store_coherent(dst, x);
+        else *reinterpret_cast<f32x2 *>(dst) = x;
     }
 }
 
-// Dynamic LDS of state_mfma_d64: staging tiles or reduction slots, plus one word.
+// The calling workgroup has just issued the stores of partial `c` of head `bh`:
+// publish it, then wait until all C partials of the head are published.
+// Returns false if the bounded wait ran out.  All threads must call.
+__device__ __forceinline__ bool state_publish_and_wait(void *ws, int BH, int bh, int c, int C, int phase,
+                                                       unsigned long long epoch, uint32_t spin_limit, int lane)
+{
+    unsigned long long *flags = ws_flags(ws, BH, kStateElems, bh, phase);
+    coherent_stores_done();                             // this wave's stores are performed
+    __syncthreads();
+    if (threadIdx.x == 0) flag_publish(flags + c, epoch);
+    const bool ok = flags_wait_all(flags, C, epoch, spin_limit, lane);
+    if (!ok && threadIdx.x == 0) *ws_error(ws, BH, kStateElems) = epoch;
+    return ok;
+}
+
+// Dynamic LDS of state_mfma_d64: staging tiles or reduction slots.
 template <int TILE, int WAVES>
 __host__ __device__ constexpr int state_lds_bytes() {
     constexpr int stage = WAVES * 2 * TILE * kRowBytes, red = 2 * kSlotFloats * 4;
-    return (stage > red ? stage : red) + 16;
+    return stage > red ? stage : red;
 }
 
 // grid = (C, B*H), block = 64*WAVES.  Wave w of workgroup c owns tiles
 // WAVES*c + w + WAVES*C*i (i = 0, 1, ...) of the T = ceil((t1-t0)/TILE) tiles.
-template <int TILE, int WAVES, int DEPTH>
+// FINALIZE: the C workgroups of a head wait for each other's partials and each
+// folds one slice of them into S, z; this needs the whole grid to be resident.
+// Otherwise only the partials are written and state_reduce finishes the job.
+template <int TILE, int WAVES, int DEPTH, bool FINALIZE>
 __global__ __launch_bounds__(64 * WAVES, 1) void state_mfma_d64(
     const uint16_t *__restrict__ K, const uint16_t *__restrict__ V, TokStrides st, int H, int t0, int t1,
     int C, int accumulate, float *__restrict__ S, float *__restrict__ z, void *__restrict__ ws,
-    unsigned long long epoch)
+    unsigned long long epoch, uint32_t spin_limit)
 {
     constexpr int THREADS = 64 * WAVES;
     constexpr int kTileBytes = TILE * kRowBytes;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-    uint32_t *lds_word = reinterpret_cast<uint32_t *>(lds + state_lds_bytes<TILE, WAVES>() - 16);
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1), wave = tid >> 6;
@@ -341,8 +336,11 @@ __global__ __launch_bounds__(64 * WAVES, 1) void state_mfma_d64(
     float *partials = static_cast<float *>(ws) + (size_t)bh * kMaxChunks * kStateElems;
     state_wg_reduce_store<WAVES>(acc, reinterpret_cast<float *>(lds), wave, lane,
                                  partials + (size_t)c * kStateElems);
-    if (state_arrive_is_last(ws, BH, bh, C, epoch, lds_word))
-        state_finalize<THREADS, false>(partials, C, accumulate, S + (size_t)bh * 64 * 64, z + (size_t)bh * 64);
+    if (FINALIZE) {
+        state_publish_and_wait(ws, BH, bh, c, C, 0, epoch, spin_limit, lane);
+        state_finalize_slice<THREADS, false>(partials, c, C, accumulate, S + (size_t)bh * 64 * 64,
+                                             z + (size_t)bh * 64);
+    }
 }
 
 }  // namespace sv

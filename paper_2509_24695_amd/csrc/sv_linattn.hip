@@ -36,11 +36,13 @@ struct Shape {
 
 struct Device {
     int num_cu = 0;
-    int fused_resident_wgs = 0;     // how many block-step workgroups fit on the device at once
+    int state_resident_wgs = 0;     // how many state workgroups fit on the device at once
+    int fused_resident_wgs = 0;     // the same for the one-launch block step
     bool ok = false;
 };
 
-auto *const kStateKernel = state_mfma_d64<kStateTile, kStateWaves, kStateDepth>;
+auto *const kStateKernel = state_mfma_d64<kStateTile, kStateWaves, kStateDepth, true>;
+auto *const kStatePartialKernel = state_mfma_d64<kStateTile, kStateWaves, kStateDepth, false>;
 auto *const kApplyKernel = apply_mfma_d64<kApplyHiLo, kApplyWaves, kApplyDepth>;
 auto *const kFusedKernel = block_step_mfma_d64<kStateTile, kStateWaves, kStateDepth, kApplyHiLo, kApplyDepth>;
 constexpr int kStateLds = state_lds_bytes<kStateTile, kStateWaves>();
@@ -65,6 +67,8 @@ const Device &device_info()
         d.num_cu = prop.multiProcessorCount;
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kStateKernel),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, kStateLds);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kStatePartialKernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, kStateLds);
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kApplyKernel),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, kApplyLds);
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kFusedKernel),
@@ -74,20 +78,25 @@ const Device &device_info()
                                                          64 * kStateWaves, kFusedLds) != hipSuccess)
             per_cu = 0;
         d.fused_resident_wgs = per_cu * d.num_cu;
+        per_cu = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(kStateKernel),
+                                                         64 * kStateWaves, kStateLds) != hipSuccess)
+            per_cu = 0;
+        d.state_resident_wgs = per_cu * d.num_cu;
         (void)hipGetLastError();
         d.ok = d.num_cu > 0;
     }
     return d;
 }
 
-// Fresh 40-bit tag for the workspace's counters and flags; unique per call
-// within the process and seeded from the clock so that stale workspace
-// contents of an earlier process do not look current.
+// Fresh 64-bit tag for the workspace's flags; unique per call within the process
+// and seeded from the clock so that stale workspace contents of an earlier
+// process do not look current.
 unsigned long long next_epoch()
 {
     static std::atomic<unsigned long long> ctr{
-        (unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count() * 2654435761ull};
-    return (ctr.fetch_add(1, std::memory_order_relaxed) & ((1ull << 40) - 1)) | 1ull << 39;
+        (unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count() * 0x9E3779B97F4A7C15ull};
+    return (ctr.fetch_add(1, std::memory_order_relaxed) << 1) | 1ull;   // odd, never zero, never repeated
 }
 
 // Token chunks (workgroups) per head: about one workgroup per compute unit over
@@ -147,15 +156,23 @@ sv_status enqueue_state(const void *K, const void *V, const Shape &s, int t0, in
     const int E = s.d * s.d + s.d;
     const dim3 rgrid((E + kThreads - 1) / kThreads, s.BH);
     if (n == 0) {                                   // overwrite with the empty sum
-        if (s.d == 64) state_reduce<64><<<rgrid, kThreads, 0, stream>>>(static_cast<float *>(ws), 0, 0, S, z);
-        else state_reduce<32><<<rgrid, kThreads, 0, stream>>>(static_cast<float *>(ws), 0, 0, S, z);
+        if (s.d == 64) state_reduce<64><<<rgrid, kThreads, 0, stream>>>(static_cast<float *>(ws), 0, 0, 0, S, z);
+        else state_reduce<32><<<rgrid, kThreads, 0, stream>>>(static_cast<float *>(ws), 0, 0, 0, S, z);
         return launch_status();
     }
     if (s.bf16 && s.d == 64) {
         const int C = plan_chunks(s.BH, n, kStateTile * kStateWaves, dev.num_cu);
-        kStateKernel<<<dim3(C, s.BH), 64 * kStateWaves, kStateLds, stream>>>(
-            static_cast<const uint16_t *>(K), static_cast<const uint16_t *>(V), s.st, s.H, t0, t1, C, accumulate, S, z,
-            ws, next_epoch());
+        auto *k = static_cast<const uint16_t *>(K);
+        auto *v = static_cast<const uint16_t *>(V);
+        if ((int64_t)C * s.BH <= dev.state_resident_wgs) {
+            // the head's workgroups wait for each other inside the kernel: all must be resident
+            kStateKernel<<<dim3(C, s.BH), 64 * kStateWaves, kStateLds, stream>>>(
+                k, v, s.st, s.H, t0, t1, C, accumulate, S, z, ws, next_epoch(), kSpinLimit);
+        } else {
+            kStatePartialKernel<<<dim3(C, s.BH), 64 * kStateWaves, kStateLds, stream>>>(
+                k, v, s.st, s.H, t0, t1, C, accumulate, S, z, ws, 0ull, 0u);
+            state_reduce<64><<<rgrid, kThreads, 0, stream>>>(static_cast<float *>(ws), C, kMaxChunks, accumulate, S, z);
+        }
         return launch_status();
     }
     // fp32 validation mode and bf16 d = 32: plain-FMA partials, then the fixed-order reduction
@@ -172,8 +189,8 @@ sv_status enqueue_state(const void *K, const void *V, const Shape &s, int t0, in
         state_partial_generic<float, 32><<<grid, kThreads, 0, stream>>>(
             static_cast<const float *>(K), static_cast<const float *>(V), s.st, s.H, t0, t1, C, wsf);
     }
-    if (s.d == 64) state_reduce<64><<<rgrid, kThreads, 0, stream>>>(wsf, C, accumulate, S, z);
-    else state_reduce<32><<<rgrid, kThreads, 0, stream>>>(wsf, C, accumulate, S, z);
+    if (s.d == 64) state_reduce<64><<<rgrid, kThreads, 0, stream>>>(wsf, C, C, accumulate, S, z);
+    else state_reduce<32><<<rgrid, kThreads, 0, stream>>>(wsf, C, C, accumulate, S, z);
     return launch_status();
 }
 

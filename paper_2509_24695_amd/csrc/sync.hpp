@@ -7,9 +7,8 @@
 //
 // The workspace a caller hands in has undefined contents, and the library may
 // not spend a launch on clearing it.  Every call therefore draws a fresh
-// 40-bit epoch on the host; counters and flags in the workspace carry the
-// epoch in their upper bits, and a word whose epoch differs from the current
-// call's is treated as "not yet touched by this call".
+// epoch on the host; a flag word in the workspace that does not hold the
+// current call's epoch means "not yet published in this call".
 #pragma once
 
 #include "common.hpp"
@@ -39,34 +38,30 @@ __device__ __forceinline__ void coherent_stores_done() {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
-constexpr int kEpochShift = 24;                              // low 24 bits: arrival count
-constexpr unsigned long long kCountMask = (1ull << kEpochShift) - 1;
-
-// Arrival ticket 0..n-1 of the calling workgroup for this epoch.  Stale contents
-// (another epoch, or garbage) count as zero arrivals.
-__device__ __forceinline__ uint32_t ticket_take(unsigned long long *ctr, unsigned long long epoch)
-{
-    unsigned long long old = __hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    for (;;) {
-        const unsigned long long nw = ((old >> kEpochShift) == epoch) ? old + 1 : ((epoch << kEpochShift) | 1ull);
-        if (__hip_atomic_compare_exchange_strong(ctr, &old, nw, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
-                                                 __HIP_MEMORY_SCOPE_AGENT))
-            return (uint32_t)(nw & kCountMask) - 1u;
-    }
-}
-
+// Epoch-tagged arrival flags.  A workgroup publishes by storing the call's
+// epoch into its own word (after its data stores have been performed); nobody
+// ever needs a read-modify-write, so one signal costs one store and one poll.
 __device__ __forceinline__ void flag_publish(unsigned long long *flag, unsigned long long epoch)
 {
     __hip_atomic_store(flag, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Spins until *flag == epoch, at most `spin_limit` polls; returns false on
-// timeout so that every wave still reaches the end of the kernel.
-__device__ __forceinline__ bool flag_wait(const unsigned long long *flag, unsigned long long epoch, uint32_t spin_limit)
+// Every lane of the calling wave polls until the first n (<= 64) words at
+// `flags` all hold `epoch`; lane i watches word i.  At most `spin_limit` polls:
+// returns false on timeout so that every wave still reaches the end of the
+// kernel.  Loads issued after a true return observe everything the publishers
+// stored coherently before publishing.
+__device__ __forceinline__ bool flags_wait_all(const unsigned long long *flags, int n, unsigned long long epoch,
+                                               uint32_t spin_limit, int lane)
 {
     for (uint32_t i = 0; i < spin_limit; ++i) {
-        if (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == epoch) return true;
-        __builtin_amdgcn_s_sleep(2);
+        unsigned long long v = epoch;
+        if (lane < n) v = __hip_atomic_load(flags + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (__all(v == epoch)) {
+            asm volatile("" ::: "memory");
+            return true;
+        }
+        __builtin_amdgcn_s_sleep(1);
     }
     return false;
 }
