@@ -9,8 +9,9 @@ device and resident in HBM before the timed region starts; buffer sets rotate
 so that repeats are not served from the 256 MB Infinity Cache.
 
 Prints ONE JSON line.  `value` is tokens/s of the layer (B*N / time per step).
-`roofline` refers to the slower of the two kernels of a step (state-partial or
-apply), timed with HIP events on the launch stream inside the timed region.
+`roofline` refers to the slower of the two kernels of a step (state or apply),
+timed with HIP events on the launch stream over a second pass of the same steps
+(events between kernels cost a few microseconds, so they stay out of `value`).
 `cpu_baseline` is the float64 oracle timed on the host cores on the same
 workload.  Block-causal workloads are reported under `block_stream`.
 """
@@ -29,6 +30,15 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of this file, each counter
+# scaled by what it reads for a plain device copy of known size (FETCH_SIZE x 1.9997: it books the
+# 128-byte requests these kernels and the copy issue as 64 bytes; WRITE_SIZE x 1.0000).  Source:
+# profiles/traffic_pmc_bidir_480p.txt.  Algorithmic bytes per launch are 268 369 920.
+MEASURED_TRAFFIC_BYTES = {
+    ("apply", "bidir_480p"): int((67677.5 * 1.99965 + 131040.0) * 1024),
+    ("state", "bidir_480p"): int((133367.3 * 1.99965 + 4688.0) * 1024),
+}
+
 
 def _parse():
     ap = argparse.ArgumentParser()
@@ -40,6 +50,9 @@ def _parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-block-stream", action="store_true")
     ap.add_argument("--stream-blocks", type=int, default=80)
+    ap.add_argument("--calibration-copy", type=int, default=0,
+                    help="also run this many plain device copies of one token tensor (known size: "
+                         "the same bytes read and written), for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE")
     return ap.parse_args()
 
 
@@ -78,20 +91,26 @@ def bench_bidirectional(w, steps, warmup, n_sets, sv, torch):
     for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
+    # timed region: exactly `steps` steps, nothing else on the stream
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    # second pass of `steps` steps with HIP events on the launch stream around each call: per-kernel
+    # durations (an event between two kernels costs a few microseconds, so this pass is not `value`)
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
+    t1 = time.perf_counter()
     for i in range(steps):
         step(i, events[i])
     torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+    wall_ev = time.perf_counter() - t1
     t_state = [e[0].elapsed_time(e[1]) for e in events]      # ms
     t_apply = [e[1].elapsed_time(e[2]) for e in events]
-    t_step_ev = [e[0].elapsed_time(e[2]) for e in events]
     return {
-        "ms_per_step": wall / steps * 1e3,
+        "ms_per_step": wall / steps * 1e3, "ms_per_step_with_events": wall_ev / steps * 1e3,
         "ms_state": statistics.mean(t_state), "ms_apply": statistics.mean(t_apply),
-        "ms_step_events_median": statistics.median(t_step_ev),
         "n_sets": n_sets, "sets": sets,
     }
 
@@ -218,12 +237,21 @@ def main():
         "tflops": w.algorithmic_flops / sec / 1e12,
         "hbm_GBps_step": w.algorithmic_bytes / sec / 1e9,
         "hbm_frac_step": w.algorithmic_bytes / sec / 1e9 / HBM_PEAK_GBPS,
-        "kernels_ms": {"state(partial+reduce)": r["ms_state"], "apply": r["ms_apply"],
-                       "step_events_median": r["ms_step_events_median"]},
+        "kernels_ms": {"state": r["ms_state"], "apply": r["ms_apply"],
+                       "step_with_events": r["ms_per_step_with_events"]},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((dom, w.name)),
                      "algorithmic_bytes_per_launch": half, "avg_launch_ms": dom_ms},
     }
+    if args.calibration_copy > 0:
+        src = r["sets"][0][0]
+        dst = torch.empty_like(src)
+        for _ in range(args.calibration_copy):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["calibration_copy"] = {"copies": args.calibration_copy, "bytes_read_each": src.numel() * 2,
+                                   "bytes_written_each": src.numel() * 2}
     if not args.no_block_stream:
         out["block_stream"] = [
             bench_block_stream(wl.workload("block_480p"), 10, sv, torch),

@@ -92,17 +92,21 @@ def state(K, V, t0=None, t1=None, S=None, z=None):
 
 def apply(Q, S, z, eps, t0=None, t1=None):
     """O for tokens [t0, t1) (shape [B][H][t1-t0][d]) from a given state."""
-    Q = _widen(Q)
-    B, H, N, d = Q.shape
+    Q = np.asarray(Q)
+    if Q.ndim != 4:
+        raise ValueError("tokens must be [B][H][N][d]")
+    N = Q.shape[2]
     t0 = 0 if t0 is None else int(t0)
     t1 = N if t1 is None else int(t1)
     if not 0 <= t0 <= t1 <= N:
         raise ValueError("token range out of bounds")
+    Q = _widen(Q[:, :, t0:t1, :])                 # only the rows that are asked for
+    B, H, n, d = Q.shape
     S = np.ascontiguousarray(S, dtype=np.float64).reshape(B, H, d, d)
     z = np.ascontiguousarray(z, dtype=np.float64).reshape(B, H, d)
-    O = np.zeros((B, H, N, d), np.float64)
-    _load().orc_apply(_p(Q), B, H, N, d, t0, t1, _p(S), _p(z), float(eps), _p(O))
-    return np.ascontiguousarray(O[:, :, t0:t1, :])
+    O = np.zeros((B, H, n, d), np.float64)
+    _load().orc_apply(_p(Q), B, H, n, d, 0, n, _p(S), _p(z), float(eps), _p(O))
+    return O
 
 
 def bidirectional(Q, K, V, eps):
