@@ -114,14 +114,14 @@ struct ApplyOperands {
 // One wave's share of the token range [t0, t1): tiles first_tile, first_tile +
 // tile_step, ... below n_tiles (32 tokens each).  `tileQ` is this wave's private
 // LDS tile (kApplyTile * kRowBytes bytes).  `qreg` holds the first DEPTH tiles,
-// already requested by the caller with apply_prefetch.
-template <int DEPTH>
+// already requested by the caller with apply_prefetch (stages FROM..TO-1 per call).
+template <int DEPTH, int FROM = 0, int TO = DEPTH>
 __device__ __forceinline__ void apply_prefetch(const uint16_t *Qh, int64_t stride_n, int t0, int t1, int first_tile,
                                                int tile_step, int n_tiles, int lane,
                                                u32x4 (&qreg)[DEPTH][kApplyTile / 8])
 {
 #pragma unroll
-    for (int s = 0; s < DEPTH; ++s) {
+    for (int s = FROM; s < TO; ++s) {
         const int t = first_tile + s * tile_step;
         if (t < n_tiles) apply_tile_load(Qh, stride_n, t0 + t * kApplyTile, t1, lane, qreg[s]);
     }

@@ -45,12 +45,13 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma_d64(
     const int64_t head_off = b * st.b + h * st.h;
     float *Sh = S + (size_t)bh * 64 * 64, *zh = z + (size_t)bh * 64;
 
-    // ---- this wave's first DEPTH_A tiles of Q_b are requested right away: they arrive during the
-    //      state phase and make no later load wait behind them -----------------------------------
+    // ---- this wave's first two tiles of Q_b are requested right away: they arrive during the state
+    //      phase and make no later load wait behind them ---------------------------------------------
     const int n_tiles_q = (N + kApplyTile - 1) / kApplyTile;
     const int first = WAVES * c + wave, step = WAVES * C;
+    constexpr int kEarly = DEPTH_A < 2 ? DEPTH_A : 2;
     u32x4 qreg[DEPTH_A][kApplyTile / 8];
-    apply_prefetch<DEPTH_A>(Q + head_off, st.n, 0, N, first, step, n_tiles_q, lane, qreg);
+    apply_prefetch<DEPTH_A, 0, kEarly>(Q + head_off, st.n, 0, N, first, step, n_tiles_q, lane, qreg);
 
     // ---- fold this workgroup's share of K_b, V_b ------------------------------------------------
     {
@@ -60,6 +61,8 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma_d64(
         unsigned char *tileK = lds + wave * 2 * kTileBytes;
         state_accumulate<TILE, DEPTH_S>(K + head_off, V + head_off, st.n, 0, N, WAVES * c + wave, WAVES * C, n_tiles,
                                         tileK, tileK + kTileBytes, lane, acc);
+        // the rest of this wave's Q prefetch streams in while the head's state is being agreed on
+        apply_prefetch<DEPTH_A, kEarly, DEPTH_A>(Q + head_off, st.n, 0, N, first, step, n_tiles_q, lane, qreg);
         float *partials = static_cast<float *>(ws) + (size_t)bh * kMaxChunks * kStateElems;
         state_wg_reduce_store<WAVES>(acc, reinterpret_cast<float *>(lds), wave, lane,
                                      partials + (size_t)c * kStateElems);
