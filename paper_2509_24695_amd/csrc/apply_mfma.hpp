@@ -127,93 +127,132 @@ __device__ __forceinline__ void apply_prefetch(const uint16_t *Qh, int64_t strid
     }
 }
 
-template <bool HILO, int DEPTH>
+template <bool HILO, int DEPTH, int NB>
 __device__ __forceinline__ void apply_tiles(const uint16_t *Qh, uint16_t *Oh, int64_t stride_n, int t0, int t1,
                                             int first_tile, int tile_step, int n_tiles, unsigned char *tileQ,
                                             int lane, const ApplyOperands<HILO> &A, float eps,
                                             u32x4 (&qreg)[DEPTH][kApplyTile / 8])
 {
+    static_assert(DEPTH % NB == 0, "stages are consumed NB at a time");
     constexpr int NS = HILO ? 2 : 1;
+    constexpr int kTileBytes = kApplyTile * kRowBytes;
     const int n = lane & 31, g = lane >> 5;
     const int wr_off = (lane >> 3) * kRowBytes + (lane & 7) * 16;
 
+    // NB tiles go through each phase together, so that one tile's LDS and
+    // conversion latencies hide behind the other's MFMA chain.
     int tile = first_tile;
     while (tile < n_tiles) {
 #pragma unroll
-        for (int s = 0; s < DEPTH; ++s) {
+        for (int s0 = 0; s0 < DEPTH; s0 += NB) {
             if (tile < n_tiles) {
-                const int tok0 = t0 + tile * kApplyTile;
+                bool valid[NB];
+#pragma unroll
+                for (int j = 0; j < NB; ++j) valid[j] = tile + j * tile_step < n_tiles;
+
                 wave_lds_fence();
 #pragma unroll
-                for (int i = 0; i < kApplyTile / 8; ++i)
-                    *reinterpret_cast<u32x4 *>(tileQ + wr_off + 8 * i * kRowBytes) = relu_bf16x8(qreg[s][i]);   // phi(Q)
-                const int nxt = tile + DEPTH * tile_step;
-                if (nxt < n_tiles) apply_tile_load(Qh, stride_n, t0 + nxt * kApplyTile, t1, lane, qreg[s]);
+                for (int j = 0; j < NB; ++j)
+                    if (valid[j]) {
+#pragma unroll
+                        for (int i = 0; i < kApplyTile / 8; ++i)
+                            *reinterpret_cast<u32x4 *>(tileQ + j * kTileBytes + wr_off + 8 * i * kRowBytes) =
+                                relu_bf16x8(qreg[s0 + j][i]);                                   // phi(Q)
+                        const int nxt = tile + (j + DEPTH) * tile_step;
+                        if (nxt < n_tiles)
+                            apply_tile_load(Qh, stride_n, t0 + nxt * kApplyTile, t1, lane, qreg[s0 + j]);
+                    }
                 wave_lds_fence();
 
                 // B operands: features 16*ks + 8g .. +8 of token n
-                bf16x8 Bq[4];
+                bf16x8 Bq[NB][4];
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks)
-                    Bq[ks] = *reinterpret_cast<const bf16x8 *>(tileQ + n * kRowBytes + (16 * ks + 8 * g) * 2);
+                for (int j = 0; j < NB; ++j)
+                    if (valid[j]) {
+#pragma unroll
+                        for (int ks = 0; ks < 4; ++ks)
+                            Bq[j][ks] = *reinterpret_cast<const bf16x8 *>(tileQ + j * kTileBytes + n * kRowBytes +
+                                                                          (16 * ks + 8 * g) * 2);
+                    }
 
-                f32x16 acc[2], accz;
+                f32x16 acc[NB][2], accz[NB];
 #pragma unroll
-                for (int i = 0; i < 16; ++i) { acc[0][i] = 0.f; acc[1][i] = 0.f; accz[i] = 0.f; }
+                for (int j = 0; j < NB; ++j)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) { acc[j][0][i] = 0.f; acc[j][1][i] = 0.f; accz[j][i] = 0.f; }
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks)
-                    accz = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.zrow[ks], Bq[ks], accz, 0, 0, 0);
+#pragma unroll
+                    for (int j = 0; j < NB; ++j)
+                        if (valid[j])
+                            accz[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.zrow[ks], Bq[j][ks], accz[j], 0, 0, 0);
 #pragma unroll
                 for (int p = NS - 1; p >= 0; --p)      // small (lo) terms first
 #pragma unroll
-                    for (int ks = 0; ks < 4; ++ks) {
-                        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.s[p][0][ks], Bq[ks], acc[0], 0, 0, 0);
-                        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.s[p][1][ks], Bq[ks], acc[1], 0, 0, 0);
+                    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                        for (int j = 0; j < NB; ++j)
+                            if (valid[j]) {
+                                acc[j][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.s[p][0][ks], Bq[j][ks],
+                                                                                    acc[j][0], 0, 0, 0);
+                                acc[j][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.s[p][1][ks], Bq[j][ks],
+                                                                                    acc[j][1], 0, 0, 0);
+                            }
+
+                wave_lds_fence();
+#pragma unroll
+                for (int j = 0; j < NB; ++j)
+                    if (valid[j]) {
+                        // denominator: rows 0 (hi) and 1 (lo) of the z block sit in registers 0 and 1 of
+                        // the lanes of the lower half; the upper half fetches them across the wave
+                        float den = accz[j][1] + accz[j][0];
+                        den = __shfl(den, n);
+                        const float inv = 1.0f / (den + eps);
+#pragma unroll
+                        for (int rb = 0; rb < 2; ++rb) {
+                            const f32x16 &a = acc[j][rb];
+                            u32x4 lo4, hi4;
+                            lo4.x = pack_bf16x2(a[0] * inv, a[1] * inv);
+                            lo4.y = pack_bf16x2(a[2] * inv, a[3] * inv);
+                            lo4.z = pack_bf16x2(a[4] * inv, a[5] * inv);
+                            lo4.w = pack_bf16x2(a[6] * inv, a[7] * inv);
+                            hi4.x = pack_bf16x2(a[8] * inv, a[9] * inv);
+                            hi4.y = pack_bf16x2(a[10] * inv, a[11] * inv);
+                            hi4.z = pack_bf16x2(a[12] * inv, a[13] * inv);
+                            hi4.w = pack_bf16x2(a[14] * inv, a[15] * inv);
+                            unsigned char *row = tileQ + j * kTileBytes + n * kRowBytes + (32 * g + 16 * rb) * 2;
+                            *reinterpret_cast<u32x4 *>(row) = lo4;
+                            *reinterpret_cast<u32x4 *>(row + 16) = hi4;
+                        }
                     }
-
-                // denominator: rows 0 (hi) and 1 (lo) of the z block sit in registers 0 and 1 of
-                // the lanes of the lower half; the upper half fetches them across the wave
-                float den = accz[1] + accz[0];
-                den = __shfl(den, n);
-                const float inv = 1.0f / (den + eps);
-
                 wave_lds_fence();
 #pragma unroll
-                for (int rb = 0; rb < 2; ++rb) {
-                    u32x4 lo4, hi4;
-                    lo4.x = pack_bf16x2(acc[rb][0] * inv, acc[rb][1] * inv);
-                    lo4.y = pack_bf16x2(acc[rb][2] * inv, acc[rb][3] * inv);
-                    lo4.z = pack_bf16x2(acc[rb][4] * inv, acc[rb][5] * inv);
-                    lo4.w = pack_bf16x2(acc[rb][6] * inv, acc[rb][7] * inv);
-                    hi4.x = pack_bf16x2(acc[rb][8] * inv, acc[rb][9] * inv);
-                    hi4.y = pack_bf16x2(acc[rb][10] * inv, acc[rb][11] * inv);
-                    hi4.z = pack_bf16x2(acc[rb][12] * inv, acc[rb][13] * inv);
-                    hi4.w = pack_bf16x2(acc[rb][14] * inv, acc[rb][15] * inv);
-                    unsigned char *row = tileQ + n * kRowBytes + (32 * g + 16 * rb) * 2;
-                    *reinterpret_cast<u32x4 *>(row) = lo4;
-                    *reinterpret_cast<u32x4 *>(row + 16) = hi4;
-                }
-                wave_lds_fence();
+                for (int j = 0; j < NB; ++j)
+                    if (valid[j]) {
+                        const int tok0 = t0 + (tile + j * tile_step) * kApplyTile;
 #pragma unroll
-                for (int i = 0; i < kApplyTile / 8; ++i) {
-                    const int tok = tok0 + (lane >> 3) + 8 * i;
-                    const u32x4 o = *reinterpret_cast<const u32x4 *>(tileQ + wr_off + 8 * i * kRowBytes);
-                    if (tok < t1) store_stream16(Oh + (int64_t)tok * stride_n + (lane & 7) * 8, o);
-                }
+                        for (int i = 0; i < kApplyTile / 8; ++i) {
+                            const int tok = tok0 + (lane >> 3) + 8 * i;
+                            const u32x4 o = *reinterpret_cast<const u32x4 *>(tileQ + j * kTileBytes + wr_off +
+                                                                             8 * i * kRowBytes);
+                            if (tok < t1) store_stream16(Oh + (int64_t)tok * stride_n + (lane & 7) * 8, o);
+                        }
+                    }
             }
-            tile += tile_step;
+            tile += NB * tile_step;
         }
     }
 }
 
-template <int WAVES>
-__host__ __device__ constexpr int apply_lds_bytes() { return WAVES * kApplyTile * kRowBytes; }
+template <int WAVES, int NB>
+__host__ __device__ constexpr int apply_lds_bytes() { return WAVES * NB * kApplyTile * kRowBytes; }
 
 // grid = (C, B*H), block = 64*WAVES.  Wave w of workgroup c owns tiles
 // WAVES*c + w + WAVES*C*i (i = 0, 1, ...) of the T = ceil((t1-t0)/32) tiles,
 // the same round-robin deal as the state kernel.
 // HILO = false drops the low half of S (one MFMA pass instead of two).
-template <bool HILO, int WAVES, int DEPTH>
+// NB tiles of a wave are in the arithmetic phase together.
+template <bool HILO, int WAVES, int DEPTH, int NB>
 __global__ __launch_bounds__(64 * WAVES, 1) void apply_mfma_d64(
     const uint16_t *__restrict__ Q, uint16_t *__restrict__ O, TokStrides st, int H, int t0, int t1, int C,
     const float *__restrict__ S, const float *__restrict__ z, float eps)
@@ -232,8 +271,8 @@ __global__ __launch_bounds__(64 * WAVES, 1) void apply_mfma_d64(
     apply_prefetch<DEPTH>(Qh, st.n, t0, t1, first, step, n_tiles, lane, qreg);   // in flight while S is fetched
     ApplyOperands<HILO> A;
     A.template load<false>(S + (size_t)bh * 64 * 64, z + (size_t)bh * 64, lane);
-    apply_tiles<HILO, DEPTH>(Qh, Oh, st.n, t0, t1, first, step, n_tiles, lds + wave * kApplyTile * kRowBytes, lane,
-                             A, eps, qreg);
+    apply_tiles<HILO, DEPTH, NB>(Qh, Oh, st.n, t0, t1, first, step, n_tiles,
+                                 lds + wave * NB * kApplyTile * kRowBytes, lane, A, eps, qreg);
 }
 
 }  // namespace sv

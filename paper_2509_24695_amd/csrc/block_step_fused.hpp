@@ -21,14 +21,14 @@
 
 namespace sv {
 
-template <int TILE, int WAVES>
+template <int TILE, int WAVES, int NB>
 __host__ __device__ constexpr int block_step_lds_bytes() {
-    return state_lds_bytes<TILE, WAVES>() > apply_lds_bytes<WAVES>() ? state_lds_bytes<TILE, WAVES>()
-                                                                     : apply_lds_bytes<WAVES>();
+    return state_lds_bytes<TILE, WAVES>() > apply_lds_bytes<WAVES, NB>() ? state_lds_bytes<TILE, WAVES>()
+                                                                         : apply_lds_bytes<WAVES, NB>();
 }
 
 // grid = (C, B*H) with C*B*H <= resident workgroup capacity, block = 64*WAVES.
-template <int TILE, int WAVES, int DEPTH_S, bool HILO, int DEPTH_A>
+template <int TILE, int WAVES, int DEPTH_S, bool HILO, int DEPTH_A, int NB>
 __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma_d64(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
     uint16_t *__restrict__ O, TokStrides st, int H, int N, int C, float *__restrict__ S, float *__restrict__ z,
@@ -58,9 +58,12 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma_d64(
         const int n_tiles = (N + TILE - 1) / TILE;
         StateAcc acc;
         acc.clear();
+        StateStages<TILE, DEPTH_S> stg;
         unsigned char *tileK = lds + wave * 2 * kTileBytes;
+        state_prefetch<TILE, DEPTH_S>(K + head_off, V + head_off, st.n, 0, N, WAVES * c + wave, WAVES * C, n_tiles,
+                                      lane, stg);
         state_accumulate<TILE, DEPTH_S>(K + head_off, V + head_off, st.n, 0, N, WAVES * c + wave, WAVES * C, n_tiles,
-                                        tileK, tileK + kTileBytes, lane, acc);
+                                        tileK, tileK + kTileBytes, lane, stg, acc);
         // the rest of this wave's Q prefetch streams in while the head's state is being agreed on
         apply_prefetch<DEPTH_A, kEarly, DEPTH_A>(Q + head_off, st.n, 0, N, first, step, n_tiles_q, lane, qreg);
         float *partials = static_cast<float *>(ws) + (size_t)bh * kMaxChunks * kStateElems;
@@ -80,8 +83,8 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma_d64(
     // ---- apply the updated state to this workgroup's share of Q_b ----------------------------------
     ApplyOperands<HILO> A;
     A.template load<true>(Sh, zh, lane);
-    apply_tiles<HILO, DEPTH_A>(Q + head_off, O + head_off, st.n, 0, N, first, step, n_tiles_q,
-                               lds + wave * kApplyTile * kRowBytes, lane, A, eps, qreg);
+    apply_tiles<HILO, DEPTH_A, NB>(Q + head_off, O + head_off, st.n, 0, N, first, step, n_tiles_q,
+                                   lds + wave * NB * kApplyTile * kRowBytes, lane, A, eps, qreg);
 }
 
 }  // namespace sv

@@ -107,25 +107,39 @@ __device__ __forceinline__ void lds_gather_pairs(const unsigned char *tile, int 
     odd = __builtin_bit_cast(bf16x8, hi);
 }
 
+// Register staging of one wave: the K and V rows of DEPTH tiles in flight.
+template <int TILE, int DEPTH>
+struct StateStages {
+    u32x4 k[DEPTH][TILE / 8], v[DEPTH][TILE / 8];
+};
+
+// Requests the first DEPTH tiles of a wave's share (tiles first_tile,
+// first_tile + tile_step, ... below n_tiles).
+template <int TILE, int DEPTH>
+__device__ __forceinline__ void state_prefetch(const uint16_t *Kh, const uint16_t *Vh, int64_t stride_n, int t0,
+                                               int t1, int first_tile, int tile_step, int n_tiles, int lane,
+                                               StateStages<TILE, DEPTH> &st)
+{
+#pragma unroll
+    for (int s = 0; s < DEPTH; ++s) {
+        const int t = first_tile + s * tile_step;
+        if (t < n_tiles) state_tile_load<TILE>(Kh, Vh, stride_n, t0 + t * TILE, t1, lane, st.k[s], st.v[s]);
+    }
+}
+
 // One wave's share of the token range [t0, t1): tiles first_tile, first_tile +
-// tile_step, ... below n_tiles.  Tokens past t1 are loaded as zeros, which add
+// tile_step, ... below n_tiles, the first DEPTH of which state_prefetch has
+// already requested into `st`.  Tokens past t1 are loaded as zeros, which add
 // nothing to either sum.  `tileK`/`tileV` are this wave's private LDS tiles.
 template <int TILE, int DEPTH>
 __device__ __forceinline__ void state_accumulate(const uint16_t *Kh, const uint16_t *Vh, int64_t stride_n, int t0,
                                                  int t1, int first_tile, int tile_step, int n_tiles,
                                                  unsigned char *tileK, unsigned char *tileV, int lane,
-                                                 StateAcc &acc)
+                                                 StateStages<TILE, DEPTH> &st, StateAcc &acc)
 {
     static_assert(TILE == 16 || TILE == 32, "tile is one or two MFMA k-steps");
     const int r = lane & 31, g = lane >> 5;
     const int wr_off = (lane >> 3) * kRowBytes + (lane & 7) * 16;
-
-    u32x4 kreg[DEPTH][TILE / 8], vreg[DEPTH][TILE / 8];
-#pragma unroll
-    for (int s = 0; s < DEPTH; ++s) {
-        const int t = first_tile + s * tile_step;
-        if (t < n_tiles) state_tile_load<TILE>(Kh, Vh, stride_n, t0 + t * TILE, t1, lane, kreg[s], vreg[s]);
-    }
 
     int tile = first_tile;
     while (tile < n_tiles) {
@@ -135,8 +149,8 @@ __device__ __forceinline__ void state_accumulate(const uint16_t *Kh, const uint1
                 // phi(K) on the packed pairs; key sum in fp32 from the same registers
 #pragma unroll
                 for (int i = 0; i < TILE / 8; ++i) {
-                    const u32x4 kk = relu_bf16x8(kreg[s][i]);
-                    kreg[s][i] = kk;
+                    const u32x4 kk = relu_bf16x8(st.k[s][i]);
+                    st.k[s][i] = kk;
                     acc.z[0] += bf16_lo(kk.x);  acc.z[1] += bf16_hi(kk.x);
                     acc.z[2] += bf16_lo(kk.y);  acc.z[3] += bf16_hi(kk.y);
                     acc.z[4] += bf16_lo(kk.z);  acc.z[5] += bf16_hi(kk.z);
@@ -145,13 +159,13 @@ __device__ __forceinline__ void state_accumulate(const uint16_t *Kh, const uint1
                 wave_lds_fence();   // earlier reads of the tile buffer are done before it is overwritten
 #pragma unroll
                 for (int i = 0; i < TILE / 8; ++i) {
-                    *reinterpret_cast<u32x4 *>(tileK + wr_off + 8 * i * kRowBytes) = kreg[s][i];
-                    *reinterpret_cast<u32x4 *>(tileV + wr_off + 8 * i * kRowBytes) = vreg[s][i];
+                    *reinterpret_cast<u32x4 *>(tileK + wr_off + 8 * i * kRowBytes) = st.k[s][i];
+                    *reinterpret_cast<u32x4 *>(tileV + wr_off + 8 * i * kRowBytes) = st.v[s][i];
                 }
                 // refill this stage: DEPTH tiles ahead
                 const int nxt = tile + DEPTH * tile_step;
                 if (nxt < n_tiles)
-                    state_tile_load<TILE>(Kh, Vh, stride_n, t0 + nxt * TILE, t1, lane, kreg[s], vreg[s]);
+                    state_tile_load<TILE>(Kh, Vh, stride_n, t0 + nxt * TILE, t1, lane, st.k[s], st.v[s]);
                 wave_lds_fence();
 #pragma unroll
                 for (int ks = 0; ks < TILE / 16; ++ks) {
@@ -282,19 +296,31 @@ __device__ __forceinline__ void state_finalize_slice(const float *__restrict__ p
     }
 }
 
-// The calling workgroup has just issued the stores of partial `c` of head `bh`:
-// publish it, then wait until all C partials of the head are published.
-// Returns false if the bounded wait ran out.  All threads must call.
+// The calling workgroup has just issued coherent stores that belong to phase
+// `phase` (0: partial c, 1: slice c of the new state) of head `bh`: publish them.
+// All threads must call.
+__device__ __forceinline__ void state_publish(void *ws, int BH, int bh, int c, int phase, unsigned long long epoch)
+{
+    coherent_stores_done();                             // this wave's stores are performed
+    __syncthreads();
+    if (threadIdx.x == 0) flag_publish(ws_flags(ws, BH, kStateElems, bh, phase) + c, epoch);
+}
+
+// Waits until all C workgroups of head `bh` have published `phase`.  Returns
+// false (and records it in the workspace) if the bounded wait ran out.
+__device__ __forceinline__ bool state_wait(void *ws, int BH, int bh, int C, int phase, unsigned long long epoch,
+                                           uint32_t spin_limit, int lane)
+{
+    const bool ok = flags_wait_all(ws_flags(ws, BH, kStateElems, bh, phase), C, epoch, spin_limit, lane);
+    if (!ok && threadIdx.x == 0) *ws_error(ws, BH, kStateElems) = epoch;
+    return ok;
+}
+
 __device__ __forceinline__ bool state_publish_and_wait(void *ws, int BH, int bh, int c, int C, int phase,
                                                        unsigned long long epoch, uint32_t spin_limit, int lane)
 {
-    unsigned long long *flags = ws_flags(ws, BH, kStateElems, bh, phase);
-    coherent_stores_done();                             // this wave's stores are performed
-    __syncthreads();
-    if (threadIdx.x == 0) flag_publish(flags + c, epoch);
-    const bool ok = flags_wait_all(flags, C, epoch, spin_limit, lane);
-    if (!ok && threadIdx.x == 0) *ws_error(ws, BH, kStateElems) = epoch;
-    return ok;
+    state_publish(ws, BH, bh, c, phase, epoch);
+    return state_wait(ws, BH, bh, C, phase, epoch, spin_limit, lane);
 }
 
 // Dynamic LDS of state_mfma_d64: staging tiles or reduction slots.
@@ -329,9 +355,11 @@ __global__ __launch_bounds__(64 * WAVES, 1) void state_mfma_d64(
 
     StateAcc acc;
     acc.clear();
+    StateStages<TILE, DEPTH> stg;
     unsigned char *tileK = lds + wave * 2 * kTileBytes;
+    state_prefetch<TILE, DEPTH>(Kh, Vh, st.n, t0, t1, WAVES * c + wave, WAVES * C, n_tiles, lane, stg);
     state_accumulate<TILE, DEPTH>(Kh, Vh, st.n, t0, t1, WAVES * c + wave, WAVES * C, n_tiles, tileK,
-                                  tileK + kTileBytes, lane, acc);
+                                  tileK + kTileBytes, lane, stg, acc);
 
     float *partials = static_cast<float *>(ws) + (size_t)bh * kMaxChunks * kStateElems;
     state_wg_reduce_store<WAVES>(acc, reinterpret_cast<float *>(lds), wave, lane,

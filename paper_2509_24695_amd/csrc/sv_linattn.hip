@@ -25,6 +25,7 @@ constexpr int kVersion = 200;   // 0.2.0
 constexpr int kStateTile = 32, kStateWaves = 4, kStateDepth = 2;
 constexpr int kApplyWaves = 4, kApplyDepth = 2;
 constexpr int kFusedApplyDepth = 6;   // Q tiles per wave held in registers across the in-kernel waits
+constexpr int kApplyBatch = 1;        // tiles of a wave that share the arithmetic phase
 constexpr bool kApplyHiLo = true;
 constexpr uint32_t kSpinLimit = 1u << 24;      // polls of ~100 ns: far beyond any real wait
 
@@ -44,11 +45,11 @@ struct Device {
 
 auto *const kStateKernel = state_mfma_d64<kStateTile, kStateWaves, kStateDepth, true>;
 auto *const kStatePartialKernel = state_mfma_d64<kStateTile, kStateWaves, kStateDepth, false>;
-auto *const kApplyKernel = apply_mfma_d64<kApplyHiLo, kApplyWaves, kApplyDepth>;
-auto *const kFusedKernel = block_step_mfma_d64<kStateTile, kStateWaves, kStateDepth, kApplyHiLo, kFusedApplyDepth>;
+auto *const kApplyKernel = apply_mfma_d64<kApplyHiLo, kApplyWaves, kApplyDepth, kApplyBatch>;
+auto *const kFusedKernel = block_step_mfma_d64<kStateTile, kStateWaves, kStateDepth, kApplyHiLo, kFusedApplyDepth, kApplyBatch>;
 constexpr int kStateLds = state_lds_bytes<kStateTile, kStateWaves>();
-constexpr int kApplyLds = apply_lds_bytes<kApplyWaves>();
-constexpr int kFusedLds = block_step_lds_bytes<kStateTile, kStateWaves>();
+constexpr int kApplyLds = apply_lds_bytes<kApplyWaves, kApplyBatch>();
+constexpr int kFusedLds = block_step_lds_bytes<kStateTile, kStateWaves, kApplyBatch>();
 
 // Per-device facts, queried once (no device memory is touched).
 const Device &device_info()
