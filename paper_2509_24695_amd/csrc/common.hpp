@@ -62,8 +62,11 @@ __device__ __forceinline__ u32x4 load_stream16(const void *p) {
     return *reinterpret_cast<const u32x4 *>(p);
 #endif
 }
+#ifndef SV_STORE_NT
+#define SV_STORE_NT SV_STREAM_NT
+#endif
 __device__ __forceinline__ void store_stream16(void *p, u32x4 v) {
-#if SV_STREAM_NT
+#if SV_STORE_NT
     __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(p));
 #else
     *reinterpret_cast<u32x4 *>(p) = v;

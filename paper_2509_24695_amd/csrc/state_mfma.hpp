@@ -31,7 +31,6 @@ namespace sv {
 
 constexpr int kRowBytes = 144;   // 128-byte token row + 16 bytes of padding (bank spread, keeps 16-byte alignment)
 constexpr int kStateElems = 64 * 64 + 64;            // S then z of one head, d = 64
-constexpr int kSlotFloats = 72 * kWave;              // one wave's accumulators laid out register-major
 
 // Workspace layout (B*H = BH heads, `elems` = d*d + d):
 //   float  partial[BH][kMaxChunks][elems]
@@ -185,50 +184,20 @@ __device__ __forceinline__ void state_accumulate(const uint16_t *Kh, const uint1
 
 // Adds the WAVES waves' accumulators in a fixed tree order and stores the
 // workgroup's partial state, S in [k][v] order followed by z, to `out`
-// (kStateElems floats) with coherent stores spread over all threads.  The tree
-// runs register-major through two LDS slots until two waves are left; those two
-// write their sums in [k][v] order and every thread adds and stores its share.
-// Must be called by all threads; the staging tiles are dead afterwards.
+// (kStateElems floats) with coherent stores spread over all threads.  Every
+// wave lays its accumulators out in [k][v] order in its own LDS slot (the key
+// sum after a wavefront-level reduction); after one barrier each thread adds the
+// slots for its share of the elements, wave w absorbing wave w + h for
+// h = WAVES/2, ..., 1.  Must be called by all threads; the staging tiles are
+// dead afterwards.  LDS: WAVES * kStateElems floats.
 template <int WAVES>
-__device__ __forceinline__ void state_wg_reduce_store(StateAcc &acc, float *slot, int wave, int lane,
+__device__ __forceinline__ void state_wg_reduce_store(StateAcc &acc, float *slots, int wave, int lane,
                                                       float *__restrict__ out)
 {
-    static_assert(WAVES == 4 || WAVES == 8, "tree below assumes 4 or 8 waves");
     constexpr int THREADS = 64 * WAVES;
-    auto put = [&](float *dst) {
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-            for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) dst[((rb * 2 + cb) * 16 + i) * kWave + lane] = acc.s[rb][cb][i];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) dst[(64 + e) * kWave + lane] = acc.z[e];
-    };
-    auto add = [&](const float *src) {
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-            for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) acc.s[rb][cb][i] += src[((rb * 2 + cb) * 16 + i) * kWave + lane];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc.z[e] += src[(64 + e) * kWave + lane];
-    };
     __syncthreads();                                   // all waves are done with their staging tiles
-#pragma unroll
-    for (int h = WAVES / 2; h >= 2; h /= 2) {          // wave w absorbs wave w + h
-#pragma unroll
-        for (int base = 0; base < h; base += 2) {      // two waves at a time (two slots)
-            if (wave >= h + base && wave < h + base + 2 && wave < 2 * h) put(slot + (wave - h - base) * kSlotFloats);
-            __syncthreads();
-            if (wave >= base && wave < base + 2 && wave < h) add(slot + (wave - base) * kSlotFloats);
-            __syncthreads();
-        }
-    }
-    // waves 0 and 1 lay their sums out as [k][v] then z (kStateElems floats each)
-    if (wave < 2) {
-        float *dst = slot + wave * kSlotFloats;
+    {
+        float *dst = slots + wave * kStateElems;
         // 32x32 accumulator layout: register i of lane l is row 8*(i/4) + 4*(l/32) + i%4, column l%32.
         const int r = lane & 31, g = lane >> 5;
 #pragma unroll
@@ -256,9 +225,14 @@ __device__ __forceinline__ void state_wg_reduce_store(StateAcc &acc, float *slot
     }
     __syncthreads();
     for (int v = threadIdx.x; v < kStateElems / 2; v += THREADS) {
-        const f32x2 a = *reinterpret_cast<const f32x2 *>(slot + 2 * v);
-        const f32x2 b = *reinterpret_cast<const f32x2 *>(slot + kSlotFloats + 2 * v);
-        store_coherent(out + 2 * v, a + b);
+        f32x2 x[WAVES];
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) x[w] = *reinterpret_cast<const f32x2 *>(slots + w * kStateElems + 2 * v);
+#pragma unroll
+        for (int h = WAVES / 2; h >= 1; h /= 2)
+#pragma unroll
+            for (int w = 0; w < h; ++w) x[w] += x[w + h];
+        store_coherent(out + 2 * v, x[0]);
     }
 }
 
@@ -326,7 +300,7 @@ __device__ __forceinline__ bool state_publish_and_wait(void *ws, int BH, int bh,
 // Dynamic LDS of state_mfma_d64: staging tiles or reduction slots.
 template <int TILE, int WAVES>
 __host__ __device__ constexpr int state_lds_bytes() {
-    constexpr int stage = WAVES * 2 * TILE * kRowBytes, red = 2 * kSlotFloats * 4;
+    constexpr int stage = WAVES * 2 * TILE * kRowBytes, red = WAVES * kStateElems * 4;
     return stage > red ? stage : red;
 }
 

@@ -245,3 +245,51 @@ def test_errors_leave_outputs_untouched():
     assert e.value.status == 6
     torch.cuda.synchronize()
     assert (S == 3.0).all()
+
+
+# ---- launch shapes beyond the resident grid, and the timeout word ---------------------------------
+
+@pytest.mark.parametrize("BH", [130, 300])
+def test_many_heads_bidirectional_and_block(BH):
+    """More heads than compute units: one chunk per head; at 300 heads the grid is not resident, so
+    the state call takes the two-launch route and the block step the state + apply route."""
+    import torch
+    B, H, N, d = 1, BH, 150, 64
+    say(f"many_heads BH={BH} N={N}")
+    Q, K, V = _draw(7900 + BH, B, H, N, d, "bf16")
+    O_ref, S_ref, z_ref = orc.bidirectional(Q, K, V, 1e-6)
+    Qd, Kd, Vd = to_dev(Q), to_dev(K), to_dev(V)
+    O, S, z = gpu_bidirectional(Qd, Kd, Vd, 1e-6)
+    _check_state(S, z, S_ref, z_ref, "state")
+    metrics.check(to_host(O), O_ref, "bf16", "O")
+    # the same tokens as two blocks through the block step
+    S2, z2 = new_state(B, H, d)
+    ws = new_workspace(B, H, N, d)
+    O2 = torch.empty_like(Qd)
+    for a, b in ((0, 70), (70, 150)):
+        q, k, v, o = (t[:, :, a:b] for t in (Qd, Kd, Vd, O2))
+        sv.sv_block_linattn_step(q, k, v, sv.desc_of(q), S2, z2, 1e-6, o, ws)
+    torch.cuda.synchronize()
+    blocks = [tuple(np.ascontiguousarray(t[:, :, a:b]) for t in (Q, K, V)) for a, b in ((0, 70), (70, 150))]
+    outs = list(orc.block_stream(blocks, 1e-6))
+    metrics.check(to_host(O2)[:, :, :70], outs[0][0], "bf16", "block 0")
+    metrics.check(to_host(O2)[:, :, 70:], outs[1][0], "bf16", "block 1")
+    _check_state(S2, z2, outs[1][1], outs[1][2], "carried state")
+
+
+def test_bounded_waits_never_time_out():
+    """The workspace's last-but-one 8-byte word records a timed-out wait; it must stay clear."""
+    import torch
+    B, H, N, d = 1, 32, 4680, 64
+    say("bounded_waits_never_time_out")
+    Q, K, V = (to_dev(t) for t in _draw(7950, B, H, N, d, "bf16"))
+    ws = new_workspace(B, H, N, d)
+    ws.zero_()
+    S, z = new_state(B, H, d)
+    O = torch.empty_like(Q)
+    dsc = sv.desc_of(Q)
+    for _ in range(20):
+        sv.sv_linattn_state(K, V, dsc, 0, N, 0, S, z, ws)
+        sv.sv_block_linattn_step(Q, K, V, dsc, S, z, 1e-6, O, ws)
+    torch.cuda.synchronize()
+    assert int(ws[-16:-8].view(torch.int64)[0]) == 0
