@@ -108,6 +108,17 @@ sv_status sv_block_linattn_step(const void *Qb, const void *Kb, const void *Vb,
                                 float *S, float *z, float eps, void *Ob,
                                 void *workspace, size_t workspace_bytes, void *stream);
 
+/* The same block WITHOUT committing it (the noisy denoising passes of Alg. 1:
+ * G(x; t_j, KV) attends to the cache plus the block itself, and only the final
+ * pass at t = 0 updates the cache):
+ *     O_b = phi(Q_b) (S + phi(K_b)^T V_b) / (phi(Q_b) (z + sum phi(K_b)) + eps)
+ * S and z are read only; the updated state exists only inside `workspace`
+ * during the call.  Same arguments, checks and errors as sv_block_linattn_step. */
+sv_status sv_block_linattn_lookahead(const void *Qb, const void *Kb, const void *Vb,
+                                     const sv_tensor_desc *blk,
+                                     const float *S, const float *z, float eps, void *Ob,
+                                     void *workspace, size_t workspace_bytes, void *stream);
+
 /* Human-readable name of a status code (static storage). */
 const char *sv_status_string(int status);
 

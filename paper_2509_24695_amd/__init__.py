@@ -6,6 +6,6 @@ memory and streams only; every step of the computation runs in the library.
 """
 from .binding import (  # noqa: F401
     SV_BF16, SV_F32, SvError, TensorDesc, desc_of, library_path, load_library,
-    sv_block_linattn_step, sv_linattn_apply, sv_linattn_state,
+    sv_block_linattn_lookahead, sv_block_linattn_step, sv_linattn_apply, sv_linattn_state,
     sv_linattn_workspace_bytes, sv_status_string, sv_version, EXPORTS,
 )

@@ -15,7 +15,7 @@ SV_BF16, SV_F32 = 0, 1
 
 EXPORTS = (
     "sv_linattn_workspace_bytes", "sv_linattn_state", "sv_linattn_apply",
-    "sv_block_linattn_step", "sv_status_string", "sv_version",
+    "sv_block_linattn_step", "sv_block_linattn_lookahead", "sv_status_string", "sv_version",
 )
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
@@ -75,6 +75,8 @@ def load_library():
     lib.sv_linattn_apply.restype = ctypes.c_int
     lib.sv_block_linattn_step.argtypes = [vp, vp, vp, dp, vp, vp, ctypes.c_float, vp, vp, sz, vp]
     lib.sv_block_linattn_step.restype = ctypes.c_int
+    lib.sv_block_linattn_lookahead.argtypes = [vp, vp, vp, dp, vp, vp, ctypes.c_float, vp, vp, sz, vp]
+    lib.sv_block_linattn_lookahead.restype = ctypes.c_int
     lib.sv_status_string.argtypes = [ctypes.c_int]
     lib.sv_status_string.restype = ctypes.c_char_p
     lib.sv_version.argtypes = []
@@ -158,3 +160,12 @@ def sv_block_linattn_step(Qb, Kb, Vb, blk: TensorDesc, S, z, eps: float, Ob, wor
     _check(load_library().sv_block_linattn_step(_ptr(Qb), _ptr(Kb), _ptr(Vb), ctypes.byref(d) if d else None,
                                                 _ptr(S), _ptr(z), float(eps), _ptr(Ob), _ptr(workspace), wb,
                                                 _stream(stream)), "sv_block_linattn_step")
+
+
+def sv_block_linattn_lookahead(Qb, Kb, Vb, blk: TensorDesc, S, z, eps: float, Ob, workspace,
+                               workspace_bytes: int | None = None, stream=None) -> None:
+    d = blk._c() if blk is not None else None
+    wb = _nbytes(workspace) if workspace_bytes is None else int(workspace_bytes)
+    _check(load_library().sv_block_linattn_lookahead(_ptr(Qb), _ptr(Kb), _ptr(Vb), ctypes.byref(d) if d else None,
+                                                     _ptr(S), _ptr(z), float(eps), _ptr(Ob), _ptr(workspace), wb,
+                                                     _stream(stream)), "sv_block_linattn_lookahead")

@@ -31,8 +31,8 @@ __host__ __device__ constexpr int block_step_lds_bytes() {
 template <int TILE, int WAVES, int DEPTH_S, bool HILO, int DEPTH_A, int NB>
 __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma_d64(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
-    uint16_t *__restrict__ O, TokStrides st, int H, int N, int C, float *__restrict__ S, float *__restrict__ z,
-    float eps, void *__restrict__ ws, unsigned long long epoch, uint32_t spin_limit)
+    uint16_t *__restrict__ O, TokStrides st, int H, int N, int C, const float *S_in, const float *z_in,
+    float *S_out, float *z_out, float eps, void *__restrict__ ws, unsigned long long epoch, uint32_t spin_limit)
 {
     constexpr int THREADS = 64 * WAVES;
     constexpr int kTileBytes = TILE * kRowBytes;
@@ -43,7 +43,10 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma_d64(
     const int c = blockIdx.x, bh = blockIdx.y, BH = gridDim.y;
     const int b = bh / H, h = bh % H;
     const int64_t head_off = b * st.b + h * st.h;
-    float *Sh = S + (size_t)bh * 64 * 64, *zh = z + (size_t)bh * 64;
+    // the carried state is read from S_in, z_in and the updated one written to S_out, z_out: the same
+    // arrays when the step commits, a scratch copy when it only looks ahead
+    const float *Sc = S_in + (size_t)bh * 64 * 64, *zc = z_in + (size_t)bh * 64;
+    float *Sh = S_out + (size_t)bh * 64 * 64, *zh = z_out + (size_t)bh * 64;
 
     // ---- this wave's first two tiles of Q_b are requested right away: they arrive during the state
     //      phase and make no later load wait behind them ---------------------------------------------
@@ -76,7 +79,7 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma_d64(
     {
         const float *partials = static_cast<const float *>(ws) + (size_t)bh * kMaxChunks * kStateElems;
         state_publish_and_wait(ws, BH, bh, c, C, 0, epoch, spin_limit, lane);
-        state_finalize_slice<THREADS, true>(partials, c, C, 1, Sh, zh);
+        state_finalize_slice<THREADS, true>(partials, c, C, Sc, zc, Sh, zh);
         state_publish_and_wait(ws, BH, bh, c, C, 1, epoch, spin_limit, lane);
     }
 

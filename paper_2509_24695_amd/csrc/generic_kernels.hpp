@@ -72,22 +72,24 @@ __global__ __launch_bounds__(kThreads) void state_partial_generic(
     if (tid % TPR == 0) out[D * D + k] = zacc;
 }
 
-// S, z (+)= sum over chunks of the partial states, in chunk order:
-//   x = accumulate ? old : 0;  for c = 0..C-1: x += ws[bh][c][e]
+// S_out, z_out = (S_in, z_in or 0) + sum over chunks of the partial states, in chunk order:
+//   x = S_in ? S_in[e] : 0;  for c = 0..C-1: x += ws[bh][c][e]
+// S_in may be null or equal to S_out (in place).
 // The fixed order makes the result bit-reproducible (no float atomics).
 // grid = (ceil((D*D+D)/256), B*H).  C == 0 zero-fills or leaves the state as is.
 // Partial c of head bh starts at ws + (bh*chunk_stride + c) * (D*D+D).
 template <int D>
 __global__ __launch_bounds__(kThreads) void state_reduce(
-    const float *__restrict__ ws, int C, int chunk_stride, int accumulate, float *__restrict__ S,
-    float *__restrict__ z)
+    const float *__restrict__ ws, int C, int chunk_stride, const float *S_in, const float *z_in, float *S_out,
+    float *z_out)
 {
     constexpr int E = D * D + D;
     const int e = blockIdx.x * kThreads + threadIdx.x;
     const int bh = blockIdx.y;
     if (e >= E) return;
-    float *dst = e < D * D ? S + (int64_t)bh * D * D + e : z + (int64_t)bh * D + (e - D * D);
-    float x = accumulate ? *dst : 0.f;
+    const int64_t off = e < D * D ? (int64_t)bh * D * D + e : (int64_t)bh * D + (e - D * D);
+    float *dst = (e < D * D ? S_out : z_out) + off;
+    float x = S_in ? (e < D * D ? S_in : z_in)[off] : 0.f;
     const float *p = ws + (int64_t)bh * chunk_stride * E + e;
     for (int c = 0; c < C; ++c) x += p[(int64_t)c * E];
     *dst = x;

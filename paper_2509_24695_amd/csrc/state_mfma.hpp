@@ -34,21 +34,32 @@ constexpr int kStateElems = 64 * 64 + 64;            // S then z of one head, d 
 
 // Workspace layout (B*H = BH heads, `elems` = d*d + d):
 //   float  partial[BH][kMaxChunks][elems]
+//   float  lookahead[BH][elems]       S then z per head: the updated state of a step that does not commit
 //   u64    flags[BH][2][kMaxChunks]   epoch-tagged: [0] partial c stored, [1] slice c of the new state stored
 //   u64    error, pad                 non-zero if a bounded wait ever timed out
 __host__ __device__ constexpr size_t ws_partial_bytes(int BH, int elems) {
     return (size_t)BH * kMaxChunks * elems * sizeof(float);
 }
+__host__ __device__ constexpr size_t ws_lookahead_bytes(int BH, int elems) {
+    return (size_t)BH * elems * sizeof(float);
+}
+// S part of the look-ahead state ([BH][d*d]); the z part ([BH][d]) follows it.
+__host__ __device__ __forceinline__ float *ws_lookahead(void *ws, int BH, int elems) {
+    return reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + ws_partial_bytes(BH, elems));
+}
+__host__ __device__ __forceinline__ unsigned long long *ws_flag_base(void *ws, int BH, int elems) {
+    return reinterpret_cast<unsigned long long *>(static_cast<unsigned char *>(ws) + ws_partial_bytes(BH, elems) +
+                                                  ws_lookahead_bytes(BH, elems));
+}
 __host__ __device__ __forceinline__ unsigned long long *ws_flags(void *ws, int BH, int elems, int bh, int phase) {
-    return reinterpret_cast<unsigned long long *>(static_cast<unsigned char *>(ws) + ws_partial_bytes(BH, elems)) +
-           ((size_t)bh * 2 + phase) * kMaxChunks;
+    return ws_flag_base(ws, BH, elems) + ((size_t)bh * 2 + phase) * kMaxChunks;
 }
 __host__ __device__ __forceinline__ unsigned long long *ws_error(void *ws, int BH, int elems) {
-    return reinterpret_cast<unsigned long long *>(static_cast<unsigned char *>(ws) + ws_partial_bytes(BH, elems)) +
-           (size_t)BH * 2 * kMaxChunks;
+    return ws_flag_base(ws, BH, elems) + (size_t)BH * 2 * kMaxChunks;
 }
 __host__ __device__ constexpr size_t ws_total_bytes(int BH, int elems) {
-    return ws_partial_bytes(BH, elems) + ((size_t)BH * 2 * kMaxChunks + 2) * sizeof(unsigned long long);
+    return ws_partial_bytes(BH, elems) + ws_lookahead_bytes(BH, elems) +
+           ((size_t)BH * 2 * kMaxChunks + 2) * sizeof(unsigned long long);
 }
 
 // Registers of one lane: the 64x64 fp32 partial state as four 32x32 MFMA
@@ -238,22 +249,24 @@ __device__ __forceinline__ void state_wg_reduce_store(StateAcc &acc, float *slot
 
 // Slice c of the head's state (8-byte units [c*per, (c+1)*per) of the
 // kStateElems values, per = ceil(2080 / C)):
-//   S, z (+)= partial[0] + partial[1] + ... + partial[C-1], in that order.
+//   S_out, z_out = (S_in, z_in or 0) + partial[0] + partial[1] + ... + partial[C-1], in that order.
+// S_in may be null (no carried state) or equal to S_out (update in place).
 // Partials come in through coherent loads, up to eight chunks in flight.
 // COHERENT_OUT: also store the result coherently (other workgroups of this
 // kernel are going to read it).
 template <int THREADS, bool COHERENT_OUT>
-__device__ __forceinline__ void state_finalize_slice(const float *__restrict__ partials, int c, int C, int accumulate,
-                                                     float *__restrict__ S, float *__restrict__ z)
+__device__ __forceinline__ void state_finalize_slice(const float *__restrict__ partials, int c, int C,
+                                                     const float *S_in, const float *z_in, float *S_out,
+                                                     float *z_out)
 {
     constexpr int kVecs = kStateElems / 2;                       // 2080 float2
     constexpr int GROUP = 8;                                     // chunks in flight
     const int per = (kVecs + C - 1) / C;
     const int lo = c * per, hi = lo + per < kVecs ? lo + per : kVecs;
     for (int v = lo + (int)threadIdx.x; v < hi; v += THREADS) {
-        float *dst = v < 2048 ? S + 2 * v : z + 2 * (v - 2048);
+        float *dst = v < 2048 ? S_out + 2 * v : z_out + 2 * (v - 2048);
         f32x2 x = {0.f, 0.f};
-        if (accumulate) x = *reinterpret_cast<const f32x2 *>(dst);
+        if (S_in) x = *reinterpret_cast<const f32x2 *>(v < 2048 ? S_in + 2 * v : z_in + 2 * (v - 2048));
         for (int c0 = 0; c0 < C; c0 += GROUP) {
             f32x2 p[GROUP];
 #pragma unroll
@@ -307,12 +320,13 @@ __host__ __device__ constexpr int state_lds_bytes() {
 // grid = (C, B*H), block = 64*WAVES.  Wave w of workgroup c owns tiles
 // WAVES*c + w + WAVES*C*i (i = 0, 1, ...) of the T = ceil((t1-t0)/TILE) tiles.
 // FINALIZE: the C workgroups of a head wait for each other's partials and each
-// folds one slice of them into S, z; this needs the whole grid to be resident.
+// folds one slice of them: S_out, z_out = (S_in, z_in, or 0 if S_in is null) +
+// partials; this needs the whole grid to be resident.
 // Otherwise only the partials are written and state_reduce finishes the job.
 template <int TILE, int WAVES, int DEPTH, bool FINALIZE>
 __global__ __launch_bounds__(64 * WAVES, 1) void state_mfma_d64(
     const uint16_t *__restrict__ K, const uint16_t *__restrict__ V, TokStrides st, int H, int t0, int t1,
-    int C, int accumulate, float *__restrict__ S, float *__restrict__ z, void *__restrict__ ws,
+    int C, const float *S_in, const float *z_in, float *S_out, float *z_out, void *__restrict__ ws,
     unsigned long long epoch, uint32_t spin_limit)
 {
     constexpr int THREADS = 64 * WAVES;
@@ -340,8 +354,9 @@ __global__ __launch_bounds__(64 * WAVES, 1) void state_mfma_d64(
                                  partials + (size_t)c * kStateElems);
     if (FINALIZE) {
         state_publish_and_wait(ws, BH, bh, c, C, 0, epoch, spin_limit, lane);
-        state_finalize_slice<THREADS, false>(partials, c, C, accumulate, S + (size_t)bh * 64 * 64,
-                                             z + (size_t)bh * 64);
+        state_finalize_slice<THREADS, false>(partials, c, C, S_in ? S_in + (size_t)bh * 64 * 64 : nullptr,
+                                             z_in + (size_t)bh * 64, S_out + (size_t)bh * 64 * 64,
+                                             z_out + (size_t)bh * 64);
     }
 }
 

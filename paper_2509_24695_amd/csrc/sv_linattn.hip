@@ -19,7 +19,7 @@ namespace {
 
 using namespace sv;
 
-constexpr int kVersion = 200;   // 0.2.0
+constexpr int kVersion = 300;   // 0.3.0
 
 // Tuned launch shapes of the bf16 d = 64 kernels (one workgroup per compute unit).
 constexpr int kStateTile = 32, kStateWaves = 4, kStateDepth = 2;
@@ -147,19 +147,21 @@ sv_status launch_status() { return hipGetLastError() == hipSuccess ? SV_OK : SV_
 
 bool eps_ok(float eps) { return isfinite(eps) && eps >= 0.f; }
 
-// S, z (+)= state of tokens [t0,t1).  All arguments are already validated.
-sv_status enqueue_state(const void *K, const void *V, const Shape &s, int t0, int t1, int accumulate, float *S,
-                        float *z, void *ws, hipStream_t stream)
+// S_out, z_out = (S_in, z_in, or 0 when S_in is null) + state of tokens [t0,t1).  S_in may equal S_out.
+// All arguments are already validated.
+sv_status enqueue_state(const void *K, const void *V, const Shape &s, int t0, int t1, const float *S_in,
+                        const float *z_in, float *S_out, float *z_out, void *ws, hipStream_t stream)
 {
     const int n = t1 - t0;
-    if (n == 0 && accumulate) return SV_OK;
+    if (n == 0 && S_in == S_out) return SV_OK;
     const Device &dev = device_info();
     if (!dev.ok) return SV_ERR_LAUNCH;
     const int E = s.d * s.d + s.d;
     const dim3 rgrid((E + kThreads - 1) / kThreads, s.BH);
-    if (n == 0) {                                   // overwrite with the empty sum
-        if (s.d == 64) state_reduce<64><<<rgrid, kThreads, 0, stream>>>(static_cast<float *>(ws), 0, 0, 0, S, z);
-        else state_reduce<32><<<rgrid, kThreads, 0, stream>>>(static_cast<float *>(ws), 0, 0, 0, S, z);
+    float *wsf = static_cast<float *>(ws);
+    if (n == 0) {                                   // the empty sum: zero fill, or a copy of the carried state
+        if (s.d == 64) state_reduce<64><<<rgrid, kThreads, 0, stream>>>(wsf, 0, 0, S_in, z_in, S_out, z_out);
+        else state_reduce<32><<<rgrid, kThreads, 0, stream>>>(wsf, 0, 0, S_in, z_in, S_out, z_out);
         return launch_status();
     }
     if (s.bf16 && s.d == 64) {
@@ -169,18 +171,17 @@ sv_status enqueue_state(const void *K, const void *V, const Shape &s, int t0, in
         if ((int64_t)C * s.BH <= dev.state_resident_wgs) {
             // the head's workgroups wait for each other inside the kernel: all must be resident
             kStateKernel<<<dim3(C, s.BH), 64 * kStateWaves, kStateLds, stream>>>(
-                k, v, s.st, s.H, t0, t1, C, accumulate, S, z, ws, next_epoch(), kSpinLimit);
+                k, v, s.st, s.H, t0, t1, C, S_in, z_in, S_out, z_out, ws, next_epoch(), kSpinLimit);
         } else {
             kStatePartialKernel<<<dim3(C, s.BH), 64 * kStateWaves, kStateLds, stream>>>(
-                k, v, s.st, s.H, t0, t1, C, accumulate, S, z, ws, 0ull, 0u);
-            state_reduce<64><<<rgrid, kThreads, 0, stream>>>(static_cast<float *>(ws), C, kMaxChunks, accumulate, S, z);
+                k, v, s.st, s.H, t0, t1, C, S_in, z_in, S_out, z_out, ws, 0ull, 0u);
+            state_reduce<64><<<rgrid, kThreads, 0, stream>>>(wsf, C, kMaxChunks, S_in, z_in, S_out, z_out);
         }
         return launch_status();
     }
     // fp32 validation mode and bf16 d = 32: plain-FMA partials, then the fixed-order reduction
     const int C = plan_chunks(s.BH, n, 32, 2 * dev.num_cu);
     const dim3 grid(C, s.BH);
-    float *wsf = static_cast<float *>(ws);
     if (s.bf16) {
         state_partial_generic<uint16_t, 32><<<grid, kThreads, 0, stream>>>(
             static_cast<const uint16_t *>(K), static_cast<const uint16_t *>(V), s.st, s.H, t0, t1, C, wsf);
@@ -191,8 +192,8 @@ sv_status enqueue_state(const void *K, const void *V, const Shape &s, int t0, in
         state_partial_generic<float, 32><<<grid, kThreads, 0, stream>>>(
             static_cast<const float *>(K), static_cast<const float *>(V), s.st, s.H, t0, t1, C, wsf);
     }
-    if (s.d == 64) state_reduce<64><<<rgrid, kThreads, 0, stream>>>(wsf, C, C, accumulate, S, z);
-    else state_reduce<32><<<rgrid, kThreads, 0, stream>>>(wsf, C, C, accumulate, S, z);
+    if (s.d == 64) state_reduce<64><<<rgrid, kThreads, 0, stream>>>(wsf, C, C, S_in, z_in, S_out, z_out);
+    else state_reduce<32><<<rgrid, kThreads, 0, stream>>>(wsf, C, C, S_in, z_in, S_out, z_out);
     return launch_status();
 }
 
@@ -254,7 +255,7 @@ sv_status sv_linattn_state(const void *K, const void *V, const sv_tensor_desc *k
     if (!aligned16(K) || !aligned16(V) || !aligned16(S) || !aligned16(z) || !aligned16(workspace))
         return SV_ERR_ALIGN;
     if (workspace_bytes_given < workspace_bytes(s.BH, s.d)) return SV_ERR_WORKSPACE;
-    return enqueue_state(K, V, s, tok_begin, tok_end, accumulate != 0, S, z, workspace,
+    return enqueue_state(K, V, s, tok_begin, tok_end, accumulate ? S : nullptr, z, S, z, workspace,
                          static_cast<hipStream_t>(stream));
 }
 
@@ -271,36 +272,56 @@ sv_status sv_linattn_apply(const void *Q, const sv_tensor_desc *q, int32_t tok_b
     return enqueue_apply(Q, s, tok_begin, tok_end, S, z, eps, O, static_cast<hipStream_t>(stream));
 }
 
-sv_status sv_block_linattn_step(const void *Qb, const void *Kb, const void *Vb, const sv_tensor_desc *blk, float *S,
-                                float *z, float eps, void *Ob, void *workspace, size_t workspace_bytes_given,
-                                void *stream)
+// Shared body of the committing and the look-ahead block step: the updated state goes to S_out, z_out.
+static sv_status block_step(const void *Qb, const void *Kb, const void *Vb, const sv_tensor_desc *blk, const float *S_in,
+                            const float *z_in, float *S_out, float *z_out, bool lookahead, float eps, void *Ob,
+                            void *workspace, size_t workspace_bytes_given, void *stream)
 {
-    if (!Qb || !Kb || !Vb || !S || !z || !Ob || !workspace) return SV_ERR_NULL;
+    if (!Qb || !Kb || !Vb || !S_in || !z_in || !Ob || !workspace) return SV_ERR_NULL;
     Shape s;
     sv_status rc = check_desc(blk, &s);
     if (rc != SV_OK) return rc;
     if (!eps_ok(eps)) return SV_ERR_RANGE;
-    if (!aligned16(Qb) || !aligned16(Kb) || !aligned16(Vb) || !aligned16(Ob) || !aligned16(S) || !aligned16(z) ||
-        !aligned16(workspace))
+    if (!aligned16(Qb) || !aligned16(Kb) || !aligned16(Vb) || !aligned16(Ob) || !aligned16(S_in) ||
+        !aligned16(z_in) || !aligned16(workspace))
         return SV_ERR_ALIGN;
     if (workspace_bytes_given < workspace_bytes(s.BH, s.d)) return SV_ERR_WORKSPACE;
+    if (lookahead) {                                 // the updated state lives in the workspace only
+        S_out = ws_lookahead(workspace, s.BH, s.d * s.d + s.d);
+        z_out = S_out + (size_t)s.BH * s.d * s.d;
+    }
     auto hs = static_cast<hipStream_t>(stream);
     if (s.bf16 && s.d == 64) {
         const Device &dev = device_info();
         if (!dev.ok) return SV_ERR_LAUNCH;
-        // One launch when the whole grid can be resident at once (needed by the in-kernel wait).
+        // One launch when the whole grid can be resident at once (needed by the in-kernel waits).
         const int C = plan_chunks(s.BH, s.N, kStateTile * kStateWaves, dev.num_cu);
         if ((int64_t)C * s.BH <= dev.fused_resident_wgs) {
             kFusedKernel<<<dim3(C, s.BH), 64 * kStateWaves, kFusedLds, hs>>>(
                 static_cast<const uint16_t *>(Qb), static_cast<const uint16_t *>(Kb),
-                static_cast<const uint16_t *>(Vb), static_cast<uint16_t *>(Ob), s.st, s.H, s.N, C, S, z, eps,
-                workspace, next_epoch(), kSpinLimit);
+                static_cast<const uint16_t *>(Vb), static_cast<uint16_t *>(Ob), s.st, s.H, s.N, C, S_in, z_in, S_out,
+                z_out, eps, workspace, next_epoch(), kSpinLimit);
             return launch_status();
         }
     }
-    rc = enqueue_state(Kb, Vb, s, 0, s.N, 1, S, z, workspace, hs);
+    rc = enqueue_state(Kb, Vb, s, 0, s.N, S_in, z_in, S_out, z_out, workspace, hs);
     if (rc != SV_OK) return rc;
-    return enqueue_apply(Qb, s, 0, s.N, S, z, eps, Ob, hs);
+    return enqueue_apply(Qb, s, 0, s.N, S_out, z_out, eps, Ob, hs);
+}
+
+sv_status sv_block_linattn_step(const void *Qb, const void *Kb, const void *Vb, const sv_tensor_desc *blk, float *S,
+                                float *z, float eps, void *Ob, void *workspace, size_t workspace_bytes_given,
+                                void *stream)
+{
+    return block_step(Qb, Kb, Vb, blk, S, z, S, z, false, eps, Ob, workspace, workspace_bytes_given, stream);
+}
+
+sv_status sv_block_linattn_lookahead(const void *Qb, const void *Kb, const void *Vb, const sv_tensor_desc *blk,
+                                     const float *S, const float *z, float eps, void *Ob, void *workspace,
+                                     size_t workspace_bytes_given, void *stream)
+{
+    return block_step(Qb, Kb, Vb, blk, S, z, nullptr, nullptr, true, eps, Ob, workspace, workspace_bytes_given,
+                      stream);
 }
 
 const char *sv_status_string(int status)

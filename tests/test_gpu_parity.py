@@ -293,3 +293,39 @@ def test_bounded_waits_never_time_out():
         sv.sv_block_linattn_step(Q, K, V, dsc, S, z, 1e-6, O, ws)
     torch.cuda.synchronize()
     assert int(ws[-16:-8].view(torch.int64)[0]) == 0
+
+
+# ---- look-ahead step: the cache is used but not updated (noisy passes of Alg. 1) -------------------
+
+@pytest.mark.parametrize("dtype,d,H", [("bf16", 64, 8), ("f32", 32, 2), ("bf16", 64, 300)])
+def test_lookahead_leaves_state_untouched(dtype, d, H):
+    import torch
+    B, N0, N1 = 1, 900, 333
+    say(f"lookahead dtype={dtype} d={d} H={H}")
+    Q0, K0, V0 = _draw(8000, B, H, N0, d, dtype)
+    Q1, K1, V1 = _draw(8001, B, H, N1, d, dtype)
+    S, z = new_state(B, H, d)
+    ws = new_workspace(B, H, max(N0, N1), d)
+    d0 = [to_dev(t) for t in (Q0, K0, V0)]
+    d1 = [to_dev(t) for t in (Q1, K1, V1)]
+    O0 = torch.empty_like(d0[0])
+    sv.sv_block_linattn_step(*d0, sv.desc_of(d0[0]), S, z, 1e-6, O0, ws)        # some carried state
+    torch.cuda.synchronize()
+    S_before, z_before = S.clone(), z.clone()
+    O_look = torch.empty_like(d1[0])
+    sv.sv_block_linattn_lookahead(*d1, sv.desc_of(d1[0]), S, z, 1e-6, O_look, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(S, S_before) and torch.equal(z, z_before)
+    O_commit = torch.empty_like(d1[0])
+    sv.sv_block_linattn_step(*d1, sv.desc_of(d1[0]), S, z, 1e-6, O_commit, ws)
+    torch.cuda.synchronize()
+    assert not torch.equal(S, S_before)
+    # both passes see the same updated state, so their outputs are bit-identical
+    view = torch.int16 if dtype == "bf16" else torch.int32
+    assert torch.equal(O_look.view(view), O_commit.view(view))
+    S0r, z0r = orc.state(K0, V0)
+    O_ref, S_same, z_same = orc.block_step(Q1, K1, V1, S0r, z0r, 1e-6, commit=False)
+    assert np.array_equal(S_same, S0r)
+    metrics.check(to_host(O_look), O_ref, dtype, "lookahead O")
+    _, S1r, z1r = orc.block_step(Q1, K1, V1, S0r, z0r, 1e-6, commit=True)
+    _check_state(S, z, S1r, z1r, "state after the committing pass")

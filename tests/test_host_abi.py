@@ -62,10 +62,10 @@ def test_bad_descriptors(kwargs, status):
     with pytest.raises(sv.SvError) as e:
         sv.sv_linattn_apply(FAKE, _desc(**kwargs), 0, 1, FAKE, FAKE, 1e-6, FAKE)
     assert e.value.status == status
-    with pytest.raises(sv.SvError) as e:
-        sv.sv_block_linattn_step(FAKE, FAKE, FAKE, _desc(**kwargs), FAKE, FAKE, 1e-6, FAKE, FAKE,
-                                 workspace_bytes=1 << 30)
-    assert e.value.status == status
+    for step in (sv.sv_block_linattn_step, sv.sv_block_linattn_lookahead):
+        with pytest.raises(sv.SvError) as e:
+            step(FAKE, FAKE, FAKE, _desc(**kwargs), FAKE, FAKE, 1e-6, FAKE, FAKE, workspace_bytes=1 << 30)
+        assert e.value.status == status
 
 
 def test_null_range_alignment_workspace_eps():
