@@ -35,16 +35,16 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 # 128-byte requests these kernels and the copy issue as 64 bytes; WRITE_SIZE x 1.0000).  Source:
 # profiles/traffic_pmc_bidir_480p.txt.  Algorithmic bytes per launch are 268 369 920.
 MEASURED_TRAFFIC_BYTES = {
-    ("apply", "bidir_480p"): int((67677.5 * 1.99965 + 131040.0) * 1024),
-    ("state", "bidir_480p"): int((133367.3 * 1.99965 + 4688.0) * 1024),
+    ("apply", "bidir_480p"): int((67677.1 * 1.99965 + 131040.0) * 1024),
+    ("state", "bidir_480p"): int((133355.3 * 1.99965 + 4688.0) * 1024),
 }
 
 
 def _parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=60)
-    ap.add_argument("--warmup", type=int, default=6)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="bidir_480p", choices=["bidir_480p", "bidir_720p"])
     ap.add_argument("--sets", type=int, default=0, help="rotating buffer sets (0 = enough for > 1.5 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
