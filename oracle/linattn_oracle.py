@@ -35,10 +35,10 @@ def _load():
         lib = ctypes.CDLL(build())
         i64, dbl, vp = ctypes.c_int64, ctypes.c_double, ctypes.c_void_p
         lib.orc_num_threads.restype = ctypes.c_int
-        lib.orc_state.argtypes = [vp, vp, i64, i64, i64, i64, i64, i64, ctypes.c_int, vp, vp]
-        lib.orc_apply.argtypes = [vp, i64, i64, i64, i64, i64, i64, vp, vp, dbl, vp]
-        lib.orc_bidirectional.argtypes = [vp, vp, vp, i64, i64, i64, i64, dbl, vp, vp, vp]
-        lib.orc_block_step.argtypes = [vp, vp, vp, i64, i64, i64, i64, dbl, vp, vp,
+        lib.orc_state.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, ctypes.c_int, vp, vp]
+        lib.orc_apply.argtypes = [vp, vp, i64, i64, i64, i64, i64, i64, vp, vp, dbl, vp]
+        lib.orc_bidirectional.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, dbl, vp, vp, vp]
+        lib.orc_block_step.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, dbl, vp, vp,
                                        ctypes.c_int, vp, vp, vp]
         for f in (lib.orc_state, lib.orc_apply, lib.orc_bidirectional, lib.orc_block_step):
             f.restype = None
@@ -64,11 +64,21 @@ def _widen(x: np.ndarray) -> np.ndarray:
     return np.ascontiguousarray(x)
 
 
-def _p(a: np.ndarray):
-    return a.ctypes.data_as(ctypes.c_void_p)
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
 
 
-def state(K, V, t0=None, t1=None, S=None, z=None):
+def _rope(rope, N, d):
+    """Rotation table [N][d/2][2] (cos, sin) as contiguous float32, or None."""
+    if rope is None:
+        return None
+    r = np.ascontiguousarray(rope, dtype=np.float32)
+    if r.shape != (N, d // 2, 2):
+        raise ValueError(f"rope table must be [N][d/2][2] = {(N, d // 2, 2)}, got {r.shape}")
+    return r
+
+
+def state(K, V, t0=None, t1=None, S=None, z=None, rope=None):
     """S, z over tokens [t0, t1); if S and z are given the sums are added to
     copies of them (the caller's arrays are not modified)."""
     K, V = _widen(K), _widen(V)
@@ -86,11 +96,11 @@ def state(K, V, t0=None, t1=None, S=None, z=None):
     else:
         S = np.empty((B, H, d, d), np.float64)
         z = np.empty((B, H, d), np.float64)
-    _load().orc_state(_p(K), _p(V), B, H, N, d, t0, t1, int(acc), _p(S), _p(z))
+    _load().orc_state(_p(K), _p(V), _p(_rope(rope, N, d)), B, H, N, d, t0, t1, int(acc), _p(S), _p(z))
     return S, z
 
 
-def apply(Q, S, z, eps, t0=None, t1=None):
+def apply(Q, S, z, eps, t0=None, t1=None, rope=None):
     """O for tokens [t0, t1) (shape [B][H][t1-t0][d]) from a given state."""
     Q = np.asarray(Q)
     if Q.ndim != 4:
@@ -102,14 +112,15 @@ def apply(Q, S, z, eps, t0=None, t1=None):
         raise ValueError("token range out of bounds")
     Q = _widen(Q[:, :, t0:t1, :])                 # only the rows that are asked for
     B, H, n, d = Q.shape
+    rope = None if rope is None else _rope(np.asarray(rope)[t0:t1], n, d)
     S = np.ascontiguousarray(S, dtype=np.float64).reshape(B, H, d, d)
     z = np.ascontiguousarray(z, dtype=np.float64).reshape(B, H, d)
     O = np.zeros((B, H, n, d), np.float64)
-    _load().orc_apply(_p(Q), B, H, n, d, 0, n, _p(S), _p(z), float(eps), _p(O))
+    _load().orc_apply(_p(Q), _p(rope), B, H, n, d, 0, n, _p(S), _p(z), float(eps), _p(O))
     return O
 
 
-def bidirectional(Q, K, V, eps):
+def bidirectional(Q, K, V, eps, rope=None):
     """O, S, z of a bidirectional layer."""
     Q, K, V = _widen(Q), _widen(K), _widen(V)
     if not (Q.shape == K.shape == V.shape):
@@ -118,11 +129,12 @@ def bidirectional(Q, K, V, eps):
     O = np.empty((B, H, N, d), np.float64)
     S = np.empty((B, H, d, d), np.float64)
     z = np.empty((B, H, d), np.float64)
-    _load().orc_bidirectional(_p(Q), _p(K), _p(V), B, H, N, d, float(eps), _p(O), _p(S), _p(z))
+    _load().orc_bidirectional(_p(Q), _p(K), _p(V), _p(_rope(rope, N, d)), B, H, N, d, float(eps), _p(O), _p(S),
+                              _p(z))
     return O, S, z
 
 
-def block_step(Qb, Kb, Vb, S, z, eps, commit=True):
+def block_step(Qb, Kb, Vb, S, z, eps, commit=True, rope=None):
     """One block of the block-causal stream. Returns (O_b, S_new, z_new); with
     commit=False the returned state equals the state passed in."""
     Qb, Kb, Vb = _widen(Qb), _widen(Kb), _widen(Vb)
@@ -133,7 +145,7 @@ def block_step(Qb, Kb, Vb, S, z, eps, commit=True):
     z = np.array(z, dtype=np.float64, copy=True).reshape(B, H, d)
     St, zt = np.empty_like(S), np.empty_like(z)
     Ob = np.empty((B, H, Nb, d), np.float64)
-    _load().orc_block_step(_p(Qb), _p(Kb), _p(Vb), B, H, Nb, d, float(eps), _p(S), _p(z),
+    _load().orc_block_step(_p(Qb), _p(Kb), _p(Vb), _p(_rope(rope, Nb, d)), B, H, Nb, d, float(eps), _p(S), _p(z),
                            int(bool(commit)), _p(St), _p(zt), _p(Ob))
     return Ob, S, z
 
@@ -143,12 +155,13 @@ def zero_state(B, H, d):
     return np.zeros((B, H, d, d), np.float64), np.zeros((B, H, d), np.float64)
 
 
-def block_stream(blocks, eps, S=None, z=None):
+def block_stream(blocks, eps, S=None, z=None, ropes=None):
     """Run block_step over an iterable of (Qb, Kb, Vb); yields (O_b, S, z) after
-    each block, starting from the given state or from the empty cache."""
-    for (Qb, Kb, Vb) in blocks:
+    each block, starting from the given state or from the empty cache.  `ropes`
+    is an optional sequence of per-block rotation tables."""
+    for m, (Qb, Kb, Vb) in enumerate(blocks):
         if S is None:
             B, H, _, d = np.asarray(Qb).shape
             S, z = zero_state(B, H, d)
-        Ob, S, z = block_step(Qb, Kb, Vb, S, z, eps, commit=True)
+        Ob, S, z = block_step(Qb, Kb, Vb, S, z, eps, commit=True, rope=None if ropes is None else ropes[m])
         yield Ob, S, z

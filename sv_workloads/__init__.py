@@ -19,7 +19,7 @@ import numpy as np
 
 __all__ = [
     "Workload", "WORKLOADS", "workload", "draw_qkv", "draw_block",
-    "draw_tensors", "f32_to_bf16_bits", "bf16_bits_to_f32", "as_f32",
+    "draw_tensors", "f32_to_bf16_bits", "bf16_bits_to_f32", "as_f32", "rope_table_3d",
 ]
 
 
@@ -151,3 +151,31 @@ def draw_block(w: Workload, m: int):
 def as_f32(x: np.ndarray, dtype: str) -> np.ndarray:
     """The stored values as fp32, exactly (bf16 bits are widened)."""
     return bf16_bits_to_f32(x) if dtype == "bf16" else np.asarray(x, np.float32)
+
+
+def rope_table_3d(frames: int, rows: int, cols: int, d: int, base: float = 10000.0,
+                  t0: int = 0) -> np.ndarray:
+    """Rotation table [frames*rows*cols][d/2][2] (cos, sin) in fp32 for tokens laid
+    out frame-major, then row, then column: a 3-D rotary embedding.
+
+    The paper says "3D RoPE" without frequencies; this generator (a proposal, used
+    for test and benchmark inputs only) gives the d/2 feature pairs to the three
+    axes in the proportion 2:3:3 (time gets what is left after rows and columns
+    take floor(3/8 * d/2) each) and uses angle = position * base^(-i/n_axis) for
+    the i-th pair of an axis with n_axis pairs.  `t0` is the index of the first
+    frame (blocks of a stream continue the time axis).  The library itself only
+    sees the table."""
+    half = d // 2
+    n_hw = (3 * half) // 8
+    n_t = half - 2 * n_hw
+    t = np.arange(t0, t0 + frames, dtype=np.float64)[:, None, None]
+    r = np.arange(rows, dtype=np.float64)[None, :, None]
+    c = np.arange(cols, dtype=np.float64)[None, None, :]
+    ang = np.empty((frames, rows, cols, half), np.float64)
+    for i in range(n_t):
+        ang[..., i] = t * base ** (-i / n_t)
+    for i in range(n_hw):
+        ang[..., n_t + i] = r * base ** (-i / n_hw)
+        ang[..., n_t + n_hw + i] = c * base ** (-i / n_hw)
+    ang = ang.reshape(frames * rows * cols, half)
+    return np.stack([np.cos(ang), np.sin(ang)], axis=-1).astype(np.float32)

@@ -39,3 +39,31 @@ def kernel_score_attention_dense(Q, K, V, eps, block_of=None):
         b = np.asarray(block_of)
         A = A * (b[None, :] <= b[:, None])
     return (A @ V) / (A.sum(axis=1, keepdims=True) + eps)
+
+
+def rotate_pairs(X, table):
+    """rot_t(x) for every token: adjacent feature pairs (2p, 2p+1) of row t turned
+    by the angle whose (cos, sin) is table[t][p]."""
+    X = np.asarray(X, np.float64)
+    c = np.asarray(table, np.float64)[..., 0]
+    s = np.asarray(table, np.float64)[..., 1]
+    Y = np.empty_like(X)
+    Y[:, 0::2] = X[:, 0::2] * c - X[:, 1::2] * s
+    Y[:, 1::2] = X[:, 0::2] * s + X[:, 1::2] * c
+    return Y
+
+
+def kernel_score_attention_rope(Q, K, V, table, eps, block_of=None):
+    """The full Sec. 3.2 equation as O(N^2) attention with TWO score matrices:
+    numerator scores from rotated ReLU features, denominator scores from the
+    un-rotated ones."""
+    pQ = np.maximum(np.asarray(Q, np.float64), 0.0)
+    pK = np.maximum(np.asarray(K, np.float64), 0.0)
+    V = np.asarray(V, np.float64)
+    A_num = rotate_pairs(pQ, table) @ rotate_pairs(pK, table).T
+    A_den = pQ @ pK.T
+    if block_of is not None:
+        b = np.asarray(block_of)
+        mask = b[None, :] <= b[:, None]
+        A_num, A_den = A_num * mask, A_den * mask
+    return (A_num @ V) / (A_den.sum(axis=1, keepdims=True) + eps)
