@@ -119,6 +119,42 @@ sv_status sv_block_linattn_lookahead(const void *Qb, const void *Kb, const void 
                                      const float *S, const float *z, float eps, void *Ob,
                                      void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- RoPE variants: the full linear-attention equation of Sec. 3.2 ----------------
+ *
+ *     O_i = RoPE(phi(Q_i)) (sum_j RoPE(phi(K_j))^T V_j) / (phi(Q_i) (sum_j phi(K_j)^T) + eps)
+ *
+ * RoPE is applied AFTER the ReLU and only in the numerator; the denominator keeps
+ * the un-rotated features so that it stays positive.  `rope` is a DEVICE pointer
+ * to fp32 [N][d/2][2]: row t belongs to token t of the descriptor (for a block
+ * step: token t of the block) and holds, per feature pair p = (2p, 2p+1), the
+ * cosine and sine of that pair's angle:
+ *     y[2p] = x[2p] cos - x[2p+1] sin,    y[2p+1] = x[2p] sin + x[2p+1] cos.
+ * One table serves all batches and heads.  How angles derive from a token's
+ * (frame, row, column) position is up to the caller (the paper names "3D RoPE"
+ * without frequencies).  The table must be 16-byte aligned and not NULL.  S then
+ * holds the state of ROTATED keys; z, the key sum, is never rotated.  In SV_BF16
+ * mode rotated features are rounded to bf16 before the MFMA.  Everything else
+ * (arguments, checks, errors, determinism) is as in the call without _rope. */
+sv_status sv_linattn_state_rope(const void *K, const void *V, const sv_tensor_desc *kv,
+                                const float *rope, int32_t tok_begin, int32_t tok_end,
+                                int accumulate, float *S, float *z,
+                                void *workspace, size_t workspace_bytes, void *stream);
+
+sv_status sv_linattn_apply_rope(const void *Q, const sv_tensor_desc *q, const float *rope,
+                                int32_t tok_begin, int32_t tok_end,
+                                const float *S, const float *z, float eps,
+                                void *O, void *stream);
+
+sv_status sv_block_linattn_step_rope(const void *Qb, const void *Kb, const void *Vb,
+                                     const sv_tensor_desc *blk, const float *rope,
+                                     float *S, float *z, float eps, void *Ob,
+                                     void *workspace, size_t workspace_bytes, void *stream);
+
+sv_status sv_block_linattn_lookahead_rope(const void *Qb, const void *Kb, const void *Vb,
+                                          const sv_tensor_desc *blk, const float *rope,
+                                          const float *S, const float *z, float eps, void *Ob,
+                                          void *workspace, size_t workspace_bytes, void *stream);
+
 /* Human-readable name of a status code (static storage). */
 const char *sv_status_string(int status);
 

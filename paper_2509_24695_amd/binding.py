@@ -16,6 +16,8 @@ SV_BF16, SV_F32 = 0, 1
 EXPORTS = (
     "sv_linattn_workspace_bytes", "sv_linattn_state", "sv_linattn_apply",
     "sv_block_linattn_step", "sv_block_linattn_lookahead", "sv_status_string", "sv_version",
+    "sv_linattn_state_rope", "sv_linattn_apply_rope", "sv_block_linattn_step_rope",
+    "sv_block_linattn_lookahead_rope",
 )
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
@@ -77,6 +79,13 @@ def load_library():
     lib.sv_block_linattn_step.restype = ctypes.c_int
     lib.sv_block_linattn_lookahead.argtypes = [vp, vp, vp, dp, vp, vp, ctypes.c_float, vp, vp, sz, vp]
     lib.sv_block_linattn_lookahead.restype = ctypes.c_int
+    lib.sv_linattn_state_rope.argtypes = [vp, vp, dp, vp, i32, i32, ctypes.c_int, vp, vp, vp, sz, vp]
+    lib.sv_linattn_apply_rope.argtypes = [vp, dp, vp, i32, i32, vp, vp, ctypes.c_float, vp, vp]
+    lib.sv_block_linattn_step_rope.argtypes = [vp, vp, vp, dp, vp, vp, vp, ctypes.c_float, vp, vp, sz, vp]
+    lib.sv_block_linattn_lookahead_rope.argtypes = [vp, vp, vp, dp, vp, vp, vp, ctypes.c_float, vp, vp, sz, vp]
+    for f in (lib.sv_linattn_state_rope, lib.sv_linattn_apply_rope, lib.sv_block_linattn_step_rope,
+              lib.sv_block_linattn_lookahead_rope):
+        f.restype = ctypes.c_int
     lib.sv_status_string.argtypes = [ctypes.c_int]
     lib.sv_status_string.restype = ctypes.c_char_p
     lib.sv_version.argtypes = []
@@ -169,3 +178,39 @@ def sv_block_linattn_lookahead(Qb, Kb, Vb, blk: TensorDesc, S, z, eps: float, Ob
     _check(load_library().sv_block_linattn_lookahead(_ptr(Qb), _ptr(Kb), _ptr(Vb), ctypes.byref(d) if d else None,
                                                      _ptr(S), _ptr(z), float(eps), _ptr(Ob), _ptr(workspace), wb,
                                                      _stream(stream)), "sv_block_linattn_lookahead")
+
+
+def sv_linattn_state_rope(K, V, kv: TensorDesc, rope, tok_begin: int, tok_end: int, accumulate: int, S, z,
+                          workspace, workspace_bytes: int | None = None, stream=None) -> None:
+    d = kv._c() if kv is not None else None
+    wb = _nbytes(workspace) if workspace_bytes is None else int(workspace_bytes)
+    _check(load_library().sv_linattn_state_rope(_ptr(K), _ptr(V), ctypes.byref(d) if d else None, _ptr(rope),
+                                                tok_begin, tok_end, int(accumulate), _ptr(S), _ptr(z),
+                                                _ptr(workspace), wb, _stream(stream)), "sv_linattn_state_rope")
+
+
+def sv_linattn_apply_rope(Q, q: TensorDesc, rope, tok_begin: int, tok_end: int, S, z, eps: float, O,
+                          stream=None) -> None:
+    d = q._c() if q is not None else None
+    _check(load_library().sv_linattn_apply_rope(_ptr(Q), ctypes.byref(d) if d else None, _ptr(rope), tok_begin,
+                                                tok_end, _ptr(S), _ptr(z), float(eps), _ptr(O), _stream(stream)),
+           "sv_linattn_apply_rope")
+
+
+def _block_rope(fn_name, Qb, Kb, Vb, blk, rope, S, z, eps, Ob, workspace, workspace_bytes, stream):
+    d = blk._c() if blk is not None else None
+    wb = _nbytes(workspace) if workspace_bytes is None else int(workspace_bytes)
+    fn = getattr(load_library(), fn_name)
+    _check(fn(_ptr(Qb), _ptr(Kb), _ptr(Vb), ctypes.byref(d) if d else None, _ptr(rope), _ptr(S), _ptr(z), float(eps),
+              _ptr(Ob), _ptr(workspace), wb, _stream(stream)), fn_name)
+
+
+def sv_block_linattn_step_rope(Qb, Kb, Vb, blk: TensorDesc, rope, S, z, eps: float, Ob, workspace,
+                               workspace_bytes: int | None = None, stream=None) -> None:
+    _block_rope("sv_block_linattn_step_rope", Qb, Kb, Vb, blk, rope, S, z, eps, Ob, workspace, workspace_bytes, stream)
+
+
+def sv_block_linattn_lookahead_rope(Qb, Kb, Vb, blk: TensorDesc, rope, S, z, eps: float, Ob, workspace,
+                                    workspace_bytes: int | None = None, stream=None) -> None:
+    _block_rope("sv_block_linattn_lookahead_rope", Qb, Kb, Vb, blk, rope, S, z, eps, Ob, workspace, workspace_bytes,
+                stream)

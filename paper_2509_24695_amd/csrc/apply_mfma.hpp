@@ -127,17 +127,25 @@ __device__ __forceinline__ void apply_prefetch(const uint16_t *Qh, int64_t strid
     }
 }
 
-template <bool HILO, int DEPTH, int NB>
-__device__ __forceinline__ void apply_tiles(const uint16_t *Qh, uint16_t *Oh, int64_t stride_n, int t0, int t1,
-                                            int first_tile, int tile_step, int n_tiles, unsigned char *tileQ,
-                                            int lane, const ApplyOperands<HILO> &A, float eps,
+// ROPE: the numerator uses queries rotated after the ReLU (table row = token index); the
+// denominator keeps the plain ones.  The wave's LDS region then holds a second,
+// rotated copy of each tile after the NB plain ones, and `rope` is the table.
+template <bool HILO, int DEPTH, int NB, bool ROPE>
+__device__ __forceinline__ void apply_tiles(const uint16_t *Qh, uint16_t *Oh, const float *rope, int64_t stride_n,
+                                            int t0, int t1, int first_tile, int tile_step, int n_tiles,
+                                            unsigned char *tileQ, int lane, const ApplyOperands<HILO> &A, float eps,
                                             u32x4 (&qreg)[DEPTH][kApplyTile / 8])
 {
     static_assert(DEPTH % NB == 0, "stages are consumed NB at a time");
+    static_assert(!ROPE || (NB == 1 && DEPTH % 2 == 0), "the table ring below alternates between two slots");
     constexpr int NS = HILO ? 2 : 1;
     constexpr int kTileBytes = kApplyTile * kRowBytes;
     const int n = lane & 31, g = lane >> 5;
     const int wr_off = (lane >> 3) * kRowBytes + (lane & 7) * 16;
+
+    // rotation-table entries of the tile in work and of the next one (slot = stage parity)
+    f32x4 cs[ROPE ? 2 : 1][kApplyTile / 8][2];
+    if (ROPE && first_tile < n_tiles) rope_tile_load<kApplyTile>(rope, t0 + first_tile * kApplyTile, t1, lane, cs[0]);
 
     // NB tiles go through each phase together, so that one tile's LDS and
     // conversion latencies hide behind the other's MFMA chain.
@@ -155,24 +163,35 @@ __device__ __forceinline__ void apply_tiles(const uint16_t *Qh, uint16_t *Oh, in
                 for (int j = 0; j < NB; ++j)
                     if (valid[j]) {
 #pragma unroll
-                        for (int i = 0; i < kApplyTile / 8; ++i)
-                            *reinterpret_cast<u32x4 *>(tileQ + j * kTileBytes + wr_off + 8 * i * kRowBytes) =
-                                relu_bf16x8(qreg[s0 + j][i]);                                   // phi(Q)
+                        for (int i = 0; i < kApplyTile / 8; ++i) {
+                            const u32x4 pq = relu_bf16x8(qreg[s0 + j][i]);                          // phi(Q)
+                            *reinterpret_cast<u32x4 *>(tileQ + j * kTileBytes + wr_off + 8 * i * kRowBytes) = pq;
+                            if (ROPE)
+                                *reinterpret_cast<u32x4 *>(tileQ + (NB + j) * kTileBytes + wr_off + 8 * i * kRowBytes) =
+                                    rope_rotate_bf16x8(pq, cs[ROPE ? s0 & 1 : 0][i][0], cs[ROPE ? s0 & 1 : 0][i][1]);
+                        }
                         const int nxt = tile + (j + DEPTH) * tile_step;
                         if (nxt < n_tiles)
                             apply_tile_load(Qh, stride_n, t0 + nxt * kApplyTile, t1, lane, qreg[s0 + j]);
+                        if (ROPE && tile + tile_step < n_tiles)
+                            rope_tile_load<kApplyTile>(rope, t0 + (tile + tile_step) * kApplyTile, t1, lane,
+                                                       cs[ROPE ? (s0 & 1) ^ 1 : 0]);
                     }
                 wave_lds_fence();
 
-                // B operands: features 16*ks + 8g .. +8 of token n
-                bf16x8 Bq[NB][4];
+                // B operands: features 16*ks + 8g .. +8 of token n (Br: the rotated copy for the numerator)
+                bf16x8 Bq[NB][4], Br[ROPE ? NB : 1][4];
 #pragma unroll
                 for (int j = 0; j < NB; ++j)
                     if (valid[j]) {
 #pragma unroll
-                        for (int ks = 0; ks < 4; ++ks)
+                        for (int ks = 0; ks < 4; ++ks) {
                             Bq[j][ks] = *reinterpret_cast<const bf16x8 *>(tileQ + j * kTileBytes + n * kRowBytes +
                                                                           (16 * ks + 8 * g) * 2);
+                            if (ROPE)
+                                Br[j][ks] = *reinterpret_cast<const bf16x8 *>(tileQ + (NB + j) * kTileBytes +
+                                                                              n * kRowBytes + (16 * ks + 8 * g) * 2);
+                        }
                     }
 
                 f32x16 acc[NB][2], accz[NB];
@@ -193,10 +212,9 @@ __device__ __forceinline__ void apply_tiles(const uint16_t *Qh, uint16_t *Oh, in
 #pragma unroll
                         for (int j = 0; j < NB; ++j)
                             if (valid[j]) {
-                                acc[j][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.s[p][0][ks], Bq[j][ks],
-                                                                                    acc[j][0], 0, 0, 0);
-                                acc[j][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.s[p][1][ks], Bq[j][ks],
-                                                                                    acc[j][1], 0, 0, 0);
+                                const bf16x8 bq = ROPE ? Br[ROPE ? j : 0][ks] : Bq[j][ks];
+                                acc[j][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.s[p][0][ks], bq, acc[j][0], 0, 0, 0);
+                                acc[j][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.s[p][1][ks], bq, acc[j][1], 0, 0, 0);
                             }
 
                 wave_lds_fence();
@@ -244,18 +262,21 @@ __device__ __forceinline__ void apply_tiles(const uint16_t *Qh, uint16_t *Oh, in
     }
 }
 
-template <int WAVES, int NB>
-__host__ __device__ constexpr int apply_lds_bytes() { return WAVES * NB * kApplyTile * kRowBytes; }
+// LDS bytes per wave and in total: NB tiles, twice that with ROPE (plain + rotated copies).
+template <int NB, bool ROPE>
+__host__ __device__ constexpr int apply_wave_lds_bytes() { return (ROPE ? 2 : 1) * NB * kApplyTile * kRowBytes; }
+template <int WAVES, int NB, bool ROPE>
+__host__ __device__ constexpr int apply_lds_bytes() { return WAVES * apply_wave_lds_bytes<NB, ROPE>(); }
 
 // grid = (C, B*H), block = 64*WAVES.  Wave w of workgroup c owns tiles
 // WAVES*c + w + WAVES*C*i (i = 0, 1, ...) of the T = ceil((t1-t0)/32) tiles,
 // the same round-robin deal as the state kernel.
 // HILO = false drops the low half of S (one MFMA pass instead of two).
 // NB tiles of a wave are in the arithmetic phase together.
-template <bool HILO, int WAVES, int DEPTH, int NB>
+template <bool HILO, int WAVES, int DEPTH, int NB, bool ROPE>
 __global__ __launch_bounds__(64 * WAVES, 1) void apply_mfma_d64(
-    const uint16_t *__restrict__ Q, uint16_t *__restrict__ O, TokStrides st, int H, int t0, int t1, int C,
-    const float *__restrict__ S, const float *__restrict__ z, float eps)
+    const uint16_t *__restrict__ Q, uint16_t *__restrict__ O, const float *__restrict__ rope, TokStrides st, int H,
+    int t0, int t1, int C, const float *__restrict__ S, const float *__restrict__ z, float eps)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int tid = threadIdx.x;
@@ -271,8 +292,8 @@ __global__ __launch_bounds__(64 * WAVES, 1) void apply_mfma_d64(
     apply_prefetch<DEPTH>(Qh, st.n, t0, t1, first, step, n_tiles, lane, qreg);   // in flight while S is fetched
     ApplyOperands<HILO> A;
     A.template load<false>(S + (size_t)bh * 64 * 64, z + (size_t)bh * 64, lane);
-    apply_tiles<HILO, DEPTH, NB>(Qh, Oh, st.n, t0, t1, first, step, n_tiles,
-                                 lds + wave * NB * kApplyTile * kRowBytes, lane, A, eps, qreg);
+    apply_tiles<HILO, DEPTH, NB, ROPE>(Qh, Oh, rope, st.n, t0, t1, first, step, n_tiles,
+                                       lds + wave * apply_wave_lds_bytes<NB, ROPE>(), lane, A, eps, qreg);
 }
 
 }  // namespace sv

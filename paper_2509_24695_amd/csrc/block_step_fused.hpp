@@ -21,17 +21,18 @@
 
 namespace sv {
 
-template <int TILE, int WAVES, int NB>
+template <int TILE, int WAVES, int NB, bool ROPE>
 __host__ __device__ constexpr int block_step_lds_bytes() {
-    return state_lds_bytes<TILE, WAVES>() > apply_lds_bytes<WAVES, NB>() ? state_lds_bytes<TILE, WAVES>()
-                                                                         : apply_lds_bytes<WAVES, NB>();
+    return state_lds_bytes<TILE, WAVES>() > apply_lds_bytes<WAVES, NB, ROPE>() ? state_lds_bytes<TILE, WAVES>()
+                                                                               : apply_lds_bytes<WAVES, NB, ROPE>();
 }
 
 // grid = (C, B*H) with C*B*H <= resident workgroup capacity, block = 64*WAVES.
-template <int TILE, int WAVES, int DEPTH_S, bool HILO, int DEPTH_A, int NB>
+// ROPE: keys and queries are rotated after the ReLU in the numerator path (table row = token of the block).
+template <int TILE, int WAVES, int DEPTH_S, bool HILO, int DEPTH_A, int NB, bool ROPE>
 __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma_d64(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
-    uint16_t *__restrict__ O, TokStrides st, int H, int N, int C, const float *S_in, const float *z_in,
+    uint16_t *__restrict__ O, const float *__restrict__ rope, TokStrides st, int H, int N, int C, const float *S_in, const float *z_in,
     float *S_out, float *z_out, float eps, void *__restrict__ ws, unsigned long long epoch, uint32_t spin_limit)
 {
     constexpr int THREADS = 64 * WAVES;
@@ -61,12 +62,12 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma_d64(
         const int n_tiles = (N + TILE - 1) / TILE;
         StateAcc acc;
         acc.clear();
-        StateStages<TILE, DEPTH_S> stg;
+        StateStages<TILE, DEPTH_S, ROPE> stg;
         unsigned char *tileK = lds + wave * 2 * kTileBytes;
-        state_prefetch<TILE, DEPTH_S>(K + head_off, V + head_off, st.n, 0, N, WAVES * c + wave, WAVES * C, n_tiles,
-                                      lane, stg);
-        state_accumulate<TILE, DEPTH_S>(K + head_off, V + head_off, st.n, 0, N, WAVES * c + wave, WAVES * C, n_tiles,
-                                        tileK, tileK + kTileBytes, lane, stg, acc);
+        state_prefetch<TILE, DEPTH_S, ROPE>(K + head_off, V + head_off, rope, st.n, 0, N, WAVES * c + wave, WAVES * C,
+                                            n_tiles, lane, stg);
+        state_accumulate<TILE, DEPTH_S, ROPE>(K + head_off, V + head_off, rope, st.n, 0, N, WAVES * c + wave,
+                                              WAVES * C, n_tiles, tileK, tileK + kTileBytes, lane, stg, acc);
         // the rest of this wave's Q prefetch streams in while the head's state is being agreed on
         apply_prefetch<DEPTH_A, kEarly, DEPTH_A>(Q + head_off, st.n, 0, N, first, step, n_tiles_q, lane, qreg);
         float *partials = static_cast<float *>(ws) + (size_t)bh * kMaxChunks * kStateElems;
@@ -86,8 +87,8 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma_d64(
     // ---- apply the updated state to this workgroup's share of Q_b ----------------------------------
     ApplyOperands<HILO> A;
     A.template load<true>(Sh, zh, lane);
-    apply_tiles<HILO, DEPTH_A, NB>(Q + head_off, O + head_off, st.n, 0, N, first, step, n_tiles_q,
-                                   lds + wave * NB * kApplyTile * kRowBytes, lane, A, eps, qreg);
+    apply_tiles<HILO, DEPTH_A, NB, ROPE>(Q + head_off, O + head_off, rope, st.n, 0, N, first, step, n_tiles_q,
+                                         lds + wave * apply_wave_lds_bytes<NB, ROPE>(), lane, A, eps, qreg);
 }
 
 }  // namespace sv

@@ -50,6 +50,43 @@ __device__ __forceinline__ u32x4 relu_bf16x8(u32x4 v) {
     return v;
 }
 
+// ---- RoPE after ReLU (numerator of the Sec. 3.2 equation) ----------------------------------------
+// A rotation table row holds d/2 (cos, sin) fp32 pairs of one token; feature pair
+// (2p, 2p+1) is turned by angle p:  y[2p] = x[2p] cos - x[2p+1] sin,  y[2p+1] = x[2p] sin + x[2p+1] cos.
+// A 32-bit word of a bf16 token row is exactly one such pair.
+__device__ __forceinline__ uint32_t rope_rotate_pair(uint32_t w, float c, float s) {
+    const float a = bf16_lo(w), b = bf16_hi(w);
+    return pack_bf16x2(a * c - b * s, a * s + b * c);
+}
+// Four pairs (16 bytes of a token row) with their four (cos, sin) entries.
+__device__ __forceinline__ u32x4 rope_rotate_bf16x8(u32x4 w, f32x4 cs01, f32x4 cs23) {
+    u32x4 r;
+    r.x = rope_rotate_pair(w.x, cs01.x, cs01.y);
+    r.y = rope_rotate_pair(w.y, cs01.z, cs01.w);
+    r.z = rope_rotate_pair(w.z, cs23.x, cs23.y);
+    r.w = rope_rotate_pair(w.w, cs23.z, cs23.w);
+    return r;
+}
+// Table entries for the 16-byte chunks a lane holds of a d = 64 tile in the coalesced layout
+// (token tok0 + lane/8 + 8i, pairs 4*(lane%8) .. +3).  Rows past t1 are not touched.
+template <int TILE>
+__device__ __forceinline__ void rope_tile_load(const float *__restrict__ rope, int tok0, int t1, int lane,
+                                               f32x4 (&cs)[TILE / 8][2])
+{
+#pragma unroll
+    for (int i = 0; i < TILE / 8; ++i) {
+        const int tok = tok0 + (lane >> 3) + 8 * i;
+        f32x4 a = {1.f, 0.f, 1.f, 0.f}, b = {1.f, 0.f, 1.f, 0.f};
+        if (tok < t1) {
+            const float *row = rope + (int64_t)tok * 64 + (lane & 7) * 8;
+            a = *reinterpret_cast<const f32x4 *>(row);
+            b = *reinterpret_cast<const f32x4 *>(row + 4);
+        }
+        cs[i][0] = a;
+        cs[i][1] = b;
+    }
+}
+
 // Streaming 16-byte global accesses.  Tokens are read once and outputs written
 // once, so with SV_STREAM_NT both are marked non-temporal.
 #ifndef SV_STREAM_NT

@@ -15,15 +15,18 @@ namespace sv {
 //   ws[(bh*C + c)][D*D + k] = sum_{j in chunk c} phi(K[j][k])             (denominator bracket)
 // grid = (C, B*H), block = 256.  Tiles hold TT tokens; chunk c owns tiles
 // [c*T/C, (c+1)*T/C) of the T tiles that cover [t0, t1).
+// rope != null: the keys that meet V are rotated after the ReLU (table row = token index,
+// D/2 (cos, sin) pairs); the key sum uses the plain ones.
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void state_partial_generic(
-    const T *__restrict__ K, const T *__restrict__ V, TokStrides st, int H, int t0, int t1, int C,
-    float *__restrict__ ws)
+    const T *__restrict__ K, const T *__restrict__ V, const float *__restrict__ rope, TokStrides st, int H, int t0,
+    int t1, int C, float *__restrict__ ws)
 {
     constexpr int TT = 32;
     constexpr int EPT = D * D / kThreads;   // S elements per thread (one row segment)
     constexpr int TPR = D / EPT;            // threads per S row
-    __shared__ float sK[TT][D];
+    __shared__ float sK[TT][D];             // keys as they enter S (rotated when rope is given)
+    __shared__ float sP[TT][D];             // phi(K) as it enters the key sum
     __shared__ float sV[TT][D];
 
     const int tid = threadIdx.x;
@@ -44,22 +47,32 @@ __global__ __launch_bounds__(kThreads) void state_partial_generic(
 
     for (int tile = tile_lo; tile < tile_hi; ++tile) {
         const int tok0 = t0 + tile * TT;
-        for (int idx = tid; idx < TT * D; idx += kThreads) {
-            const int j = idx / D, f = idx % D;
+        for (int idx = tid; idx < TT * D / 2; idx += kThreads) {       // one feature pair per step
+            const int j = idx / (D / 2), p = idx % (D / 2);
             const int tok = tok0 + j;
-            float kv = 0.f, vv = 0.f;
+            float a = 0.f, b = 0.f, va = 0.f, vb = 0.f, c = 1.f, s = 0.f;
             if (tok < t1) {
-                kv = fmaxf(Elem<T>::load(Kh + (int64_t)tok * st.n + f), 0.f);   // phi = ReLU
-                vv = Elem<T>::load(Vh + (int64_t)tok * st.n + f);
+                a = fmaxf(Elem<T>::load(Kh + (int64_t)tok * st.n + 2 * p), 0.f);       // phi = ReLU
+                b = fmaxf(Elem<T>::load(Kh + (int64_t)tok * st.n + 2 * p + 1), 0.f);
+                va = Elem<T>::load(Vh + (int64_t)tok * st.n + 2 * p);
+                vb = Elem<T>::load(Vh + (int64_t)tok * st.n + 2 * p + 1);
+                if (rope) {
+                    c = rope[(int64_t)tok * D + 2 * p];
+                    s = rope[(int64_t)tok * D + 2 * p + 1];
+                }
             }
-            sK[j][f] = kv;
-            sV[j][f] = vv;
+            sP[j][2 * p] = a;
+            sP[j][2 * p + 1] = b;
+            sK[j][2 * p] = a * c - b * s;
+            sK[j][2 * p + 1] = a * s + b * c;
+            sV[j][2 * p] = va;
+            sV[j][2 * p + 1] = vb;
         }
         __syncthreads();
 #pragma unroll 4
         for (int j = 0; j < TT; ++j) {
             const float a = sK[j][k];
-            zacc += a;
+            zacc += sP[j][k];
 #pragma unroll
             for (int e = 0; e < EPT; ++e) acc[e] = fmaf(a, sV[j][v0 + e], acc[e]);
         }
@@ -98,17 +111,19 @@ __global__ __launch_bounds__(kThreads) void state_reduce(
 // O[i][v] = (sum_k phi(Q[i][k]) S[k][v]) / (sum_k phi(Q[i][k]) z[k] + eps)   (Sec. 3.2, right-hand form)
 // grid = (C, B*H), block = 256.  The head's S and z stay in LDS for the whole
 // token range of the workgroup.
+// rope != null: the numerator uses queries rotated after the ReLU, the denominator the plain ones.
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void apply_generic(
-    const T *__restrict__ Q, T *__restrict__ O, TokStrides st, int H, int t0, int t1, int C,
-    const float *__restrict__ S, const float *__restrict__ z, float eps)
+    const T *__restrict__ Q, T *__restrict__ O, const float *__restrict__ rope, TokStrides st, int H, int t0, int t1,
+    int C, const float *__restrict__ S, const float *__restrict__ z, float eps)
 {
     constexpr int VPT = 4;                   // outputs per thread
     constexpr int TPT = D / VPT;             // threads per token
     constexpr int TT = kThreads / TPT;       // tokens per tile
     __shared__ float sS[D][D];
     __shared__ float sz[D];
-    __shared__ float sQ[TT][D];
+    __shared__ float sQ[TT][D];              // queries of the numerator (rotated when rope is given)
+    __shared__ float sP[TT][D];              // phi(Q) of the denominator
 
     const int tid = threadIdx.x;
     const int c = blockIdx.x, bh = blockIdx.y;
@@ -127,10 +142,22 @@ __global__ __launch_bounds__(kThreads) void apply_generic(
     for (int tile = tile_lo; tile < tile_hi; ++tile) {
         const int tok0 = t0 + tile * TT;
         __syncthreads();
-        for (int idx = tid; idx < TT * D; idx += kThreads) {
-            const int jj = idx / D, f = idx % D;
+        for (int idx = tid; idx < TT * D / 2; idx += kThreads) {
+            const int jj = idx / (D / 2), p = idx % (D / 2);
             const int tok = tok0 + jj;
-            sQ[jj][f] = tok < t1 ? fmaxf(Elem<T>::load(Qh + (int64_t)tok * st.n + f), 0.f) : 0.f;
+            float a = 0.f, b = 0.f, c = 1.f, s = 0.f;
+            if (tok < t1) {
+                a = fmaxf(Elem<T>::load(Qh + (int64_t)tok * st.n + 2 * p), 0.f);
+                b = fmaxf(Elem<T>::load(Qh + (int64_t)tok * st.n + 2 * p + 1), 0.f);
+                if (rope) {
+                    c = rope[(int64_t)tok * D + 2 * p];
+                    s = rope[(int64_t)tok * D + 2 * p + 1];
+                }
+            }
+            sP[jj][2 * p] = a;
+            sP[jj][2 * p + 1] = b;
+            sQ[jj][2 * p] = a * c - b * s;
+            sQ[jj][2 * p + 1] = a * s + b * c;
         }
         __syncthreads();
         float num[VPT] = {0.f, 0.f, 0.f, 0.f};
@@ -138,7 +165,7 @@ __global__ __launch_bounds__(kThreads) void apply_generic(
 #pragma unroll 8
         for (int k = 0; k < D; ++k) {
             const float q = sQ[j][k];
-            den = fmaf(q, sz[k], den);
+            den = fmaf(sP[j][k], sz[k], den);
 #pragma unroll
             for (int e = 0; e < VPT; ++e) num[e] = fmaf(q, sS[k][v0 + e], num[e]);
         }

@@ -117,23 +117,28 @@ __device__ __forceinline__ void lds_gather_pairs(const unsigned char *tile, int 
     odd = __builtin_bit_cast(bf16x8, hi);
 }
 
-// Register staging of one wave: the K and V rows of DEPTH tiles in flight.
-template <int TILE, int DEPTH>
+// Register staging of one wave: the K and V rows of DEPTH tiles in flight, and
+// with ROPE the rotation-table entries that go with the K rows.
+template <int TILE, int DEPTH, bool ROPE>
 struct StateStages {
     u32x4 k[DEPTH][TILE / 8], v[DEPTH][TILE / 8];
+    f32x4 cs[ROPE ? DEPTH : 1][TILE / 8][2];
 };
 
 // Requests the first DEPTH tiles of a wave's share (tiles first_tile,
 // first_tile + tile_step, ... below n_tiles).
-template <int TILE, int DEPTH>
-__device__ __forceinline__ void state_prefetch(const uint16_t *Kh, const uint16_t *Vh, int64_t stride_n, int t0,
-                                               int t1, int first_tile, int tile_step, int n_tiles, int lane,
-                                               StateStages<TILE, DEPTH> &st)
+template <int TILE, int DEPTH, bool ROPE>
+__device__ __forceinline__ void state_prefetch(const uint16_t *Kh, const uint16_t *Vh, const float *rope,
+                                               int64_t stride_n, int t0, int t1, int first_tile, int tile_step,
+                                               int n_tiles, int lane, StateStages<TILE, DEPTH, ROPE> &st)
 {
 #pragma unroll
     for (int s = 0; s < DEPTH; ++s) {
         const int t = first_tile + s * tile_step;
-        if (t < n_tiles) state_tile_load<TILE>(Kh, Vh, stride_n, t0 + t * TILE, t1, lane, st.k[s], st.v[s]);
+        if (t < n_tiles) {
+            state_tile_load<TILE>(Kh, Vh, stride_n, t0 + t * TILE, t1, lane, st.k[s], st.v[s]);
+            if (ROPE) rope_tile_load<TILE>(rope, t0 + t * TILE, t1, lane, st.cs[ROPE ? s : 0]);
+        }
     }
 }
 
@@ -141,11 +146,11 @@ __device__ __forceinline__ void state_prefetch(const uint16_t *Kh, const uint16_
 // tile_step, ... below n_tiles, the first DEPTH of which state_prefetch has
 // already requested into `st`.  Tokens past t1 are loaded as zeros, which add
 // nothing to either sum.  `tileK`/`tileV` are this wave's private LDS tiles.
-template <int TILE, int DEPTH>
-__device__ __forceinline__ void state_accumulate(const uint16_t *Kh, const uint16_t *Vh, int64_t stride_n, int t0,
-                                                 int t1, int first_tile, int tile_step, int n_tiles,
-                                                 unsigned char *tileK, unsigned char *tileV, int lane,
-                                                 StateStages<TILE, DEPTH> &st, StateAcc &acc)
+template <int TILE, int DEPTH, bool ROPE>
+__device__ __forceinline__ void state_accumulate(const uint16_t *Kh, const uint16_t *Vh, const float *rope,
+                                                 int64_t stride_n, int t0, int t1, int first_tile, int tile_step,
+                                                 int n_tiles, unsigned char *tileK, unsigned char *tileV, int lane,
+                                                 StateStages<TILE, DEPTH, ROPE> &st, StateAcc &acc)
 {
     static_assert(TILE == 16 || TILE == 32, "tile is one or two MFMA k-steps");
     const int r = lane & 31, g = lane >> 5;
@@ -160,11 +165,12 @@ __device__ __forceinline__ void state_accumulate(const uint16_t *Kh, const uint1
 #pragma unroll
                 for (int i = 0; i < TILE / 8; ++i) {
                     const u32x4 kk = relu_bf16x8(st.k[s][i]);
-                    st.k[s][i] = kk;
                     acc.z[0] += bf16_lo(kk.x);  acc.z[1] += bf16_hi(kk.x);
                     acc.z[2] += bf16_lo(kk.y);  acc.z[3] += bf16_hi(kk.y);
                     acc.z[4] += bf16_lo(kk.z);  acc.z[5] += bf16_hi(kk.z);
                     acc.z[6] += bf16_lo(kk.w);  acc.z[7] += bf16_hi(kk.w);
+                    // the key sum above is never rotated; the keys that meet V are (RoPE after ReLU)
+                    st.k[s][i] = ROPE ? rope_rotate_bf16x8(kk, st.cs[ROPE ? s : 0][i][0], st.cs[ROPE ? s : 0][i][1]) : kk;
                 }
                 wave_lds_fence();   // earlier reads of the tile buffer are done before it is overwritten
 #pragma unroll
@@ -174,8 +180,10 @@ __device__ __forceinline__ void state_accumulate(const uint16_t *Kh, const uint1
                 }
                 // refill this stage: DEPTH tiles ahead
                 const int nxt = tile + DEPTH * tile_step;
-                if (nxt < n_tiles)
+                if (nxt < n_tiles) {
                     state_tile_load<TILE>(Kh, Vh, stride_n, t0 + nxt * TILE, t1, lane, st.k[s], st.v[s]);
+                    if (ROPE) rope_tile_load<TILE>(rope, t0 + nxt * TILE, t1, lane, st.cs[ROPE ? s : 0]);
+                }
                 wave_lds_fence();
 #pragma unroll
                 for (int ks = 0; ks < TILE / 16; ++ks) {
@@ -323,9 +331,11 @@ __host__ __device__ constexpr int state_lds_bytes() {
 // folds one slice of them: S_out, z_out = (S_in, z_in, or 0 if S_in is null) +
 // partials; this needs the whole grid to be resident.
 // Otherwise only the partials are written and state_reduce finishes the job.
-template <int TILE, int WAVES, int DEPTH, bool FINALIZE>
+// ROPE: keys are rotated (table row = token index, d/2 (cos, sin) pairs) before they meet V.
+template <int TILE, int WAVES, int DEPTH, bool FINALIZE, bool ROPE>
 __global__ __launch_bounds__(64 * WAVES, 1) void state_mfma_d64(
-    const uint16_t *__restrict__ K, const uint16_t *__restrict__ V, TokStrides st, int H, int t0, int t1,
+    const uint16_t *__restrict__ K, const uint16_t *__restrict__ V, const float *__restrict__ rope, TokStrides st,
+    int H, int t0, int t1,
     int C, const float *S_in, const float *z_in, float *S_out, float *z_out, void *__restrict__ ws,
     unsigned long long epoch, uint32_t spin_limit)
 {
@@ -343,11 +353,11 @@ __global__ __launch_bounds__(64 * WAVES, 1) void state_mfma_d64(
 
     StateAcc acc;
     acc.clear();
-    StateStages<TILE, DEPTH> stg;
+    StateStages<TILE, DEPTH, ROPE> stg;
     unsigned char *tileK = lds + wave * 2 * kTileBytes;
-    state_prefetch<TILE, DEPTH>(Kh, Vh, st.n, t0, t1, WAVES * c + wave, WAVES * C, n_tiles, lane, stg);
-    state_accumulate<TILE, DEPTH>(Kh, Vh, st.n, t0, t1, WAVES * c + wave, WAVES * C, n_tiles, tileK,
-                                  tileK + kTileBytes, lane, stg, acc);
+    state_prefetch<TILE, DEPTH, ROPE>(Kh, Vh, rope, st.n, t0, t1, WAVES * c + wave, WAVES * C, n_tiles, lane, stg);
+    state_accumulate<TILE, DEPTH, ROPE>(Kh, Vh, rope, st.n, t0, t1, WAVES * c + wave, WAVES * C, n_tiles, tileK,
+                                        tileK + kTileBytes, lane, stg, acc);
 
     float *partials = static_cast<float *>(ws) + (size_t)bh * kMaxChunks * kStateElems;
     state_wg_reduce_store<WAVES>(acc, reinterpret_cast<float *>(lds), wave, lane,

@@ -19,7 +19,7 @@ namespace {
 
 using namespace sv;
 
-constexpr int kVersion = 300;   // 0.3.0
+constexpr int kVersion = 400;   // 0.4.0
 
 // Tuned launch shapes of the bf16 d = 64 kernels (one workgroup per compute unit).
 constexpr int kStateTile = 32, kStateWaves = 4, kStateDepth = 2;
@@ -38,18 +38,42 @@ struct Shape {
 
 struct Device {
     int num_cu = 0;
-    int state_resident_wgs = 0;     // how many state workgroups fit on the device at once
-    int fused_resident_wgs = 0;     // the same for the one-launch block step
+    int state_resident_wgs[2] = {0, 0};   // how many state workgroups fit on the device at once [plain, RoPE]
+    int fused_resident_wgs[2] = {0, 0};   // the same for the one-launch block step
     bool ok = false;
 };
 
-auto *const kStateKernel = state_mfma_d64<kStateTile, kStateWaves, kStateDepth, true>;
-auto *const kStatePartialKernel = state_mfma_d64<kStateTile, kStateWaves, kStateDepth, false>;
-auto *const kApplyKernel = apply_mfma_d64<kApplyHiLo, kApplyWaves, kApplyDepth, kApplyBatch>;
-auto *const kFusedKernel = block_step_mfma_d64<kStateTile, kStateWaves, kStateDepth, kApplyHiLo, kFusedApplyDepth, kApplyBatch>;
-constexpr int kStateLds = state_lds_bytes<kStateTile, kStateWaves>();
-constexpr int kApplyLds = apply_lds_bytes<kApplyWaves, kApplyBatch>();
-constexpr int kFusedLds = block_step_lds_bytes<kStateTile, kStateWaves, kApplyBatch>();
+// The kernels in use, with and without RoPE (index 1: rotation table given).
+template <bool ROPE> struct Kernels {
+    static constexpr auto state = state_mfma_d64<kStateTile, kStateWaves, kStateDepth, true, ROPE>;
+    static constexpr auto state_partial = state_mfma_d64<kStateTile, kStateWaves, kStateDepth, false, ROPE>;
+    static constexpr auto apply = apply_mfma_d64<kApplyHiLo, kApplyWaves, kApplyDepth, kApplyBatch, ROPE>;
+    static constexpr auto fused =
+        block_step_mfma_d64<kStateTile, kStateWaves, kStateDepth, kApplyHiLo, kFusedApplyDepth, kApplyBatch, ROPE>;
+    static constexpr int state_lds = state_lds_bytes<kStateTile, kStateWaves>();
+    static constexpr int apply_lds = apply_lds_bytes<kApplyWaves, kApplyBatch, ROPE>();
+    static constexpr int fused_lds = block_step_lds_bytes<kStateTile, kStateWaves, kApplyBatch, ROPE>();
+};
+
+template <bool ROPE> void init_kernels(Device &d)
+{
+    using KN = Kernels<ROPE>;
+    const auto attr = hipFuncAttributeMaxDynamicSharedMemorySize;
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(KN::state), attr, KN::state_lds);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(KN::state_partial), attr, KN::state_lds);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(KN::apply), attr, KN::apply_lds);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(KN::fused), attr, KN::fused_lds);
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(KN::fused),
+                                                     64 * kStateWaves, KN::fused_lds) != hipSuccess)
+        per_cu = 0;
+    d.fused_resident_wgs[ROPE] = per_cu * d.num_cu;
+    per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(KN::state),
+                                                     64 * kStateWaves, KN::state_lds) != hipSuccess)
+        per_cu = 0;
+    d.state_resident_wgs[ROPE] = per_cu * d.num_cu;
+}
 
 // Per-device facts, queried once (no device memory is touched).
 const Device &device_info()
@@ -67,24 +91,8 @@ const Device &device_info()
         hipDeviceProp_t prop;
         if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return d;
         d.num_cu = prop.multiProcessorCount;
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kStateKernel),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, kStateLds);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kStatePartialKernel),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, kStateLds);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kApplyKernel),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, kApplyLds);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kFusedKernel),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, kFusedLds);
-        int per_cu = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(kFusedKernel),
-                                                         64 * kStateWaves, kFusedLds) != hipSuccess)
-            per_cu = 0;
-        d.fused_resident_wgs = per_cu * d.num_cu;
-        per_cu = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(kStateKernel),
-                                                         64 * kStateWaves, kStateLds) != hipSuccess)
-            per_cu = 0;
-        d.state_resident_wgs = per_cu * d.num_cu;
+        init_kernels<false>(d);
+        init_kernels<true>(d);
         (void)hipGetLastError();
         d.ok = d.num_cu > 0;
     }
@@ -148,9 +156,28 @@ sv_status launch_status() { return hipGetLastError() == hipSuccess ? SV_OK : SV_
 bool eps_ok(float eps) { return isfinite(eps) && eps >= 0.f; }
 
 // S_out, z_out = (S_in, z_in, or 0 when S_in is null) + state of tokens [t0,t1).  S_in may equal S_out.
-// All arguments are already validated.
-sv_status enqueue_state(const void *K, const void *V, const Shape &s, int t0, int t1, const float *S_in,
-                        const float *z_in, float *S_out, float *z_out, void *ws, hipStream_t stream)
+// rope: rotation table or null.  All arguments are already validated.
+template <bool ROPE>
+void launch_state_mfma(const uint16_t *k, const uint16_t *v, const float *rope, const Shape &s, int t0, int t1, int C,
+                       const float *S_in, const float *z_in, float *S_out, float *z_out, void *ws, const Device &dev,
+                       dim3 rgrid, hipStream_t stream)
+{
+    using KN = Kernels<ROPE>;
+    if ((int64_t)C * s.BH <= dev.state_resident_wgs[ROPE]) {
+        // the head's workgroups wait for each other inside the kernel: all must be resident
+        KN::state<<<dim3(C, s.BH), 64 * kStateWaves, KN::state_lds, stream>>>(
+            k, v, rope, s.st, s.H, t0, t1, C, S_in, z_in, S_out, z_out, ws, next_epoch(), kSpinLimit);
+    } else {
+        KN::state_partial<<<dim3(C, s.BH), 64 * kStateWaves, KN::state_lds, stream>>>(
+            k, v, rope, s.st, s.H, t0, t1, C, S_in, z_in, S_out, z_out, ws, 0ull, 0u);
+        state_reduce<64><<<rgrid, kThreads, 0, stream>>>(static_cast<float *>(ws), C, kMaxChunks, S_in, z_in, S_out,
+                                                        z_out);
+    }
+}
+
+sv_status enqueue_state(const void *K, const void *V, const float *rope, const Shape &s, int t0, int t1,
+                        const float *S_in, const float *z_in, float *S_out, float *z_out, void *ws,
+                        hipStream_t stream)
 {
     const int n = t1 - t0;
     if (n == 0 && S_in == S_out) return SV_OK;
@@ -168,15 +195,8 @@ sv_status enqueue_state(const void *K, const void *V, const Shape &s, int t0, in
         const int C = plan_chunks(s.BH, n, kStateTile * kStateWaves, dev.num_cu);
         auto *k = static_cast<const uint16_t *>(K);
         auto *v = static_cast<const uint16_t *>(V);
-        if ((int64_t)C * s.BH <= dev.state_resident_wgs) {
-            // the head's workgroups wait for each other inside the kernel: all must be resident
-            kStateKernel<<<dim3(C, s.BH), 64 * kStateWaves, kStateLds, stream>>>(
-                k, v, s.st, s.H, t0, t1, C, S_in, z_in, S_out, z_out, ws, next_epoch(), kSpinLimit);
-        } else {
-            kStatePartialKernel<<<dim3(C, s.BH), 64 * kStateWaves, kStateLds, stream>>>(
-                k, v, s.st, s.H, t0, t1, C, S_in, z_in, S_out, z_out, ws, 0ull, 0u);
-            state_reduce<64><<<rgrid, kThreads, 0, stream>>>(wsf, C, kMaxChunks, S_in, z_in, S_out, z_out);
-        }
+        if (rope) launch_state_mfma<true>(k, v, rope, s, t0, t1, C, S_in, z_in, S_out, z_out, ws, dev, rgrid, stream);
+        else launch_state_mfma<false>(k, v, rope, s, t0, t1, C, S_in, z_in, S_out, z_out, ws, dev, rgrid, stream);
         return launch_status();
     }
     // fp32 validation mode and bf16 d = 32: plain-FMA partials, then the fixed-order reduction
@@ -184,21 +204,21 @@ sv_status enqueue_state(const void *K, const void *V, const Shape &s, int t0, in
     const dim3 grid(C, s.BH);
     if (s.bf16) {
         state_partial_generic<uint16_t, 32><<<grid, kThreads, 0, stream>>>(
-            static_cast<const uint16_t *>(K), static_cast<const uint16_t *>(V), s.st, s.H, t0, t1, C, wsf);
+            static_cast<const uint16_t *>(K), static_cast<const uint16_t *>(V), rope, s.st, s.H, t0, t1, C, wsf);
     } else if (s.d == 64) {
         state_partial_generic<float, 64><<<grid, kThreads, 0, stream>>>(
-            static_cast<const float *>(K), static_cast<const float *>(V), s.st, s.H, t0, t1, C, wsf);
+            static_cast<const float *>(K), static_cast<const float *>(V), rope, s.st, s.H, t0, t1, C, wsf);
     } else {
         state_partial_generic<float, 32><<<grid, kThreads, 0, stream>>>(
-            static_cast<const float *>(K), static_cast<const float *>(V), s.st, s.H, t0, t1, C, wsf);
+            static_cast<const float *>(K), static_cast<const float *>(V), rope, s.st, s.H, t0, t1, C, wsf);
     }
     if (s.d == 64) state_reduce<64><<<rgrid, kThreads, 0, stream>>>(wsf, C, C, S_in, z_in, S_out, z_out);
     else state_reduce<32><<<rgrid, kThreads, 0, stream>>>(wsf, C, C, S_in, z_in, S_out, z_out);
     return launch_status();
 }
 
-sv_status enqueue_apply(const void *Q, const Shape &s, int t0, int t1, const float *S, const float *z, float eps,
-                        void *O, hipStream_t stream)
+sv_status enqueue_apply(const void *Q, const float *rope, const Shape &s, int t0, int t1, const float *S,
+                        const float *z, float eps, void *O, hipStream_t stream)
 {
     const int n = t1 - t0;
     if (n == 0) return SV_OK;
@@ -209,8 +229,14 @@ sv_status enqueue_apply(const void *Q, const Shape &s, int t0, int t1, const flo
         const int steps = (n + kApplyTile * kApplyWaves - 1) / (kApplyTile * kApplyWaves);
         if (C > steps) C = steps;
         if (C < 1) C = 1;
-        kApplyKernel<<<dim3(C, s.BH), 64 * kApplyWaves, kApplyLds, stream>>>(
-            static_cast<const uint16_t *>(Q), static_cast<uint16_t *>(O), s.st, s.H, t0, t1, C, S, z, eps);
+        auto *q = static_cast<const uint16_t *>(Q);
+        auto *o = static_cast<uint16_t *>(O);
+        if (rope)
+            Kernels<true>::apply<<<dim3(C, s.BH), 64 * kApplyWaves, Kernels<true>::apply_lds, stream>>>(
+                q, o, rope, s.st, s.H, t0, t1, C, S, z, eps);
+        else
+            Kernels<false>::apply<<<dim3(C, s.BH), 64 * kApplyWaves, Kernels<false>::apply_lds, stream>>>(
+                q, o, rope, s.st, s.H, t0, t1, C, S, z, eps);
         return launch_status();
     }
     const int tile = kThreads / (s.d / 4);          // generic tiles: 256 threads / (d/4 threads per token)
@@ -220,16 +246,93 @@ sv_status enqueue_apply(const void *Q, const Shape &s, int t0, int t1, const flo
     const dim3 grid(C, s.BH);
     if (s.bf16) {
         apply_generic<uint16_t, 32><<<grid, kThreads, 0, stream>>>(static_cast<const uint16_t *>(Q),
-                                                                  static_cast<uint16_t *>(O), s.st, s.H, t0, t1, C, S,
-                                                                  z, eps);
+                                                                  static_cast<uint16_t *>(O), rope, s.st, s.H, t0, t1,
+                                                                  C, S, z, eps);
     } else if (s.d == 64) {
         apply_generic<float, 64><<<grid, kThreads, 0, stream>>>(static_cast<const float *>(Q), static_cast<float *>(O),
-                                                               s.st, s.H, t0, t1, C, S, z, eps);
+                                                               rope, s.st, s.H, t0, t1, C, S, z, eps);
     } else {
         apply_generic<float, 32><<<grid, kThreads, 0, stream>>>(static_cast<const float *>(Q), static_cast<float *>(O),
-                                                               s.st, s.H, t0, t1, C, S, z, eps);
+                                                               rope, s.st, s.H, t0, t1, C, S, z, eps);
     }
     return launch_status();
+}
+
+// ---- bodies shared by the plain and the RoPE entry points (rope may be null) -------------------------------
+
+sv_status do_state(const void *K, const void *V, const sv_tensor_desc *kv, const float *rope, bool want_rope,
+                   int32_t tok_begin, int32_t tok_end, int accumulate, float *S, float *z, void *workspace,
+                   size_t workspace_bytes_given, void *stream)
+{
+    if (!K || !V || !S || !z || !workspace || (want_rope && !rope)) return SV_ERR_NULL;
+    Shape s;
+    sv_status rc = check_desc(kv, &s);
+    if (rc != SV_OK) return rc;
+    if ((rc = check_range(s, tok_begin, tok_end)) != SV_OK) return rc;
+    if (!aligned16(K) || !aligned16(V) || !aligned16(S) || !aligned16(z) || !aligned16(workspace) || !aligned16(rope))
+        return SV_ERR_ALIGN;
+    if (workspace_bytes_given < workspace_bytes(s.BH, s.d)) return SV_ERR_WORKSPACE;
+    return enqueue_state(K, V, rope, s, tok_begin, tok_end, accumulate ? S : nullptr, z, S, z, workspace,
+                         static_cast<hipStream_t>(stream));
+}
+
+sv_status do_apply(const void *Q, const sv_tensor_desc *q, const float *rope, bool want_rope, int32_t tok_begin,
+                   int32_t tok_end, const float *S, const float *z, float eps, void *O, void *stream)
+{
+    if (!Q || !S || !z || !O || (want_rope && !rope)) return SV_ERR_NULL;
+    Shape s;
+    sv_status rc = check_desc(q, &s);
+    if (rc != SV_OK) return rc;
+    if ((rc = check_range(s, tok_begin, tok_end)) != SV_OK) return rc;
+    if (!eps_ok(eps)) return SV_ERR_RANGE;
+    if (!aligned16(Q) || !aligned16(O) || !aligned16(S) || !aligned16(z) || !aligned16(rope)) return SV_ERR_ALIGN;
+    return enqueue_apply(Q, rope, s, tok_begin, tok_end, S, z, eps, O, static_cast<hipStream_t>(stream));
+}
+
+// The committing and the look-ahead block step: the updated state goes to S_out, z_out.
+sv_status do_block_step(const void *Qb, const void *Kb, const void *Vb, const sv_tensor_desc *blk, const float *rope,
+                        bool want_rope, const float *S_in, const float *z_in, float *S_out, float *z_out,
+                        bool lookahead, float eps, void *Ob, void *workspace, size_t workspace_bytes_given,
+                        void *stream)
+{
+    if (!Qb || !Kb || !Vb || !S_in || !z_in || !Ob || !workspace || (want_rope && !rope)) return SV_ERR_NULL;
+    Shape s;
+    sv_status rc = check_desc(blk, &s);
+    if (rc != SV_OK) return rc;
+    if (!eps_ok(eps)) return SV_ERR_RANGE;
+    if (!aligned16(Qb) || !aligned16(Kb) || !aligned16(Vb) || !aligned16(Ob) || !aligned16(S_in) ||
+        !aligned16(z_in) || !aligned16(workspace) || !aligned16(rope))
+        return SV_ERR_ALIGN;
+    if (workspace_bytes_given < workspace_bytes(s.BH, s.d)) return SV_ERR_WORKSPACE;
+    if (lookahead) {                                 // the updated state lives in the workspace only
+        S_out = ws_lookahead(workspace, s.BH, s.d * s.d + s.d);
+        z_out = S_out + (size_t)s.BH * s.d * s.d;
+    }
+    auto hs = static_cast<hipStream_t>(stream);
+    if (s.bf16 && s.d == 64) {
+        const Device &dev = device_info();
+        if (!dev.ok) return SV_ERR_LAUNCH;
+        // One launch when the whole grid can be resident at once (needed by the in-kernel waits).
+        const int C = plan_chunks(s.BH, s.N, kStateTile * kStateWaves, dev.num_cu);
+        if ((int64_t)C * s.BH <= dev.fused_resident_wgs[rope ? 1 : 0]) {
+            auto *q = static_cast<const uint16_t *>(Qb);
+            auto *k = static_cast<const uint16_t *>(Kb);
+            auto *v = static_cast<const uint16_t *>(Vb);
+            auto *o = static_cast<uint16_t *>(Ob);
+            if (rope)
+                Kernels<true>::fused<<<dim3(C, s.BH), 64 * kStateWaves, Kernels<true>::fused_lds, hs>>>(
+                    q, k, v, o, rope, s.st, s.H, s.N, C, S_in, z_in, S_out, z_out, eps, workspace, next_epoch(),
+                    kSpinLimit);
+            else
+                Kernels<false>::fused<<<dim3(C, s.BH), 64 * kStateWaves, Kernels<false>::fused_lds, hs>>>(
+                    q, k, v, o, rope, s.st, s.H, s.N, C, S_in, z_in, S_out, z_out, eps, workspace, next_epoch(),
+                    kSpinLimit);
+            return launch_status();
+        }
+    }
+    rc = enqueue_state(Kb, Vb, rope, s, 0, s.N, S_in, z_in, S_out, z_out, workspace, hs);
+    if (rc != SV_OK) return rc;
+    return enqueue_apply(Qb, rope, s, 0, s.N, S_out, z_out, eps, Ob, hs);
 }
 
 }  // namespace
@@ -247,81 +350,60 @@ sv_status sv_linattn_state(const void *K, const void *V, const sv_tensor_desc *k
                            int32_t tok_end, int accumulate, float *S, float *z, void *workspace,
                            size_t workspace_bytes_given, void *stream)
 {
-    if (!K || !V || !S || !z || !workspace) return SV_ERR_NULL;
-    Shape s;
-    sv_status rc = check_desc(kv, &s);
-    if (rc != SV_OK) return rc;
-    if ((rc = check_range(s, tok_begin, tok_end)) != SV_OK) return rc;
-    if (!aligned16(K) || !aligned16(V) || !aligned16(S) || !aligned16(z) || !aligned16(workspace))
-        return SV_ERR_ALIGN;
-    if (workspace_bytes_given < workspace_bytes(s.BH, s.d)) return SV_ERR_WORKSPACE;
-    return enqueue_state(K, V, s, tok_begin, tok_end, accumulate ? S : nullptr, z, S, z, workspace,
-                         static_cast<hipStream_t>(stream));
+    return do_state(K, V, kv, nullptr, false, tok_begin, tok_end, accumulate, S, z, workspace,
+                    workspace_bytes_given, stream);
 }
 
 sv_status sv_linattn_apply(const void *Q, const sv_tensor_desc *q, int32_t tok_begin, int32_t tok_end,
                            const float *S, const float *z, float eps, void *O, void *stream)
 {
-    if (!Q || !S || !z || !O) return SV_ERR_NULL;
-    Shape s;
-    sv_status rc = check_desc(q, &s);
-    if (rc != SV_OK) return rc;
-    if ((rc = check_range(s, tok_begin, tok_end)) != SV_OK) return rc;
-    if (!eps_ok(eps)) return SV_ERR_RANGE;
-    if (!aligned16(Q) || !aligned16(O) || !aligned16(S) || !aligned16(z)) return SV_ERR_ALIGN;
-    return enqueue_apply(Q, s, tok_begin, tok_end, S, z, eps, O, static_cast<hipStream_t>(stream));
-}
-
-// Shared body of the committing and the look-ahead block step: the updated state goes to S_out, z_out.
-static sv_status block_step(const void *Qb, const void *Kb, const void *Vb, const sv_tensor_desc *blk, const float *S_in,
-                            const float *z_in, float *S_out, float *z_out, bool lookahead, float eps, void *Ob,
-                            void *workspace, size_t workspace_bytes_given, void *stream)
-{
-    if (!Qb || !Kb || !Vb || !S_in || !z_in || !Ob || !workspace) return SV_ERR_NULL;
-    Shape s;
-    sv_status rc = check_desc(blk, &s);
-    if (rc != SV_OK) return rc;
-    if (!eps_ok(eps)) return SV_ERR_RANGE;
-    if (!aligned16(Qb) || !aligned16(Kb) || !aligned16(Vb) || !aligned16(Ob) || !aligned16(S_in) ||
-        !aligned16(z_in) || !aligned16(workspace))
-        return SV_ERR_ALIGN;
-    if (workspace_bytes_given < workspace_bytes(s.BH, s.d)) return SV_ERR_WORKSPACE;
-    if (lookahead) {                                 // the updated state lives in the workspace only
-        S_out = ws_lookahead(workspace, s.BH, s.d * s.d + s.d);
-        z_out = S_out + (size_t)s.BH * s.d * s.d;
-    }
-    auto hs = static_cast<hipStream_t>(stream);
-    if (s.bf16 && s.d == 64) {
-        const Device &dev = device_info();
-        if (!dev.ok) return SV_ERR_LAUNCH;
-        // One launch when the whole grid can be resident at once (needed by the in-kernel waits).
-        const int C = plan_chunks(s.BH, s.N, kStateTile * kStateWaves, dev.num_cu);
-        if ((int64_t)C * s.BH <= dev.fused_resident_wgs) {
-            kFusedKernel<<<dim3(C, s.BH), 64 * kStateWaves, kFusedLds, hs>>>(
-                static_cast<const uint16_t *>(Qb), static_cast<const uint16_t *>(Kb),
-                static_cast<const uint16_t *>(Vb), static_cast<uint16_t *>(Ob), s.st, s.H, s.N, C, S_in, z_in, S_out,
-                z_out, eps, workspace, next_epoch(), kSpinLimit);
-            return launch_status();
-        }
-    }
-    rc = enqueue_state(Kb, Vb, s, 0, s.N, S_in, z_in, S_out, z_out, workspace, hs);
-    if (rc != SV_OK) return rc;
-    return enqueue_apply(Qb, s, 0, s.N, S_out, z_out, eps, Ob, hs);
+    return do_apply(Q, q, nullptr, false, tok_begin, tok_end, S, z, eps, O, stream);
 }
 
 sv_status sv_block_linattn_step(const void *Qb, const void *Kb, const void *Vb, const sv_tensor_desc *blk, float *S,
                                 float *z, float eps, void *Ob, void *workspace, size_t workspace_bytes_given,
                                 void *stream)
 {
-    return block_step(Qb, Kb, Vb, blk, S, z, S, z, false, eps, Ob, workspace, workspace_bytes_given, stream);
+    return do_block_step(Qb, Kb, Vb, blk, nullptr, false, S, z, S, z, false, eps, Ob, workspace,
+                         workspace_bytes_given, stream);
 }
 
 sv_status sv_block_linattn_lookahead(const void *Qb, const void *Kb, const void *Vb, const sv_tensor_desc *blk,
                                      const float *S, const float *z, float eps, void *Ob, void *workspace,
                                      size_t workspace_bytes_given, void *stream)
 {
-    return block_step(Qb, Kb, Vb, blk, S, z, nullptr, nullptr, true, eps, Ob, workspace, workspace_bytes_given,
-                      stream);
+    return do_block_step(Qb, Kb, Vb, blk, nullptr, false, S, z, nullptr, nullptr, true, eps, Ob, workspace,
+                         workspace_bytes_given, stream);
+}
+
+sv_status sv_linattn_state_rope(const void *K, const void *V, const sv_tensor_desc *kv, const float *rope,
+                                int32_t tok_begin, int32_t tok_end, int accumulate, float *S, float *z,
+                                void *workspace, size_t workspace_bytes_given, void *stream)
+{
+    return do_state(K, V, kv, rope, true, tok_begin, tok_end, accumulate, S, z, workspace, workspace_bytes_given,
+                    stream);
+}
+
+sv_status sv_linattn_apply_rope(const void *Q, const sv_tensor_desc *q, const float *rope, int32_t tok_begin,
+                                int32_t tok_end, const float *S, const float *z, float eps, void *O, void *stream)
+{
+    return do_apply(Q, q, rope, true, tok_begin, tok_end, S, z, eps, O, stream);
+}
+
+sv_status sv_block_linattn_step_rope(const void *Qb, const void *Kb, const void *Vb, const sv_tensor_desc *blk,
+                                     const float *rope, float *S, float *z, float eps, void *Ob, void *workspace,
+                                     size_t workspace_bytes_given, void *stream)
+{
+    return do_block_step(Qb, Kb, Vb, blk, rope, true, S, z, S, z, false, eps, Ob, workspace, workspace_bytes_given,
+                         stream);
+}
+
+sv_status sv_block_linattn_lookahead_rope(const void *Qb, const void *Kb, const void *Vb, const sv_tensor_desc *blk,
+                                          const float *rope, const float *S, const float *z, float eps, void *Ob,
+                                          void *workspace, size_t workspace_bytes_given, void *stream)
+{
+    return do_block_step(Qb, Kb, Vb, blk, rope, true, S, z, nullptr, nullptr, true, eps, Ob, workspace,
+                         workspace_bytes_given, stream);
 }
 
 const char *sv_status_string(int status)

@@ -108,3 +108,22 @@ def test_product_path_does_not_import_the_oracle():
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.lower(), f
     assert binding.load_library() is not None
+
+
+def test_rope_entry_points_check_arguments():
+    d = _desc()
+    big = 1 << 30
+    with pytest.raises(sv.SvError) as e:      # table is required
+        sv.sv_linattn_state_rope(FAKE, FAKE, d, None, 0, 1, 0, FAKE, FAKE, FAKE, workspace_bytes=big)
+    assert e.value.status == 1
+    with pytest.raises(sv.SvError) as e:      # and must be 16-byte aligned
+        sv.sv_linattn_apply_rope(FAKE, d, FAKE + 4, 0, 1, FAKE, FAKE, 1e-6, FAKE)
+    assert e.value.status == 4
+    with pytest.raises(sv.SvError) as e:
+        sv.sv_block_linattn_step_rope(FAKE, FAKE, FAKE, _desc(d=48), FAKE, FAKE, FAKE, 1e-6, FAKE, FAKE,
+                                      workspace_bytes=big)
+    assert e.value.status == 3
+    with pytest.raises(sv.SvError) as e:
+        sv.sv_block_linattn_lookahead_rope(FAKE, FAKE, FAKE, d, FAKE, FAKE, FAKE, -1.0, FAKE, FAKE,
+                                           workspace_bytes=big)
+    assert e.value.status == 5
