@@ -49,6 +49,7 @@ def _parse():
     ap.add_argument("--sets", type=int, default=0, help="rotating buffer sets (0 = enough for > 1.5 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-block-stream", action="store_true")
+    ap.add_argument("--no-rope", action="store_true", help="skip the RoPE-variant timings")
     ap.add_argument("--stream-blocks", type=int, default=80)
     ap.add_argument("--calibration-copy", type=int, default=0,
                     help="also run this many plain device copies of one token tensor (known size: "
@@ -61,16 +62,24 @@ def _randn_bf16(shape, gen):
     return (torch.randn(shape, device="cuda", dtype=torch.float32, generator=gen) * 0.5).to(torch.bfloat16)
 
 
-def bench_bidirectional(w, steps, warmup, n_sets, sv, torch):
+def _rope_table(w, torch, t0=0):
+    import sv_workloads as wl
+    return torch.from_numpy(wl.rope_table_3d(*w.grid, w.d, t0=t0)).cuda()
+
+
+def bench_bidirectional(w, steps, warmup, n_sets, sv, torch, rope=None, sets=None):
+    """`rope`: device table -> the RoPE entry points are timed instead of the plain ones."""
     B, H, N, d = w.B, w.H, w.N, w.d
     gen = torch.Generator(device="cuda")
     gen.manual_seed(w.seed)
     if n_sets <= 0:
         n_sets = max(2, -(-int(1.5e9) // w.algorithmic_bytes))
-    sets = []
-    for _ in range(n_sets):
-        q, k, v = (_randn_bf16((B, H, N, d), gen) for _ in range(3))
-        sets.append((q, k, v, torch.empty_like(q)))
+    if sets is None:
+        sets = []
+        for _ in range(n_sets):
+            q, k, v = (_randn_bf16((B, H, N, d), gen) for _ in range(3))
+            sets.append((q, k, v, torch.empty_like(q)))
+    n_sets = len(sets)
     S = torch.empty((B, H, d, d), dtype=torch.float32, device="cuda")
     z = torch.empty((B, H, d), dtype=torch.float32, device="cuda")
     ws = torch.empty(sv.sv_linattn_workspace_bytes(B, H, N, d), dtype=torch.uint8, device="cuda")
@@ -81,10 +90,16 @@ def bench_bidirectional(w, steps, warmup, n_sets, sv, torch):
         q, k, v, o = sets[i % n_sets]
         if ev:
             ev[0].record(stream)
-        sv.sv_linattn_state(k, v, dsc, 0, N, 0, S, z, ws, stream=stream)
+        if rope is None:
+            sv.sv_linattn_state(k, v, dsc, 0, N, 0, S, z, ws, stream=stream)
+        else:
+            sv.sv_linattn_state_rope(k, v, dsc, rope, 0, N, 0, S, z, ws, stream=stream)
         if ev:
             ev[1].record(stream)
-        sv.sv_linattn_apply(q, dsc, 0, N, S, z, w.eps, o, stream=stream)
+        if rope is None:
+            sv.sv_linattn_apply(q, dsc, 0, N, S, z, w.eps, o, stream=stream)
+        else:
+            sv.sv_linattn_apply_rope(q, dsc, rope, 0, N, S, z, w.eps, o, stream=stream)
         if ev:
             ev[2].record(stream)
 
@@ -115,8 +130,9 @@ def bench_bidirectional(w, steps, warmup, n_sets, sv, torch):
     }
 
 
-def bench_block_stream(w, n_blocks, sv, torch):
-    """Whole stream enqueued back to back, one event pair per block; no host sync inside."""
+def bench_block_stream(w, n_blocks, sv, torch, rope=False):
+    """Whole stream enqueued back to back, one event pair per block; no host sync inside.
+    `rope`: time sv_block_linattn_step_rope with one table per block (time axis continuing)."""
     B, H, N, d = w.B, w.H, w.N, w.d
     gen = torch.Generator(device="cuda")
     gen.manual_seed(w.seed)
@@ -130,14 +146,22 @@ def bench_block_stream(w, n_blocks, sv, torch):
     lib_bytes = S.numel() * 4 + z.numel() * 4 + ws.numel()
     dsc = sv.desc_of(blocks[0][0])
     stream = torch.cuda.current_stream()
+    tables = [_rope_table(w, torch, t0=m * w.grid[0]) for m in range(n_blocks)] if rope else None
+
+    def one(m):
+        q, k, v, o = blocks[m]
+        if tables is None:
+            sv.sv_block_linattn_step(q, k, v, dsc, S, z, w.eps, o, ws, stream=stream)
+        else:
+            sv.sv_block_linattn_step_rope(q, k, v, dsc, tables[m], S, z, w.eps, o, ws, stream=stream)
 
     def run(events=None):
         S.zero_()
         z.zero_()
-        for m, (q, k, v, o) in enumerate(blocks):
+        for m in range(n_blocks):
             if events:
                 events[m][0].record(stream)
-            sv.sv_block_linattn_step(q, k, v, dsc, S, z, w.eps, o, ws, stream=stream)
+            one(m)
             if events:
                 events[m][1].record(stream)
 
@@ -151,8 +175,8 @@ def bench_block_stream(w, n_blocks, sv, torch):
     z.zero_()
     torch.cuda.synchronize()
     a.record(stream)
-    for (q, k, v, o) in blocks:
-        sv.sv_block_linattn_step(q, k, v, dsc, S, z, w.eps, o, ws, stream=stream)
+    for m in range(n_blocks):
+        one(m)
     b.record(stream)
     torch.cuda.synchronize()
     stream_ms = a.elapsed_time(b)
@@ -170,7 +194,7 @@ def bench_block_stream(w, n_blocks, sv, torch):
              if len(tail) > 1 else 0.0)
     per_block_us = stream_ms * 1e3 / n_blocks
     return {
-        "workload": w.name, "blocks": n_blocks, "tokens_per_block": N,
+        "workload": w.name, "rope": bool(rope), "blocks": n_blocks, "tokens_per_block": N,
         "us_per_block_stream": per_block_us,
         "tokens_per_s": B * N / (per_block_us * 1e-6),
         "hbm_GBps": w.algorithmic_bytes / (per_block_us * 1e-6) / 1e9,
@@ -252,11 +276,26 @@ def main():
         torch.cuda.synchronize()
         out["calibration_copy"] = {"copies": args.calibration_copy, "bytes_read_each": src.numel() * 2,
                                    "bytes_written_each": src.numel() * 2}
+    if not args.no_rope:
+        # the same layer through the RoPE entry points (full equation of Sec. 3.2); the table
+        # [N][d/2][2] fp32 is extra traffic (N*d*4 bytes per kernel, shared by the heads through L2)
+        rr = bench_bidirectional(w, args.steps, args.warmup, 0, sv, torch, rope=_rope_table(w, torch),
+                                 sets=r["sets"])
+        out["rope_variant"] = {
+            "ms_per_step": rr["ms_per_step"], "tokens_per_s": w.B * w.N / (rr["ms_per_step"] * 1e-3),
+            "hbm_frac_step": w.algorithmic_bytes / (rr["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "kernels_ms": {"state": rr["ms_state"], "apply": rr["ms_apply"]},
+        }
     if not args.no_block_stream:
         out["block_stream"] = [
             bench_block_stream(wl.workload("block_480p"), 10, sv, torch),
             bench_block_stream(wl.workload("stream_720p"), args.stream_blocks, sv, torch),
         ]
+        if not args.no_rope:
+            out["block_stream"] += [
+                bench_block_stream(wl.workload("block_480p"), 10, sv, torch, rope=True),
+                bench_block_stream(wl.workload("stream_720p"), args.stream_blocks, sv, torch, rope=True),
+            ]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, r["sets"], torch)
     print(json.dumps(out))

@@ -19,7 +19,10 @@
 // token row.  Q tiles come in with coalesced non-temporal 16-byte loads and
 // pass through a wave-private LDS tile to reach that layout; O tiles go back
 // through the same tile so that stores are coalesced too.  No workgroup
-// barrier is needed anywhere.
+// barrier is needed anywhere.  On this hardware loads and stores share one
+// in-order completion counter, and every stage issues a fixed number of both, so
+// a tile waits only for its own loads: the stores of earlier tiles and the loads
+// of later ones stay in flight.
 #pragma once
 
 #include "common.hpp"
@@ -29,19 +32,6 @@
 namespace sv {
 
 constexpr int kApplyTile = 32;   // tokens per wave tile (the N dimension of the 32x32x16 MFMA)
-
-__device__ __forceinline__ void apply_tile_load(const uint16_t *Qh, int64_t stride_n, int tok0, int t1, int lane,
-                                                u32x4 (&qreg)[kApplyTile / 8])
-{
-    const int col = lane & 7;
-#pragma unroll
-    for (int i = 0; i < kApplyTile / 8; ++i) {
-        const int tok = tok0 + (lane >> 3) + 8 * i;
-        u32x4 q = {0u, 0u, 0u, 0u};
-        if (tok < t1) q = load_stream16(Qh + (int64_t)tok * stride_n + col * 8);
-        qreg[i] = q;
-    }
-}
 
 // The state of one head as MFMA A operands, per lane (m = lane%32, g = lane/32).
 //   S rows: MFMA row m of row block rb stands for output feature
@@ -111,189 +101,170 @@ struct ApplyOperands {
     }
 };
 
-// One wave's share of the token range [t0, t1): tiles first_tile, first_tile +
-// tile_step, ... below n_tiles (32 tokens each).  `tileQ` is this wave's private
-// LDS tile (kApplyTile * kRowBytes bytes).  `qreg` holds the first DEPTH tiles,
-// already requested by the caller with apply_prefetch (stages FROM..TO-1 per call).
-template <int DEPTH, int FROM = 0, int TO = DEPTH>
-__device__ __forceinline__ void apply_prefetch(const uint16_t *Qh, int64_t stride_n, int t0, int t1, int first_tile,
-                                               int tile_step, int n_tiles, int lane,
-                                               u32x4 (&qreg)[DEPTH][kApplyTile / 8])
+// One wave's token stream: buffer resources over the head's Q and O rows (and the
+// rotation table) below the end of the token range, the wave's tile walk (32
+// tokens per tile), and the register staging of DEPTH tiles in flight.
+template <int DEPTH, bool ROPE>
+struct ApplyStream {
+    rsrc_t rQ, rO, rT;
+    uint32_t row_bytes;
+    TileWalk walk;
+    u32x4 q[DEPTH][kApplyTile / 8];
+    f32x4 cs[ROPE ? DEPTH : 1][kApplyTile / 8][2];
+
+    __device__ __forceinline__ ApplyStream(const uint16_t *Qh, uint16_t *Oh, const float *rope, int64_t stride_n,
+                                           int t1, const TileWalk &w)
+        : rQ(make_rsrc(Qh, (uint32_t)t1 * (uint32_t)stride_n * 2u)),
+          rO(make_rsrc(Oh, (uint32_t)t1 * (uint32_t)stride_n * 2u)),
+          rT(make_rsrc(rope, ROPE ? (uint32_t)t1 * 256u : 0u)), row_bytes((uint32_t)stride_n * 2u), walk(w) {}
+
+    // Requests the wave's i-th tile into stage s; past the share nothing is read.
+    __device__ __forceinline__ void request(int s, int i, int lane)
+    {
+        token_tile_load<kApplyTile>(rQ, walk.offset<kApplyTile>(i, row_bytes), row_bytes, lane, q[s]);
+        if (ROPE) rope_tile_load<kApplyTile>(rT, walk.offset<kApplyTile>(i, 256u), lane, cs[ROPE ? s : 0]);
+    }
+};
+
+// Requests tiles FROM .. TO-1 of the wave's share into the stages of the same numbers.
+template <int FROM, int TO, int DEPTH, bool ROPE>
+__device__ __forceinline__ void apply_prefetch(ApplyStream<DEPTH, ROPE> &st, int lane)
 {
 #pragma unroll
     for (int s = FROM; s < TO; ++s) {
-        const int t = first_tile + s * tile_step;
-        if (t < n_tiles) apply_tile_load(Qh, stride_n, t0 + t * kApplyTile, t1, lane, qreg[s]);
+        st.request(s, s, lane);
+        __builtin_amdgcn_sched_barrier(0);   // requests go out in stage order, as they do in the loop
     }
 }
 
-// ROPE: the numerator uses queries rotated after the ReLU (table row = token index); the
-// denominator keeps the plain ones.  The wave's LDS region then holds a second,
-// rotated copy of each tile after the NB plain ones, and `rope` is the table.
-template <bool HILO, int DEPTH, int NB, bool ROPE>
-__device__ __forceinline__ void apply_tiles(const uint16_t *Qh, uint16_t *Oh, const float *rope, int64_t stride_n,
-                                            int t0, int t1, int first_tile, int tile_step, int n_tiles,
-                                            unsigned char *tileQ, int lane, const ApplyOperands<HILO> &A, float eps,
-                                            u32x4 (&qreg)[DEPTH][kApplyTile / 8])
+// Applies the state in `A` to the wave's share, whose first DEPTH tiles
+// apply_prefetch has requested.  `tileQ` is this wave's private LDS region: one
+// tile of kApplyTile * kRowBytes bytes, two with ROPE (the numerator then uses
+// queries rotated after the ReLU, the denominator the plain ones).  Tiles are
+// taken DEPTH at a time; every stage issues its loads and stores whether or not it
+// still has a tile (out of range they do nothing), only the arithmetic is skipped.
+template <bool HILO, int DEPTH, bool ROPE>
+__device__ __forceinline__ void apply_tiles(ApplyStream<DEPTH, ROPE> &st, unsigned char *tileQ, int lane,
+                                            const ApplyOperands<HILO> &A, float eps)
 {
-    static_assert(DEPTH % NB == 0, "stages are consumed NB at a time");
-    static_assert(!ROPE || (NB == 1 && DEPTH % 2 == 0), "the table ring below alternates between two slots");
     constexpr int NS = HILO ? 2 : 1;
     constexpr int kTileBytes = kApplyTile * kRowBytes;
     const int n = lane & 31, g = lane >> 5;
     const int wr_off = (lane >> 3) * kRowBytes + (lane & 7) * 16;
+    const uint32_t lane_off = (uint32_t)(lane >> 3) * st.row_bytes + (uint32_t)(lane & 7) * 16u;
 
-    // rotation-table entries of the tile in work and of the next one (slot = stage parity)
-    f32x4 cs[ROPE ? 2 : 1][kApplyTile / 8][2];
-    if (ROPE && first_tile < n_tiles) rope_tile_load<kApplyTile>(rope, t0 + first_tile * kApplyTile, t1, lane, cs[0]);
-
-    // NB tiles go through each phase together, so that one tile's LDS and
-    // conversion latencies hide behind the other's MFMA chain.
-    int tile = first_tile;
-    while (tile < n_tiles) {
+    auto round = [&](int i0) __attribute__((always_inline)) {
 #pragma unroll
-        for (int s0 = 0; s0 < DEPTH; s0 += NB) {
-            if (tile < n_tiles) {
-                bool valid[NB];
-#pragma unroll
-                for (int j = 0; j < NB; ++j) valid[j] = tile + j * tile_step < n_tiles;
-
+        for (int s = 0; s < DEPTH; ++s) {
+            __builtin_amdgcn_sched_barrier(0);   // stages stay in program order (see state_accumulate)
+            const bool valid = i0 + s < st.walk.count;
+            const uint32_t out_off = st.walk.template offset<kApplyTile>(i0 + s, st.row_bytes);
+            if (valid) {
                 wave_lds_fence();
 #pragma unroll
-                for (int j = 0; j < NB; ++j)
-                    if (valid[j]) {
-#pragma unroll
-                        for (int i = 0; i < kApplyTile / 8; ++i) {
-                            const u32x4 pq = relu_bf16x8(qreg[s0 + j][i]);                          // phi(Q)
-                            *reinterpret_cast<u32x4 *>(tileQ + j * kTileBytes + wr_off + 8 * i * kRowBytes) = pq;
-                            if (ROPE)
-                                *reinterpret_cast<u32x4 *>(tileQ + (NB + j) * kTileBytes + wr_off + 8 * i * kRowBytes) =
-                                    rope_rotate_bf16x8(pq, cs[ROPE ? s0 & 1 : 0][i][0], cs[ROPE ? s0 & 1 : 0][i][1]);
-                        }
-                        const int nxt = tile + (j + DEPTH) * tile_step;
-                        if (nxt < n_tiles)
-                            apply_tile_load(Qh, stride_n, t0 + nxt * kApplyTile, t1, lane, qreg[s0 + j]);
-                        if (ROPE && tile + tile_step < n_tiles)
-                            rope_tile_load<kApplyTile>(rope, t0 + (tile + tile_step) * kApplyTile, t1, lane,
-                                                       cs[ROPE ? (s0 & 1) ^ 1 : 0]);
-                    }
+                for (int i = 0; i < kApplyTile / 8; ++i) {
+                    const u32x4 pq = relu_bf16x8(st.q[s][i]);                          // phi(Q)
+                    *reinterpret_cast<u32x4 *>(tileQ + wr_off + 8 * i * kRowBytes) = pq;
+                    if (ROPE)
+                        *reinterpret_cast<u32x4 *>(tileQ + kTileBytes + wr_off + 8 * i * kRowBytes) =
+                            rope_rotate_bf16x8(pq, st.cs[ROPE ? s : 0][i][0], st.cs[ROPE ? s : 0][i][1]);
+                }
+            }
+            st.request(s, i0 + s + DEPTH, lane);   // refill this stage: DEPTH tiles ahead
+            __builtin_amdgcn_sched_barrier(0);
+            u32x4 o[kApplyTile / 8] = {};
+            if (valid) {
                 wave_lds_fence();
-
                 // B operands: features 16*ks + 8g .. +8 of token n (Br: the rotated copy for the numerator)
-                bf16x8 Bq[NB][4], Br[ROPE ? NB : 1][4];
+                bf16x8 Bq[4], Br[4];
 #pragma unroll
-                for (int j = 0; j < NB; ++j)
-                    if (valid[j]) {
+                for (int ks = 0; ks < 4; ++ks) {
+                    Bq[ks] = *reinterpret_cast<const bf16x8 *>(tileQ + n * kRowBytes + (16 * ks + 8 * g) * 2);
+                    Br[ks] = ROPE ? *reinterpret_cast<const bf16x8 *>(tileQ + kTileBytes + n * kRowBytes +
+                                                                      (16 * ks + 8 * g) * 2)
+                                  : Bq[ks];
+                }
+                f32x16 acc[2], accz;
 #pragma unroll
-                        for (int ks = 0; ks < 4; ++ks) {
-                            Bq[j][ks] = *reinterpret_cast<const bf16x8 *>(tileQ + j * kTileBytes + n * kRowBytes +
-                                                                          (16 * ks + 8 * g) * 2);
-                            if (ROPE)
-                                Br[j][ks] = *reinterpret_cast<const bf16x8 *>(tileQ + (NB + j) * kTileBytes +
-                                                                              n * kRowBytes + (16 * ks + 8 * g) * 2);
-                        }
-                    }
-
-                f32x16 acc[NB][2], accz[NB];
-#pragma unroll
-                for (int j = 0; j < NB; ++j)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) { acc[j][0][i] = 0.f; acc[j][1][i] = 0.f; accz[j][i] = 0.f; }
+                for (int i = 0; i < 16; ++i) { acc[0][i] = 0.f; acc[1][i] = 0.f; accz[i] = 0.f; }
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-                    for (int j = 0; j < NB; ++j)
-                        if (valid[j])
-                            accz[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.zrow[ks], Bq[j][ks], accz[j], 0, 0, 0);
+                    accz = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.zrow[ks], Bq[ks], accz, 0, 0, 0);
 #pragma unroll
                 for (int p = NS - 1; p >= 0; --p)      // small (lo) terms first
 #pragma unroll
-                    for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-                        for (int j = 0; j < NB; ++j)
-                            if (valid[j]) {
-                                const bf16x8 bq = ROPE ? Br[ROPE ? j : 0][ks] : Bq[j][ks];
-                                acc[j][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.s[p][0][ks], bq, acc[j][0], 0, 0, 0);
-                                acc[j][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.s[p][1][ks], bq, acc[j][1], 0, 0, 0);
-                            }
-
-                wave_lds_fence();
-#pragma unroll
-                for (int j = 0; j < NB; ++j)
-                    if (valid[j]) {
-                        // denominator: rows 0 (hi) and 1 (lo) of the z block sit in registers 0 and 1 of
-                        // the lanes of the lower half; the upper half fetches them across the wave
-                        float den = accz[j][1] + accz[j][0];
-                        den = __shfl(den, n);
-                        const float inv = 1.0f / (den + eps);
-#pragma unroll
-                        for (int rb = 0; rb < 2; ++rb) {
-                            const f32x16 &a = acc[j][rb];
-                            u32x4 lo4, hi4;
-                            lo4.x = pack_bf16x2(a[0] * inv, a[1] * inv);
-                            lo4.y = pack_bf16x2(a[2] * inv, a[3] * inv);
-                            lo4.z = pack_bf16x2(a[4] * inv, a[5] * inv);
-                            lo4.w = pack_bf16x2(a[6] * inv, a[7] * inv);
-                            hi4.x = pack_bf16x2(a[8] * inv, a[9] * inv);
-                            hi4.y = pack_bf16x2(a[10] * inv, a[11] * inv);
-                            hi4.z = pack_bf16x2(a[12] * inv, a[13] * inv);
-                            hi4.w = pack_bf16x2(a[14] * inv, a[15] * inv);
-                            unsigned char *row = tileQ + j * kTileBytes + n * kRowBytes + (32 * g + 16 * rb) * 2;
-                            *reinterpret_cast<u32x4 *>(row) = lo4;
-                            *reinterpret_cast<u32x4 *>(row + 16) = hi4;
-                        }
+                    for (int ks = 0; ks < 4; ++ks) {
+                        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.s[p][0][ks], Br[ks], acc[0], 0, 0, 0);
+                        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.s[p][1][ks], Br[ks], acc[1], 0, 0, 0);
                     }
                 wave_lds_fence();
+                // denominator: rows 0 (hi) and 1 (lo) of the z block sit in registers 0 and 1 of
+                // the lanes of the lower half; the upper half fetches them across the wave
+                float den = accz[1] + accz[0];
+                den = __shfl(den, n);
+                const float inv = 1.0f / (den + eps);
 #pragma unroll
-                for (int j = 0; j < NB; ++j)
-                    if (valid[j]) {
-                        const int tok0 = t0 + (tile + j * tile_step) * kApplyTile;
+                for (int rb = 0; rb < 2; ++rb) {
+                    const f32x16 &a = acc[rb];
+                    u32x4 lo4, hi4;
+                    lo4.x = pack_bf16x2(a[0] * inv, a[1] * inv);
+                    lo4.y = pack_bf16x2(a[2] * inv, a[3] * inv);
+                    lo4.z = pack_bf16x2(a[4] * inv, a[5] * inv);
+                    lo4.w = pack_bf16x2(a[6] * inv, a[7] * inv);
+                    hi4.x = pack_bf16x2(a[8] * inv, a[9] * inv);
+                    hi4.y = pack_bf16x2(a[10] * inv, a[11] * inv);
+                    hi4.z = pack_bf16x2(a[12] * inv, a[13] * inv);
+                    hi4.w = pack_bf16x2(a[14] * inv, a[15] * inv);
+                    unsigned char *row = tileQ + n * kRowBytes + (32 * g + 16 * rb) * 2;
+                    *reinterpret_cast<u32x4 *>(row) = lo4;
+                    *reinterpret_cast<u32x4 *>(row + 16) = hi4;
+                }
+                wave_lds_fence();
 #pragma unroll
-                        for (int i = 0; i < kApplyTile / 8; ++i) {
-                            const int tok = tok0 + (lane >> 3) + 8 * i;
-                            const u32x4 o = *reinterpret_cast<const u32x4 *>(tileQ + j * kTileBytes + wr_off +
-                                                                             8 * i * kRowBytes);
-                            if (tok < t1) store_stream16(Oh + (int64_t)tok * stride_n + (lane & 7) * 8, o);
-                        }
-                    }
+                for (int i = 0; i < kApplyTile / 8; ++i)
+                    o[i] = *reinterpret_cast<const u32x4 *>(tileQ + wr_off + 8 * i * kRowBytes);
             }
-            tile += NB * tile_step;
+#pragma unroll
+            for (int i = 0; i < kApplyTile / 8; ++i)
+                store_stream16(st.rO, out_off + lane_off + (uint32_t)i * 8u * st.row_bytes, o[i]);
         }
-    }
+    };
+    // The first round stands apart so that the loop is entered with the same sequence of
+    // outstanding loads and stores that its own rounds leave behind: the compiler sizes the
+    // loop's waits for the worse of the two.
+    if (st.walk.count > 0) round(0);
+    for (int i0 = DEPTH; i0 < st.walk.count; i0 += DEPTH) round(i0);
 }
 
-// LDS bytes per wave and in total: NB tiles, twice that with ROPE (plain + rotated copies).
-template <int NB, bool ROPE>
-__host__ __device__ constexpr int apply_wave_lds_bytes() { return (ROPE ? 2 : 1) * NB * kApplyTile * kRowBytes; }
-template <int WAVES, int NB, bool ROPE>
-__host__ __device__ constexpr int apply_lds_bytes() { return WAVES * apply_wave_lds_bytes<NB, ROPE>(); }
+// LDS bytes per wave and in total: one tile, two with ROPE (plain + rotated copy).
+template <bool ROPE>
+__host__ __device__ constexpr int apply_wave_lds_bytes() { return (ROPE ? 2 : 1) * kApplyTile * kRowBytes; }
+template <int WAVES, bool ROPE>
+__host__ __device__ constexpr int apply_lds_bytes() { return WAVES * apply_wave_lds_bytes<ROPE>(); }
 
 // grid = (C, B*H), block = 64*WAVES.  Wave w of workgroup c owns tiles
 // WAVES*c + w + WAVES*C*i (i = 0, 1, ...) of the T = ceil((t1-t0)/32) tiles,
 // the same round-robin deal as the state kernel.
 // HILO = false drops the low half of S (one MFMA pass instead of two).
-// NB tiles of a wave are in the arithmetic phase together.
-template <bool HILO, int WAVES, int DEPTH, int NB, bool ROPE>
+template <bool HILO, int WAVES, int DEPTH, bool ROPE>
 __global__ __launch_bounds__(64 * WAVES, 1) void apply_mfma_d64(
     const uint16_t *__restrict__ Q, uint16_t *__restrict__ O, const float *__restrict__ rope, TokStrides st, int H,
     int t0, int t1, int C, const float *__restrict__ S, const float *__restrict__ z, float eps)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int tid = threadIdx.x;
-    const int lane = tid & (kWave - 1), wave = tid >> 6;
+    const int lane = tid & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = blockIdx.x, bh = blockIdx.y;
     const int b = bh / H, h = bh % H;
     const uint16_t *Qh = Q + b * st.b + h * st.h;
     uint16_t *Oh = O + b * st.b + h * st.h;
     const int n_tiles = (t1 - t0 + kApplyTile - 1) / kApplyTile;
-    const int first = WAVES * c + wave, step = WAVES * C;
 
-    u32x4 qreg[DEPTH][kApplyTile / 8];
-    apply_prefetch<DEPTH>(Qh, st.n, t0, t1, first, step, n_tiles, lane, qreg);   // in flight while S is fetched
+    ApplyStream<DEPTH, ROPE> stream(Qh, Oh, rope, st.n, t1, TileWalk(t0, WAVES * c + wave, WAVES * C, n_tiles));
+    apply_prefetch<0, DEPTH>(stream, lane);   // in flight while S is fetched
     ApplyOperands<HILO> A;
     A.template load<false>(S + (size_t)bh * 64 * 64, z + (size_t)bh * 64, lane);
-    apply_tiles<HILO, DEPTH, NB, ROPE>(Qh, Oh, rope, st.n, t0, t1, first, step, n_tiles,
-                                       lds + wave * apply_wave_lds_bytes<NB, ROPE>(), lane, A, eps, qreg);
+    apply_tiles<HILO>(stream, lds + wave * apply_wave_lds_bytes<ROPE>(), lane, A, eps);
 }
 
 }  // namespace sv

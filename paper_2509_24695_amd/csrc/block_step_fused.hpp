@@ -21,15 +21,15 @@
 
 namespace sv {
 
-template <int TILE, int WAVES, int NB, bool ROPE>
+template <int TILE, int WAVES, bool ROPE>
 __host__ __device__ constexpr int block_step_lds_bytes() {
-    return state_lds_bytes<TILE, WAVES>() > apply_lds_bytes<WAVES, NB, ROPE>() ? state_lds_bytes<TILE, WAVES>()
-                                                                               : apply_lds_bytes<WAVES, NB, ROPE>();
+    return state_lds_bytes<TILE, WAVES>() > apply_lds_bytes<WAVES, ROPE>() ? state_lds_bytes<TILE, WAVES>()
+                                                                           : apply_lds_bytes<WAVES, ROPE>();
 }
 
 // grid = (C, B*H) with C*B*H <= resident workgroup capacity, block = 64*WAVES.
 // ROPE: keys and queries are rotated after the ReLU in the numerator path (table row = token of the block).
-template <int TILE, int WAVES, int DEPTH_S, bool HILO, int DEPTH_A, int NB, bool ROPE>
+template <int TILE, int WAVES, int DEPTH_S, bool HILO, int DEPTH_A, bool ROPE>
 __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma_d64(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
     uint16_t *__restrict__ O, const float *__restrict__ rope, TokStrides st, int H, int N, int C, const float *S_in, const float *z_in,
@@ -40,7 +40,7 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma_d64(
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
     const int tid = threadIdx.x;
-    const int lane = tid & (kWave - 1), wave = tid >> 6;
+    const int lane = tid & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = blockIdx.x, bh = blockIdx.y, BH = gridDim.y;
     const int b = bh / H, h = bh % H;
     const int64_t head_off = b * st.b + h * st.h;
@@ -51,25 +51,22 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma_d64(
 
     // ---- this wave's first two tiles of Q_b are requested right away: they arrive during the state
     //      phase and make no later load wait behind them ---------------------------------------------
-    const int n_tiles_q = (N + kApplyTile - 1) / kApplyTile;
-    const int first = WAVES * c + wave, step = WAVES * C;
+    const TileWalk walk(0, WAVES * c + wave, WAVES * C, (N + TILE - 1) / TILE);
+    static_assert(TILE == kApplyTile, "one tile walk serves both phases");
     constexpr int kEarly = DEPTH_A < 2 ? DEPTH_A : 2;
-    u32x4 qreg[DEPTH_A][kApplyTile / 8];
-    apply_prefetch<DEPTH_A, 0, kEarly>(Q + head_off, st.n, 0, N, first, step, n_tiles_q, lane, qreg);
+    ApplyStream<DEPTH_A, ROPE> qstream(Q + head_off, O + head_off, rope, st.n, N, walk);
+    apply_prefetch<0, kEarly>(qstream, lane);
 
     // ---- fold this workgroup's share of K_b, V_b ------------------------------------------------
     {
-        const int n_tiles = (N + TILE - 1) / TILE;
         StateAcc acc;
         acc.clear();
-        StateStages<TILE, DEPTH_S, ROPE> stg;
+        StateStream<TILE, DEPTH_S, ROPE> kvstream(K + head_off, V + head_off, rope, st.n, N, walk);
         unsigned char *tileK = lds + wave * 2 * kTileBytes;
-        state_prefetch<TILE, DEPTH_S, ROPE>(K + head_off, V + head_off, rope, st.n, 0, N, WAVES * c + wave, WAVES * C,
-                                            n_tiles, lane, stg);
-        state_accumulate<TILE, DEPTH_S, ROPE>(K + head_off, V + head_off, rope, st.n, 0, N, WAVES * c + wave,
-                                              WAVES * C, n_tiles, tileK, tileK + kTileBytes, lane, stg, acc);
+        state_prefetch(kvstream, lane);
+        state_accumulate(kvstream, tileK, tileK + kTileBytes, lane, acc);
         // the rest of this wave's Q prefetch streams in while the head's state is being agreed on
-        apply_prefetch<DEPTH_A, kEarly, DEPTH_A>(Q + head_off, st.n, 0, N, first, step, n_tiles_q, lane, qreg);
+        apply_prefetch<kEarly, DEPTH_A>(qstream, lane);
         float *partials = static_cast<float *>(ws) + (size_t)bh * kMaxChunks * kStateElems;
         state_wg_reduce_store<WAVES>(acc, reinterpret_cast<float *>(lds), wave, lane,
                                      partials + (size_t)c * kStateElems);
@@ -87,8 +84,7 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma_d64(
     // ---- apply the updated state to this workgroup's share of Q_b ----------------------------------
     ApplyOperands<HILO> A;
     A.template load<true>(Sh, zh, lane);
-    apply_tiles<HILO, DEPTH_A, NB, ROPE>(Q + head_off, O + head_off, rope, st.n, 0, N, first, step, n_tiles_q,
-                                         lds + wave * apply_wave_lds_bytes<NB, ROPE>(), lane, A, eps, qreg);
+    apply_tiles<HILO>(qstream, lds + wave * apply_wave_lds_bytes<ROPE>(), lane, A, eps);
 }
 
 }  // namespace sv

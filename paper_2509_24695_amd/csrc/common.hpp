@@ -67,47 +67,60 @@ __device__ __forceinline__ u32x4 rope_rotate_bf16x8(u32x4 w, f32x4 cs01, f32x4 c
     r.w = rope_rotate_pair(w.w, cs23.z, cs23.w);
     return r;
 }
-// Table entries for the 16-byte chunks a lane holds of a d = 64 tile in the coalesced layout
-// (token tok0 + lane/8 + 8i, pairs 4*(lane%8) .. +3).  Rows past t1 are not touched.
-template <int TILE>
-__device__ __forceinline__ void rope_tile_load(const float *__restrict__ rope, int tok0, int t1, int lane,
-                                               f32x4 (&cs)[TILE / 8][2])
-{
-#pragma unroll
-    for (int i = 0; i < TILE / 8; ++i) {
-        const int tok = tok0 + (lane >> 3) + 8 * i;
-        f32x4 a = {1.f, 0.f, 1.f, 0.f}, b = {1.f, 0.f, 1.f, 0.f};
-        if (tok < t1) {
-            const float *row = rope + (int64_t)tok * 64 + (lane & 7) * 8;
-            a = *reinterpret_cast<const f32x4 *>(row);
-            b = *reinterpret_cast<const f32x4 *>(row + 4);
-        }
-        cs[i][0] = a;
-        cs[i][1] = b;
-    }
+// ---- range-checked streaming access ------------------------------------------------------------
+//
+// Token tiles are addressed through buffer resources: the hardware compares each
+// lane's byte offset with the resource's size, returns zeros for loads at or past
+// it and drops such stores.  Ragged tails and tiles past the end of a wave's share
+// therefore need no branch, every stage of a software pipeline issues the same
+// number of memory instructions, and the compiler can wait for exactly the
+// loads it needs (s_waitcnt vmcnt(n)) while later ones stay in flight.  Offsets are
+// 32-bit: the host routes tensors whose heads span 2 GiB or more to other kernels.
+using rsrc_t = __amdgpu_buffer_rsrc_t;
+constexpr uint32_t kOutOfRange = 0x80000000u;   // an offset no resource built here covers
+
+// `p` must be wave-uniform.  Bytes [0, bytes) are addressable.
+__device__ __forceinline__ rsrc_t make_rsrc(const void *p, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, bytes, 0x00020000);
 }
 
-// Streaming 16-byte global accesses.  Tokens are read once and outputs written
-// once, so with SV_STREAM_NT both are marked non-temporal.
+// Tokens are read once and outputs written once, so with SV_STREAM_NT both are
+// marked non-temporal.
 #ifndef SV_STREAM_NT
 #define SV_STREAM_NT 1
 #endif
-__device__ __forceinline__ u32x4 load_stream16(const void *p) {
-#if SV_STREAM_NT
-    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
-#else
-    return *reinterpret_cast<const u32x4 *>(p);
-#endif
-}
 #ifndef SV_STORE_NT
 #define SV_STORE_NT SV_STREAM_NT
 #endif
-__device__ __forceinline__ void store_stream16(void *p, u32x4 v) {
-#if SV_STORE_NT
-    __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(p));
-#else
-    *reinterpret_cast<u32x4 *>(p) = v;
-#endif
+__device__ __forceinline__ u32x4 load_stream16(rsrc_t r, uint32_t off) {
+    return __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, SV_STREAM_NT ? 2 : 0);
+}
+__device__ __forceinline__ void store_stream16(rsrc_t r, uint32_t off, u32x4 v) {
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, off, 0, SV_STORE_NT ? 2 : 0);
+}
+// Cached 16-byte load (rotation table: shared by all heads, worth keeping in L2).
+__device__ __forceinline__ f32x4 load_cached16(rsrc_t r, uint32_t off) {
+    return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0));
+}
+
+// Byte offset of the first row of the tile that starts at token `tok0`, or kOutOfRange.
+__device__ __forceinline__ uint32_t tile_offset(bool valid, int tok0, uint32_t row_bytes) {
+    return valid ? (uint32_t)tok0 * row_bytes : kOutOfRange;
+}
+
+// Table entries for the 16-byte chunks a lane holds of a d = 64 tile in the coalesced layout
+// (token tok0 + lane/8 + 8i, pairs 4*(lane%8) .. +3).  `rT` covers the table rows below the
+// end of the token range; `off0` = tile_offset(.., 256).  Rows out of range read as zeros,
+// which turn the (all-zero) features they meet into zeros.
+template <int TILE>
+__device__ __forceinline__ void rope_tile_load(rsrc_t rT, uint32_t off0, int lane, f32x4 (&cs)[TILE / 8][2])
+{
+    const uint32_t lane_off = (uint32_t)(lane >> 3) * 256u + (uint32_t)(lane & 7) * 32u;
+#pragma unroll
+    for (int i = 0; i < TILE / 8; ++i) {
+        cs[i][0] = load_cached16(rT, off0 + lane_off + i * 2048u);
+        cs[i][1] = load_cached16(rT, off0 + lane_off + i * 2048u + 16u);
+    }
 }
 
 // ---- typed scalar access used by the generic (any dtype) kernels --------------------------

@@ -79,23 +79,30 @@ struct StateAcc {
     }
 };
 
-template <int TILE>
-__device__ __forceinline__ void state_tile_load(const uint16_t *Kh, const uint16_t *Vh, int64_t stride_n,
-                                                int tok0, int t1, int lane, u32x4 (&kreg)[TILE / 8],
-                                                u32x4 (&vreg)[TILE / 8])
-{
-    const int col = lane & 7;
-#pragma unroll
-    for (int i = 0; i < TILE / 8; ++i) {
-        const int tok = tok0 + (lane >> 3) + 8 * i;
-        u32x4 kk = {0u, 0u, 0u, 0u}, vv = {0u, 0u, 0u, 0u};
-        if (tok < t1) {
-            kk = load_stream16(Kh + (int64_t)tok * stride_n + col * 8);
-            vv = load_stream16(Vh + (int64_t)tok * stride_n + col * 8);
-        }
-        kreg[i] = kk;
-        vreg[i] = vv;
+// A wave's share of the tiles that cover the token range [t0, t1): tiles
+// first + i*step for i = 0 .. count-1 (all values wave-uniform).
+struct TileWalk {
+    int t0, first, step, count;
+    __device__ __forceinline__ TileWalk(int t0_, int first_, int step_, int n_tiles)
+        : t0(t0_), first(first_), step(step_),
+          count(first_ < n_tiles ? (n_tiles - first_ + step_ - 1) / step_ : 0) {}
+    // first token of the wave's i-th tile of TILE tokens
+    template <int TILE> __device__ __forceinline__ int token(int i) const { return t0 + (first + i * step) * TILE; }
+    // its byte offset for rows of row_bytes bytes, kOutOfRange past the share
+    template <int TILE> __device__ __forceinline__ uint32_t offset(int i, uint32_t row_bytes) const {
+        return tile_offset(i < count, token<TILE>(i), row_bytes);
     }
+};
+
+// Coalesced load of a TILE x 64 bf16 tile: lane l takes bytes 16*(l%8) .. +16 of
+// rows l/8 + 8i.  `off0` is the tile's byte offset (TileWalk::offset).
+template <int TILE>
+__device__ __forceinline__ void token_tile_load(rsrc_t r, uint32_t off0, uint32_t row_bytes, int lane,
+                                                u32x4 (&reg)[TILE / 8])
+{
+    const uint32_t lane_off = (uint32_t)(lane >> 3) * row_bytes + (uint32_t)(lane & 7) * 16u;
+#pragma unroll
+    for (int i = 0; i < TILE / 8; ++i) reg[i] = load_stream16(r, off0 + lane_off + (uint32_t)i * 8u * row_bytes);
 }
 
 // Gathers 8 tokens (rows tok_row .. tok_row+7) of 32-bit word `r` from an LDS
@@ -117,86 +124,91 @@ __device__ __forceinline__ void lds_gather_pairs(const unsigned char *tile, int 
     odd = __builtin_bit_cast(bf16x8, hi);
 }
 
-// Register staging of one wave: the K and V rows of DEPTH tiles in flight, and
-// with ROPE the rotation-table entries that go with the K rows.
+// One wave's input stream: buffer resources over the head's K and V rows (and
+// the rotation table) below the end of the token range, the wave's tile walk,
+// and the register staging of DEPTH tiles in flight.
 template <int TILE, int DEPTH, bool ROPE>
-struct StateStages {
+struct StateStream {
+    rsrc_t rK, rV, rT;
+    uint32_t row_bytes;
+    TileWalk walk;
     u32x4 k[DEPTH][TILE / 8], v[DEPTH][TILE / 8];
     f32x4 cs[ROPE ? DEPTH : 1][TILE / 8][2];
+
+    __device__ __forceinline__ StateStream(const uint16_t *Kh, const uint16_t *Vh, const float *rope,
+                                           int64_t stride_n, int t1, const TileWalk &w)
+        : rK(make_rsrc(Kh, (uint32_t)t1 * (uint32_t)stride_n * 2u)),
+          rV(make_rsrc(Vh, (uint32_t)t1 * (uint32_t)stride_n * 2u)),
+          rT(make_rsrc(rope, ROPE ? (uint32_t)t1 * 256u : 0u)), row_bytes((uint32_t)stride_n * 2u), walk(w) {}
+
+    // Requests the wave's i-th tile into stage s.  Always the same number of memory
+    // instructions: past the wave's share they read nothing and return zeros.
+    __device__ __forceinline__ void request(int s, int i, int lane)
+    {
+        token_tile_load<TILE>(rK, walk.offset<TILE>(i, row_bytes), row_bytes, lane, k[s]);
+        token_tile_load<TILE>(rV, walk.offset<TILE>(i, row_bytes), row_bytes, lane, v[s]);
+        if (ROPE) rope_tile_load<TILE>(rT, walk.offset<TILE>(i, 256u), lane, cs[ROPE ? s : 0]);
+    }
 };
 
-// Requests the first DEPTH tiles of a wave's share (tiles first_tile,
-// first_tile + tile_step, ... below n_tiles).
+// Requests the first DEPTH tiles of a wave's share.
 template <int TILE, int DEPTH, bool ROPE>
-__device__ __forceinline__ void state_prefetch(const uint16_t *Kh, const uint16_t *Vh, const float *rope,
-                                               int64_t stride_n, int t0, int t1, int first_tile, int tile_step,
-                                               int n_tiles, int lane, StateStages<TILE, DEPTH, ROPE> &st)
+__device__ __forceinline__ void state_prefetch(StateStream<TILE, DEPTH, ROPE> &st, int lane)
 {
 #pragma unroll
     for (int s = 0; s < DEPTH; ++s) {
-        const int t = first_tile + s * tile_step;
-        if (t < n_tiles) {
-            state_tile_load<TILE>(Kh, Vh, stride_n, t0 + t * TILE, t1, lane, st.k[s], st.v[s]);
-            if (ROPE) rope_tile_load<TILE>(rope, t0 + t * TILE, t1, lane, st.cs[ROPE ? s : 0]);
-        }
+        st.request(s, s, lane);
+        __builtin_amdgcn_sched_barrier(0);   // requests go out in stage order, as they do in the loop
     }
 }
 
-// One wave's share of the token range [t0, t1): tiles first_tile, first_tile +
-// tile_step, ... below n_tiles, the first DEPTH of which state_prefetch has
-// already requested into `st`.  Tokens past t1 are loaded as zeros, which add
-// nothing to either sum.  `tileK`/`tileV` are this wave's private LDS tiles.
+// Accumulates the wave's share, whose first DEPTH tiles state_prefetch has
+// requested.  Tiles are taken DEPTH at a time; in the last round the stages past
+// the share hold zeros, as do tokens past t1, and add nothing to either sum.  `tileK`/`tileV` are this wave's private LDS tiles.
 template <int TILE, int DEPTH, bool ROPE>
-__device__ __forceinline__ void state_accumulate(const uint16_t *Kh, const uint16_t *Vh, const float *rope,
-                                                 int64_t stride_n, int t0, int t1, int first_tile, int tile_step,
-                                                 int n_tiles, unsigned char *tileK, unsigned char *tileV, int lane,
-                                                 StateStages<TILE, DEPTH, ROPE> &st, StateAcc &acc)
+__device__ __forceinline__ void state_accumulate(StateStream<TILE, DEPTH, ROPE> &st, unsigned char *tileK,
+                                                 unsigned char *tileV, int lane, StateAcc &acc)
 {
     static_assert(TILE == 16 || TILE == 32, "tile is one or two MFMA k-steps");
     const int r = lane & 31, g = lane >> 5;
     const int wr_off = (lane >> 3) * kRowBytes + (lane & 7) * 16;
 
-    int tile = first_tile;
-    while (tile < n_tiles) {
+    for (int i0 = 0; i0 < st.walk.count; i0 += DEPTH) {
 #pragma unroll
         for (int s = 0; s < DEPTH; ++s) {
-            if (tile < n_tiles) {
-                // phi(K) on the packed pairs; key sum in fp32 from the same registers
+            // keep each stage's work together: a later stage's registers must not be touched (and
+            // waited for) before this stage has been refilled
+            __builtin_amdgcn_sched_barrier(0);
+            // phi(K) on the packed pairs; key sum in fp32 from the same registers
 #pragma unroll
-                for (int i = 0; i < TILE / 8; ++i) {
-                    const u32x4 kk = relu_bf16x8(st.k[s][i]);
-                    acc.z[0] += bf16_lo(kk.x);  acc.z[1] += bf16_hi(kk.x);
-                    acc.z[2] += bf16_lo(kk.y);  acc.z[3] += bf16_hi(kk.y);
-                    acc.z[4] += bf16_lo(kk.z);  acc.z[5] += bf16_hi(kk.z);
-                    acc.z[6] += bf16_lo(kk.w);  acc.z[7] += bf16_hi(kk.w);
-                    // the key sum above is never rotated; the keys that meet V are (RoPE after ReLU)
-                    st.k[s][i] = ROPE ? rope_rotate_bf16x8(kk, st.cs[ROPE ? s : 0][i][0], st.cs[ROPE ? s : 0][i][1]) : kk;
-                }
-                wave_lds_fence();   // earlier reads of the tile buffer are done before it is overwritten
-#pragma unroll
-                for (int i = 0; i < TILE / 8; ++i) {
-                    *reinterpret_cast<u32x4 *>(tileK + wr_off + 8 * i * kRowBytes) = st.k[s][i];
-                    *reinterpret_cast<u32x4 *>(tileV + wr_off + 8 * i * kRowBytes) = st.v[s][i];
-                }
-                // refill this stage: DEPTH tiles ahead
-                const int nxt = tile + DEPTH * tile_step;
-                if (nxt < n_tiles) {
-                    state_tile_load<TILE>(Kh, Vh, stride_n, t0 + nxt * TILE, t1, lane, st.k[s], st.v[s]);
-                    if (ROPE) rope_tile_load<TILE>(rope, t0 + nxt * TILE, t1, lane, st.cs[ROPE ? s : 0]);
-                }
-                wave_lds_fence();
-#pragma unroll
-                for (int ks = 0; ks < TILE / 16; ++ks) {
-                    bf16x8 a0, a1, b0, b1;
-                    lds_gather_pairs(tileK, 16 * ks + 8 * g, r, a0, a1);
-                    lds_gather_pairs(tileV, 16 * ks + 8 * g, r, b0, b1);
-                    acc.s[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc.s[0][0], 0, 0, 0);
-                    acc.s[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc.s[0][1], 0, 0, 0);
-                    acc.s[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc.s[1][0], 0, 0, 0);
-                    acc.s[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc.s[1][1], 0, 0, 0);
-                }
+            for (int i = 0; i < TILE / 8; ++i) {
+                const u32x4 kk = relu_bf16x8(st.k[s][i]);
+                acc.z[0] += bf16_lo(kk.x);  acc.z[1] += bf16_hi(kk.x);
+                acc.z[2] += bf16_lo(kk.y);  acc.z[3] += bf16_hi(kk.y);
+                acc.z[4] += bf16_lo(kk.z);  acc.z[5] += bf16_hi(kk.z);
+                acc.z[6] += bf16_lo(kk.w);  acc.z[7] += bf16_hi(kk.w);
+                // the key sum above is never rotated; the keys that meet V are (RoPE after ReLU)
+                st.k[s][i] = ROPE ? rope_rotate_bf16x8(kk, st.cs[ROPE ? s : 0][i][0], st.cs[ROPE ? s : 0][i][1]) : kk;
             }
-            tile += tile_step;
+            wave_lds_fence();   // earlier reads of the tile buffer are done before it is overwritten
+#pragma unroll
+            for (int i = 0; i < TILE / 8; ++i) {
+                *reinterpret_cast<u32x4 *>(tileK + wr_off + 8 * i * kRowBytes) = st.k[s][i];
+                *reinterpret_cast<u32x4 *>(tileV + wr_off + 8 * i * kRowBytes) = st.v[s][i];
+            }
+            st.request(s, i0 + s + DEPTH, lane);   // refill this stage: DEPTH tiles ahead
+            __builtin_amdgcn_sched_barrier(0);
+            wave_lds_fence();
+#pragma unroll
+            for (int ks = 0; ks < TILE / 16; ++ks) {
+                bf16x8 a0, a1, b0, b1;
+                lds_gather_pairs(tileK, 16 * ks + 8 * g, r, a0, a1);
+                lds_gather_pairs(tileV, 16 * ks + 8 * g, r, b0, b1);
+                acc.s[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc.s[0][0], 0, 0, 0);
+                acc.s[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc.s[0][1], 0, 0, 0);
+                acc.s[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc.s[1][0], 0, 0, 0);
+                acc.s[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc.s[1][1], 0, 0, 0);
+            }
         }
     }
 }
@@ -344,7 +356,7 @@ __global__ __launch_bounds__(64 * WAVES, 1) void state_mfma_d64(
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
     const int tid = threadIdx.x;
-    const int lane = tid & (kWave - 1), wave = tid >> 6;
+    const int lane = tid & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = blockIdx.x, bh = blockIdx.y, BH = gridDim.y;
     const int b = bh / H, h = bh % H;
     const uint16_t *Kh = K + b * st.b + h * st.h;
@@ -353,11 +365,10 @@ __global__ __launch_bounds__(64 * WAVES, 1) void state_mfma_d64(
 
     StateAcc acc;
     acc.clear();
-    StateStages<TILE, DEPTH, ROPE> stg;
+    StateStream<TILE, DEPTH, ROPE> stream(Kh, Vh, rope, st.n, t1, TileWalk(t0, WAVES * c + wave, WAVES * C, n_tiles));
     unsigned char *tileK = lds + wave * 2 * kTileBytes;
-    state_prefetch<TILE, DEPTH, ROPE>(Kh, Vh, rope, st.n, t0, t1, WAVES * c + wave, WAVES * C, n_tiles, lane, stg);
-    state_accumulate<TILE, DEPTH, ROPE>(Kh, Vh, rope, st.n, t0, t1, WAVES * c + wave, WAVES * C, n_tiles, tileK,
-                                        tileK + kTileBytes, lane, stg, acc);
+    state_prefetch(stream, lane);
+    state_accumulate(stream, tileK, tileK + kTileBytes, lane, acc);
 
     float *partials = static_cast<float *>(ws) + (size_t)bh * kMaxChunks * kStateElems;
     state_wg_reduce_store<WAVES>(acc, reinterpret_cast<float *>(lds), wave, lane,

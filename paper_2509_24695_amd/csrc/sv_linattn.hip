@@ -22,10 +22,12 @@ using namespace sv;
 constexpr int kVersion = 400;   // 0.4.0
 
 // Tuned launch shapes of the bf16 d = 64 kernels (one workgroup per compute unit).
-constexpr int kStateTile = 32, kStateWaves = 4, kStateDepth = 2;
-constexpr int kApplyWaves = 4, kApplyDepth = 2;
-constexpr int kFusedApplyDepth = 6;   // Q tiles per wave held in registers across the in-kernel waits
-constexpr int kApplyBatch = 1;        // tiles of a wave that share the arithmetic phase
+// Depths are tiles in flight per wave, [plain, RoPE]: a RoPE stage also holds its table rows.
+constexpr int kStateTile = 32, kStateWaves = 4, kApplyWaves = 4;
+constexpr int kStateDepth[2] = {2, 2};
+constexpr int kApplyDepth[2] = {2, 2};
+constexpr int kFusedStateDepth[2] = {2, 2};
+constexpr int kFusedApplyDepth[2] = {6, 2};   // Q tiles held in registers across the in-kernel waits
 constexpr bool kApplyHiLo = true;
 constexpr uint32_t kSpinLimit = 1u << 24;      // polls of ~100 ns: far beyond any real wait
 
@@ -45,14 +47,14 @@ struct Device {
 
 // The kernels in use, with and without RoPE (index 1: rotation table given).
 template <bool ROPE> struct Kernels {
-    static constexpr auto state = state_mfma_d64<kStateTile, kStateWaves, kStateDepth, true, ROPE>;
-    static constexpr auto state_partial = state_mfma_d64<kStateTile, kStateWaves, kStateDepth, false, ROPE>;
-    static constexpr auto apply = apply_mfma_d64<kApplyHiLo, kApplyWaves, kApplyDepth, kApplyBatch, ROPE>;
-    static constexpr auto fused =
-        block_step_mfma_d64<kStateTile, kStateWaves, kStateDepth, kApplyHiLo, kFusedApplyDepth, kApplyBatch, ROPE>;
+    static constexpr auto state = state_mfma_d64<kStateTile, kStateWaves, kStateDepth[ROPE], true, ROPE>;
+    static constexpr auto state_partial = state_mfma_d64<kStateTile, kStateWaves, kStateDepth[ROPE], false, ROPE>;
+    static constexpr auto apply = apply_mfma_d64<kApplyHiLo, kApplyWaves, kApplyDepth[ROPE], ROPE>;
+    static constexpr auto fused = block_step_mfma_d64<kStateTile, kStateWaves, kFusedStateDepth[ROPE], kApplyHiLo,
+                                                      kFusedApplyDepth[ROPE], ROPE>;
     static constexpr int state_lds = state_lds_bytes<kStateTile, kStateWaves>();
-    static constexpr int apply_lds = apply_lds_bytes<kApplyWaves, kApplyBatch, ROPE>();
-    static constexpr int fused_lds = block_step_lds_bytes<kStateTile, kStateWaves, kApplyBatch, ROPE>();
+    static constexpr int apply_lds = apply_lds_bytes<kApplyWaves, ROPE>();
+    static constexpr int fused_lds = block_step_lds_bytes<kStateTile, kStateWaves, ROPE>();
 };
 
 template <bool ROPE> void init_kernels(Device &d)
@@ -144,6 +146,13 @@ sv_status check_desc(const sv_tensor_desc *t, Shape *s)
     return SV_OK;
 }
 
+// The MFMA kernels address a head's tokens (and the rotation table) with 32-bit byte offsets.
+bool mfma_path(const Shape &s, const float *rope)
+{
+    constexpr int64_t kLimit = int64_t(1) << 31;
+    return s.bf16 && s.d == 64 && (int64_t)s.N * s.st.n * 2 < kLimit && (!rope || (int64_t)s.N * 256 < kLimit);
+}
+
 sv_status check_range(const Shape &s, int32_t t0, int32_t t1)
 {
     return (t0 < 0 || t1 < t0 || t1 > s.N) ? SV_ERR_RANGE : SV_OK;
@@ -191,7 +200,7 @@ sv_status enqueue_state(const void *K, const void *V, const float *rope, const S
         else state_reduce<32><<<rgrid, kThreads, 0, stream>>>(wsf, 0, 0, S_in, z_in, S_out, z_out);
         return launch_status();
     }
-    if (s.bf16 && s.d == 64) {
+    if (mfma_path(s, rope)) {
         const int C = plan_chunks(s.BH, n, kStateTile * kStateWaves, dev.num_cu);
         auto *k = static_cast<const uint16_t *>(K);
         auto *v = static_cast<const uint16_t *>(V);
@@ -199,10 +208,13 @@ sv_status enqueue_state(const void *K, const void *V, const float *rope, const S
         else launch_state_mfma<false>(k, v, rope, s, t0, t1, C, S_in, z_in, S_out, z_out, ws, dev, rgrid, stream);
         return launch_status();
     }
-    // fp32 validation mode and bf16 d = 32: plain-FMA partials, then the fixed-order reduction
+    // fp32 validation mode, bf16 d = 32 and oversized heads: plain-FMA partials, then the fixed-order reduction
     const int C = plan_chunks(s.BH, n, 32, 2 * dev.num_cu);
     const dim3 grid(C, s.BH);
-    if (s.bf16) {
+    if (s.bf16 && s.d == 64) {
+        state_partial_generic<uint16_t, 64><<<grid, kThreads, 0, stream>>>(
+            static_cast<const uint16_t *>(K), static_cast<const uint16_t *>(V), rope, s.st, s.H, t0, t1, C, wsf);
+    } else if (s.bf16) {
         state_partial_generic<uint16_t, 32><<<grid, kThreads, 0, stream>>>(
             static_cast<const uint16_t *>(K), static_cast<const uint16_t *>(V), rope, s.st, s.H, t0, t1, C, wsf);
     } else if (s.d == 64) {
@@ -224,7 +236,7 @@ sv_status enqueue_apply(const void *Q, const float *rope, const Shape &s, int t0
     if (n == 0) return SV_OK;
     const Device &dev = device_info();
     if (!dev.ok) return SV_ERR_LAUNCH;
-    if (s.bf16 && s.d == 64) {
+    if (mfma_path(s, rope)) {
         int C = dev.num_cu / s.BH;
         const int steps = (n + kApplyTile * kApplyWaves - 1) / (kApplyTile * kApplyWaves);
         if (C > steps) C = steps;
@@ -244,7 +256,11 @@ sv_status enqueue_apply(const void *Q, const float *rope, const Shape &s, int t0
     const int n_tiles = (n + tile - 1) / tile;
     if (C > n_tiles) C = n_tiles;
     const dim3 grid(C, s.BH);
-    if (s.bf16) {
+    if (s.bf16 && s.d == 64) {
+        apply_generic<uint16_t, 64><<<grid, kThreads, 0, stream>>>(static_cast<const uint16_t *>(Q),
+                                                                  static_cast<uint16_t *>(O), rope, s.st, s.H, t0, t1,
+                                                                  C, S, z, eps);
+    } else if (s.bf16) {
         apply_generic<uint16_t, 32><<<grid, kThreads, 0, stream>>>(static_cast<const uint16_t *>(Q),
                                                                   static_cast<uint16_t *>(O), rope, s.st, s.H, t0, t1,
                                                                   C, S, z, eps);
@@ -309,7 +325,7 @@ sv_status do_block_step(const void *Qb, const void *Kb, const void *Vb, const sv
         z_out = S_out + (size_t)s.BH * s.d * s.d;
     }
     auto hs = static_cast<hipStream_t>(stream);
-    if (s.bf16 && s.d == 64) {
+    if (mfma_path(s, rope)) {
         const Device &dev = device_info();
         if (!dev.ok) return SV_ERR_LAUNCH;
         // One launch when the whole grid can be resident at once (needed by the in-kernel waits).

@@ -42,6 +42,7 @@ class Workload:
     n_blocks: int = 0
     per_block_seed: bool = False
     eps: float = 1e-6
+    grid: tuple = ()    # (latent frames, rows, cols) of the N tokens, when they form a video volume
 
     @property
     def elem_bytes(self) -> int:
@@ -67,20 +68,20 @@ class Workload:
 WORKLOADS = {
     # 4 latent frames x 16 x 16 tokens, fp32 validation mode
     "tiny_f32": Workload("tiny_f32", B=1, H=2, N=4 * 16 * 16, d=32, dtype="f32",
-                         scale=1.0, seed=1001),
+                         scale=1.0, seed=1001, grid=(4, 16, 16)),
     # 480p-like bidirectional layer
     "bidir_480p": Workload("bidir_480p", B=1, H=32, N=21 * 30 * 52, d=64,
-                           dtype="bf16", scale=0.5, seed=1002),
+                           dtype="bf16", scale=0.5, seed=1002, grid=(21, 30, 52)),
     # 720p-like bidirectional layer, conditional + unconditional pair
     "bidir_720p": Workload("bidir_720p", B=2, H=32, N=21 * 45 * 80, d=64,
-                           dtype="bf16", scale=0.5, seed=1003),
+                           dtype="bf16", scale=0.5, seed=1003, grid=(21, 45, 80)),
     # block-causal, 10 blocks of 3 latent frames x 30 x 52
     "block_480p": Workload("block_480p", B=1, H=32, N=3 * 30 * 52, d=64,
-                           dtype="bf16", scale=0.5, seed=1004, n_blocks=10),
+                           dtype="bf16", scale=0.5, seed=1004, n_blocks=10, grid=(3, 30, 52)),
     # minute-length stream, 80 blocks of 3 latent frames x 45 x 80
     "stream_720p": Workload("stream_720p", B=1, H=32, N=3 * 45 * 80, d=64,
                             dtype="bf16", scale=0.5, seed=5000, n_blocks=80,
-                            per_block_seed=True),
+                            per_block_seed=True, grid=(3, 45, 80)),
 }
 
 
