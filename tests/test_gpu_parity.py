@@ -127,6 +127,44 @@ def test_strided_token_layout():
     metrics.check(to_host(O), O_ref, "bf16", "strided O")
 
 
+@pytest.mark.parametrize("log2_stride,path", [(19, "MFMA kernels, offsets near 1 GiB"),
+                                              (20, "head spans more than 2 GiB: generic kernels")])
+def test_far_apart_token_rows(log2_stride, path):
+    """Token rows 1-2 MiB apart: the bf16 d=64 kernels address a head with 32-bit byte offsets and
+    the library must route heads that do not fit to kernels that do not."""
+    import torch
+    B, H, N, d = 1, 1, 1100, 64
+    stride_n = 1 << log2_stride
+    say(f"far_apart_token_rows stride_n=2^{log2_stride} ({path})")
+    Q, K, V = _draw(7400, B, H, N, d, "bf16")
+    O_ref, S_ref, z_ref = orc.bidirectional(Q, K, V, 1e-6)
+
+    def spread(x):
+        base = torch.zeros(N * stride_n, dtype=torch.bfloat16, device="cuda")
+        view = base.as_strided((B, H, N, d), (N * stride_n, N * stride_n, stride_n, 1))
+        if x is not None:
+            view.copy_(to_dev(x))
+        return view
+
+    Qd, Kd, Vd, O = spread(Q), spread(K), spread(V), spread(None)
+    dsc = sv.desc_of(Qd)
+    assert dsc.stride_n == stride_n
+    S, z = new_state(B, H, d)
+    ws = new_workspace(B, H, N, d)
+    sv.sv_linattn_state(Kd, Vd, dsc, 0, N, 0, S, z, ws)
+    sv.sv_linattn_apply(Qd, dsc, 0, N, S, z, 1e-6, O)
+    torch.cuda.synchronize()
+    _check_state(S, z, S_ref, z_ref, "far apart")
+    metrics.check(to_host(O), O_ref, "bf16", "far apart O")
+    # the block step over the same rows, from a zero state, must agree with the two calls
+    S2, z2 = new_state(B, H, d)
+    O2 = spread(None)
+    sv.sv_block_linattn_step(Qd, Kd, Vd, dsc, S2, z2, 1e-6, O2, ws)
+    torch.cuda.synchronize()
+    _check_state(S2, z2, S_ref, z_ref, "far apart block step")
+    metrics.check(to_host(O2), O_ref, "bf16", "far apart block step O")
+
+
 # ---- degenerate rows -------------------------------------------------------------------------
 
 @pytest.mark.parametrize("dtype,d", [("bf16", 64), ("f32", 32)])
