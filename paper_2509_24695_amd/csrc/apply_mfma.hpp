@@ -260,7 +260,7 @@ __global__ __launch_bounds__(64 * WAVES, 1) void apply_mfma_d64(
     uint16_t *Oh = O + b * st.b + h * st.h;
     const int n_tiles = (t1 - t0 + kApplyTile - 1) / kApplyTile;
 
-    ApplyStream<DEPTH, ROPE> stream(Qh, Oh, rope, st.n, t1, TileWalk(t0, WAVES * c + wave, WAVES * C, n_tiles));
+    ApplyStream<DEPTH, ROPE> stream(Qh, Oh, rope, st.n, t1, TileWalk(t0, WAVES * c + wave, WAVES * C, n_tiles, bh));
     apply_prefetch<0, DEPTH>(stream, lane);   // in flight while S is fetched
     ApplyOperands<HILO> A;
     A.template load<false>(S + (size_t)bh * 64 * 64, z + (size_t)bh * 64, lane);

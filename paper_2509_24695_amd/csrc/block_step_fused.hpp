@@ -51,7 +51,7 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma_d64(
 
     // ---- this wave's first two tiles of Q_b are requested right away: they arrive during the state
     //      phase and make no later load wait behind them ---------------------------------------------
-    const TileWalk walk(0, WAVES * c + wave, WAVES * C, (N + TILE - 1) / TILE);
+    const TileWalk walk(0, WAVES * c + wave, WAVES * C, (N + TILE - 1) / TILE, bh);
     static_assert(TILE == kApplyTile, "one tile walk serves both phases");
     constexpr int kEarly = DEPTH_A < 2 ? DEPTH_A : 2;
     ApplyStream<DEPTH_A, ROPE> qstream(Q + head_off, O + head_off, rope, st.n, N, walk);
