@@ -35,8 +35,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 # 128-byte requests these kernels and the copy issue as 64 bytes; WRITE_SIZE x 1.0000).  Source:
 # profiles/traffic_pmc_bidir_480p.txt.  Algorithmic bytes per launch are 268 369 920.
 MEASURED_TRAFFIC_BYTES = {
-    ("apply", "bidir_480p"): int((67677.1 * 1.99965 + 131040.0) * 1024),
-    ("state", "bidir_480p"): int((133355.3 * 1.99965 + 4688.0) * 1024),
+    ("apply", "bidir_480p"): int((67687.9 * 1.99964 + 131040.1) * 1024),
+    ("state", "bidir_480p"): int((133348.0 * 1.99964 + 4688.0) * 1024),
 }
 
 
