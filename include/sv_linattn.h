@@ -20,7 +20,8 @@
  *    call returns.  The library never allocates, frees or keeps a pointer.
  *  - Token tensors are [B][H][N][d] with d contiguous; the other three strides
  *    are given in elements.  Pointers must be 16-byte aligned and the strides
- *    multiples of 16 bytes.  d must be 32 or 64.
+ *    multiples of 16 bytes.  d must be 32, 64, 112 or 128 (112 is the head
+ *    dimension of the paper's 2B model, Appendix model-configuration table).
  *  - S is [B][H][d][d] fp32, row = key feature k, column = value feature v, so
  *    that out = phi(Q) * S.  z is [B][H][d] fp32.  Both dense.
  *  - SV_BF16 tokens: bf16 storage, bf16 MFMA products with fp32 accumulation,
@@ -48,7 +49,7 @@ typedef enum {
     SV_OK = 0,
     SV_ERR_NULL = 1,        /* a required pointer is NULL                           */
     SV_ERR_SHAPE = 2,       /* B, H, N <= 0, stride_n < d, or overlapping strides    */
-    SV_ERR_UNSUPPORTED = 3, /* d not in {32, 64} or unknown dtype                    */
+    SV_ERR_UNSUPPORTED = 3, /* d not in {32, 64, 112, 128} or unknown dtype          */
     SV_ERR_ALIGN = 4,       /* pointer or stride not a multiple of 16 bytes          */
     SV_ERR_RANGE = 5,       /* token range outside [0, N], or eps negative/non-finite */
     SV_ERR_WORKSPACE = 6,   /* workspace smaller than sv_linattn_workspace_bytes()   */

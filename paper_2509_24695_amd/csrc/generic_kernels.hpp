@@ -2,7 +2,8 @@
 // fixed-order partial-state reduction used by all paths.
 //
 // These serve the fp32 validation mode (results within 1e-5 of a float64
-// evaluation) and the bf16 shapes that have no MFMA kernel.  Products are fp32
+// evaluation) and the bf16 shapes that have no MFMA kernel.  D is the head
+// dimension: 32, 64, 112 or 128.  Products are fp32
 // FMAs in token order inside a chunk; chunks are combined by state_reduce.
 #pragma once
 
@@ -14,7 +15,9 @@ namespace sv {
 //   ws[(bh*C + c)][k*D + v] = sum_{j in chunk c} phi(K[j][k]) V[j][v]     (Sec. 3.2, numerator bracket)
 //   ws[(bh*C + c)][D*D + k] = sum_{j in chunk c} phi(K[j][k])             (denominator bracket)
 // grid = (C, B*H), block = 256.  Tiles hold TT tokens; chunk c owns tiles
-// [c*T/C, (c+1)*T/C) of the T tiles that cover [t0, t1).
+// [c*T/C, (c+1)*T/C) of the T tiles that cover [t0, t1).  Row k of S is shared
+// by TPR threads (the largest power of two with D*TPR <= 256); threads past
+// D*TPR only help with the loads.
 // rope != null: the keys that meet V are rotated after the ReLU (table row = token index,
 // D/2 (cos, sin) pairs); the key sum uses the plain ones.
 template <typename T, int D>
@@ -23,8 +26,9 @@ __global__ __launch_bounds__(kThreads) void state_partial_generic(
     int t1, int C, float *__restrict__ ws)
 {
     constexpr int TT = 32;
-    constexpr int EPT = D * D / kThreads;   // S elements per thread (one row segment)
-    constexpr int TPR = D / EPT;            // threads per S row
+    constexpr int TPR = D <= 32 ? 8 : (D <= 64 ? 4 : 2);   // threads per S row
+    constexpr int EPT = D / TPR;                           // S elements per thread (one row segment)
+    static_assert(D % TPR == 0 && D * TPR <= kThreads, "row segments tile the state");
     __shared__ float sK[TT][D];             // keys as they enter S (rotated when rope is given)
     __shared__ float sP[TT][D];             // phi(K) as it enters the key sum
     __shared__ float sV[TT][D];
@@ -39,7 +43,8 @@ __global__ __launch_bounds__(kThreads) void state_partial_generic(
     const int tile_lo = chunk_tile_begin(c, C, n_tiles);
     const int tile_hi = chunk_tile_begin(c + 1, C, n_tiles);
 
-    const int k = tid / TPR, v0 = (tid % TPR) * EPT;
+    const bool owner = tid < D * TPR;
+    const int k = owner ? tid / TPR : 0, v0 = (tid % TPR) * EPT;
     float acc[EPT];
 #pragma unroll
     for (int e = 0; e < EPT; ++e) acc[e] = 0.f;
@@ -69,16 +74,19 @@ __global__ __launch_bounds__(kThreads) void state_partial_generic(
             sV[j][2 * p + 1] = vb;
         }
         __syncthreads();
+        if (owner) {
 #pragma unroll 4
-        for (int j = 0; j < TT; ++j) {
-            const float a = sK[j][k];
-            zacc += sP[j][k];
+            for (int j = 0; j < TT; ++j) {
+                const float a = sK[j][k];
+                zacc += sP[j][k];
 #pragma unroll
-            for (int e = 0; e < EPT; ++e) acc[e] = fmaf(a, sV[j][v0 + e], acc[e]);
+                for (int e = 0; e < EPT; ++e) acc[e] = fmaf(a, sV[j][v0 + e], acc[e]);
+            }
         }
         __syncthreads();
     }
 
+    if (!owner) return;
     float *out = ws + ((int64_t)bh * C + c) * (D * D + D);
 #pragma unroll
     for (int e = 0; e < EPT; ++e) out[k * D + v0 + e] = acc[e];
@@ -109,9 +117,14 @@ __global__ __launch_bounds__(kThreads) void state_reduce(
 }
 
 // O[i][v] = (sum_k phi(Q[i][k]) S[k][v]) / (sum_k phi(Q[i][k]) z[k] + eps)   (Sec. 3.2, right-hand form)
-// grid = (C, B*H), block = 256.  The head's S and z stay in LDS for the whole
-// token range of the workgroup.
+// grid = (C, B*H), block = 256, dynamic LDS = apply_generic_lds_bytes<D>().  The head's
+// S and z stay in LDS for the whole token range of the workgroup; D/4 threads
+// serve one token, 256/(D/4) tokens (rounded down) make a tile.
 // rope != null: the numerator uses queries rotated after the ReLU, the denominator the plain ones.
+template <int D> __host__ __device__ constexpr int apply_generic_tile() { return kThreads / (D / 4); }
+template <int D> __host__ __device__ constexpr int apply_generic_lds_bytes() {
+    return (D * D + D + 2 * apply_generic_tile<D>() * D) * (int)sizeof(float);
+}
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void apply_generic(
     const T *__restrict__ Q, T *__restrict__ O, const float *__restrict__ rope, TokStrides st, int H, int t0, int t1,
@@ -119,11 +132,12 @@ __global__ __launch_bounds__(kThreads) void apply_generic(
 {
     constexpr int VPT = 4;                   // outputs per thread
     constexpr int TPT = D / VPT;             // threads per token
-    constexpr int TT = kThreads / TPT;       // tokens per tile
-    __shared__ float sS[D][D];
-    __shared__ float sz[D];
-    __shared__ float sQ[TT][D];              // queries of the numerator (rotated when rope is given)
-    __shared__ float sP[TT][D];              // phi(Q) of the denominator
+    constexpr int TT = apply_generic_tile<D>();   // tokens per tile
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    float (*sS)[D] = reinterpret_cast<float (*)[D]>(lds_raw);
+    float *sz = reinterpret_cast<float *>(lds_raw) + D * D;
+    float (*sQ)[D] = reinterpret_cast<float (*)[D]>(sz + D);        // queries of the numerator (rotated with rope)
+    float (*sP)[D] = reinterpret_cast<float (*)[D]>(sz + D + TT * D);   // phi(Q) of the denominator
 
     const int tid = threadIdx.x;
     const int c = blockIdx.x, bh = blockIdx.y;
@@ -138,6 +152,7 @@ __global__ __launch_bounds__(kThreads) void apply_generic(
     const int tile_lo = chunk_tile_begin(c, C, n_tiles);
     const int tile_hi = chunk_tile_begin(c + 1, C, n_tiles);
     const int j = tid / TPT, v0 = (tid % TPT) * VPT;
+    const bool worker = j < TT;              // 256 is not a multiple of D/4 for every D
 
     for (int tile = tile_lo; tile < tile_hi; ++tile) {
         const int tok0 = t0 + tile * TT;
@@ -162,15 +177,17 @@ __global__ __launch_bounds__(kThreads) void apply_generic(
         __syncthreads();
         float num[VPT] = {0.f, 0.f, 0.f, 0.f};
         float den = 0.f;
+        if (worker) {
 #pragma unroll 8
-        for (int k = 0; k < D; ++k) {
-            const float q = sQ[j][k];
-            den = fmaf(sP[j][k], sz[k], den);
+            for (int k = 0; k < D; ++k) {
+                const float q = sQ[j][k];
+                den = fmaf(sP[j][k], sz[k], den);
 #pragma unroll
-            for (int e = 0; e < VPT; ++e) num[e] = fmaf(q, sS[k][v0 + e], num[e]);
+                for (int e = 0; e < VPT; ++e) num[e] = fmaf(q, sS[k][v0 + e], num[e]);
+            }
         }
         const int tok = tok0 + j;
-        if (tok < t1) {
+        if (worker && tok < t1) {
             const float dd = den + eps;
 #pragma unroll
             for (int e = 0; e < VPT; ++e) Elem<T>::store(Oh + (int64_t)tok * st.n + v0 + e, num[e] / dd);

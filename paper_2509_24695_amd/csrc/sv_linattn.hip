@@ -8,6 +8,7 @@
 #include <atomic>
 #include <chrono>
 #include <mutex>
+#include <type_traits>
 
 #include "apply_mfma.hpp"
 #include "block_step_fused.hpp"
@@ -77,6 +78,19 @@ template <bool ROPE> void init_kernels(Device &d)
     d.state_resident_wgs[ROPE] = per_cu * d.num_cu;
 }
 
+bool head_dim_ok(int d) { return d == 32 || d == 64 || d == 112 || d == 128; }
+
+// Calls f(std::integral_constant<int, D>) for the supported head dimension d.
+template <typename F> void with_head_dim(int d, F &&f)
+{
+    switch (d) {
+    case 32: f(std::integral_constant<int, 32>{}); break;
+    case 64: f(std::integral_constant<int, 64>{}); break;
+    case 112: f(std::integral_constant<int, 112>{}); break;
+    default: f(std::integral_constant<int, 128>{}); break;
+    }
+}
+
 // Per-device facts, queried once (no device memory is touched).
 const Device &device_info()
 {
@@ -95,6 +109,14 @@ const Device &device_info()
         d.num_cu = prop.multiProcessorCount;
         init_kernels<false>(d);
         init_kernels<true>(d);
+        for (int hd : {32, 64, 112, 128})          // the larger generic apply kernels need more than 64 KB of LDS
+            with_head_dim(hd, [&](auto D) {
+                const auto attr = hipFuncAttributeMaxDynamicSharedMemorySize;
+                (void)hipFuncSetAttribute(reinterpret_cast<const void *>(apply_generic<uint16_t, D()>), attr,
+                                          apply_generic_lds_bytes<D()>());
+                (void)hipFuncSetAttribute(reinterpret_cast<const void *>(apply_generic<float, D()>), attr,
+                                          apply_generic_lds_bytes<D()>());
+            });
         (void)hipGetLastError();
         d.ok = d.num_cu > 0;
     }
@@ -131,7 +153,7 @@ sv_status check_desc(const sv_tensor_desc *t, Shape *s)
 {
     if (!t) return SV_ERR_NULL;
     if (t->dtype != SV_BF16 && t->dtype != SV_F32) return SV_ERR_UNSUPPORTED;
-    if (t->d != 32 && t->d != 64) return SV_ERR_UNSUPPORTED;
+    if (!head_dim_ok(t->d)) return SV_ERR_UNSUPPORTED;
     if (t->B <= 0 || t->H <= 0 || t->N <= 0) return SV_ERR_SHAPE;
     if ((int64_t)t->B * t->H > 65535) return SV_ERR_SHAPE;           // grid.y limit
     if (t->stride_n < t->d || t->stride_b < 0 || t->stride_h < 0) return SV_ERR_SHAPE;
@@ -196,8 +218,9 @@ sv_status enqueue_state(const void *K, const void *V, const float *rope, const S
     const dim3 rgrid((E + kThreads - 1) / kThreads, s.BH);
     float *wsf = static_cast<float *>(ws);
     if (n == 0) {                                   // the empty sum: zero fill, or a copy of the carried state
-        if (s.d == 64) state_reduce<64><<<rgrid, kThreads, 0, stream>>>(wsf, 0, 0, S_in, z_in, S_out, z_out);
-        else state_reduce<32><<<rgrid, kThreads, 0, stream>>>(wsf, 0, 0, S_in, z_in, S_out, z_out);
+        with_head_dim(s.d, [&](auto D) {
+            state_reduce<D()><<<rgrid, kThreads, 0, stream>>>(wsf, 0, 0, S_in, z_in, S_out, z_out);
+        });
         return launch_status();
     }
     if (mfma_path(s, rope)) {
@@ -211,21 +234,15 @@ sv_status enqueue_state(const void *K, const void *V, const float *rope, const S
     // fp32 validation mode, bf16 d = 32 and oversized heads: plain-FMA partials, then the fixed-order reduction
     const int C = plan_chunks(s.BH, n, 32, 2 * dev.num_cu);
     const dim3 grid(C, s.BH);
-    if (s.bf16 && s.d == 64) {
-        state_partial_generic<uint16_t, 64><<<grid, kThreads, 0, stream>>>(
-            static_cast<const uint16_t *>(K), static_cast<const uint16_t *>(V), rope, s.st, s.H, t0, t1, C, wsf);
-    } else if (s.bf16) {
-        state_partial_generic<uint16_t, 32><<<grid, kThreads, 0, stream>>>(
-            static_cast<const uint16_t *>(K), static_cast<const uint16_t *>(V), rope, s.st, s.H, t0, t1, C, wsf);
-    } else if (s.d == 64) {
-        state_partial_generic<float, 64><<<grid, kThreads, 0, stream>>>(
-            static_cast<const float *>(K), static_cast<const float *>(V), rope, s.st, s.H, t0, t1, C, wsf);
-    } else {
-        state_partial_generic<float, 32><<<grid, kThreads, 0, stream>>>(
-            static_cast<const float *>(K), static_cast<const float *>(V), rope, s.st, s.H, t0, t1, C, wsf);
-    }
-    if (s.d == 64) state_reduce<64><<<rgrid, kThreads, 0, stream>>>(wsf, C, C, S_in, z_in, S_out, z_out);
-    else state_reduce<32><<<rgrid, kThreads, 0, stream>>>(wsf, C, C, S_in, z_in, S_out, z_out);
+    with_head_dim(s.d, [&](auto D) {
+        if (s.bf16)
+            state_partial_generic<uint16_t, D()><<<grid, kThreads, 0, stream>>>(
+                static_cast<const uint16_t *>(K), static_cast<const uint16_t *>(V), rope, s.st, s.H, t0, t1, C, wsf);
+        else
+            state_partial_generic<float, D()><<<grid, kThreads, 0, stream>>>(
+                static_cast<const float *>(K), static_cast<const float *>(V), rope, s.st, s.H, t0, t1, C, wsf);
+        state_reduce<D()><<<rgrid, kThreads, 0, stream>>>(wsf, C, C, S_in, z_in, S_out, z_out);
+    });
     return launch_status();
 }
 
@@ -256,21 +273,15 @@ sv_status enqueue_apply(const void *Q, const float *rope, const Shape &s, int t0
     const int n_tiles = (n + tile - 1) / tile;
     if (C > n_tiles) C = n_tiles;
     const dim3 grid(C, s.BH);
-    if (s.bf16 && s.d == 64) {
-        apply_generic<uint16_t, 64><<<grid, kThreads, 0, stream>>>(static_cast<const uint16_t *>(Q),
-                                                                  static_cast<uint16_t *>(O), rope, s.st, s.H, t0, t1,
-                                                                  C, S, z, eps);
-    } else if (s.bf16) {
-        apply_generic<uint16_t, 32><<<grid, kThreads, 0, stream>>>(static_cast<const uint16_t *>(Q),
-                                                                  static_cast<uint16_t *>(O), rope, s.st, s.H, t0, t1,
-                                                                  C, S, z, eps);
-    } else if (s.d == 64) {
-        apply_generic<float, 64><<<grid, kThreads, 0, stream>>>(static_cast<const float *>(Q), static_cast<float *>(O),
-                                                               rope, s.st, s.H, t0, t1, C, S, z, eps);
-    } else {
-        apply_generic<float, 32><<<grid, kThreads, 0, stream>>>(static_cast<const float *>(Q), static_cast<float *>(O),
-                                                               rope, s.st, s.H, t0, t1, C, S, z, eps);
-    }
+    with_head_dim(s.d, [&](auto D) {
+        constexpr int lds = apply_generic_lds_bytes<D()>();
+        if (s.bf16)
+            apply_generic<uint16_t, D()><<<grid, kThreads, lds, stream>>>(
+                static_cast<const uint16_t *>(Q), static_cast<uint16_t *>(O), rope, s.st, s.H, t0, t1, C, S, z, eps);
+        else
+            apply_generic<float, D()><<<grid, kThreads, lds, stream>>>(
+                static_cast<const float *>(Q), static_cast<float *>(O), rope, s.st, s.H, t0, t1, C, S, z, eps);
+    });
     return launch_status();
 }
 
@@ -357,7 +368,7 @@ extern "C" {
 
 size_t sv_linattn_workspace_bytes(int32_t B, int32_t H, int32_t n_tokens, int32_t d)
 {
-    if (B <= 0 || H <= 0 || n_tokens < 0 || (d != 32 && d != 64)) return 0;
+    if (B <= 0 || H <= 0 || n_tokens < 0 || !head_dim_ok(d)) return 0;
     if ((int64_t)B * H > 65535) return 0;
     return workspace_bytes(B * H, d);
 }

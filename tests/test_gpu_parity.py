@@ -46,7 +46,8 @@ def test_tiny_f32_bidirectional():
 
 # ---- small shapes: several tiles, ragged tails, both dtypes and head dims ----------------------
 
-@pytest.mark.parametrize("dtype,d", [("bf16", 64), ("bf16", 32), ("f32", 64), ("f32", 32)])
+@pytest.mark.parametrize("dtype,d", [("bf16", 64), ("bf16", 32), ("f32", 64), ("f32", 32),
+                                     ("bf16", 112), ("bf16", 128), ("f32", 112), ("f32", 128)])
 @pytest.mark.parametrize("B,H,N", [(1, 1, 1), (1, 2, 7), (2, 3, 33), (1, 2, 100), (1, 4, 1000), (2, 2, 4681)])
 def test_bidirectional_small(dtype, d, B, H, N):
     say(f"bidirectional_small dtype={dtype} d={d} B={B} H={H} N={N}")
@@ -57,7 +58,7 @@ def test_bidirectional_small(dtype, d, B, H, N):
     metrics.check(to_host(O), O_ref, dtype, "O")
 
 
-@pytest.mark.parametrize("dtype,d", [("bf16", 64), ("f32", 32)])
+@pytest.mark.parametrize("dtype,d", [("bf16", 64), ("f32", 32), ("bf16", 112), ("bf16", 128), ("f32", 112)])
 def test_state_range_and_accumulate(dtype, d):
     """Token ranges and accumulate semantics; chunked sums equal the one-shot sum."""
     import torch
@@ -85,7 +86,7 @@ def test_state_range_and_accumulate(dtype, d):
     assert not to_host(S).any() and not to_host(z).any()
 
 
-@pytest.mark.parametrize("dtype,d", [("bf16", 64), ("f32", 32)])
+@pytest.mark.parametrize("dtype,d", [("bf16", 64), ("f32", 32), ("bf16", 112), ("bf16", 128), ("f32", 112)])
 def test_apply_range_leaves_other_rows_untouched(dtype, d):
     import torch
     B, H, N = 1, 2, 500
@@ -167,7 +168,7 @@ def test_far_apart_token_rows(log2_stride, path):
 
 # ---- degenerate rows -------------------------------------------------------------------------
 
-@pytest.mark.parametrize("dtype,d", [("bf16", 64), ("f32", 32)])
+@pytest.mark.parametrize("dtype,d", [("bf16", 64), ("f32", 32), ("bf16", 112), ("bf16", 128), ("f32", 112)])
 def test_degenerate_rows(dtype, d):
     say(f"degenerate_rows dtype={dtype} d={d}")
     B, H, N = 1, 2, 70
@@ -203,7 +204,7 @@ def _gpu_stream(blocks, eps, B, H, d):
     return outs, S, z
 
 
-@pytest.mark.parametrize("dtype,d", [("bf16", 64), ("f32", 32)])
+@pytest.mark.parametrize("dtype,d", [("bf16", 64), ("f32", 32), ("bf16", 112), ("bf16", 128), ("f32", 112)])
 def test_block_stream_small(dtype, d):
     B, H = 1, 3
     sizes = [130, 1, 64, 333, 17]
@@ -335,7 +336,8 @@ def test_bounded_waits_never_time_out():
 
 # ---- look-ahead step: the cache is used but not updated (noisy passes of Alg. 1) -------------------
 
-@pytest.mark.parametrize("dtype,d,H", [("bf16", 64, 8), ("f32", 32, 2), ("bf16", 64, 300)])
+@pytest.mark.parametrize("dtype,d,H", [("bf16", 64, 8), ("f32", 32, 2), ("bf16", 64, 300), ("bf16", 112, 20),
+                                       ("bf16", 128, 7), ("f32", 128, 2)])
 def test_lookahead_leaves_state_untouched(dtype, d, H):
     import torch
     B, N0, N1 = 1, 900, 333

@@ -41,7 +41,8 @@ def _check_state(S, z, S_ref, z_ref, dtype, what):
     assert metrics.rel_l2(zg, z_ref) <= 1e-5 and metrics.max_rel(zg, z_ref) <= 1e-5, f"{what}: z"
 
 
-@pytest.mark.parametrize("dtype,d", [("bf16", 64), ("f32", 32), ("bf16", 32), ("f32", 64)])
+@pytest.mark.parametrize("dtype,d", [("bf16", 64), ("f32", 32), ("bf16", 32), ("f32", 64), ("bf16", 112), ("bf16", 128),
+                                     ("f32", 112)])
 @pytest.mark.parametrize("B,H,N", [(1, 1, 1), (2, 3, 33), (1, 4, 1000), (1, 2, 4681)])
 def test_rope_bidirectional(dtype, d, B, H, N):
     import torch
@@ -110,7 +111,8 @@ def test_zero_angles_equal_the_plain_kernels_bitwise():
     assert torch.equal(S1, S2) and torch.equal(z1, z2) and torch.equal(O1.view(torch.int16), O2.view(torch.int16))
 
 
-@pytest.mark.parametrize("dtype,d,H", [("bf16", 64, 32), ("f32", 32, 2), ("bf16", 64, 300)])
+@pytest.mark.parametrize("dtype,d,H", [("bf16", 64, 32), ("f32", 32, 2), ("bf16", 64, 300), ("bf16", 112, 20),
+                                       ("bf16", 128, 5)])
 def test_rope_block_stream_with_3d_table(dtype, d, H):
     """Blocks of latent frames with a 3-D table whose time axis continues across blocks; the last
     block is also run as a look-ahead first."""

@@ -28,7 +28,7 @@ def _relerr(a, b):
 
 # ---- P1: brute-force O(N^2) kernel-score attention --------------------------------------
 
-@pytest.mark.parametrize("N,d", [(1, 32), (2, 32), (7, 64), (64, 32), (65, 64)])
+@pytest.mark.parametrize("N,d", [(1, 32), (2, 32), (7, 64), (64, 32), (65, 64), (40, 112), (33, 128)])
 def test_bidirectional_equals_bruteforce_small(N, d):
     Q, K, V = _rand(10 + N, 1, 2, N, d)
     O, _, _ = orc.bidirectional(Q, K, V, 1e-6)
