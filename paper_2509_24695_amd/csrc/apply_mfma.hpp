@@ -1,4 +1,4 @@
-// bf16 MFMA apply for d = 64 on gfx950.
+// bf16 MFMA apply for d = 64, 112 and 128 on gfx950.
 //
 //   O[i][v] = (sum_k phi(Q[i][k]) S[k][v]) / (sum_k phi(Q[i][k]) z[k] + eps)
 //
@@ -23,61 +23,65 @@
 // in-order completion counter, and every stage issues a fixed number of both, so
 // a tile waits only for its own loads: the stores of earlier tiles and the loads
 // of later ones stay in flight.
+//
+// d = 112 and 128 (DP = 128): a wave produces 64 of a token's output features
+// (value block vb), so it keeps a 128 x 64 panel of S in registers and runs
+// twice as many k-steps over the whole query row; two waves of a workgroup
+// share each tile of Q (the second load is served by the caches) and write
+// the two halves of the O rows.  For d = 112 the features past 112 are
+// addressed out of range: they read as zeros and their stores are dropped.
 #pragma once
 
 #include "common.hpp"
-#include "state_mfma.hpp"   // kRowBytes
+#include "state_mfma.hpp"   // TileWalk, kOutOfRange handling
 #include "sync.hpp"
 
 namespace sv {
 
 constexpr int kApplyTile = 32;   // tokens per wave tile (the N dimension of the 32x32x16 MFMA)
 
-// The state of one head as MFMA A operands, per lane (m = lane%32, g = lane/32).
+// LDS row of a Q tile: DP bf16 features + 16 bytes of padding (bank spread, keeps 16-byte alignment).
+template <int DP> __host__ __device__ constexpr int apply_row_bytes() { return DP * 2 + 16; }
+
+// The state of one head as MFMA A operands for the 64 output features of value
+// block vb, per lane (m = lane%32, g = lane/32).
 //   S rows: MFMA row m of row block rb stands for output feature
-//     F(rb, m) = 32*((m/4)%2) + 16*rb + 4*(m/8) + m%4,
+//     64*vb + F(rb, m),  F(rb, m) = 32*((m/4)%2) + 16*rb + 4*(m/8) + m%4,
 //   chosen so that accumulator register i of a lane in half g' = lane/32 is
-//   output feature 32*g' + 16*rb + i of the lane's token.
+//   output feature 64*vb + 32*g' + 16*rb + i of the lane's token.
 //   z rows: row 0 = hi(z), row 1 = lo(z), rows 2..31 = 0.
-template <bool HILO>
+// The contraction runs over DP key features in DP/16 k-steps; S is d x d (row
+// length d) and z has d entries, anything past d counts as zero.
+template <int DP, bool HILO>
 struct ApplyOperands {
     static constexpr int NS = HILO ? 2 : 1;
-    bf16x8 s[NS][2][4];    // [hi/lo][row block][k-step]
-    bf16x8 zrow[4];        // [k-step]
+    static constexpr int KS = DP / 16;
+    bf16x8 s[NS][2][KS];   // [hi/lo][row block][k-step]
+    bf16x8 zrow[KS];       // [k-step]
 
     // COHERENT: the state was written by another workgroup of this same kernel.
     template <bool COHERENT>
-    __device__ __forceinline__ void load(const float *__restrict__ Sh, const float *__restrict__ zh, int lane)
+    __device__ __forceinline__ void load(const float *__restrict__ Sh, const float *__restrict__ zh, int d, int vb,
+                                         int lane)
     {
         const int m = lane & 31, g = lane >> 5;
-        float sv_[2][4][8];
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) {
-            const int F = 32 * ((m >> 2) & 1) + 16 * rb + 4 * (m >> 3) + (m & 3);
+            const int F = 64 * vb + 32 * ((m >> 2) & 1) + 16 * rb + 4 * (m >> 3) + (m & 3);
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
+            for (int ks = 0; ks < KS; ++ks) {
+                float sv_[8];
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    const float *p = Sh + (16 * ks + 8 * g + i) * 64 + F;
-                    sv_[rb][ks][i] = COHERENT ? load_coherent1(p) : *p;
+                    const int k = 16 * ks + 8 * g + i;
+                    const float *p = Sh + k * d + F;
+                    sv_[i] = 0.f;
+                    if (DP == 64 || (k < d && F < d)) sv_[i] = COHERENT ? load_coherent1(p) : *p;
                 }
-        }
-        float zv[4][8];
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const float *p = zh + 16 * ks + 8 * g + i;
-                zv[ks][i] = COHERENT ? load_coherent1(p) : *p;
-            }
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
                 uint32_t hi[4], lo[4];
 #pragma unroll
                 for (int p = 0; p < 4; ++p) {
-                    const float a = sv_[rb][ks][2 * p], b = sv_[rb][ks][2 * p + 1];
+                    const float a = sv_[2 * p], b = sv_[2 * p + 1];
                     hi[p] = pack_bf16x2(a, b);
                     lo[p] = pack_bf16x2(a - bf16_lo(hi[p]), b - bf16_hi(hi[p]));
                 }
@@ -85,12 +89,18 @@ struct ApplyOperands {
                 s[0][rb][ks] = __builtin_bit_cast(bf16x8, h4);
                 if (HILO) s[NS - 1][rb][ks] = __builtin_bit_cast(bf16x8, l4);
             }
+        }
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
+        for (int ks = 0; ks < KS; ++ks) {
             uint32_t w[4];
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
-                const float a = zv[ks][2 * p], b = zv[ks][2 * p + 1];
+                const int k = 16 * ks + 8 * g + 2 * p;
+                float a = 0.f, b = 0.f;
+                if (DP == 64 || k < d) {       // d is even: k and k + 1 exist together
+                    a = COHERENT ? load_coherent1(zh + k) : zh[k];
+                    b = COHERENT ? load_coherent1(zh + k + 1) : zh[k + 1];
+                }
                 const uint32_t hi = pack_bf16x2(a, b);
                 const uint32_t lo = pack_bf16x2(a - bf16_lo(hi), b - bf16_hi(hi));
                 w[p] = m == 0 ? hi : (m == 1 ? lo : 0u);
@@ -103,100 +113,120 @@ struct ApplyOperands {
 
 // One wave's token stream: buffer resources over the head's Q and O rows (and the
 // rotation table) below the end of the token range, the wave's tile walk (32
-// tokens per tile), and the register staging of DEPTH tiles in flight.
-template <int DEPTH, bool ROPE>
+// tokens per tile), and the register staging of DEPTH tiles in flight.  A Q row
+// takes DP/8 lanes of 16 bytes, so one load instruction covers 512/DP rows; the
+// wave writes output features 64*vb .. +64 (8 lanes of 16 bytes per row).
+template <int DP, int DEPTH, bool ROPE>
 struct ApplyStream {
+    static constexpr int LPR = DP / 8;            // lanes per Q row
+    static constexpr int RPI = kWave / LPR;       // Q rows per load instruction
+    static constexpr int NLD = kApplyTile / RPI;  // load instructions per tile
     rsrc_t rQ, rO, rT;
-    uint32_t row_bytes;
+    uint32_t row_bytes, table_row_bytes;
+    uint32_t lane_off_q, lane_off_o, lane_off_t;
+    bool valid_q, valid_o;
     TileWalk walk;
-    u32x4 q[DEPTH][kApplyTile / 8];
-    f32x4 cs[ROPE ? DEPTH : 1][kApplyTile / 8][2];
+    u32x4 q[DEPTH][NLD];
+    f32x4 cs[ROPE ? DEPTH : 1][NLD][2];
 
     __device__ __forceinline__ ApplyStream(const uint16_t *Qh, uint16_t *Oh, const float *rope, int64_t stride_n,
-                                           int t1, const TileWalk &w)
+                                           int t1, int d, int vb, int lane, const TileWalk &w)
         : rQ(make_rsrc(Qh, (uint32_t)t1 * (uint32_t)stride_n * 2u)),
           rO(make_rsrc(Oh, (uint32_t)t1 * (uint32_t)stride_n * 2u)),
-          rT(make_rsrc(rope, ROPE ? (uint32_t)t1 * 256u : 0u)), row_bytes((uint32_t)stride_n * 2u), walk(w) {}
+          rT(make_rsrc(rope, ROPE ? (uint32_t)t1 * (uint32_t)d * 4u : 0u)), row_bytes((uint32_t)stride_n * 2u),
+          table_row_bytes((uint32_t)d * 4u), walk(w)
+    {
+        const uint32_t qrow = (uint32_t)(lane / LPR), qcol = (uint32_t)(lane % LPR);
+        lane_off_q = qrow * row_bytes + qcol * 16u;
+        lane_off_t = qrow * table_row_bytes + qcol * 32u;
+        valid_q = (int)qcol * 8 < d;
+        lane_off_o = (uint32_t)(lane >> 3) * row_bytes + (uint32_t)vb * 128u + (uint32_t)(lane & 7) * 16u;
+        valid_o = vb * 64 + (lane & 7) * 8 < d;
+    }
 
     // Requests the wave's i-th tile into stage s; past the share nothing is read.
-    __device__ __forceinline__ void request(int s, int i, int lane)
+    __device__ __forceinline__ void request(int s, int i)
     {
-        token_tile_load<kApplyTile>(rQ, walk.offset<kApplyTile>(i, row_bytes), row_bytes, lane, q[s]);
-        if (ROPE) rope_tile_load<kApplyTile>(rT, walk.offset<kApplyTile>(i, 256u), lane, cs[ROPE ? s : 0]);
+        const uint32_t base = valid_q ? walk.offset<kApplyTile>(i, row_bytes) : kOutOfRange;
+#pragma unroll
+        for (int j = 0; j < NLD; ++j)
+            q[s][j] = load_stream16(rQ, base + lane_off_q + (uint32_t)j * (uint32_t)RPI * row_bytes);
+        if (ROPE)
+            rope_tile_load<NLD>(rT, valid_q ? walk.offset<kApplyTile>(i, table_row_bytes) : kOutOfRange, lane_off_t,
+                                (uint32_t)RPI * table_row_bytes, cs[ROPE ? s : 0]);
     }
 };
 
 // Requests tiles FROM .. TO-1 of the wave's share into the stages of the same numbers.
-template <int FROM, int TO, int DEPTH, bool ROPE>
-__device__ __forceinline__ void apply_prefetch(ApplyStream<DEPTH, ROPE> &st, int lane)
+template <int FROM, int TO, int DP, int DEPTH, bool ROPE>
+__device__ __forceinline__ void apply_prefetch(ApplyStream<DP, DEPTH, ROPE> &st)
 {
 #pragma unroll
     for (int s = FROM; s < TO; ++s) {
-        st.request(s, s, lane);
+        st.request(s, s);
         __builtin_amdgcn_sched_barrier(0);   // requests go out in stage order, as they do in the loop
     }
 }
 
 // Applies the state in `A` to the wave's share, whose first DEPTH tiles
 // apply_prefetch has requested.  `tileQ` is this wave's private LDS region: one
-// tile of kApplyTile * kRowBytes bytes, two with ROPE (the numerator then uses
-// queries rotated after the ReLU, the denominator the plain ones).  Tiles are
-// taken DEPTH at a time; every stage issues its loads and stores whether or not it
-// still has a tile (out of range they do nothing), only the arithmetic is skipped.
-template <bool HILO, int DEPTH, bool ROPE>
-__device__ __forceinline__ void apply_tiles(ApplyStream<DEPTH, ROPE> &st, unsigned char *tileQ, int lane,
-                                            const ApplyOperands<HILO> &A, float eps)
+// tile of kApplyTile rows of apply_row_bytes<DP>() bytes, two with ROPE (the
+// numerator then uses queries rotated after the ReLU, the denominator the plain
+// ones).  Tiles are taken DEPTH at a time; every stage issues its loads and
+// stores whether or not it still has a tile (out of range they do nothing), only
+// the arithmetic is skipped.
+template <int DP, bool HILO, int DEPTH, bool ROPE>
+__device__ __forceinline__ void apply_tiles(ApplyStream<DP, DEPTH, ROPE> &st, unsigned char *tileQ, int lane,
+                                            const ApplyOperands<DP, HILO> &A, float eps)
 {
+    using Stream = ApplyStream<DP, DEPTH, ROPE>;
     constexpr int NS = HILO ? 2 : 1;
-    constexpr int kTileBytes = kApplyTile * kRowBytes;
+    constexpr int KS = DP / 16;
+    constexpr int kRow = apply_row_bytes<DP>();
+    constexpr int kTileBytes = kApplyTile * kRow;
     const int n = lane & 31, g = lane >> 5;
-    const int wr_off = (lane >> 3) * kRowBytes + (lane & 7) * 16;
-    const uint32_t lane_off = (uint32_t)(lane >> 3) * st.row_bytes + (uint32_t)(lane & 7) * 16u;
+    const int wr_off = (lane / Stream::LPR) * kRow + (lane % Stream::LPR) * 16;   // where a loaded chunk goes
+    const int rd_off = (lane >> 3) * kRow + (lane & 7) * 16;                       // where an output chunk comes from
 
     auto round = [&](int i0) __attribute__((always_inline)) {
 #pragma unroll
         for (int s = 0; s < DEPTH; ++s) {
             __builtin_amdgcn_sched_barrier(0);   // stages stay in program order (see state_accumulate)
             const bool valid = i0 + s < st.walk.count;
-            const uint32_t out_off = st.walk.template offset<kApplyTile>(i0 + s, st.row_bytes);
+            const uint32_t out_off = st.valid_o ? st.walk.template offset<kApplyTile>(i0 + s, st.row_bytes) : kOutOfRange;
             if (valid) {
                 wave_lds_fence();
 #pragma unroll
-                for (int i = 0; i < kApplyTile / 8; ++i) {
-                    const u32x4 pq = relu_bf16x8(st.q[s][i]);                          // phi(Q)
-                    *reinterpret_cast<u32x4 *>(tileQ + wr_off + 8 * i * kRowBytes) = pq;
+                for (int j = 0; j < Stream::NLD; ++j) {
+                    const u32x4 pq = relu_bf16x8(st.q[s][j]);                          // phi(Q)
+                    *reinterpret_cast<u32x4 *>(tileQ + wr_off + Stream::RPI * j * kRow) = pq;
                     if (ROPE)
-                        *reinterpret_cast<u32x4 *>(tileQ + kTileBytes + wr_off + 8 * i * kRowBytes) =
-                            rope_rotate_bf16x8(pq, st.cs[ROPE ? s : 0][i][0], st.cs[ROPE ? s : 0][i][1]);
+                        *reinterpret_cast<u32x4 *>(tileQ + kTileBytes + wr_off + Stream::RPI * j * kRow) =
+                            rope_rotate_bf16x8(pq, st.cs[ROPE ? s : 0][j][0], st.cs[ROPE ? s : 0][j][1]);
                 }
             }
-            st.request(s, i0 + s + DEPTH, lane);   // refill this stage: DEPTH tiles ahead
+            st.request(s, i0 + s + DEPTH);   // refill this stage: DEPTH tiles ahead
             __builtin_amdgcn_sched_barrier(0);
             u32x4 o[kApplyTile / 8] = {};
             if (valid) {
                 wave_lds_fence();
-                // B operands: features 16*ks + 8g .. +8 of token n (Br: the rotated copy for the numerator)
-                bf16x8 Bq[4], Br[4];
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks) {
-                    Bq[ks] = *reinterpret_cast<const bf16x8 *>(tileQ + n * kRowBytes + (16 * ks + 8 * g) * 2);
-                    Br[ks] = ROPE ? *reinterpret_cast<const bf16x8 *>(tileQ + kTileBytes + n * kRowBytes +
-                                                                      (16 * ks + 8 * g) * 2)
-                                  : Bq[ks];
-                }
                 f32x16 acc[2], accz;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) { acc[0][i] = 0.f; acc[1][i] = 0.f; accz[i] = 0.f; }
+                // B operands: features 16*ks + 8g .. +8 of token n (br: the rotated copy for the numerator)
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks)
-                    accz = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.zrow[ks], Bq[ks], accz, 0, 0, 0);
+                for (int ks = 0; ks < KS; ++ks) {
+                    const bf16x8 bq = *reinterpret_cast<const bf16x8 *>(tileQ + n * kRow + (16 * ks + 8 * g) * 2);
+                    const bf16x8 br = ROPE ? *reinterpret_cast<const bf16x8 *>(tileQ + kTileBytes + n * kRow +
+                                                                               (16 * ks + 8 * g) * 2)
+                                           : bq;
+                    accz = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.zrow[ks], bq, accz, 0, 0, 0);
 #pragma unroll
-                for (int p = NS - 1; p >= 0; --p)      // small (lo) terms first
-#pragma unroll
-                    for (int ks = 0; ks < 4; ++ks) {
-                        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.s[p][0][ks], Br[ks], acc[0], 0, 0, 0);
-                        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.s[p][1][ks], Br[ks], acc[1], 0, 0, 0);
+                    for (int p = NS - 1; p >= 0; --p) {      // small (lo) terms first
+                        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.s[p][0][ks], br, acc[0], 0, 0, 0);
+                        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.s[p][1][ks], br, acc[1], 0, 0, 0);
                     }
+                }
                 wave_lds_fence();
                 // denominator: rows 0 (hi) and 1 (lo) of the z block sit in registers 0 and 1 of
                 // the lanes of the lower half; the upper half fetches them across the wave
@@ -215,18 +245,18 @@ __device__ __forceinline__ void apply_tiles(ApplyStream<DEPTH, ROPE> &st, unsign
                     hi4.y = pack_bf16x2(a[10] * inv, a[11] * inv);
                     hi4.z = pack_bf16x2(a[12] * inv, a[13] * inv);
                     hi4.w = pack_bf16x2(a[14] * inv, a[15] * inv);
-                    unsigned char *row = tileQ + n * kRowBytes + (32 * g + 16 * rb) * 2;
+                    unsigned char *row = tileQ + n * kRow + (32 * g + 16 * rb) * 2;
                     *reinterpret_cast<u32x4 *>(row) = lo4;
                     *reinterpret_cast<u32x4 *>(row + 16) = hi4;
                 }
                 wave_lds_fence();
 #pragma unroll
                 for (int i = 0; i < kApplyTile / 8; ++i)
-                    o[i] = *reinterpret_cast<const u32x4 *>(tileQ + wr_off + 8 * i * kRowBytes);
+                    o[i] = *reinterpret_cast<const u32x4 *>(tileQ + rd_off + 8 * i * kRow);
             }
 #pragma unroll
             for (int i = 0; i < kApplyTile / 8; ++i)
-                store_stream16(st.rO, out_off + lane_off + (uint32_t)i * 8u * st.row_bytes, o[i]);
+                store_stream16(st.rO, out_off + st.lane_off_o + (uint32_t)i * 8u * st.row_bytes, o[i]);
         }
     };
     // The first round stands apart so that the loop is entered with the same sequence of
@@ -237,34 +267,47 @@ __device__ __forceinline__ void apply_tiles(ApplyStream<DEPTH, ROPE> &st, unsign
 }
 
 // LDS bytes per wave and in total: one tile, two with ROPE (plain + rotated copy).
-template <bool ROPE>
-__host__ __device__ constexpr int apply_wave_lds_bytes() { return (ROPE ? 2 : 1) * kApplyTile * kRowBytes; }
-template <int WAVES, bool ROPE>
-__host__ __device__ constexpr int apply_lds_bytes() { return WAVES * apply_wave_lds_bytes<ROPE>(); }
+template <int DP, bool ROPE>
+__host__ __device__ constexpr int apply_wave_lds_bytes() { return (ROPE ? 2 : 1) * kApplyTile * apply_row_bytes<DP>(); }
+template <int DP, int WAVES, bool ROPE>
+__host__ __device__ constexpr int apply_lds_bytes() { return WAVES * apply_wave_lds_bytes<DP, ROPE>(); }
 
-// grid = (C, B*H), block = 64*WAVES.  Wave w of workgroup c owns tiles
-// WAVES*c + w + WAVES*C*i (i = 0, 1, ...) of the T = ceil((t1-t0)/32) tiles,
-// the same round-robin deal as the state kernel.
-// HILO = false drops the low half of S (one MFMA pass instead of two).
-template <bool HILO, int WAVES, int DEPTH, bool ROPE>
-__global__ __launch_bounds__(64 * WAVES, 1) void apply_mfma_d64(
+// How the waves of workgroup c of C split a head's tiles and output features.
+//   DP = 64:  wave w owns tiles WAVES*c + w + WAVES*C*i (i = 0, 1, ...) and all 64 features;
+//   DP = 128: waves 2t, 2t+1 own tiles (WAVES/2)*c + t + (WAVES/2)*C*i; wave w writes value block w%2.
+template <int DP, int WAVES>
+struct ApplySplit {
+    int first, step, vb;
+    __device__ __forceinline__ ApplySplit(int c, int C, int wave)
+        : first(DP == 64 ? WAVES * c + wave : (WAVES / 2) * c + (wave >> 1)),
+          step(DP == 64 ? WAVES * C : (WAVES / 2) * C), vb(DP == 64 ? 0 : wave & 1) {}
+};
+
+// grid = (C, B*H), block = 64*WAVES; the T = ceil((t1-t0)/32) tiles are dealt
+// round-robin as in the state kernel.  DP = 64 serves d = 64, DP = 128 serves
+// d = 112 and 128.  HILO = false drops the low half of S (one MFMA pass instead of two).
+template <int DP, bool HILO, int WAVES, int DEPTH, bool ROPE>
+__global__ __launch_bounds__(64 * WAVES, 1) void apply_mfma(
     const uint16_t *__restrict__ Q, uint16_t *__restrict__ O, const float *__restrict__ rope, TokStrides st, int H,
-    int t0, int t1, int C, const float *__restrict__ S, const float *__restrict__ z, float eps)
+    int d_arg, int t0, int t1, int C, const float *__restrict__ S, const float *__restrict__ z, float eps)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = blockIdx.x, bh = blockIdx.y;
     const int b = bh / H, h = bh % H;
+    const int d = DP == 64 ? 64 : d_arg;
     const uint16_t *Qh = Q + b * st.b + h * st.h;
     uint16_t *Oh = O + b * st.b + h * st.h;
     const int n_tiles = (t1 - t0 + kApplyTile - 1) / kApplyTile;
+    const ApplySplit<DP, WAVES> split(c, C, wave);
 
-    ApplyStream<DEPTH, ROPE> stream(Qh, Oh, rope, st.n, t1, TileWalk(t0, WAVES * c + wave, WAVES * C, n_tiles, bh));
-    apply_prefetch<0, DEPTH>(stream, lane);   // in flight while S is fetched
-    ApplyOperands<HILO> A;
-    A.template load<false>(S + (size_t)bh * 64 * 64, z + (size_t)bh * 64, lane);
-    apply_tiles<HILO>(stream, lds + wave * apply_wave_lds_bytes<ROPE>(), lane, A, eps);
+    ApplyStream<DP, DEPTH, ROPE> stream(Qh, Oh, rope, st.n, t1, d, split.vb, lane,
+                                        TileWalk(t0, split.first, split.step, n_tiles, bh));
+    apply_prefetch<0, DEPTH>(stream);   // in flight while S is fetched
+    ApplyOperands<DP, HILO> A;
+    A.template load<false>(S + (size_t)bh * d * d, z + (size_t)bh * d, d, split.vb, lane);
+    apply_tiles<DP, HILO>(stream, lds + wave * apply_wave_lds_bytes<DP, ROPE>(), lane, A, eps);
 }
 
 }  // namespace sv

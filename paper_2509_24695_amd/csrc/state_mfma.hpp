@@ -1,4 +1,4 @@
-// bf16 MFMA state reduction for d = 64 on gfx950.
+// bf16 MFMA state reduction for d = 64, 112 and 128 on gfx950.
 //
 //   S[k][v] (+)= sum_j phi(K[j][k]) V[j][v],   z[k] (+)= sum_j phi(K[j][k])
 //
@@ -22,6 +22,14 @@
 // flight.  Workgroup partials go to the workspace; once all partials of a head
 // are published, each of its workgroups adds up one slice of them in chunk
 // order (bit-reproducible, no float atomics).
+//
+// d = 112 and 128 (DP = 128): the state is four 64 x 64 quadrants and the four
+// waves of a workgroup take one each, all walking the same tiles: wave w folds
+// key features 64*(w%2) .. +64 against value features 64*(w/2) .. +64 with the
+// very same code that handles a whole d = 64 tile.  Each half row is then loaded
+// by two waves of the same compute unit at about the same time (the second one
+// is served by the caches, HBM sees it once).  For d = 112 the features past
+// 112 are addressed out of range and read as zeros.
 #pragma once
 
 #include "common.hpp"
@@ -30,7 +38,7 @@
 namespace sv {
 
 constexpr int kRowBytes = 144;   // 128-byte token row + 16 bytes of padding (bank spread, keeps 16-byte alignment)
-constexpr int kStateElems = 64 * 64 + 64;            // S then z of one head, d = 64
+constexpr int kStateElems = 64 * 64 + 64;            // S then z of one head, d = 64; also one 64 x 64 quadrant + its z
 
 // Workspace layout (B*H = BH heads, `elems` = d*d + d):
 //   float  partial[BH][kMaxChunks][elems]
@@ -103,15 +111,17 @@ struct TileWalk {
     }
 };
 
-// Coalesced load of a TILE x 64 bf16 tile: lane l takes bytes 16*(l%8) .. +16 of
-// rows l/8 + 8i.  `off0` is the tile's byte offset (TileWalk::offset).
+// Coalesced load of a TILE x 64 bf16 tile (64 features = 128 bytes of each token
+// row): lane l takes 16 bytes of rows l/8 + 8i.  `off0` is the tile's byte offset
+// (TileWalk::offset), `lane_off` = (l/8) * row_bytes + column bytes of the lane.
+// `lane_valid` = false makes the lane read zeros (features past d).
 template <int TILE>
-__device__ __forceinline__ void token_tile_load(rsrc_t r, uint32_t off0, uint32_t row_bytes, int lane,
-                                                u32x4 (&reg)[TILE / 8])
+__device__ __forceinline__ void token_tile_load(rsrc_t r, uint32_t off0, uint32_t row_bytes, uint32_t lane_off,
+                                                bool lane_valid, u32x4 (&reg)[TILE / 8])
 {
-    const uint32_t lane_off = (uint32_t)(lane >> 3) * row_bytes + (uint32_t)(lane & 7) * 16u;
+    const uint32_t base = lane_valid ? off0 : kOutOfRange;   // kept apart from lane_off: the sum must not wrap
 #pragma unroll
-    for (int i = 0; i < TILE / 8; ++i) reg[i] = load_stream16(r, off0 + lane_off + (uint32_t)i * 8u * row_bytes);
+    for (int i = 0; i < TILE / 8; ++i) reg[i] = load_stream16(r, base + lane_off + (uint32_t)i * 8u * row_bytes);
 }
 
 // Gathers 8 tokens (rows tok_row .. tok_row+7) of 32-bit word `r` from an LDS
@@ -135,38 +145,55 @@ __device__ __forceinline__ void lds_gather_pairs(const unsigned char *tile, int 
 
 // One wave's input stream: buffer resources over the head's K and V rows (and
 // the rotation table) below the end of the token range, the wave's tile walk,
-// and the register staging of DEPTH tiles in flight.
+// and the register staging of DEPTH tiles in flight.  The wave reads key
+// features 64*kb .. +64 and value features 64*vb .. +64 of each token (kb = vb =
+// 0 for d = 64); d is the number of features that exist.
 template <int TILE, int DEPTH, bool ROPE>
 struct StateStream {
     rsrc_t rK, rV, rT;
-    uint32_t row_bytes;
+    uint32_t row_bytes, table_row_bytes;
+    uint32_t lane_off_k, lane_off_v, lane_off_t;
+    bool valid_k, valid_v;
     TileWalk walk;
     u32x4 k[DEPTH][TILE / 8], v[DEPTH][TILE / 8];
     f32x4 cs[ROPE ? DEPTH : 1][TILE / 8][2];
 
     __device__ __forceinline__ StateStream(const uint16_t *Kh, const uint16_t *Vh, const float *rope,
-                                           int64_t stride_n, int t1, const TileWalk &w)
+                                           int64_t stride_n, int t1, int d, int kb, int vb, int lane,
+                                           const TileWalk &w)
         : rK(make_rsrc(Kh, (uint32_t)t1 * (uint32_t)stride_n * 2u)),
           rV(make_rsrc(Vh, (uint32_t)t1 * (uint32_t)stride_n * 2u)),
-          rT(make_rsrc(rope, ROPE ? (uint32_t)t1 * 256u : 0u)), row_bytes((uint32_t)stride_n * 2u), walk(w) {}
+          rT(make_rsrc(rope, ROPE ? (uint32_t)t1 * (uint32_t)d * 4u : 0u)), row_bytes((uint32_t)stride_n * 2u),
+          table_row_bytes((uint32_t)d * 4u), walk(w)
+    {
+        const uint32_t row = (uint32_t)(lane >> 3), col = (uint32_t)(lane & 7);
+        lane_off_k = row * row_bytes + (uint32_t)kb * 128u + col * 16u;
+        lane_off_v = row * row_bytes + (uint32_t)vb * 128u + col * 16u;
+        lane_off_t = row * table_row_bytes + (uint32_t)kb * 256u + col * 32u;
+        valid_k = kb * 64 + (int)col * 8 < d;
+        valid_v = vb * 64 + (int)col * 8 < d;
+    }
 
     // Requests the wave's i-th tile into stage s.  Always the same number of memory
     // instructions: past the wave's share they read nothing and return zeros.
-    __device__ __forceinline__ void request(int s, int i, int lane)
+    __device__ __forceinline__ void request(int s, int i)
     {
-        token_tile_load<TILE>(rK, walk.offset<TILE>(i, row_bytes), row_bytes, lane, k[s]);
-        token_tile_load<TILE>(rV, walk.offset<TILE>(i, row_bytes), row_bytes, lane, v[s]);
-        if (ROPE) rope_tile_load<TILE>(rT, walk.offset<TILE>(i, 256u), lane, cs[ROPE ? s : 0]);
+        const uint32_t off0 = walk.offset<TILE>(i, row_bytes);
+        token_tile_load<TILE>(rK, off0, row_bytes, lane_off_k, valid_k, k[s]);
+        token_tile_load<TILE>(rV, off0, row_bytes, lane_off_v, valid_v, v[s]);
+        if (ROPE)
+            rope_tile_load<TILE / 8>(rT, valid_k ? walk.offset<TILE>(i, table_row_bytes) : kOutOfRange, lane_off_t,
+                                     8u * table_row_bytes, cs[ROPE ? s : 0]);
     }
 };
 
 // Requests the first DEPTH tiles of a wave's share.
 template <int TILE, int DEPTH, bool ROPE>
-__device__ __forceinline__ void state_prefetch(StateStream<TILE, DEPTH, ROPE> &st, int lane)
+__device__ __forceinline__ void state_prefetch(StateStream<TILE, DEPTH, ROPE> &st)
 {
 #pragma unroll
     for (int s = 0; s < DEPTH; ++s) {
-        st.request(s, s, lane);
+        st.request(s, s);
         __builtin_amdgcn_sched_barrier(0);   // requests go out in stage order, as they do in the loop
     }
 }
@@ -205,7 +232,7 @@ __device__ __forceinline__ void state_accumulate(StateStream<TILE, DEPTH, ROPE> 
                 *reinterpret_cast<u32x4 *>(tileK + wr_off + 8 * i * kRowBytes) = st.k[s][i];
                 *reinterpret_cast<u32x4 *>(tileV + wr_off + 8 * i * kRowBytes) = st.v[s][i];
             }
-            st.request(s, i0 + s + DEPTH, lane);   // refill this stage: DEPTH tiles ahead
+            st.request(s, i0 + s + DEPTH);   // refill this stage: DEPTH tiles ahead
             __builtin_amdgcn_sched_barrier(0);
             wave_lds_fence();
 #pragma unroll
@@ -222,47 +249,49 @@ __device__ __forceinline__ void state_accumulate(StateStream<TILE, DEPTH, ROPE> 
     }
 }
 
-// Adds the WAVES waves' accumulators in a fixed tree order and stores the
+// Lays one wave's accumulators out in [k][v] order (64 x 64 floats, then the 64
+// key sums after a wavefront-level reduction) in its LDS slot `dst`.
+__device__ __forceinline__ void state_acc_to_slot(StateAcc &acc, float *dst, int lane)
+{
+    // 32x32 accumulator layout: register i of lane l is row 8*(i/4) + 4*(l/32) + i%4, column l%32.
+    const int r = lane & 31, g = lane >> 5;
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int m = 8 * (i >> 2) + 4 * g + (i & 3);
+            const int k = 2 * m + rb;
+            f32x2 pair = {acc.s[rb][0][i], acc.s[rb][1][i]};   // value features 2r, 2r+1
+            *reinterpret_cast<f32x2 *>(dst + k * 64 + 2 * r) = pair;
+        }
+    // key sum: lanes with equal lane%8 hold the same 8 features (wavefront-level reduction)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        float x = acc.z[e];
+        x += __shfl_xor(x, 8);
+        x += __shfl_xor(x, 16);
+        x += __shfl_xor(x, 32);
+        acc.z[e] = x;
+    }
+    if (lane < 8) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dst[64 * 64 + lane * 8 + e] = acc.z[e];
+    }
+}
+
+// d = 64: adds the WAVES waves' accumulators in a fixed tree order and stores the
 // workgroup's partial state, S in [k][v] order followed by z, to `out`
-// (kStateElems floats) with coherent stores spread over all threads.  Every
-// wave lays its accumulators out in [k][v] order in its own LDS slot (the key
-// sum after a wavefront-level reduction); after one barrier each thread adds the
-// slots for its share of the elements, wave w absorbing wave w + h for
-// h = WAVES/2, ..., 1.  Must be called by all threads; the staging tiles are
-// dead afterwards.  LDS: WAVES * kStateElems floats.
+// (kStateElems floats) with coherent stores spread over all threads: after one
+// barrier each thread adds the waves' slots for its share of the elements,
+// wave w absorbing wave w + h for h = WAVES/2, ..., 1.  Must be called by all
+// threads; the staging tiles are dead afterwards.  LDS: WAVES * kStateElems floats.
 template <int WAVES>
 __device__ __forceinline__ void state_wg_reduce_store(StateAcc &acc, float *slots, int wave, int lane,
                                                       float *__restrict__ out)
 {
     constexpr int THREADS = 64 * WAVES;
     __syncthreads();                                   // all waves are done with their staging tiles
-    {
-        float *dst = slots + wave * kStateElems;
-        // 32x32 accumulator layout: register i of lane l is row 8*(i/4) + 4*(l/32) + i%4, column l%32.
-        const int r = lane & 31, g = lane >> 5;
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int m = 8 * (i >> 2) + 4 * g + (i & 3);
-                const int k = 2 * m + rb;
-                f32x2 pair = {acc.s[rb][0][i], acc.s[rb][1][i]};   // value features 2r, 2r+1
-                *reinterpret_cast<f32x2 *>(dst + k * 64 + 2 * r) = pair;
-            }
-        // key sum: lanes with equal lane%8 hold the same 8 features (wavefront-level reduction)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            float x = acc.z[e];
-            x += __shfl_xor(x, 8);
-            x += __shfl_xor(x, 16);
-            x += __shfl_xor(x, 32);
-            acc.z[e] = x;
-        }
-        if (lane < 8) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) dst[64 * 64 + lane * 8 + e] = acc.z[e];
-        }
-    }
+    state_acc_to_slot(acc, slots + wave * kStateElems, lane);
     __syncthreads();
     for (int v = threadIdx.x; v < kStateElems / 2; v += THREADS) {
         f32x2 x[WAVES];
@@ -276,32 +305,56 @@ __device__ __forceinline__ void state_wg_reduce_store(StateAcc &acc, float *slot
     }
 }
 
+// d = 112, 128: wave w holds quadrant (key block w%2, value block w/2) of the
+// workgroup's partial state; the four slots are stitched into the d x d matrix
+// (row length d) followed by the d key sums (taken from the waves of value
+// block 0) and stored to `out` (d*d + d floats) with coherent stores.
+__device__ __forceinline__ void state_wg_quadrant_store(StateAcc &acc, float *slots, int wave, int lane, int d,
+                                                        float *__restrict__ out)
+{
+    __syncthreads();                                   // all waves are done with their staging tiles
+    state_acc_to_slot(acc, slots + wave * kStateElems, lane);
+    __syncthreads();
+    const int s_units = d * d / 2, units = s_units + d / 2;
+    for (int u = threadIdx.x; u < units; u += 4 * kWave) {
+        const float *src;
+        if (u < s_units) {
+            const int k = (2 * u) / d, v = 2 * u - k * d;
+            src = slots + ((k >> 6) + 2 * (v >> 6)) * kStateElems + (k & 63) * 64 + (v & 63);
+        } else {
+            const int k = 2 * (u - s_units);
+            src = slots + (k >> 6) * kStateElems + 64 * 64 + (k & 63);
+        }
+        store_coherent(out + 2 * u, *reinterpret_cast<const f32x2 *>(src));
+    }
+}
+
 // Slice c of the head's state (8-byte units [c*per, (c+1)*per) of the
-// kStateElems values, per = ceil(2080 / C)):
+// d*d + d values, per = ceil(units / C)):
 //   S_out, z_out = (S_in, z_in or 0) + partial[0] + partial[1] + ... + partial[C-1], in that order.
 // S_in may be null (no carried state) or equal to S_out (update in place).
 // Partials come in through coherent loads, up to eight chunks in flight.
 // COHERENT_OUT: also store the result coherently (other workgroups of this
 // kernel are going to read it).
 template <int THREADS, bool COHERENT_OUT>
-__device__ __forceinline__ void state_finalize_slice(const float *__restrict__ partials, int c, int C,
+__device__ __forceinline__ void state_finalize_slice(const float *__restrict__ partials, int c, int C, int d,
                                                      const float *S_in, const float *z_in, float *S_out,
                                                      float *z_out)
 {
-    constexpr int kVecs = kStateElems / 2;                       // 2080 float2
     constexpr int GROUP = 8;                                     // chunks in flight
-    const int per = (kVecs + C - 1) / C;
-    const int lo = c * per, hi = lo + per < kVecs ? lo + per : kVecs;
+    const int s_units = d * d / 2, units = s_units + d / 2, elems = 2 * units;
+    const int per = (units + C - 1) / C;
+    const int lo = c * per, hi = lo + per < units ? lo + per : units;
     for (int v = lo + (int)threadIdx.x; v < hi; v += THREADS) {
-        float *dst = v < 2048 ? S_out + 2 * v : z_out + 2 * (v - 2048);
+        float *dst = v < s_units ? S_out + 2 * v : z_out + 2 * (v - s_units);
         f32x2 x = {0.f, 0.f};
-        if (S_in) x = *reinterpret_cast<const f32x2 *>(v < 2048 ? S_in + 2 * v : z_in + 2 * (v - 2048));
+        if (S_in) x = *reinterpret_cast<const f32x2 *>(v < s_units ? S_in + 2 * v : z_in + 2 * (v - s_units));
         for (int c0 = 0; c0 < C; c0 += GROUP) {
             f32x2 p[GROUP];
 #pragma unroll
             for (int cc = 0; cc < GROUP; ++cc) {
                 p[cc] = f32x2{0.f, 0.f};
-                if (c0 + cc < C) p[cc] = load_coherent(partials + (size_t)(c0 + cc) * kStateElems + 2 * v);
+                if (c0 + cc < C) p[cc] = load_coherent(partials + (size_t)(c0 + cc) * elems + 2 * v);
             }
 #pragma unroll
             for (int cc = 0; cc < GROUP; ++cc)
@@ -315,51 +368,64 @@ __device__ __forceinline__ void state_finalize_slice(const float *__restrict__ p
 // The calling workgroup has just issued coherent stores that belong to phase
 // `phase` (0: partial c, 1: slice c of the new state) of head `bh`: publish them.
 // All threads must call.
-__device__ __forceinline__ void state_publish(void *ws, int BH, int bh, int c, int phase, unsigned long long epoch)
+__device__ __forceinline__ void state_publish(void *ws, int BH, int elems, int bh, int c, int phase,
+                                              unsigned long long epoch)
 {
     coherent_stores_done();                             // this wave's stores are performed
     __syncthreads();
-    if (threadIdx.x == 0) flag_publish(ws_flags(ws, BH, kStateElems, bh, phase) + c, epoch);
+    if (threadIdx.x == 0) flag_publish(ws_flags(ws, BH, elems, bh, phase) + c, epoch);
 }
 
 // Waits until all C workgroups of head `bh` have published `phase`.  Returns
 // false (and records it in the workspace) if the bounded wait ran out.
-__device__ __forceinline__ bool state_wait(void *ws, int BH, int bh, int C, int phase, unsigned long long epoch,
-                                           uint32_t spin_limit, int lane)
+__device__ __forceinline__ bool state_wait(void *ws, int BH, int elems, int bh, int C, int phase,
+                                           unsigned long long epoch, uint32_t spin_limit, int lane)
 {
-    const bool ok = flags_wait_all(ws_flags(ws, BH, kStateElems, bh, phase), C, epoch, spin_limit, lane);
-    if (!ok && threadIdx.x == 0) *ws_error(ws, BH, kStateElems) = epoch;
+    const bool ok = flags_wait_all(ws_flags(ws, BH, elems, bh, phase), C, epoch, spin_limit, lane);
+    if (!ok && threadIdx.x == 0) *ws_error(ws, BH, elems) = epoch;
     return ok;
 }
 
-__device__ __forceinline__ bool state_publish_and_wait(void *ws, int BH, int bh, int c, int C, int phase,
+__device__ __forceinline__ bool state_publish_and_wait(void *ws, int BH, int elems, int bh, int c, int C, int phase,
                                                        unsigned long long epoch, uint32_t spin_limit, int lane)
 {
-    state_publish(ws, BH, bh, c, phase, epoch);
-    return state_wait(ws, BH, bh, C, phase, epoch, spin_limit, lane);
+    state_publish(ws, BH, elems, bh, c, phase, epoch);
+    return state_wait(ws, BH, elems, bh, C, phase, epoch, spin_limit, lane);
 }
 
-// Dynamic LDS of state_mfma_d64: staging tiles or reduction slots.
+// Dynamic LDS of state_mfma: staging tiles or reduction slots.
 template <int TILE, int WAVES>
 __host__ __device__ constexpr int state_lds_bytes() {
     constexpr int stage = WAVES * 2 * TILE * kRowBytes, red = WAVES * kStateElems * 4;
     return stage > red ? stage : red;
 }
 
-// grid = (C, B*H), block = 64*WAVES.  Wave w of workgroup c owns tiles
-// WAVES*c + w + WAVES*C*i (i = 0, 1, ...) of the T = ceil((t1-t0)/TILE) tiles.
+// How the waves of workgroup c of C split a head's tiles and features.
+//   DP = 64:  wave w owns tiles WAVES*c + w + WAVES*C*i (i = 0, 1, ...) and all 64 features;
+//   DP = 128: all four waves own tiles c + C*i; wave w takes key block w%2, value block w/2.
+template <int DP, int WAVES>
+struct StateSplit {
+    int first, step, kb, vb;
+    __device__ __forceinline__ StateSplit(int c, int C, int wave)
+        : first(DP == 64 ? WAVES * c + wave : c), step(DP == 64 ? WAVES * C : C), kb(DP == 64 ? 0 : wave & 1),
+          vb(DP == 64 ? 0 : wave >> 1) {}
+};
+
+// grid = (C, B*H), block = 64*WAVES.  DP = 64 serves d = 64, DP = 128 serves
+// d = 112 and 128 (WAVES must be 4); T = ceil((t1-t0)/TILE) tiles cover the range.
 // FINALIZE: the C workgroups of a head wait for each other's partials and each
 // folds one slice of them: S_out, z_out = (S_in, z_in, or 0 if S_in is null) +
 // partials; this needs the whole grid to be resident.
 // Otherwise only the partials are written and state_reduce finishes the job.
 // ROPE: keys are rotated (table row = token index, d/2 (cos, sin) pairs) before they meet V.
-template <int TILE, int WAVES, int DEPTH, bool FINALIZE, bool ROPE>
-__global__ __launch_bounds__(64 * WAVES, 1) void state_mfma_d64(
+template <int DP, int TILE, int WAVES, int DEPTH, bool FINALIZE, bool ROPE>
+__global__ __launch_bounds__(64 * WAVES, 1) void state_mfma(
     const uint16_t *__restrict__ K, const uint16_t *__restrict__ V, const float *__restrict__ rope, TokStrides st,
-    int H, int t0, int t1,
+    int H, int d_arg, int t0, int t1,
     int C, const float *S_in, const float *z_in, float *S_out, float *z_out, void *__restrict__ ws,
     unsigned long long epoch, uint32_t spin_limit)
 {
+    static_assert(DP == 64 || (DP == 128 && WAVES == 4), "one wave per 64 x 64 quadrant");
     constexpr int THREADS = 64 * WAVES;
     constexpr int kTileBytes = TILE * kRowBytes;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -368,25 +434,30 @@ __global__ __launch_bounds__(64 * WAVES, 1) void state_mfma_d64(
     const int lane = tid & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = blockIdx.x, bh = blockIdx.y, BH = gridDim.y;
     const int b = bh / H, h = bh % H;
+    const int d = DP == 64 ? 64 : d_arg, elems = d * d + d;
     const uint16_t *Kh = K + b * st.b + h * st.h;
     const uint16_t *Vh = V + b * st.b + h * st.h;
     const int n_tiles = (t1 - t0 + TILE - 1) / TILE;
+    const StateSplit<DP, WAVES> split(c, C, wave);
 
     StateAcc acc;
     acc.clear();
-    StateStream<TILE, DEPTH, ROPE> stream(Kh, Vh, rope, st.n, t1, TileWalk(t0, WAVES * c + wave, WAVES * C, n_tiles, bh));
+    StateStream<TILE, DEPTH, ROPE> stream(Kh, Vh, rope, st.n, t1, d, split.kb, split.vb, lane,
+                                          TileWalk(t0, split.first, split.step, n_tiles, bh));
     unsigned char *tileK = lds + wave * 2 * kTileBytes;
-    state_prefetch(stream, lane);
+    state_prefetch(stream);
     state_accumulate(stream, tileK, tileK + kTileBytes, lane, acc);
 
-    float *partials = static_cast<float *>(ws) + (size_t)bh * kMaxChunks * kStateElems;
-    state_wg_reduce_store<WAVES>(acc, reinterpret_cast<float *>(lds), wave, lane,
-                                 partials + (size_t)c * kStateElems);
+    float *partials = static_cast<float *>(ws) + (size_t)bh * kMaxChunks * elems;
+    if (DP == 64)
+        state_wg_reduce_store<WAVES>(acc, reinterpret_cast<float *>(lds), wave, lane, partials + (size_t)c * elems);
+    else
+        state_wg_quadrant_store(acc, reinterpret_cast<float *>(lds), wave, lane, d, partials + (size_t)c * elems);
     if (FINALIZE) {
-        state_publish_and_wait(ws, BH, bh, c, C, 0, epoch, spin_limit, lane);
-        state_finalize_slice<THREADS, false>(partials, c, C, S_in ? S_in + (size_t)bh * 64 * 64 : nullptr,
-                                             z_in + (size_t)bh * 64, S_out + (size_t)bh * 64 * 64,
-                                             z_out + (size_t)bh * 64);
+        state_publish_and_wait(ws, BH, elems, bh, c, C, 0, epoch, spin_limit, lane);
+        state_finalize_slice<THREADS, false>(partials, c, C, d, S_in ? S_in + (size_t)bh * d * d : nullptr,
+                                             z_in + (size_t)bh * d, S_out + (size_t)bh * d * d,
+                                             z_out + (size_t)bh * d);
     }
 }
 

@@ -22,13 +22,14 @@ using namespace sv;
 
 constexpr int kVersion = 400;   // 0.4.0
 
-// Tuned launch shapes of the bf16 d = 64 kernels (one workgroup per compute unit).
-// Depths are tiles in flight per wave, [plain, RoPE]: a RoPE stage also holds its table rows.
+// Tuned launch shapes of the bf16 MFMA kernels (one workgroup per compute unit).
+// DP = 64 serves d = 64; DP = 128 serves d = 112 and 128.  Depths are tiles in
+// flight per wave, [DP = 128][RoPE]: a RoPE stage also holds its table rows.
 constexpr int kStateTile = 32, kStateWaves = 4, kApplyWaves = 4;
-constexpr int kStateDepth[2] = {2, 2};
-constexpr int kApplyDepth[2] = {2, 2};
-constexpr int kFusedStateDepth[2] = {2, 2};
-constexpr int kFusedApplyDepth[2] = {6, 2};   // Q tiles held in registers across the in-kernel waits
+constexpr int kStateDepth[2][2] = {{2, 2}, {2, 2}};
+constexpr int kApplyDepth[2][2] = {{2, 2}, {2, 1}};
+constexpr int kFusedStateDepth[2][2] = {{2, 2}, {2, 2}};
+constexpr int kFusedApplyDepth[2][2] = {{6, 2}, {2, 1}};   // Q tiles held in registers across the in-kernel waits
 constexpr bool kApplyHiLo = true;
 constexpr uint32_t kSpinLimit = 1u << 24;      // polls of ~100 ns: far beyond any real wait
 
@@ -41,26 +42,31 @@ struct Shape {
 
 struct Device {
     int num_cu = 0;
-    int state_resident_wgs[2] = {0, 0};   // how many state workgroups fit on the device at once [plain, RoPE]
-    int fused_resident_wgs[2] = {0, 0};   // the same for the one-launch block step
+    // how many workgroups fit on the device at once, [DP = 128][RoPE]
+    int state_resident_wgs[2][2] = {{0, 0}, {0, 0}};   // state kernel with in-kernel finalize
+    int fused_resident_wgs[2][2] = {{0, 0}, {0, 0}};   // one-launch block step
     bool ok = false;
 };
 
-// The kernels in use, with and without RoPE (index 1: rotation table given).
-template <bool ROPE> struct Kernels {
-    static constexpr auto state = state_mfma_d64<kStateTile, kStateWaves, kStateDepth[ROPE], true, ROPE>;
-    static constexpr auto state_partial = state_mfma_d64<kStateTile, kStateWaves, kStateDepth[ROPE], false, ROPE>;
-    static constexpr auto apply = apply_mfma_d64<kApplyHiLo, kApplyWaves, kApplyDepth[ROPE], ROPE>;
-    static constexpr auto fused = block_step_mfma_d64<kStateTile, kStateWaves, kFusedStateDepth[ROPE], kApplyHiLo,
-                                                      kFusedApplyDepth[ROPE], ROPE>;
+// The kernels in use, by padded head dimension and with or without RoPE.
+template <int DP, bool ROPE> struct Kernels {
+    static constexpr int W = DP == 128;
+    static constexpr auto state = state_mfma<DP, kStateTile, kStateWaves, kStateDepth[W][ROPE], true, ROPE>;
+    static constexpr auto state_partial = state_mfma<DP, kStateTile, kStateWaves, kStateDepth[W][ROPE], false, ROPE>;
+    static constexpr auto apply = apply_mfma<DP, kApplyHiLo, kApplyWaves, kApplyDepth[W][ROPE], ROPE>;
+    static constexpr auto fused = block_step_mfma<DP, kStateTile, kStateWaves, kFusedStateDepth[W][ROPE], kApplyHiLo,
+                                                  kFusedApplyDepth[W][ROPE], ROPE>;
     static constexpr int state_lds = state_lds_bytes<kStateTile, kStateWaves>();
-    static constexpr int apply_lds = apply_lds_bytes<kApplyWaves, ROPE>();
-    static constexpr int fused_lds = block_step_lds_bytes<kStateTile, kStateWaves, ROPE>();
+    static constexpr int apply_lds = apply_lds_bytes<DP, kApplyWaves, ROPE>();
+    static constexpr int fused_lds = block_step_lds_bytes<DP, kStateTile, kStateWaves, ROPE>();
+    // tokens one workgroup covers per round of its tile walk
+    static constexpr int state_wg_tokens = DP == 64 ? kStateTile * kStateWaves : kStateTile;
+    static constexpr int apply_wg_tokens = DP == 64 ? kApplyTile * kApplyWaves : kApplyTile * kApplyWaves / 2;
 };
 
-template <bool ROPE> void init_kernels(Device &d)
+template <int DP, bool ROPE> void init_kernels(Device &d)
 {
-    using KN = Kernels<ROPE>;
+    using KN = Kernels<DP, ROPE>;
     const auto attr = hipFuncAttributeMaxDynamicSharedMemorySize;
     (void)hipFuncSetAttribute(reinterpret_cast<const void *>(KN::state), attr, KN::state_lds);
     (void)hipFuncSetAttribute(reinterpret_cast<const void *>(KN::state_partial), attr, KN::state_lds);
@@ -70,12 +76,24 @@ template <bool ROPE> void init_kernels(Device &d)
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(KN::fused),
                                                      64 * kStateWaves, KN::fused_lds) != hipSuccess)
         per_cu = 0;
-    d.fused_resident_wgs[ROPE] = per_cu * d.num_cu;
+    d.fused_resident_wgs[KN::W][ROPE] = per_cu * d.num_cu;
     per_cu = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(KN::state),
                                                      64 * kStateWaves, KN::state_lds) != hipSuccess)
         per_cu = 0;
-    d.state_resident_wgs[ROPE] = per_cu * d.num_cu;
+    d.state_resident_wgs[KN::W][ROPE] = per_cu * d.num_cu;
+}
+
+// Calls f(Kernels<DP, ROPE>{}) for the MFMA kernel family that serves head dimension d.
+template <typename F> void with_mfma_kernels(int d, bool rope, F &&f)
+{
+    if (d == 64) {
+        if (rope) f(Kernels<64, true>{});
+        else f(Kernels<64, false>{});
+    } else {
+        if (rope) f(Kernels<128, true>{});
+        else f(Kernels<128, false>{});
+    }
 }
 
 bool head_dim_ok(int d) { return d == 32 || d == 64 || d == 112 || d == 128; }
@@ -107,8 +125,10 @@ const Device &device_info()
         hipDeviceProp_t prop;
         if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return d;
         d.num_cu = prop.multiProcessorCount;
-        init_kernels<false>(d);
-        init_kernels<true>(d);
+        init_kernels<64, false>(d);
+        init_kernels<64, true>(d);
+        init_kernels<128, false>(d);
+        init_kernels<128, true>(d);
         for (int hd : {32, 64, 112, 128})          // the larger generic apply kernels need more than 64 KB of LDS
             with_head_dim(hd, [&](auto D) {
                 const auto attr = hipFuncAttributeMaxDynamicSharedMemorySize;
@@ -172,7 +192,7 @@ sv_status check_desc(const sv_tensor_desc *t, Shape *s)
 bool mfma_path(const Shape &s, const float *rope)
 {
     constexpr int64_t kLimit = int64_t(1) << 31;
-    return s.bf16 && s.d == 64 && (int64_t)s.N * s.st.n * 2 < kLimit && (!rope || (int64_t)s.N * 256 < kLimit);
+    return s.bf16 && s.d >= 64 && (int64_t)s.N * s.st.n * 2 < kLimit && (!rope || (int64_t)s.N * s.d * 4 < kLimit);
 }
 
 sv_status check_range(const Shape &s, int32_t t0, int32_t t1)
@@ -188,22 +208,26 @@ bool eps_ok(float eps) { return isfinite(eps) && eps >= 0.f; }
 
 // S_out, z_out = (S_in, z_in, or 0 when S_in is null) + state of tokens [t0,t1).  S_in may equal S_out.
 // rope: rotation table or null.  All arguments are already validated.
-template <bool ROPE>
-void launch_state_mfma(const uint16_t *k, const uint16_t *v, const float *rope, const Shape &s, int t0, int t1, int C,
+void launch_state_mfma(const uint16_t *k, const uint16_t *v, const float *rope, const Shape &s, int t0, int t1,
                        const float *S_in, const float *z_in, float *S_out, float *z_out, void *ws, const Device &dev,
                        dim3 rgrid, hipStream_t stream)
 {
-    using KN = Kernels<ROPE>;
-    if ((int64_t)C * s.BH <= dev.state_resident_wgs[ROPE]) {
-        // the head's workgroups wait for each other inside the kernel: all must be resident
-        KN::state<<<dim3(C, s.BH), 64 * kStateWaves, KN::state_lds, stream>>>(
-            k, v, rope, s.st, s.H, t0, t1, C, S_in, z_in, S_out, z_out, ws, next_epoch(), kSpinLimit);
-    } else {
-        KN::state_partial<<<dim3(C, s.BH), 64 * kStateWaves, KN::state_lds, stream>>>(
-            k, v, rope, s.st, s.H, t0, t1, C, S_in, z_in, S_out, z_out, ws, 0ull, 0u);
-        state_reduce<64><<<rgrid, kThreads, 0, stream>>>(static_cast<float *>(ws), C, kMaxChunks, S_in, z_in, S_out,
-                                                        z_out);
-    }
+    with_mfma_kernels(s.d, rope != nullptr, [&](auto kn) {
+        using KN = decltype(kn);
+        const int C = plan_chunks(s.BH, t1 - t0, KN::state_wg_tokens, dev.num_cu);
+        if ((int64_t)C * s.BH <= dev.state_resident_wgs[KN::W][rope != nullptr]) {
+            // the head's workgroups wait for each other inside the kernel: all must be resident
+            KN::state<<<dim3(C, s.BH), 64 * kStateWaves, KN::state_lds, stream>>>(
+                k, v, rope, s.st, s.H, s.d, t0, t1, C, S_in, z_in, S_out, z_out, ws, next_epoch(), kSpinLimit);
+        } else {
+            KN::state_partial<<<dim3(C, s.BH), 64 * kStateWaves, KN::state_lds, stream>>>(
+                k, v, rope, s.st, s.H, s.d, t0, t1, C, S_in, z_in, S_out, z_out, ws, 0ull, 0u);
+            with_head_dim(s.d, [&](auto D) {
+                state_reduce<D()><<<rgrid, kThreads, 0, stream>>>(static_cast<float *>(ws), C, kMaxChunks, S_in, z_in,
+                                                                 S_out, z_out);
+            });
+        }
+    });
 }
 
 sv_status enqueue_state(const void *K, const void *V, const float *rope, const Shape &s, int t0, int t1,
@@ -224,11 +248,8 @@ sv_status enqueue_state(const void *K, const void *V, const float *rope, const S
         return launch_status();
     }
     if (mfma_path(s, rope)) {
-        const int C = plan_chunks(s.BH, n, kStateTile * kStateWaves, dev.num_cu);
-        auto *k = static_cast<const uint16_t *>(K);
-        auto *v = static_cast<const uint16_t *>(V);
-        if (rope) launch_state_mfma<true>(k, v, rope, s, t0, t1, C, S_in, z_in, S_out, z_out, ws, dev, rgrid, stream);
-        else launch_state_mfma<false>(k, v, rope, s, t0, t1, C, S_in, z_in, S_out, z_out, ws, dev, rgrid, stream);
+        launch_state_mfma(static_cast<const uint16_t *>(K), static_cast<const uint16_t *>(V), rope, s, t0, t1, S_in,
+                          z_in, S_out, z_out, ws, dev, rgrid, stream);
         return launch_status();
     }
     // fp32 validation mode, bf16 d = 32 and oversized heads: plain-FMA partials, then the fixed-order reduction
@@ -254,18 +275,16 @@ sv_status enqueue_apply(const void *Q, const float *rope, const Shape &s, int t0
     const Device &dev = device_info();
     if (!dev.ok) return SV_ERR_LAUNCH;
     if (mfma_path(s, rope)) {
-        int C = dev.num_cu / s.BH;
-        const int steps = (n + kApplyTile * kApplyWaves - 1) / (kApplyTile * kApplyWaves);
-        if (C > steps) C = steps;
-        if (C < 1) C = 1;
-        auto *q = static_cast<const uint16_t *>(Q);
-        auto *o = static_cast<uint16_t *>(O);
-        if (rope)
-            Kernels<true>::apply<<<dim3(C, s.BH), 64 * kApplyWaves, Kernels<true>::apply_lds, stream>>>(
-                q, o, rope, s.st, s.H, t0, t1, C, S, z, eps);
-        else
-            Kernels<false>::apply<<<dim3(C, s.BH), 64 * kApplyWaves, Kernels<false>::apply_lds, stream>>>(
-                q, o, rope, s.st, s.H, t0, t1, C, S, z, eps);
+        with_mfma_kernels(s.d, rope != nullptr, [&](auto kn) {
+            using KN = decltype(kn);
+            int C = dev.num_cu / s.BH;
+            const int steps = (n + KN::apply_wg_tokens - 1) / KN::apply_wg_tokens;
+            if (C > steps) C = steps;
+            if (C < 1) C = 1;
+            KN::apply<<<dim3(C, s.BH), 64 * kApplyWaves, KN::apply_lds, stream>>>(
+                static_cast<const uint16_t *>(Q), static_cast<uint16_t *>(O), rope, s.st, s.H, s.d, t0, t1, C, S, z,
+                eps);
+        });
         return launch_status();
     }
     const int tile = kThreads / (s.d / 4);          // generic tiles: 256 threads / (d/4 threads per token)
@@ -339,23 +358,19 @@ sv_status do_block_step(const void *Qb, const void *Kb, const void *Vb, const sv
     if (mfma_path(s, rope)) {
         const Device &dev = device_info();
         if (!dev.ok) return SV_ERR_LAUNCH;
-        // One launch when the whole grid can be resident at once (needed by the in-kernel waits).
-        const int C = plan_chunks(s.BH, s.N, kStateTile * kStateWaves, dev.num_cu);
-        if ((int64_t)C * s.BH <= dev.fused_resident_wgs[rope ? 1 : 0]) {
-            auto *q = static_cast<const uint16_t *>(Qb);
-            auto *k = static_cast<const uint16_t *>(Kb);
-            auto *v = static_cast<const uint16_t *>(Vb);
-            auto *o = static_cast<uint16_t *>(Ob);
-            if (rope)
-                Kernels<true>::fused<<<dim3(C, s.BH), 64 * kStateWaves, Kernels<true>::fused_lds, hs>>>(
-                    q, k, v, o, rope, s.st, s.H, s.N, C, S_in, z_in, S_out, z_out, eps, workspace, next_epoch(),
-                    kSpinLimit);
-            else
-                Kernels<false>::fused<<<dim3(C, s.BH), 64 * kStateWaves, Kernels<false>::fused_lds, hs>>>(
-                    q, k, v, o, rope, s.st, s.H, s.N, C, S_in, z_in, S_out, z_out, eps, workspace, next_epoch(),
-                    kSpinLimit);
-            return launch_status();
-        }
+        bool launched = false;
+        with_mfma_kernels(s.d, rope != nullptr, [&](auto kn) {
+            using KN = decltype(kn);
+            // One launch when the whole grid can be resident at once (needed by the in-kernel waits).
+            const int C = plan_chunks(s.BH, s.N, KN::state_wg_tokens, dev.num_cu);
+            if ((int64_t)C * s.BH > dev.fused_resident_wgs[KN::W][rope != nullptr]) return;
+            KN::fused<<<dim3(C, s.BH), 64 * kStateWaves, KN::fused_lds, hs>>>(
+                static_cast<const uint16_t *>(Qb), static_cast<const uint16_t *>(Kb),
+                static_cast<const uint16_t *>(Vb), static_cast<uint16_t *>(Ob), rope, s.st, s.H, s.d, s.N, C, S_in,
+                z_in, S_out, z_out, eps, workspace, next_epoch(), kSpinLimit);
+            launched = true;
+        });
+        if (launched) return launch_status();
     }
     rc = enqueue_state(Kb, Vb, rope, s, 0, s.N, S_in, z_in, S_out, z_out, workspace, hs);
     if (rc != SV_OK) return rc;
