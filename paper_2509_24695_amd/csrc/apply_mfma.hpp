@@ -150,7 +150,7 @@ struct ApplyStream {
         const uint32_t base = valid_q ? walk.offset<kApplyTile>(i, row_bytes) : kOutOfRange;
 #pragma unroll
         for (int j = 0; j < NLD; ++j)
-            q[s][j] = load_stream16(rQ, base + lane_off_q + (uint32_t)j * (uint32_t)RPI * row_bytes);
+            q[s][j] = load_tokens16<DP == 64>(rQ, base + lane_off_q + (uint32_t)j * (uint32_t)RPI * row_bytes);
         if (ROPE)
             rope_tile_load<NLD>(rT, valid_q ? walk.offset<kApplyTile>(i, table_row_bytes) : kOutOfRange, lane_off_t,
                                 (uint32_t)RPI * table_row_bytes, cs[ROPE ? s : 0]);

@@ -68,19 +68,19 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
         const StateSplit<DP, WAVES> ssplit(c, C, wave);
         StateAcc acc;
         acc.clear();
-        StateStream<TILE, DEPTH_S, ROPE> kvstream(K + head_off, V + head_off, rope, st.n, N, d, ssplit.kb, ssplit.vb,
+        StateStream<TILE, DEPTH_S, ROPE, DP == 64> kvstream(K + head_off, V + head_off, rope, st.n, N, d, ssplit.kb, ssplit.vb,
                                                   lane, TileWalk(0, ssplit.first, ssplit.step, n_tiles, bh));
         unsigned char *tileK = lds + wave * 2 * kTileBytes;
         state_prefetch(kvstream);
-        state_accumulate(kvstream, tileK, tileK + kTileBytes, lane, acc);
+        state_accumulate(kvstream, tileK, tileK + kTileBytes, lane, ssplit.vb == 0, acc);
         // the rest of this wave's Q prefetch streams in while the head's state is being agreed on
         apply_prefetch<kEarly, DEPTH_A>(qstream);
         float *partials = static_cast<float *>(ws) + (size_t)bh * kMaxChunks * elems;
         if (DP == 64)
-            state_wg_reduce_store<WAVES>(acc, reinterpret_cast<float *>(lds), wave, lane,
+            state_wg_reduce_store<WAVES, ROPE>(acc, reinterpret_cast<float *>(lds), wave, lane,
                                          partials + (size_t)c * elems);
         else
-            state_wg_quadrant_store(acc, reinterpret_cast<float *>(lds), wave, lane, d, partials + (size_t)c * elems);
+            state_wg_quadrant_store<ROPE>(acc, reinterpret_cast<float *>(lds), wave, lane, d, partials + (size_t)c * elems);
     }
 
     // ---- once all partials of the head are there, fold this workgroup's slice into S, z in place,

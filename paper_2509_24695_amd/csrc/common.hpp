@@ -95,6 +95,10 @@ __device__ __forceinline__ rsrc_t make_rsrc(const void *p, uint32_t bytes) {
 __device__ __forceinline__ u32x4 load_stream16(rsrc_t r, uint32_t off) {
     return __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, SV_STREAM_NT ? 2 : 0);
 }
+// Token bytes that one wave reads (STREAM) or that a second wave reads again soon after.
+template <bool STREAM> __device__ __forceinline__ u32x4 load_tokens16(rsrc_t r, uint32_t off) {
+    return __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, STREAM && SV_STREAM_NT ? 2 : 0);
+}
 __device__ __forceinline__ void store_stream16(rsrc_t r, uint32_t off, u32x4 v) {
     __builtin_amdgcn_raw_buffer_store_b128(v, r, off, 0, SV_STORE_NT ? 2 : 0);
 }

@@ -7,14 +7,14 @@
 //
 // The contraction runs over tokens, but K and V are stored feature-contiguous,
 // so both MFMA operands need a transpose.  Each wave works alone on tiles of
-// TILE tokens: coalesced non-temporal 16-byte loads (8 lanes cover one 128-byte
-// token row), ReLU on the packed bf16 pairs, a store into the wave's private
-// LDS tile, and 32-bit LDS reads down the token axis that are re-packed into
-// operands.  A 32-bit word holds features (2r, 2r+1) of one token, so lane r
-// of a 32-row MFMA block serves row "feature 2r" in block 0 and "feature 2r+1"
-// in block 1: the row/column permutation is undone when the accumulators are
-// written out.  Because a wave only ever reads LDS it wrote itself, no
-// workgroup barrier is needed inside the token loop.
+// TILE tokens: coalesced non-temporal 16-byte loads (8 lanes cover 128 bytes of
+// a token row), ReLU on the packed bf16 pairs, a store into the wave's private
+// LDS tile, and transposing LDS reads (ds_read_b64_tr_b16: 16 lanes fetch four
+// 32-byte row segments and each lane receives its column of them, i.e. one
+// feature of four consecutive tokens) that deliver the operands ready-made.
+// The key sum comes out of the same pass as a product with a block of ones
+// (exact: phi(K) times 1.0, fp32 accumulation).  Because a wave only ever reads
+// LDS it wrote itself, no workgroup barrier is needed inside the token loop.
 //
 // One workgroup per compute unit and a round-robin deal of tiles keep the whole
 // grid streaming through a narrow, moving window of each head's tokens, which
@@ -70,18 +70,25 @@ __host__ __device__ constexpr size_t ws_total_bytes(int BH, int elems) {
            ((size_t)BH * 2 * kMaxChunks + 2) * sizeof(unsigned long long);
 }
 
-// Registers of one lane: the 64x64 fp32 partial state as four 32x32 MFMA
-// accumulators, plus 8 key-sum lanes.
+// Registers of one lane: a 64x64 fp32 partial state as four 32x32 MFMA
+// accumulators, S[32*rb + m][32*cb + n], and the key sums: as two more
+// accumulators whose columns all hold sum_j phi(K[j][32*rb + m]) (plain
+// kernels), or as 8 per-lane sums (RoPE kernels, where the keys that reach the
+// MFMA are rotated but the key sum is not).
 struct StateAcc {
-    f32x16 s[2][2];   // [row block = key feature parity][col block = value feature parity]
+    f32x16 s[2][2];   // [key feature block][value feature block]
+    f32x16 zm[2];     // [key feature block]
     float z[8];       // features (lane%8)*8 + e of the tokens this lane loaded
     __device__ __forceinline__ void clear() {
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
+        for (int rb = 0; rb < 2; ++rb) {
 #pragma unroll
             for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) s[rb][cb][i] = 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) zm[rb][i] = 0.f;
+        }
 #pragma unroll
         for (int e = 0; e < 8; ++e) z[e] = 0.f;
     }
@@ -114,33 +121,34 @@ struct TileWalk {
 // Coalesced load of a TILE x 64 bf16 tile (64 features = 128 bytes of each token
 // row): lane l takes 16 bytes of rows l/8 + 8i.  `off0` is the tile's byte offset
 // (TileWalk::offset), `lane_off` = (l/8) * row_bytes + column bytes of the lane.
-// `lane_valid` = false makes the lane read zeros (features past d).
-template <int TILE>
+// `lane_valid` = false makes the lane read zeros (features past d).  STREAM: the
+// bytes are read by this wave only (non-temporal); otherwise a second wave
+// reads them too and they should stay cached.
+template <int TILE, bool STREAM>
 __device__ __forceinline__ void token_tile_load(rsrc_t r, uint32_t off0, uint32_t row_bytes, uint32_t lane_off,
                                                 bool lane_valid, u32x4 (&reg)[TILE / 8])
 {
     const uint32_t base = lane_valid ? off0 : kOutOfRange;   // kept apart from lane_off: the sum must not wrap
 #pragma unroll
-    for (int i = 0; i < TILE / 8; ++i) reg[i] = load_stream16(r, base + lane_off + (uint32_t)i * 8u * row_bytes);
+    for (int i = 0; i < TILE / 8; ++i)
+        reg[i] = load_tokens16<STREAM>(r, base + lane_off + (uint32_t)i * 8u * row_bytes);
 }
 
-// Gathers 8 tokens (rows tok_row .. tok_row+7) of 32-bit word `r` from an LDS
-// tile and packs the low halves (even feature) and high halves (odd feature)
-// into two MFMA operands.
-__device__ __forceinline__ void lds_gather_pairs(const unsigned char *tile, int tok_row, int r,
-                                                 bf16x8 &even, bf16x8 &odd)
+// MFMA operand from a token-major LDS tile: for the lane's MFMA row
+// r = lane%32 and k-group g = lane/32, features f0 + r of tokens tok0 + 8g .. +8.
+// Two transposing reads of four tokens each; within a block of 16 lanes, lane i
+// supplies the address of token (i/4), features 4*(i%4) .. +4 of the block's 16.
+__device__ __forceinline__ bf16x8 lds_tr_operand(const unsigned char *tile, int tok0, int f0, int lane)
 {
-    uint32_t w[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-        w[i] = *reinterpret_cast<const uint32_t *>(tile + (tok_row + i) * kRowBytes + r * 4);
-    u32x4 lo, hi;
-    lo.x = (w[0] & 0xffffu) | (w[1] << 16);  hi.x = (w[0] >> 16) | (w[1] & 0xffff0000u);
-    lo.y = (w[2] & 0xffffu) | (w[3] << 16);  hi.y = (w[2] >> 16) | (w[3] & 0xffff0000u);
-    lo.z = (w[4] & 0xffffu) | (w[5] << 16);  hi.z = (w[4] >> 16) | (w[5] & 0xffff0000u);
-    lo.w = (w[6] & 0xffffu) | (w[7] << 16);  hi.w = (w[6] >> 16) | (w[7] & 0xffff0000u);
-    even = __builtin_bit_cast(bf16x8, lo);
-    odd = __builtin_bit_cast(bf16x8, hi);
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
+    const int i = lane & 15, fb = (lane >> 4) & 1, g = lane >> 5;
+    const unsigned char *p = tile + (tok0 + 8 * g + (i >> 2)) * kRowBytes + (f0 + 16 * fb + 4 * (i & 3)) * 2;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 4 * kRowBytes));
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, both);
 }
 
 // One wave's input stream: buffer resources over the head's K and V rows (and
@@ -148,7 +156,7 @@ __device__ __forceinline__ void lds_gather_pairs(const unsigned char *tile, int 
 // and the register staging of DEPTH tiles in flight.  The wave reads key
 // features 64*kb .. +64 and value features 64*vb .. +64 of each token (kb = vb =
 // 0 for d = 64); d is the number of features that exist.
-template <int TILE, int DEPTH, bool ROPE>
+template <int TILE, int DEPTH, bool ROPE, bool STREAM>
 struct StateStream {
     rsrc_t rK, rV, rT;
     uint32_t row_bytes, table_row_bytes;
@@ -179,8 +187,8 @@ struct StateStream {
     __device__ __forceinline__ void request(int s, int i)
     {
         const uint32_t off0 = walk.offset<TILE>(i, row_bytes);
-        token_tile_load<TILE>(rK, off0, row_bytes, lane_off_k, valid_k, k[s]);
-        token_tile_load<TILE>(rV, off0, row_bytes, lane_off_v, valid_v, v[s]);
+        token_tile_load<TILE, STREAM>(rK, off0, row_bytes, lane_off_k, valid_k, k[s]);
+        token_tile_load<TILE, STREAM>(rV, off0, row_bytes, lane_off_v, valid_v, v[s]);
         if (ROPE)
             rope_tile_load<TILE / 8>(rT, valid_k ? walk.offset<TILE>(i, table_row_bytes) : kOutOfRange, lane_off_t,
                                      8u * table_row_bytes, cs[ROPE ? s : 0]);
@@ -188,8 +196,8 @@ struct StateStream {
 };
 
 // Requests the first DEPTH tiles of a wave's share.
-template <int TILE, int DEPTH, bool ROPE>
-__device__ __forceinline__ void state_prefetch(StateStream<TILE, DEPTH, ROPE> &st)
+template <int TILE, int DEPTH, bool ROPE, bool STREAM>
+__device__ __forceinline__ void state_prefetch(StateStream<TILE, DEPTH, ROPE, STREAM> &st)
 {
 #pragma unroll
     for (int s = 0; s < DEPTH; ++s) {
@@ -200,13 +208,14 @@ __device__ __forceinline__ void state_prefetch(StateStream<TILE, DEPTH, ROPE> &s
 
 // Accumulates the wave's share, whose first DEPTH tiles state_prefetch has
 // requested.  Tiles are taken DEPTH at a time; in the last round the stages past
-// the share hold zeros, as do tokens past t1, and add nothing to either sum.  `tileK`/`tileV` are this wave's private LDS tiles.
-template <int TILE, int DEPTH, bool ROPE>
-__device__ __forceinline__ void state_accumulate(StateStream<TILE, DEPTH, ROPE> &st, unsigned char *tileK,
-                                                 unsigned char *tileV, int lane, StateAcc &acc)
+// the share hold zeros, as do tokens past t1, and add nothing to either sum.
+// `tileK`/`tileV` are this wave's private LDS tiles.  want_z (wave-uniform):
+// this wave's key sums are needed (plain kernels; RoPE kernels always sum).
+template <int TILE, int DEPTH, bool ROPE, bool STREAM>
+__device__ __forceinline__ void state_accumulate(StateStream<TILE, DEPTH, ROPE, STREAM> &st, unsigned char *tileK,
+                                                 unsigned char *tileV, int lane, bool want_z, StateAcc &acc)
 {
     static_assert(TILE == 16 || TILE == 32, "tile is one or two MFMA k-steps");
-    const int r = lane & 31, g = lane >> 5;
     const int wr_off = (lane >> 3) * kRowBytes + (lane & 7) * 16;
 
     for (int i0 = 0; i0 < st.walk.count; i0 += DEPTH) {
@@ -215,15 +224,17 @@ __device__ __forceinline__ void state_accumulate(StateStream<TILE, DEPTH, ROPE> 
             // keep each stage's work together: a later stage's registers must not be touched (and
             // waited for) before this stage has been refilled
             __builtin_amdgcn_sched_barrier(0);
-            // phi(K) on the packed pairs; key sum in fp32 from the same registers
+            // phi(K) on the packed pairs
 #pragma unroll
             for (int i = 0; i < TILE / 8; ++i) {
                 const u32x4 kk = relu_bf16x8(st.k[s][i]);
-                acc.z[0] += bf16_lo(kk.x);  acc.z[1] += bf16_hi(kk.x);
-                acc.z[2] += bf16_lo(kk.y);  acc.z[3] += bf16_hi(kk.y);
-                acc.z[4] += bf16_lo(kk.z);  acc.z[5] += bf16_hi(kk.z);
-                acc.z[6] += bf16_lo(kk.w);  acc.z[7] += bf16_hi(kk.w);
-                // the key sum above is never rotated; the keys that meet V are (RoPE after ReLU)
+                if (ROPE) {
+                    // the key sum is never rotated; the keys that meet V are (RoPE after ReLU)
+                    acc.z[0] += bf16_lo(kk.x);  acc.z[1] += bf16_hi(kk.x);
+                    acc.z[2] += bf16_lo(kk.y);  acc.z[3] += bf16_hi(kk.y);
+                    acc.z[4] += bf16_lo(kk.z);  acc.z[5] += bf16_hi(kk.z);
+                    acc.z[6] += bf16_lo(kk.w);  acc.z[7] += bf16_hi(kk.w);
+                }
                 st.k[s][i] = ROPE ? rope_rotate_bf16x8(kk, st.cs[ROPE ? s : 0][i][0], st.cs[ROPE ? s : 0][i][1]) : kk;
             }
             wave_lds_fence();   // earlier reads of the tile buffer are done before it is overwritten
@@ -237,45 +248,54 @@ __device__ __forceinline__ void state_accumulate(StateStream<TILE, DEPTH, ROPE> 
             wave_lds_fence();
 #pragma unroll
             for (int ks = 0; ks < TILE / 16; ++ks) {
-                bf16x8 a0, a1, b0, b1;
-                lds_gather_pairs(tileK, 16 * ks + 8 * g, r, a0, a1);
-                lds_gather_pairs(tileV, 16 * ks + 8 * g, r, b0, b1);
+                const bf16x8 a0 = lds_tr_operand(tileK, 16 * ks, 0, lane), a1 = lds_tr_operand(tileK, 16 * ks, 32, lane);
+                const bf16x8 b0 = lds_tr_operand(tileV, 16 * ks, 0, lane), b1 = lds_tr_operand(tileV, 16 * ks, 32, lane);
                 acc.s[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc.s[0][0], 0, 0, 0);
                 acc.s[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc.s[0][1], 0, 0, 0);
                 acc.s[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc.s[1][0], 0, 0, 0);
                 acc.s[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc.s[1][1], 0, 0, 0);
+                if (!ROPE && want_z) {
+                    const uint32_t one2 = 0x3f803f80u;   // bf16 (1.0, 1.0)
+                    const u32x4 ones4 = {one2, one2, one2, one2};
+                    const bf16x8 ones = __builtin_bit_cast(bf16x8, ones4);
+                    acc.zm[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, ones, acc.zm[0], 0, 0, 0);
+                    acc.zm[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, ones, acc.zm[1], 0, 0, 0);
+                }
             }
         }
     }
 }
 
 // Lays one wave's accumulators out in [k][v] order (64 x 64 floats, then the 64
-// key sums after a wavefront-level reduction) in its LDS slot `dst`.
+// key sums) in its LDS slot `dst`.
+template <bool ROPE>
 __device__ __forceinline__ void state_acc_to_slot(StateAcc &acc, float *dst, int lane)
 {
     // 32x32 accumulator layout: register i of lane l is row 8*(i/4) + 4*(l/32) + i%4, column l%32.
-    const int r = lane & 31, g = lane >> 5;
+    const int n = lane & 31, g = lane >> 5;
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            const int m = 8 * (i >> 2) + 4 * g + (i & 3);
-            const int k = 2 * m + rb;
-            f32x2 pair = {acc.s[rb][0][i], acc.s[rb][1][i]};   // value features 2r, 2r+1
-            *reinterpret_cast<f32x2 *>(dst + k * 64 + 2 * r) = pair;
+            const int k = 32 * rb + 8 * (i >> 2) + 4 * g + (i & 3);
+            dst[k * 64 + n] = acc.s[rb][0][i];
+            dst[k * 64 + 32 + n] = acc.s[rb][1][i];
+            if (!ROPE && n == 0) dst[64 * 64 + k] = acc.zm[rb][i];   // every column of zm holds the key sums
         }
-    // key sum: lanes with equal lane%8 hold the same 8 features (wavefront-level reduction)
+    if (ROPE) {
+        // lanes with equal lane%8 hold the same 8 features (wavefront-level reduction)
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        float x = acc.z[e];
-        x += __shfl_xor(x, 8);
-        x += __shfl_xor(x, 16);
-        x += __shfl_xor(x, 32);
-        acc.z[e] = x;
-    }
-    if (lane < 8) {
+        for (int e = 0; e < 8; ++e) {
+            float x = acc.z[e];
+            x += __shfl_xor(x, 8);
+            x += __shfl_xor(x, 16);
+            x += __shfl_xor(x, 32);
+            acc.z[e] = x;
+        }
+        if (lane < 8) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) dst[64 * 64 + lane * 8 + e] = acc.z[e];
+            for (int e = 0; e < 8; ++e) dst[64 * 64 + lane * 8 + e] = acc.z[e];
+        }
     }
 }
 
@@ -285,13 +305,13 @@ __device__ __forceinline__ void state_acc_to_slot(StateAcc &acc, float *dst, int
 // barrier each thread adds the waves' slots for its share of the elements,
 // wave w absorbing wave w + h for h = WAVES/2, ..., 1.  Must be called by all
 // threads; the staging tiles are dead afterwards.  LDS: WAVES * kStateElems floats.
-template <int WAVES>
+template <int WAVES, bool ROPE>
 __device__ __forceinline__ void state_wg_reduce_store(StateAcc &acc, float *slots, int wave, int lane,
                                                       float *__restrict__ out)
 {
     constexpr int THREADS = 64 * WAVES;
     __syncthreads();                                   // all waves are done with their staging tiles
-    state_acc_to_slot(acc, slots + wave * kStateElems, lane);
+    state_acc_to_slot<ROPE>(acc, slots + wave * kStateElems, lane);
     __syncthreads();
     for (int v = threadIdx.x; v < kStateElems / 2; v += THREADS) {
         f32x2 x[WAVES];
@@ -309,11 +329,12 @@ __device__ __forceinline__ void state_wg_reduce_store(StateAcc &acc, float *slot
 // workgroup's partial state; the four slots are stitched into the d x d matrix
 // (row length d) followed by the d key sums (taken from the waves of value
 // block 0) and stored to `out` (d*d + d floats) with coherent stores.
+template <bool ROPE>
 __device__ __forceinline__ void state_wg_quadrant_store(StateAcc &acc, float *slots, int wave, int lane, int d,
                                                         float *__restrict__ out)
 {
     __syncthreads();                                   // all waves are done with their staging tiles
-    state_acc_to_slot(acc, slots + wave * kStateElems, lane);
+    state_acc_to_slot<ROPE>(acc, slots + wave * kStateElems, lane);
     __syncthreads();
     const int s_units = d * d / 2, units = s_units + d / 2;
     for (int u = threadIdx.x; u < units; u += 4 * kWave) {
@@ -442,17 +463,19 @@ __global__ __launch_bounds__(64 * WAVES, 1) void state_mfma(
 
     StateAcc acc;
     acc.clear();
-    StateStream<TILE, DEPTH, ROPE> stream(Kh, Vh, rope, st.n, t1, d, split.kb, split.vb, lane,
+    StateStream<TILE, DEPTH, ROPE, DP == 64> stream(Kh, Vh, rope, st.n, t1, d, split.kb, split.vb, lane,
                                           TileWalk(t0, split.first, split.step, n_tiles, bh));
     unsigned char *tileK = lds + wave * 2 * kTileBytes;
     state_prefetch(stream);
-    state_accumulate(stream, tileK, tileK + kTileBytes, lane, acc);
+    state_accumulate(stream, tileK, tileK + kTileBytes, lane, split.vb == 0, acc);
 
     float *partials = static_cast<float *>(ws) + (size_t)bh * kMaxChunks * elems;
     if (DP == 64)
-        state_wg_reduce_store<WAVES>(acc, reinterpret_cast<float *>(lds), wave, lane, partials + (size_t)c * elems);
+        state_wg_reduce_store<WAVES, ROPE>(acc, reinterpret_cast<float *>(lds), wave, lane,
+                                           partials + (size_t)c * elems);
     else
-        state_wg_quadrant_store(acc, reinterpret_cast<float *>(lds), wave, lane, d, partials + (size_t)c * elems);
+        state_wg_quadrant_store<ROPE>(acc, reinterpret_cast<float *>(lds), wave, lane, d,
+                                      partials + (size_t)c * elems);
     if (FINALIZE) {
         state_publish_and_wait(ws, BH, elems, bh, c, C, 0, epoch, spin_limit, lane);
         state_finalize_slice<THREADS, false>(partials, c, C, d, S_in ? S_in + (size_t)bh * d * d : nullptr,
