@@ -24,12 +24,10 @@
 // a tile waits only for its own loads: the stores of earlier tiles and the loads
 // of later ones stay in flight.
 //
-// d = 112 and 128 (DP = 128): a wave produces 64 of a token's output features
-// (value block vb), so it keeps a 128 x 64 panel of S in registers and runs
-// twice as many k-steps over the whole query row; two waves of a workgroup
-// share each tile of Q (the second load is served by the caches) and write
-// the two halves of the O rows.  For d = 112 the features past 112 are
-// addressed out of range: they read as zeros and their stores are dropped.
+// d = 112 and 128: a wave produces 64 of a token's output features (value
+// block vb), so it keeps a 128 x 64 panel of S in registers (ApplyOperands<128>)
+// and runs twice as many k-steps; the token streaming for that case is in
+// coop128.hpp.
 #pragma once
 
 #include "common.hpp"
@@ -39,9 +37,6 @@
 namespace sv {
 
 constexpr int kApplyTile = 32;   // tokens per wave tile (the N dimension of the 32x32x16 MFMA)
-
-// LDS row of a Q tile: DP bf16 features + 16 bytes of padding (bank spread, keeps 16-byte alignment).
-template <int DP> __host__ __device__ constexpr int apply_row_bytes() { return DP * 2 + 16; }
 
 // The state of one head as MFMA A operands for the 64 output features of value
 // block vb, per lane (m = lane%32, g = lane/32).
@@ -111,55 +106,41 @@ struct ApplyOperands {
     }
 };
 
-// One wave's token stream: buffer resources over the head's Q and O rows (and the
-// rotation table) below the end of the token range, the wave's tile walk (32
-// tokens per tile), and the register staging of DEPTH tiles in flight.  A Q row
-// takes DP/8 lanes of 16 bytes, so one load instruction covers 512/DP rows; the
-// wave writes output features 64*vb .. +64 (8 lanes of 16 bytes per row).
-template <int DP, int DEPTH, bool ROPE>
+// One wave's token stream (d = 64): buffer resources over the head's Q and O
+// rows (and the rotation table) below the end of the token range, the wave's tile
+// walk (32 tokens per tile), and the register staging of DEPTH tiles in flight.
+template <int DEPTH, bool ROPE>
 struct ApplyStream {
-    static constexpr int LPR = DP / 8;            // lanes per Q row
-    static constexpr int RPI = kWave / LPR;       // Q rows per load instruction
-    static constexpr int NLD = kApplyTile / RPI;  // load instructions per tile
     rsrc_t rQ, rO, rT;
-    uint32_t row_bytes, table_row_bytes;
-    uint32_t lane_off_q, lane_off_o, lane_off_t;
-    bool valid_q, valid_o;
+    uint32_t row_bytes, lane_off, lane_off_t;
     TileWalk walk;
-    u32x4 q[DEPTH][NLD];
-    f32x4 cs[ROPE ? DEPTH : 1][NLD][2];
+    u32x4 q[DEPTH][kApplyTile / 8];
+    f32x4 cs[ROPE ? DEPTH : 1][kApplyTile / 8][2];
 
     __device__ __forceinline__ ApplyStream(const uint16_t *Qh, uint16_t *Oh, const float *rope, int64_t stride_n,
-                                           int t1, int d, int vb, int lane, const TileWalk &w)
+                                           int t1, int lane, const TileWalk &w)
         : rQ(make_rsrc(Qh, (uint32_t)t1 * (uint32_t)stride_n * 2u)),
           rO(make_rsrc(Oh, (uint32_t)t1 * (uint32_t)stride_n * 2u)),
-          rT(make_rsrc(rope, ROPE ? (uint32_t)t1 * (uint32_t)d * 4u : 0u)), row_bytes((uint32_t)stride_n * 2u),
-          table_row_bytes((uint32_t)d * 4u), walk(w)
-    {
-        const uint32_t qrow = (uint32_t)(lane / LPR), qcol = (uint32_t)(lane % LPR);
-        lane_off_q = qrow * row_bytes + qcol * 16u;
-        lane_off_t = qrow * table_row_bytes + qcol * 32u;
-        valid_q = (int)qcol * 8 < d;
-        lane_off_o = (uint32_t)(lane >> 3) * row_bytes + (uint32_t)vb * 128u + (uint32_t)(lane & 7) * 16u;
-        valid_o = vb * 64 + (lane & 7) * 8 < d;
-    }
+          rT(make_rsrc(rope, ROPE ? (uint32_t)t1 * 256u : 0u)), row_bytes((uint32_t)stride_n * 2u),
+          lane_off((uint32_t)(lane >> 3) * (uint32_t)stride_n * 2u + (uint32_t)(lane & 7) * 16u),
+          lane_off_t((uint32_t)(lane >> 3) * 256u + (uint32_t)(lane & 7) * 32u), walk(w) {}
 
     // Requests the wave's i-th tile into stage s; past the share nothing is read.
     __device__ __forceinline__ void request(int s, int i)
     {
-        const uint32_t base = valid_q ? walk.offset<kApplyTile>(i, row_bytes) : kOutOfRange;
+        const uint32_t base = walk.offset<kApplyTile>(i, row_bytes);
 #pragma unroll
-        for (int j = 0; j < NLD; ++j)
-            q[s][j] = load_tokens16<DP == 64>(rQ, base + lane_off_q + (uint32_t)j * (uint32_t)RPI * row_bytes);
+        for (int j = 0; j < kApplyTile / 8; ++j)
+            q[s][j] = load_stream16(rQ, base + lane_off + (uint32_t)j * 8u * row_bytes);
         if (ROPE)
-            rope_tile_load<NLD>(rT, valid_q ? walk.offset<kApplyTile>(i, table_row_bytes) : kOutOfRange, lane_off_t,
-                                (uint32_t)RPI * table_row_bytes, cs[ROPE ? s : 0]);
+            rope_tile_load<kApplyTile / 8>(rT, walk.offset<kApplyTile>(i, 256u), lane_off_t, 8u * 256u,
+                                           cs[ROPE ? s : 0]);
     }
 };
 
 // Requests tiles FROM .. TO-1 of the wave's share into the stages of the same numbers.
-template <int FROM, int TO, int DP, int DEPTH, bool ROPE>
-__device__ __forceinline__ void apply_prefetch(ApplyStream<DP, DEPTH, ROPE> &st)
+template <int FROM, int TO, int DEPTH, bool ROPE>
+__device__ __forceinline__ void apply_prefetch(ApplyStream<DEPTH, ROPE> &st)
 {
 #pragma unroll
     for (int s = FROM; s < TO; ++s) {
@@ -170,38 +151,36 @@ __device__ __forceinline__ void apply_prefetch(ApplyStream<DP, DEPTH, ROPE> &st)
 
 // Applies the state in `A` to the wave's share, whose first DEPTH tiles
 // apply_prefetch has requested.  `tileQ` is this wave's private LDS region: one
-// tile of kApplyTile rows of apply_row_bytes<DP>() bytes, two with ROPE (the
+// tile of kApplyTile rows of kRowBytes bytes, two with ROPE (the
 // numerator then uses queries rotated after the ReLU, the denominator the plain
 // ones).  Tiles are taken DEPTH at a time; every stage issues its loads and
 // stores whether or not it still has a tile (out of range they do nothing), only
 // the arithmetic is skipped.
-template <int DP, bool HILO, int DEPTH, bool ROPE>
-__device__ __forceinline__ void apply_tiles(ApplyStream<DP, DEPTH, ROPE> &st, unsigned char *tileQ, int lane,
-                                            const ApplyOperands<DP, HILO> &A, float eps)
+template <bool HILO, int DEPTH, bool ROPE>
+__device__ __forceinline__ void apply_tiles(ApplyStream<DEPTH, ROPE> &st, unsigned char *tileQ, int lane,
+                                            const ApplyOperands<64, HILO> &A, float eps)
 {
-    using Stream = ApplyStream<DP, DEPTH, ROPE>;
     constexpr int NS = HILO ? 2 : 1;
-    constexpr int KS = DP / 16;
-    constexpr int kRow = apply_row_bytes<DP>();
+    constexpr int KS = 4;
+    constexpr int kRow = kRowBytes;
     constexpr int kTileBytes = kApplyTile * kRow;
     const int n = lane & 31, g = lane >> 5;
-    const int wr_off = (lane / Stream::LPR) * kRow + (lane % Stream::LPR) * 16;   // where a loaded chunk goes
-    const int rd_off = (lane >> 3) * kRow + (lane & 7) * 16;                       // where an output chunk comes from
+    const int wr_off = (lane >> 3) * kRow + (lane & 7) * 16;   // the lane's chunk of a coalesced tile
 
     auto round = [&](int i0) __attribute__((always_inline)) {
 #pragma unroll
         for (int s = 0; s < DEPTH; ++s) {
             __builtin_amdgcn_sched_barrier(0);   // stages stay in program order (see state_accumulate)
             const bool valid = i0 + s < st.walk.count;
-            const uint32_t out_off = st.valid_o ? st.walk.template offset<kApplyTile>(i0 + s, st.row_bytes) : kOutOfRange;
+            const uint32_t out_off = st.walk.template offset<kApplyTile>(i0 + s, st.row_bytes);
             if (valid) {
                 wave_lds_fence();
 #pragma unroll
-                for (int j = 0; j < Stream::NLD; ++j) {
+                for (int j = 0; j < kApplyTile / 8; ++j) {
                     const u32x4 pq = relu_bf16x8(st.q[s][j]);                          // phi(Q)
-                    *reinterpret_cast<u32x4 *>(tileQ + wr_off + Stream::RPI * j * kRow) = pq;
+                    *reinterpret_cast<u32x4 *>(tileQ + wr_off + 8 * j * kRow) = pq;
                     if (ROPE)
-                        *reinterpret_cast<u32x4 *>(tileQ + kTileBytes + wr_off + Stream::RPI * j * kRow) =
+                        *reinterpret_cast<u32x4 *>(tileQ + kTileBytes + wr_off + 8 * j * kRow) =
                             rope_rotate_bf16x8(pq, st.cs[ROPE ? s : 0][j][0], st.cs[ROPE ? s : 0][j][1]);
                 }
             }
@@ -252,11 +231,11 @@ __device__ __forceinline__ void apply_tiles(ApplyStream<DP, DEPTH, ROPE> &st, un
                 wave_lds_fence();
 #pragma unroll
                 for (int i = 0; i < kApplyTile / 8; ++i)
-                    o[i] = *reinterpret_cast<const u32x4 *>(tileQ + rd_off + 8 * i * kRow);
+                    o[i] = *reinterpret_cast<const u32x4 *>(tileQ + wr_off + 8 * i * kRow);
             }
 #pragma unroll
             for (int i = 0; i < kApplyTile / 8; ++i)
-                store_stream16(st.rO, out_off + st.lane_off_o + (uint32_t)i * 8u * st.row_bytes, o[i]);
+                store_stream16(st.rO, out_off + st.lane_off + (uint32_t)i * 8u * st.row_bytes, o[i]);
         }
     };
     // The first round stands apart so that the loop is entered with the same sequence of
@@ -267,47 +246,35 @@ __device__ __forceinline__ void apply_tiles(ApplyStream<DP, DEPTH, ROPE> &st, un
 }
 
 // LDS bytes per wave and in total: one tile, two with ROPE (plain + rotated copy).
-template <int DP, bool ROPE>
-__host__ __device__ constexpr int apply_wave_lds_bytes() { return (ROPE ? 2 : 1) * kApplyTile * apply_row_bytes<DP>(); }
-template <int DP, int WAVES, bool ROPE>
-__host__ __device__ constexpr int apply_lds_bytes() { return WAVES * apply_wave_lds_bytes<DP, ROPE>(); }
+template <bool ROPE>
+__host__ __device__ constexpr int apply_wave_lds_bytes() { return (ROPE ? 2 : 1) * kApplyTile * kRowBytes; }
+template <int WAVES, bool ROPE>
+__host__ __device__ constexpr int apply_lds_bytes() { return WAVES * apply_wave_lds_bytes<ROPE>(); }
 
-// How the waves of workgroup c of C split a head's tiles and output features.
-//   DP = 64:  wave w owns tiles WAVES*c + w + WAVES*C*i (i = 0, 1, ...) and all 64 features;
-//   DP = 128: waves 2t, 2t+1 own tiles (WAVES/2)*c + t + (WAVES/2)*C*i; wave w writes value block w%2.
-template <int DP, int WAVES>
-struct ApplySplit {
-    int first, step, vb;
-    __device__ __forceinline__ ApplySplit(int c, int C, int wave)
-        : first(DP == 64 ? WAVES * c + wave : (WAVES / 2) * c + (wave >> 1)),
-          step(DP == 64 ? WAVES * C : (WAVES / 2) * C), vb(DP == 64 ? 0 : wave & 1) {}
-};
-
-// grid = (C, B*H), block = 64*WAVES; the T = ceil((t1-t0)/32) tiles are dealt
-// round-robin as in the state kernel.  DP = 64 serves d = 64, DP = 128 serves
-// d = 112 and 128.  HILO = false drops the low half of S (one MFMA pass instead of two).
-template <int DP, bool HILO, int WAVES, int DEPTH, bool ROPE>
-__global__ __launch_bounds__(64 * WAVES, 1) void apply_mfma(
+// grid = (C, B*H), block = 64*WAVES.  Wave w of workgroup c owns tiles
+// WAVES*c + w + WAVES*C*i (i = 0, 1, ...) of the T = ceil((t1-t0)/32) tiles,
+// the same round-robin deal as the state kernel.
+// HILO = false drops the low half of S (one MFMA pass instead of two).
+template <bool HILO, int WAVES, int DEPTH, bool ROPE>
+__global__ __launch_bounds__(64 * WAVES, 1) void apply_mfma_d64(
     const uint16_t *__restrict__ Q, uint16_t *__restrict__ O, const float *__restrict__ rope, TokStrides st, int H,
-    int d_arg, int t0, int t1, int C, const float *__restrict__ S, const float *__restrict__ z, float eps)
+    int d_unused, int t0, int t1, int C, const float *__restrict__ S, const float *__restrict__ z, float eps)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = blockIdx.x, bh = blockIdx.y;
     const int b = bh / H, h = bh % H;
-    const int d = DP == 64 ? 64 : d_arg;
     const uint16_t *Qh = Q + b * st.b + h * st.h;
     uint16_t *Oh = O + b * st.b + h * st.h;
     const int n_tiles = (t1 - t0 + kApplyTile - 1) / kApplyTile;
-    const ApplySplit<DP, WAVES> split(c, C, wave);
 
-    ApplyStream<DP, DEPTH, ROPE> stream(Qh, Oh, rope, st.n, t1, d, split.vb, lane,
-                                        TileWalk(t0, split.first, split.step, n_tiles, bh));
+    ApplyStream<DEPTH, ROPE> stream(Qh, Oh, rope, st.n, t1, lane,
+                                    TileWalk(t0, WAVES * c + wave, WAVES * C, n_tiles, bh));
     apply_prefetch<0, DEPTH>(stream);   // in flight while S is fetched
-    ApplyOperands<DP, HILO> A;
-    A.template load<false>(S + (size_t)bh * d * d, z + (size_t)bh * d, d, split.vb, lane);
-    apply_tiles<DP, HILO>(stream, lds + wave * apply_wave_lds_bytes<DP, ROPE>(), lane, A, eps);
+    ApplyOperands<64, HILO> A;
+    A.template load<false>(S + (size_t)bh * 64 * 64, z + (size_t)bh * 64, 64, 0, lane);
+    apply_tiles<HILO>(stream, lds + wave * apply_wave_lds_bytes<ROPE>(), lane, A, eps);
 }
 
 }  // namespace sv

@@ -17,19 +17,22 @@
 #pragma once
 
 #include "apply_mfma.hpp"
+#include "coop128.hpp"
 #include "state_mfma.hpp"
 
 namespace sv {
 
 template <int DP, int TILE, int WAVES, bool ROPE>
 __host__ __device__ constexpr int block_step_lds_bytes() {
-    return state_lds_bytes<TILE, WAVES>() > apply_lds_bytes<DP, WAVES, ROPE>() ? state_lds_bytes<TILE, WAVES>()
-                                                                               : apply_lds_bytes<DP, WAVES, ROPE>();
+    constexpr int s = DP == 64 ? state_lds_bytes<TILE, WAVES>() : state_d128_lds_bytes<ROPE>();
+    constexpr int a = DP == 64 ? apply_lds_bytes<WAVES, ROPE>() : coop_apply_lds_bytes<ROPE>();
+    return s > a ? s : a;
 }
 
 // grid = (C, B*H) with C*B*H <= resident workgroup capacity, block = 64*WAVES.
-// DP = 64 serves d = 64, DP = 128 serves d = 112 and 128 (waves split features as
-// in state_mfma and apply_mfma).
+// DP = 64 serves d = 64 (waves work alone, as in state_mfma_d64 and apply_mfma_d64),
+// DP = 128 serves d = 112 and 128 (waves share tiles, as in state_mfma_d128 and
+// apply_mfma_d128; WAVES must be 4).
 // ROPE: keys and queries are rotated after the ReLU in the numerator path (table row = token of the block).
 template <int DP, int TILE, int WAVES, int DEPTH_S, bool HILO, int DEPTH_A, bool ROPE>
 __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
@@ -39,6 +42,7 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
     unsigned long long epoch, uint32_t spin_limit)
 {
     static_assert(TILE == kApplyTile, "both phases walk tiles of the same size");
+    static_assert(DP == 64 || WAVES == 4, "the cooperative kernels are written for four waves");
     constexpr int THREADS = 64 * WAVES;
     constexpr int kTileBytes = TILE * kRowBytes;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -54,48 +58,64 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
     // arrays when the step commits, a scratch copy when it only looks ahead
     const float *Sc = S_in + (size_t)bh * d * d, *zc = z_in + (size_t)bh * d;
     float *Sh = S_out + (size_t)bh * d * d, *zh = z_out + (size_t)bh * d;
+    float *partials = static_cast<float *>(ws) + (size_t)bh * kMaxChunks * elems;
 
-    // ---- this wave's first two tiles of Q_b are requested right away: they arrive during the state
-    //      phase and make no later load wait behind them ---------------------------------------------
-    const ApplySplit<DP, WAVES> asplit(c, C, wave);
-    constexpr int kEarly = DEPTH_A < 2 ? DEPTH_A : 2;
-    ApplyStream<DP, DEPTH_A, ROPE> qstream(Q + head_off, O + head_off, rope, st.n, N, d, asplit.vb, lane,
-                                           TileWalk(0, asplit.first, asplit.step, n_tiles, bh));
-    apply_prefetch<0, kEarly>(qstream);
-
-    // ---- fold this workgroup's share of K_b, V_b ------------------------------------------------
-    {
-        const StateSplit<DP, WAVES> ssplit(c, C, wave);
-        StateAcc acc;
-        acc.clear();
-        StateStream<TILE, DEPTH_S, ROPE, DP == 64> kvstream(K + head_off, V + head_off, rope, st.n, N, d, ssplit.kb, ssplit.vb,
-                                                  lane, TileWalk(0, ssplit.first, ssplit.step, n_tiles, bh));
-        unsigned char *tileK = lds + wave * 2 * kTileBytes;
-        state_prefetch(kvstream);
-        state_accumulate(kvstream, tileK, tileK + kTileBytes, lane, ssplit.vb == 0, acc);
-        // the rest of this wave's Q prefetch streams in while the head's state is being agreed on
-        apply_prefetch<kEarly, DEPTH_A>(qstream);
-        float *partials = static_cast<float *>(ws) + (size_t)bh * kMaxChunks * elems;
-        if (DP == 64)
-            state_wg_reduce_store<WAVES, ROPE>(acc, reinterpret_cast<float *>(lds), wave, lane,
-                                         partials + (size_t)c * elems);
-        else
-            state_wg_quadrant_store<ROPE>(acc, reinterpret_cast<float *>(lds), wave, lane, d, partials + (size_t)c * elems);
-    }
-
-    // ---- once all partials of the head are there, fold this workgroup's slice into S, z in place,
-    //      then wait for the other slices -------------------------------------------------------
-    {
-        const float *partials = static_cast<const float *>(ws) + (size_t)bh * kMaxChunks * elems;
+    // Once all partials of the head are there, fold this workgroup's slice into S, z, then wait for
+    // the other slices.
+    auto agree_on_state = [&]() __attribute__((always_inline)) {
         state_publish_and_wait(ws, BH, elems, bh, c, C, 0, epoch, spin_limit, lane);
         state_finalize_slice<THREADS, true>(partials, c, C, d, Sc, zc, Sh, zh);
         state_publish_and_wait(ws, BH, elems, bh, c, C, 1, epoch, spin_limit, lane);
-    }
+    };
 
-    // ---- apply the updated state to this workgroup's share of Q_b ----------------------------------
-    ApplyOperands<DP, HILO> A;
-    A.template load<true>(Sh, zh, d, asplit.vb, lane);
-    apply_tiles<DP, HILO>(qstream, lds + wave * apply_wave_lds_bytes<DP, ROPE>(), lane, A, eps);
+    if constexpr (DP == 64) {
+        // ---- this wave's first two tiles of Q_b are requested right away: they arrive during the
+        //      state phase and make no later load wait behind them --------------------------------
+        constexpr int kEarly = DEPTH_A < 2 ? DEPTH_A : 2;
+        const TileWalk walk(0, WAVES * c + wave, WAVES * C, n_tiles, bh);
+        ApplyStream<DEPTH_A, ROPE> qstream(Q + head_off, O + head_off, rope, st.n, N, lane, walk);
+        apply_prefetch<0, kEarly>(qstream);
+
+        // ---- fold this workgroup's share of K_b, V_b ----------------------------------------------
+        {
+            StateAcc acc;
+            acc.clear();
+            StateStream<TILE, DEPTH_S, ROPE> kvstream(K + head_off, V + head_off, rope, st.n, N, lane, walk);
+            unsigned char *tileK = lds + wave * 2 * kTileBytes;
+            state_prefetch(kvstream);
+            state_accumulate(kvstream, tileK, tileK + kTileBytes, lane, acc);
+            // the rest of this wave's Q prefetch streams in while the head's state is being agreed on
+            apply_prefetch<kEarly, DEPTH_A>(qstream);
+            state_wg_reduce_store<WAVES, ROPE>(acc, reinterpret_cast<float *>(lds), wave, lane,
+                                               partials + (size_t)c * elems);
+        }
+        agree_on_state();
+
+        // ---- apply the updated state to this workgroup's share of Q_b --------------------------------
+        ApplyOperands<64, HILO> A;
+        A.template load<true>(Sh, zh, 64, 0, lane);
+        apply_tiles<HILO>(qstream, lds + wave * apply_wave_lds_bytes<ROPE>(), lane, A, eps);
+    } else {
+        constexpr int kEarly = DEPTH_A < 2 ? DEPTH_A : 2;
+        CoopApplyStream<DEPTH_A, ROPE> qstream(Q + head_off, O + head_off, rope, st.n, N, d, wave, lane,
+                                               TileWalk(0, c, C, (N + 63) / 64, bh));
+        coop_apply_prefetch<0, kEarly>(qstream);
+        {
+            StateAcc acc;
+            acc.clear();
+            CoopStateStream<DEPTH_S, ROPE> kvstream(K + head_off, V + head_off, rope, st.n, N, d, wave, lane,
+                                                    TileWalk(0, c, C, n_tiles, bh));
+            coop_state_prefetch(kvstream);
+            state_accumulate_coop(kvstream, lds, wave, lane, wave & 1, wave >> 1, acc);
+            coop_apply_prefetch<kEarly, DEPTH_A>(qstream);
+            state_wg_quadrant_store(acc, reinterpret_cast<float *>(lds), wave, lane, d, partials + (size_t)c * elems);
+        }
+        agree_on_state();
+        __syncthreads();   // the reduction slots in LDS are dead before the apply phase reuses the space
+        ApplyOperands<128, HILO> A;
+        A.template load<true>(Sh, zh, d, wave & 1, lane);
+        apply_tiles_coop<HILO>(qstream, lds, wave, lane, A, eps);
+    }
 }
 
 }  // namespace sv

@@ -1,0 +1,359 @@
+// Token streaming for d = 112 and 128 (DP = 128): the four waves of a workgroup
+// work on the same tile together.
+//
+// With 64 features a wave can keep a whole 64 x 64 state (or a 64-column panel
+// of it) to itself and never talks to its neighbours.  With 128 the state is
+// four such quadrants and the apply needs two panels, so every token row is
+// needed by two waves.  Letting both fetch it costs far more than the extra
+// instructions: half rows of 224 or 256 bytes split cache lines between waves
+// and the non-temporal streams fetch them twice (measured: 2.4 TB/s instead of
+// 5.4).  Here each wave loads whole rows that nobody else loads, the tile is
+// assembled in workgroup-shared LDS, and one barrier per tile (state) or two per
+// pair of tiles (apply) hand it to the waves that compute:
+//
+//   state: wave w loads rows 8w .. 8w+8 of K and V of the tile, then folds key
+//          block w%2 against value block w/2 (a 64 x 64 quadrant) from LDS;
+//   apply: wave w loads rows 16w .. 16w+16 of a pair of Q tiles, computes value
+//          block w%2 of tile w/2 into a shared output tile, then stores whole
+//          rows 16w .. 16w+16 of O.
+//
+// Barriers are bare s_barrier instructions behind an LDS-only wait, so the
+// global loads of later tiles and the stores of earlier ones stay in flight
+// across them.  For d = 112 the features past 112 are addressed out of range:
+// they read as zeros and their stores are dropped.
+#pragma once
+
+#include "apply_mfma.hpp"
+#include "state_mfma.hpp"
+
+namespace sv {
+
+constexpr int kCoopRow = 128 * 2 + 16;           // LDS row: 128 bf16 features + padding
+constexpr int kCoopTile = 32 * kCoopRow;         // one 32-token tile in LDS
+
+// All LDS traffic of this wave is done, then all waves of the workgroup meet.
+// Global memory traffic is not waited for.
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// ---- state ---------------------------------------------------------------------------------------
+
+// One wave's share of the workgroup's K/V stream: rows 8*wave .. +8 of every tile
+// (16 lanes of 16 bytes per row, 4 rows per load instruction), DEPTH tiles in flight.
+template <int DEPTH, bool ROPE>
+struct CoopStateStream {
+    static constexpr int NLD = 2;
+    rsrc_t rK, rV, rT;
+    uint32_t row_bytes, table_row_bytes, lane_off, lane_off_t;
+    bool valid;
+    TileWalk walk;                       // the workgroup's tiles: identical in all four waves
+    u32x4 k[DEPTH][NLD], v[DEPTH][NLD];
+    f32x4 cs[ROPE ? DEPTH : 1][NLD][2];
+
+    __device__ __forceinline__ CoopStateStream(const uint16_t *Kh, const uint16_t *Vh, const float *rope,
+                                               int64_t stride_n, int t1, int d, int wave, int lane, const TileWalk &w)
+        : rK(make_rsrc(Kh, (uint32_t)t1 * (uint32_t)stride_n * 2u)),
+          rV(make_rsrc(Vh, (uint32_t)t1 * (uint32_t)stride_n * 2u)),
+          rT(make_rsrc(rope, ROPE ? (uint32_t)t1 * (uint32_t)d * 4u : 0u)), row_bytes((uint32_t)stride_n * 2u),
+          table_row_bytes((uint32_t)d * 4u), walk(w)
+    {
+        const uint32_t row = 8u * (uint32_t)wave + (uint32_t)(lane >> 4), col = (uint32_t)(lane & 15);
+        lane_off = row * row_bytes + col * 16u;
+        lane_off_t = row * table_row_bytes + col * 32u;
+        valid = (int)col * 8 < d;
+    }
+
+    __device__ __forceinline__ void request(int s, int i)
+    {
+        const uint32_t base = valid ? walk.offset<32>(i, row_bytes) : kOutOfRange;
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) {
+            k[s][j] = load_stream16(rK, base + lane_off + (uint32_t)j * 4u * row_bytes);
+            v[s][j] = load_stream16(rV, base + lane_off + (uint32_t)j * 4u * row_bytes);
+        }
+        if (ROPE)
+            rope_tile_load<NLD>(rT, valid ? walk.offset<32>(i, table_row_bytes) : kOutOfRange, lane_off_t,
+                                4u * table_row_bytes, cs[ROPE ? s : 0]);
+    }
+};
+
+template <int DEPTH, bool ROPE>
+__device__ __forceinline__ void coop_state_prefetch(CoopStateStream<DEPTH, ROPE> &st)
+{
+#pragma unroll
+    for (int s = 0; s < DEPTH; ++s) {
+        st.request(s, s);
+        __builtin_amdgcn_sched_barrier(0);   // requests go out in stage order, as they do in the loop
+    }
+}
+
+// LDS of the state phase: K and V tiles, double-buffered; with ROPE also the
+// un-rotated phi(K) (the key sum is never rotated).
+template <bool ROPE> __host__ __device__ constexpr int coop_state_lds_bytes() { return (ROPE ? 6 : 4) * kCoopTile; }
+
+// Accumulates quadrant (kb, vb) of the workgroup's partial state over the
+// workgroup's tiles.  Must be called by all four waves (it contains barriers; the
+// tile count is the same in all of them).  Key sums are kept by the waves with vb == 0.
+template <int DEPTH, bool ROPE>
+__device__ __forceinline__ void state_accumulate_coop(CoopStateStream<DEPTH, ROPE> &st, unsigned char *lds, int wave,
+                                                      int lane, int kb, int vb, StateAcc &acc)
+{
+    static_assert(DEPTH % 2 == 0, "stage parity selects the LDS buffer");
+    const int wr_off = (8 * wave + (lane >> 4)) * kCoopRow + (lane & 15) * 16;
+    const uint32_t one2 = 0x3f803f80u;   // bf16 (1.0, 1.0)
+    const u32x4 ones4 = {one2, one2, one2, one2};
+    const bf16x8 ones = __builtin_bit_cast(bf16x8, ones4);
+
+    for (int i0 = 0; i0 < st.walk.count; i0 += DEPTH) {
+#pragma unroll
+        for (int s = 0; s < DEPTH; ++s) {
+            __builtin_amdgcn_sched_barrier(0);   // stages stay in program order
+            const bool valid = i0 + s < st.walk.count;
+            unsigned char *bufK = lds + (s & 1) * kCoopTile, *bufV = lds + (2 + (s & 1)) * kCoopTile;
+            unsigned char *bufP = ROPE ? lds + (4 + (s & 1)) * kCoopTile : bufK;   // un-rotated phi(K)
+            if (valid) {
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const u32x4 kk = relu_bf16x8(st.k[s][j]);
+                    if (ROPE) {
+                        *reinterpret_cast<u32x4 *>(bufP + wr_off + 4 * j * kCoopRow) = kk;
+                        *reinterpret_cast<u32x4 *>(bufK + wr_off + 4 * j * kCoopRow) =
+                            rope_rotate_bf16x8(kk, st.cs[ROPE ? s : 0][j][0], st.cs[ROPE ? s : 0][j][1]);
+                    } else {
+                        *reinterpret_cast<u32x4 *>(bufK + wr_off + 4 * j * kCoopRow) = kk;
+                    }
+                    *reinterpret_cast<u32x4 *>(bufV + wr_off + 4 * j * kCoopRow) = st.v[s][j];
+                }
+            }
+            st.request(s, i0 + s + DEPTH);   // refill this stage: DEPTH tiles ahead
+            __builtin_amdgcn_sched_barrier(0);
+            if (valid) {
+                // The tile is complete after this barrier.  Its buffer is written again two tiles
+                // later, by waves that have passed the next tile's barrier, which every wave
+                // reaches only after it is done reading this one.
+                lds_barrier();
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) {
+                    const bf16x8 a0 = lds_tr_operand<kCoopRow>(bufK, 16 * ks, 64 * kb, lane);
+                    const bf16x8 a1 = lds_tr_operand<kCoopRow>(bufK, 16 * ks, 64 * kb + 32, lane);
+                    const bf16x8 b0 = lds_tr_operand<kCoopRow>(bufV, 16 * ks, 64 * vb, lane);
+                    const bf16x8 b1 = lds_tr_operand<kCoopRow>(bufV, 16 * ks, 64 * vb + 32, lane);
+                    acc.s[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc.s[0][0], 0, 0, 0);
+                    acc.s[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc.s[0][1], 0, 0, 0);
+                    acc.s[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc.s[1][0], 0, 0, 0);
+                    acc.s[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc.s[1][1], 0, 0, 0);
+                    if (vb == 0) {
+                        const bf16x8 p0 = ROPE ? lds_tr_operand<kCoopRow>(bufP, 16 * ks, 64 * kb, lane) : a0;
+                        const bf16x8 p1 = ROPE ? lds_tr_operand<kCoopRow>(bufP, 16 * ks, 64 * kb + 32, lane) : a1;
+                        acc.zm[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p0, ones, acc.zm[0], 0, 0, 0);
+                        acc.zm[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p1, ones, acc.zm[1], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ---- apply ---------------------------------------------------------------------------------------
+
+// One wave's share of the workgroup's Q/O stream: rows 16*wave .. +16 of every
+// pair of tiles (64 tokens), both for the loads of Q and for the stores of O.
+template <int DEPTH, bool ROPE>
+struct CoopApplyStream {
+    static constexpr int NLD = 4;
+    rsrc_t rQ, rO, rT;
+    uint32_t row_bytes, table_row_bytes, lane_off, lane_off_t;
+    bool valid;
+    TileWalk walk;                       // the workgroup's tile pairs (units of 64 tokens)
+    u32x4 q[DEPTH][NLD];
+    f32x4 cs[ROPE ? DEPTH : 1][NLD][2];
+
+    __device__ __forceinline__ CoopApplyStream(const uint16_t *Qh, uint16_t *Oh, const float *rope, int64_t stride_n,
+                                               int t1, int d, int wave, int lane, const TileWalk &w)
+        : rQ(make_rsrc(Qh, (uint32_t)t1 * (uint32_t)stride_n * 2u)),
+          rO(make_rsrc(Oh, (uint32_t)t1 * (uint32_t)stride_n * 2u)),
+          rT(make_rsrc(rope, ROPE ? (uint32_t)t1 * (uint32_t)d * 4u : 0u)), row_bytes((uint32_t)stride_n * 2u),
+          table_row_bytes((uint32_t)d * 4u), walk(w)
+    {
+        const uint32_t row = 16u * (uint32_t)wave + (uint32_t)(lane >> 4), col = (uint32_t)(lane & 15);
+        lane_off = row * row_bytes + col * 16u;
+        lane_off_t = row * table_row_bytes + col * 32u;
+        valid = (int)col * 8 < d;
+    }
+
+    __device__ __forceinline__ void request(int s, int i)
+    {
+        const uint32_t base = valid ? walk.offset<64>(i, row_bytes) : kOutOfRange;
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) q[s][j] = load_stream16(rQ, base + lane_off + (uint32_t)j * 4u * row_bytes);
+        if (ROPE)
+            rope_tile_load<NLD>(rT, valid ? walk.offset<64>(i, table_row_bytes) : kOutOfRange, lane_off_t,
+                                4u * table_row_bytes, cs[ROPE ? s : 0]);
+    }
+};
+
+template <int FROM, int TO, int DEPTH, bool ROPE>
+__device__ __forceinline__ void coop_apply_prefetch(CoopApplyStream<DEPTH, ROPE> &st)
+{
+#pragma unroll
+    for (int s = FROM; s < TO; ++s) {
+        st.request(s, s);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// LDS of the apply phase: a pair of Q tiles (with ROPE also their rotated copy) and a pair of O tiles.
+template <bool ROPE> __host__ __device__ constexpr int coop_apply_lds_bytes() { return (ROPE ? 6 : 4) * kCoopTile; }
+
+// Applies the state panel in `A` (value block wave%2) to tile wave/2 of every pair
+// of the workgroup's share.  Must be called by all four waves.
+template <bool HILO, int DEPTH, bool ROPE>
+__device__ __forceinline__ void apply_tiles_coop(CoopApplyStream<DEPTH, ROPE> &st, unsigned char *lds, int wave,
+                                                 int lane, const ApplyOperands<128, HILO> &A, float eps)
+{
+    constexpr int NS = HILO ? 2 : 1;
+    const int t = wave >> 1, vb = wave & 1;
+    const int n = lane & 31, g = lane >> 5;
+    unsigned char *bufQ = lds, *bufR = ROPE ? lds + 2 * kCoopTile : lds, *bufO = lds + (ROPE ? 4 : 2) * kCoopTile;
+    const int wr_off = (16 * wave + (lane >> 4)) * kCoopRow + (lane & 15) * 16;   // the wave's own rows
+    const unsigned char *brow = bufQ + (32 * t + n) * kCoopRow, *rrow = bufR + (32 * t + n) * kCoopRow;
+    unsigned char *orow = bufO + (32 * t + n) * kCoopRow + (64 * vb + 32 * g) * 2;
+
+    auto round = [&](int i0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int s = 0; s < DEPTH; ++s) {
+            __builtin_amdgcn_sched_barrier(0);   // stages stay in program order
+            const bool valid = i0 + s < st.walk.count;
+            const uint32_t out_off = st.valid ? st.walk.template offset<64>(i0 + s, st.row_bytes) : kOutOfRange;
+            if (valid) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const u32x4 pq = relu_bf16x8(st.q[s][j]);                          // phi(Q)
+                    *reinterpret_cast<u32x4 *>(bufQ + wr_off + 4 * j * kCoopRow) = pq;
+                    if (ROPE)
+                        *reinterpret_cast<u32x4 *>(bufR + wr_off + 4 * j * kCoopRow) =
+                            rope_rotate_bf16x8(pq, st.cs[ROPE ? s : 0][j][0], st.cs[ROPE ? s : 0][j][1]);
+                }
+            }
+            st.request(s, i0 + s + DEPTH);   // refill this stage: DEPTH pairs ahead
+            __builtin_amdgcn_sched_barrier(0);
+            u32x4 o[4] = {};
+            if (valid) {
+                // Q tiles complete.  They are overwritten in the next round, by waves that have
+                // passed the second barrier below, which every wave reaches after its reads.
+                lds_barrier();
+                f32x16 acc[2], accz;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) { acc[0][i] = 0.f; acc[1][i] = 0.f; accz[i] = 0.f; }
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks) {
+                    const bf16x8 bq = *reinterpret_cast<const bf16x8 *>(brow + (16 * ks + 8 * g) * 2);
+                    const bf16x8 br = ROPE ? *reinterpret_cast<const bf16x8 *>(rrow + (16 * ks + 8 * g) * 2) : bq;
+                    accz = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.zrow[ks], bq, accz, 0, 0, 0);
+#pragma unroll
+                    for (int p = NS - 1; p >= 0; --p) {      // small (lo) terms first
+                        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.s[p][0][ks], br, acc[0], 0, 0, 0);
+                        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.s[p][1][ks], br, acc[1], 0, 0, 0);
+                    }
+                }
+                float den = accz[1] + accz[0];      // rows 0 (hi) and 1 (lo) of the z block
+                den = __shfl(den, n);
+                const float inv = 1.0f / (den + eps);
+#pragma unroll
+                for (int rb = 0; rb < 2; ++rb) {
+                    const f32x16 &a = acc[rb];
+                    u32x4 lo4, hi4;
+                    lo4.x = pack_bf16x2(a[0] * inv, a[1] * inv);
+                    lo4.y = pack_bf16x2(a[2] * inv, a[3] * inv);
+                    lo4.z = pack_bf16x2(a[4] * inv, a[5] * inv);
+                    lo4.w = pack_bf16x2(a[6] * inv, a[7] * inv);
+                    hi4.x = pack_bf16x2(a[8] * inv, a[9] * inv);
+                    hi4.y = pack_bf16x2(a[10] * inv, a[11] * inv);
+                    hi4.z = pack_bf16x2(a[12] * inv, a[13] * inv);
+                    hi4.w = pack_bf16x2(a[14] * inv, a[15] * inv);
+                    *reinterpret_cast<u32x4 *>(orow + 32 * rb) = lo4;
+                    *reinterpret_cast<u32x4 *>(orow + 32 * rb + 16) = hi4;
+                }
+                // O tiles complete after this barrier; they are overwritten after the first
+                // barrier of the next round, which every wave reaches after the reads below.
+                lds_barrier();
+#pragma unroll
+                for (int j = 0; j < 4; ++j) o[j] = *reinterpret_cast<const u32x4 *>(bufO + wr_off + 4 * j * kCoopRow);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                store_stream16(st.rO, out_off + st.lane_off + (uint32_t)j * 4u * st.row_bytes, o[j]);
+        }
+    };
+    // first round apart: the loop is entered in its own steady state of outstanding loads and stores
+    if (st.walk.count > 0) round(0);
+    for (int i0 = DEPTH; i0 < st.walk.count; i0 += DEPTH) round(i0);
+}
+
+// ---- kernels ---------------------------------------------------------------------------------------
+
+// Dynamic LDS: the larger of the streaming buffers and the four reduction slots.
+template <bool ROPE>
+__host__ __device__ constexpr int state_d128_lds_bytes() {
+    return coop_state_lds_bytes<ROPE>() > 4 * kStateElems * 4 ? coop_state_lds_bytes<ROPE>() : 4 * kStateElems * 4;
+}
+
+// State reduction for d = 112 or 128.  grid = (C, B*H), block = 256; workgroup c
+// owns tiles c + C*i of the T = ceil((t1-t0)/32) tiles.  FINALIZE and ROPE as in
+// state_mfma_d64; partial states and S are d x d with row length d.
+template <int DEPTH, bool FINALIZE, bool ROPE>
+__global__ __launch_bounds__(256, 1) void state_mfma_d128(
+    const uint16_t *__restrict__ K, const uint16_t *__restrict__ V, const float *__restrict__ rope, TokStrides st,
+    int H, int d, int t0, int t1, int C, const float *S_in, const float *z_in, float *S_out, float *z_out,
+    void *__restrict__ ws, unsigned long long epoch, uint32_t spin_limit)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c = blockIdx.x, bh = blockIdx.y, BH = gridDim.y;
+    const int b = bh / H, h = bh % H;
+    const int elems = d * d + d;
+    const uint16_t *Kh = K + b * st.b + h * st.h;
+    const uint16_t *Vh = V + b * st.b + h * st.h;
+    const int n_tiles = (t1 - t0 + 31) / 32;
+
+    StateAcc acc;
+    acc.clear();
+    CoopStateStream<DEPTH, ROPE> stream(Kh, Vh, rope, st.n, t1, d, wave, lane, TileWalk(t0, c, C, n_tiles, bh));
+    coop_state_prefetch(stream);
+    state_accumulate_coop(stream, lds, wave, lane, wave & 1, wave >> 1, acc);
+
+    float *partials = static_cast<float *>(ws) + (size_t)bh * kMaxChunks * elems;
+    state_wg_quadrant_store(acc, reinterpret_cast<float *>(lds), wave, lane, d, partials + (size_t)c * elems);
+    if (FINALIZE) {
+        state_publish_and_wait(ws, BH, elems, bh, c, C, 0, epoch, spin_limit, lane);
+        state_finalize_slice<256, false>(partials, c, C, d, S_in ? S_in + (size_t)bh * d * d : nullptr,
+                                         z_in + (size_t)bh * d, S_out + (size_t)bh * d * d, z_out + (size_t)bh * d);
+    }
+}
+
+// Apply for d = 112 or 128.  grid = (C, B*H), block = 256; workgroup c owns the
+// pairs of tiles c + C*i of the ceil((t1-t0)/64) pairs.
+template <bool HILO, int DEPTH, bool ROPE>
+__global__ __launch_bounds__(256, 1) void apply_mfma_d128(
+    const uint16_t *__restrict__ Q, uint16_t *__restrict__ O, const float *__restrict__ rope, TokStrides st, int H,
+    int d, int t0, int t1, int C, const float *__restrict__ S, const float *__restrict__ z, float eps)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c = blockIdx.x, bh = blockIdx.y;
+    const int b = bh / H, h = bh % H;
+    const uint16_t *Qh = Q + b * st.b + h * st.h;
+    uint16_t *Oh = O + b * st.b + h * st.h;
+    const int n_pairs = (t1 - t0 + 63) / 64;
+
+    CoopApplyStream<DEPTH, ROPE> stream(Qh, Oh, rope, st.n, t1, d, wave, lane, TileWalk(t0, c, C, n_pairs, bh));
+    coop_apply_prefetch<0, DEPTH>(stream);   // in flight while S is fetched
+    ApplyOperands<128, HILO> A;
+    A.template load<false>(S + (size_t)bh * d * d, z + (size_t)bh * d, d, wave & 1, lane);
+    apply_tiles_coop<HILO>(stream, lds, wave, lane, A, eps);
+}
+
+}  // namespace sv

@@ -1,4 +1,4 @@
-// bf16 MFMA state reduction for d = 64, 112 and 128 on gfx950.
+// bf16 MFMA state reduction for d = 64 on gfx950 (and the parts shared with d = 112, 128).
 //
 //   S[k][v] (+)= sum_j phi(K[j][k]) V[j][v],   z[k] (+)= sum_j phi(K[j][k])
 //
@@ -23,13 +23,9 @@
 // are published, each of its workgroups adds up one slice of them in chunk
 // order (bit-reproducible, no float atomics).
 //
-// d = 112 and 128 (DP = 128): the state is four 64 x 64 quadrants and the four
-// waves of a workgroup take one each, all walking the same tiles: wave w folds
-// key features 64*(w%2) .. +64 against value features 64*(w/2) .. +64 with the
-// very same code that handles a whole d = 64 tile.  Each half row is then loaded
-// by two waves of the same compute unit at about the same time (the second one
-// is served by the caches, HBM sees it once).  For d = 112 the features past
-// 112 are addressed out of range and read as zeros.
+// d = 112 and 128 are served by the workgroup-cooperative kernels of coop128.hpp,
+// which reuse the pieces below (tile walk, transposing reads, accumulators,
+// partial-state reduction).
 #pragma once
 
 #include "common.hpp"
@@ -118,34 +114,30 @@ struct TileWalk {
     }
 };
 
-// Coalesced load of a TILE x 64 bf16 tile (64 features = 128 bytes of each token
-// row): lane l takes 16 bytes of rows l/8 + 8i.  `off0` is the tile's byte offset
-// (TileWalk::offset), `lane_off` = (l/8) * row_bytes + column bytes of the lane.
-// `lane_valid` = false makes the lane read zeros (features past d).  STREAM: the
-// bytes are read by this wave only (non-temporal); otherwise a second wave
-// reads them too and they should stay cached.
-template <int TILE, bool STREAM>
-__device__ __forceinline__ void token_tile_load(rsrc_t r, uint32_t off0, uint32_t row_bytes, uint32_t lane_off,
-                                                bool lane_valid, u32x4 (&reg)[TILE / 8])
+// Coalesced load of a TILE x 64 bf16 tile: lane l takes bytes 16*(l%8) .. +16 of
+// rows l/8 + 8i.  `off0` is the tile's byte offset (TileWalk::offset).
+template <int TILE>
+__device__ __forceinline__ void token_tile_load(rsrc_t r, uint32_t off0, uint32_t row_bytes, int lane,
+                                                u32x4 (&reg)[TILE / 8])
 {
-    const uint32_t base = lane_valid ? off0 : kOutOfRange;   // kept apart from lane_off: the sum must not wrap
+    const uint32_t lane_off = (uint32_t)(lane >> 3) * row_bytes + (uint32_t)(lane & 7) * 16u;
 #pragma unroll
-    for (int i = 0; i < TILE / 8; ++i)
-        reg[i] = load_tokens16<STREAM>(r, base + lane_off + (uint32_t)i * 8u * row_bytes);
+    for (int i = 0; i < TILE / 8; ++i) reg[i] = load_stream16(r, off0 + lane_off + (uint32_t)i * 8u * row_bytes);
 }
 
 // MFMA operand from a token-major LDS tile: for the lane's MFMA row
 // r = lane%32 and k-group g = lane/32, features f0 + r of tokens tok0 + 8g .. +8.
 // Two transposing reads of four tokens each; within a block of 16 lanes, lane i
 // supplies the address of token (i/4), features 4*(i%4) .. +4 of the block's 16.
+template <int ROWB = kRowBytes>
 __device__ __forceinline__ bf16x8 lds_tr_operand(const unsigned char *tile, int tok0, int f0, int lane)
 {
     typedef short s16x4 __attribute__((ext_vector_type(4)));
     typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
     const int i = lane & 15, fb = (lane >> 4) & 1, g = lane >> 5;
-    const unsigned char *p = tile + (tok0 + 8 * g + (i >> 2)) * kRowBytes + (f0 + 16 * fb + 4 * (i & 3)) * 2;
+    const unsigned char *p = tile + (tok0 + 8 * g + (i >> 2)) * ROWB + (f0 + 16 * fb + 4 * (i & 3)) * 2;
     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p));
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 4 * kRowBytes));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 4 * ROWB));
     typedef short s16x8 __attribute__((ext_vector_type(8)));
     const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
     return __builtin_bit_cast(bf16x8, both);
@@ -153,51 +145,36 @@ __device__ __forceinline__ bf16x8 lds_tr_operand(const unsigned char *tile, int 
 
 // One wave's input stream: buffer resources over the head's K and V rows (and
 // the rotation table) below the end of the token range, the wave's tile walk,
-// and the register staging of DEPTH tiles in flight.  The wave reads key
-// features 64*kb .. +64 and value features 64*vb .. +64 of each token (kb = vb =
-// 0 for d = 64); d is the number of features that exist.
-template <int TILE, int DEPTH, bool ROPE, bool STREAM>
+// and the register staging of DEPTH tiles in flight.
+template <int TILE, int DEPTH, bool ROPE>
 struct StateStream {
     rsrc_t rK, rV, rT;
-    uint32_t row_bytes, table_row_bytes;
-    uint32_t lane_off_k, lane_off_v, lane_off_t;
-    bool valid_k, valid_v;
+    uint32_t row_bytes, lane_off_t;
+    int lane;
     TileWalk walk;
     u32x4 k[DEPTH][TILE / 8], v[DEPTH][TILE / 8];
     f32x4 cs[ROPE ? DEPTH : 1][TILE / 8][2];
 
     __device__ __forceinline__ StateStream(const uint16_t *Kh, const uint16_t *Vh, const float *rope,
-                                           int64_t stride_n, int t1, int d, int kb, int vb, int lane,
-                                           const TileWalk &w)
+                                           int64_t stride_n, int t1, int lane_, const TileWalk &w)
         : rK(make_rsrc(Kh, (uint32_t)t1 * (uint32_t)stride_n * 2u)),
           rV(make_rsrc(Vh, (uint32_t)t1 * (uint32_t)stride_n * 2u)),
-          rT(make_rsrc(rope, ROPE ? (uint32_t)t1 * (uint32_t)d * 4u : 0u)), row_bytes((uint32_t)stride_n * 2u),
-          table_row_bytes((uint32_t)d * 4u), walk(w)
-    {
-        const uint32_t row = (uint32_t)(lane >> 3), col = (uint32_t)(lane & 7);
-        lane_off_k = row * row_bytes + (uint32_t)kb * 128u + col * 16u;
-        lane_off_v = row * row_bytes + (uint32_t)vb * 128u + col * 16u;
-        lane_off_t = row * table_row_bytes + (uint32_t)kb * 256u + col * 32u;
-        valid_k = kb * 64 + (int)col * 8 < d;
-        valid_v = vb * 64 + (int)col * 8 < d;
-    }
+          rT(make_rsrc(rope, ROPE ? (uint32_t)t1 * 256u : 0u)), row_bytes((uint32_t)stride_n * 2u),
+          lane_off_t((uint32_t)(lane_ >> 3) * 256u + (uint32_t)(lane_ & 7) * 32u), lane(lane_), walk(w) {}
 
     // Requests the wave's i-th tile into stage s.  Always the same number of memory
     // instructions: past the wave's share they read nothing and return zeros.
     __device__ __forceinline__ void request(int s, int i)
     {
-        const uint32_t off0 = walk.offset<TILE>(i, row_bytes);
-        token_tile_load<TILE, STREAM>(rK, off0, row_bytes, lane_off_k, valid_k, k[s]);
-        token_tile_load<TILE, STREAM>(rV, off0, row_bytes, lane_off_v, valid_v, v[s]);
-        if (ROPE)
-            rope_tile_load<TILE / 8>(rT, valid_k ? walk.offset<TILE>(i, table_row_bytes) : kOutOfRange, lane_off_t,
-                                     8u * table_row_bytes, cs[ROPE ? s : 0]);
+        token_tile_load<TILE>(rK, walk.offset<TILE>(i, row_bytes), row_bytes, lane, k[s]);
+        token_tile_load<TILE>(rV, walk.offset<TILE>(i, row_bytes), row_bytes, lane, v[s]);
+        if (ROPE) rope_tile_load<TILE / 8>(rT, walk.offset<TILE>(i, 256u), lane_off_t, 8u * 256u, cs[ROPE ? s : 0]);
     }
 };
 
 // Requests the first DEPTH tiles of a wave's share.
-template <int TILE, int DEPTH, bool ROPE, bool STREAM>
-__device__ __forceinline__ void state_prefetch(StateStream<TILE, DEPTH, ROPE, STREAM> &st)
+template <int TILE, int DEPTH, bool ROPE>
+__device__ __forceinline__ void state_prefetch(StateStream<TILE, DEPTH, ROPE> &st)
 {
 #pragma unroll
     for (int s = 0; s < DEPTH; ++s) {
@@ -209,11 +186,10 @@ __device__ __forceinline__ void state_prefetch(StateStream<TILE, DEPTH, ROPE, ST
 // Accumulates the wave's share, whose first DEPTH tiles state_prefetch has
 // requested.  Tiles are taken DEPTH at a time; in the last round the stages past
 // the share hold zeros, as do tokens past t1, and add nothing to either sum.
-// `tileK`/`tileV` are this wave's private LDS tiles.  want_z (wave-uniform):
-// this wave's key sums are needed (plain kernels; RoPE kernels always sum).
-template <int TILE, int DEPTH, bool ROPE, bool STREAM>
-__device__ __forceinline__ void state_accumulate(StateStream<TILE, DEPTH, ROPE, STREAM> &st, unsigned char *tileK,
-                                                 unsigned char *tileV, int lane, bool want_z, StateAcc &acc)
+// `tileK`/`tileV` are this wave's private LDS tiles.
+template <int TILE, int DEPTH, bool ROPE>
+__device__ __forceinline__ void state_accumulate(StateStream<TILE, DEPTH, ROPE> &st, unsigned char *tileK,
+                                                 unsigned char *tileV, int lane, StateAcc &acc)
 {
     static_assert(TILE == 16 || TILE == 32, "tile is one or two MFMA k-steps");
     const int wr_off = (lane >> 3) * kRowBytes + (lane & 7) * 16;
@@ -254,7 +230,7 @@ __device__ __forceinline__ void state_accumulate(StateStream<TILE, DEPTH, ROPE, 
                 acc.s[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc.s[0][1], 0, 0, 0);
                 acc.s[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc.s[1][0], 0, 0, 0);
                 acc.s[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc.s[1][1], 0, 0, 0);
-                if (!ROPE && want_z) {
+                if (!ROPE) {
                     const uint32_t one2 = 0x3f803f80u;   // bf16 (1.0, 1.0)
                     const u32x4 ones4 = {one2, one2, one2, one2};
                     const bf16x8 ones = __builtin_bit_cast(bf16x8, ones4);
@@ -267,8 +243,9 @@ __device__ __forceinline__ void state_accumulate(StateStream<TILE, DEPTH, ROPE, 
 }
 
 // Lays one wave's accumulators out in [k][v] order (64 x 64 floats, then the 64
-// key sums) in its LDS slot `dst`.
-template <bool ROPE>
+// key sums) in its LDS slot `dst`.  ZVALU: the key sums are the per-lane sums
+// acc.z (RoPE kernels for d = 64), otherwise the accumulators acc.zm.
+template <bool ZVALU>
 __device__ __forceinline__ void state_acc_to_slot(StateAcc &acc, float *dst, int lane)
 {
     // 32x32 accumulator layout: register i of lane l is row 8*(i/4) + 4*(l/32) + i%4, column l%32.
@@ -280,9 +257,9 @@ __device__ __forceinline__ void state_acc_to_slot(StateAcc &acc, float *dst, int
             const int k = 32 * rb + 8 * (i >> 2) + 4 * g + (i & 3);
             dst[k * 64 + n] = acc.s[rb][0][i];
             dst[k * 64 + 32 + n] = acc.s[rb][1][i];
-            if (!ROPE && n == 0) dst[64 * 64 + k] = acc.zm[rb][i];   // every column of zm holds the key sums
+            if (!ZVALU && n == 0) dst[64 * 64 + k] = acc.zm[rb][i];   // every column of zm holds the key sums
         }
-    if (ROPE) {
+    if (ZVALU) {
         // lanes with equal lane%8 hold the same 8 features (wavefront-level reduction)
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -329,12 +306,11 @@ __device__ __forceinline__ void state_wg_reduce_store(StateAcc &acc, float *slot
 // workgroup's partial state; the four slots are stitched into the d x d matrix
 // (row length d) followed by the d key sums (taken from the waves of value
 // block 0) and stored to `out` (d*d + d floats) with coherent stores.
-template <bool ROPE>
 __device__ __forceinline__ void state_wg_quadrant_store(StateAcc &acc, float *slots, int wave, int lane, int d,
                                                         float *__restrict__ out)
 {
     __syncthreads();                                   // all waves are done with their staging tiles
-    state_acc_to_slot<ROPE>(acc, slots + wave * kStateElems, lane);
+    state_acc_to_slot<false>(acc, slots + wave * kStateElems, lane);
     __syncthreads();
     const int s_units = d * d / 2, units = s_units + d / 2;
     for (int u = threadIdx.x; u < units; u += 4 * kWave) {
@@ -421,32 +397,20 @@ __host__ __device__ constexpr int state_lds_bytes() {
     return stage > red ? stage : red;
 }
 
-// How the waves of workgroup c of C split a head's tiles and features.
-//   DP = 64:  wave w owns tiles WAVES*c + w + WAVES*C*i (i = 0, 1, ...) and all 64 features;
-//   DP = 128: all four waves own tiles c + C*i; wave w takes key block w%2, value block w/2.
-template <int DP, int WAVES>
-struct StateSplit {
-    int first, step, kb, vb;
-    __device__ __forceinline__ StateSplit(int c, int C, int wave)
-        : first(DP == 64 ? WAVES * c + wave : c), step(DP == 64 ? WAVES * C : C), kb(DP == 64 ? 0 : wave & 1),
-          vb(DP == 64 ? 0 : wave >> 1) {}
-};
-
-// grid = (C, B*H), block = 64*WAVES.  DP = 64 serves d = 64, DP = 128 serves
-// d = 112 and 128 (WAVES must be 4); T = ceil((t1-t0)/TILE) tiles cover the range.
+// grid = (C, B*H), block = 64*WAVES.  Wave w of workgroup c owns tiles
+// WAVES*c + w + WAVES*C*i (i = 0, 1, ...) of the T = ceil((t1-t0)/TILE) tiles.
 // FINALIZE: the C workgroups of a head wait for each other's partials and each
 // folds one slice of them: S_out, z_out = (S_in, z_in, or 0 if S_in is null) +
 // partials; this needs the whole grid to be resident.
 // Otherwise only the partials are written and state_reduce finishes the job.
 // ROPE: keys are rotated (table row = token index, d/2 (cos, sin) pairs) before they meet V.
-template <int DP, int TILE, int WAVES, int DEPTH, bool FINALIZE, bool ROPE>
-__global__ __launch_bounds__(64 * WAVES, 1) void state_mfma(
+template <int TILE, int WAVES, int DEPTH, bool FINALIZE, bool ROPE>
+__global__ __launch_bounds__(64 * WAVES, 1) void state_mfma_d64(
     const uint16_t *__restrict__ K, const uint16_t *__restrict__ V, const float *__restrict__ rope, TokStrides st,
-    int H, int d_arg, int t0, int t1,
+    int H, int d_unused, int t0, int t1,
     int C, const float *S_in, const float *z_in, float *S_out, float *z_out, void *__restrict__ ws,
     unsigned long long epoch, uint32_t spin_limit)
 {
-    static_assert(DP == 64 || (DP == 128 && WAVES == 4), "one wave per 64 x 64 quadrant");
     constexpr int THREADS = 64 * WAVES;
     constexpr int kTileBytes = TILE * kRowBytes;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -455,32 +419,26 @@ __global__ __launch_bounds__(64 * WAVES, 1) void state_mfma(
     const int lane = tid & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = blockIdx.x, bh = blockIdx.y, BH = gridDim.y;
     const int b = bh / H, h = bh % H;
-    const int d = DP == 64 ? 64 : d_arg, elems = d * d + d;
     const uint16_t *Kh = K + b * st.b + h * st.h;
     const uint16_t *Vh = V + b * st.b + h * st.h;
     const int n_tiles = (t1 - t0 + TILE - 1) / TILE;
-    const StateSplit<DP, WAVES> split(c, C, wave);
 
     StateAcc acc;
     acc.clear();
-    StateStream<TILE, DEPTH, ROPE, DP == 64> stream(Kh, Vh, rope, st.n, t1, d, split.kb, split.vb, lane,
-                                          TileWalk(t0, split.first, split.step, n_tiles, bh));
+    StateStream<TILE, DEPTH, ROPE> stream(Kh, Vh, rope, st.n, t1, lane,
+                                          TileWalk(t0, WAVES * c + wave, WAVES * C, n_tiles, bh));
     unsigned char *tileK = lds + wave * 2 * kTileBytes;
     state_prefetch(stream);
-    state_accumulate(stream, tileK, tileK + kTileBytes, lane, split.vb == 0, acc);
+    state_accumulate(stream, tileK, tileK + kTileBytes, lane, acc);
 
-    float *partials = static_cast<float *>(ws) + (size_t)bh * kMaxChunks * elems;
-    if (DP == 64)
-        state_wg_reduce_store<WAVES, ROPE>(acc, reinterpret_cast<float *>(lds), wave, lane,
-                                           partials + (size_t)c * elems);
-    else
-        state_wg_quadrant_store<ROPE>(acc, reinterpret_cast<float *>(lds), wave, lane, d,
-                                      partials + (size_t)c * elems);
+    float *partials = static_cast<float *>(ws) + (size_t)bh * kMaxChunks * kStateElems;
+    state_wg_reduce_store<WAVES, ROPE>(acc, reinterpret_cast<float *>(lds), wave, lane,
+                                       partials + (size_t)c * kStateElems);
     if (FINALIZE) {
-        state_publish_and_wait(ws, BH, elems, bh, c, C, 0, epoch, spin_limit, lane);
-        state_finalize_slice<THREADS, false>(partials, c, C, d, S_in ? S_in + (size_t)bh * d * d : nullptr,
-                                             z_in + (size_t)bh * d, S_out + (size_t)bh * d * d,
-                                             z_out + (size_t)bh * d);
+        state_publish_and_wait(ws, BH, kStateElems, bh, c, C, 0, epoch, spin_limit, lane);
+        state_finalize_slice<THREADS, false>(partials, c, C, 64, S_in ? S_in + (size_t)bh * 64 * 64 : nullptr,
+                                             z_in + (size_t)bh * 64, S_out + (size_t)bh * 64 * 64,
+                                             z_out + (size_t)bh * 64);
     }
 }
 

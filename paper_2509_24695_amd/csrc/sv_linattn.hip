@@ -12,6 +12,7 @@
 
 #include "apply_mfma.hpp"
 #include "block_step_fused.hpp"
+#include "coop128.hpp"
 #include "common.hpp"
 #include "generic_kernels.hpp"
 #include "state_mfma.hpp"
@@ -26,10 +27,10 @@ constexpr int kVersion = 400;   // 0.4.0
 // DP = 64 serves d = 64; DP = 128 serves d = 112 and 128.  Depths are tiles in
 // flight per wave, [DP = 128][RoPE]: a RoPE stage also holds its table rows.
 constexpr int kStateTile = 32, kStateWaves = 4, kApplyWaves = 4;
-constexpr int kStateDepth[2][2] = {{2, 2}, {2, 2}};
-constexpr int kApplyDepth[2][2] = {{2, 2}, {2, 1}};
-constexpr int kFusedStateDepth[2][2] = {{2, 2}, {2, 2}};
-constexpr int kFusedApplyDepth[2][2] = {{6, 2}, {2, 1}};   // Q tiles held in registers across the in-kernel waits
+constexpr int kStateDepth[2][2] = {{2, 2}, {8, 4}};
+constexpr int kApplyDepth[2][2] = {{2, 2}, {2, 2}};
+constexpr int kFusedStateDepth[2][2] = {{2, 2}, {4, 2}};
+constexpr int kFusedApplyDepth[2][2] = {{6, 2}, {2, 2}};   // Q tiles held in registers across the in-kernel waits
 constexpr bool kApplyHiLo = true;
 constexpr uint32_t kSpinLimit = 1u << 24;      // polls of ~100 ns: far beyond any real wait
 
@@ -49,19 +50,33 @@ struct Device {
 };
 
 // The kernels in use, by padded head dimension and with or without RoPE.
-template <int DP, bool ROPE> struct Kernels {
-    static constexpr int W = DP == 128;
-    static constexpr auto state = state_mfma<DP, kStateTile, kStateWaves, kStateDepth[W][ROPE], true, ROPE>;
-    static constexpr auto state_partial = state_mfma<DP, kStateTile, kStateWaves, kStateDepth[W][ROPE], false, ROPE>;
-    static constexpr auto apply = apply_mfma<DP, kApplyHiLo, kApplyWaves, kApplyDepth[W][ROPE], ROPE>;
-    static constexpr auto fused = block_step_mfma<DP, kStateTile, kStateWaves, kFusedStateDepth[W][ROPE], kApplyHiLo,
+template <int DP, bool ROPE> struct Kernels;
+template <bool ROPE> struct Kernels<64, ROPE> {
+    static constexpr int W = 0;
+    static constexpr auto state = state_mfma_d64<kStateTile, kStateWaves, kStateDepth[W][ROPE], true, ROPE>;
+    static constexpr auto state_partial = state_mfma_d64<kStateTile, kStateWaves, kStateDepth[W][ROPE], false, ROPE>;
+    static constexpr auto apply = apply_mfma_d64<kApplyHiLo, kApplyWaves, kApplyDepth[W][ROPE], ROPE>;
+    static constexpr auto fused = block_step_mfma<64, kStateTile, kStateWaves, kFusedStateDepth[W][ROPE], kApplyHiLo,
                                                   kFusedApplyDepth[W][ROPE], ROPE>;
     static constexpr int state_lds = state_lds_bytes<kStateTile, kStateWaves>();
-    static constexpr int apply_lds = apply_lds_bytes<DP, kApplyWaves, ROPE>();
-    static constexpr int fused_lds = block_step_lds_bytes<DP, kStateTile, kStateWaves, ROPE>();
+    static constexpr int apply_lds = apply_lds_bytes<kApplyWaves, ROPE>();
+    static constexpr int fused_lds = block_step_lds_bytes<64, kStateTile, kStateWaves, ROPE>();
     // tokens one workgroup covers per round of its tile walk
-    static constexpr int state_wg_tokens = DP == 64 ? kStateTile * kStateWaves : kStateTile;
-    static constexpr int apply_wg_tokens = DP == 64 ? kApplyTile * kApplyWaves : kApplyTile * kApplyWaves / 2;
+    static constexpr int state_wg_tokens = kStateTile * kStateWaves;
+    static constexpr int apply_wg_tokens = kApplyTile * kApplyWaves;
+};
+template <bool ROPE> struct Kernels<128, ROPE> {
+    static constexpr int W = 1;
+    static constexpr auto state = state_mfma_d128<kStateDepth[W][ROPE], true, ROPE>;
+    static constexpr auto state_partial = state_mfma_d128<kStateDepth[W][ROPE], false, ROPE>;
+    static constexpr auto apply = apply_mfma_d128<kApplyHiLo, kApplyDepth[W][ROPE], ROPE>;
+    static constexpr auto fused = block_step_mfma<128, kStateTile, kStateWaves, kFusedStateDepth[W][ROPE], kApplyHiLo,
+                                                  kFusedApplyDepth[W][ROPE], ROPE>;
+    static constexpr int state_lds = state_d128_lds_bytes<ROPE>();
+    static constexpr int apply_lds = coop_apply_lds_bytes<ROPE>();
+    static constexpr int fused_lds = block_step_lds_bytes<128, kStateTile, kStateWaves, ROPE>();
+    static constexpr int state_wg_tokens = 32;   // the four waves share one tile
+    static constexpr int apply_wg_tokens = 64;   // ... and one pair of tiles
 };
 
 template <int DP, bool ROPE> void init_kernels(Device &d)

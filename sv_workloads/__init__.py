@@ -5,7 +5,7 @@ benchmarks.  It holds no arithmetic of the method itself: only the workload
 shapes, the random draw, and the storage format of the drawn values (bf16 bit
 patterns or fp32).
 
-The five workloads stand in for the paper's video resolutions (Sec. 4.1 and the
+The workloads stand in for the paper's video resolutions (Sec. 4.1 and the
 latency tables): 480x832x81 and 720x1280x81 clips tokenised to 21x30x52 and
 21x45x80 latent tokens, and the one-minute block-autoregressive stream of
 Sec. 3.3.3.  Real activations are not available, so every tensor is i.i.d.
@@ -75,6 +75,11 @@ WORKLOADS = {
     # 720p-like bidirectional layer, conditional + unconditional pair
     "bidir_720p": Workload("bidir_720p", B=2, H=32, N=21 * 45 * 80, d=64,
                            dtype="bf16", scale=0.5, seed=1003, grid=(21, 45, 80)),
+    # the same layer in the geometry of the paper's 2B model: 20 heads of 112 features
+    "bidir_480p_h20d112": Workload("bidir_480p_h20d112", B=1, H=20, N=21 * 30 * 52, d=112,
+                                   dtype="bf16", scale=0.5, seed=1012, grid=(21, 30, 52)),
+    "block_480p_h20d112": Workload("block_480p_h20d112", B=1, H=20, N=3 * 30 * 52, d=112,
+                                   dtype="bf16", scale=0.5, seed=1014, n_blocks=10, grid=(3, 30, 52)),
     # block-causal, 10 blocks of 3 latent frames x 30 x 52
     "block_480p": Workload("block_480p", B=1, H=32, N=3 * 30 * 52, d=64,
                            dtype="bf16", scale=0.5, seed=1004, n_blocks=10, grid=(3, 30, 52)),

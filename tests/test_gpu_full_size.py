@@ -1,4 +1,4 @@
-"""GPU parity at the full sizes of the five workloads, in the launch
+"""GPU parity at the full sizes of the workloads, in the launch
 configuration bench.py times.  Where the oracle's O would be large, the state is
 checked in full (it needs every token) and O on sampled token ranges, which the
 oracle computes row by row from its own state: the first rows, the ragged last
@@ -48,8 +48,9 @@ def _check_sampled(O_host, Q, S_ref, z_ref, eps, dtype, seed, what):
     return worst
 
 
-def test_bidir_480p_full():
-    w = wl.workload("bidir_480p")
+@pytest.mark.parametrize("name", ["bidir_480p", "bidir_480p_h20d112"])
+def test_bidir_480p_full(name):
+    w = wl.workload(name)
     say(f"{w.name} full size B={w.B} H={w.H} N={w.N}")
     Q, K, V = wl.draw_qkv(w)
     O, S, z = gpu_bidirectional(to_dev(Q), to_dev(K), to_dev(V), w.eps)
@@ -74,9 +75,10 @@ def test_bidir_720p_sampled():
     print(f"{w.name}: worst over sampled ranges {m}")
 
 
-def test_block_480p_full():
+@pytest.mark.parametrize("name", ["block_480p", "block_480p_h20d112"])
+def test_block_480p_full(name):
     import torch
-    w = wl.workload("block_480p")
+    w = wl.workload(name)
     say(f"{w.name} full size: {w.n_blocks} blocks of {w.N} tokens")
     Q, K, V = wl.draw_qkv(w)
     Qd, Kd, Vd = to_dev(Q), to_dev(K), to_dev(V)
@@ -129,3 +131,41 @@ def test_stream_720p_sampled():
     # carried key sum after 864 000 tokens: closed form N sigma / sqrt(2 pi) = 172 342
     total = w.N * w.n_blocks
     assert abs(to_host(z).mean() / (total * 0.5 / np.sqrt(2 * np.pi)) - 1) < 2e-3
+
+
+def test_rope_h20d112_full_size_sampled():
+    """The paper's head geometry with the 3-D rotation table: state in full, O on sampled ranges;
+    then the first blocks of the block-causal stream through the one-launch step."""
+    import torch
+    w = wl.workload("bidir_480p_h20d112")
+    say(f"rope {w.name} full size")
+    Q, K, V = wl.draw_qkv(w)
+    T = wl.rope_table_3d(*w.grid, w.d)
+    Qd, Kd, Vd = to_dev(Q), to_dev(K), to_dev(V)
+    Td = torch.from_numpy(T).cuda()
+    S, z = new_state(w.B, w.H, w.d)
+    ws = new_workspace(w.B, w.H, w.N, w.d)
+    O = torch.empty_like(Qd)
+    dsc = sv.desc_of(Qd)
+    sv.sv_linattn_state_rope(Kd, Vd, dsc, Td, 0, w.N, 0, S, z, ws)
+    sv.sv_linattn_apply_rope(Qd, dsc, Td, 0, w.N, S, z, w.eps, O)
+    torch.cuda.synchronize()
+    S_ref, z_ref = orc.state(K, V, rope=T)
+    assert metrics.rel_l2(to_host(S), S_ref) <= 3e-3          # rotated keys are rounded to bf16 once more
+    assert metrics.rel_l2(to_host(z), z_ref) <= STATE_TOL and metrics.max_rel(to_host(z), z_ref) <= STATE_TOL
+    Oh = to_host(O)
+    assert np.isfinite(Oh).all()
+    for (a, b) in _ranges(w.N, 77):
+        metrics.check(Oh[:, :, a:b], orc.apply(Q, S_ref, z_ref, w.eps, a, b, rope=T), "bf16", f"tokens [{a},{b})")
+    # block stream: three blocks of three latent frames each, time axis continuing
+    wb = wl.workload("block_480p_h20d112")
+    S, z = new_state(wb.B, wb.H, wb.d)
+    blocks = [tuple(np.ascontiguousarray(t[:, :, m * wb.N:(m + 1) * wb.N]) for t in (Q, K, V)) for m in range(3)]
+    tables = [wl.rope_table_3d(*wb.grid, wb.d, t0=m * wb.grid[0]) for m in range(3)]
+    refs = list(orc.block_stream(blocks, wb.eps, ropes=tables))
+    for m, (q, k, v) in enumerate(blocks):
+        qd, kd, vd = to_dev(q), to_dev(k), to_dev(v)
+        o = torch.empty_like(qd)
+        sv.sv_block_linattn_step_rope(qd, kd, vd, sv.desc_of(qd), torch.from_numpy(tables[m]).cuda(), S, z, wb.eps, o, ws)
+        torch.cuda.synchronize()
+        metrics.check(to_host(o), refs[m][0], "bf16", f"rope block {m}")
