@@ -45,11 +45,13 @@ def _parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="bidir_480p", choices=["bidir_480p", "bidir_720p"])
+    ap.add_argument("--workload", default="bidir_480p", choices=["bidir_480p", "bidir_720p", "bidir_480p_h20d112"])
     ap.add_argument("--sets", type=int, default=0, help="rotating buffer sets (0 = enough for > 1.5 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-block-stream", action="store_true")
     ap.add_argument("--no-rope", action="store_true", help="skip the RoPE-variant timings")
+    ap.add_argument("--no-d112", action="store_true",
+                    help="skip the timings in the geometry of the paper's 2B model (20 heads of 112 features)")
     ap.add_argument("--stream-blocks", type=int, default=80)
     ap.add_argument("--calibration-copy", type=int, default=0,
                     help="also run this many plain device copies of one token tensor (known size: "
@@ -286,11 +288,34 @@ def main():
             "hbm_frac_step": w.algorithmic_bytes / (rr["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
             "kernels_ms": {"state": rr["ms_state"], "apply": rr["ms_apply"]},
         }
+    if not args.no_d112 and w.d == 64:
+        # the same token grid in the paper's own head geometry (model-configuration table): H = 20, d = 112
+        w2 = wl.workload(w.name + "_h20d112") if w.name == "bidir_480p" else None
+        if w2 is not None:
+            r2 = bench_bidirectional(w2, args.steps, args.warmup, 0, sv, torch)
+            g = {"workload": f"{w2.name}: B={w2.B} H={w2.H} N={w2.N} d={w2.d}", "ms_per_step": r2["ms_per_step"],
+                 "tokens_per_s": w2.B * w2.N / (r2["ms_per_step"] * 1e-3),
+                 "hbm_frac_step": w2.algorithmic_bytes / (r2["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                 "kernels_ms": {"state": r2["ms_state"], "apply": r2["ms_apply"]}}
+            if not args.no_rope:
+                r3 = bench_bidirectional(w2, args.steps, args.warmup, 0, sv, torch, rope=_rope_table(w2, torch),
+                                         sets=r2["sets"])
+                g["rope"] = {"ms_per_step": r3["ms_per_step"],
+                             "tokens_per_s": w2.B * w2.N / (r3["ms_per_step"] * 1e-3),
+                             "hbm_frac_step": w2.algorithmic_bytes / (r3["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                             "kernels_ms": {"state": r3["ms_state"], "apply": r3["ms_apply"]}}
+            del r2
+            out["geometry_h20d112"] = g
     if not args.no_block_stream:
         out["block_stream"] = [
             bench_block_stream(wl.workload("block_480p"), 10, sv, torch),
             bench_block_stream(wl.workload("stream_720p"), args.stream_blocks, sv, torch),
         ]
+        if not args.no_d112:
+            out["block_stream"].append(bench_block_stream(wl.workload("block_480p_h20d112"), 10, sv, torch))
+            if not args.no_rope:
+                out["block_stream"].append(bench_block_stream(wl.workload("block_480p_h20d112"), 10, sv, torch,
+                                                              rope=True))
         if not args.no_rope:
             out["block_stream"] += [
                 bench_block_stream(wl.workload("block_480p"), 10, sv, torch, rope=True),
