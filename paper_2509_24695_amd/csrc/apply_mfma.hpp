@@ -258,7 +258,7 @@ __host__ __device__ constexpr int apply_lds_bytes() { return WAVES * apply_wave_
 template <bool HILO, int WAVES, int DEPTH, bool ROPE>
 __global__ __launch_bounds__(64 * WAVES, 1) void apply_mfma_d64(
     const uint16_t *__restrict__ Q, uint16_t *__restrict__ O, const float *__restrict__ rope, TokStrides st, int H,
-    int d_unused, int t0, int t1, int C, const float *__restrict__ S, const float *__restrict__ z, float eps)
+    int /* d: always 64; keeps the argument list of the d = 112/128 kernel */, int t0, int t1, int C, const float *__restrict__ S, const float *__restrict__ z, float eps)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int tid = threadIdx.x;

@@ -407,7 +407,7 @@ __host__ __device__ constexpr int state_lds_bytes() {
 template <int TILE, int WAVES, int DEPTH, bool FINALIZE, bool ROPE>
 __global__ __launch_bounds__(64 * WAVES, 1) void state_mfma_d64(
     const uint16_t *__restrict__ K, const uint16_t *__restrict__ V, const float *__restrict__ rope, TokStrides st,
-    int H, int d_unused, int t0, int t1,
+    int H, int /* d: always 64; keeps the argument list of the d = 112/128 kernel */, int t0, int t1,
     int C, const float *S_in, const float *z_in, float *S_out, float *z_out, void *__restrict__ ws,
     unsigned long long epoch, uint32_t spin_limit)
 {

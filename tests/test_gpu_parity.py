@@ -288,13 +288,13 @@ def test_errors_leave_outputs_untouched():
 
 # ---- launch shapes beyond the resident grid, and the timeout word ---------------------------------
 
-@pytest.mark.parametrize("BH", [130, 300])
-def test_many_heads_bidirectional_and_block(BH):
+@pytest.mark.parametrize("BH,d", [(130, 64), (300, 64), (130, 112), (300, 112), (300, 128)])
+def test_many_heads_bidirectional_and_block(BH, d):
     """More heads than compute units: one chunk per head; at 300 heads the grid is not resident, so
     the state call takes the two-launch route and the block step the state + apply route."""
     import torch
-    B, H, N, d = 1, BH, 150, 64
-    say(f"many_heads BH={BH} N={N}")
+    B, H, N = 1, BH, 150
+    say(f"many_heads BH={BH} N={N} d={d}")
     Q, K, V = _draw(7900 + BH, B, H, N, d, "bf16")
     O_ref, S_ref, z_ref = orc.bidirectional(Q, K, V, 1e-6)
     Qd, Kd, Vd = to_dev(Q), to_dev(K), to_dev(V)
@@ -316,10 +316,11 @@ def test_many_heads_bidirectional_and_block(BH):
     _check_state(S2, z2, outs[1][1], outs[1][2], "carried state")
 
 
-def test_bounded_waits_never_time_out():
+@pytest.mark.parametrize("H,d", [(32, 64), (20, 112)])
+def test_bounded_waits_never_time_out(H, d):
     """The workspace's last-but-one 8-byte word records a timed-out wait; it must stay clear."""
     import torch
-    B, H, N, d = 1, 32, 4680, 64
+    B, N = 1, 4680
     say("bounded_waits_never_time_out")
     Q, K, V = (to_dev(t) for t in _draw(7950, B, H, N, d, "bf16"))
     ws = new_workspace(B, H, N, d)
