@@ -188,6 +188,31 @@ def bench_block_stream(w, n_blocks, sv, torch, rope=False):
     torch.cuda.synchronize()
     lat = [e[0].elapsed_time(e[1]) * 1e3 for e in events]            # us
     peak_extra = torch.cuda.max_memory_allocated() - mem_before
+    # pass 3: the whole stream recorded once into a HIP graph and replayed (the workspace is switched
+    # to device-side epochs for that)
+    sv.sv_linattn_workspace_init(ws, B, H, d, stream=stream)
+    run()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        cap = torch.cuda.current_stream()
+        for m in range(n_blocks):
+            q, k, v, o = blocks[m]
+            if tables is None:
+                sv.sv_block_linattn_step(q, k, v, dsc, S, z, w.eps, o, ws, stream=cap)
+            else:
+                sv.sv_block_linattn_step_rope(q, k, v, dsc, tables[m], S, z, w.eps, o, ws, stream=cap)
+    graph.replay()
+    torch.cuda.synchronize()
+    ga, gb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 5
+    ga.record(stream)
+    for _ in range(reps):
+        graph.replay()
+    gb.record(stream)
+    torch.cuda.synchronize()
+    graph_us = ga.elapsed_time(gb) * 1e3 / (reps * n_blocks)
     tail = lat[1:] if len(lat) > 1 else lat
     med = statistics.median(tail)
     xs = list(range(len(tail)))
@@ -197,7 +222,7 @@ def bench_block_stream(w, n_blocks, sv, torch, rope=False):
     per_block_us = stream_ms * 1e3 / n_blocks
     return {
         "workload": w.name, "rope": bool(rope), "blocks": n_blocks, "tokens_per_block": N,
-        "us_per_block_stream": per_block_us,
+        "us_per_block_stream": per_block_us, "us_per_block_graph_replay": graph_us,
         "tokens_per_s": B * N / (per_block_us * 1e-6),
         "hbm_GBps": w.algorithmic_bytes / (per_block_us * 1e-6) / 1e9,
         "hbm_frac": w.algorithmic_bytes / (per_block_us * 1e-6) / 1e9 / HBM_PEAK_GBPS,

@@ -75,6 +75,22 @@ typedef struct {
  * video length (Sec. 3.3.1, cost table).  Returns 0 for unsupported arguments. */
 size_t sv_linattn_workspace_bytes(int32_t B, int32_t H, int32_t n_tokens, int32_t d);
 
+/* Optional: prepares a workspace for calls that are recorded into a HIP graph.
+ * (For callers that replay captured launches; no passage of the paper.)
+ * sv_linattn_state and the block steps tag their cross-workgroup flags with an
+ * epoch that the host draws afresh for every call and passes as a kernel
+ * argument; a captured launch replays with the SAME argument, and a replay would
+ * mistake the flags of the previous replay for its own.  After this call (one
+ * tiny kernel on `stream`; it must have completed, in stream order, before the
+ * workspace is used) the kernels draw their epochs from a counter inside the
+ * workspace instead, so the same launches may be captured once and replayed any
+ * number of times.  B, H, d as given to sv_linattn_workspace_bytes.  The
+ * workspace must then serve one stream at a time (as always), and a graph must be
+ * replayed with the workspace it was captured with.  Eager calls work with or
+ * without initialisation. */
+sv_status sv_linattn_workspace_init(void *workspace, size_t workspace_bytes,
+                                    int32_t B, int32_t H, int32_t d, void *stream);
+
 /* State reduction (numerator and denominator brackets of the Sec. 3.2 equation;
  * S_j and the key sum of Sec. 3.3.1) over tokens [tok_begin, tok_end):
  *     accumulate == 0:  S, z  = sums            (overwritten)

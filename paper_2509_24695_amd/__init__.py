@@ -8,5 +8,5 @@ from .binding import (  # noqa: F401
     SV_BF16, SV_F32, SvError, TensorDesc, desc_of, library_path, load_library,
     sv_block_linattn_lookahead, sv_block_linattn_step, sv_linattn_apply, sv_linattn_state,
     sv_linattn_workspace_bytes, sv_status_string, sv_version, EXPORTS,
-    sv_linattn_state_rope, sv_linattn_apply_rope, sv_block_linattn_step_rope, sv_block_linattn_lookahead_rope,
+    sv_linattn_state_rope, sv_linattn_apply_rope, sv_block_linattn_step_rope, sv_block_linattn_lookahead_rope, sv_linattn_workspace_init,
 )

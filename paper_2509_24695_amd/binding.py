@@ -17,7 +17,7 @@ EXPORTS = (
     "sv_linattn_workspace_bytes", "sv_linattn_state", "sv_linattn_apply",
     "sv_block_linattn_step", "sv_block_linattn_lookahead", "sv_status_string", "sv_version",
     "sv_linattn_state_rope", "sv_linattn_apply_rope", "sv_block_linattn_step_rope",
-    "sv_block_linattn_lookahead_rope",
+    "sv_block_linattn_lookahead_rope", "sv_linattn_workspace_init",
 )
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
@@ -86,6 +86,8 @@ def load_library():
     for f in (lib.sv_linattn_state_rope, lib.sv_linattn_apply_rope, lib.sv_block_linattn_step_rope,
               lib.sv_block_linattn_lookahead_rope):
         f.restype = ctypes.c_int
+    lib.sv_linattn_workspace_init.argtypes = [vp, sz, i32, i32, i32, vp]
+    lib.sv_linattn_workspace_init.restype = ctypes.c_int
     lib.sv_status_string.argtypes = [ctypes.c_int]
     lib.sv_status_string.restype = ctypes.c_char_p
     lib.sv_version.argtypes = []
@@ -214,3 +216,10 @@ def sv_block_linattn_lookahead_rope(Qb, Kb, Vb, blk: TensorDesc, rope, S, z, eps
                                     workspace_bytes: int | None = None, stream=None) -> None:
     _block_rope("sv_block_linattn_lookahead_rope", Qb, Kb, Vb, blk, rope, S, z, eps, Ob, workspace, workspace_bytes,
                 stream)
+
+
+def sv_linattn_workspace_init(workspace, B: int, H: int, d: int, workspace_bytes: int | None = None,
+                              stream=None) -> None:
+    wb = _nbytes(workspace) if workspace_bytes is None else int(workspace_bytes)
+    _check(load_library().sv_linattn_workspace_init(_ptr(workspace), wb, int(B), int(H), int(d), _stream(stream)),
+           "sv_linattn_workspace_init")

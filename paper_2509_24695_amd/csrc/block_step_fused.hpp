@@ -25,8 +25,8 @@ namespace sv {
 template <int DP, int TILE, int WAVES, bool ROPE>
 __host__ __device__ constexpr int block_step_lds_bytes() {
     constexpr int s = DP == 64 ? state_lds_bytes<TILE, WAVES>() : state_d128_lds_bytes<ROPE>();
-    constexpr int a = DP == 64 ? apply_lds_bytes<WAVES, ROPE>() : coop_apply_lds_bytes<ROPE>();
-    return s > a ? s : a;
+    constexpr int a = (DP == 64 ? apply_lds_bytes<WAVES, ROPE>() : coop_apply_lds_bytes<ROPE>()) + kEpochLdsBytes;
+    return s > a ? s : a;   // both include the epoch word, which sits at the very end
 }
 
 // grid = (C, B*H) with C*B*H <= resident workgroup capacity, block = 64*WAVES.
@@ -59,10 +59,14 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
     const float *Sc = S_in + (size_t)bh * d * d, *zc = z_in + (size_t)bh * d;
     float *Sh = S_out + (size_t)bh * d * d, *zh = z_out + (size_t)bh * d;
     float *partials = static_cast<float *>(ws) + (size_t)bh * kMaxChunks * elems;
+    EpochSource es;
+    es.begin(ws, BH, elems, epoch);
 
     // Once all partials of the head are there, fold this workgroup's slice into S, z, then wait for
     // the other slices.
     auto agree_on_state = [&]() __attribute__((always_inline)) {
+        epoch = es.resolve(reinterpret_cast<unsigned long long *>(
+            lds + block_step_lds_bytes<DP, TILE, WAVES, ROPE>() - kEpochLdsBytes));
         state_publish_and_wait(ws, BH, elems, bh, c, C, 0, epoch, spin_limit, lane);
         state_finalize_slice<THREADS, true>(partials, c, C, d, Sc, zc, Sh, zh);
         state_publish_and_wait(ws, BH, elems, bh, c, C, 1, epoch, spin_limit, lane);

@@ -296,7 +296,8 @@ __device__ __forceinline__ void apply_tiles_coop(CoopApplyStream<DEPTH, ROPE> &s
 // Dynamic LDS: the larger of the streaming buffers and the four reduction slots.
 template <bool ROPE>
 __host__ __device__ constexpr int state_d128_lds_bytes() {
-    return coop_state_lds_bytes<ROPE>() > 4 * kStateElems * 4 ? coop_state_lds_bytes<ROPE>() : 4 * kStateElems * 4;
+    return (coop_state_lds_bytes<ROPE>() > 4 * kStateElems * 4 ? coop_state_lds_bytes<ROPE>() : 4 * kStateElems * 4) +
+           kEpochLdsBytes;
 }
 
 // State reduction for d = 112 or 128.  grid = (C, B*H), block = 256; workgroup c
@@ -317,6 +318,8 @@ __global__ __launch_bounds__(256, 1) void state_mfma_d128(
     const uint16_t *Kh = K + b * st.b + h * st.h;
     const uint16_t *Vh = V + b * st.b + h * st.h;
     const int n_tiles = (t1 - t0 + 31) / 32;
+    EpochSource es;
+    if (FINALIZE) es.begin(ws, BH, elems, epoch);
 
     StateAcc acc;
     acc.clear();
@@ -327,6 +330,7 @@ __global__ __launch_bounds__(256, 1) void state_mfma_d128(
     float *partials = static_cast<float *>(ws) + (size_t)bh * kMaxChunks * elems;
     state_wg_quadrant_store(acc, reinterpret_cast<float *>(lds), wave, lane, d, partials + (size_t)c * elems);
     if (FINALIZE) {
+        epoch = es.resolve(reinterpret_cast<unsigned long long *>(lds + state_d128_lds_bytes<ROPE>() - kEpochLdsBytes));
         state_publish_and_wait(ws, BH, elems, bh, c, C, 0, epoch, spin_limit, lane);
         state_finalize_slice<256, false>(partials, c, C, d, S_in ? S_in + (size_t)bh * d * d : nullptr,
                                          z_in + (size_t)bh * d, S_out + (size_t)bh * d * d, z_out + (size_t)bh * d);

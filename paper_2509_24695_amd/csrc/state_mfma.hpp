@@ -40,7 +40,8 @@ constexpr int kStateElems = 64 * 64 + 64;            // S then z of one head, d 
 //   float  partial[BH][kMaxChunks][elems]
 //   float  lookahead[BH][elems]       S then z per head: the updated state of a step that does not commit
 //   u64    flags[BH][2][kMaxChunks]   epoch-tagged: [0] partial c stored, [1] slice c of the new state stored
-//   u64    error, pad                 non-zero if a bounded wait ever timed out
+//   u64    error, magic, pad, pad     error: non-zero if a bounded wait ever timed out
+//   u64    tickets[BH]                magic, tickets: device-side epochs (EpochSource), unused unless initialised
 __host__ __device__ constexpr size_t ws_partial_bytes(int BH, int elems) {
     return (size_t)BH * kMaxChunks * elems * sizeof(float);
 }
@@ -61,10 +62,68 @@ __host__ __device__ __forceinline__ unsigned long long *ws_flags(void *ws, int B
 __host__ __device__ __forceinline__ unsigned long long *ws_error(void *ws, int BH, int elems) {
     return ws_flag_base(ws, BH, elems) + (size_t)BH * 2 * kMaxChunks;
 }
+__host__ __device__ __forceinline__ unsigned long long *ws_magic(void *ws, int BH, int elems) {
+    return ws_error(ws, BH, elems) + 1;
+}
+__host__ __device__ __forceinline__ unsigned long long *ws_tickets(void *ws, int BH, int elems) {
+    return ws_error(ws, BH, elems) + 4;
+}
 __host__ __device__ constexpr size_t ws_total_bytes(int BH, int elems) {
     return ws_partial_bytes(BH, elems) + ws_lookahead_bytes(BH, elems) +
-           ((size_t)BH * 2 * kMaxChunks + 2) * sizeof(unsigned long long);
+           ((size_t)BH * 2 * kMaxChunks + 4 + (size_t)BH) * sizeof(unsigned long long);
 }
+
+// Where a launch gets the epoch that tags its flags.
+//
+// Normally the host draws a fresh one per call and passes it as a kernel
+// argument.  A launch recorded in a HIP graph replays with the same arguments, so
+// a workspace can be switched to device-side epochs instead: once its header holds
+// kWsMagic (sv_linattn_workspace_init), every launch takes its epochs from ticket
+// counters in the workspace, one per head (flags are per head, so only a head's
+// workgroups have to agree).  Each workgroup of a head adds to the head's counter
+// when it starts, workgroup 0 adding what is missing to kTicketQuantum in total;
+// launches on a stream do not overlap, so all workgroups of the head's n-th
+// launch draw tickets in [n * quantum, (n + 1) * quantum) and agree on n, however
+// many workgroups each launch gave the head.  Nothing is ever reset.
+// Device epochs are even, host epochs odd: they never collide.
+constexpr unsigned long long kWsMagic = 0x73764c696e417474ull;
+constexpr unsigned long long kTicketQuantum = 1ull << 20;     // far more than a head ever has workgroups
+
+struct EpochSource {
+    unsigned long long host, ticket;    // ticket is meaningful in thread 0 only
+    bool device;
+
+    // First thing in the kernel (grid = (C, B*H)): the memory operations return long
+    // before resolve() needs them.
+    __device__ __forceinline__ void begin(void *ws, int BH, int elems, unsigned long long host_epoch)
+    {
+        host = host_epoch;
+        ticket = 0;
+        device = false;
+        if (threadIdx.x == 0) {
+            const unsigned long long magic =
+                __hip_atomic_load(ws_magic(ws, BH, elems), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            device = magic == kWsMagic;
+            if (device) {
+                const unsigned long long w = blockIdx.x == 0 ? kTicketQuantum - (gridDim.x - 1) : 1ull;
+                ticket = __hip_atomic_fetch_add(ws_tickets(ws, BH, elems) + blockIdx.y, w, __ATOMIC_RELAXED,
+                                                __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+
+    // The launch's epoch for this head, in all threads.  Must be called by all threads
+    // (one barrier); `lds_word` is 8 bytes of LDS that nothing else uses.
+    __device__ __forceinline__ unsigned long long resolve(unsigned long long *lds_word) const
+    {
+        if (threadIdx.x == 0) *lds_word = device ? ((ticket / kTicketQuantum + 1) << 1) : host;
+        __syncthreads();
+        return *lds_word;
+    }
+};
+
+// Bytes of LDS that kernels with in-kernel waits append to their dynamic allocation for resolve().
+constexpr int kEpochLdsBytes = 16;
 
 // Registers of one lane: a 64x64 fp32 partial state as four 32x32 MFMA
 // accumulators, S[32*rb + m][32*cb + n], and the key sums: as two more
@@ -394,7 +453,7 @@ __device__ __forceinline__ bool state_publish_and_wait(void *ws, int BH, int ele
 template <int TILE, int WAVES>
 __host__ __device__ constexpr int state_lds_bytes() {
     constexpr int stage = WAVES * 2 * TILE * kRowBytes, red = WAVES * kStateElems * 4;
-    return stage > red ? stage : red;
+    return (stage > red ? stage : red) + kEpochLdsBytes;
 }
 
 // grid = (C, B*H), block = 64*WAVES.  Wave w of workgroup c owns tiles
@@ -422,6 +481,8 @@ __global__ __launch_bounds__(64 * WAVES, 1) void state_mfma_d64(
     const uint16_t *Kh = K + b * st.b + h * st.h;
     const uint16_t *Vh = V + b * st.b + h * st.h;
     const int n_tiles = (t1 - t0 + TILE - 1) / TILE;
+    EpochSource es;
+    if (FINALIZE) es.begin(ws, BH, kStateElems, epoch);
 
     StateAcc acc;
     acc.clear();
@@ -435,6 +496,7 @@ __global__ __launch_bounds__(64 * WAVES, 1) void state_mfma_d64(
     state_wg_reduce_store<WAVES, ROPE>(acc, reinterpret_cast<float *>(lds), wave, lane,
                                        partials + (size_t)c * kStateElems);
     if (FINALIZE) {
+        epoch = es.resolve(reinterpret_cast<unsigned long long *>(lds + state_lds_bytes<TILE, WAVES>() - kEpochLdsBytes));
         state_publish_and_wait(ws, BH, kStateElems, bh, c, C, 0, epoch, spin_limit, lane);
         state_finalize_slice<THREADS, false>(partials, c, C, 64, S_in ? S_in + (size_t)bh * 64 * 64 : nullptr,
                                              z_in + (size_t)bh * 64, S_out + (size_t)bh * 64 * 64,

@@ -111,6 +111,17 @@ template <typename F> void with_mfma_kernels(int d, bool rope, F &&f)
     }
 }
 
+// Switches a workspace to device-side epochs (and clears its error word).
+__global__ void workspace_header_init(unsigned long long *error, unsigned long long *magic, unsigned long long *tickets,
+                                      int BH)
+{
+    for (int i = threadIdx.x; i < BH; i += blockDim.x) tickets[i] = 0ull;
+    if (threadIdx.x == 0) {
+        *error = 0ull;
+        *magic = kWsMagic;
+    }
+}
+
 bool head_dim_ok(int d) { return d == 32 || d == 64 || d == 112 || d == 128; }
 
 // Calls f(std::integral_constant<int, D>) for the supported head dimension d.
@@ -401,6 +412,20 @@ size_t sv_linattn_workspace_bytes(int32_t B, int32_t H, int32_t n_tokens, int32_
     if (B <= 0 || H <= 0 || n_tokens < 0 || !head_dim_ok(d)) return 0;
     if ((int64_t)B * H > 65535) return 0;
     return workspace_bytes(B * H, d);
+}
+
+sv_status sv_linattn_workspace_init(void *workspace, size_t workspace_bytes_given, int32_t B, int32_t H, int32_t d,
+                                    void *stream)
+{
+    if (!workspace) return SV_ERR_NULL;
+    if (B <= 0 || H <= 0 || (int64_t)B * H > 65535) return SV_ERR_SHAPE;
+    if (!head_dim_ok(d)) return SV_ERR_UNSUPPORTED;
+    if (!aligned16(workspace)) return SV_ERR_ALIGN;
+    if (workspace_bytes_given < workspace_bytes(B * H, d)) return SV_ERR_WORKSPACE;
+    const int BH = B * H, elems = d * d + d;
+    workspace_header_init<<<1, kThreads, 0, static_cast<hipStream_t>(stream)>>>(
+        ws_error(workspace, BH, elems), ws_magic(workspace, BH, elems), ws_tickets(workspace, BH, elems), BH);
+    return launch_status();
 }
 
 sv_status sv_linattn_state(const void *K, const void *V, const sv_tensor_desc *kv, int32_t tok_begin,

@@ -318,7 +318,8 @@ def test_many_heads_bidirectional_and_block(BH, d):
 
 @pytest.mark.parametrize("H,d", [(32, 64), (20, 112)])
 def test_bounded_waits_never_time_out(H, d):
-    """The workspace's last-but-one 8-byte word records a timed-out wait; it must stay clear."""
+    """The workspace ends with [error, magic, pad, pad, tickets[B*H]] (8-byte words); the error word
+    records a timed-out wait and must stay clear."""
     import torch
     B, N = 1, 4680
     say("bounded_waits_never_time_out")
@@ -332,7 +333,8 @@ def test_bounded_waits_never_time_out(H, d):
         sv.sv_linattn_state(K, V, dsc, 0, N, 0, S, z, ws)
         sv.sv_block_linattn_step(Q, K, V, dsc, S, z, 1e-6, O, ws)
     torch.cuda.synchronize()
-    assert int(ws[-16:-8].view(torch.int64)[0]) == 0
+    err = ws.numel() - 32 - 8 * B * H
+    assert int(ws[err:err + 8].view(torch.int64)[0]) == 0
 
 
 # ---- look-ahead step: the cache is used but not updated (noisy passes of Alg. 1) -------------------

@@ -127,3 +127,19 @@ def test_rope_entry_points_check_arguments():
         sv.sv_block_linattn_lookahead_rope(FAKE, FAKE, FAKE, d, FAKE, FAKE, FAKE, -1.0, FAKE, FAKE,
                                            workspace_bytes=big)
     assert e.value.status == 5
+
+
+def test_workspace_init_checks_arguments():
+    big = 1 << 30
+    with pytest.raises(sv.SvError) as e:
+        sv.sv_linattn_workspace_init(None, 1, 2, 64, workspace_bytes=big)
+    assert e.value.status == 1
+    with pytest.raises(sv.SvError) as e:
+        sv.sv_linattn_workspace_init(FAKE, 1, 2, 48, workspace_bytes=big)
+    assert e.value.status == 3
+    with pytest.raises(sv.SvError) as e:
+        sv.sv_linattn_workspace_init(FAKE, 1, 2, 64, workspace_bytes=sv.sv_linattn_workspace_bytes(1, 2, 10, 64) - 1)
+    assert e.value.status == 6
+    with pytest.raises(sv.SvError) as e:
+        sv.sv_linattn_workspace_init(FAKE + 8, 1, 2, 64, workspace_bytes=big)
+    assert e.value.status == 4
