@@ -65,12 +65,25 @@ def _randn_bf16(shape, gen):
 
 
 def _rope_table(w, torch, t0=0):
+    """Full rotation table [N][d/2][2] of the workload's token grid (device tensor)."""
     import sv_workloads as wl
     return torch.from_numpy(wl.rope_table_3d(*w.grid, w.d, t0=t0)).cuda()
 
 
+def _rope_3d(w, torch, sv, t0=0):
+    """The same embedding as three per-axis tables (sv.Rope3D)."""
+    import sv_workloads as wl
+    return sv.Rope3D.from_tensors(*(torch.from_numpy(t).cuda()
+                                    for t in wl.rope_tables_3d_factored(*w.grid, w.d, t0=t0)))
+
+
+def _is_3d(rope):
+    return rope is not None and rope.__class__.__name__ == "Rope3D"
+
+
 def bench_bidirectional(w, steps, warmup, n_sets, sv, torch, rope=None, sets=None):
-    """`rope`: device table -> the RoPE entry points are timed instead of the plain ones."""
+    """`rope`: a device table or an sv.Rope3D -> the _rope / _rope3d entry points are timed instead of
+    the plain ones."""
     B, H, N, d = w.B, w.H, w.N, w.d
     gen = torch.Generator(device="cuda")
     gen.manual_seed(w.seed)
@@ -94,12 +107,16 @@ def bench_bidirectional(w, steps, warmup, n_sets, sv, torch, rope=None, sets=Non
             ev[0].record(stream)
         if rope is None:
             sv.sv_linattn_state(k, v, dsc, 0, N, 0, S, z, ws, stream=stream)
+        elif _is_3d(rope):
+            sv.sv_linattn_state_rope3d(k, v, dsc, rope, 0, N, 0, S, z, ws, stream=stream)
         else:
             sv.sv_linattn_state_rope(k, v, dsc, rope, 0, N, 0, S, z, ws, stream=stream)
         if ev:
             ev[1].record(stream)
         if rope is None:
             sv.sv_linattn_apply(q, dsc, 0, N, S, z, w.eps, o, stream=stream)
+        elif _is_3d(rope):
+            sv.sv_linattn_apply_rope3d(q, dsc, rope, 0, N, S, z, w.eps, o, stream=stream)
         else:
             sv.sv_linattn_apply_rope(q, dsc, rope, 0, N, S, z, w.eps, o, stream=stream)
         if ev:
@@ -134,7 +151,9 @@ def bench_bidirectional(w, steps, warmup, n_sets, sv, torch, rope=None, sets=Non
 
 def bench_block_stream(w, n_blocks, sv, torch, rope=False):
     """Whole stream enqueued back to back, one event pair per block; no host sync inside.
-    `rope`: time sv_block_linattn_step_rope with one table per block (time axis continuing)."""
+    `rope`: False, "table" (sv_block_linattn_step_rope, one full table per block) or "3d"
+    (sv_block_linattn_step_rope3d, per-axis tables; the frame table of each block continues the
+    time axis)."""
     B, H, N, d = w.B, w.H, w.N, w.d
     gen = torch.Generator(device="cuda")
     gen.manual_seed(w.seed)
@@ -148,14 +167,20 @@ def bench_block_stream(w, n_blocks, sv, torch, rope=False):
     lib_bytes = S.numel() * 4 + z.numel() * 4 + ws.numel()
     dsc = sv.desc_of(blocks[0][0])
     stream = torch.cuda.current_stream()
-    tables = [_rope_table(w, torch, t0=m * w.grid[0]) for m in range(n_blocks)] if rope else None
+    if rope == "3d":
+        tables = [_rope_3d(w, torch, sv, t0=m * w.grid[0]) for m in range(n_blocks)]
+    elif rope:
+        tables = [_rope_table(w, torch, t0=m * w.grid[0]) for m in range(n_blocks)]
+    else:
+        tables = None
+    step_rope = sv.sv_block_linattn_step_rope3d if rope == "3d" else sv.sv_block_linattn_step_rope
 
     def one(m):
         q, k, v, o = blocks[m]
         if tables is None:
             sv.sv_block_linattn_step(q, k, v, dsc, S, z, w.eps, o, ws, stream=stream)
         else:
-            sv.sv_block_linattn_step_rope(q, k, v, dsc, tables[m], S, z, w.eps, o, ws, stream=stream)
+            step_rope(q, k, v, dsc, tables[m], S, z, w.eps, o, ws, stream=stream)
 
     def run(events=None):
         S.zero_()
@@ -202,7 +227,7 @@ def bench_block_stream(w, n_blocks, sv, torch, rope=False):
             if tables is None:
                 sv.sv_block_linattn_step(q, k, v, dsc, S, z, w.eps, o, ws, stream=cap)
             else:
-                sv.sv_block_linattn_step_rope(q, k, v, dsc, tables[m], S, z, w.eps, o, ws, stream=cap)
+                step_rope(q, k, v, dsc, tables[m], S, z, w.eps, o, ws, stream=cap)
     graph.replay()
     torch.cuda.synchronize()
     ga, gb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -221,7 +246,7 @@ def bench_block_stream(w, n_blocks, sv, torch, rope=False):
              if len(tail) > 1 else 0.0)
     per_block_us = stream_ms * 1e3 / n_blocks
     return {
-        "workload": w.name, "rope": bool(rope), "blocks": n_blocks, "tokens_per_block": N,
+        "workload": w.name, "rope": ("table" if rope is True else rope), "blocks": n_blocks, "tokens_per_block": N,
         "us_per_block_stream": per_block_us, "us_per_block_graph_replay": graph_us,
         "tokens_per_s": B * N / (per_block_us * 1e-6),
         "hbm_GBps": w.algorithmic_bytes / (per_block_us * 1e-6) / 1e9,
@@ -313,6 +338,14 @@ def main():
             "hbm_frac_step": w.algorithmic_bytes / (rr["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
             "kernels_ms": {"state": rr["ms_state"], "apply": rr["ms_apply"]},
         }
+        # ... and with the rotation given as three per-axis tables that stay on chip
+        rr = bench_bidirectional(w, args.steps, args.warmup, 0, sv, torch, rope=_rope_3d(w, torch, sv),
+                                 sets=r["sets"])
+        out["rope3d_variant"] = {
+            "ms_per_step": rr["ms_per_step"], "tokens_per_s": w.B * w.N / (rr["ms_per_step"] * 1e-3),
+            "hbm_frac_step": w.algorithmic_bytes / (rr["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "kernels_ms": {"state": rr["ms_state"], "apply": rr["ms_apply"]},
+        }
     if not args.no_d112 and w.d == 64:
         # the same token grid in the paper's own head geometry (model-configuration table): H = 20, d = 112
         w2 = wl.workload(w.name + "_h20d112") if w.name == "bidir_480p" else None
@@ -329,6 +362,12 @@ def main():
                              "tokens_per_s": w2.B * w2.N / (r3["ms_per_step"] * 1e-3),
                              "hbm_frac_step": w2.algorithmic_bytes / (r3["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                              "kernels_ms": {"state": r3["ms_state"], "apply": r3["ms_apply"]}}
+                r3 = bench_bidirectional(w2, args.steps, args.warmup, 0, sv, torch, rope=_rope_3d(w2, torch, sv),
+                                         sets=r2["sets"])
+                g["rope3d"] = {"ms_per_step": r3["ms_per_step"],
+                               "tokens_per_s": w2.B * w2.N / (r3["ms_per_step"] * 1e-3),
+                               "hbm_frac_step": w2.algorithmic_bytes / (r3["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                               "kernels_ms": {"state": r3["ms_state"], "apply": r3["ms_apply"]}}
             del r2
             out["geometry_h20d112"] = g
     if not args.no_block_stream:
@@ -341,10 +380,14 @@ def main():
             if not args.no_rope:
                 out["block_stream"].append(bench_block_stream(wl.workload("block_480p_h20d112"), 10, sv, torch,
                                                               rope=True))
+                out["block_stream"].append(bench_block_stream(wl.workload("block_480p_h20d112"), 10, sv, torch,
+                                                              rope="3d"))
         if not args.no_rope:
             out["block_stream"] += [
                 bench_block_stream(wl.workload("block_480p"), 10, sv, torch, rope=True),
                 bench_block_stream(wl.workload("stream_720p"), args.stream_blocks, sv, torch, rope=True),
+                bench_block_stream(wl.workload("block_480p"), 10, sv, torch, rope="3d"),
+                bench_block_stream(wl.workload("stream_720p"), args.stream_blocks, sv, torch, rope="3d"),
             ]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, r["sets"], torch)

@@ -172,6 +172,49 @@ sv_status sv_block_linattn_lookahead_rope(const void *Qb, const void *Kb, const 
                                           const float *S, const float *z, float eps, void *Ob,
                                           void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- RoPE variants with factored 3-D tables ------------------------------------------
+ *
+ * The same equation as the _rope calls, for the usual 3-D rotary embedding in
+ * which feature pair p is turned by ONE coordinate of the token: its frame, its
+ * row or its column.  Token t of the descriptor (of the block, for a step) sits at
+ *     frame t / (rows*cols),  row (t / cols) % rows,  column t % cols,
+ * so frames*rows*cols must equal the descriptor's N.  Pairs [0, n_t) follow the
+ * frame, pairs [n_t, n_t + n_h) the row, pairs [n_t + n_h, d/2) the column
+ * (n_t + n_h + n_w = d/2); cs_t, cs_h, cs_w are DEVICE pointers to fp32
+ * [frames][n_t][2], [rows][n_h][2], [cols][n_w][2] = (cos, sin), 8-byte
+ * aligned, NULL allowed for an axis with no pairs.  For a block stream the
+ * caller passes, per block, the frame table of that block's frames (the time
+ * axis continues across blocks) and the same row and column tables.
+ * The three tables are a few KB and stay on chip during the call: unlike a full
+ * [N][d/2][2] table they add nothing to the token streams.  The descriptor is a
+ * HOST pointer, read before the call returns.  Results equal those of the _rope
+ * calls on the expanded table. */
+typedef struct {
+    int32_t frames, rows, cols;
+    int32_t n_t, n_h, n_w;
+    const float *cs_t, *cs_h, *cs_w;
+} sv_rope3d;
+
+sv_status sv_linattn_state_rope3d(const void *K, const void *V, const sv_tensor_desc *kv,
+                                  const sv_rope3d *rope, int32_t tok_begin, int32_t tok_end,
+                                  int accumulate, float *S, float *z,
+                                  void *workspace, size_t workspace_bytes, void *stream);
+
+sv_status sv_linattn_apply_rope3d(const void *Q, const sv_tensor_desc *q, const sv_rope3d *rope,
+                                  int32_t tok_begin, int32_t tok_end,
+                                  const float *S, const float *z, float eps,
+                                  void *O, void *stream);
+
+sv_status sv_block_linattn_step_rope3d(const void *Qb, const void *Kb, const void *Vb,
+                                       const sv_tensor_desc *blk, const sv_rope3d *rope,
+                                       float *S, float *z, float eps, void *Ob,
+                                       void *workspace, size_t workspace_bytes, void *stream);
+
+sv_status sv_block_linattn_lookahead_rope3d(const void *Qb, const void *Kb, const void *Vb,
+                                            const sv_tensor_desc *blk, const sv_rope3d *rope,
+                                            const float *S, const float *z, float eps, void *Ob,
+                                            void *workspace, size_t workspace_bytes, void *stream);
+
 /* Human-readable name of a status code (static storage). */
 const char *sv_status_string(int status);
 

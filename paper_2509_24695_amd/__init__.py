@@ -9,4 +9,6 @@ from .binding import (  # noqa: F401
     sv_block_linattn_lookahead, sv_block_linattn_step, sv_linattn_apply, sv_linattn_state,
     sv_linattn_workspace_bytes, sv_status_string, sv_version, EXPORTS,
     sv_linattn_state_rope, sv_linattn_apply_rope, sv_block_linattn_step_rope, sv_block_linattn_lookahead_rope, sv_linattn_workspace_init,
+    Rope3D, sv_linattn_state_rope3d, sv_linattn_apply_rope3d, sv_block_linattn_step_rope3d,
+    sv_block_linattn_lookahead_rope3d,
 )

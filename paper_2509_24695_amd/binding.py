@@ -18,6 +18,8 @@ EXPORTS = (
     "sv_block_linattn_step", "sv_block_linattn_lookahead", "sv_status_string", "sv_version",
     "sv_linattn_state_rope", "sv_linattn_apply_rope", "sv_block_linattn_step_rope",
     "sv_block_linattn_lookahead_rope", "sv_linattn_workspace_init",
+    "sv_linattn_state_rope3d", "sv_linattn_apply_rope3d", "sv_block_linattn_step_rope3d",
+    "sv_block_linattn_lookahead_rope3d",
 )
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
@@ -85,6 +87,14 @@ def load_library():
     lib.sv_block_linattn_lookahead_rope.argtypes = [vp, vp, vp, dp, vp, vp, vp, ctypes.c_float, vp, vp, sz, vp]
     for f in (lib.sv_linattn_state_rope, lib.sv_linattn_apply_rope, lib.sv_block_linattn_step_rope,
               lib.sv_block_linattn_lookahead_rope):
+        f.restype = ctypes.c_int
+    rp = ctypes.POINTER(_CRope3D)
+    lib.sv_linattn_state_rope3d.argtypes = [vp, vp, dp, rp, i32, i32, ctypes.c_int, vp, vp, vp, sz, vp]
+    lib.sv_linattn_apply_rope3d.argtypes = [vp, dp, rp, i32, i32, vp, vp, ctypes.c_float, vp, vp]
+    lib.sv_block_linattn_step_rope3d.argtypes = [vp, vp, vp, dp, rp, vp, vp, ctypes.c_float, vp, vp, sz, vp]
+    lib.sv_block_linattn_lookahead_rope3d.argtypes = [vp, vp, vp, dp, rp, vp, vp, ctypes.c_float, vp, vp, sz, vp]
+    for f in (lib.sv_linattn_state_rope3d, lib.sv_linattn_apply_rope3d, lib.sv_block_linattn_step_rope3d,
+              lib.sv_block_linattn_lookahead_rope3d):
         f.restype = ctypes.c_int
     lib.sv_linattn_workspace_init.argtypes = [vp, sz, i32, i32, i32, vp]
     lib.sv_linattn_workspace_init.restype = ctypes.c_int
@@ -223,3 +233,72 @@ def sv_linattn_workspace_init(workspace, B: int, H: int, d: int, workspace_bytes
     wb = _nbytes(workspace) if workspace_bytes is None else int(workspace_bytes)
     _check(load_library().sv_linattn_workspace_init(_ptr(workspace), wb, int(B), int(H), int(d), _stream(stream)),
            "sv_linattn_workspace_init")
+
+
+class _CRope3D(ctypes.Structure):
+    _fields_ = [("frames", ctypes.c_int32), ("rows", ctypes.c_int32), ("cols", ctypes.c_int32),
+                ("n_t", ctypes.c_int32), ("n_h", ctypes.c_int32), ("n_w", ctypes.c_int32),
+                ("cs_t", ctypes.c_void_p), ("cs_h", ctypes.c_void_p), ("cs_w", ctypes.c_void_p)]
+
+
+class Rope3D:
+    """Factored 3-D rotary tables (sv_rope3d): device tensors (or raw pointers) cs_t [frames][n_t][2],
+    cs_h [rows][n_h][2], cs_w [cols][n_w][2], fp32."""
+
+    def __init__(self, frames, rows, cols, n_t, n_h, n_w, cs_t, cs_h, cs_w):
+        self.frames, self.rows, self.cols = int(frames), int(rows), int(cols)
+        self.n_t, self.n_h, self.n_w = int(n_t), int(n_h), int(n_w)
+        self.cs_t, self.cs_h, self.cs_w = cs_t, cs_h, cs_w      # keeps the tensors alive
+
+    @classmethod
+    def from_tensors(cls, cs_t, cs_h, cs_w):
+        return cls(cs_t.shape[0], cs_h.shape[0], cs_w.shape[0], cs_t.shape[1], cs_h.shape[1], cs_w.shape[1],
+                   cs_t, cs_h, cs_w)
+
+    def _c(self):
+        def p(x):
+            v = _ptr(x)
+            return v.value if isinstance(v, ctypes.c_void_p) else v
+        return _CRope3D(self.frames, self.rows, self.cols, self.n_t, self.n_h, self.n_w, p(self.cs_t), p(self.cs_h),
+                        p(self.cs_w))
+
+
+def _r3(rope):
+    return ctypes.byref(rope._c()) if rope is not None else None
+
+
+def sv_linattn_state_rope3d(K, V, kv: TensorDesc, rope: Rope3D, tok_begin: int, tok_end: int, accumulate: int, S, z,
+                            workspace, workspace_bytes: int | None = None, stream=None) -> None:
+    d = kv._c() if kv is not None else None
+    wb = _nbytes(workspace) if workspace_bytes is None else int(workspace_bytes)
+    _check(load_library().sv_linattn_state_rope3d(_ptr(K), _ptr(V), ctypes.byref(d) if d else None, _r3(rope),
+                                                  tok_begin, tok_end, int(accumulate), _ptr(S), _ptr(z),
+                                                  _ptr(workspace), wb, _stream(stream)), "sv_linattn_state_rope3d")
+
+
+def sv_linattn_apply_rope3d(Q, q: TensorDesc, rope: Rope3D, tok_begin: int, tok_end: int, S, z, eps: float, O,
+                            stream=None) -> None:
+    d = q._c() if q is not None else None
+    _check(load_library().sv_linattn_apply_rope3d(_ptr(Q), ctypes.byref(d) if d else None, _r3(rope), tok_begin,
+                                                  tok_end, _ptr(S), _ptr(z), float(eps), _ptr(O), _stream(stream)),
+           "sv_linattn_apply_rope3d")
+
+
+def _block_rope3d(fn_name, Qb, Kb, Vb, blk, rope, S, z, eps, Ob, workspace, workspace_bytes, stream):
+    d = blk._c() if blk is not None else None
+    wb = _nbytes(workspace) if workspace_bytes is None else int(workspace_bytes)
+    fn = getattr(load_library(), fn_name)
+    _check(fn(_ptr(Qb), _ptr(Kb), _ptr(Vb), ctypes.byref(d) if d else None, _r3(rope), _ptr(S), _ptr(z), float(eps),
+              _ptr(Ob), _ptr(workspace), wb, _stream(stream)), fn_name)
+
+
+def sv_block_linattn_step_rope3d(Qb, Kb, Vb, blk: TensorDesc, rope: Rope3D, S, z, eps: float, Ob, workspace,
+                                 workspace_bytes: int | None = None, stream=None) -> None:
+    _block_rope3d("sv_block_linattn_step_rope3d", Qb, Kb, Vb, blk, rope, S, z, eps, Ob, workspace, workspace_bytes,
+                  stream)
+
+
+def sv_block_linattn_lookahead_rope3d(Qb, Kb, Vb, blk: TensorDesc, rope: Rope3D, S, z, eps: float, Ob, workspace,
+                                      workspace_bytes: int | None = None, stream=None) -> None:
+    _block_rope3d("sv_block_linattn_lookahead_rope3d", Qb, Kb, Vb, blk, rope, S, z, eps, Ob, workspace,
+                  workspace_bytes, stream)

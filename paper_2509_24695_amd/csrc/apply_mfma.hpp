@@ -107,23 +107,23 @@ struct ApplyOperands {
 };
 
 // One wave's token stream (d = 64): buffer resources over the head's Q and O
-// rows (and the rotation table) below the end of the token range, the wave's tile
-// walk (32 tokens per tile), and the register staging of DEPTH tiles in flight.
-template <int DEPTH, bool ROPE>
+// rows below the end of the token range, the wave's tile walk (32 tokens per
+// tile), the register staging of DEPTH tiles in flight, and the rotation source.
+template <int DEPTH, int ROPE>
 struct ApplyStream {
-    rsrc_t rQ, rO, rT;
-    uint32_t row_bytes, lane_off, lane_off_t;
+    rsrc_t rQ, rO;
+    uint32_t row_bytes, lane_off;
     TileWalk walk;
     u32x4 q[DEPTH][kApplyTile / 8];
-    f32x4 cs[ROPE ? DEPTH : 1][kApplyTile / 8][2];
+    Rotator<ROPE, kApplyTile / 8, DEPTH> rot;
 
-    __device__ __forceinline__ ApplyStream(const uint16_t *Qh, uint16_t *Oh, const float *rope, int64_t stride_n,
-                                           int t1, int lane, const TileWalk &w)
+    __device__ __forceinline__ ApplyStream(const uint16_t *Qh, uint16_t *Oh, const RopeArg &rope,
+                                           const unsigned char *lds_tab, int64_t stride_n, int t1, int lane,
+                                           const TileWalk &w)
         : rQ(make_rsrc(Qh, (uint32_t)t1 * (uint32_t)stride_n * 2u)),
-          rO(make_rsrc(Oh, (uint32_t)t1 * (uint32_t)stride_n * 2u)),
-          rT(make_rsrc(rope, ROPE ? (uint32_t)t1 * 256u : 0u)), row_bytes((uint32_t)stride_n * 2u),
-          lane_off((uint32_t)(lane >> 3) * (uint32_t)stride_n * 2u + (uint32_t)(lane & 7) * 16u),
-          lane_off_t((uint32_t)(lane >> 3) * 256u + (uint32_t)(lane & 7) * 32u), walk(w) {}
+          rO(make_rsrc(Oh, (uint32_t)t1 * (uint32_t)stride_n * 2u)), row_bytes((uint32_t)stride_n * 2u),
+          lane_off((uint32_t)(lane >> 3) * (uint32_t)stride_n * 2u + (uint32_t)(lane & 7) * 16u), walk(w),
+          rot(rope, t1, 64, lane >> 3, 8, 4 * (lane & 7), 1, lds_tab) {}
 
     // Requests the wave's i-th tile into stage s; past the share nothing is read.
     __device__ __forceinline__ void request(int s, int i)
@@ -132,14 +132,12 @@ struct ApplyStream {
 #pragma unroll
         for (int j = 0; j < kApplyTile / 8; ++j)
             q[s][j] = load_stream16(rQ, base + lane_off + (uint32_t)j * 8u * row_bytes);
-        if (ROPE)
-            rope_tile_load<kApplyTile / 8>(rT, walk.offset<kApplyTile>(i, 256u), lane_off_t, 8u * 256u,
-                                           cs[ROPE ? s : 0]);
+        rot.request(s, i < walk.count, walk.token<kApplyTile>(i));
     }
 };
 
 // Requests tiles FROM .. TO-1 of the wave's share into the stages of the same numbers.
-template <int FROM, int TO, int DEPTH, bool ROPE>
+template <int FROM, int TO, int DEPTH, int ROPE>
 __device__ __forceinline__ void apply_prefetch(ApplyStream<DEPTH, ROPE> &st)
 {
 #pragma unroll
@@ -156,7 +154,7 @@ __device__ __forceinline__ void apply_prefetch(ApplyStream<DEPTH, ROPE> &st)
 // ones).  Tiles are taken DEPTH at a time; every stage issues its loads and
 // stores whether or not it still has a tile (out of range they do nothing), only
 // the arithmetic is skipped.
-template <bool HILO, int DEPTH, bool ROPE>
+template <bool HILO, int DEPTH, int ROPE>
 __device__ __forceinline__ void apply_tiles(ApplyStream<DEPTH, ROPE> &st, unsigned char *tileQ, int lane,
                                             const ApplyOperands<64, HILO> &A, float eps)
 {
@@ -175,13 +173,12 @@ __device__ __forceinline__ void apply_tiles(ApplyStream<DEPTH, ROPE> &st, unsign
             const uint32_t out_off = st.walk.template offset<kApplyTile>(i0 + s, st.row_bytes);
             if (valid) {
                 wave_lds_fence();
+                st.rot.begin_tile(st.walk.template token<kApplyTile>(i0 + s));
 #pragma unroll
                 for (int j = 0; j < kApplyTile / 8; ++j) {
                     const u32x4 pq = relu_bf16x8(st.q[s][j]);                          // phi(Q)
                     *reinterpret_cast<u32x4 *>(tileQ + wr_off + 8 * j * kRow) = pq;
-                    if (ROPE)
-                        *reinterpret_cast<u32x4 *>(tileQ + kTileBytes + wr_off + 8 * j * kRow) =
-                            rope_rotate_bf16x8(pq, st.cs[ROPE ? s : 0][j][0], st.cs[ROPE ? s : 0][j][1]);
+                    if (ROPE) *reinterpret_cast<u32x4 *>(tileQ + kTileBytes + wr_off + 8 * j * kRow) = st.rot.rotate(s, j, pq);
                 }
             }
             st.request(s, i0 + s + DEPTH);   // refill this stage: DEPTH tiles ahead
@@ -246,18 +243,19 @@ __device__ __forceinline__ void apply_tiles(ApplyStream<DEPTH, ROPE> &st, unsign
 }
 
 // LDS bytes per wave and in total: one tile, two with ROPE (plain + rotated copy).
-template <bool ROPE>
+template <int ROPE>
 __host__ __device__ constexpr int apply_wave_lds_bytes() { return (ROPE ? 2 : 1) * kApplyTile * kRowBytes; }
-template <int WAVES, bool ROPE>
+template <int WAVES, int ROPE>
 __host__ __device__ constexpr int apply_lds_bytes() { return WAVES * apply_wave_lds_bytes<ROPE>(); }
 
 // grid = (C, B*H), block = 64*WAVES.  Wave w of workgroup c owns tiles
 // WAVES*c + w + WAVES*C*i (i = 0, 1, ...) of the T = ceil((t1-t0)/32) tiles,
 // the same round-robin deal as the state kernel.
 // HILO = false drops the low half of S (one MFMA pass instead of two).
-template <bool HILO, int WAVES, int DEPTH, bool ROPE>
+// ROPE (kRopeNone/Table/3D); with kRope3D the dynamic LDS carries kRope3dLdsBytes more.
+template <bool HILO, int WAVES, int DEPTH, int ROPE>
 __global__ __launch_bounds__(64 * WAVES, 1) void apply_mfma_d64(
-    const uint16_t *__restrict__ Q, uint16_t *__restrict__ O, const float *__restrict__ rope, TokStrides st, int H,
+    const uint16_t *__restrict__ Q, uint16_t *__restrict__ O, RopeArg rope, TokStrides st, int H,
     int /* d: always 64; keeps the argument list of the d = 112/128 kernel */, int t0, int t1, int C, const float *__restrict__ S, const float *__restrict__ z, float eps)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -269,9 +267,13 @@ __global__ __launch_bounds__(64 * WAVES, 1) void apply_mfma_d64(
     uint16_t *Oh = O + b * st.b + h * st.h;
     const int n_tiles = (t1 - t0 + kApplyTile - 1) / kApplyTile;
 
-    ApplyStream<DEPTH, ROPE> stream(Qh, Oh, rope, st.n, t1, lane,
+    ApplyStream<DEPTH, ROPE> stream(Qh, Oh, rope, lds + apply_lds_bytes<WAVES, ROPE>(), st.n, t1, lane,
                                     TileWalk(t0, WAVES * c + wave, WAVES * C, n_tiles, bh));
     apply_prefetch<0, DEPTH>(stream);   // in flight while S is fetched
+    if (ROPE == kRope3D) {
+        rope3d_lds_fill(lds + apply_lds_bytes<WAVES, ROPE>(), rope.r3);
+        __syncthreads();
+    }
     ApplyOperands<64, HILO> A;
     A.template load<false>(S + (size_t)bh * 64 * 64, z + (size_t)bh * 64, 64, 0, lane);
     apply_tiles<HILO>(stream, lds + wave * apply_wave_lds_bytes<ROPE>(), lane, A, eps);

@@ -22,7 +22,7 @@
 
 namespace sv {
 
-template <int DP, int TILE, int WAVES, bool ROPE>
+template <int DP, int TILE, int WAVES, int ROPE>
 __host__ __device__ constexpr int block_step_lds_bytes() {
     constexpr int s = DP == 64 ? state_lds_bytes<TILE, WAVES>() : state_d128_lds_bytes<ROPE>();
     constexpr int a = (DP == 64 ? apply_lds_bytes<WAVES, ROPE>() : coop_apply_lds_bytes<ROPE>()) + kEpochLdsBytes;
@@ -34,10 +34,10 @@ __host__ __device__ constexpr int block_step_lds_bytes() {
 // DP = 128 serves d = 112 and 128 (waves share tiles, as in state_mfma_d128 and
 // apply_mfma_d128; WAVES must be 4).
 // ROPE: keys and queries are rotated after the ReLU in the numerator path (table row = token of the block).
-template <int DP, int TILE, int WAVES, int DEPTH_S, bool HILO, int DEPTH_A, bool ROPE>
+template <int DP, int TILE, int WAVES, int DEPTH_S, bool HILO, int DEPTH_A, int ROPE>
 __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
-    uint16_t *__restrict__ O, const float *__restrict__ rope, TokStrides st, int H, int d_arg, int N, int C,
+    uint16_t *__restrict__ O, RopeArg rope, TokStrides st, int H, int d_arg, int N, int C,
     const float *S_in, const float *z_in, float *S_out, float *z_out, float eps, void *__restrict__ ws,
     unsigned long long epoch, uint32_t spin_limit)
 {
@@ -61,6 +61,8 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
     float *partials = static_cast<float *>(ws) + (size_t)bh * kMaxChunks * elems;
     EpochSource es;
     es.begin(ws, BH, elems, epoch);
+    // kRope3D: the tables sit behind everything else in LDS and live through both phases
+    const unsigned char *lds_tab = lds + block_step_lds_bytes<DP, TILE, WAVES, ROPE>();
 
     // Once all partials of the head are there, fold this workgroup's slice into S, z, then wait for
     // the other slices.
@@ -77,20 +79,24 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
         //      state phase and make no later load wait behind them --------------------------------
         constexpr int kEarly = DEPTH_A < 2 ? DEPTH_A : 2;
         const TileWalk walk(0, WAVES * c + wave, WAVES * C, n_tiles, bh);
-        ApplyStream<DEPTH_A, ROPE> qstream(Q + head_off, O + head_off, rope, st.n, N, lane, walk);
+        ApplyStream<DEPTH_A, ROPE> qstream(Q + head_off, O + head_off, rope, lds_tab, st.n, N, lane, walk);
         apply_prefetch<0, kEarly>(qstream);
 
         // ---- fold this workgroup's share of K_b, V_b ----------------------------------------------
         {
             StateAcc acc;
             acc.clear();
-            StateStream<TILE, DEPTH_S, ROPE> kvstream(K + head_off, V + head_off, rope, st.n, N, lane, walk);
+            StateStream<TILE, DEPTH_S, ROPE> kvstream(K + head_off, V + head_off, rope, lds_tab, st.n, N, lane, walk);
             unsigned char *tileK = lds + wave * 2 * kTileBytes;
             state_prefetch(kvstream);
+            if (ROPE == kRope3D) {
+                rope3d_lds_fill(lds + block_step_lds_bytes<DP, TILE, WAVES, ROPE>(), rope.r3);
+                __syncthreads();
+            }
             state_accumulate(kvstream, tileK, tileK + kTileBytes, lane, acc);
             // the rest of this wave's Q prefetch streams in while the head's state is being agreed on
             apply_prefetch<kEarly, DEPTH_A>(qstream);
-            state_wg_reduce_store<WAVES, ROPE>(acc, reinterpret_cast<float *>(lds), wave, lane,
+            state_wg_reduce_store<WAVES, ROPE != kRopeNone>(acc, reinterpret_cast<float *>(lds), wave, lane,
                                                partials + (size_t)c * elems);
         }
         agree_on_state();
@@ -101,15 +107,19 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
         apply_tiles<HILO>(qstream, lds + wave * apply_wave_lds_bytes<ROPE>(), lane, A, eps);
     } else {
         constexpr int kEarly = DEPTH_A < 2 ? DEPTH_A : 2;
-        CoopApplyStream<DEPTH_A, ROPE> qstream(Q + head_off, O + head_off, rope, st.n, N, d, wave, lane,
+        CoopApplyStream<DEPTH_A, ROPE> qstream(Q + head_off, O + head_off, rope, lds_tab, st.n, N, d, wave, lane,
                                                TileWalk(0, c, C, (N + 63) / 64, bh));
         coop_apply_prefetch<0, kEarly>(qstream);
         {
             StateAcc acc;
             acc.clear();
-            CoopStateStream<DEPTH_S, ROPE> kvstream(K + head_off, V + head_off, rope, st.n, N, d, wave, lane,
+            CoopStateStream<DEPTH_S, ROPE> kvstream(K + head_off, V + head_off, rope, lds_tab, st.n, N, d, wave, lane,
                                                     TileWalk(0, c, C, n_tiles, bh));
             coop_state_prefetch(kvstream);
+            if (ROPE == kRope3D) {
+                rope3d_lds_fill(lds + block_step_lds_bytes<DP, TILE, WAVES, ROPE>(), rope.r3);
+                __syncthreads();
+            }
             state_accumulate_coop(kvstream, lds, wave, lane, wave & 1, wave >> 1, acc);
             coop_apply_prefetch<kEarly, DEPTH_A>(qstream);
             state_wg_quadrant_store(acc, reinterpret_cast<float *>(lds), wave, lane, d, partials + (size_t)c * elems);

@@ -112,23 +112,6 @@ __device__ __forceinline__ uint32_t tile_offset(bool valid, int tok0, uint32_t r
     return valid ? (uint32_t)tok0 * row_bytes : kOutOfRange;
 }
 
-// Table entries that go with the 16-byte chunks a lane holds of a token tile in the coalesced
-// layout: rows `row0 + rows_per_step * i` of the tile (i < STEPS), four (cos, sin) pairs = 32
-// bytes per chunk.  `rT` covers the table rows below the end of the token range; `off0` is the
-// tile's byte offset in the table (kOutOfRange past the share), `lane_off` the byte offset of the
-// lane's first entry inside the tile, `step_bytes` the distance between a lane's rows.  Rows out of
-// range read as zeros, which turn the (all-zero) features they meet into zeros.
-template <int STEPS>
-__device__ __forceinline__ void rope_tile_load(rsrc_t rT, uint32_t off0, uint32_t lane_off, uint32_t step_bytes,
-                                               f32x4 (&cs)[STEPS][2])
-{
-#pragma unroll
-    for (int i = 0; i < STEPS; ++i) {
-        cs[i][0] = load_cached16(rT, off0 + lane_off + (uint32_t)i * step_bytes);
-        cs[i][1] = load_cached16(rT, off0 + lane_off + (uint32_t)i * step_bytes + 16u);
-    }
-}
-
 // ---- typed scalar access used by the generic (any dtype) kernels --------------------------
 
 template <typename T> struct Elem;

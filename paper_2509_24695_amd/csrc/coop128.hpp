@@ -41,28 +41,24 @@ __device__ __forceinline__ void lds_barrier() {
 
 // One wave's share of the workgroup's K/V stream: rows 8*wave .. +8 of every tile
 // (16 lanes of 16 bytes per row, 4 rows per load instruction), DEPTH tiles in flight.
-template <int DEPTH, bool ROPE>
+template <int DEPTH, int ROPE>
 struct CoopStateStream {
     static constexpr int NLD = 2;
-    rsrc_t rK, rV, rT;
-    uint32_t row_bytes, table_row_bytes, lane_off, lane_off_t;
+    rsrc_t rK, rV;
+    uint32_t row_bytes, lane_off;
     bool valid;
     TileWalk walk;                       // the workgroup's tiles: identical in all four waves
     u32x4 k[DEPTH][NLD], v[DEPTH][NLD];
-    f32x4 cs[ROPE ? DEPTH : 1][NLD][2];
+    Rotator<ROPE, NLD, DEPTH> rot;
 
-    __device__ __forceinline__ CoopStateStream(const uint16_t *Kh, const uint16_t *Vh, const float *rope,
-                                               int64_t stride_n, int t1, int d, int wave, int lane, const TileWalk &w)
+    __device__ __forceinline__ CoopStateStream(const uint16_t *Kh, const uint16_t *Vh, const RopeArg &rope,
+                                               const unsigned char *lds_tab, int64_t stride_n, int t1, int d, int wave,
+                                               int lane, const TileWalk &w)
         : rK(make_rsrc(Kh, (uint32_t)t1 * (uint32_t)stride_n * 2u)),
-          rV(make_rsrc(Vh, (uint32_t)t1 * (uint32_t)stride_n * 2u)),
-          rT(make_rsrc(rope, ROPE ? (uint32_t)t1 * (uint32_t)d * 4u : 0u)), row_bytes((uint32_t)stride_n * 2u),
-          table_row_bytes((uint32_t)d * 4u), walk(w)
-    {
-        const uint32_t row = 8u * (uint32_t)wave + (uint32_t)(lane >> 4), col = (uint32_t)(lane & 15);
-        lane_off = row * row_bytes + col * 16u;
-        lane_off_t = row * table_row_bytes + col * 32u;
-        valid = (int)col * 8 < d;
-    }
+          rV(make_rsrc(Vh, (uint32_t)t1 * (uint32_t)stride_n * 2u)), row_bytes((uint32_t)stride_n * 2u),
+          lane_off((uint32_t)(8 * wave + (lane >> 4)) * (uint32_t)stride_n * 2u + (uint32_t)(lane & 15) * 16u),
+          valid((lane & 15) * 8 < d), walk(w),
+          rot(rope, t1, d, 8 * wave + (lane >> 4), 4, 4 * (lane & 15), 1, lds_tab) {}
 
     __device__ __forceinline__ void request(int s, int i)
     {
@@ -72,13 +68,11 @@ struct CoopStateStream {
             k[s][j] = load_stream16(rK, base + lane_off + (uint32_t)j * 4u * row_bytes);
             v[s][j] = load_stream16(rV, base + lane_off + (uint32_t)j * 4u * row_bytes);
         }
-        if (ROPE)
-            rope_tile_load<NLD>(rT, valid ? walk.offset<32>(i, table_row_bytes) : kOutOfRange, lane_off_t,
-                                4u * table_row_bytes, cs[ROPE ? s : 0]);
+        rot.request(s, i < walk.count, walk.token<32>(i));
     }
 };
 
-template <int DEPTH, bool ROPE>
+template <int DEPTH, int ROPE>
 __device__ __forceinline__ void coop_state_prefetch(CoopStateStream<DEPTH, ROPE> &st)
 {
 #pragma unroll
@@ -90,12 +84,12 @@ __device__ __forceinline__ void coop_state_prefetch(CoopStateStream<DEPTH, ROPE>
 
 // LDS of the state phase: K and V tiles, double-buffered; with ROPE also the
 // un-rotated phi(K) (the key sum is never rotated).
-template <bool ROPE> __host__ __device__ constexpr int coop_state_lds_bytes() { return (ROPE ? 6 : 4) * kCoopTile; }
+template <int ROPE> __host__ __device__ constexpr int coop_state_lds_bytes() { return (ROPE ? 6 : 4) * kCoopTile; }
 
 // Accumulates quadrant (kb, vb) of the workgroup's partial state over the
 // workgroup's tiles.  Must be called by all four waves (it contains barriers; the
 // tile count is the same in all of them).  Key sums are kept by the waves with vb == 0.
-template <int DEPTH, bool ROPE>
+template <int DEPTH, int ROPE>
 __device__ __forceinline__ void state_accumulate_coop(CoopStateStream<DEPTH, ROPE> &st, unsigned char *lds, int wave,
                                                       int lane, int kb, int vb, StateAcc &acc)
 {
@@ -113,13 +107,13 @@ __device__ __forceinline__ void state_accumulate_coop(CoopStateStream<DEPTH, ROP
             unsigned char *bufK = lds + (s & 1) * kCoopTile, *bufV = lds + (2 + (s & 1)) * kCoopTile;
             unsigned char *bufP = ROPE ? lds + (4 + (s & 1)) * kCoopTile : bufK;   // un-rotated phi(K)
             if (valid) {
+                st.rot.begin_tile(st.walk.template token<32>(i0 + s));
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
                     const u32x4 kk = relu_bf16x8(st.k[s][j]);
                     if (ROPE) {
                         *reinterpret_cast<u32x4 *>(bufP + wr_off + 4 * j * kCoopRow) = kk;
-                        *reinterpret_cast<u32x4 *>(bufK + wr_off + 4 * j * kCoopRow) =
-                            rope_rotate_bf16x8(kk, st.cs[ROPE ? s : 0][j][0], st.cs[ROPE ? s : 0][j][1]);
+                        *reinterpret_cast<u32x4 *>(bufK + wr_off + 4 * j * kCoopRow) = st.rot.rotate(s, j, kk);
                     } else {
                         *reinterpret_cast<u32x4 *>(bufK + wr_off + 4 * j * kCoopRow) = kk;
                     }
@@ -159,41 +153,35 @@ __device__ __forceinline__ void state_accumulate_coop(CoopStateStream<DEPTH, ROP
 
 // One wave's share of the workgroup's Q/O stream: rows 16*wave .. +16 of every
 // pair of tiles (64 tokens), both for the loads of Q and for the stores of O.
-template <int DEPTH, bool ROPE>
+template <int DEPTH, int ROPE>
 struct CoopApplyStream {
     static constexpr int NLD = 4;
-    rsrc_t rQ, rO, rT;
-    uint32_t row_bytes, table_row_bytes, lane_off, lane_off_t;
+    rsrc_t rQ, rO;
+    uint32_t row_bytes, lane_off;
     bool valid;
     TileWalk walk;                       // the workgroup's tile pairs (units of 64 tokens)
     u32x4 q[DEPTH][NLD];
-    f32x4 cs[ROPE ? DEPTH : 1][NLD][2];
+    Rotator<ROPE, NLD, DEPTH> rot;
 
-    __device__ __forceinline__ CoopApplyStream(const uint16_t *Qh, uint16_t *Oh, const float *rope, int64_t stride_n,
-                                               int t1, int d, int wave, int lane, const TileWalk &w)
+    __device__ __forceinline__ CoopApplyStream(const uint16_t *Qh, uint16_t *Oh, const RopeArg &rope,
+                                               const unsigned char *lds_tab, int64_t stride_n, int t1, int d, int wave,
+                                               int lane, const TileWalk &w)
         : rQ(make_rsrc(Qh, (uint32_t)t1 * (uint32_t)stride_n * 2u)),
-          rO(make_rsrc(Oh, (uint32_t)t1 * (uint32_t)stride_n * 2u)),
-          rT(make_rsrc(rope, ROPE ? (uint32_t)t1 * (uint32_t)d * 4u : 0u)), row_bytes((uint32_t)stride_n * 2u),
-          table_row_bytes((uint32_t)d * 4u), walk(w)
-    {
-        const uint32_t row = 16u * (uint32_t)wave + (uint32_t)(lane >> 4), col = (uint32_t)(lane & 15);
-        lane_off = row * row_bytes + col * 16u;
-        lane_off_t = row * table_row_bytes + col * 32u;
-        valid = (int)col * 8 < d;
-    }
+          rO(make_rsrc(Oh, (uint32_t)t1 * (uint32_t)stride_n * 2u)), row_bytes((uint32_t)stride_n * 2u),
+          lane_off((uint32_t)(16 * wave + (lane >> 4)) * (uint32_t)stride_n * 2u + (uint32_t)(lane & 15) * 16u),
+          valid((lane & 15) * 8 < d), walk(w),
+          rot(rope, t1, d, 16 * wave + (lane >> 4), 4, 4 * (lane & 15), 1, lds_tab) {}
 
     __device__ __forceinline__ void request(int s, int i)
     {
         const uint32_t base = valid ? walk.offset<64>(i, row_bytes) : kOutOfRange;
 #pragma unroll
         for (int j = 0; j < NLD; ++j) q[s][j] = load_stream16(rQ, base + lane_off + (uint32_t)j * 4u * row_bytes);
-        if (ROPE)
-            rope_tile_load<NLD>(rT, valid ? walk.offset<64>(i, table_row_bytes) : kOutOfRange, lane_off_t,
-                                4u * table_row_bytes, cs[ROPE ? s : 0]);
+        rot.request(s, i < walk.count, walk.token<64>(i));
     }
 };
 
-template <int FROM, int TO, int DEPTH, bool ROPE>
+template <int FROM, int TO, int DEPTH, int ROPE>
 __device__ __forceinline__ void coop_apply_prefetch(CoopApplyStream<DEPTH, ROPE> &st)
 {
 #pragma unroll
@@ -204,11 +192,11 @@ __device__ __forceinline__ void coop_apply_prefetch(CoopApplyStream<DEPTH, ROPE>
 }
 
 // LDS of the apply phase: a pair of Q tiles (with ROPE also their rotated copy) and a pair of O tiles.
-template <bool ROPE> __host__ __device__ constexpr int coop_apply_lds_bytes() { return (ROPE ? 6 : 4) * kCoopTile; }
+template <int ROPE> __host__ __device__ constexpr int coop_apply_lds_bytes() { return (ROPE ? 6 : 4) * kCoopTile; }
 
 // Applies the state panel in `A` (value block wave%2) to tile wave/2 of every pair
 // of the workgroup's share.  Must be called by all four waves.
-template <bool HILO, int DEPTH, bool ROPE>
+template <bool HILO, int DEPTH, int ROPE>
 __device__ __forceinline__ void apply_tiles_coop(CoopApplyStream<DEPTH, ROPE> &st, unsigned char *lds, int wave,
                                                  int lane, const ApplyOperands<128, HILO> &A, float eps)
 {
@@ -227,13 +215,12 @@ __device__ __forceinline__ void apply_tiles_coop(CoopApplyStream<DEPTH, ROPE> &s
             const bool valid = i0 + s < st.walk.count;
             const uint32_t out_off = st.valid ? st.walk.template offset<64>(i0 + s, st.row_bytes) : kOutOfRange;
             if (valid) {
+                st.rot.begin_tile(st.walk.template token<64>(i0 + s));
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const u32x4 pq = relu_bf16x8(st.q[s][j]);                          // phi(Q)
                     *reinterpret_cast<u32x4 *>(bufQ + wr_off + 4 * j * kCoopRow) = pq;
-                    if (ROPE)
-                        *reinterpret_cast<u32x4 *>(bufR + wr_off + 4 * j * kCoopRow) =
-                            rope_rotate_bf16x8(pq, st.cs[ROPE ? s : 0][j][0], st.cs[ROPE ? s : 0][j][1]);
+                    if (ROPE) *reinterpret_cast<u32x4 *>(bufR + wr_off + 4 * j * kCoopRow) = st.rot.rotate(s, j, pq);
                 }
             }
             st.request(s, i0 + s + DEPTH);   // refill this stage: DEPTH pairs ahead
@@ -294,7 +281,7 @@ __device__ __forceinline__ void apply_tiles_coop(CoopApplyStream<DEPTH, ROPE> &s
 // ---- kernels ---------------------------------------------------------------------------------------
 
 // Dynamic LDS: the larger of the streaming buffers and the four reduction slots.
-template <bool ROPE>
+template <int ROPE>
 __host__ __device__ constexpr int state_d128_lds_bytes() {
     return (coop_state_lds_bytes<ROPE>() > 4 * kStateElems * 4 ? coop_state_lds_bytes<ROPE>() : 4 * kStateElems * 4) +
            kEpochLdsBytes;
@@ -303,9 +290,9 @@ __host__ __device__ constexpr int state_d128_lds_bytes() {
 // State reduction for d = 112 or 128.  grid = (C, B*H), block = 256; workgroup c
 // owns tiles c + C*i of the T = ceil((t1-t0)/32) tiles.  FINALIZE and ROPE as in
 // state_mfma_d64; partial states and S are d x d with row length d.
-template <int DEPTH, bool FINALIZE, bool ROPE>
+template <int DEPTH, bool FINALIZE, int ROPE>
 __global__ __launch_bounds__(256, 1) void state_mfma_d128(
-    const uint16_t *__restrict__ K, const uint16_t *__restrict__ V, const float *__restrict__ rope, TokStrides st,
+    const uint16_t *__restrict__ K, const uint16_t *__restrict__ V, RopeArg rope, TokStrides st,
     int H, int d, int t0, int t1, int C, const float *S_in, const float *z_in, float *S_out, float *z_out,
     void *__restrict__ ws, unsigned long long epoch, uint32_t spin_limit)
 {
@@ -323,8 +310,13 @@ __global__ __launch_bounds__(256, 1) void state_mfma_d128(
 
     StateAcc acc;
     acc.clear();
-    CoopStateStream<DEPTH, ROPE> stream(Kh, Vh, rope, st.n, t1, d, wave, lane, TileWalk(t0, c, C, n_tiles, bh));
+    CoopStateStream<DEPTH, ROPE> stream(Kh, Vh, rope, lds + state_d128_lds_bytes<ROPE>(), st.n, t1, d, wave, lane,
+                                        TileWalk(t0, c, C, n_tiles, bh));
     coop_state_prefetch(stream);
+    if (ROPE == kRope3D) {
+        rope3d_lds_fill(lds + state_d128_lds_bytes<ROPE>(), rope.r3);
+        __syncthreads();
+    }
     state_accumulate_coop(stream, lds, wave, lane, wave & 1, wave >> 1, acc);
 
     float *partials = static_cast<float *>(ws) + (size_t)bh * kMaxChunks * elems;
@@ -339,9 +331,9 @@ __global__ __launch_bounds__(256, 1) void state_mfma_d128(
 
 // Apply for d = 112 or 128.  grid = (C, B*H), block = 256; workgroup c owns the
 // pairs of tiles c + C*i of the ceil((t1-t0)/64) pairs.
-template <bool HILO, int DEPTH, bool ROPE>
+template <bool HILO, int DEPTH, int ROPE>
 __global__ __launch_bounds__(256, 1) void apply_mfma_d128(
-    const uint16_t *__restrict__ Q, uint16_t *__restrict__ O, const float *__restrict__ rope, TokStrides st, int H,
+    const uint16_t *__restrict__ Q, uint16_t *__restrict__ O, RopeArg rope, TokStrides st, int H,
     int d, int t0, int t1, int C, const float *__restrict__ S, const float *__restrict__ z, float eps)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -353,8 +345,13 @@ __global__ __launch_bounds__(256, 1) void apply_mfma_d128(
     uint16_t *Oh = O + b * st.b + h * st.h;
     const int n_pairs = (t1 - t0 + 63) / 64;
 
-    CoopApplyStream<DEPTH, ROPE> stream(Qh, Oh, rope, st.n, t1, d, wave, lane, TileWalk(t0, c, C, n_pairs, bh));
+    CoopApplyStream<DEPTH, ROPE> stream(Qh, Oh, rope, lds + coop_apply_lds_bytes<ROPE>(), st.n, t1, d, wave, lane,
+                                        TileWalk(t0, c, C, n_pairs, bh));
     coop_apply_prefetch<0, DEPTH>(stream);   // in flight while S is fetched
+    if (ROPE == kRope3D) {
+        rope3d_lds_fill(lds + coop_apply_lds_bytes<ROPE>(), rope.r3);
+        __syncthreads();
+    }
     ApplyOperands<128, HILO> A;
     A.template load<false>(S + (size_t)bh * d * d, z + (size_t)bh * d, d, wave & 1, lane);
     apply_tiles_coop<HILO>(stream, lds, wave, lane, A, eps);

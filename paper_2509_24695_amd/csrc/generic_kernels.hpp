@@ -8,6 +8,7 @@
 #pragma once
 
 #include "common.hpp"
+#include "rope.hpp"
 
 namespace sv {
 
@@ -18,11 +19,11 @@ namespace sv {
 // [c*T/C, (c+1)*T/C) of the T tiles that cover [t0, t1).  Row k of S is shared
 // by TPR threads (the largest power of two with D*TPR <= 256); threads past
 // D*TPR only help with the loads.
-// rope != null: the keys that meet V are rotated after the ReLU (table row = token index,
-// D/2 (cos, sin) pairs); the key sum uses the plain ones.
+// rope_mode (kRopeNone/Table/3D): the keys that meet V are rotated after the ReLU; the key sum
+// uses the plain ones.
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void state_partial_generic(
-    const T *__restrict__ K, const T *__restrict__ V, const float *__restrict__ rope, TokStrides st, int H, int t0,
+    const T *__restrict__ K, const T *__restrict__ V, RopeArg rope, int rope_mode, TokStrides st, int H, int t0,
     int t1, int C, float *__restrict__ ws)
 {
     constexpr int TT = 32;
@@ -61,9 +62,13 @@ __global__ __launch_bounds__(kThreads) void state_partial_generic(
                 b = fmaxf(Elem<T>::load(Kh + (int64_t)tok * st.n + 2 * p + 1), 0.f);
                 va = Elem<T>::load(Vh + (int64_t)tok * st.n + 2 * p);
                 vb = Elem<T>::load(Vh + (int64_t)tok * st.n + 2 * p + 1);
-                if (rope) {
-                    c = rope[(int64_t)tok * D + 2 * p];
-                    s = rope[(int64_t)tok * D + 2 * p + 1];
+                if (rope_mode == kRopeTable) {
+                    c = rope.table[(int64_t)tok * D + 2 * p];
+                    s = rope.table[(int64_t)tok * D + 2 * p + 1];
+                } else if (rope_mode == kRope3D) {
+                    const f32x2 e = rope3d_entry_global(rope.r3, tok, p);
+                    c = e.x;
+                    s = e.y;
                 }
             }
             sP[j][2 * p] = a;
@@ -120,14 +125,15 @@ __global__ __launch_bounds__(kThreads) void state_reduce(
 // grid = (C, B*H), block = 256, dynamic LDS = apply_generic_lds_bytes<D>().  The head's
 // S and z stay in LDS for the whole token range of the workgroup; D/4 threads
 // serve one token, 256/(D/4) tokens (rounded down) make a tile.
-// rope != null: the numerator uses queries rotated after the ReLU, the denominator the plain ones.
+// rope_mode (kRopeNone/Table/3D): the numerator uses queries rotated after the ReLU, the denominator
+// the plain ones.
 template <int D> __host__ __device__ constexpr int apply_generic_tile() { return kThreads / (D / 4); }
 template <int D> __host__ __device__ constexpr int apply_generic_lds_bytes() {
     return (D * D + D + 2 * apply_generic_tile<D>() * D) * (int)sizeof(float);
 }
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void apply_generic(
-    const T *__restrict__ Q, T *__restrict__ O, const float *__restrict__ rope, TokStrides st, int H, int t0, int t1,
+    const T *__restrict__ Q, T *__restrict__ O, RopeArg rope, int rope_mode, TokStrides st, int H, int t0, int t1,
     int C, const float *__restrict__ S, const float *__restrict__ z, float eps)
 {
     constexpr int VPT = 4;                   // outputs per thread
@@ -164,9 +170,13 @@ __global__ __launch_bounds__(kThreads) void apply_generic(
             if (tok < t1) {
                 a = fmaxf(Elem<T>::load(Qh + (int64_t)tok * st.n + 2 * p), 0.f);
                 b = fmaxf(Elem<T>::load(Qh + (int64_t)tok * st.n + 2 * p + 1), 0.f);
-                if (rope) {
-                    c = rope[(int64_t)tok * D + 2 * p];
-                    s = rope[(int64_t)tok * D + 2 * p + 1];
+                if (rope_mode == kRopeTable) {
+                    c = rope.table[(int64_t)tok * D + 2 * p];
+                    s = rope.table[(int64_t)tok * D + 2 * p + 1];
+                } else if (rope_mode == kRope3D) {
+                    const f32x2 e = rope3d_entry_global(rope.r3, tok, p);
+                    c = e.x;
+                    s = e.y;
                 }
             }
             sP[jj][2 * p] = a;

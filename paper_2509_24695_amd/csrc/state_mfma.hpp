@@ -29,6 +29,7 @@
 #pragma once
 
 #include "common.hpp"
+#include "rope.hpp"
 #include "sync.hpp"
 
 namespace sv {
@@ -202,24 +203,24 @@ __device__ __forceinline__ bf16x8 lds_tr_operand(const unsigned char *tile, int 
     return __builtin_bit_cast(bf16x8, both);
 }
 
-// One wave's input stream: buffer resources over the head's K and V rows (and
-// the rotation table) below the end of the token range, the wave's tile walk,
-// and the register staging of DEPTH tiles in flight.
-template <int TILE, int DEPTH, bool ROPE>
+// One wave's input stream: buffer resources over the head's K and V rows below
+// the end of the token range, the wave's tile walk, the register staging of
+// DEPTH tiles in flight, and the rotation source (ROPE: kRopeNone/Table/3D).
+template <int TILE, int DEPTH, int ROPE>
 struct StateStream {
-    rsrc_t rK, rV, rT;
-    uint32_t row_bytes, lane_off_t;
+    rsrc_t rK, rV;
+    uint32_t row_bytes;
     int lane;
     TileWalk walk;
     u32x4 k[DEPTH][TILE / 8], v[DEPTH][TILE / 8];
-    f32x4 cs[ROPE ? DEPTH : 1][TILE / 8][2];
+    Rotator<ROPE, TILE / 8, DEPTH> rot;
 
-    __device__ __forceinline__ StateStream(const uint16_t *Kh, const uint16_t *Vh, const float *rope,
-                                           int64_t stride_n, int t1, int lane_, const TileWalk &w)
+    __device__ __forceinline__ StateStream(const uint16_t *Kh, const uint16_t *Vh, const RopeArg &rope,
+                                           const unsigned char *lds_tab, int64_t stride_n, int t1, int lane_,
+                                           const TileWalk &w)
         : rK(make_rsrc(Kh, (uint32_t)t1 * (uint32_t)stride_n * 2u)),
-          rV(make_rsrc(Vh, (uint32_t)t1 * (uint32_t)stride_n * 2u)),
-          rT(make_rsrc(rope, ROPE ? (uint32_t)t1 * 256u : 0u)), row_bytes((uint32_t)stride_n * 2u),
-          lane_off_t((uint32_t)(lane_ >> 3) * 256u + (uint32_t)(lane_ & 7) * 32u), lane(lane_), walk(w) {}
+          rV(make_rsrc(Vh, (uint32_t)t1 * (uint32_t)stride_n * 2u)), row_bytes((uint32_t)stride_n * 2u), lane(lane_),
+          walk(w), rot(rope, t1, 64, lane_ >> 3, 8, 4 * (lane_ & 7), 1, lds_tab) {}
 
     // Requests the wave's i-th tile into stage s.  Always the same number of memory
     // instructions: past the wave's share they read nothing and return zeros.
@@ -227,12 +228,12 @@ struct StateStream {
     {
         token_tile_load<TILE>(rK, walk.offset<TILE>(i, row_bytes), row_bytes, lane, k[s]);
         token_tile_load<TILE>(rV, walk.offset<TILE>(i, row_bytes), row_bytes, lane, v[s]);
-        if (ROPE) rope_tile_load<TILE / 8>(rT, walk.offset<TILE>(i, 256u), lane_off_t, 8u * 256u, cs[ROPE ? s : 0]);
+        rot.request(s, i < walk.count, walk.token<TILE>(i));
     }
 };
 
 // Requests the first DEPTH tiles of a wave's share.
-template <int TILE, int DEPTH, bool ROPE>
+template <int TILE, int DEPTH, int ROPE>
 __device__ __forceinline__ void state_prefetch(StateStream<TILE, DEPTH, ROPE> &st)
 {
 #pragma unroll
@@ -246,7 +247,7 @@ __device__ __forceinline__ void state_prefetch(StateStream<TILE, DEPTH, ROPE> &s
 // requested.  Tiles are taken DEPTH at a time; in the last round the stages past
 // the share hold zeros, as do tokens past t1, and add nothing to either sum.
 // `tileK`/`tileV` are this wave's private LDS tiles.
-template <int TILE, int DEPTH, bool ROPE>
+template <int TILE, int DEPTH, int ROPE>
 __device__ __forceinline__ void state_accumulate(StateStream<TILE, DEPTH, ROPE> &st, unsigned char *tileK,
                                                  unsigned char *tileV, int lane, StateAcc &acc)
 {
@@ -260,6 +261,7 @@ __device__ __forceinline__ void state_accumulate(StateStream<TILE, DEPTH, ROPE> 
             // waited for) before this stage has been refilled
             __builtin_amdgcn_sched_barrier(0);
             // phi(K) on the packed pairs
+            st.rot.begin_tile(st.walk.template token<TILE>(i0 + s));
 #pragma unroll
             for (int i = 0; i < TILE / 8; ++i) {
                 const u32x4 kk = relu_bf16x8(st.k[s][i]);
@@ -270,7 +272,7 @@ __device__ __forceinline__ void state_accumulate(StateStream<TILE, DEPTH, ROPE> 
                     acc.z[4] += bf16_lo(kk.z);  acc.z[5] += bf16_hi(kk.z);
                     acc.z[6] += bf16_lo(kk.w);  acc.z[7] += bf16_hi(kk.w);
                 }
-                st.k[s][i] = ROPE ? rope_rotate_bf16x8(kk, st.cs[ROPE ? s : 0][i][0], st.cs[ROPE ? s : 0][i][1]) : kk;
+                st.k[s][i] = st.rot.rotate(s, i, kk);
             }
             wave_lds_fence();   // earlier reads of the tile buffer are done before it is overwritten
 #pragma unroll
@@ -341,13 +343,13 @@ __device__ __forceinline__ void state_acc_to_slot(StateAcc &acc, float *dst, int
 // barrier each thread adds the waves' slots for its share of the elements,
 // wave w absorbing wave w + h for h = WAVES/2, ..., 1.  Must be called by all
 // threads; the staging tiles are dead afterwards.  LDS: WAVES * kStateElems floats.
-template <int WAVES, bool ROPE>
+template <int WAVES, bool ZVALU>
 __device__ __forceinline__ void state_wg_reduce_store(StateAcc &acc, float *slots, int wave, int lane,
                                                       float *__restrict__ out)
 {
     constexpr int THREADS = 64 * WAVES;
     __syncthreads();                                   // all waves are done with their staging tiles
-    state_acc_to_slot<ROPE>(acc, slots + wave * kStateElems, lane);
+    state_acc_to_slot<ZVALU>(acc, slots + wave * kStateElems, lane);
     __syncthreads();
     for (int v = threadIdx.x; v < kStateElems / 2; v += THREADS) {
         f32x2 x[WAVES];
@@ -462,10 +464,11 @@ __host__ __device__ constexpr int state_lds_bytes() {
 // folds one slice of them: S_out, z_out = (S_in, z_in, or 0 if S_in is null) +
 // partials; this needs the whole grid to be resident.
 // Otherwise only the partials are written and state_reduce finishes the job.
-// ROPE: keys are rotated (table row = token index, d/2 (cos, sin) pairs) before they meet V.
-template <int TILE, int WAVES, int DEPTH, bool FINALIZE, bool ROPE>
+// ROPE (kRopeNone/Table/3D): keys are rotated before they meet V; with kRope3D the dynamic LDS
+// carries kRope3dLdsBytes more for the tables.
+template <int TILE, int WAVES, int DEPTH, bool FINALIZE, int ROPE>
 __global__ __launch_bounds__(64 * WAVES, 1) void state_mfma_d64(
-    const uint16_t *__restrict__ K, const uint16_t *__restrict__ V, const float *__restrict__ rope, TokStrides st,
+    const uint16_t *__restrict__ K, const uint16_t *__restrict__ V, RopeArg rope, TokStrides st,
     int H, int /* d: always 64; keeps the argument list of the d = 112/128 kernel */, int t0, int t1,
     int C, const float *S_in, const float *z_in, float *S_out, float *z_out, void *__restrict__ ws,
     unsigned long long epoch, uint32_t spin_limit)
@@ -486,15 +489,20 @@ __global__ __launch_bounds__(64 * WAVES, 1) void state_mfma_d64(
 
     StateAcc acc;
     acc.clear();
-    StateStream<TILE, DEPTH, ROPE> stream(Kh, Vh, rope, st.n, t1, lane,
+    const unsigned char *lds_tab = lds + state_lds_bytes<TILE, WAVES>();
+    StateStream<TILE, DEPTH, ROPE> stream(Kh, Vh, rope, lds_tab, st.n, t1, lane,
                                           TileWalk(t0, WAVES * c + wave, WAVES * C, n_tiles, bh));
     unsigned char *tileK = lds + wave * 2 * kTileBytes;
     state_prefetch(stream);
+    if (ROPE == kRope3D) {
+        rope3d_lds_fill(lds + state_lds_bytes<TILE, WAVES>(), rope.r3);
+        __syncthreads();
+    }
     state_accumulate(stream, tileK, tileK + kTileBytes, lane, acc);
 
     float *partials = static_cast<float *>(ws) + (size_t)bh * kMaxChunks * kStateElems;
-    state_wg_reduce_store<WAVES, ROPE>(acc, reinterpret_cast<float *>(lds), wave, lane,
-                                       partials + (size_t)c * kStateElems);
+    state_wg_reduce_store<WAVES, ROPE != kRopeNone>(acc, reinterpret_cast<float *>(lds), wave, lane,
+                                                    partials + (size_t)c * kStateElems);
     if (FINALIZE) {
         epoch = es.resolve(reinterpret_cast<unsigned long long *>(lds + state_lds_bytes<TILE, WAVES>() - kEpochLdsBytes));
         state_publish_and_wait(ws, BH, kStateElems, bh, c, C, 0, epoch, spin_limit, lane);

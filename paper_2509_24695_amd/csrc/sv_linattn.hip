@@ -25,12 +25,13 @@ constexpr int kVersion = 400;   // 0.4.0
 
 // Tuned launch shapes of the bf16 MFMA kernels (one workgroup per compute unit).
 // DP = 64 serves d = 64; DP = 128 serves d = 112 and 128.  Depths are tiles in
-// flight per wave, [DP = 128][RoPE]: a RoPE stage also holds its table rows.
+// flight per wave, [DP = 128][RoPE mode: none, table, 3-D]: a stage of the table mode also
+// holds its table rows.
 constexpr int kStateTile = 32, kStateWaves = 4, kApplyWaves = 4;
-constexpr int kStateDepth[2][2] = {{2, 2}, {8, 4}};
-constexpr int kApplyDepth[2][2] = {{2, 2}, {2, 2}};
-constexpr int kFusedStateDepth[2][2] = {{2, 2}, {4, 2}};
-constexpr int kFusedApplyDepth[2][2] = {{6, 2}, {2, 2}};   // Q tiles held in registers across the in-kernel waits
+constexpr int kStateDepth[2][3] = {{2, 2, 2}, {8, 4, 8}};
+constexpr int kApplyDepth[2][3] = {{2, 2, 2}, {2, 2, 2}};
+constexpr int kFusedStateDepth[2][3] = {{2, 2, 2}, {4, 2, 4}};
+constexpr int kFusedApplyDepth[2][3] = {{6, 2, 6}, {2, 2, 2}};   // Q tiles held in registers across the in-kernel waits
 constexpr bool kApplyHiLo = true;
 constexpr uint32_t kSpinLimit = 1u << 24;      // polls of ~100 ns: far beyond any real wait
 
@@ -43,43 +44,46 @@ struct Shape {
 
 struct Device {
     int num_cu = 0;
-    // how many workgroups fit on the device at once, [DP = 128][RoPE]
-    int state_resident_wgs[2][2] = {{0, 0}, {0, 0}};   // state kernel with in-kernel finalize
-    int fused_resident_wgs[2][2] = {{0, 0}, {0, 0}};   // one-launch block step
+    // how many workgroups fit on the device at once, [DP = 128][RoPE mode]
+    int state_resident_wgs[2][3] = {{0, 0, 0}, {0, 0, 0}};   // state kernel with in-kernel finalize
+    int fused_resident_wgs[2][3] = {{0, 0, 0}, {0, 0, 0}};   // one-launch block step
     bool ok = false;
 };
 
-// The kernels in use, by padded head dimension and with or without RoPE.
-template <int DP, bool ROPE> struct Kernels;
-template <bool ROPE> struct Kernels<64, ROPE> {
+// The kernels in use, by padded head dimension and RoPE mode.  LDS sizes include the room for the
+// factored tables where the mode needs it.
+template <int DP, int ROPE> struct Kernels;
+template <int ROPE> struct Kernels<64, ROPE> {
+    static constexpr int kTab = ROPE == kRope3D ? kRope3dLdsBytes : 0;
     static constexpr int W = 0;
     static constexpr auto state = state_mfma_d64<kStateTile, kStateWaves, kStateDepth[W][ROPE], true, ROPE>;
     static constexpr auto state_partial = state_mfma_d64<kStateTile, kStateWaves, kStateDepth[W][ROPE], false, ROPE>;
     static constexpr auto apply = apply_mfma_d64<kApplyHiLo, kApplyWaves, kApplyDepth[W][ROPE], ROPE>;
     static constexpr auto fused = block_step_mfma<64, kStateTile, kStateWaves, kFusedStateDepth[W][ROPE], kApplyHiLo,
                                                   kFusedApplyDepth[W][ROPE], ROPE>;
-    static constexpr int state_lds = state_lds_bytes<kStateTile, kStateWaves>();
-    static constexpr int apply_lds = apply_lds_bytes<kApplyWaves, ROPE>();
-    static constexpr int fused_lds = block_step_lds_bytes<64, kStateTile, kStateWaves, ROPE>();
+    static constexpr int state_lds = state_lds_bytes<kStateTile, kStateWaves>() + kTab;
+    static constexpr int apply_lds = apply_lds_bytes<kApplyWaves, ROPE>() + kTab;
+    static constexpr int fused_lds = block_step_lds_bytes<64, kStateTile, kStateWaves, ROPE>() + kTab;
     // tokens one workgroup covers per round of its tile walk
     static constexpr int state_wg_tokens = kStateTile * kStateWaves;
     static constexpr int apply_wg_tokens = kApplyTile * kApplyWaves;
 };
-template <bool ROPE> struct Kernels<128, ROPE> {
+template <int ROPE> struct Kernels<128, ROPE> {
     static constexpr int W = 1;
+    static constexpr int kTab = ROPE == kRope3D ? kRope3dLdsBytes : 0;
     static constexpr auto state = state_mfma_d128<kStateDepth[W][ROPE], true, ROPE>;
     static constexpr auto state_partial = state_mfma_d128<kStateDepth[W][ROPE], false, ROPE>;
     static constexpr auto apply = apply_mfma_d128<kApplyHiLo, kApplyDepth[W][ROPE], ROPE>;
     static constexpr auto fused = block_step_mfma<128, kStateTile, kStateWaves, kFusedStateDepth[W][ROPE], kApplyHiLo,
                                                   kFusedApplyDepth[W][ROPE], ROPE>;
-    static constexpr int state_lds = state_d128_lds_bytes<ROPE>();
-    static constexpr int apply_lds = coop_apply_lds_bytes<ROPE>();
-    static constexpr int fused_lds = block_step_lds_bytes<128, kStateTile, kStateWaves, ROPE>();
+    static constexpr int state_lds = state_d128_lds_bytes<ROPE>() + kTab;
+    static constexpr int apply_lds = coop_apply_lds_bytes<ROPE>() + kTab;
+    static constexpr int fused_lds = block_step_lds_bytes<128, kStateTile, kStateWaves, ROPE>() + kTab;
     static constexpr int state_wg_tokens = 32;   // the four waves share one tile
     static constexpr int apply_wg_tokens = 64;   // ... and one pair of tiles
 };
 
-template <int DP, bool ROPE> void init_kernels(Device &d)
+template <int DP, int ROPE> void init_kernels(Device &d)
 {
     using KN = Kernels<DP, ROPE>;
     const auto attr = hipFuncAttributeMaxDynamicSharedMemorySize;
@@ -99,17 +103,25 @@ template <int DP, bool ROPE> void init_kernels(Device &d)
     d.state_resident_wgs[KN::W][ROPE] = per_cu * d.num_cu;
 }
 
-// Calls f(Kernels<DP, ROPE>{}) for the MFMA kernel family that serves head dimension d.
-template <typename F> void with_mfma_kernels(int d, bool rope, F &&f)
+// Calls f(Kernels<DP, ROPE>{}) for the MFMA kernel family that serves head dimension d and RoPE mode.
+template <typename F> void with_mfma_kernels(int d, int rope_mode, F &&f)
 {
     if (d == 64) {
-        if (rope) f(Kernels<64, true>{});
-        else f(Kernels<64, false>{});
+        if (rope_mode == kRope3D) f(Kernels<64, kRope3D>{});
+        else if (rope_mode == kRopeTable) f(Kernels<64, kRopeTable>{});
+        else f(Kernels<64, kRopeNone>{});
     } else {
-        if (rope) f(Kernels<128, true>{});
-        else f(Kernels<128, false>{});
+        if (rope_mode == kRope3D) f(Kernels<128, kRope3D>{});
+        else if (rope_mode == kRopeTable) f(Kernels<128, kRopeTable>{});
+        else f(Kernels<128, kRopeNone>{});
     }
 }
+
+// The rotation a call asks for, validated.
+struct Rope {
+    int mode = kRopeNone;
+    RopeArg arg{};
+};
 
 // Switches a workspace to device-side epochs (and clears its error word).
 __global__ void workspace_header_init(unsigned long long *error, unsigned long long *magic, unsigned long long *tickets,
@@ -151,10 +163,12 @@ const Device &device_info()
         hipDeviceProp_t prop;
         if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return d;
         d.num_cu = prop.multiProcessorCount;
-        init_kernels<64, false>(d);
-        init_kernels<64, true>(d);
-        init_kernels<128, false>(d);
-        init_kernels<128, true>(d);
+        init_kernels<64, kRopeNone>(d);
+        init_kernels<64, kRopeTable>(d);
+        init_kernels<64, kRope3D>(d);
+        init_kernels<128, kRopeNone>(d);
+        init_kernels<128, kRopeTable>(d);
+        init_kernels<128, kRope3D>(d);
         for (int hd : {32, 64, 112, 128})          // the larger generic apply kernels need more than 64 KB of LDS
             with_head_dim(hd, [&](auto D) {
                 const auto attr = hipFuncAttributeMaxDynamicSharedMemorySize;
@@ -215,10 +229,16 @@ sv_status check_desc(const sv_tensor_desc *t, Shape *s)
 }
 
 // The MFMA kernels address a head's tokens (and the rotation table) with 32-bit byte offsets.
-bool mfma_path(const Shape &s, const float *rope)
+bool mfma_path(const Shape &s, const Rope &rope)
 {
     constexpr int64_t kLimit = int64_t(1) << 31;
-    return s.bf16 && s.d >= 64 && (int64_t)s.N * s.st.n * 2 < kLimit && (!rope || (int64_t)s.N * s.d * 4 < kLimit);
+    if (!s.bf16 || s.d < 64 || (int64_t)s.N * s.st.n * 2 >= kLimit) return false;
+    if (rope.mode == kRopeTable && (int64_t)s.N * s.d * 4 >= kLimit) return false;
+    if (rope.mode == kRope3D) {            // the three tables must fit the LDS set aside for them
+        const Rope3D &r = rope.arg.r3;
+        if ((int64_t)rope3d_entries(r.frames, r.rows, r.cols, r.n_t, r.n_h, r.n_w) * 8 > kRope3dLdsBytes) return false;
+    }
+    return true;
 }
 
 sv_status check_range(const Shape &s, int32_t t0, int32_t t1)
@@ -234,20 +254,20 @@ bool eps_ok(float eps) { return isfinite(eps) && eps >= 0.f; }
 
 // S_out, z_out = (S_in, z_in, or 0 when S_in is null) + state of tokens [t0,t1).  S_in may equal S_out.
 // rope: rotation table or null.  All arguments are already validated.
-void launch_state_mfma(const uint16_t *k, const uint16_t *v, const float *rope, const Shape &s, int t0, int t1,
+void launch_state_mfma(const uint16_t *k, const uint16_t *v, const Rope &rope, const Shape &s, int t0, int t1,
                        const float *S_in, const float *z_in, float *S_out, float *z_out, void *ws, const Device &dev,
                        dim3 rgrid, hipStream_t stream)
 {
-    with_mfma_kernels(s.d, rope != nullptr, [&](auto kn) {
+    with_mfma_kernels(s.d, rope.mode, [&](auto kn) {
         using KN = decltype(kn);
         const int C = plan_chunks(s.BH, t1 - t0, KN::state_wg_tokens, dev.num_cu);
-        if ((int64_t)C * s.BH <= dev.state_resident_wgs[KN::W][rope != nullptr]) {
+        if ((int64_t)C * s.BH <= dev.state_resident_wgs[KN::W][rope.mode]) {
             // the head's workgroups wait for each other inside the kernel: all must be resident
             KN::state<<<dim3(C, s.BH), 64 * kStateWaves, KN::state_lds, stream>>>(
-                k, v, rope, s.st, s.H, s.d, t0, t1, C, S_in, z_in, S_out, z_out, ws, next_epoch(), kSpinLimit);
+                k, v, rope.arg, s.st, s.H, s.d, t0, t1, C, S_in, z_in, S_out, z_out, ws, next_epoch(), kSpinLimit);
         } else {
             KN::state_partial<<<dim3(C, s.BH), 64 * kStateWaves, KN::state_lds, stream>>>(
-                k, v, rope, s.st, s.H, s.d, t0, t1, C, S_in, z_in, S_out, z_out, ws, 0ull, 0u);
+                k, v, rope.arg, s.st, s.H, s.d, t0, t1, C, S_in, z_in, S_out, z_out, ws, 0ull, 0u);
             with_head_dim(s.d, [&](auto D) {
                 state_reduce<D()><<<rgrid, kThreads, 0, stream>>>(static_cast<float *>(ws), C, kMaxChunks, S_in, z_in,
                                                                  S_out, z_out);
@@ -256,7 +276,7 @@ void launch_state_mfma(const uint16_t *k, const uint16_t *v, const float *rope, 
     });
 }
 
-sv_status enqueue_state(const void *K, const void *V, const float *rope, const Shape &s, int t0, int t1,
+sv_status enqueue_state(const void *K, const void *V, const Rope &rope, const Shape &s, int t0, int t1,
                         const float *S_in, const float *z_in, float *S_out, float *z_out, void *ws,
                         hipStream_t stream)
 {
@@ -284,16 +304,18 @@ sv_status enqueue_state(const void *K, const void *V, const float *rope, const S
     with_head_dim(s.d, [&](auto D) {
         if (s.bf16)
             state_partial_generic<uint16_t, D()><<<grid, kThreads, 0, stream>>>(
-                static_cast<const uint16_t *>(K), static_cast<const uint16_t *>(V), rope, s.st, s.H, t0, t1, C, wsf);
+                static_cast<const uint16_t *>(K), static_cast<const uint16_t *>(V), rope.arg, rope.mode, s.st, s.H, t0, t1,
+                C, wsf);
         else
             state_partial_generic<float, D()><<<grid, kThreads, 0, stream>>>(
-                static_cast<const float *>(K), static_cast<const float *>(V), rope, s.st, s.H, t0, t1, C, wsf);
+                static_cast<const float *>(K), static_cast<const float *>(V), rope.arg, rope.mode, s.st, s.H, t0, t1, C,
+                wsf);
         state_reduce<D()><<<rgrid, kThreads, 0, stream>>>(wsf, C, C, S_in, z_in, S_out, z_out);
     });
     return launch_status();
 }
 
-sv_status enqueue_apply(const void *Q, const float *rope, const Shape &s, int t0, int t1, const float *S,
+sv_status enqueue_apply(const void *Q, const Rope &rope, const Shape &s, int t0, int t1, const float *S,
                         const float *z, float eps, void *O, hipStream_t stream)
 {
     const int n = t1 - t0;
@@ -301,15 +323,15 @@ sv_status enqueue_apply(const void *Q, const float *rope, const Shape &s, int t0
     const Device &dev = device_info();
     if (!dev.ok) return SV_ERR_LAUNCH;
     if (mfma_path(s, rope)) {
-        with_mfma_kernels(s.d, rope != nullptr, [&](auto kn) {
+        with_mfma_kernels(s.d, rope.mode, [&](auto kn) {
             using KN = decltype(kn);
             int C = dev.num_cu / s.BH;
             const int steps = (n + KN::apply_wg_tokens - 1) / KN::apply_wg_tokens;
             if (C > steps) C = steps;
             if (C < 1) C = 1;
             KN::apply<<<dim3(C, s.BH), 64 * kApplyWaves, KN::apply_lds, stream>>>(
-                static_cast<const uint16_t *>(Q), static_cast<uint16_t *>(O), rope, s.st, s.H, s.d, t0, t1, C, S, z,
-                eps);
+                static_cast<const uint16_t *>(Q), static_cast<uint16_t *>(O), rope.arg, s.st, s.H, s.d, t0, t1, C, S,
+                z, eps);
         });
         return launch_status();
     }
@@ -322,58 +344,96 @@ sv_status enqueue_apply(const void *Q, const float *rope, const Shape &s, int t0
         constexpr int lds = apply_generic_lds_bytes<D()>();
         if (s.bf16)
             apply_generic<uint16_t, D()><<<grid, kThreads, lds, stream>>>(
-                static_cast<const uint16_t *>(Q), static_cast<uint16_t *>(O), rope, s.st, s.H, t0, t1, C, S, z, eps);
+                static_cast<const uint16_t *>(Q), static_cast<uint16_t *>(O), rope.arg, rope.mode, s.st, s.H, t0, t1, C,
+                S, z, eps);
         else
             apply_generic<float, D()><<<grid, kThreads, lds, stream>>>(
-                static_cast<const float *>(Q), static_cast<float *>(O), rope, s.st, s.H, t0, t1, C, S, z, eps);
+                static_cast<const float *>(Q), static_cast<float *>(O), rope.arg, rope.mode, s.st, s.H, t0, t1, C, S, z,
+                eps);
     });
     return launch_status();
 }
 
-// ---- bodies shared by the plain and the RoPE entry points (rope may be null) -------------------------------
+// ---- bodies shared by the plain and the RoPE entry points ------------------------------------------------------
 
-sv_status do_state(const void *K, const void *V, const sv_tensor_desc *kv, const float *rope, bool want_rope,
-                   int32_t tok_begin, int32_t tok_end, int accumulate, float *S, float *z, void *workspace,
+// What an entry point was given: nothing, a full table, or factored 3-D tables.
+struct RopeSpec {
+    int mode;
+    const float *table;
+    const sv_rope3d *r3;
+};
+constexpr RopeSpec kNoRope{kRopeNone, nullptr, nullptr};
+
+// Checks the rotation arguments against the descriptor and fills `out`.
+sv_status resolve_rope(const RopeSpec &spec, const Shape &s, Rope *out)
+{
+    out->mode = spec.mode;
+    if (spec.mode == kRopeTable) {
+        if (!spec.table) return SV_ERR_NULL;
+        if (!aligned16(spec.table)) return SV_ERR_ALIGN;
+        out->arg.table = spec.table;
+    } else if (spec.mode == kRope3D) {
+        const sv_rope3d *r = spec.r3;
+        if (!r) return SV_ERR_NULL;
+        if (r->frames <= 0 || r->rows <= 0 || r->cols <= 0 || r->n_t < 0 || r->n_h < 0 || r->n_w < 0)
+            return SV_ERR_SHAPE;
+        if ((int64_t)r->frames * r->rows * r->cols != s.N || r->n_t + r->n_h + r->n_w != s.d / 2) return SV_ERR_SHAPE;
+        if ((r->n_t > 0 && !r->cs_t) || (r->n_h > 0 && !r->cs_h) || (r->n_w > 0 && !r->cs_w)) return SV_ERR_NULL;
+        if ((reinterpret_cast<uintptr_t>(r->cs_t) | reinterpret_cast<uintptr_t>(r->cs_h) |
+             reinterpret_cast<uintptr_t>(r->cs_w)) & 7u)
+            return SV_ERR_ALIGN;
+        out->arg.r3 = Rope3D{r->cs_t, r->cs_h, r->cs_w, r->frames, r->rows, r->cols, r->n_t, r->n_h, r->n_w};
+    }
+    return SV_OK;
+}
+
+sv_status do_state(const void *K, const void *V, const sv_tensor_desc *kv, const RopeSpec &spec, int32_t tok_begin,
+                   int32_t tok_end, int accumulate, float *S, float *z, void *workspace,
                    size_t workspace_bytes_given, void *stream)
 {
-    if (!K || !V || !S || !z || !workspace || (want_rope && !rope)) return SV_ERR_NULL;
+    if (!K || !V || !S || !z || !workspace) return SV_ERR_NULL;
     Shape s;
     sv_status rc = check_desc(kv, &s);
     if (rc != SV_OK) return rc;
     if ((rc = check_range(s, tok_begin, tok_end)) != SV_OK) return rc;
-    if (!aligned16(K) || !aligned16(V) || !aligned16(S) || !aligned16(z) || !aligned16(workspace) || !aligned16(rope))
-        return SV_ERR_ALIGN;
+    Rope rope;
+    if ((rc = resolve_rope(spec, s, &rope)) != SV_OK) return rc;
+    if (!aligned16(K) || !aligned16(V) || !aligned16(S) || !aligned16(z) || !aligned16(workspace)) return SV_ERR_ALIGN;
     if (workspace_bytes_given < workspace_bytes(s.BH, s.d)) return SV_ERR_WORKSPACE;
     return enqueue_state(K, V, rope, s, tok_begin, tok_end, accumulate ? S : nullptr, z, S, z, workspace,
                          static_cast<hipStream_t>(stream));
 }
 
-sv_status do_apply(const void *Q, const sv_tensor_desc *q, const float *rope, bool want_rope, int32_t tok_begin,
-                   int32_t tok_end, const float *S, const float *z, float eps, void *O, void *stream)
+sv_status do_apply(const void *Q, const sv_tensor_desc *q, const RopeSpec &spec, int32_t tok_begin, int32_t tok_end,
+                   const float *S, const float *z, float eps, void *O, void *stream)
 {
-    if (!Q || !S || !z || !O || (want_rope && !rope)) return SV_ERR_NULL;
+    if (!Q || !S || !z || !O) return SV_ERR_NULL;
     Shape s;
     sv_status rc = check_desc(q, &s);
     if (rc != SV_OK) return rc;
     if ((rc = check_range(s, tok_begin, tok_end)) != SV_OK) return rc;
     if (!eps_ok(eps)) return SV_ERR_RANGE;
-    if (!aligned16(Q) || !aligned16(O) || !aligned16(S) || !aligned16(z) || !aligned16(rope)) return SV_ERR_ALIGN;
+    Rope rope;
+    if ((rc = resolve_rope(spec, s, &rope)) != SV_OK) return rc;
+    if (!aligned16(Q) || !aligned16(O) || !aligned16(S) || !aligned16(z)) return SV_ERR_ALIGN;
     return enqueue_apply(Q, rope, s, tok_begin, tok_end, S, z, eps, O, static_cast<hipStream_t>(stream));
 }
 
 // The committing and the look-ahead block step: the updated state goes to S_out, z_out.
-sv_status do_block_step(const void *Qb, const void *Kb, const void *Vb, const sv_tensor_desc *blk, const float *rope,
-                        bool want_rope, const float *S_in, const float *z_in, float *S_out, float *z_out,
+sv_status do_block_step(const void *Qb, const void *Kb, const void *Vb, const sv_tensor_desc *blk,
+                        const RopeSpec &spec, const float *S_in, const float *z_in, float *S_out, float *z_out,
                         bool lookahead, float eps, void *Ob, void *workspace, size_t workspace_bytes_given,
                         void *stream)
 {
-    if (!Qb || !Kb || !Vb || !S_in || !z_in || !Ob || !workspace || (want_rope && !rope)) return SV_ERR_NULL;
+    if (!Qb || !Kb || !Vb || !S_in || !z_in || !Ob || !workspace) return SV_ERR_NULL;
     Shape s;
     sv_status rc = check_desc(blk, &s);
     if (rc != SV_OK) return rc;
     if (!eps_ok(eps)) return SV_ERR_RANGE;
+    Rope rope;
+    if ((rc = resolve_rope(spec, s, &rope)) != SV_OK) return rc;
     if (!aligned16(Qb) || !aligned16(Kb) || !aligned16(Vb) || !aligned16(Ob) || !aligned16(S_in) ||
-        !aligned16(z_in) || !aligned16(workspace) || !aligned16(rope))
+        !aligned16(z_in) || !aligned16(workspace))
         return SV_ERR_ALIGN;
     if (workspace_bytes_given < workspace_bytes(s.BH, s.d)) return SV_ERR_WORKSPACE;
     if (lookahead) {                                 // the updated state lives in the workspace only
@@ -385,14 +445,14 @@ sv_status do_block_step(const void *Qb, const void *Kb, const void *Vb, const sv
         const Device &dev = device_info();
         if (!dev.ok) return SV_ERR_LAUNCH;
         bool launched = false;
-        with_mfma_kernels(s.d, rope != nullptr, [&](auto kn) {
+        with_mfma_kernels(s.d, rope.mode, [&](auto kn) {
             using KN = decltype(kn);
             // One launch when the whole grid can be resident at once (needed by the in-kernel waits).
             const int C = plan_chunks(s.BH, s.N, KN::state_wg_tokens, dev.num_cu);
-            if ((int64_t)C * s.BH > dev.fused_resident_wgs[KN::W][rope != nullptr]) return;
+            if ((int64_t)C * s.BH > dev.fused_resident_wgs[KN::W][rope.mode]) return;
             KN::fused<<<dim3(C, s.BH), 64 * kStateWaves, KN::fused_lds, hs>>>(
                 static_cast<const uint16_t *>(Qb), static_cast<const uint16_t *>(Kb),
-                static_cast<const uint16_t *>(Vb), static_cast<uint16_t *>(Ob), rope, s.st, s.H, s.d, s.N, C, S_in,
+                static_cast<const uint16_t *>(Vb), static_cast<uint16_t *>(Ob), rope.arg, s.st, s.H, s.d, s.N, C, S_in,
                 z_in, S_out, z_out, eps, workspace, next_epoch(), kSpinLimit);
             launched = true;
         });
@@ -432,21 +492,21 @@ sv_status sv_linattn_state(const void *K, const void *V, const sv_tensor_desc *k
                            int32_t tok_end, int accumulate, float *S, float *z, void *workspace,
                            size_t workspace_bytes_given, void *stream)
 {
-    return do_state(K, V, kv, nullptr, false, tok_begin, tok_end, accumulate, S, z, workspace,
+    return do_state(K, V, kv, kNoRope, tok_begin, tok_end, accumulate, S, z, workspace,
                     workspace_bytes_given, stream);
 }
 
 sv_status sv_linattn_apply(const void *Q, const sv_tensor_desc *q, int32_t tok_begin, int32_t tok_end,
                            const float *S, const float *z, float eps, void *O, void *stream)
 {
-    return do_apply(Q, q, nullptr, false, tok_begin, tok_end, S, z, eps, O, stream);
+    return do_apply(Q, q, kNoRope, tok_begin, tok_end, S, z, eps, O, stream);
 }
 
 sv_status sv_block_linattn_step(const void *Qb, const void *Kb, const void *Vb, const sv_tensor_desc *blk, float *S,
                                 float *z, float eps, void *Ob, void *workspace, size_t workspace_bytes_given,
                                 void *stream)
 {
-    return do_block_step(Qb, Kb, Vb, blk, nullptr, false, S, z, S, z, false, eps, Ob, workspace,
+    return do_block_step(Qb, Kb, Vb, blk, kNoRope, S, z, S, z, false, eps, Ob, workspace,
                          workspace_bytes_given, stream);
 }
 
@@ -454,7 +514,7 @@ sv_status sv_block_linattn_lookahead(const void *Qb, const void *Kb, const void 
                                      const float *S, const float *z, float eps, void *Ob, void *workspace,
                                      size_t workspace_bytes_given, void *stream)
 {
-    return do_block_step(Qb, Kb, Vb, blk, nullptr, false, S, z, nullptr, nullptr, true, eps, Ob, workspace,
+    return do_block_step(Qb, Kb, Vb, blk, kNoRope, S, z, nullptr, nullptr, true, eps, Ob, workspace,
                          workspace_bytes_given, stream);
 }
 
@@ -462,21 +522,21 @@ sv_status sv_linattn_state_rope(const void *K, const void *V, const sv_tensor_de
                                 int32_t tok_begin, int32_t tok_end, int accumulate, float *S, float *z,
                                 void *workspace, size_t workspace_bytes_given, void *stream)
 {
-    return do_state(K, V, kv, rope, true, tok_begin, tok_end, accumulate, S, z, workspace, workspace_bytes_given,
+    return do_state(K, V, kv, RopeSpec{kRopeTable, rope, nullptr}, tok_begin, tok_end, accumulate, S, z, workspace, workspace_bytes_given,
                     stream);
 }
 
 sv_status sv_linattn_apply_rope(const void *Q, const sv_tensor_desc *q, const float *rope, int32_t tok_begin,
                                 int32_t tok_end, const float *S, const float *z, float eps, void *O, void *stream)
 {
-    return do_apply(Q, q, rope, true, tok_begin, tok_end, S, z, eps, O, stream);
+    return do_apply(Q, q, RopeSpec{kRopeTable, rope, nullptr}, tok_begin, tok_end, S, z, eps, O, stream);
 }
 
 sv_status sv_block_linattn_step_rope(const void *Qb, const void *Kb, const void *Vb, const sv_tensor_desc *blk,
                                      const float *rope, float *S, float *z, float eps, void *Ob, void *workspace,
                                      size_t workspace_bytes_given, void *stream)
 {
-    return do_block_step(Qb, Kb, Vb, blk, rope, true, S, z, S, z, false, eps, Ob, workspace, workspace_bytes_given,
+    return do_block_step(Qb, Kb, Vb, blk, RopeSpec{kRopeTable, rope, nullptr}, S, z, S, z, false, eps, Ob, workspace, workspace_bytes_given,
                          stream);
 }
 
@@ -484,8 +544,39 @@ sv_status sv_block_linattn_lookahead_rope(const void *Qb, const void *Kb, const 
                                           const float *rope, const float *S, const float *z, float eps, void *Ob,
                                           void *workspace, size_t workspace_bytes_given, void *stream)
 {
-    return do_block_step(Qb, Kb, Vb, blk, rope, true, S, z, nullptr, nullptr, true, eps, Ob, workspace,
+    return do_block_step(Qb, Kb, Vb, blk, RopeSpec{kRopeTable, rope, nullptr}, S, z, nullptr, nullptr, true, eps, Ob, workspace,
                          workspace_bytes_given, stream);
+}
+
+sv_status sv_linattn_state_rope3d(const void *K, const void *V, const sv_tensor_desc *kv, const sv_rope3d *rope,
+                                  int32_t tok_begin, int32_t tok_end, int accumulate, float *S, float *z,
+                                  void *workspace, size_t workspace_bytes_given, void *stream)
+{
+    return do_state(K, V, kv, RopeSpec{kRope3D, nullptr, rope}, tok_begin, tok_end, accumulate, S, z, workspace,
+                    workspace_bytes_given, stream);
+}
+
+sv_status sv_linattn_apply_rope3d(const void *Q, const sv_tensor_desc *q, const sv_rope3d *rope, int32_t tok_begin,
+                                  int32_t tok_end, const float *S, const float *z, float eps, void *O, void *stream)
+{
+    return do_apply(Q, q, RopeSpec{kRope3D, nullptr, rope}, tok_begin, tok_end, S, z, eps, O, stream);
+}
+
+sv_status sv_block_linattn_step_rope3d(const void *Qb, const void *Kb, const void *Vb, const sv_tensor_desc *blk,
+                                       const sv_rope3d *rope, float *S, float *z, float eps, void *Ob, void *workspace,
+                                       size_t workspace_bytes_given, void *stream)
+{
+    return do_block_step(Qb, Kb, Vb, blk, RopeSpec{kRope3D, nullptr, rope}, S, z, S, z, false, eps, Ob, workspace,
+                         workspace_bytes_given, stream);
+}
+
+sv_status sv_block_linattn_lookahead_rope3d(const void *Qb, const void *Kb, const void *Vb,
+                                            const sv_tensor_desc *blk, const sv_rope3d *rope, const float *S,
+                                            const float *z, float eps, void *Ob, void *workspace,
+                                            size_t workspace_bytes_given, void *stream)
+{
+    return do_block_step(Qb, Kb, Vb, blk, RopeSpec{kRope3D, nullptr, rope}, S, z, nullptr, nullptr, true, eps, Ob,
+                         workspace, workspace_bytes_given, stream);
 }
 
 const char *sv_status_string(int status)

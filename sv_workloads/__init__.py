@@ -19,7 +19,8 @@ import numpy as np
 
 __all__ = [
     "Workload", "WORKLOADS", "workload", "draw_qkv", "draw_block",
-    "draw_tensors", "f32_to_bf16_bits", "bf16_bits_to_f32", "as_f32", "rope_table_3d",
+    "draw_tensors", "f32_to_bf16_bits", "bf16_bits_to_f32", "as_f32", "rope_table_3d", "rope_tables_3d_factored",
+    "expand_rope_tables",
 ]
 
 
@@ -185,3 +186,27 @@ def rope_table_3d(frames: int, rows: int, cols: int, d: int, base: float = 10000
         ang[..., n_t + n_hw + i] = c * base ** (-i / n_hw)
     ang = ang.reshape(frames * rows * cols, half)
     return np.stack([np.cos(ang), np.sin(ang)], axis=-1).astype(np.float32)
+
+
+def rope_tables_3d_factored(frames: int, rows: int, cols: int, d: int, base: float = 10000.0, t0: int = 0):
+    """The same 3-D rotary embedding as `rope_table_3d`, as the three per-axis tables it
+    is made of: (cs_t [frames][n_t][2], cs_h [rows][n_h][2], cs_w [cols][n_w][2]) in fp32,
+    pairs ordered frame, row, column."""
+    half = d // 2
+    n_hw = (3 * half) // 8
+    n_t = half - 2 * n_hw
+
+    def axis(pos, n):
+        ang = pos[:, None].astype(np.float64) * base ** (-np.arange(n, dtype=np.float64) / max(n, 1))[None, :]
+        return np.stack([np.cos(ang), np.sin(ang)], axis=-1).astype(np.float32)
+
+    return (axis(np.arange(t0, t0 + frames), n_t), axis(np.arange(rows), n_hw), axis(np.arange(cols), n_hw))
+
+
+def expand_rope_tables(cs_t: np.ndarray, cs_h: np.ndarray, cs_w: np.ndarray) -> np.ndarray:
+    """Full table [frames*rows*cols][n_t+n_h+n_w][2] of factored tables (tokens frame-major, then
+    row, then column): pure indexing, no arithmetic."""
+    frames, rows, cols = cs_t.shape[0], cs_h.shape[0], cs_w.shape[0]
+    f, r, c = np.meshgrid(np.arange(frames), np.arange(rows), np.arange(cols), indexing="ij")
+    full = np.concatenate([cs_t[f.ravel()], cs_h[r.ravel()], cs_w[c.ravel()]], axis=1)
+    return np.ascontiguousarray(full, dtype=np.float32)

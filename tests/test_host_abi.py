@@ -143,3 +143,30 @@ def test_workspace_init_checks_arguments():
     with pytest.raises(sv.SvError) as e:
         sv.sv_linattn_workspace_init(FAKE + 8, 1, 2, 64, workspace_bytes=big)
     assert e.value.status == 4
+
+
+def test_rope3d_entry_points_check_arguments():
+    d = _desc()                                  # N tokens, d features as in the other tests
+    big = 1 << 30
+    N, dim = d.N, d.d
+
+    def rope(frames=1, rows=1, cols=N, n_t=0, n_h=0, n_w=dim // 2, cs_t=None, cs_h=None, cs_w=FAKE):
+        return sv.Rope3D(frames, rows, cols, n_t, n_h, n_w, cs_t, cs_h, cs_w)
+
+    with pytest.raises(sv.SvError) as e:          # descriptor of the tables is required
+        sv.sv_linattn_state_rope3d(FAKE, FAKE, d, None, 0, 1, 0, FAKE, FAKE, FAKE, workspace_bytes=big)
+    assert e.value.status == 1
+    with pytest.raises(sv.SvError) as e:          # frames*rows*cols must be N
+        sv.sv_linattn_apply_rope3d(FAKE, d, rope(cols=N + 1), 0, 1, FAKE, FAKE, 1e-6, FAKE)
+    assert e.value.status == 2
+    with pytest.raises(sv.SvError) as e:          # pairs must add up to d/2
+        sv.sv_linattn_apply_rope3d(FAKE, d, rope(n_w=dim // 2 - 1), 0, 1, FAKE, FAKE, 1e-6, FAKE)
+    assert e.value.status == 2
+    with pytest.raises(sv.SvError) as e:          # an axis with pairs needs its table
+        sv.sv_block_linattn_step_rope3d(FAKE, FAKE, FAKE, d, rope(cs_w=None), FAKE, FAKE, 1e-6, FAKE, FAKE,
+                                        workspace_bytes=big)
+    assert e.value.status == 1
+    with pytest.raises(sv.SvError) as e:          # 8-byte alignment of the tables
+        sv.sv_block_linattn_lookahead_rope3d(FAKE, FAKE, FAKE, d, rope(cs_w=FAKE + 4), FAKE, FAKE, 1e-6, FAKE, FAKE,
+                                             workspace_bytes=big)
+    assert e.value.status == 4

@@ -123,3 +123,16 @@ def test_3d_table_generator():
     assert (r1[:n_t, 1] == 0).all() and (r1[n_t:n_t + n_hw, 1] != 0).all() and (r1[n_t + n_hw:, 1] == 0).all()
     # blocks of a stream continue the time axis
     assert np.array_equal(wl.rope_table_3d(2, 4, 5, 64, t0=1), T[20:])
+
+
+def test_factored_tables_expand_to_the_full_table():
+    """The per-axis tables and the full table come from two separate generators; expanding the
+    former by pure indexing must reproduce the latter bit for bit (this is what lets the GPU's
+    factored-table entry points be checked against the oracle's full-table form)."""
+    for (fr, ro, co, d, t0) in [(3, 5, 7, 64, 0), (2, 4, 3, 32, 5), (3, 6, 9, 112, 3), (1, 1, 1, 64, 0)]:
+        cs_t, cs_h, cs_w = wl.rope_tables_3d_factored(fr, ro, co, d, t0=t0)
+        assert cs_t.shape[1] + cs_h.shape[1] + cs_w.shape[1] == d // 2
+        full = wl.expand_rope_tables(cs_t, cs_h, cs_w)
+        ref = wl.rope_table_3d(fr, ro, co, d, t0=t0)
+        assert full.shape == ref.shape and full.dtype == np.float32
+        assert np.array_equal(full, ref)
