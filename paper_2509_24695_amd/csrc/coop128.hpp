@@ -89,6 +89,12 @@ template <int ROPE> __host__ __device__ constexpr int coop_state_lds_bytes() { r
 // Accumulates quadrant (kb, vb) of the workgroup's partial state over the
 // workgroup's tiles.  Must be called by all four waves (it contains barriers; the
 // tile count is the same in all of them).  Key sums are kept by the waves with vb == 0.
+//
+// Software pipeline, one barrier per tile: while the matrix cores work on tile i
+// (operands from LDS buffer i%2), the wave's vector ALU puts its rows of tile
+// i+1 (ReLU, rotation) into the other buffer; the barrier at the end of the step
+// says both that tile i+1 is complete and that everybody is done reading tile i,
+// whose buffer the next step overwrites.
 template <int DEPTH, int ROPE>
 __device__ __forceinline__ void state_accumulate_coop(CoopStateStream<DEPTH, ROPE> &st, unsigned char *lds, int wave,
                                                       int lane, int kb, int vb, StateAcc &acc)
@@ -98,35 +104,40 @@ __device__ __forceinline__ void state_accumulate_coop(CoopStateStream<DEPTH, ROP
     const uint32_t one2 = 0x3f803f80u;   // bf16 (1.0, 1.0)
     const u32x4 ones4 = {one2, one2, one2, one2};
     const bf16x8 ones = __builtin_bit_cast(bf16x8, ones4);
+    const int count = st.walk.count;
+    if (count == 0) return;
 
-    for (int i0 = 0; i0 < st.walk.count; i0 += DEPTH) {
+    // This wave's rows of the workgroup's i-th tile go from stage s into LDS buffer s%2; the stage
+    // is refilled DEPTH tiles ahead whether or not tile i exists (out of range nothing is read).
+    auto prepare = [&](int s, int i) __attribute__((always_inline)) {
+        unsigned char *bufK = lds + (s & 1) * kCoopTile, *bufV = lds + (2 + (s & 1)) * kCoopTile;
+        unsigned char *bufP = lds + (4 + (s & 1)) * kCoopTile;   // un-rotated phi(K), ROPE only
+        if (i < count) {
+            st.rot.begin_tile(st.walk.template token<32>(i));
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const u32x4 kk = relu_bf16x8(st.k[s][j]);
+                if (ROPE) {
+                    *reinterpret_cast<u32x4 *>(bufP + wr_off + 4 * j * kCoopRow) = kk;
+                    *reinterpret_cast<u32x4 *>(bufK + wr_off + 4 * j * kCoopRow) = st.rot.rotate(s, j, kk);
+                } else {
+                    *reinterpret_cast<u32x4 *>(bufK + wr_off + 4 * j * kCoopRow) = kk;
+                }
+                *reinterpret_cast<u32x4 *>(bufV + wr_off + 4 * j * kCoopRow) = st.v[s][j];
+            }
+        }
+        st.request(s, i + DEPTH);
+    };
+
+    prepare(0, 0);
+    lds_barrier();
+    for (int i0 = 0; i0 < count; i0 += DEPTH) {
 #pragma unroll
         for (int s = 0; s < DEPTH; ++s) {
             __builtin_amdgcn_sched_barrier(0);   // stages stay in program order
-            const bool valid = i0 + s < st.walk.count;
-            unsigned char *bufK = lds + (s & 1) * kCoopTile, *bufV = lds + (2 + (s & 1)) * kCoopTile;
-            unsigned char *bufP = ROPE ? lds + (4 + (s & 1)) * kCoopTile : bufK;   // un-rotated phi(K)
-            if (valid) {
-                st.rot.begin_tile(st.walk.template token<32>(i0 + s));
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    const u32x4 kk = relu_bf16x8(st.k[s][j]);
-                    if (ROPE) {
-                        *reinterpret_cast<u32x4 *>(bufP + wr_off + 4 * j * kCoopRow) = kk;
-                        *reinterpret_cast<u32x4 *>(bufK + wr_off + 4 * j * kCoopRow) = st.rot.rotate(s, j, kk);
-                    } else {
-                        *reinterpret_cast<u32x4 *>(bufK + wr_off + 4 * j * kCoopRow) = kk;
-                    }
-                    *reinterpret_cast<u32x4 *>(bufV + wr_off + 4 * j * kCoopRow) = st.v[s][j];
-                }
-            }
-            st.request(s, i0 + s + DEPTH);   // refill this stage: DEPTH tiles ahead
-            __builtin_amdgcn_sched_barrier(0);
-            if (valid) {
-                // The tile is complete after this barrier.  Its buffer is written again two tiles
-                // later, by waves that have passed the next tile's barrier, which every wave
-                // reaches only after it is done reading this one.
-                lds_barrier();
+            if (i0 + s < count) {
+                const unsigned char *bufK = lds + (s & 1) * kCoopTile, *bufV = lds + (2 + (s & 1)) * kCoopTile;
+                const unsigned char *bufP = ROPE ? lds + (4 + (s & 1)) * kCoopTile : bufK;
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
                     const bf16x8 a0 = lds_tr_operand<kCoopRow>(bufK, 16 * ks, 64 * kb, lane);
@@ -145,6 +156,9 @@ __device__ __forceinline__ void state_accumulate_coop(CoopStateStream<DEPTH, ROP
                     }
                 }
             }
+            prepare((s + 1) % DEPTH, i0 + s + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            if (i0 + s < count) lds_barrier();
         }
     }
 }
