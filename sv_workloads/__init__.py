@@ -1,4 +1,5 @@
-"""Seeded synthetic inputs for ReLU linear attention over video token sequences.
+"""Seeded synthetic inputs for ReLU linear attention (and the Mix-FFN's temporal
+convolution) over video token sequences.
 
 This module serves both the CPU oracle's tests and the HIP path's tests and
 benchmarks.  It holds no arithmetic of the method itself: only the workload
@@ -20,7 +21,7 @@ import numpy as np
 __all__ = [
     "Workload", "WORKLOADS", "workload", "draw_qkv", "draw_block",
     "draw_tensors", "f32_to_bf16_bits", "bf16_bits_to_f32", "as_f32", "rope_table_3d", "rope_tables_3d_factored",
-    "expand_rope_tables",
+    "expand_rope_tables", "TconvWorkload", "TCONV_WORKLOADS", "draw_tconv",
 ]
 
 
@@ -210,3 +211,51 @@ def expand_rope_tables(cs_t: np.ndarray, cs_h: np.ndarray, cs_w: np.ndarray) -> 
     f, r, c = np.meshgrid(np.arange(frames), np.arange(rows), np.arange(cols), indexing="ij")
     full = np.concatenate([cs_t[f.ravel()], cs_h[r.ravel()], cs_w[c.ravel()]], axis=1)
     return np.ascontiguousarray(full, dtype=np.float32)
+
+
+@dataclass(frozen=True)
+class TconvWorkload:
+    """Shape of one temporal-convolution configuration (Mix-FFN, Sec. 3.2 and 3.3.1):
+    `n_blocks` consecutive blocks of T latent frames of HW tokens with D channels
+    (`n_blocks == 1`: the whole clip at once, as in the bidirectional model)."""
+    name: str
+    B: int
+    T: int          # latent frames per block
+    HW: int         # tokens per frame
+    D: int          # channels (hidden size of the model)
+    seed: int
+    n_blocks: int = 1
+
+    @property
+    def tokens(self) -> int:
+        return self.B * self.T * self.HW
+
+    @property
+    def algorithmic_flops(self) -> int:
+        """Three D x D taps per token, multiply and add (per block)."""
+        return 2 * 3 * self.D * self.D * self.tokens
+
+    @property
+    def algorithmic_bytes(self) -> int:
+        """Input read once, output written once, weights read once, cache in and out (per block)."""
+        return 2 * (2 * self.tokens * self.D + 3 * self.D * self.D + 2 * self.B * self.HW * self.D)
+
+
+TCONV_WORKLOADS = {
+    # several tiles with ragged tails in tokens, channels and frames
+    "tconv_tiny": TconvWorkload("tconv_tiny", B=2, T=5, HW=53, D=328, seed=2001, n_blocks=3),
+    # the 2B model's hidden size (20 heads x 112) on the 480p token grid, whole clip
+    "tconv_480p": TconvWorkload("tconv_480p", B=1, T=21, HW=30 * 52, D=2240, seed=2002),
+    # the same in blocks of 3 latent frames
+    "tconv_block_480p": TconvWorkload("tconv_block_480p", B=1, T=3, HW=30 * 52, D=2240, seed=2003, n_blocks=7),
+}
+
+
+def draw_tconv(w: TconvWorkload):
+    """x [B][n_blocks*T][HW][D] and W [3][D][D] (tap, out, in) as bf16 bit patterns: x ~ N(0, 1)
+    from PCG64(seed), W ~ N(0, 1 / (3 D)) from PCG64(seed + 7919), so that the convolution output
+    has about the input's variance (block m is frames [m*T, (m+1)*T))."""
+    x, = draw_tensors(w.seed, (w.B, w.n_blocks * w.T, w.HW, w.D), 1.0, "bf16", count=1)
+    rng = np.random.Generator(np.random.PCG64(w.seed + 7919))
+    wt = rng.standard_normal(size=(3, w.D, w.D), dtype=np.float32) * np.float32(1.0 / np.sqrt(3.0 * w.D))
+    return x, f32_to_bf16_bits(wt)
