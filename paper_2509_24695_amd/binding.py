@@ -1,7 +1,7 @@
 """ctypes binding of libsvlinattn.so: argument marshalling only.
 
 The functions carry the names and argument order of the C ABI
-(include/sv_linattn.h).  Device buffers are torch tensors (or raw integer
+(include/sv_linattn.h, include/sv_tconv.h).  Device buffers are torch tensors (or raw integer
 device addresses); nothing here computes, and there is no fallback: if the
 shared library is missing, loading raises.
 """
@@ -19,7 +19,7 @@ EXPORTS = (
     "sv_linattn_state_rope", "sv_linattn_apply_rope", "sv_block_linattn_step_rope",
     "sv_block_linattn_lookahead_rope", "sv_linattn_workspace_init",
     "sv_linattn_state_rope3d", "sv_linattn_apply_rope3d", "sv_block_linattn_step_rope3d",
-    "sv_block_linattn_lookahead_rope3d",
+    "sv_block_linattn_lookahead_rope3d", "sv_tconv_block_step",
 )
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
@@ -96,6 +96,8 @@ def load_library():
     for f in (lib.sv_linattn_state_rope3d, lib.sv_linattn_apply_rope3d, lib.sv_block_linattn_step_rope3d,
               lib.sv_block_linattn_lookahead_rope3d):
         f.restype = ctypes.c_int
+    lib.sv_tconv_block_step.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp]
+    lib.sv_tconv_block_step.restype = ctypes.c_int
     lib.sv_linattn_workspace_init.argtypes = [vp, sz, i32, i32, i32, vp]
     lib.sv_linattn_workspace_init.restype = ctypes.c_int
     lib.sv_status_string.argtypes = [ctypes.c_int]
@@ -302,3 +304,13 @@ def sv_block_linattn_lookahead_rope3d(Qb, Kb, Vb, blk: TensorDesc, rope: Rope3D,
                                       workspace_bytes: int | None = None, stream=None) -> None:
     _block_rope3d("sv_block_linattn_lookahead_rope3d", Qb, Kb, Vb, blk, rope, S, z, eps, Ob, workspace,
                   workspace_bytes, stream)
+
+
+def sv_tconv_block_step(x, W, cache_in, y, cache_out, B: int, T: int, HW: int, D: int, dtype: int = SV_BF16,
+                        stream=None) -> None:
+    """One block through the Mix-FFN's temporal convolution with shortcut (include/sv_tconv.h):
+    x, y [B][T][HW][D], W [3][D][D], cache_in / cache_out [B][HW][D] or None."""
+    rc = load_library().sv_tconv_block_step(_ptr(x), _ptr(W), _ptr(cache_in), _ptr(y), _ptr(cache_out), B, T, HW, D,
+                                            dtype, _stream(stream))
+    if rc != 0:
+        raise SvError(rc, "sv_tconv_block_step")

@@ -1,0 +1,73 @@
+// C ABI of the temporal convolution (include/sv_tconv.h): argument checks and launches.
+#include "../../include/sv_tconv.h"
+
+#include "tconv_mfma.hpp"
+
+namespace {
+
+using namespace sv;
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool overlaps(const void *a, size_t na, const void *b, size_t nb)
+{
+    const auto pa = reinterpret_cast<uintptr_t>(a), pb = reinterpret_cast<uintptr_t>(b);
+    return pa < pb + nb && pb < pa + na;
+}
+
+// The tile kernel needs its 128 KB of dynamic LDS allowed once per device.
+bool tconv_kernel_ready()
+{
+    static bool ready[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return false;
+    if (!ready[dev]) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(tconv_mfma), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                kTcLdsBytes) != hipSuccess)
+            return false;
+        ready[dev] = true;
+    }
+    return true;
+}
+
+}  // namespace
+
+extern "C" sv_status sv_tconv_block_step(const void *x, const void *W, const void *cache_in, void *y, void *cache_out,
+                                         int32_t B, int32_t T, int32_t HW, int32_t D, int32_t dtype, void *stream)
+{
+    if (!x || !W || !y) return SV_ERR_NULL;
+    if (B <= 0 || T <= 0 || HW <= 0 || D <= 0) return SV_ERR_SHAPE;
+    if (dtype != SV_BF16) return SV_ERR_UNSUPPORTED;
+    if (D % 8 != 0) return SV_ERR_UNSUPPORTED;
+    const int64_t M = (int64_t)B * T * HW;
+    if (M >= (int64_t)1 << 31 || (int64_t)3 * D * D >= (int64_t)1 << 31) return SV_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(W) || !aligned16(y) || !aligned16(cache_in) || !aligned16(cache_out))
+        return SV_ERR_ALIGN;
+    const size_t tok_bytes = (size_t)M * D * 2, w_bytes = (size_t)3 * D * D * 2, cache_bytes = (size_t)B * HW * D * 2;
+    if (overlaps(y, tok_bytes, x, tok_bytes) || overlaps(y, tok_bytes, W, w_bytes) ||
+        (cache_in && overlaps(y, tok_bytes, cache_in, cache_bytes)))
+        return SV_ERR_SHAPE;
+    if (!tconv_kernel_ready()) return SV_ERR_LAUNCH;
+
+    TconvArgs a;
+    a.x = static_cast<const uint16_t *>(x);
+    a.W = static_cast<const uint16_t *>(W);
+    a.cache = static_cast<const uint16_t *>(cache_in);
+    a.y = static_cast<uint16_t *>(y);
+    a.B = B; a.T = T; a.HW = HW; a.D = D;
+    a.tiles_m = (int)((M + kTcBM - 1) / kTcBM);
+    a.tiles_n = (D + kTcBN - 1) / kTcBN;
+    a.groups = (a.tiles_m + kTcGroupM - 1) / kTcGroupM;
+    const int64_t wgs = (int64_t)8 * ((a.groups + 7) / 8) * kTcGroupM * a.tiles_n;
+    if (wgs >= (int64_t)1 << 31) return SV_ERR_SHAPE;
+    auto hs = static_cast<hipStream_t>(stream);
+    tconv_mfma<<<dim3((unsigned)wgs), kThreads, kTcLdsBytes, hs>>>(a);
+    if (hipGetLastError() != hipSuccess) return SV_ERR_LAUNCH;
+    if (cache_out) {
+        const int64_t vecs = (int64_t)B * HW * D / 8;
+        const int blocks = (int)((vecs + kThreads - 1) / kThreads < 2048 ? (vecs + kThreads - 1) / kThreads : 2048);
+        tconv_cache_store<<<blocks, kThreads, 0, hs>>>(a.x, static_cast<uint16_t *>(cache_out), B, T, HW, D);
+        if (hipGetLastError() != hipSuccess) return SV_ERR_LAUNCH;
+    }
+    return SV_OK;
+}

@@ -13,7 +13,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared_symbols():
-    text = open(os.path.join(ROOT, "include", "sv_linattn.h")).read()
+    text = "".join(open(os.path.join(ROOT, "include", h)).read() for h in sorted(os.listdir(os.path.join(ROOT, "include")))
+                   if h.endswith(".h"))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(sv_[a-z_0-9]+)\s*\(", text)))
 
@@ -170,3 +171,22 @@ def test_rope3d_entry_points_check_arguments():
         sv.sv_block_linattn_lookahead_rope3d(FAKE, FAKE, FAKE, d, rope(cs_w=FAKE + 4), FAKE, FAKE, 1e-6, FAKE, FAKE,
                                              workspace_bytes=big)
     assert e.value.status == 4
+
+
+def test_tconv_checks_arguments():
+    def call(x=FAKE, W=FAKE + (1 << 28), cache_in=None, y=FAKE + (1 << 29), cache_out=None, B=1, T=3, HW=100, D=64,
+             dtype=sv.SV_BF16):
+        with pytest.raises(sv.SvError) as e:
+            sv.sv_tconv_block_step(x, W, cache_in, y, cache_out, B, T, HW, D, dtype)
+        return e.value.status
+
+    assert call(x=None) == 1 and call(W=None) == 1 and call(y=None) == 1
+    assert call(B=0) == 2 and call(T=0) == 2 and call(HW=-1) == 2 and call(D=0) == 2
+    assert call(dtype=sv.SV_F32) == 3
+    assert call(D=60) == 3                                  # not a multiple of 8
+    assert call(B=1 << 12, T=1 << 10, HW=1 << 10) == 2      # 2^32 token rows
+    assert call(D=1 << 15) == 2                             # 3 * D * D does not fit
+    assert call(x=FAKE + 8) == 4 and call(cache_in=FAKE + (1 << 27) + 4) == 4 and call(cache_out=FAKE + 2) == 4
+    assert call(y=FAKE) == 2                                # y on top of x
+    assert call(y=FAKE + 64) == 2                           # y inside x
+    assert call(cache_in=FAKE + (1 << 29) + 1024) == 2      # cache_in inside y
