@@ -31,12 +31,6 @@ namespace sv {
 constexpr int kCoopRow = 128 * 2 + 16;           // LDS row: 128 bf16 features + padding
 constexpr int kCoopTile = 32 * kCoopRow;         // one 32-token tile in LDS
 
-// All LDS traffic of this wave is done, then all waves of the workgroup meet.
-// Global memory traffic is not waited for.
-__device__ __forceinline__ void lds_barrier() {
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
-
 // ---- state ---------------------------------------------------------------------------------------
 
 // One wave's share of the workgroup's K/V stream: rows 8*wave .. +8 of every tile

@@ -22,8 +22,10 @@ bool tconv_kernel_ready()
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return false;
     if (!ready[dev]) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(tconv_mfma), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                kTcLdsBytes) != hipSuccess)
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(tconv_mfma<false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kTcLdsBytes) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void *>(tconv_mfma<true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kTcLdsBytes) != hipSuccess)
             return false;
         ready[dev] = true;
     }
@@ -40,7 +42,7 @@ extern "C" sv_status sv_tconv_block_step(const void *x, const void *W, const voi
     if (dtype != SV_BF16) return SV_ERR_UNSUPPORTED;
     if (D % 8 != 0) return SV_ERR_UNSUPPORTED;
     const int64_t M = (int64_t)B * T * HW;
-    if (M >= (int64_t)1 << 31 || (int64_t)3 * D * D >= (int64_t)1 << 31) return SV_ERR_SHAPE;
+    if (M >= (int64_t)1 << 31 || (int64_t)3 * D * D >= (int64_t)1 << 31 || D > kTcMaxD) return SV_ERR_SHAPE;
     if (!aligned16(x) || !aligned16(W) || !aligned16(y) || !aligned16(cache_in) || !aligned16(cache_out))
         return SV_ERR_ALIGN;
     const size_t tok_bytes = (size_t)M * D * 2, w_bytes = (size_t)3 * D * D * 2, cache_bytes = (size_t)B * HW * D * 2;
@@ -57,11 +59,12 @@ extern "C" sv_status sv_tconv_block_step(const void *x, const void *W, const voi
     a.B = B; a.T = T; a.HW = HW; a.D = D;
     a.tiles_m = (int)((M + kTcBM - 1) / kTcBM);
     a.tiles_n = (D + kTcBN - 1) / kTcBN;
-    a.groups = (a.tiles_m + kTcGroupM - 1) / kTcGroupM;
-    const int64_t wgs = (int64_t)8 * ((a.groups + 7) / 8) * kTcGroupM * a.tiles_n;
+    const int64_t tiles = (int64_t)a.tiles_m * a.tiles_n, wgs = 8 * ((tiles + 7) / 8);
     if (wgs >= (int64_t)1 << 31) return SV_ERR_SHAPE;
+    a.tiles = (int)tiles;
     auto hs = static_cast<hipStream_t>(stream);
-    tconv_mfma<<<dim3((unsigned)wgs), kThreads, kTcLdsBytes, hs>>>(a);
+    if (D % kTcBK == 0) tconv_mfma<false><<<dim3((unsigned)wgs), kThreads, kTcLdsBytes, hs>>>(a);
+    else tconv_mfma<true><<<dim3((unsigned)wgs), kThreads, kTcLdsBytes, hs>>>(a);
     if (hipGetLastError() != hipSuccess) return SV_ERR_LAUNCH;
     if (cache_out) {
         const int64_t vecs = (int64_t)B * HW * D / 8;

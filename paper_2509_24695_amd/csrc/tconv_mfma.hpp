@@ -7,132 +7,154 @@
 // of the same position in frame t + tap - 1: a row of x, the cached last frame of the previous
 // block for frame -1 (zeros without a cache), zeros for frame T.  So the A operand of the GEMM
 // is x read three times with its rows shifted by -HW, 0, +HW tokens, the contraction runs over
-// 3*D, and nothing is materialised.
+// 3*D, and nothing is materialised.  Rows that are zero (frame -1 without a cache, frame T,
+// token and channel tails, the K tail when D is not a multiple of the K-step) are read from a
+// row of zeros in device memory, so the loader has no special cases.
 //
-// Tiling: a workgroup of four waves owns a 256-token x 256-channel tile of y; wave (wm, wn) owns
-// a 128 x 128 quadrant as 4 x 4 accumulators of v_mfma_f32_32x32x16_bf16.  Both operands are
-// K-contiguous ([token][channel] and [out][in]), so a K-step of 64 is a [256][64] bf16 tile of
-// each (32 KB + 32 KB), double-buffered in LDS: global loads of step s+1 are issued before the
-// products of step s and land in registers meanwhile, then go to the other LDS buffer, one
-// barrier per step.  LDS rows are 128 bytes; the 16-byte chunk c of row r sits at chunk slot
-// c ^ f(r), f(r) = 4*(r&1) ^ ((r>>1)&7), which spreads the 16-byte reads of consecutive rows
-// (one matrix operand: 32 rows, one chunk column) over all banks and keeps the writes of a
-// wave (8 rows x 8 chunks) contiguous.
+// Tiling: a workgroup of four waves (one per SIMD) owns a 256-token x 256-channel tile of y; wave
+// (wm, wn) owns a 128 x 128 quadrant as 4 x 4 accumulators of v_mfma_f32_32x32x16_bf16.  Both
+// operands are K-contiguous ([token][channel] and [out][in]), so a K-step of 32 is a [256][32]
+// bf16 tile of each (16 KB + 16 KB), and LDS holds a ring of four such stages.
+//
+// Pipeline: operand tiles go from global memory straight into LDS (global_load_lds_dwordx4: a
+// wave's 64 lanes fill 1 KB of consecutive LDS, no staging registers, completion counted by
+// vmcnt).  With one wave per SIMD nothing but the wave itself can fill the time the matrix core
+// works, so every memory instruction sits between two MFMAs.  Step s (stage s & 3):
+//   first half   16 MFMAs on operand registers of K-chunk 0; reads K-chunk 1 of stage s
+//   barrier      after waiting for this wave's loads of step s+1 and its own LDS reads
+//   second half  16 MFMAs on K-chunk 1; reads K-chunk 0 of stage s+1; requests step s+4 into
+//                stage s (every wave has read it: the barrier has passed)
+// so a tile is requested three and a half steps before its first use.  Steps past the end
+// repeat the last one into stages nobody reads: the loop body has no conditions.
+//
+// LDS rows are 64 bytes; the 16-byte chunk c of row r sits at chunk slot c ^ f(r),
+// f(r) = ((r>>1)&3) ^ ((r>>3)&1), which spreads the 16-byte reads of consecutive rows (one matrix
+// operand: 32 rows, one chunk column) over all banks whether the hardware serves 8 or 16 lanes
+// per cycle; the lane that fills slot (r, c') therefore loads chunk c' ^ f(r) of row r.
 #pragma once
 
 #include "common.hpp"
 
 namespace sv {
 
-constexpr int kTcBM = 256, kTcBN = 256, kTcBK = 64;
+constexpr int kTcBM = 256, kTcBN = 256, kTcBK = 32;
 constexpr int kTcTileBytes = kTcBM * kTcBK * 2;               // one operand tile of one K-step
 constexpr int kTcStageBytes = 2 * kTcTileBytes;               // A and B
-constexpr int kTcLdsBytes = 2 * kTcStageBytes;                // double-buffered
-constexpr int kTcGroupM = 4;                                  // token tiles per XCD group
+constexpr int kTcStages = 4;
+constexpr int kTcLdsBytes = kTcStages * kTcStageBytes;
+constexpr int kTcGroupM = 4;                                  // token tiles per group of the tile order
 constexpr int kTcEpiPitch = 128 * 4 + 32;                     // fp32 row of a wave's quadrant in the epilogue
+constexpr int kTcMaxD = 32768;                                // length of the row of zeros
+static_assert(4 * 32 * kTcEpiPitch <= kTcLdsBytes, "epilogue staging fits in the operand ring");
+
+// A row of zeros for operand rows that do not exist.  Never written.
+static __device__ __align__(16) uint16_t tc_zero_row[kTcMaxD];
 
 struct TconvArgs {
     const uint16_t *x, *W, *cache;     // cache may be null
     uint16_t *y;
     int B, T, HW, D;
-    int tiles_m, tiles_n, groups;      // token tiles, channel tiles, ceil(tiles_m / kTcGroupM)
+    int tiles_m, tiles_n, tiles;       // token tiles, channel tiles, their product
 };
 
-__device__ __forceinline__ uint32_t tc_swizzle(int r) { return (uint32_t)(((r & 1) << 2) ^ ((r >> 1) & 7)); }
+__device__ __forceinline__ uint32_t tc_swizzle(int r) { return (uint32_t)(((r >> 1) & 3) ^ ((r >> 3) & 1)); }
 
-// Workgroup id -> tile.  Consecutive workgroup ids go to the eight XCDs in turn, each with its own
-// L2: XCD e takes the groups e, e+8, ... of kTcGroupM token tiles and walks a group channel tile
-// first, so the workgroups that run on one XCD at a time share a few token tiles and all of W's
-// current K-slice.
+// Workgroup id -> tile.  Tiles are ordered in groups of kTcGroupM token tiles, token tile
+// fastest inside a group; consecutive workgroup ids go to the eight XCDs in turn, each with its
+// own L2, so XCD e takes the e-th eighth of that order: the workgroups that run on one XCD at a
+// time share a few token tiles and W's current K-slice, and all XCDs get the same number of
+// tiles (to within one) however few there are.
 __device__ __forceinline__ bool tc_tile_of(const TconvArgs &a, int wg, int &tm, int &tn)
 {
     const int xcd = wg & 7, seq = wg >> 3;
-    const int per_group = kTcGroupM * a.tiles_n;
-    const int g = (seq / per_group) * 8 + xcd, in = seq % per_group;
-    tm = g * kTcGroupM + in / a.tiles_n;
-    tn = in % a.tiles_n;
-    return g < a.groups && tm < a.tiles_m;
+    const int begin = (int)(((int64_t)xcd * a.tiles) >> 3), end = (int)(((int64_t)(xcd + 1) * a.tiles) >> 3);
+    const int t = begin + seq;
+    if (t >= end) return false;
+    const int per_group = kTcGroupM * a.tiles_n, g = t / per_group, in = t - g * per_group;
+    const int rows = min(kTcGroupM, a.tiles_m - g * kTcGroupM);      // token tiles in this (maybe last) group
+    tn = in / rows;
+    tm = g * kTcGroupM + (in - tn * rows);
+    return true;
 }
 
+// 16 bytes per lane from global memory to LDS: lane l of the wave writes lds_wave_base + 16 l.
+__device__ __forceinline__ void tc_load_to_lds(const uint16_t *src, unsigned char *lds_wave_base)
+{
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                     (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
+}
+
+// KTAIL: D is not a multiple of the K-step, the last K-step of a tap has chunks past the row end.
+template <bool KTAIL>
 __global__ __launch_bounds__(kThreads) void tconv_mfma(TconvArgs a)
 {
     extern __shared__ __align__(16) unsigned char lds[];
     int tm, tn;
     if (!tc_tile_of(a, (int)blockIdx.x, tm, tn)) return;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave & 1, wn = wave >> 1;
     const int M = a.B * a.T * a.HW, D = a.D;
     const int m0 = tm * kTcBM, n0 = tn * kTcBN;
     const int KC = (D + kTcBK - 1) / kTcBK, steps = 3 * KC;
 
-    // ---- loader role: chunk c8 of rows r0 + 32 i ------------------------------------------------
-    const int c8 = tid & 7, r0 = tid >> 3;
-    int row_t[8], row_c[8];            // frame of the row (or a large value past M), cache row index
+    // ---- loader role: one 16-byte chunk of rows r0 + 64 i of both operand tiles ------------------
+    const int r0 = tid >> 2, c4 = (tid & 3) ^ (int)tc_swizzle(r0);   // c4: the chunk whose slot is this lane's
+    int row_t[4], row_c[4];            // frame of the row (or a large value past M), cache row index
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int g = m0 + r0 + 32 * i, gc = g < M ? g : M - 1;
+    for (int i = 0; i < 4; ++i) {
+        const int g = m0 + r0 + 64 * i, gc = g < M ? g : M - 1;
         const int thw = a.T * a.HW, b = gc / thw, rem = gc - b * thw, t = rem / a.HW;
         row_t[i] = g < M ? t : 1 << 20;      // rows past the last token: every tap sees them as past the block
         row_c[i] = b * a.HW + (rem - t * a.HW);
     }
-    uint32_t zeroB = 0;                // W rows past the last output channel
-#pragma unroll
-    for (int i = 0; i < 8; ++i) zeroB |= (n0 + r0 + 32 * i >= D ? 1u : 0u) << i;
-
-    const uint16_t *srcA[8];
-    uint32_t zeroA = 0;
+    const uint16_t *srcA[4], *srcB[4]; // the lane's chunk of each row at K-step 0 of the current tap
     auto set_tap = [&](int tap) {
-        zeroA = 0;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
+        for (int i = 0; i < 4; ++i) {
             const int ts = row_t[i] + tap - 1;
             const bool front = ts < 0, zero = ts >= a.T || (front && !a.cache);
-            const uint16_t *in_x = a.x + ((int64_t)(m0 + r0 + 32 * i) + (int64_t)(tap - 1) * a.HW) * D;
+            const uint16_t *in_x = a.x + ((int64_t)(m0 + r0 + 64 * i) + (int64_t)(tap - 1) * a.HW) * D;
             const uint16_t *in_c = a.cache + (int64_t)row_c[i] * D;
-            srcA[i] = zero ? a.x : (front ? in_c : in_x);       // zero rows read some valid row and drop it
-            zeroA |= (zero ? 1u : 0u) << i;
+            srcA[i] = (zero ? tc_zero_row : (front ? in_c : in_x)) + c4 * 8;
+            const int n = n0 + r0 + 64 * i;
+            srcB[i] = (n >= D ? tc_zero_row : a.W + ((int64_t)tap * D + n) * D) + c4 * 8;
         }
     };
-
-    u32x4 stA[8], stB[8];
-    bool ktail = false;
-    uint32_t zeroA_req = 0;            // zeroA of the step in the staging registers
-    // Requests the operand tiles of K-step (tap, kc) into registers.
-    auto request = [&](int tap, int kc) {
-        int col = kc * kTcBK + c8 * 8;
-        ktail = col >= D;
-        col = ktail ? 0 : col;
-        zeroA_req = zeroA;
-        const uint16_t *wrow = a.W + ((int64_t)tap * D + (n0 + r0)) * D + col;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) stA[i] = *reinterpret_cast<const u32x4 *>(srcA[i] + col);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const bool zr = (zeroB >> i) & 1u;
-            stB[i] = *reinterpret_cast<const u32x4 *>(zr ? a.W : wrow + (int64_t)(32 * i) * D);
-        }
+    int tap_n = 0, kc_n = 0;           // the step to request next
+    auto advance = [&]() {
+        if (kc_n + 1 < KC) {
+            ++kc_n;
+        } else if (tap_n < 2) {
+            kc_n = 0;
+            set_tap(++tap_n);
+        }                              // else: stay on the last step
     };
-    const uint32_t wr_off = (uint32_t)r0 * 128u + ((c8 ^ tc_swizzle(r0)) << 4);
-    auto deposit = [&](int buf) {
-        unsigned char *A = lds + buf * kTcStageBytes, *Bt = A + kTcTileBytes;
-        const u32x4 zero = {0u, 0u, 0u, 0u};
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const bool zA = ktail || ((zeroA_req >> i) & 1u), zB = ktail || ((zeroB >> i) & 1u);
-            *reinterpret_cast<u32x4 *>(A + wr_off + i * 4096) = zA ? zero : stA[i];
-            *reinterpret_cast<u32x4 *>(Bt + wr_off + i * 4096) = zB ? zero : stB[i];
-        }
+    // Source of load m (m < 4: A row pass m, else B row pass m - 4) of the step to request next.
+    auto source = [&](int m) -> const uint16_t * {
+        const uint16_t *p = (m < 4 ? srcA[m] : srcB[m - 4]) + kc_n * kTcBK;
+        if (KTAIL && kc_n * kTcBK + c4 * 8 >= D) p = tc_zero_row;
+        return p;
+    };
+    auto request_one = [&](int stage, int m) {
+        unsigned char *dst = lds + stage * kTcStageBytes + (m < 4 ? 0 : kTcTileBytes) + ((m & 3) * 64 + wave * 16) * 64;
+        tc_load_to_lds(source(m), dst);
     };
 
     // ---- consumer role ------------------------------------------------------------------------------
-    uint32_t ko[4];                    // byte offset of K-chunk pair kk inside the lane's operand row
+    uint32_t ko[2];                    // byte offset of K-chunk pair kk inside the lane's operand row
     {
         const uint32_t g = (uint32_t)(lane >> 5) ^ tc_swizzle(lane & 31);
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) ko[kk] = (((uint32_t)kk << 1) ^ g) << 4;
+        for (int kk = 0; kk < 2; ++kk) ko[kk] = (((uint32_t)kk << 1) ^ g) << 4;
     }
-    const uint32_t rdA = (uint32_t)(wm * 128 + (lane & 31)) * 128u, rdB = (uint32_t)(wn * 128 + (lane & 31)) * 128u;
+    const uint32_t rdA = (uint32_t)(wm * 128 + (lane & 31)) * 64u;
+    const uint32_t rdB = (uint32_t)kTcTileBytes + (uint32_t)(wn * 128 + (lane & 31)) * 64u;
+    // operand m of a set: A row block m (m < 4) or B row block m - 4
+    auto operand = [&](int stage, int kk, int m) -> bf16x8 {
+        const unsigned char *base = lds + stage * kTcStageBytes + (m < 4 ? rdA : rdB) + (m & 3) * 2048 + ko[kk];
+        return *reinterpret_cast<const bf16x8 *>(base);
+    };
 
     f32x16 acc[4][4];
 #pragma unroll
@@ -141,49 +163,47 @@ __global__ __launch_bounds__(kThreads) void tconv_mfma(TconvArgs a)
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+    bf16x8 op[2][8];                   // op[kk][0..3] = A row blocks, op[kk][4..7] = B row blocks
 
-    int tap_n = 0, kc_n = 0;           // the step to request next
-    auto advance = [&]() {
-        if (++kc_n == KC) {
-            kc_n = 0;
-            ++tap_n;
-            if (tap_n < 3) set_tap(tap_n);
-        }
-    };
+    // ---- prologue: steps 0..3 requested, step 0 arrived -----------------------------------------------
     set_tap(0);
-    request(0, 0);
-    advance();
-    deposit(0);
-    __syncthreads();
-
-    auto products = [&](int buf) {
-        const unsigned char *A = lds + buf * kTcStageBytes, *Bt = A + kTcTileBytes;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            bf16x8 av[4], bv[4];
+    for (int st = 0; st < kTcStages; ++st) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) av[i] = *reinterpret_cast<const bf16x8 *>(A + rdA + i * 4096 + ko[kk]);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) bv[j] = *reinterpret_cast<const bf16x8 *>(Bt + rdB + j * 4096 + ko[kk]);
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
-        }
-    };
-    for (int s = 0; s + 1 < steps; ++s) {
-        request(tap_n, kc_n);
+        for (int m = 0; m < 8; ++m) request_one(st, m);
         advance();
-        products(s & 1);
-        deposit((s & 1) ^ 1);
-        __syncthreads();
     }
-    products((steps - 1) & 1);
-    __syncthreads();
+    asm volatile("s_waitcnt vmcnt(24)\n\ts_barrier" ::: "memory");
+#pragma unroll
+    for (int m = 0; m < 8; ++m) op[0][m] = operand(0, 0, m);
+
+    for (int s = 0; s < steps; ++s) {
+        const int cur = s & 3, nxt = (s + 1) & 3;
+#pragma unroll
+        for (int m = 0; m < 16; ++m) {
+            acc[m >> 2][m & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[0][m >> 2], op[0][4 + (m & 3)],
+                                                                          acc[m >> 2][m & 3], 0, 0, 0);
+            if (m < 8) op[1][m] = operand(cur, 1, m);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // this wave's loads of step s+1 have landed (those of steps s+2 and s+3 may be in flight) and its reads
+        // of stage s are done; then so have everybody's
+        asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+#pragma unroll
+        for (int m = 0; m < 16; ++m) {
+            acc[m >> 2][m & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[1][m >> 2], op[1][4 + (m & 3)],
+                                                                          acc[m >> 2][m & 3], 0, 0, 0);
+            if (m < 8) op[0][m] = operand(nxt, 0, m);
+            else request_one(cur, m - 8);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        advance();
+    }
+    // the repeated loads of the last steps must not land on the epilogue's staging
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 
     // ---- epilogue: y = bf16(x + acc), 32 token rows of the wave's quadrant at a time through LDS ----
-    // (the operand tiles are dead after the loop's last barrier; each wave uses its own region)
+    // (nobody reads the operand ring any more; each wave uses its own region)
     unsigned char *epi = lds + wave * (32 * kTcEpiPitch);
     const int er = lane >> 4, ec = lane & 15;                 // reader: row in a group of four, 8-channel chunk
     const int n = n0 + wn * 128 + ec * 8;
