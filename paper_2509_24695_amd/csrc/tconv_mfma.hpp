@@ -20,11 +20,12 @@
 // wave's 64 lanes fill 1 KB of consecutive LDS, no staging registers, completion counted by
 // vmcnt).  With one wave per SIMD nothing but the wave itself can fill the time the matrix core
 // works, so every memory instruction sits between two MFMAs.  Step s (stage s & 3):
-//   first half   16 MFMAs on operand registers of K-chunk 0; reads K-chunk 1 of stage s
+//   first half   16 MFMAs on operand registers of K-chunk 0; reads K-chunk 1 of stage s;
+//                requests the B rows of step s+3
 //   barrier      after waiting for this wave's loads of step s+1 and its own LDS reads
-//   second half  16 MFMAs on K-chunk 1; reads K-chunk 0 of stage s+1; requests step s+4 into
-//                stage s (every wave has read it: the barrier has passed)
-// so a tile is requested three and a half steps before its first use.  Steps past the end
+//   second half  16 MFMAs on K-chunk 1; reads K-chunk 0 of stage s+1; requests the A rows of
+//                step s+4 into stage s (every wave has read it: the barrier has passed)
+// so a tile is requested two to three steps before its first use.  Steps past the end
 // repeat the last one into stages nobody reads: the loop body has no conditions.
 //
 // LDS rows are 64 bytes; the 16-byte chunk c of row r sits at chunk slot c ^ f(r),
@@ -165,39 +166,57 @@ __global__ __launch_bounds__(kThreads) void tconv_mfma(TconvArgs a)
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
     bf16x8 op[2][8];                   // op[kk][0..3] = A row blocks, op[kk][4..7] = B row blocks
 
-    // ---- prologue: steps 0..3 requested, step 0 arrived -----------------------------------------------
+    // ---- prologue: steps 0..2 and the A half of step 3 requested, step 0 arrived --------------------
     set_tap(0);
 #pragma unroll
-    for (int st = 0; st < kTcStages; ++st) {
+    for (int st = 0; st < kTcStages - 1; ++st) {
 #pragma unroll
         for (int m = 0; m < 8; ++m) request_one(st, m);
         advance();
     }
-    asm volatile("s_waitcnt vmcnt(24)\n\ts_barrier" ::: "memory");
+#pragma unroll
+    for (int m = 0; m < 4; ++m) request_one(kTcStages - 1, m);
+    asm volatile("s_waitcnt vmcnt(20)\n\ts_barrier" ::: "memory");
 #pragma unroll
     for (int m = 0; m < 8; ++m) op[0][m] = operand(0, 0, m);
 
+    // A load instruction keeps the wave from issuing for longer than one MFMA runs, so the eight
+    // loads of a step are spread out: one after every second MFMA of the second half of one step
+    // (A rows) and of the first half of the next (B rows).
     for (int s = 0; s < steps; ++s) {
-        const int cur = s & 3, nxt = (s + 1) & 3;
+        const int cur = s & 3, nxt = (s + 1) & 3, prv = (s + 3) & 3;
 #pragma unroll
         for (int m = 0; m < 16; ++m) {
             acc[m >> 2][m & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[0][m >> 2], op[0][4 + (m & 3)],
                                                                           acc[m >> 2][m & 3], 0, 0, 0);
+#ifndef TC_EXP_NOREADS
             if (m < 8) op[1][m] = operand(cur, 1, m);
+#endif
+#ifndef TC_EXP_NOLOADS
+            if (m >= 8 && (m & 1)) request_one(prv, 4 + ((m - 8) >> 1));     // B rows of step s+3
+#endif
             __builtin_amdgcn_sched_barrier(0);
         }
+        advance();
         // this wave's loads of step s+1 have landed (those of steps s+2 and s+3 may be in flight) and its reads
         // of stage s are done; then so have everybody's
+#ifdef TC_EXP_NOBARRIER
+        asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
+#else
         asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+#endif
 #pragma unroll
         for (int m = 0; m < 16; ++m) {
             acc[m >> 2][m & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[1][m >> 2], op[1][4 + (m & 3)],
                                                                           acc[m >> 2][m & 3], 0, 0, 0);
+#ifndef TC_EXP_NOREADS
             if (m < 8) op[0][m] = operand(nxt, 0, m);
-            else request_one(cur, m - 8);
+#endif
+#ifndef TC_EXP_NOLOADS
+            if (m >= 8 && (m & 1)) request_one(cur, (m - 8) >> 1);           // A rows of step s+4
+#endif
             __builtin_amdgcn_sched_barrier(0);
         }
-        advance();
     }
     // the repeated loads of the last steps must not land on the epilogue's staging
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
