@@ -189,32 +189,20 @@ __global__ __launch_bounds__(kThreads) void tconv_mfma(TconvArgs a)
         for (int m = 0; m < 16; ++m) {
             acc[m >> 2][m & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[0][m >> 2], op[0][4 + (m & 3)],
                                                                           acc[m >> 2][m & 3], 0, 0, 0);
-#ifndef TC_EXP_NOREADS
             if (m < 8) op[1][m] = operand(cur, 1, m);
-#endif
-#ifndef TC_EXP_NOLOADS
             if (m >= 8 && (m & 1)) request_one(prv, 4 + ((m - 8) >> 1));     // B rows of step s+3
-#endif
             __builtin_amdgcn_sched_barrier(0);
         }
         advance();
         // this wave's loads of step s+1 have landed (those of steps s+2 and s+3 may be in flight) and its reads
         // of stage s are done; then so have everybody's
-#ifdef TC_EXP_NOBARRIER
-        asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
-#else
         asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-#endif
 #pragma unroll
         for (int m = 0; m < 16; ++m) {
             acc[m >> 2][m & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[1][m >> 2], op[1][4 + (m & 3)],
                                                                           acc[m >> 2][m & 3], 0, 0, 0);
-#ifndef TC_EXP_NOREADS
             if (m < 8) op[0][m] = operand(nxt, 0, m);
-#endif
-#ifndef TC_EXP_NOLOADS
             if (m >= 8 && (m & 1)) request_one(cur, (m - 8) >> 1);           // A rows of step s+4
-#endif
             __builtin_amdgcn_sched_barrier(0);
         }
     }

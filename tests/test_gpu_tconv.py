@@ -47,6 +47,8 @@ CASES = [
     TconvWorkload("wide", B=2, T=3, HW=211, D=584, seed=2103, n_blocks=2),
     # more token-tile groups than XCDs take in one round
     TconvWorkload("many_tiles", B=1, T=4, HW=2400, D=64, seed=2104, n_blocks=1),
+    # more tiles than compute units (several rounds), ragged in tokens, channels and the K-step
+    TconvWorkload("rounds", B=1, T=2, HW=8900, D=760, seed=2105, n_blocks=1),
 ]
 
 
@@ -96,3 +98,26 @@ def test_repeatable_bits():
     y1, _ = _run_block(xd, Wd, None, w.B, w.T, w.HW, w.D)
     y2, _ = _run_block(xd, Wd, None, w.B, w.T, w.HW, w.D)
     assert torch.equal(y1.view(torch.int16), y2.view(torch.int16))
+
+
+@pytest.mark.parametrize("name", ["tconv_480p", "tconv_block_480p"])
+def test_full_size_sampled_rows(name):
+    """The benchmark's shapes in the benchmark's launch configuration; the oracle computes sampled
+    token rows one by one (all channels of each), among them the rows at every kind of boundary."""
+    w = TCONV_WORKLOADS[name]
+    xb, Wb = draw_tconv(w)
+    Wd = to_dev(Wb)
+    rng = np.random.Generator(np.random.PCG64(w.seed + 1))
+    first = w.n_blocks - 1 if w.n_blocks > 1 else 0        # for streams: the last block, with a real cache
+    blk = np.ascontiguousarray(xb[:, first * w.T:(first + 1) * w.T])
+    cache = np.ascontiguousarray(xb[:, first * w.T - 1]) if first > 0 else None
+    say(f"tconv full size {name}: B={w.B} T={w.T} HW={w.HW} D={w.D} cache={'yes' if cache is not None else 'no'}")
+    y, cache_new = _run_block(to_dev(blk), Wd, None if cache is None else to_dev(cache), w.B, w.T, w.HW, w.D)
+    rows = [(0, 0, 0), (0, 0, w.HW - 1), (0, w.T - 1, 0), (w.B - 1, w.T - 1, w.HW - 1), (0, w.T // 2, 255), (0, w.T // 2, 256)]
+    rows += [(int(rng.integers(w.B)), int(rng.integers(w.T)), int(rng.integers(w.HW))) for _ in range(150)]
+    ref = orc.tconv_rows(blk, Wb, cache, rows)
+    yh = to_host(y).astype(np.float64)
+    got = np.stack([yh[b, t, p] for b, t, p in rows])
+    _check(got, ref, name)
+    assert np.isfinite(yh).all()
+    assert np.array_equal(to_host(cache_new), to_host(to_dev(np.ascontiguousarray(blk[:, -1]))))
