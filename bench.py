@@ -29,14 +29,17 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix rate, published
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of this file, each counter
 # scaled by what it reads for a plain device copy of known size (FETCH_SIZE x 1.9997: it books the
 # 128-byte requests these kernels and the copy issue as 64 bytes; WRITE_SIZE x 1.0000).  Source:
-# profiles/traffic_pmc_bidir_480p.txt.  Algorithmic bytes per launch are 268 369 920.
+# profiles/traffic_pmc_bench_kernels.txt.  Algorithmic bytes per launch are 268 369 920.
 MEASURED_TRAFFIC_BYTES = {
-    ("apply", "bidir_480p"): int((67687.9 * 1.99964 + 131040.1) * 1024),
-    ("state", "bidir_480p"): int((133348.0 * 1.99964 + 4688.0) * 1024),
+    ("apply", "bidir_480p"): int((67688.2 * 1.99964 + 131040.0) * 1024),
+    ("state", "bidir_480p"): int((133347.7 * 1.99964 + 4688.0) * 1024),
+    ("apply", "bidir_480p_h20d112"): int((75795.1 * 1.99964 + 143325.0) * 1024),
+    ("state", "bidir_480p_h20d112"): int((149498.1 * 1.99964 + 12861.2) * 1024),
 }
 
 
@@ -50,6 +53,7 @@ def _parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-block-stream", action="store_true")
     ap.add_argument("--no-rope", action="store_true", help="skip the RoPE-variant timings")
+    ap.add_argument("--no-tconv", action="store_true", help="skip the Mix-FFN temporal-convolution timings")
     ap.add_argument("--no-d112", action="store_true",
                     help="skip the timings in the geometry of the paper's 2B model (20 heads of 112 features)")
     ap.add_argument("--stream-blocks", type=int, default=80)
@@ -257,6 +261,39 @@ def bench_block_stream(w, n_blocks, sv, torch, rope=False):
     }
 
 
+def bench_tconv(w, iters, sv, torch):
+    """Mix-FFN temporal convolution (sv_tconv_block_step): the stream of w.n_blocks blocks enqueued back
+    to back with the one-frame cache carried and committed after every block, `iters` passes between one
+    event pair.  Its own roofline is the matrix cores' (2 * 3 * D * D flops per token)."""
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(w.seed)
+    xs = [_randn_bf16((w.B, w.T, w.HW, w.D), gen) * 2.0 for _ in range(w.n_blocks)]       # ~N(0, 1)
+    ys = [torch.empty_like(x) for x in xs]
+    W = (_randn_bf16((3, w.D, w.D), gen).float() * (2.0 / (3 * w.D) ** 0.5)).to(torch.bfloat16)
+    cache = torch.zeros((w.B, w.HW, w.D), dtype=torch.bfloat16, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def run():
+        for m in range(w.n_blocks):
+            sv.sv_tconv_block_step(xs[m], W, cache if m else None, ys[m], cache, w.B, w.T, w.HW, w.D, stream=stream)
+
+    run()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record(stream)
+    for _ in range(iters):
+        run()
+    b.record(stream)
+    torch.cuda.synchronize()
+    us = a.elapsed_time(b) * 1e3 / (iters * w.n_blocks)
+    tflops = w.algorithmic_flops / us / 1e6
+    return {"workload": f"{w.name}: B={w.B} T={w.T} HW={w.HW} D={w.D}, {w.n_blocks} block(s)", "us_per_block": us,
+            "tokens_per_s": w.tokens / (us * 1e-6), "dtype": "bf16",
+            "roofline": {"bound": "mfma", "kernel": "tconv_mfma", "achieved": tflops, "peak": MFMA_BF16_PEAK_TFLOPS,
+                         "unit": "TFLOP/s", "frac": tflops / MFMA_BF16_PEAK_TFLOPS,
+                         "algorithmic_flops_per_launch": w.algorithmic_flops}}
+
+
 def cpu_baseline(w, sets, torch):
     """The float64 oracle on the host cores, on the full workload (one buffer set)."""
     import numpy as np
@@ -389,6 +426,10 @@ def main():
                 bench_block_stream(wl.workload("block_480p"), 10, sv, torch, rope="3d"),
                 bench_block_stream(wl.workload("stream_720p"), args.stream_blocks, sv, torch, rope="3d"),
             ]
+    if not args.no_tconv:
+        # the other cached operator of the block-causal model (Sec. 3.3.1): dense, so bound by the matrix cores
+        out["tconv"] = [bench_tconv(wl.TCONV_WORKLOADS["tconv_480p"], 5, sv, torch),
+                        bench_tconv(wl.TCONV_WORKLOADS["tconv_block_480p"], 5, sv, torch)]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, r["sets"], torch)
     print(json.dumps(out))

@@ -68,6 +68,11 @@ def load_library():
         raise ImportError(
             f"{_LIB_PATH} is missing: build it with `python -m paper_2509_24695_amd.build` "
             "(hipcc, --offload-arch=gfx950). There is no CPU or PyTorch fallback.")
+    # PyTorch ships its own copy of the HIP runtime.  Callers hand this library device pointers
+    # and streams that PyTorch made, so both must talk to one runtime: PyTorch's is loaded first
+    # and the library's dependency on libamdhip64 then resolves to it.  Loaded the other way round
+    # the process holds two runtimes and the first launch fails.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(_LIB_PATH)
     vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
     dp = ctypes.POINTER(_CDesc)

@@ -21,14 +21,14 @@ namespace {
 
 using namespace sv;
 
-constexpr int kVersion = 400;   // 0.4.0
+constexpr int kVersion = 500;   // 0.5.0
 
 // Tuned launch shapes of the bf16 MFMA kernels (one workgroup per compute unit).
 // DP = 64 serves d = 64; DP = 128 serves d = 112 and 128.  Depths are tiles in
 // flight per wave, [DP = 128][RoPE mode: none, table, 3-D]: a stage of the table mode also
 // holds its table rows.
 constexpr int kStateTile = 32, kStateWaves = 4, kApplyWaves = 4;
-constexpr int kStateDepth[2][3] = {{2, 2, 2}, {8, 4, 8}};
+constexpr int kStateDepth[2][3] = {{2, 2, 2}, {8, 4, 4}};
 constexpr int kApplyDepth[2][3] = {{2, 2, 2}, {2, 2, 2}};
 constexpr int kFusedStateDepth[2][3] = {{2, 2, 2}, {4, 2, 4}};
 constexpr int kFusedApplyDepth[2][3] = {{6, 2, 6}, {2, 2, 2}};   // Q tiles held in registers across the in-kernel waits
