@@ -113,3 +113,48 @@ def test_state_call_graph_replays():
         assert torch.equal(O.view(torch.int16), O_eager.view(torch.int16)) and torch.equal(S, S_eager), f"replay {rep}"
         enqueue()                                  # eager call between replays
         torch.cuda.synchronize()
+
+
+def test_tconv_stream_graph_replays():
+    """Three blocks of the temporal convolution with the cache updated in place, captured once and
+    replayed; the cache is reset by a copy kernel inside the graph."""
+    import torch
+    from oracle import tconv_oracle as torc
+    w = wl.TCONV_WORKLOADS["tconv_tiny"]
+    say(f"graph replay of sv_tconv_block_step: B={w.B} T={w.T} HW={w.HW} D={w.D}, {w.n_blocks} blocks")
+    xb, Wb = wl.draw_tconv(w)
+    blocks = [np.ascontiguousarray(xb[:, m * w.T:(m + 1) * w.T]) for m in range(w.n_blocks)]
+    xs, Wd = [to_dev(b) for b in blocks], to_dev(Wb)
+    ys = [torch.empty_like(x) for x in xs]
+    start = to_dev(np.ascontiguousarray(xb[:, 0]))            # some frame as the cache before block 0
+    cache = torch.empty_like(start)
+
+    def enqueue(stream=None):
+        for x, y in zip(xs, ys):
+            sv.sv_tconv_block_step(x, Wd, cache, y, cache, w.B, w.T, w.HW, w.D, stream=stream)
+
+    cache.copy_(start)
+    enqueue()                                                 # first call: one-time set-up happens outside the capture
+    torch.cuda.synchronize()
+    ref_cache = xb[:, 0]
+    for m, blk in enumerate(blocks):
+        y_ref, ref_cache = torc.tconv_block(blk, Wb, ref_cache)
+        metrics.check(to_host(ys[m]), y_ref, "bf16", f"eager tconv block {m}")
+    eager = [y.clone() for y in ys]
+    cache_eager = cache.clone()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        cache.copy_(start)
+        enqueue(stream=torch.cuda.current_stream())
+    for rep in range(3):
+        for y in ys:
+            y.fill_(5.0)
+        cache.fill_(9.0)
+        graph.replay()
+        torch.cuda.synchronize()
+        for m in range(w.n_blocks):
+            assert torch.equal(ys[m].view(torch.int16), eager[m].view(torch.int16)), f"replay {rep} block {m}"
+        assert torch.equal(cache.view(torch.int16), cache_eager.view(torch.int16)), f"replay {rep} cache"
+        cache.copy_(start)                                    # eager work between the replays
+        enqueue()
+        torch.cuda.synchronize()
