@@ -53,9 +53,8 @@ extern "C" {
  * on `stream` (hipStream_t as void*, NULL = default stream); the library
  * allocates nothing and keeps no pointer.  Results are bit-reproducible (fixed
  * summation order, no atomics).  The first call on a device raises the kernel's
- * LDS limit and reads the device properties: make it before capturing the
- * stream into a HIP graph; later calls only enqueue two kernels and may be
- * captured. */
+ * LDS limit (a function attribute): make it before capturing the stream into a
+ * HIP graph; later calls only enqueue two kernels and may be captured. */
 sv_status sv_tconv_block_step(const void *x, const void *W, const void *cache_in,
                               void *y, void *cache_out,
                               int32_t B, int32_t T, int32_t HW, int32_t D,

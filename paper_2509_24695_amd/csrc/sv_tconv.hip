@@ -1,6 +1,8 @@
 // C ABI of the temporal convolution (include/sv_tconv.h): argument checks and launches.
 #include "../../include/sv_tconv.h"
 
+#include <mutex>
+
 #include "tconv_mfma.hpp"
 
 namespace {
@@ -19,8 +21,10 @@ bool overlaps(const void *a, size_t na, const void *b, size_t nb)
 bool tconv_kernel_ready()
 {
     static bool ready[64] = {};
+    static std::mutex mu;
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return false;
+    std::lock_guard<std::mutex> lock(mu);
     if (!ready[dev]) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(tconv_mfma<false>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kTcLdsBytes) != hipSuccess ||
