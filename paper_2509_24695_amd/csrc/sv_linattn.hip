@@ -16,6 +16,7 @@
 #include "common.hpp"
 #include "generic_kernels.hpp"
 #include "state_mfma.hpp"
+#include "wide_state.hpp"
 
 namespace {
 
@@ -29,6 +30,7 @@ constexpr int kVersion = 500;   // 0.5.0
 // holds its table rows.
 constexpr int kStateTile = 32, kStateWaves = 4, kApplyWaves = 4;
 constexpr int kStateDepth[2][3] = {{2, 2, 2}, {8, 4, 4}};
+constexpr int kWideStateDepth = 3;            // 16-token tiles in flight per wave of the wave-private d = 112/128 state kernel
 constexpr int kApplyDepth[2][3] = {{2, 2, 2}, {2, 2, 2}};
 constexpr int kFusedStateDepth[2][3] = {{2, 2, 2}, {4, 2, 4}};
 constexpr int kFusedApplyDepth[2][3] = {{6, 2, 6}, {2, 2, 2}};   // Q tiles held in registers across the in-kernel waits
@@ -66,21 +68,29 @@ template <int ROPE> struct Kernels<64, ROPE> {
     static constexpr int fused_lds = block_step_lds_bytes<64, kStateTile, kStateWaves, ROPE>() + kTab;
     // tokens one workgroup covers per round of its tile walk
     static constexpr int state_wg_tokens = kStateTile * kStateWaves;
+    static constexpr int fused_wg_tokens = state_wg_tokens;
     static constexpr int apply_wg_tokens = kApplyTile * kApplyWaves;
 };
 template <int ROPE> struct Kernels<128, ROPE> {
     static constexpr int W = 1;
     static constexpr int kTab = ROPE == kRope3D ? kRope3dLdsBytes : 0;
-    static constexpr auto state = state_mfma_d128<kStateDepth[W][ROPE], true, ROPE>;
-    static constexpr auto state_partial = state_mfma_d128<kStateDepth[W][ROPE], false, ROPE>;
+    // State: wave-private tiles, except with a full rotation table, whose rows need the registers
+    // the wave-private kernel spends on the whole 128 x 128 state (then: one tile shared by the four waves).
+    static constexpr bool kWideState = ROPE != kRopeTable;
+    static constexpr int kWideRope = kWideState ? ROPE : kRopeNone;
+    static constexpr auto state = kWideState ? state_mfma_wide<kWideStateDepth, true, kWideRope>
+                                             : state_mfma_d128<kStateDepth[W][ROPE], true, ROPE>;
+    static constexpr auto state_partial = kWideState ? state_mfma_wide<kWideStateDepth, false, kWideRope>
+                                                     : state_mfma_d128<kStateDepth[W][ROPE], false, ROPE>;
     static constexpr auto apply = apply_mfma_d128<kApplyHiLo, kApplyDepth[W][ROPE], ROPE>;
     static constexpr auto fused = block_step_mfma<128, kStateTile, kStateWaves, kFusedStateDepth[W][ROPE], kApplyHiLo,
                                                   kFusedApplyDepth[W][ROPE], ROPE>;
-    static constexpr int state_lds = state_d128_lds_bytes<ROPE>() + kTab;
+    static constexpr int state_lds = kWideState ? kWideLdsBytes : state_d128_lds_bytes<ROPE>() + kTab;
     static constexpr int apply_lds = coop_apply_lds_bytes<ROPE>() + kTab;
     static constexpr int fused_lds = block_step_lds_bytes<128, kStateTile, kStateWaves, ROPE>() + kTab;
-    static constexpr int state_wg_tokens = 32;   // the four waves share one tile
-    static constexpr int apply_wg_tokens = 64;   // ... and one pair of tiles
+    static constexpr int state_wg_tokens = kWideState ? 4 * kWideTile : 32;   // four private tiles, or one shared
+    static constexpr int fused_wg_tokens = 32;   // the one-launch block step shares one tile in its state phase
+    static constexpr int apply_wg_tokens = 64;   // the four waves share one pair of tiles
 };
 
 template <int DP, int ROPE> void init_kernels(Device &d)
@@ -448,7 +458,7 @@ sv_status do_block_step(const void *Qb, const void *Kb, const void *Vb, const sv
         with_mfma_kernels(s.d, rope.mode, [&](auto kn) {
             using KN = decltype(kn);
             // One launch when the whole grid can be resident at once (needed by the in-kernel waits).
-            const int C = plan_chunks(s.BH, s.N, KN::state_wg_tokens, dev.num_cu);
+            const int C = plan_chunks(s.BH, s.N, KN::fused_wg_tokens, dev.num_cu);
             if ((int64_t)C * s.BH > dev.fused_resident_wgs[KN::W][rope.mode]) return;
             KN::fused<<<dim3(C, s.BH), 64 * kStateWaves, KN::fused_lds, hs>>>(
                 static_cast<const uint16_t *>(Qb), static_cast<const uint16_t *>(Kb),

@@ -1,0 +1,240 @@
+// State reduction for d = 112 and 128 with wave-private tiles (no workgroup barrier in the token loop).
+//
+//   S[k][v] (+)= sum_j phi(K[j][k]) V[j][v],   z[k] (+)= sum_j phi(K[j][k])
+//
+// (brackets of the linear-attention equation of Sec. 3.2; with ROPE the keys that meet V are
+// rotated after the ReLU, the key sum is not).
+//
+// The design of the d = 64 kernel carried over to a 128 x 128 state: every wave works alone on
+// tiles of 16 tokens (one MFMA k-step) and holds the whole partial state, sixteen 32 x 32
+// accumulators = 256 registers, which is what one wave per SIMD can afford.  Loads are whole
+// 256-byte rows (16 lanes of 16 bytes, 4 rows per instruction), the tile goes through the wave's
+// own LDS, transposing LDS reads deliver four key and four value operands, 16 MFMAs per tile.
+// The key sum is kept per lane on the vector ALU (a lane always loads the same eight features).
+// Compared with the workgroup-cooperative kernel (one 32-token tile shared by the four waves
+// behind a barrier) the per-tile costs that do not shrink with the tile - position arithmetic of
+// the rotation, waits, the barrier itself - are paid per 64 tokens of a compute unit's work
+// instead of per 32 and never hold up the other waves.
+//
+// At the end the four waves' states are added in a fixed order through LDS, a band of 32 key
+// features at a time, and stored as the workgroup's partial.
+#pragma once
+
+#include "state_mfma.hpp"
+
+namespace sv {
+
+constexpr int kWideTile = 16;                       // tokens per tile: one MFMA k-step
+constexpr int kWideRow = 128 * 2 + 16;              // LDS row: 128 bf16 features + padding
+constexpr int kWideTileBytes = kWideTile * kWideRow;
+
+// LDS map (bytes): [0, 64 KB) the reduction bands (4 waves x 32 rows x 128 floats), over the dead K/V
+// tiles (8 tiles from 0); then the rotation tables, the waves' key sums and the epoch word.
+constexpr int kWideTabOffset = 4 * 32 * 128 * 4;
+constexpr int kWideZOffset = kWideTabOffset + kRope3dLdsBytes;
+constexpr int kWideEpochOffset = kWideZOffset + 4 * 128 * 4;
+constexpr int kWideLdsBytes = kWideEpochOffset + kEpochLdsBytes;
+static_assert(8 * kWideTileBytes <= kWideTabOffset, "the tiles fit under the reduction bands");
+
+struct WideAcc {
+    f32x16 s[4][4];   // [key feature block][value feature block]
+    float z[8];       // features 8 * (lane % 16) + e of the tokens this lane loaded
+    __device__ __forceinline__ void clear() {
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+            for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) s[rb][cb][i] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) z[e] = 0.f;
+    }
+};
+
+// One wave's input stream: rows lane/16 + 4 j of every tile of its walk, DEPTH tiles in flight.
+// Lanes whose features lie past d (d = 112) address out of range: they read zeros.
+template <int DEPTH, int ROPE>
+struct WideStateStream {
+    static constexpr int NLD = kWideTile / 4;
+    rsrc_t rK, rV;
+    uint32_t row_bytes, lane_off;
+    bool valid;
+    TileWalk walk;
+    u32x4 k[DEPTH][NLD], v[DEPTH][NLD];
+    Rotator<ROPE, NLD, DEPTH> rot;
+
+    __device__ __forceinline__ WideStateStream(const uint16_t *Kh, const uint16_t *Vh, const RopeArg &rope,
+                                               const unsigned char *lds_tab, int64_t stride_n, int t1, int d, int lane,
+                                               const TileWalk &w)
+        : rK(make_rsrc(Kh, (uint32_t)t1 * (uint32_t)stride_n * 2u)),
+          rV(make_rsrc(Vh, (uint32_t)t1 * (uint32_t)stride_n * 2u)), row_bytes((uint32_t)stride_n * 2u),
+          lane_off((uint32_t)(lane >> 4) * (uint32_t)stride_n * 2u + (uint32_t)(lane & 15) * 16u),
+          valid((lane & 15) * 8 < d), walk(w), rot(rope, t1, d, lane >> 4, 4, 4 * (lane & 15), 1, lds_tab) {}
+
+    __device__ __forceinline__ void request(int s, int i)
+    {
+        const uint32_t base = valid ? walk.offset<kWideTile>(i, row_bytes) : kOutOfRange;
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) {
+            k[s][j] = load_stream16(rK, base + lane_off + (uint32_t)j * 4u * row_bytes);
+            v[s][j] = load_stream16(rV, base + lane_off + (uint32_t)j * 4u * row_bytes);
+        }
+        rot.request(s, i < walk.count, walk.token<kWideTile>(i));
+    }
+};
+
+template <int DEPTH, int ROPE>
+__device__ __forceinline__ void wide_state_prefetch(WideStateStream<DEPTH, ROPE> &st)
+{
+#pragma unroll
+    for (int s = 0; s < DEPTH; ++s) {
+        st.request(s, s);
+        __builtin_amdgcn_sched_barrier(0);   // requests go out in stage order, as they do in the loop
+    }
+}
+
+// Accumulates the wave's share (its first DEPTH tiles are requested).  Stages past the share and
+// tokens past t1 hold zeros and add nothing.  tileK, tileV: the wave's private LDS tiles.
+template <int DEPTH, int ROPE>
+__device__ __forceinline__ void wide_state_accumulate(WideStateStream<DEPTH, ROPE> &st, unsigned char *tileK,
+                                                      unsigned char *tileV, int lane, WideAcc &acc)
+{
+    constexpr int NLD = WideStateStream<DEPTH, ROPE>::NLD;
+    const int wr_off = (lane >> 4) * kWideRow + (lane & 15) * 16;
+    for (int i0 = 0; i0 < st.walk.count; i0 += DEPTH) {
+#pragma unroll
+        for (int s = 0; s < DEPTH; ++s) {
+            __builtin_amdgcn_sched_barrier(0);   // stages stay in program order
+            st.rot.begin_tile(st.walk.template token<kWideTile>(i0 + s));
+#pragma unroll
+            for (int j = 0; j < NLD; ++j) {
+                const u32x4 kk = relu_bf16x8(st.k[s][j]);
+                acc.z[0] += bf16_lo(kk.x);  acc.z[1] += bf16_hi(kk.x);
+                acc.z[2] += bf16_lo(kk.y);  acc.z[3] += bf16_hi(kk.y);
+                acc.z[4] += bf16_lo(kk.z);  acc.z[5] += bf16_hi(kk.z);
+                acc.z[6] += bf16_lo(kk.w);  acc.z[7] += bf16_hi(kk.w);
+                st.k[s][j] = st.rot.rotate(s, j, kk);
+            }
+            wave_lds_fence();   // earlier reads of the tile buffers are done before they are overwritten
+#pragma unroll
+            for (int j = 0; j < NLD; ++j) {
+                *reinterpret_cast<u32x4 *>(tileK + wr_off + 4 * j * kWideRow) = st.k[s][j];
+                *reinterpret_cast<u32x4 *>(tileV + wr_off + 4 * j * kWideRow) = st.v[s][j];
+            }
+            st.request(s, i0 + s + DEPTH);   // refill this stage: DEPTH tiles ahead
+            __builtin_amdgcn_sched_barrier(0);
+            wave_lds_fence();
+            bf16x8 a[4], b[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                a[q] = lds_tr_operand<kWideRow>(tileK, 0, 32 * q, lane);
+                b[q] = lds_tr_operand<kWideRow>(tileV, 0, 32 * q, lane);
+            }
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < 4; ++cb)
+                    acc.s[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rb], b[cb], acc.s[rb][cb], 0, 0, 0);
+        }
+    }
+}
+
+// Adds the four waves' states in the fixed order (w0 + w2) + (w1 + w3) and stores the workgroup's
+// partial (d x d, row length d, then the d key sums) to `out` with coherent stores.  Must be called
+// by all threads; the tiles in LDS are dead afterwards.  The accumulators are only read: one band
+// of 32 key features at a time, every wave lays its four blocks out in [k][v] order (16 KB each),
+// then all threads add the four copies and store the band.
+__device__ __forceinline__ void wide_state_wg_reduce_store(WideAcc &acc, unsigned char *lds, int wave, int lane, int d,
+                                                           float *__restrict__ out)
+{
+    float *band = reinterpret_cast<float *>(lds);               // [wave][32 rows][128 columns]
+    float *zs = reinterpret_cast<float *>(lds + kWideZOffset);  // [wave][128]
+    // key sums: lanes with equal lane % 16 hold the same eight features
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        float x = acc.z[e];
+        x += __shfl_xor(x, 16);
+        x += __shfl_xor(x, 32);
+        acc.z[e] = x;
+    }
+    __syncthreads();                                   // all waves are done with their tiles
+    if (lane < 16) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) zs[wave * 128 + lane * 8 + e] = acc.z[e];
+    }
+    const int n = lane & 31, g = lane >> 5;
+    const int half = d / 2;                            // 8-byte units per row of S
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb) {
+        float *mine = band + wave * (32 * 128);
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                mine[(8 * (i >> 2) + 4 * g + (i & 3)) * 128 + 32 * cb + n] = acc.s[rb][cb][i];
+        __syncthreads();
+        const int rows = d - 32 * rb < 32 ? (d - 32 * rb > 0 ? d - 32 * rb : 0) : 32;   // key features of this band below d
+        for (int u = threadIdx.x; u < rows * half; u += 4 * kWave) {
+            const int k = u / half, v = 2 * (u - k * half);
+            const float *p = band + k * 128 + v;
+            const f32x2 x0 = *reinterpret_cast<const f32x2 *>(p), x1 = *reinterpret_cast<const f32x2 *>(p + 32 * 128),
+                        x2 = *reinterpret_cast<const f32x2 *>(p + 2 * 32 * 128),
+                        x3 = *reinterpret_cast<const f32x2 *>(p + 3 * 32 * 128);
+            store_coherent(out + (size_t)(32 * rb + k) * d + v, (x0 + x2) + (x1 + x3));
+        }
+        __syncthreads();                               // the band is read before the next one is laid out
+    }
+    for (int u = threadIdx.x; u < half; u += 4 * kWave) {
+        const int k = 2 * u;
+        f32x2 x;
+        x.x = (zs[k] + zs[256 + k]) + (zs[128 + k] + zs[384 + k]);
+        x.y = (zs[k + 1] + zs[256 + k + 1]) + (zs[128 + k + 1] + zs[384 + k + 1]);
+        store_coherent(out + (size_t)d * d + k, x);
+    }
+}
+
+// grid = (C, B*H), block = 256.  Wave w of workgroup c owns tiles 4c + w + 4C i of the
+// T = ceil((t1 - t0) / 16) tiles.  FINALIZE as in state_mfma_d64.  ROPE: kRopeNone or kRope3D (the
+// table rows of kRopeTable do not fit in the registers left beside the state).
+template <int DEPTH, bool FINALIZE, int ROPE>
+__global__ __launch_bounds__(256, 1) void state_mfma_wide(
+    const uint16_t *__restrict__ K, const uint16_t *__restrict__ V, RopeArg rope, TokStrides st,
+    int H, int d, int t0, int t1, int C, const float *S_in, const float *z_in, float *S_out, float *z_out,
+    void *__restrict__ ws, unsigned long long epoch, uint32_t spin_limit)
+{
+    static_assert(ROPE == kRopeNone || ROPE == kRope3D, "no full-table form of this kernel");
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c = blockIdx.x, bh = blockIdx.y, BH = gridDim.y;
+    const int b = bh / H, h = bh % H;
+    const int elems = d * d + d;
+    const uint16_t *Kh = K + b * st.b + h * st.h;
+    const uint16_t *Vh = V + b * st.b + h * st.h;
+    const int n_tiles = (t1 - t0 + kWideTile - 1) / kWideTile;
+    EpochSource es;
+    if (FINALIZE) es.begin(ws, BH, elems, epoch);
+
+    WideAcc acc;
+    acc.clear();
+    WideStateStream<DEPTH, ROPE> stream(Kh, Vh, rope, lds + kWideTabOffset, st.n, t1, d, lane,
+                                        TileWalk(t0, 4 * c + wave, 4 * C, n_tiles, bh));
+    wide_state_prefetch(stream);
+    if (ROPE == kRope3D) {
+        rope3d_lds_fill(lds + kWideTabOffset, rope.r3);
+        __syncthreads();
+    }
+    unsigned char *tileK = lds + wave * 2 * kWideTileBytes, *tileV = tileK + kWideTileBytes;
+    wide_state_accumulate(stream, tileK, tileV, lane, acc);
+
+    float *partials = static_cast<float *>(ws) + (size_t)bh * kMaxChunks * elems;
+    wide_state_wg_reduce_store(acc, lds, wave, lane, d, partials + (size_t)c * elems);
+    if (FINALIZE) {
+        epoch = es.resolve(reinterpret_cast<unsigned long long *>(lds + kWideEpochOffset));
+        state_publish_and_wait(ws, BH, elems, bh, c, C, 0, epoch, spin_limit, lane);
+        state_finalize_slice<256, false>(partials, c, C, d, S_in ? S_in + (size_t)bh * d * d : nullptr,
+                                         z_in + (size_t)bh * d, S_out + (size_t)bh * d * d, z_out + (size_t)bh * d);
+    }
+}
+
+}  // namespace sv

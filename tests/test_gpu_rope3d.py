@@ -64,7 +64,13 @@ def test_rope3d_bidirectional(dtype, d, B, H, grid):
     sv.sv_linattn_state_rope(Kd, Vd, dsc, Td, 0, N, 0, S2, z2, ws)
     sv.sv_linattn_apply_rope(Qd, dsc, Td, 0, N, S2, z2, 1e-6, O2)
     torch.cuda.synchronize()
-    assert torch.equal(S, S2) and torch.equal(z, z2) and _same_bits(O, O2)
+    if dtype == "bf16" and d >= 112:
+        # these two forms run different state kernels here (wave-private tiles with the factored
+        # tables, one shared tile with the full table): same products, another summation order
+        assert metrics.rel_l2(to_host(S), to_host(S2)) <= 1e-6 and metrics.rel_l2(to_host(z), to_host(z2)) <= 1e-6
+        assert metrics.rel_l2(to_host(O), to_host(O2)) <= 1e-4
+    else:
+        assert torch.equal(S, S2) and torch.equal(z, z2) and _same_bits(O, O2)
 
 
 def test_rope3d_token_ranges():
