@@ -187,8 +187,8 @@ struct Rotator<kRope3D, STEPS, DEPTH> {
             const int dr = (int)(((float)c1 + 0.5f) * inv_cols);
             const int r1 = r0 + dr;
             const int df = (int)(((float)r1 + 0.5f) * inv_rows);
-            c[j] = c1 - dr * cols;
-            r[j] = r1 - df * rows;
+            c[j] = c1 - __mul24(dr, cols);
+            r[j] = r1 - __mul24(df, rows);
             const int ff = f0 + df;
             f[j] = ff < frames_m1 ? ff : frames_m1;      // rows past the last token hold zeros: any entry will do
         }
@@ -199,8 +199,9 @@ struct Rotator<kRope3D, STEPS, DEPTH> {
         uint32_t word[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const uint32_t addr = base[q] + (uint32_t)f[j] * mul_f[q] + (uint32_t)r[j] * mul_r[q] +
-                                  (uint32_t)c[j] * mul_c[q];
+            // 24-bit multiplies run at full rate (32-bit ones at a quarter); positions and strides are far below 2^24
+            const uint32_t addr = base[q] + __umul24((uint32_t)f[j], mul_f[q]) + __umul24((uint32_t)r[j], mul_r[q]) +
+                                  __umul24((uint32_t)c[j], mul_c[q]);
             const f32x2 cs = *reinterpret_cast<const f32x2 *>(tab + addr);
             word[q] = rope_rotate_pair(word[q], cs.x, cs.y);
         }

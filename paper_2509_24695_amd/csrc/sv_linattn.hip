@@ -247,6 +247,8 @@ bool mfma_path(const Shape &s, const Rope &rope)
     if (rope.mode == kRope3D) {            // the three tables must fit the LDS set aside for them
         const Rope3D &r = rope.arg.r3;
         if ((int64_t)rope3d_entries(r.frames, r.rows, r.cols, r.n_t, r.n_h, r.n_w) * 8 > kRope3dLdsBytes) return false;
+        // positions are carried in 24-bit multiplies and fp32 reciprocals there
+        if (r.frames >= (1 << 20) || r.rows >= (1 << 20) || r.cols >= (1 << 20)) return false;
     }
     return true;
 }
