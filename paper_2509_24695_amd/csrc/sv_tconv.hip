@@ -63,9 +63,8 @@ extern "C" sv_status sv_tconv_block_step(const void *x, const void *W, const voi
     a.B = B; a.T = T; a.HW = HW; a.D = D;
     a.tiles_m = (int)((M + kTcBM - 1) / kTcBM);
     a.tiles_n = (D + kTcBN - 1) / kTcBN;
-    const int64_t tiles = (int64_t)a.tiles_m * a.tiles_n, wgs = 8 * ((tiles + 7) / 8);
+    const int64_t wgs = tc_grid_size((int64_t)a.tiles_m * a.tiles_n);
     if (wgs >= (int64_t)1 << 31) return SV_ERR_SHAPE;
-    a.tiles = (int)tiles;
     auto hs = static_cast<hipStream_t>(stream);
     if (D % kTcBK == 0) tconv_mfma<false><<<dim3((unsigned)wgs), kThreads, kTcLdsBytes, hs>>>(a);
     else tconv_mfma<true><<<dim3((unsigned)wgs), kThreads, kTcLdsBytes, hs>>>(a);

@@ -35,6 +35,7 @@
 #pragma once
 
 #include "common.hpp"
+#include "tconv_tiles.hpp"
 
 namespace sv {
 
@@ -43,7 +44,6 @@ constexpr int kTcTileBytes = kTcBM * kTcBK * 2;               // one operand til
 constexpr int kTcStageBytes = 2 * kTcTileBytes;               // A and B
 constexpr int kTcStages = 4;
 constexpr int kTcLdsBytes = kTcStages * kTcStageBytes;
-constexpr int kTcGroupM = 4;                                  // token tiles per group of the tile order
 constexpr int kTcEpiPitch = 128 * 4 + 32;                     // fp32 row of a wave's quadrant in the epilogue
 constexpr int kTcMaxD = 32768;                                // length of the row of zeros
 static_assert(4 * 32 * kTcEpiPitch <= kTcLdsBytes, "epilogue staging fits in the operand ring");
@@ -55,28 +55,10 @@ struct TconvArgs {
     const uint16_t *x, *W, *cache;     // cache may be null
     uint16_t *y;
     int B, T, HW, D;
-    int tiles_m, tiles_n, tiles;       // token tiles, channel tiles, their product
+    int tiles_m, tiles_n;              // token tiles, channel tiles
 };
 
 __device__ __forceinline__ uint32_t tc_swizzle(int r) { return (uint32_t)(((r >> 1) & 3) ^ ((r >> 3) & 1)); }
-
-// Workgroup id -> tile.  Tiles are ordered in groups of kTcGroupM token tiles, token tile
-// fastest inside a group; consecutive workgroup ids go to the eight XCDs in turn, each with its
-// own L2, so XCD e takes the e-th eighth of that order: the workgroups that run on one XCD at a
-// time share a few token tiles and W's current K-slice, and all XCDs get the same number of
-// tiles (to within one) however few there are.
-__device__ __forceinline__ bool tc_tile_of(const TconvArgs &a, int wg, int &tm, int &tn)
-{
-    const int xcd = wg & 7, seq = wg >> 3;
-    const int begin = (int)(((int64_t)xcd * a.tiles) >> 3), end = (int)(((int64_t)(xcd + 1) * a.tiles) >> 3);
-    const int t = begin + seq;
-    if (t >= end) return false;
-    const int per_group = kTcGroupM * a.tiles_n, g = t / per_group, in = t - g * per_group;
-    const int rows = min(kTcGroupM, a.tiles_m - g * kTcGroupM);      // token tiles in this (maybe last) group
-    tn = in / rows;
-    tm = g * kTcGroupM + (in - tn * rows);
-    return true;
-}
 
 // 16 bytes per lane from global memory to LDS: lane l of the wave writes lds_wave_base + 16 l.
 __device__ __forceinline__ void tc_load_to_lds(const uint16_t *src, unsigned char *lds_wave_base)
@@ -91,7 +73,7 @@ __global__ __launch_bounds__(kThreads) void tconv_mfma(TconvArgs a)
 {
     extern __shared__ __align__(16) unsigned char lds[];
     int tm, tn;
-    if (!tc_tile_of(a, (int)blockIdx.x, tm, tn)) return;
+    if (!tc_tile_of(a.tiles_m, a.tiles_n, (int)blockIdx.x, tm, tn)) return;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave & 1, wn = wave >> 1;
