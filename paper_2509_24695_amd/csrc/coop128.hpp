@@ -160,14 +160,16 @@ __device__ __forceinline__ void state_accumulate_coop(CoopStateStream<DEPTH, ROP
 // ---- apply ---------------------------------------------------------------------------------------
 
 // One wave's share of the workgroup's Q/O stream: rows 16*wave .. +16 of every
-// pair of tiles (64 tokens), both for the loads of Q and for the stores of O.
-template <int DEPTH, int ROPE>
+// step of 16*WAVES tokens (WAVES = 4: a pair of 32-token tiles; WAVES = 2: one tile), both for the
+// loads of Q and for the stores of O.
+template <int DEPTH, int ROPE, int WAVES = 4>
 struct CoopApplyStream {
     static constexpr int NLD = 4;
+    static constexpr int STEP = 16 * WAVES;   // tokens per workgroup step
     rsrc_t rQ, rO;
     uint32_t row_bytes, lane_off;
     bool valid;
-    TileWalk walk;                       // the workgroup's tile pairs (units of 64 tokens)
+    TileWalk walk;                       // the workgroup's steps (units of STEP tokens)
     u32x4 q[DEPTH][NLD];
     Rotator<ROPE, NLD, DEPTH> rot;
 
@@ -182,15 +184,15 @@ struct CoopApplyStream {
 
     __device__ __forceinline__ void request(int s, int i)
     {
-        const uint32_t base = valid ? walk.offset<64>(i, row_bytes) : kOutOfRange;
+        const uint32_t base = valid ? walk.offset<STEP>(i, row_bytes) : kOutOfRange;
 #pragma unroll
         for (int j = 0; j < NLD; ++j) q[s][j] = load_stream16(rQ, base + lane_off + (uint32_t)j * 4u * row_bytes);
-        rot.request(s, i < walk.count, walk.token<64>(i));
+        rot.request(s, i < walk.count, walk.token<STEP>(i));
     }
 };
 
-template <int FROM, int TO, int DEPTH, int ROPE>
-__device__ __forceinline__ void coop_apply_prefetch(CoopApplyStream<DEPTH, ROPE> &st)
+template <int FROM, int TO, int DEPTH, int ROPE, int WAVES>
+__device__ __forceinline__ void coop_apply_prefetch(CoopApplyStream<DEPTH, ROPE, WAVES> &st)
 {
 #pragma unroll
     for (int s = FROM; s < TO; ++s) {
@@ -199,19 +201,23 @@ __device__ __forceinline__ void coop_apply_prefetch(CoopApplyStream<DEPTH, ROPE>
     }
 }
 
-// LDS of the apply phase: a pair of Q tiles (with ROPE also their rotated copy) and a pair of O tiles.
-template <int ROPE> __host__ __device__ constexpr int coop_apply_lds_bytes() { return (ROPE ? 6 : 4) * kCoopTile; }
+// LDS of the apply phase: the Q tiles of a step (with ROPE also their rotated copy) and its O tiles.
+template <int ROPE, int WAVES = 4> __host__ __device__ constexpr int coop_apply_lds_bytes() {
+    return (ROPE ? 3 : 2) * (WAVES / 2) * kCoopTile;
+}
 
-// Applies the state panel in `A` (value block wave%2) to tile wave/2 of every pair
-// of the workgroup's share.  Must be called by all four waves.
-template <bool HILO, int DEPTH, int ROPE>
-__device__ __forceinline__ void apply_tiles_coop(CoopApplyStream<DEPTH, ROPE> &st, unsigned char *lds, int wave,
+// Applies the state panel in `A` (value block wave%2) to tile wave/2 of every step
+// of the workgroup's share.  Must be called by all waves of the workgroup.
+template <bool HILO, int DEPTH, int ROPE, int WAVES>
+__device__ __forceinline__ void apply_tiles_coop(CoopApplyStream<DEPTH, ROPE, WAVES> &st, unsigned char *lds, int wave,
                                                  int lane, const ApplyOperands<128, HILO> &A, float eps)
 {
     constexpr int NS = HILO ? 2 : 1;
+    constexpr int STEP = 16 * WAVES, TILES = WAVES / 2;
     const int t = wave >> 1, vb = wave & 1;
     const int n = lane & 31, g = lane >> 5;
-    unsigned char *bufQ = lds, *bufR = ROPE ? lds + 2 * kCoopTile : lds, *bufO = lds + (ROPE ? 4 : 2) * kCoopTile;
+    unsigned char *bufQ = lds, *bufR = ROPE ? lds + TILES * kCoopTile : lds,
+                  *bufO = lds + (ROPE ? 2 : 1) * TILES * kCoopTile;
     const int wr_off = (16 * wave + (lane >> 4)) * kCoopRow + (lane & 15) * 16;   // the wave's own rows
     const unsigned char *brow = bufQ + (32 * t + n) * kCoopRow, *rrow = bufR + (32 * t + n) * kCoopRow;
     unsigned char *orow = bufO + (32 * t + n) * kCoopRow + (64 * vb + 32 * g) * 2;
@@ -221,9 +227,9 @@ __device__ __forceinline__ void apply_tiles_coop(CoopApplyStream<DEPTH, ROPE> &s
         for (int s = 0; s < DEPTH; ++s) {
             __builtin_amdgcn_sched_barrier(0);   // stages stay in program order
             const bool valid = i0 + s < st.walk.count;
-            const uint32_t out_off = st.valid ? st.walk.template offset<64>(i0 + s, st.row_bytes) : kOutOfRange;
+            const uint32_t out_off = st.valid ? st.walk.template offset<STEP>(i0 + s, st.row_bytes) : kOutOfRange;
             if (valid) {
-                st.rot.begin_tile(st.walk.template token<64>(i0 + s));
+                st.rot.begin_tile(st.walk.template token<STEP>(i0 + s));
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const u32x4 pq = relu_bf16x8(st.q[s][j]);                          // phi(Q)
@@ -337,10 +343,12 @@ __global__ __launch_bounds__(256, 1) void state_mfma_d128(
     }
 }
 
-// Apply for d = 112 or 128.  grid = (C, B*H), block = 256; workgroup c owns the
-// pairs of tiles c + C*i of the ceil((t1-t0)/64) pairs.
-template <bool HILO, int DEPTH, int ROPE>
-__global__ __launch_bounds__(256, 1) void apply_mfma_d128(
+// Apply for d = 112 or 128.  grid = (C, B*H), block = 64 * WAVES; workgroup c owns the
+// steps c + C*i of the ceil((t1-t0)/(16*WAVES)) steps of 16*WAVES tokens.  WAVES = 2: two
+// workgroups share a compute unit (one wave per SIMD either way) and only the two waves that work
+// on the same tile meet at its barriers.
+template <bool HILO, int DEPTH, int ROPE, int WAVES>
+__global__ __launch_bounds__(64 * WAVES, 1) void apply_mfma_d128(
     const uint16_t *__restrict__ Q, uint16_t *__restrict__ O, RopeArg rope, TokStrides st, int H,
     int d, int t0, int t1, int C, const float *__restrict__ S, const float *__restrict__ z, float eps)
 {
@@ -351,13 +359,14 @@ __global__ __launch_bounds__(256, 1) void apply_mfma_d128(
     const int b = bh / H, h = bh % H;
     const uint16_t *Qh = Q + b * st.b + h * st.h;
     uint16_t *Oh = O + b * st.b + h * st.h;
-    const int n_pairs = (t1 - t0 + 63) / 64;
+    constexpr int STEP = 16 * WAVES;
+    const int n_steps = (t1 - t0 + STEP - 1) / STEP;
 
-    CoopApplyStream<DEPTH, ROPE> stream(Qh, Oh, rope, lds + coop_apply_lds_bytes<ROPE>(), st.n, t1, d, wave, lane,
-                                        TileWalk(t0, c, C, n_pairs, bh));
+    CoopApplyStream<DEPTH, ROPE, WAVES> stream(Qh, Oh, rope, lds + coop_apply_lds_bytes<ROPE, WAVES>(), st.n, t1, d, wave,
+                                               lane, TileWalk(t0, c, C, n_steps, bh));
     coop_apply_prefetch<0, DEPTH>(stream);   // in flight while S is fetched
     if (ROPE == kRope3D) {
-        rope3d_lds_fill(lds + coop_apply_lds_bytes<ROPE>(), rope.r3);
+        rope3d_lds_fill(lds + coop_apply_lds_bytes<ROPE, WAVES>(), rope.r3);
         __syncthreads();
     }
     ApplyOperands<128, HILO> A;
