@@ -36,10 +36,10 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix rate, published
 # 128-byte requests these kernels and the copy issue as 64 bytes; WRITE_SIZE x 1.0000).  Source:
 # profiles/traffic_pmc_bench_kernels.txt.  Algorithmic bytes per launch are 268 369 920.
 MEASURED_TRAFFIC_BYTES = {
-    ("apply", "bidir_480p"): int((67688.2 * 1.99964 + 131040.0) * 1024),
-    ("state", "bidir_480p"): int((133347.7 * 1.99964 + 4688.0) * 1024),
-    ("apply", "bidir_480p_h20d112"): int((75795.1 * 1.99964 + 143325.0) * 1024),
-    ("state", "bidir_480p_h20d112"): int((149498.1 * 1.99964 + 12861.2) * 1024),
+    ("apply", "bidir_480p"): int((67687.9 * 1.99964 + 131040.0) * 1024),
+    ("state", "bidir_480p"): int((133343.4 * 1.99964 + 4688.0) * 1024),
+    ("apply", "bidir_480p_h20d112"): int((75795.3 * 1.99964 + 143325.0) * 1024),
+    ("state", "bidir_480p_h20d112"): int((149516.2 * 1.99964 + 12861.2) * 1024),
 }
 
 
@@ -336,7 +336,11 @@ def main():
     sec = r["ms_per_step"] * 1e-3
     half = w.algorithmic_bytes / 2          # state reads K,V; apply reads Q and writes O
     dom = "state" if r["ms_state"] >= r["ms_apply"] else "apply"
-    dom_ms = max(r["ms_state"], r["ms_apply"])
+    dom_ms_events = max(r["ms_state"], r["ms_apply"])
+    # An event between two kernels adds a marker packet (2-3 us per kernel here).  The step time of the
+    # timed region has no events inside it, so the event durations are scaled to add up to it: that is
+    # the kernel's average launch duration in the timed region (rocprofv3's kernel trace agrees within 1 us).
+    dom_ms = dom_ms_events * r["ms_per_step"] / (r["ms_state"] + r["ms_apply"])
     achieved = half / (dom_ms * 1e-3) / 1e9
     out = {
         "metric": "linear-attention tokens/s per layer (fwd)",
@@ -355,7 +359,8 @@ def main():
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get((dom, w.name)),
-                     "algorithmic_bytes_per_launch": half, "avg_launch_ms": dom_ms},
+                     "algorithmic_bytes_per_launch": half, "avg_launch_ms": dom_ms,
+                     "avg_launch_ms_between_events": dom_ms_events},
     }
     if args.calibration_copy > 0:
         src = r["sets"][0][0]
