@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "tile_walk.hpp"
+
 namespace sv {
 
 constexpr int kWave = 64;            // CDNA wavefront width
@@ -77,7 +79,6 @@ __device__ __forceinline__ u32x4 rope_rotate_bf16x8(u32x4 w, f32x4 cs01, f32x4 c
 // loads it needs (s_waitcnt vmcnt(n)) while later ones stay in flight.  Offsets are
 // 32-bit: the host routes tensors whose heads span 2 GiB or more to other kernels.
 using rsrc_t = __amdgpu_buffer_rsrc_t;
-constexpr uint32_t kOutOfRange = 0x80000000u;   // an offset no resource built here covers
 
 // `p` must be wave-uniform.  Bytes [0, bytes) are addressable.
 __device__ __forceinline__ rsrc_t make_rsrc(const void *p, uint32_t bytes) {
@@ -105,11 +106,6 @@ __device__ __forceinline__ void store_stream16(rsrc_t r, uint32_t off, u32x4 v) 
 // Cached 16-byte load (rotation table: shared by all heads, worth keeping in L2).
 __device__ __forceinline__ f32x4 load_cached16(rsrc_t r, uint32_t off) {
     return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0));
-}
-
-// Byte offset of the first row of the tile that starts at token `tok0`, or kOutOfRange.
-__device__ __forceinline__ uint32_t tile_offset(bool valid, int tok0, uint32_t row_bytes) {
-    return valid ? (uint32_t)tok0 * row_bytes : kOutOfRange;
 }
 
 // ---- typed scalar access used by the generic (any dtype) kernels --------------------------

@@ -150,30 +150,6 @@ struct StateAcc {
     }
 };
 
-// A wave's share of the tiles that cover the token range [t0, t1): tiles
-// first + j*step for j = 0 .. count-1 (all values wave-uniform), visited in the
-// cyclic order j = rot, rot+1, .., count-1, 0, .., rot-1.  Heads start at
-// different phases of their shares, head bh at (bh mod 16)/16: when all heads
-// march through memory in lockstep, some sequence lengths put their streams on
-// the same DRAM resources at the same time (N = 75 600, 64 heads: apply 290 us
-// in lockstep, 246 us staggered; no length measured got slower).
-struct TileWalk {
-    int t0, first, step, count, rot;
-    __device__ __forceinline__ TileWalk(int t0_, int first_, int step_, int n_tiles, int bh)
-        : t0(t0_), first(first_), step(step_),
-          count(first_ < n_tiles ? (n_tiles - first_ + step_ - 1) / step_ : 0), rot(((bh & 15) * count) >> 4) {}
-    // first token of the i-th tile the wave visits (TILE tokens per tile), i < count
-    template <int TILE> __device__ __forceinline__ int token(int i) const {
-        int j = i + rot;
-        j = j >= count ? j - count : j;
-        return t0 + (first + j * step) * TILE;
-    }
-    // its byte offset for rows of row_bytes bytes, kOutOfRange past the share
-    template <int TILE> __device__ __forceinline__ uint32_t offset(int i, uint32_t row_bytes) const {
-        return tile_offset(i < count, token<TILE>(i), row_bytes);
-    }
-};
-
 // Coalesced load of a TILE x 64 bf16 tile: lane l takes bytes 16*(l%8) .. +16 of
 // rows l/8 + 8i.  `off0` is the tile's byte offset (TileWalk::offset).
 template <int TILE>

@@ -4,10 +4,12 @@
 
 #include <stdint.h>
 
+#ifndef SV_HOST_DEVICE
 #if defined(__HIPCC__)
 #define SV_HOST_DEVICE __host__ __device__
 #else
 #define SV_HOST_DEVICE
+#endif
 #endif
 
 namespace sv {
