@@ -38,20 +38,21 @@ namespace sv {
 
 constexpr int kApplyTile = 32;   // tokens per wave tile (the N dimension of the 32x32x16 MFMA)
 
-// The state of one head as MFMA A operands for the 64 output features of value
+// The state of one head as MFMA A operands for the 32*NB output features of value
 // block vb, per lane (m = lane%32, g = lane/32).
 //   S rows: MFMA row m of row block rb stands for output feature
-//     64*vb + F(rb, m),  F(rb, m) = 32*((m/4)%2) + 16*rb + 4*(m/8) + m%4,
+//     32*NB*vb + F(rb, m),  F(rb, m) = 16*NB*((m/4)%2) + 16*rb + 4*(m/8) + m%4,
 //   chosen so that accumulator register i of a lane in half g' = lane/32 is
-//   output feature 64*vb + 32*g' + 16*rb + i of the lane's token.
+//   output feature 32*NB*vb + 16*NB*g' + 16*rb + i of the lane's token (NB = 2: 32
+//   consecutive features per lane, NB = 1: 16).
 //   z rows: row 0 = hi(z), row 1 = lo(z), rows 2..31 = 0.
 // The contraction runs over DP key features in DP/16 k-steps; S is d x d (row
 // length d) and z has d entries, anything past d counts as zero.
-template <int DP, bool HILO>
+template <int DP, bool HILO, int NB = 2>
 struct ApplyOperands {
     static constexpr int NS = HILO ? 2 : 1;
     static constexpr int KS = DP / 16;
-    bf16x8 s[NS][2][KS];   // [hi/lo][row block][k-step]
+    bf16x8 s[NS][NB][KS];  // [hi/lo][row block][k-step]
     bf16x8 zrow[KS];       // [k-step]
 
     // COHERENT: the state was written by another workgroup of this same kernel.
@@ -61,8 +62,8 @@ struct ApplyOperands {
     {
         const int m = lane & 31, g = lane >> 5;
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
-            const int F = 64 * vb + 32 * ((m >> 2) & 1) + 16 * rb + 4 * (m >> 3) + (m & 3);
+        for (int rb = 0; rb < NB; ++rb) {
+            const int F = 32 * NB * vb + 16 * NB * ((m >> 2) & 1) + 16 * rb + 4 * (m >> 3) + (m & 3);
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 float sv_[8];

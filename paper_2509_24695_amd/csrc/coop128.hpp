@@ -159,13 +159,17 @@ __device__ __forceinline__ void state_accumulate_coop(CoopStateStream<DEPTH, ROP
 
 // ---- apply ---------------------------------------------------------------------------------------
 
-// One wave's share of the workgroup's Q/O stream: rows 16*wave .. +16 of every
-// step of 16*WAVES tokens (WAVES = 4: a pair of 32-token tiles; WAVES = 2: one tile), both for the
-// loads of Q and for the stores of O.
-template <int DEPTH, int ROPE, int WAVES = 4>
+// One wave's share of the workgroup's Q/O stream, both for the loads of Q and for the stores of O.
+// A wave computes NB blocks of 32 output features, so 4/NB waves work on one 32-token tile and a
+// workgroup of WAVES waves takes WAVES*NB/4 tiles per step; its rows are dealt evenly to the waves:
+//   WAVES = 4, NB = 2   a pair of tiles per step, 16 rows per wave (the one-launch block step)
+//   WAVES = 2, NB = 2   one tile, 16 rows per wave
+//   WAVES = 4, NB = 1   one tile, 8 rows per wave, few enough registers for two waves per SIMD
+template <int DEPTH, int ROPE, int WAVES = 4, int NB = 2>
 struct CoopApplyStream {
-    static constexpr int NLD = 4;
-    static constexpr int STEP = 16 * WAVES;   // tokens per workgroup step
+    static constexpr int STEP = 8 * WAVES * NB;   // tokens per workgroup step
+    static constexpr int ROWS = STEP / WAVES;     // rows per wave
+    static constexpr int NLD = ROWS / 4;          // 4 rows per load instruction
     rsrc_t rQ, rO;
     uint32_t row_bytes, lane_off;
     bool valid;
@@ -178,9 +182,9 @@ struct CoopApplyStream {
                                                int lane, const TileWalk &w)
         : rQ(make_rsrc(Qh, (uint32_t)t1 * (uint32_t)stride_n * 2u)),
           rO(make_rsrc(Oh, (uint32_t)t1 * (uint32_t)stride_n * 2u)), row_bytes((uint32_t)stride_n * 2u),
-          lane_off((uint32_t)(16 * wave + (lane >> 4)) * (uint32_t)stride_n * 2u + (uint32_t)(lane & 15) * 16u),
+          lane_off((uint32_t)(ROWS * wave + (lane >> 4)) * (uint32_t)stride_n * 2u + (uint32_t)(lane & 15) * 16u),
           valid((lane & 15) * 8 < d), walk(w),
-          rot(rope, t1, d, 16 * wave + (lane >> 4), 4, 4 * (lane & 15), 1, lds_tab) {}
+          rot(rope, t1, d, ROWS * wave + (lane >> 4), 4, 4 * (lane & 15), 1, lds_tab) {}
 
     __device__ __forceinline__ void request(int s, int i)
     {
@@ -191,8 +195,8 @@ struct CoopApplyStream {
     }
 };
 
-template <int FROM, int TO, int DEPTH, int ROPE, int WAVES>
-__device__ __forceinline__ void coop_apply_prefetch(CoopApplyStream<DEPTH, ROPE, WAVES> &st)
+template <int FROM, int TO, int DEPTH, int ROPE, int WAVES, int NB>
+__device__ __forceinline__ void coop_apply_prefetch(CoopApplyStream<DEPTH, ROPE, WAVES, NB> &st)
 {
 #pragma unroll
     for (int s = FROM; s < TO; ++s) {
@@ -202,25 +206,25 @@ __device__ __forceinline__ void coop_apply_prefetch(CoopApplyStream<DEPTH, ROPE,
 }
 
 // LDS of the apply phase: the Q tiles of a step (with ROPE also their rotated copy) and its O tiles.
-template <int ROPE, int WAVES = 4> __host__ __device__ constexpr int coop_apply_lds_bytes() {
-    return (ROPE ? 3 : 2) * (WAVES / 2) * kCoopTile;
+template <int ROPE, int WAVES = 4, int NB = 2> __host__ __device__ constexpr int coop_apply_lds_bytes() {
+    return (ROPE ? 3 : 2) * (WAVES * NB / 4) * kCoopTile;
 }
 
-// Applies the state panel in `A` (value block wave%2) to tile wave/2 of every step
+// Applies the state panel in `A` (value block wave % (4/NB)) to tile wave / (4/NB) of every step
 // of the workgroup's share.  Must be called by all waves of the workgroup.
-template <bool HILO, int DEPTH, int ROPE, int WAVES>
-__device__ __forceinline__ void apply_tiles_coop(CoopApplyStream<DEPTH, ROPE, WAVES> &st, unsigned char *lds, int wave,
-                                                 int lane, const ApplyOperands<128, HILO> &A, float eps)
+template <bool HILO, int DEPTH, int ROPE, int WAVES, int NB>
+__device__ __forceinline__ void apply_tiles_coop(CoopApplyStream<DEPTH, ROPE, WAVES, NB> &st, unsigned char *lds,
+                                                 int wave, int lane, const ApplyOperands<128, HILO, NB> &A, float eps)
 {
     constexpr int NS = HILO ? 2 : 1;
-    constexpr int STEP = 16 * WAVES, TILES = WAVES / 2;
-    const int t = wave >> 1, vb = wave & 1;
+    constexpr int STEP = 8 * WAVES * NB, TILES = WAVES * NB / 4, ROWS = STEP / WAVES, NLD = ROWS / 4, WT = 4 / NB;
+    const int t = wave / WT, vb = wave % WT;
     const int n = lane & 31, g = lane >> 5;
     unsigned char *bufQ = lds, *bufR = ROPE ? lds + TILES * kCoopTile : lds,
                   *bufO = lds + (ROPE ? 2 : 1) * TILES * kCoopTile;
-    const int wr_off = (16 * wave + (lane >> 4)) * kCoopRow + (lane & 15) * 16;   // the wave's own rows
+    const int wr_off = (ROWS * wave + (lane >> 4)) * kCoopRow + (lane & 15) * 16;   // the wave's own rows
     const unsigned char *brow = bufQ + (32 * t + n) * kCoopRow, *rrow = bufR + (32 * t + n) * kCoopRow;
-    unsigned char *orow = bufO + (32 * t + n) * kCoopRow + (64 * vb + 32 * g) * 2;
+    unsigned char *orow = bufO + (32 * t + n) * kCoopRow + (32 * NB * vb + 16 * NB * g) * 2;
 
     auto round = [&](int i0) __attribute__((always_inline)) {
 #pragma unroll
@@ -231,7 +235,7 @@ __device__ __forceinline__ void apply_tiles_coop(CoopApplyStream<DEPTH, ROPE, WA
             if (valid) {
                 st.rot.begin_tile(st.walk.template token<STEP>(i0 + s));
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
+                for (int j = 0; j < NLD; ++j) {
                     const u32x4 pq = relu_bf16x8(st.q[s][j]);                          // phi(Q)
                     *reinterpret_cast<u32x4 *>(bufQ + wr_off + 4 * j * kCoopRow) = pq;
                     if (ROPE) *reinterpret_cast<u32x4 *>(bufR + wr_off + 4 * j * kCoopRow) = st.rot.rotate(s, j, pq);
@@ -239,14 +243,18 @@ __device__ __forceinline__ void apply_tiles_coop(CoopApplyStream<DEPTH, ROPE, WA
             }
             st.request(s, i0 + s + DEPTH);   // refill this stage: DEPTH pairs ahead
             __builtin_amdgcn_sched_barrier(0);
-            u32x4 o[4] = {};
+            u32x4 o[NLD] = {};
             if (valid) {
                 // Q tiles complete.  They are overwritten in the next round, by waves that have
                 // passed the second barrier below, which every wave reaches after its reads.
                 lds_barrier();
-                f32x16 acc[2], accz;
+                f32x16 acc[NB], accz;
 #pragma unroll
-                for (int i = 0; i < 16; ++i) { acc[0][i] = 0.f; acc[1][i] = 0.f; accz[i] = 0.f; }
+                for (int i = 0; i < 16; ++i) {
+#pragma unroll
+                    for (int rb = 0; rb < NB; ++rb) acc[rb][i] = 0.f;
+                    accz[i] = 0.f;
+                }
 #pragma unroll
                 for (int ks = 0; ks < 8; ++ks) {
                     const bf16x8 bq = *reinterpret_cast<const bf16x8 *>(brow + (16 * ks + 8 * g) * 2);
@@ -254,15 +262,16 @@ __device__ __forceinline__ void apply_tiles_coop(CoopApplyStream<DEPTH, ROPE, WA
                     accz = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.zrow[ks], bq, accz, 0, 0, 0);
 #pragma unroll
                     for (int p = NS - 1; p >= 0; --p) {      // small (lo) terms first
-                        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.s[p][0][ks], br, acc[0], 0, 0, 0);
-                        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.s[p][1][ks], br, acc[1], 0, 0, 0);
+#pragma unroll
+                        for (int rb = 0; rb < NB; ++rb)
+                            acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.s[p][rb][ks], br, acc[rb], 0, 0, 0);
                     }
                 }
                 float den = accz[1] + accz[0];      // rows 0 (hi) and 1 (lo) of the z block
                 den = __shfl(den, n);
                 const float inv = 1.0f / (den + eps);
 #pragma unroll
-                for (int rb = 0; rb < 2; ++rb) {
+                for (int rb = 0; rb < NB; ++rb) {
                     const f32x16 &a = acc[rb];
                     u32x4 lo4, hi4;
                     lo4.x = pack_bf16x2(a[0] * inv, a[1] * inv);
@@ -280,10 +289,10 @@ __device__ __forceinline__ void apply_tiles_coop(CoopApplyStream<DEPTH, ROPE, WA
                 // barrier of the next round, which every wave reaches after the reads below.
                 lds_barrier();
 #pragma unroll
-                for (int j = 0; j < 4; ++j) o[j] = *reinterpret_cast<const u32x4 *>(bufO + wr_off + 4 * j * kCoopRow);
+                for (int j = 0; j < NLD; ++j) o[j] = *reinterpret_cast<const u32x4 *>(bufO + wr_off + 4 * j * kCoopRow);
             }
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < NLD; ++j)
                 store_stream16(st.rO, out_off + st.lane_off + (uint32_t)j * 4u * st.row_bytes, o[j]);
         }
     };
@@ -343,12 +352,13 @@ __global__ __launch_bounds__(256, 1) void state_mfma_d128(
     }
 }
 
-// Apply for d = 112 or 128.  grid = (C, B*H), block = 64 * WAVES; workgroup c owns the
-// steps c + C*i of the ceil((t1-t0)/(16*WAVES)) steps of 16*WAVES tokens.  WAVES = 2: two
-// workgroups share a compute unit (one wave per SIMD either way) and only the two waves that work
-// on the same tile meet at its barriers.
-template <bool HILO, int DEPTH, int ROPE, int WAVES>
-__global__ __launch_bounds__(64 * WAVES, 1) void apply_mfma_d128(
+// Apply for d = 112 or 128.  grid = (C, B*H), block = 64 * WAVES; workgroup c owns the steps
+// c + C*i of the ceil((t1-t0)/STEP) steps of STEP = 8*WAVES*NB tokens (see CoopApplyStream).
+// With NB = 1 a wave keeps one 128 x 32 panel of S and fits in half a SIMD's registers: two
+// workgroups (eight waves) share a compute unit, and while one wave waits at a barrier or works on
+// the vector ALU (ReLU, rotation, scaling) the other wave of its SIMD feeds the matrix core.
+template <bool HILO, int DEPTH, int ROPE, int WAVES, int NB>
+__global__ __launch_bounds__(64 * WAVES, NB == 1 ? 2 : 1) void apply_mfma_d128(
     const uint16_t *__restrict__ Q, uint16_t *__restrict__ O, RopeArg rope, TokStrides st, int H,
     int d, int t0, int t1, int C, const float *__restrict__ S, const float *__restrict__ z, float eps)
 {
@@ -359,18 +369,18 @@ __global__ __launch_bounds__(64 * WAVES, 1) void apply_mfma_d128(
     const int b = bh / H, h = bh % H;
     const uint16_t *Qh = Q + b * st.b + h * st.h;
     uint16_t *Oh = O + b * st.b + h * st.h;
-    constexpr int STEP = 16 * WAVES;
+    constexpr int STEP = 8 * WAVES * NB;
     const int n_steps = (t1 - t0 + STEP - 1) / STEP;
 
-    CoopApplyStream<DEPTH, ROPE, WAVES> stream(Qh, Oh, rope, lds + coop_apply_lds_bytes<ROPE, WAVES>(), st.n, t1, d, wave,
-                                               lane, TileWalk(t0, c, C, n_steps, bh));
+    CoopApplyStream<DEPTH, ROPE, WAVES, NB> stream(Qh, Oh, rope, lds + coop_apply_lds_bytes<ROPE, WAVES, NB>(), st.n, t1,
+                                                   d, wave, lane, TileWalk(t0, c, C, n_steps, bh));
     coop_apply_prefetch<0, DEPTH>(stream);   // in flight while S is fetched
     if (ROPE == kRope3D) {
-        rope3d_lds_fill(lds + coop_apply_lds_bytes<ROPE, WAVES>(), rope.r3);
+        rope3d_lds_fill(lds + coop_apply_lds_bytes<ROPE, WAVES, NB>(), rope.r3);
         __syncthreads();
     }
-    ApplyOperands<128, HILO> A;
-    A.template load<false>(S + (size_t)bh * d * d, z + (size_t)bh * d, d, wave & 1, lane);
+    ApplyOperands<128, HILO, NB> A;
+    A.template load<false>(S + (size_t)bh * d * d, z + (size_t)bh * d, d, wave % (4 / NB), lane);
     apply_tiles_coop<HILO>(stream, lds, wave, lane, A, eps);
 }
 

@@ -29,7 +29,7 @@ constexpr int kVersion = 500;   // 0.5.0
 // flight per wave, [DP = 128][RoPE mode: none, table, 3-D]: a stage of the table mode also
 // holds its table rows.
 constexpr int kStateTile = 32, kStateWaves = 4, kApplyWaves = 4;
-constexpr int kCoopApplyWaves = 2;            // d = 112/128 apply: two workgroups of two waves per compute unit
+constexpr int kCoopApplyWaves = 4, kCoopApplyNB = 1;   // d = 112/128 apply: one 128 x 32 panel of S per wave, two workgroups per compute unit
 constexpr int kStateDepth[2][3] = {{2, 2, 2}, {8, 4, 4}};
 constexpr int kWideStateDepth = 3;            // 16-token tiles in flight per wave of the wave-private d = 112/128 state kernel
 constexpr int kApplyDepth[2][3] = {{2, 2, 2}, {2, 2, 2}};
@@ -84,16 +84,16 @@ template <int ROPE> struct Kernels<128, ROPE> {
                                              : state_mfma_d128<kStateDepth[W][ROPE], true, ROPE>;
     static constexpr auto state_partial = kWideState ? state_mfma_wide<kWideStateDepth, false, kWideRope>
                                                      : state_mfma_d128<kStateDepth[W][ROPE], false, ROPE>;
-    static constexpr auto apply = apply_mfma_d128<kApplyHiLo, kApplyDepth[W][ROPE], ROPE, kCoopApplyWaves>;
+    static constexpr auto apply = apply_mfma_d128<kApplyHiLo, kApplyDepth[W][ROPE], ROPE, kCoopApplyWaves, kCoopApplyNB>;
     static constexpr auto fused = block_step_mfma<128, kStateTile, kStateWaves, kFusedStateDepth[W][ROPE], kApplyHiLo,
                                                   kFusedApplyDepth[W][ROPE], ROPE>;
     static constexpr int state_lds = kWideState ? kWideLdsBytes : state_d128_lds_bytes<ROPE>() + kTab;
-    static constexpr int apply_lds = coop_apply_lds_bytes<ROPE, kCoopApplyWaves>() + kTab;
+    static constexpr int apply_lds = coop_apply_lds_bytes<ROPE, kCoopApplyWaves, kCoopApplyNB>() + kTab;
     static constexpr int fused_lds = block_step_lds_bytes<128, kStateTile, kStateWaves, ROPE>() + kTab;
     static constexpr int state_wg_tokens = kWideState ? 4 * kWideTile : 32;   // four private tiles, or one shared
     static constexpr int fused_wg_tokens = 32;   // the one-launch block step shares one tile in its state phase
-    static constexpr int apply_wg_tokens = 16 * kCoopApplyWaves;   // the waves of a workgroup share its tiles
-    static constexpr int apply_threads = 64 * kCoopApplyWaves, apply_wgs_per_cu = 4 / kCoopApplyWaves;
+    static constexpr int apply_wg_tokens = 8 * kCoopApplyWaves * kCoopApplyNB;   // the waves of a workgroup share its tiles
+    static constexpr int apply_threads = 64 * kCoopApplyWaves, apply_wgs_per_cu = 8 / (kCoopApplyWaves * kCoopApplyNB);
 };
 
 template <int DP, int ROPE> void init_kernels(Device &d)
