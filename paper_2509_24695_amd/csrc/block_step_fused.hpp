@@ -17,32 +17,30 @@
 #pragma once
 
 #include "apply_mfma.hpp"
-#include "coop128.hpp"
 #include "state_mfma.hpp"
 
 namespace sv {
 
-template <int DP, int TILE, int WAVES, int ROPE>
+template <int TILE, int WAVES, int ROPE>
 __host__ __device__ constexpr int block_step_lds_bytes() {
-    constexpr int s = DP == 64 ? state_lds_bytes<TILE, WAVES>() : state_d128_lds_bytes<ROPE>();
-    constexpr int a = (DP == 64 ? apply_lds_bytes<WAVES, ROPE>() : coop_apply_lds_bytes<ROPE>()) + kEpochLdsBytes;
+    constexpr int s = state_lds_bytes<TILE, WAVES>();
+    constexpr int a = apply_lds_bytes<WAVES, ROPE>() + kEpochLdsBytes;
     return s > a ? s : a;   // both include the epoch word, which sits at the very end
 }
 
-// grid = (C, B*H) with C*B*H <= resident workgroup capacity, block = 64*WAVES.
-// DP = 64 serves d = 64 (waves work alone, as in state_mfma_d64 and apply_mfma_d64),
-// DP = 128 serves d = 112 and 128 (waves share tiles, as in state_mfma_d128 and
-// apply_mfma_d128; WAVES must be 4).
+// grid = (C, B*H) with C*B*H <= resident workgroup capacity, block = 64*WAVES.  Waves work alone,
+// as in state_mfma_d64 and apply_mfma_d64.  (d = 112 and 128 take the step as two launches: there
+// the state and the apply kernel want different workgroup shapes, and one launch measured 2-8 us
+// slower at every block size.)
 // ROPE: keys and queries are rotated after the ReLU in the numerator path (table row = token of the block).
-template <int DP, int TILE, int WAVES, int DEPTH_S, bool HILO, int DEPTH_A, int ROPE>
+template <int TILE, int WAVES, int DEPTH_S, bool HILO, int DEPTH_A, int ROPE>
 __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
-    uint16_t *__restrict__ O, RopeArg rope, TokStrides st, int H, int d_arg, int N, int C,
+    uint16_t *__restrict__ O, RopeArg rope, TokStrides st, int H, int N, int C,
     const float *S_in, const float *z_in, float *S_out, float *z_out, float eps, void *__restrict__ ws,
     unsigned long long epoch, uint32_t spin_limit)
 {
     static_assert(TILE == kApplyTile, "both phases walk tiles of the same size");
-    static_assert(DP == 64 || WAVES == 4, "the cooperative kernels are written for four waves");
     constexpr int THREADS = 64 * WAVES;
     constexpr int kTileBytes = TILE * kRowBytes;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -51,7 +49,7 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
     const int lane = tid & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = blockIdx.x, bh = blockIdx.y, BH = gridDim.y;
     const int b = bh / H, h = bh % H;
-    const int d = DP == 64 ? 64 : d_arg, elems = d * d + d;
+    constexpr int d = 64, elems = d * d + d;
     const int64_t head_off = b * st.b + h * st.h;
     const int n_tiles = (N + TILE - 1) / TILE;
     // the carried state is read from S_in, z_in and the updated one written to S_out, z_out: the same
@@ -62,74 +60,48 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
     EpochSource es;
     es.begin(ws, BH, elems, epoch);
     // kRope3D: the tables sit behind everything else in LDS and live through both phases
-    const unsigned char *lds_tab = lds + block_step_lds_bytes<DP, TILE, WAVES, ROPE>();
+    const unsigned char *lds_tab = lds + block_step_lds_bytes<TILE, WAVES, ROPE>();
 
     // Once all partials of the head are there, fold this workgroup's slice into S, z, then wait for
     // the other slices.
     auto agree_on_state = [&]() __attribute__((always_inline)) {
         epoch = es.resolve(reinterpret_cast<unsigned long long *>(
-            lds + block_step_lds_bytes<DP, TILE, WAVES, ROPE>() - kEpochLdsBytes));
+            lds + block_step_lds_bytes<TILE, WAVES, ROPE>() - kEpochLdsBytes));
         state_publish_and_wait(ws, BH, elems, bh, c, C, 0, epoch, spin_limit, lane);
         state_finalize_slice<THREADS, true>(partials, c, C, d, Sc, zc, Sh, zh);
         state_publish_and_wait(ws, BH, elems, bh, c, C, 1, epoch, spin_limit, lane);
     };
 
-    if constexpr (DP == 64) {
-        // ---- this wave's first two tiles of Q_b are requested right away: they arrive during the
-        //      state phase and make no later load wait behind them --------------------------------
-        constexpr int kEarly = DEPTH_A < 2 ? DEPTH_A : 2;
-        const TileWalk walk(0, WAVES * c + wave, WAVES * C, n_tiles, bh);
-        ApplyStream<DEPTH_A, ROPE> qstream(Q + head_off, O + head_off, rope, lds_tab, st.n, N, lane, walk);
-        apply_prefetch<0, kEarly>(qstream);
+    // ---- this wave's first two tiles of Q_b are requested right away: they arrive during the
+    //      state phase and make no later load wait behind them --------------------------------
+    constexpr int kEarly = DEPTH_A < 2 ? DEPTH_A : 2;
+    const TileWalk walk(0, WAVES * c + wave, WAVES * C, n_tiles, bh);
+    ApplyStream<DEPTH_A, ROPE> qstream(Q + head_off, O + head_off, rope, lds_tab, st.n, N, lane, walk);
+    apply_prefetch<0, kEarly>(qstream);
 
-        // ---- fold this workgroup's share of K_b, V_b ----------------------------------------------
-        {
-            StateAcc acc;
-            acc.clear();
-            StateStream<TILE, DEPTH_S, ROPE> kvstream(K + head_off, V + head_off, rope, lds_tab, st.n, N, lane, walk);
-            unsigned char *tileK = lds + wave * 2 * kTileBytes;
-            state_prefetch(kvstream);
-            if (ROPE == kRope3D) {
-                rope3d_lds_fill(lds + block_step_lds_bytes<DP, TILE, WAVES, ROPE>(), rope.r3);
-                __syncthreads();
-            }
-            state_accumulate(kvstream, tileK, tileK + kTileBytes, lane, acc);
-            // the rest of this wave's Q prefetch streams in while the head's state is being agreed on
-            apply_prefetch<kEarly, DEPTH_A>(qstream);
-            state_wg_reduce_store<WAVES, ROPE != kRopeNone>(acc, reinterpret_cast<float *>(lds), wave, lane,
-                                               partials + (size_t)c * elems);
+    // ---- fold this workgroup's share of K_b, V_b ----------------------------------------------
+    {
+        StateAcc acc;
+        acc.clear();
+        StateStream<TILE, DEPTH_S, ROPE> kvstream(K + head_off, V + head_off, rope, lds_tab, st.n, N, lane, walk);
+        unsigned char *tileK = lds + wave * 2 * kTileBytes;
+        state_prefetch(kvstream);
+        if (ROPE == kRope3D) {
+            rope3d_lds_fill(lds + block_step_lds_bytes<TILE, WAVES, ROPE>(), rope.r3);
+            __syncthreads();
         }
-        agree_on_state();
-
-        // ---- apply the updated state to this workgroup's share of Q_b --------------------------------
-        ApplyOperands<64, HILO> A;
-        A.template load<true>(Sh, zh, 64, 0, lane);
-        apply_tiles<HILO>(qstream, lds + wave * apply_wave_lds_bytes<ROPE>(), lane, A, eps);
-    } else {
-        constexpr int kEarly = DEPTH_A < 2 ? DEPTH_A : 2;
-        CoopApplyStream<DEPTH_A, ROPE> qstream(Q + head_off, O + head_off, rope, lds_tab, st.n, N, d, wave, lane,
-                                               TileWalk(0, c, C, (N + 63) / 64, bh));
-        coop_apply_prefetch<0, kEarly>(qstream);
-        {
-            StateAcc acc;
-            acc.clear();
-            CoopStateStream<DEPTH_S, ROPE> kvstream(K + head_off, V + head_off, rope, lds_tab, st.n, N, d, wave, lane,
-                                                    TileWalk(0, c, C, n_tiles, bh));
-            coop_state_prefetch(kvstream);
-            if (ROPE == kRope3D) {
-                rope3d_lds_fill(lds + block_step_lds_bytes<DP, TILE, WAVES, ROPE>(), rope.r3);
-                __syncthreads();
-            }
-            state_accumulate_coop(kvstream, lds, wave, lane, wave & 1, wave >> 1, acc);
-            coop_apply_prefetch<kEarly, DEPTH_A>(qstream);
-            state_wg_quadrant_store(acc, reinterpret_cast<float *>(lds), wave, lane, d, partials + (size_t)c * elems);
-        }
-        agree_on_state();
-        __syncthreads();   // the reduction slots in LDS are dead before the apply phase reuses the space
-        ApplyOperands<128, HILO> A;
-        A.template load<true>(Sh, zh, d, wave & 1, lane);
-        apply_tiles_coop<HILO>(qstream, lds, wave, lane, A, eps);
+        state_accumulate(kvstream, tileK, tileK + kTileBytes, lane, acc);
+        // the rest of this wave's Q prefetch streams in while the head's state is being agreed on
+        apply_prefetch<kEarly, DEPTH_A>(qstream);
+        state_wg_reduce_store<WAVES, ROPE != kRopeNone>(acc, reinterpret_cast<float *>(lds), wave, lane,
+                                           partials + (size_t)c * elems);
     }
+    agree_on_state();
+
+    // ---- apply the updated state to this workgroup's share of Q_b --------------------------------
+    ApplyOperands<64, HILO> A;
+    A.template load<true>(Sh, zh, 64, 0, lane);
+    apply_tiles<HILO>(qstream, lds + wave * apply_wave_lds_bytes<ROPE>(), lane, A, eps);
 }
 
 }  // namespace sv

@@ -162,10 +162,10 @@ __device__ __forceinline__ void state_accumulate_coop(CoopStateStream<DEPTH, ROP
 // One wave's share of the workgroup's Q/O stream, both for the loads of Q and for the stores of O.
 // A wave computes NB blocks of 32 output features, so 4/NB waves work on one 32-token tile and a
 // workgroup of WAVES waves takes WAVES*NB/4 tiles per step; its rows are dealt evenly to the waves:
-//   WAVES = 4, NB = 2   a pair of tiles per step, 16 rows per wave (the one-launch block step)
+//   WAVES = 4, NB = 1   one tile, 8 rows per wave, few enough registers for two waves per SIMD (in use)
+//   WAVES = 4, NB = 2   a pair of tiles per step, 16 rows per wave
 //   WAVES = 2, NB = 2   one tile, 16 rows per wave
-//   WAVES = 4, NB = 1   one tile, 8 rows per wave, few enough registers for two waves per SIMD
-template <int DEPTH, int ROPE, int WAVES = 4, int NB = 2>
+template <int DEPTH, int ROPE, int WAVES, int NB>
 struct CoopApplyStream {
     static constexpr int STEP = 8 * WAVES * NB;   // tokens per workgroup step
     static constexpr int ROWS = STEP / WAVES;     // rows per wave
@@ -206,7 +206,7 @@ __device__ __forceinline__ void coop_apply_prefetch(CoopApplyStream<DEPTH, ROPE,
 }
 
 // LDS of the apply phase: the Q tiles of a step (with ROPE also their rotated copy) and its O tiles.
-template <int ROPE, int WAVES = 4, int NB = 2> __host__ __device__ constexpr int coop_apply_lds_bytes() {
+template <int ROPE, int WAVES, int NB> __host__ __device__ constexpr int coop_apply_lds_bytes() {
     return (ROPE ? 3 : 2) * (WAVES * NB / 4) * kCoopTile;
 }
 

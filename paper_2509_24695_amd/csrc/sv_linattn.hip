@@ -33,8 +33,8 @@ constexpr int kCoopApplyWaves = 4, kCoopApplyNB = 1;   // d = 112/128 apply: one
 constexpr int kStateDepth[2][3] = {{2, 2, 2}, {8, 4, 4}};
 constexpr int kWideStateDepth = 3;            // 16-token tiles in flight per wave of the wave-private d = 112/128 state kernel
 constexpr int kApplyDepth[2][3] = {{2, 2, 2}, {2, 2, 2}};
-constexpr int kFusedStateDepth[2][3] = {{2, 2, 2}, {4, 2, 4}};
-constexpr int kFusedApplyDepth[2][3] = {{6, 2, 6}, {2, 2, 2}};   // Q tiles held in registers across the in-kernel waits
+constexpr int kFusedStateDepth[3] = {2, 2, 2};   // one-launch block step (d = 64), by RoPE mode
+constexpr int kFusedApplyDepth[3] = {6, 2, 6};   // Q tiles held in registers across the in-kernel waits
 constexpr bool kApplyHiLo = true;
 constexpr uint32_t kSpinLimit = 1u << 24;      // polls of ~100 ns: far beyond any real wait
 
@@ -49,7 +49,7 @@ struct Device {
     int num_cu = 0;
     // how many workgroups fit on the device at once, [DP = 128][RoPE mode]
     int state_resident_wgs[2][3] = {{0, 0, 0}, {0, 0, 0}};   // state kernel with in-kernel finalize
-    int fused_resident_wgs[2][3] = {{0, 0, 0}, {0, 0, 0}};   // one-launch block step
+    int fused_resident_wgs[3] = {0, 0, 0};                   // one-launch block step (d = 64), by RoPE mode
     bool ok = false;
 };
 
@@ -62,11 +62,11 @@ template <int ROPE> struct Kernels<64, ROPE> {
     static constexpr auto state = state_mfma_d64<kStateTile, kStateWaves, kStateDepth[W][ROPE], true, ROPE>;
     static constexpr auto state_partial = state_mfma_d64<kStateTile, kStateWaves, kStateDepth[W][ROPE], false, ROPE>;
     static constexpr auto apply = apply_mfma_d64<kApplyHiLo, kApplyWaves, kApplyDepth[W][ROPE], ROPE>;
-    static constexpr auto fused = block_step_mfma<64, kStateTile, kStateWaves, kFusedStateDepth[W][ROPE], kApplyHiLo,
-                                                  kFusedApplyDepth[W][ROPE], ROPE>;
+    static constexpr auto fused = block_step_mfma<kStateTile, kStateWaves, kFusedStateDepth[ROPE], kApplyHiLo,
+                                                  kFusedApplyDepth[ROPE], ROPE>;
     static constexpr int state_lds = state_lds_bytes<kStateTile, kStateWaves>() + kTab;
     static constexpr int apply_lds = apply_lds_bytes<kApplyWaves, ROPE>() + kTab;
-    static constexpr int fused_lds = block_step_lds_bytes<64, kStateTile, kStateWaves, ROPE>() + kTab;
+    static constexpr int fused_lds = block_step_lds_bytes<kStateTile, kStateWaves, ROPE>() + kTab;
     // tokens one workgroup covers per round of its tile walk
     static constexpr int state_wg_tokens = kStateTile * kStateWaves;
     static constexpr int fused_wg_tokens = state_wg_tokens;
@@ -85,13 +85,9 @@ template <int ROPE> struct Kernels<128, ROPE> {
     static constexpr auto state_partial = kWideState ? state_mfma_wide<kWideStateDepth, false, kWideRope>
                                                      : state_mfma_d128<kStateDepth[W][ROPE], false, ROPE>;
     static constexpr auto apply = apply_mfma_d128<kApplyHiLo, kApplyDepth[W][ROPE], ROPE, kCoopApplyWaves, kCoopApplyNB>;
-    static constexpr auto fused = block_step_mfma<128, kStateTile, kStateWaves, kFusedStateDepth[W][ROPE], kApplyHiLo,
-                                                  kFusedApplyDepth[W][ROPE], ROPE>;
     static constexpr int state_lds = kWideState ? kWideLdsBytes : state_d128_lds_bytes<ROPE>() + kTab;
     static constexpr int apply_lds = coop_apply_lds_bytes<ROPE, kCoopApplyWaves, kCoopApplyNB>() + kTab;
-    static constexpr int fused_lds = block_step_lds_bytes<128, kStateTile, kStateWaves, ROPE>() + kTab;
     static constexpr int state_wg_tokens = kWideState ? 4 * kWideTile : 32;   // four private tiles, or one shared
-    static constexpr int fused_wg_tokens = 32;   // the one-launch block step shares one tile in its state phase
     static constexpr int apply_wg_tokens = 8 * kCoopApplyWaves * kCoopApplyNB;   // the waves of a workgroup share its tiles
     static constexpr int apply_threads = 64 * kCoopApplyWaves, apply_wgs_per_cu = 8 / (kCoopApplyWaves * kCoopApplyNB);
 };
@@ -103,13 +99,15 @@ template <int DP, int ROPE> void init_kernels(Device &d)
     (void)hipFuncSetAttribute(reinterpret_cast<const void *>(KN::state), attr, KN::state_lds);
     (void)hipFuncSetAttribute(reinterpret_cast<const void *>(KN::state_partial), attr, KN::state_lds);
     (void)hipFuncSetAttribute(reinterpret_cast<const void *>(KN::apply), attr, KN::apply_lds);
-    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(KN::fused), attr, KN::fused_lds);
     int per_cu = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(KN::fused),
-                                                     64 * kStateWaves, KN::fused_lds) != hipSuccess)
+    if constexpr (DP == 64) {                      // the one-launch block step exists for d = 64 only
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(KN::fused), attr, KN::fused_lds);
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(KN::fused),
+                                                         64 * kStateWaves, KN::fused_lds) != hipSuccess)
+            per_cu = 0;
+        d.fused_resident_wgs[ROPE] = per_cu * d.num_cu;
         per_cu = 0;
-    d.fused_resident_wgs[KN::W][ROPE] = per_cu * d.num_cu;
-    per_cu = 0;
+    }
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(KN::state),
                                                      64 * kStateWaves, KN::state_lds) != hipSuccess)
         per_cu = 0;
@@ -456,21 +454,24 @@ sv_status do_block_step(const void *Qb, const void *Kb, const void *Vb, const sv
         z_out = S_out + (size_t)s.BH * s.d * s.d;
     }
     auto hs = static_cast<hipStream_t>(stream);
-    if (mfma_path(s, rope)) {
+    if (mfma_path(s, rope) && s.d == 64) {             // one launch; d = 112, 128 are faster as two (measured)
         const Device &dev = device_info();
         if (!dev.ok) return SV_ERR_LAUNCH;
         bool launched = false;
-        with_mfma_kernels(s.d, rope.mode, [&](auto kn) {
+        auto launch = [&](auto kn) {
             using KN = decltype(kn);
             // One launch when the whole grid can be resident at once (needed by the in-kernel waits).
             const int C = plan_chunks(s.BH, s.N, KN::fused_wg_tokens, dev.num_cu);
-            if ((int64_t)C * s.BH > dev.fused_resident_wgs[KN::W][rope.mode]) return;
+            if ((int64_t)C * s.BH > dev.fused_resident_wgs[rope.mode]) return;
             KN::fused<<<dim3(C, s.BH), 64 * kStateWaves, KN::fused_lds, hs>>>(
                 static_cast<const uint16_t *>(Qb), static_cast<const uint16_t *>(Kb),
-                static_cast<const uint16_t *>(Vb), static_cast<uint16_t *>(Ob), rope.arg, s.st, s.H, s.d, s.N, C, S_in,
+                static_cast<const uint16_t *>(Vb), static_cast<uint16_t *>(Ob), rope.arg, s.st, s.H, s.N, C, S_in,
                 z_in, S_out, z_out, eps, workspace, next_epoch(), kSpinLimit);
             launched = true;
-        });
+        };
+        if (rope.mode == kRope3D) launch(Kernels<64, kRope3D>{});
+        else if (rope.mode == kRopeTable) launch(Kernels<64, kRopeTable>{});
+        else launch(Kernels<64, kRopeNone>{});
         if (launched) return launch_status();
     }
     rc = enqueue_state(Kb, Vb, rope, s, 0, s.N, S_in, z_in, S_out, z_out, workspace, hs);
