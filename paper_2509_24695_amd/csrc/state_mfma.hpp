@@ -375,27 +375,46 @@ __device__ __forceinline__ void state_finalize_slice(const float *__restrict__ p
                                                      const float *S_in, const float *z_in, float *S_out,
                                                      float *z_out)
 {
-    constexpr int GROUP = 8;                                     // chunks in flight
+    constexpr int GROUP = 16;                                    // chunks in flight per unit
+    constexpr int UNITS = 3;                                     // units a thread works on at once: the loads of a
+                                                                 // round trip of ~1 us are all issued before any is used
     const int s_units = d * d / 2, units = s_units + d / 2, elems = 2 * units;
     const int per = (units + C - 1) / C;
     const int lo = c * per, hi = lo + per < units ? lo + per : units;
-    for (int v = lo + (int)threadIdx.x; v < hi; v += THREADS) {
-        float *dst = v < s_units ? S_out + 2 * v : z_out + 2 * (v - s_units);
-        f32x2 x = {0.f, 0.f};
-        if (S_in) x = *reinterpret_cast<const f32x2 *>(v < s_units ? S_in + 2 * v : z_in + 2 * (v - s_units));
-        for (int c0 = 0; c0 < C; c0 += GROUP) {
-            f32x2 p[GROUP];
+    for (int v0 = lo + (int)threadIdx.x; v0 < hi; v0 += THREADS * UNITS) {
+        f32x2 x[UNITS];
 #pragma unroll
-            for (int cc = 0; cc < GROUP; ++cc) {
-                p[cc] = f32x2{0.f, 0.f};
-                if (c0 + cc < C) p[cc] = load_coherent(partials + (size_t)(c0 + cc) * elems + 2 * v);
+        for (int u = 0; u < UNITS; ++u) {
+            const int v = v0 + u * THREADS;
+            x[u] = f32x2{0.f, 0.f};
+            if (S_in && v < hi) x[u] = *reinterpret_cast<const f32x2 *>(v < s_units ? S_in + 2 * v : z_in + 2 * (v - s_units));
+        }
+        for (int c0 = 0; c0 < C; c0 += GROUP) {
+            f32x2 p[UNITS][GROUP];
+#pragma unroll
+            for (int u = 0; u < UNITS; ++u) {
+                const int v = v0 + u * THREADS;
+#pragma unroll
+                for (int cc = 0; cc < GROUP; ++cc) {
+                    p[u][cc] = f32x2{0.f, 0.f};
+                    if (c0 + cc < C && v < hi) p[u][cc] = load_coherent(partials + (size_t)(c0 + cc) * elems + 2 * v);
+                }
             }
 #pragma unroll
-            for (int cc = 0; cc < GROUP; ++cc)
-                if (c0 + cc < C) x += p[cc];
+            for (int u = 0; u < UNITS; ++u)
+#pragma unroll
+                for (int cc = 0; cc < GROUP; ++cc)
+                    if (c0 + cc < C) x[u] += p[u][cc];
         }
-        if (COHERENT_OUT) store_coherent(dst, x);
-        else *reinterpret_cast<f32x2 *>(dst) = x;
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) {
+            const int v = v0 + u * THREADS;
+            if (v < hi) {
+                float *dst = v < s_units ? S_out + 2 * v : z_out + 2 * (v - s_units);
+                if (COHERENT_OUT) store_coherent(dst, x[u]);
+                else *reinterpret_cast<f32x2 *>(dst) = x[u];
+            }
+        }
     }
 }
 

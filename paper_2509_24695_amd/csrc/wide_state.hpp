@@ -172,17 +172,23 @@ __device__ __forceinline__ void wide_state_wg_reduce_store(WideAcc &acc, unsigne
 #pragma unroll
             for (int i = 0; i < 16; ++i)
                 mine[(8 * (i >> 2) + 4 * g + (i & 3)) * 128 + 32 * cb + n] = acc.s[rb][cb][i];
-        __syncthreads();
-        const int rows = d - 32 * rb < 32 ? (d - 32 * rb > 0 ? d - 32 * rb : 0) : 32;   // key features of this band below d
-        for (int u = threadIdx.x; u < rows * half; u += 4 * kWave) {
-            const int k = u / half, v = 2 * (u - k * half);
-            const float *p = band + k * 128 + v;
-            const f32x2 x0 = *reinterpret_cast<const f32x2 *>(p), x1 = *reinterpret_cast<const f32x2 *>(p + 32 * 128),
-                        x2 = *reinterpret_cast<const f32x2 *>(p + 2 * 32 * 128),
-                        x3 = *reinterpret_cast<const f32x2 *>(p + 3 * 32 * 128);
-            store_coherent(out + (size_t)(32 * rb + k) * d + v, (x0 + x2) + (x1 + x3));
+        lds_barrier();                                 // LDS only: the stores of earlier bands stay in flight
+        // thread t: 8-byte unit t % 64 of rows t / 64 + 4 j of the band (no divisions; a wave stores whole rows)
+        const int cu = threadIdx.x & 63, r0 = threadIdx.x >> 6;
+        if (cu < half) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int k = r0 + 4 * j;
+                if (32 * rb + k < d) {
+                    const float *p = band + k * 128 + 2 * cu;
+                    const f32x2 x0 = *reinterpret_cast<const f32x2 *>(p), x1 = *reinterpret_cast<const f32x2 *>(p + 32 * 128),
+                                x2 = *reinterpret_cast<const f32x2 *>(p + 2 * 32 * 128),
+                                x3 = *reinterpret_cast<const f32x2 *>(p + 3 * 32 * 128);
+                    store_coherent(out + (size_t)(32 * rb + k) * d + 2 * cu, (x0 + x2) + (x1 + x3));
+                }
+            }
         }
-        __syncthreads();                               // the band is read before the next one is laid out
+        lds_barrier();                                 // the band is read before the next one is laid out
     }
     for (int u = threadIdx.x; u < half; u += 4 * kWave) {
         const int k = 2 * u;
@@ -232,9 +238,9 @@ __global__ __launch_bounds__(256, 1) void state_mfma_wide(
     if (FINALIZE) {
         epoch = es.resolve(reinterpret_cast<unsigned long long *>(lds + kWideEpochOffset));
         state_publish_and_wait(ws, BH, elems, bh, c, C, 0, epoch, spin_limit, lane);
-        state_finalize_slice<256, false>(partials, c, C, d, S_in ? S_in + (size_t)bh * d * d : nullptr,
+            state_finalize_slice<256, false>(partials, c, C, d, S_in ? S_in + (size_t)bh * d * d : nullptr,
                                          z_in + (size_t)bh * d, S_out + (size_t)bh * d * d, z_out + (size_t)bh * d);
-    }
+        }
 }
 
 }  // namespace sv
