@@ -1,26 +1,27 @@
-// Token streaming for d = 112 and 128 (DP = 128): the four waves of a workgroup
-// work on the same tile together.
+// Token streaming for d = 112 and 128 (DP = 128): the waves of a workgroup work on the same tile
+// together.
 //
-// With 64 features a wave can keep a whole 64 x 64 state (or a 64-column panel
-// of it) to itself and never talks to its neighbours.  With 128 the state is
-// four such quadrants and the apply needs two panels, so every token row is
-// needed by two waves.  Letting both fetch it costs far more than the extra
-// instructions: half rows of 224 or 256 bytes split cache lines between waves
-// and the non-temporal streams fetch them twice (measured: 2.4 TB/s instead of
-// 5.4).  Here each wave loads whole rows that nobody else loads, the tile is
-// assembled in workgroup-shared LDS, and one barrier per tile (state) or two per
-// pair of tiles (apply) hand it to the waves that compute:
+// With 64 features a wave can keep a whole 64 x 64 state (or a 64-column panel of it) to itself
+// and never talks to its neighbours.  With 128 the state is four such quadrants and the apply
+// needs several panels, so every token row is needed by more than one wave.  Letting all of them
+// fetch it costs far more than the extra instructions: half rows of 224 or 256 bytes split cache
+// lines between waves and the non-temporal streams fetch them twice (measured: 2.4 TB/s instead of
+// 5.4).  Here each wave loads whole rows that nobody else loads, the tile is assembled in
+// workgroup-shared LDS, and barriers hand it to the waves that compute:
 //
-//   state: wave w loads rows 8w .. 8w+8 of K and V of the tile, then folds key
-//          block w%2 against value block w/2 (a 64 x 64 quadrant) from LDS;
-//   apply: wave w loads rows 16w .. 16w+16 of a pair of Q tiles, computes value
-//          block w%2 of tile w/2 into a shared output tile, then stores whole
-//          rows 16w .. 16w+16 of O.
+//   state (the full-table RoPE form; the other forms use the wave-private kernel of
+//          wide_state.hpp): wave w loads rows 8w .. 8w+8 of K and V of a 32-token tile, then
+//          folds key block w%2 against value block w/2 (a 64 x 64 quadrant) from LDS; one barrier
+//          per tile;
+//   apply: wave w loads rows 8w .. 8w+8 of a 32-token Q tile, computes 32 of the 128 output
+//          features of the whole tile (its 128 x 32 panel of S stays in registers) into a shared
+//          output tile, then stores whole rows 8w .. 8w+8 of O; two barriers per tile, two
+//          workgroups per compute unit (the stream and the loop are written for other splits of
+//          the tile among the waves as well, see CoopApplyStream).
 //
-// Barriers are bare s_barrier instructions behind an LDS-only wait, so the
-// global loads of later tiles and the stores of earlier ones stay in flight
-// across them.  For d = 112 the features past 112 are addressed out of range:
-// they read as zeros and their stores are dropped.
+// Barriers are bare s_barrier instructions behind an LDS-only wait, so the global loads of later
+// tiles and the stores of earlier ones stay in flight across them.  For d = 112 the features past
+// 112 are addressed out of range: they read as zeros and their stores are dropped.
 #pragma once
 
 #include "apply_mfma.hpp"

@@ -26,13 +26,12 @@ constexpr int kVersion = 500;   // 0.5.0
 
 // Tuned launch shapes of the bf16 MFMA kernels (one workgroup per compute unit).
 // DP = 64 serves d = 64; DP = 128 serves d = 112 and 128.  Depths are tiles in
-// flight per wave, [DP = 128][RoPE mode: none, table, 3-D]: a stage of the table mode also
-// holds its table rows.
+// flight per wave (by RoPE mode: none, table, 3-D, where they differ).
 constexpr int kStateTile = 32, kStateWaves = 4, kApplyWaves = 4;
 constexpr int kCoopApplyWaves = 4, kCoopApplyNB = 1;   // d = 112/128 apply: one 128 x 32 panel of S per wave, two workgroups per compute unit
-constexpr int kStateDepth[2][3] = {{2, 2, 2}, {8, 4, 4}};
-constexpr int kWideStateDepth = 3;            // 16-token tiles in flight per wave of the wave-private d = 112/128 state kernel
-constexpr int kApplyDepth[2][3] = {{2, 2, 2}, {2, 2, 2}};
+constexpr int kStateDepth = 2, kApplyDepth = 2;
+constexpr int kWideStateDepth = 3;            // 16-token tiles of the wave-private d = 112/128 state kernel
+constexpr int kCoopStateDepth = 4;            // 32-token tiles of the shared-tile d = 112/128 state kernel (full-table RoPE)
 constexpr int kFusedStateDepth[3] = {2, 2, 2};   // one-launch block step (d = 64), by RoPE mode
 constexpr int kFusedApplyDepth[3] = {6, 2, 6};   // Q tiles held in registers across the in-kernel waits
 constexpr bool kApplyHiLo = true;
@@ -59,9 +58,9 @@ template <int DP, int ROPE> struct Kernels;
 template <int ROPE> struct Kernels<64, ROPE> {
     static constexpr int kTab = ROPE == kRope3D ? kRope3dLdsBytes : 0;
     static constexpr int W = 0;
-    static constexpr auto state = state_mfma_d64<kStateTile, kStateWaves, kStateDepth[W][ROPE], true, ROPE>;
-    static constexpr auto state_partial = state_mfma_d64<kStateTile, kStateWaves, kStateDepth[W][ROPE], false, ROPE>;
-    static constexpr auto apply = apply_mfma_d64<kApplyHiLo, kApplyWaves, kApplyDepth[W][ROPE], ROPE>;
+    static constexpr auto state = state_mfma_d64<kStateTile, kStateWaves, kStateDepth, true, ROPE>;
+    static constexpr auto state_partial = state_mfma_d64<kStateTile, kStateWaves, kStateDepth, false, ROPE>;
+    static constexpr auto apply = apply_mfma_d64<kApplyHiLo, kApplyWaves, kApplyDepth, ROPE>;
     static constexpr auto fused = block_step_mfma<kStateTile, kStateWaves, kFusedStateDepth[ROPE], kApplyHiLo,
                                                   kFusedApplyDepth[ROPE], ROPE>;
     static constexpr int state_lds = state_lds_bytes<kStateTile, kStateWaves>() + kTab;
@@ -79,12 +78,13 @@ template <int ROPE> struct Kernels<128, ROPE> {
     // State: wave-private tiles, except with a full rotation table, whose rows need the registers
     // the wave-private kernel spends on the whole 128 x 128 state (then: one tile shared by the four waves).
     static constexpr bool kWideState = ROPE != kRopeTable;
-    static constexpr int kWideRope = kWideState ? ROPE : kRopeNone;
-    static constexpr auto state = kWideState ? state_mfma_wide<kWideStateDepth, true, kWideRope>
-                                             : state_mfma_d128<kStateDepth[W][ROPE], true, ROPE>;
-    static constexpr auto state_partial = kWideState ? state_mfma_wide<kWideStateDepth, false, kWideRope>
-                                                     : state_mfma_d128<kStateDepth[W][ROPE], false, ROPE>;
-    static constexpr auto apply = apply_mfma_d128<kApplyHiLo, kApplyDepth[W][ROPE], ROPE, kCoopApplyWaves, kCoopApplyNB>;
+    template <bool FINALIZE> static constexpr auto pick_state() {
+        if constexpr (kWideState) return &state_mfma_wide<kWideStateDepth, FINALIZE, ROPE>;
+        else return &state_mfma_d128<kCoopStateDepth, FINALIZE, ROPE>;
+    }
+    static constexpr auto state = pick_state<true>();
+    static constexpr auto state_partial = pick_state<false>();
+    static constexpr auto apply = apply_mfma_d128<kApplyHiLo, kApplyDepth, ROPE, kCoopApplyWaves, kCoopApplyNB>;
     static constexpr int state_lds = kWideState ? kWideLdsBytes : state_d128_lds_bytes<ROPE>() + kTab;
     static constexpr int apply_lds = coop_apply_lds_bytes<ROPE, kCoopApplyWaves, kCoopApplyNB>() + kTab;
     static constexpr int state_wg_tokens = kWideState ? 4 * kWideTile : 32;   // four private tiles, or one shared
