@@ -48,12 +48,13 @@ constexpr int kApplyTile = 32;   // tokens per wave tile (the N dimension of the
 //   z rows: row 0 = hi(z), row 1 = lo(z), rows 2..31 = 0.
 // The contraction runs over DP key features in DP/16 k-steps; S is d x d (row
 // length d) and z has d entries, anything past d counts as zero.
-template <int DP, bool HILO, int NB = 2>
+// ZROWS = false leaves the z rows out (the caller takes the denominators another way).
+template <int DP, bool HILO, int NB = 2, bool ZROWS = true>
 struct ApplyOperands {
     static constexpr int NS = HILO ? 2 : 1;
     static constexpr int KS = DP / 16;
-    bf16x8 s[NS][NB][KS];  // [hi/lo][row block][k-step]
-    bf16x8 zrow[KS];       // [k-step]
+    bf16x8 s[NS][NB][KS];          // [hi/lo][row block][k-step]
+    bf16x8 zrow[ZROWS ? KS : 1];   // [k-step]
 
     // COHERENT: the state was written by another workgroup of this same kernel.
     template <bool COHERENT>
@@ -87,7 +88,7 @@ struct ApplyOperands {
             }
         }
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
+        for (int ks = 0; ks < (ZROWS ? KS : 0); ++ks) {
             uint32_t w[4];
 #pragma unroll
             for (int p = 0; p < 4; ++p) {

@@ -206,25 +206,33 @@ __device__ __forceinline__ void coop_apply_prefetch(CoopApplyStream<DEPTH, ROPE,
     }
 }
 
-// LDS of the apply phase: the Q tiles of a step (with ROPE also their rotated copy) and its O tiles.
-template <int ROPE, int WAVES, int NB> __host__ __device__ constexpr int coop_apply_lds_bytes() {
-    return (ROPE ? 3 : 2) * (WAVES * NB / 4) * kCoopTile;
+// LDS of the apply phase: the Q tiles of a step (as the MFMAs want them: rotated with ROPE), its
+// O tiles and the denominators of its tokens.
+template <int WAVES, int NB> __host__ __device__ constexpr int coop_apply_lds_bytes() {
+    return 2 * (WAVES * NB / 4) * kCoopTile + 8 * WAVES * NB * 4;
 }
 
 // Applies the state panel in `A` (value block wave % (4/NB)) to tile wave / (4/NB) of every step
 // of the workgroup's share.  Must be called by all waves of the workgroup.
+//
+// Denominators phi(Q_i) . z + eps: the wave that loads a row also takes its dot product with z on
+// the vector ALU (a lane holds eight features of the row and the matching eight of z, `zr`; 16
+// lanes share a row) and leaves it in LDS beside the tile.  The products are exact in fp32, the
+// unrotated phi(Q) is at hand there even with ROPE, and the matrix core is left with the numerator.
 template <bool HILO, int DEPTH, int ROPE, int WAVES, int NB>
 __device__ __forceinline__ void apply_tiles_coop(CoopApplyStream<DEPTH, ROPE, WAVES, NB> &st, unsigned char *lds,
-                                                 int wave, int lane, const ApplyOperands<128, HILO, NB> &A, float eps)
+                                                 int wave, int lane, const ApplyOperands<128, HILO, NB, false> &A,
+                                                 const float (&zr)[8], float eps)
 {
     constexpr int NS = HILO ? 2 : 1;
     constexpr int STEP = 8 * WAVES * NB, TILES = WAVES * NB / 4, ROWS = STEP / WAVES, NLD = ROWS / 4, WT = 4 / NB;
     const int t = wave / WT, vb = wave % WT;
     const int n = lane & 31, g = lane >> 5;
-    unsigned char *bufQ = lds, *bufR = ROPE ? lds + TILES * kCoopTile : lds,
-                  *bufO = lds + (ROPE ? 2 : 1) * TILES * kCoopTile;
-    const int wr_off = (ROWS * wave + (lane >> 4)) * kCoopRow + (lane & 15) * 16;   // the wave's own rows
-    const unsigned char *brow = bufQ + (32 * t + n) * kCoopRow, *rrow = bufR + (32 * t + n) * kCoopRow;
+    unsigned char *bufQ = lds, *bufO = lds + TILES * kCoopTile;
+    float *den = reinterpret_cast<float *>(lds + 2 * TILES * kCoopTile);            // [STEP]
+    const int my_row = ROWS * wave + (lane >> 4);                                   // + 4 j: the rows this lane loads
+    const int wr_off = my_row * kCoopRow + (lane & 15) * 16;
+    const unsigned char *brow = bufQ + (32 * t + n) * kCoopRow;
     unsigned char *orow = bufO + (32 * t + n) * kCoopRow + (32 * NB * vb + 16 * NB * g) * 2;
 
     auto round = [&](int i0) __attribute__((always_inline)) {
@@ -238,39 +246,45 @@ __device__ __forceinline__ void apply_tiles_coop(CoopApplyStream<DEPTH, ROPE, WA
 #pragma unroll
                 for (int j = 0; j < NLD; ++j) {
                     const u32x4 pq = relu_bf16x8(st.q[s][j]);                          // phi(Q)
-                    *reinterpret_cast<u32x4 *>(bufQ + wr_off + 4 * j * kCoopRow) = pq;
-                    if (ROPE) *reinterpret_cast<u32x4 *>(bufR + wr_off + 4 * j * kCoopRow) = st.rot.rotate(s, j, pq);
+                    float dot = bf16_lo(pq.x) * zr[0];
+                    dot = __builtin_fmaf(bf16_hi(pq.x), zr[1], dot);
+                    dot = __builtin_fmaf(bf16_lo(pq.y), zr[2], dot);
+                    dot = __builtin_fmaf(bf16_hi(pq.y), zr[3], dot);
+                    dot = __builtin_fmaf(bf16_lo(pq.z), zr[4], dot);
+                    dot = __builtin_fmaf(bf16_hi(pq.z), zr[5], dot);
+                    dot = __builtin_fmaf(bf16_lo(pq.w), zr[6], dot);
+                    dot = __builtin_fmaf(bf16_hi(pq.w), zr[7], dot);
+                    dot += __shfl_xor(dot, 1);                                          // the 16 lanes of the row
+                    dot += __shfl_xor(dot, 2);
+                    dot += __shfl_xor(dot, 4);
+                    dot += __shfl_xor(dot, 8);
+                    if ((lane & 15) == 0) den[my_row + 4 * j] = dot;
+                    *reinterpret_cast<u32x4 *>(bufQ + wr_off + 4 * j * kCoopRow) = ROPE ? st.rot.rotate(s, j, pq) : pq;
                 }
             }
-            st.request(s, i0 + s + DEPTH);   // refill this stage: DEPTH pairs ahead
+            st.request(s, i0 + s + DEPTH);   // refill this stage: DEPTH steps ahead
             __builtin_amdgcn_sched_barrier(0);
             u32x4 o[NLD] = {};
             if (valid) {
-                // Q tiles complete.  They are overwritten in the next round, by waves that have
-                // passed the second barrier below, which every wave reaches after its reads.
+                // Q tiles and denominators complete.  They are overwritten in the next round, by waves
+                // that have passed the second barrier below, which every wave reaches after its reads.
                 lds_barrier();
-                f32x16 acc[NB], accz;
+                f32x16 acc[NB];
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
+                for (int i = 0; i < 16; ++i)
 #pragma unroll
                     for (int rb = 0; rb < NB; ++rb) acc[rb][i] = 0.f;
-                    accz[i] = 0.f;
-                }
+                const float inv = 1.0f / (den[32 * t + n] + eps);
 #pragma unroll
                 for (int ks = 0; ks < 8; ++ks) {
                     const bf16x8 bq = *reinterpret_cast<const bf16x8 *>(brow + (16 * ks + 8 * g) * 2);
-                    const bf16x8 br = ROPE ? *reinterpret_cast<const bf16x8 *>(rrow + (16 * ks + 8 * g) * 2) : bq;
-                    accz = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.zrow[ks], bq, accz, 0, 0, 0);
 #pragma unroll
                     for (int p = NS - 1; p >= 0; --p) {      // small (lo) terms first
 #pragma unroll
                         for (int rb = 0; rb < NB; ++rb)
-                            acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.s[p][rb][ks], br, acc[rb], 0, 0, 0);
+                            acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.s[p][rb][ks], bq, acc[rb], 0, 0, 0);
                     }
                 }
-                float den = accz[1] + accz[0];      // rows 0 (hi) and 1 (lo) of the z block
-                den = __shfl(den, n);
-                const float inv = 1.0f / (den + eps);
 #pragma unroll
                 for (int rb = 0; rb < NB; ++rb) {
                     const f32x16 &a = acc[rb];
@@ -373,16 +387,22 @@ __global__ __launch_bounds__(64 * WAVES, NB == 1 ? 2 : 1) void apply_mfma_d128(
     constexpr int STEP = 8 * WAVES * NB;
     const int n_steps = (t1 - t0 + STEP - 1) / STEP;
 
-    CoopApplyStream<DEPTH, ROPE, WAVES, NB> stream(Qh, Oh, rope, lds + coop_apply_lds_bytes<ROPE, WAVES, NB>(), st.n, t1,
+    CoopApplyStream<DEPTH, ROPE, WAVES, NB> stream(Qh, Oh, rope, lds + coop_apply_lds_bytes<WAVES, NB>(), st.n, t1,
                                                    d, wave, lane, TileWalk(t0, c, C, n_steps, bh));
     coop_apply_prefetch<0, DEPTH>(stream);   // in flight while S is fetched
     if (ROPE == kRope3D) {
-        rope3d_lds_fill(lds + coop_apply_lds_bytes<ROPE, WAVES, NB>(), rope.r3);
+        rope3d_lds_fill(lds + coop_apply_lds_bytes<WAVES, NB>(), rope.r3);
         __syncthreads();
     }
-    ApplyOperands<128, HILO, NB> A;
+    ApplyOperands<128, HILO, NB, false> A;
     A.template load<false>(S + (size_t)bh * d * d, z + (size_t)bh * d, d, wave % (4 / NB), lane);
-    apply_tiles_coop<HILO>(stream, lds, wave, lane, A, eps);
+    float zr[8];                                   // the key sums of the eight features this lane loads of a row
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int k = 8 * (lane & 15) + e;
+        zr[e] = k < d ? z[(size_t)bh * d + k] : 0.f;
+    }
+    apply_tiles_coop<HILO>(stream, lds, wave, lane, A, zr, eps);
 }
 
 }  // namespace sv

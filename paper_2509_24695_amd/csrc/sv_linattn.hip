@@ -86,7 +86,7 @@ template <int ROPE> struct Kernels<128, ROPE> {
     static constexpr auto state_partial = pick_state<false>();
     static constexpr auto apply = apply_mfma_d128<kApplyHiLo, kApplyDepth, ROPE, kCoopApplyWaves, kCoopApplyNB>;
     static constexpr int state_lds = kWideState ? kWideLdsBytes : state_d128_lds_bytes<ROPE>() + kTab;
-    static constexpr int apply_lds = coop_apply_lds_bytes<ROPE, kCoopApplyWaves, kCoopApplyNB>() + kTab;
+    static constexpr int apply_lds = coop_apply_lds_bytes<kCoopApplyWaves, kCoopApplyNB>() + kTab;
     static constexpr int state_wg_tokens = kWideState ? 4 * kWideTile : 32;   // four private tiles, or one shared
     static constexpr int apply_wg_tokens = 8 * kCoopApplyWaves * kCoopApplyNB;   // the waves of a workgroup share its tiles
     static constexpr int apply_threads = 64 * kCoopApplyWaves, apply_wgs_per_cu = 8 / (kCoopApplyWaves * kCoopApplyNB);
