@@ -238,9 +238,9 @@ __global__ __launch_bounds__(256, 1) void state_mfma_wide(
     if (FINALIZE) {
         epoch = es.resolve(reinterpret_cast<unsigned long long *>(lds + kWideEpochOffset));
         state_publish_and_wait(ws, BH, elems, bh, c, C, 0, epoch, spin_limit, lane);
-            state_finalize_slice<256, false>(partials, c, C, d, S_in ? S_in + (size_t)bh * d * d : nullptr,
+        state_finalize_slice<256, false>(partials, c, C, d, S_in ? S_in + (size_t)bh * d * d : nullptr,
                                          z_in + (size_t)bh * d, S_out + (size_t)bh * d * d, z_out + (size_t)bh * d);
-        }
+    }
 }
 
 }  // namespace sv
