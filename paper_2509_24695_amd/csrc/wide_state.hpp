@@ -25,7 +25,11 @@
 namespace sv {
 
 constexpr int kWideTile = 16;                       // tokens per tile: one MFMA k-step
-constexpr int kWideRow = 128 * 2 + 16;              // LDS row: 128 bf16 features + padding
+// LDS row: 128 bf16 features + padding.  A transposing read takes 64 contiguous bytes from each of
+// four consecutive rows per half wave; with a row pitch of 80 words the four 16-bank windows tile
+// the 64 banks (a pitch of 68 words, enough for 16-byte reads, made them overlap: 44 % of the LDS
+// cycles of this kernel were bank conflicts).
+constexpr int kWideRow = 128 * 2 + 64;
 constexpr int kWideTileBytes = kWideTile * kWideRow;
 
 // LDS map (bytes): [0, 64 KB) the reduction bands (4 waves x 32 rows x 128 floats), over the dead K/V
