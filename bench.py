@@ -57,6 +57,8 @@ def _parse():
     ap.add_argument("--no-d112", action="store_true",
                     help="skip the timings in the geometry of the paper's 2B model (20 heads of 112 features)")
     ap.add_argument("--stream-blocks", type=int, default=80)
+    ap.add_argument("--no-stream-ceiling", action="store_true",
+                    help="skip the pure read / pure copy yardsticks")
     ap.add_argument("--calibration-copy", type=int, default=0,
                     help="also run this many plain device copies of one token tensor (known size: "
                          "the same bytes read and written), for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE")
@@ -264,6 +266,40 @@ def bench_block_stream(w, n_blocks, sv, torch, rope=False):
     }
 
 
+def bench_stream_ceiling(nbytes, sv, torch, reps=12):
+    """What the device gives kernels that only move bytes (include/sv_measure.h): a pure read of
+    `nbytes` and a pure copy that reads nbytes/2 and writes nbytes/2 (the traffic of one state and
+    of one apply launch), best average over a few launch shapes, buffers rotated so that the last
+    level cache cannot serve repeats.  Context for `roofline`, which is quoted against the published peak."""
+    n_sets = max(2, -(-int(1.5e9) // nbytes))
+    bufs = [torch.empty(nbytes, dtype=torch.uint8, device="cuda") for _ in range(n_sets)]
+    for i, b in enumerate(bufs):
+        b.fill_(i + 1)
+    half = nbytes // 2 // 16 * 16
+    sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream()
+    out = {}
+    for kind in ("read", "copy"):
+        best = None
+        for wgs in (1024, 4096, 8192, 16384, 65536):
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps + 2)]
+            for i, (e0, e1) in enumerate(ev):
+                b = bufs[i % n_sets]
+                e0.record(stream)
+                if kind == "read":
+                    sv.sv_stream_read(b, nbytes, sink, wgs, stream=stream)
+                else:
+                    sv.sv_stream_copy(b, b[half:], half, wgs, stream=stream)
+                e1.record(stream)
+            torch.cuda.synchronize()
+            ms = statistics.mean(e0.elapsed_time(e1) for e0, e1 in ev[2:])
+            if best is None or ms < best[0]:
+                best = (ms, wgs)
+        moved = nbytes if kind == "read" else 2 * half
+        out[kind] = {"bytes": moved, "us": best[0] * 1e3, "GBps": moved / (best[0] * 1e-3) / 1e9, "workgroups": best[1]}
+    return out
+
+
 def bench_tconv(w, iters, sv, torch):
     """Mix-FFN temporal convolution (sv_tconv_block_step): the stream of w.n_blocks blocks enqueued back
     to back with the one-frame cache carried and committed after every block, `iters` passes between one
@@ -365,6 +401,12 @@ def main():
                      "algorithmic_bytes_per_launch": half, "avg_launch_ms": dom_ms,
                      "avg_launch_ms_between_events": dom_ms_events},
     }
+    if not args.no_stream_ceiling:
+        c = bench_stream_ceiling(int(half), sv, torch)
+        out["stream_ceiling"] = c
+        ref = c["read"] if dom == "state" else c["copy"]     # the state kernel only reads; the apply kernel reads and writes
+        # both timed between events on the launch stream, the same way
+        out["roofline"]["frac_of_stream_ceiling"] = ref["us"] / (dom_ms_events * 1e3)
     if args.calibration_copy > 0:
         src = r["sets"][0][0]
         dst = torch.empty_like(src)

@@ -1,0 +1,40 @@
+/*
+ * sv_measure.h - streaming yardsticks (MI355X, gfx950; part of libsvlinattn.so).
+ *
+ * Not part of the method of the paper: two kernels that do nothing but move
+ * bytes, for callers that want to know what this device gives a pure stream of
+ * a given size - the ceiling the attention kernels (all of them bound by memory
+ * traffic) are measured against beside the published peak.
+ *
+ * Both take device pointers, work on `stream` (hipStream_t passed as void*,
+ * NULL = default stream), return after enqueueing, allocate nothing and keep
+ * nothing.  `wgs` workgroups of 256 threads each walk a contiguous share of the
+ * buffer with 16-byte accesses, eight in flight per thread.
+ *
+ * Errors (checked on the host before any launch): SV_ERR_NULL for a null
+ * pointer, SV_ERR_ALIGN if a pointer or `bytes` is not a multiple of 16,
+ * SV_ERR_SHAPE if wgs is outside [1, 1048576] or (copy) the buffers overlap,
+ * SV_ERR_LAUNCH if the launch failed.  bytes == 0 is legal and launches nothing.
+ */
+#ifndef SV_MEASURE_H
+#define SV_MEASURE_H
+
+#include "sv_linattn.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Reads src[0, bytes) once.  `sink` is 16 bytes of device memory that the kernel
+ * may write (it does so only for one bit pattern of the data in a million; the
+ * store is what keeps the loads alive). */
+sv_status sv_stream_read(const void *src, size_t bytes, void *sink, int32_t wgs, void *stream);
+
+/* dst[0, bytes) = src[0, bytes). */
+sv_status sv_stream_copy(const void *src, void *dst, size_t bytes, int32_t wgs, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+
+#endif /* SV_MEASURE_H */

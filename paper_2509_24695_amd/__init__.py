@@ -1,7 +1,7 @@
 """MI355X (gfx950) ReLU linear attention for long video token sequences.
 
 Thin Python binding over libsvlinattn.so (hand-written HIP kernels behind a C
-ABI, declared in include/sv_linattn.h and include/sv_tconv.h).  PyTorch is used by callers for device
+ABI, declared in include/sv_linattn.h, include/sv_tconv.h and include/sv_measure.h).  PyTorch is used by callers for device
 memory and streams only; every step of the computation runs in the library.
 """
 from .binding import (  # noqa: F401
@@ -10,5 +10,5 @@ from .binding import (  # noqa: F401
     sv_linattn_workspace_bytes, sv_status_string, sv_version, EXPORTS,
     sv_linattn_state_rope, sv_linattn_apply_rope, sv_block_linattn_step_rope, sv_block_linattn_lookahead_rope, sv_linattn_workspace_init,
     Rope3D, sv_linattn_state_rope3d, sv_linattn_apply_rope3d, sv_block_linattn_step_rope3d,
-    sv_block_linattn_lookahead_rope3d, sv_tconv_block_step,
+    sv_block_linattn_lookahead_rope3d, sv_tconv_block_step, sv_stream_read, sv_stream_copy,
 )

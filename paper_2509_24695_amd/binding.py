@@ -1,7 +1,7 @@
 """ctypes binding of libsvlinattn.so: argument marshalling only.
 
 The functions carry the names and argument order of the C ABI
-(include/sv_linattn.h, include/sv_tconv.h).  Device buffers are torch tensors (or raw integer
+(include/sv_linattn.h, include/sv_tconv.h, include/sv_measure.h).  Device buffers are torch tensors (or raw integer
 device addresses); nothing here computes, and there is no fallback: if the
 shared library is missing, loading raises.
 """
@@ -19,7 +19,7 @@ EXPORTS = (
     "sv_linattn_state_rope", "sv_linattn_apply_rope", "sv_block_linattn_step_rope",
     "sv_block_linattn_lookahead_rope", "sv_linattn_workspace_init",
     "sv_linattn_state_rope3d", "sv_linattn_apply_rope3d", "sv_block_linattn_step_rope3d",
-    "sv_block_linattn_lookahead_rope3d", "sv_tconv_block_step",
+    "sv_block_linattn_lookahead_rope3d", "sv_tconv_block_step", "sv_stream_read", "sv_stream_copy",
 )
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
@@ -103,6 +103,10 @@ def load_library():
         f.restype = ctypes.c_int
     lib.sv_tconv_block_step.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp]
     lib.sv_tconv_block_step.restype = ctypes.c_int
+    lib.sv_stream_read.argtypes = [vp, sz, vp, i32, vp]
+    lib.sv_stream_read.restype = ctypes.c_int
+    lib.sv_stream_copy.argtypes = [vp, vp, sz, i32, vp]
+    lib.sv_stream_copy.restype = ctypes.c_int
     lib.sv_linattn_workspace_init.argtypes = [vp, sz, i32, i32, i32, vp]
     lib.sv_linattn_workspace_init.restype = ctypes.c_int
     lib.sv_status_string.argtypes = [ctypes.c_int]
@@ -319,3 +323,15 @@ def sv_tconv_block_step(x, W, cache_in, y, cache_out, B: int, T: int, HW: int, D
                                             dtype, _stream(stream))
     if rc != 0:
         raise SvError(rc, "sv_tconv_block_step")
+
+
+def sv_stream_read(src, nbytes: int, sink, wgs: int, stream=None) -> None:
+    """Streaming yardstick (include/sv_measure.h): reads src[0, nbytes) once."""
+    _check(load_library().sv_stream_read(_ptr(src), int(nbytes), _ptr(sink), int(wgs), _stream(stream)),
+           "sv_stream_read")
+
+
+def sv_stream_copy(src, dst, nbytes: int, wgs: int, stream=None) -> None:
+    """Streaming yardstick (include/sv_measure.h): dst[0, nbytes) = src[0, nbytes)."""
+    _check(load_library().sv_stream_copy(_ptr(src), _ptr(dst), int(nbytes), int(wgs), _stream(stream)),
+           "sv_stream_copy")

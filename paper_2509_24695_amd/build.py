@@ -8,7 +8,7 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libsvlinattn.so")
-SOURCES = [os.path.join(CSRC, "sv_linattn.hip"), os.path.join(CSRC, "sv_tconv.hip")]
+SOURCES = [os.path.join(CSRC, f) for f in ("sv_linattn.hip", "sv_tconv.hip", "sv_measure.hip")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

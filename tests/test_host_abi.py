@@ -190,3 +190,20 @@ def test_tconv_checks_arguments():
     assert call(y=FAKE) == 2                                # y on top of x
     assert call(y=FAKE + 64) == 2                           # y inside x
     assert call(cache_in=FAKE + (1 << 29) + 1024) == 2      # cache_in inside y
+
+
+def test_stream_yardsticks_check_arguments():
+    def status(fn, *args):
+        with pytest.raises(sv.SvError) as e:
+            fn(*args)
+        return e.value.status
+
+    A, B = FAKE, FAKE + (1 << 28)
+    assert status(sv.sv_stream_read, None, 1024, B, 64) == 1 and status(sv.sv_stream_read, A, 1024, None, 64) == 1
+    assert status(sv.sv_stream_copy, None, B, 1024, 64) == 1 and status(sv.sv_stream_copy, A, None, 1024, 64) == 1
+    assert status(sv.sv_stream_read, A + 8, 1024, B, 64) == 4 and status(sv.sv_stream_read, A, 1000, B, 64) == 4
+    assert status(sv.sv_stream_copy, A, B + 4, 1024, 64) == 4 and status(sv.sv_stream_copy, A, B, 1032, 64) == 4
+    assert status(sv.sv_stream_read, A, 1024, B, 0) == 2 and status(sv.sv_stream_copy, A, B, 1024, (1 << 20) + 1) == 2
+    assert status(sv.sv_stream_copy, A, A + 512, 1024, 64) == 2          # overlapping buffers
+    sv.sv_stream_read(A, 0, B, 64)                                        # nothing to do: no launch, no error
+    sv.sv_stream_copy(A, B, 0, 64)
