@@ -5,7 +5,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-namespace {
+namespace sv {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kThreads = 256, kUnroll = 8;
@@ -42,6 +42,12 @@ __global__ __launch_bounds__(kThreads) void stream_copy(const u32x4 *__restrict_
     }
     for (; i < hi; i += kThreads) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
+
+}  // namespace sv
+
+namespace {
+
+using namespace sv;
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
