@@ -176,11 +176,20 @@ __device__ __forceinline__ void apply_tiles(ApplyStream<DEPTH, ROPE> &st, unsign
             if (valid) {
                 wave_lds_fence();
                 st.rot.begin_tile(st.walk.template token<kApplyTile>(i0 + s));
+                // the table lookups of the tile go out first; the ReLU and the plain tile fill their latency
+                f32x2 cs[kApplyTile / 8][4];
+#pragma unroll
+                for (int j = 0; j < kApplyTile / 8; ++j) st.rot.fetch(s, j, cs[j]);
+                u32x4 pq[kApplyTile / 8];
 #pragma unroll
                 for (int j = 0; j < kApplyTile / 8; ++j) {
-                    const u32x4 pq = relu_bf16x8(st.q[s][j]);                          // phi(Q)
-                    *reinterpret_cast<u32x4 *>(tileQ + wr_off + 8 * j * kRow) = pq;
-                    if (ROPE) *reinterpret_cast<u32x4 *>(tileQ + kTileBytes + wr_off + 8 * j * kRow) = st.rot.rotate(s, j, pq);
+                    pq[j] = relu_bf16x8(st.q[s][j]);                                   // phi(Q)
+                    *reinterpret_cast<u32x4 *>(tileQ + wr_off + 8 * j * kRow) = pq[j];
+                }
+                if (ROPE) {
+#pragma unroll
+                    for (int j = 0; j < kApplyTile / 8; ++j)
+                        *reinterpret_cast<u32x4 *>(tileQ + kTileBytes + wr_off + 8 * j * kRow) = st.rot.rotate_with(pq[j], cs[j]);
                 }
             }
             st.request(s, i0 + s + DEPTH);   // refill this stage: DEPTH tiles ahead

@@ -243,6 +243,10 @@ __device__ __forceinline__ void apply_tiles_coop(CoopApplyStream<DEPTH, ROPE, WA
             const uint32_t out_off = st.valid ? st.walk.template offset<STEP>(i0 + s, st.row_bytes) : kOutOfRange;
             if (valid) {
                 st.rot.begin_tile(st.walk.template token<STEP>(i0 + s));
+                // the table lookups of the step go out first; ReLU and denominators fill their latency
+                f32x2 cs[NLD][4];
+#pragma unroll
+                for (int j = 0; j < NLD; ++j) st.rot.fetch(s, j, cs[j]);
 #pragma unroll
                 for (int j = 0; j < NLD; ++j) {
                     const u32x4 pq = relu_bf16x8(st.q[s][j]);                          // phi(Q)
@@ -259,7 +263,7 @@ __device__ __forceinline__ void apply_tiles_coop(CoopApplyStream<DEPTH, ROPE, WA
                     dot += __shfl_xor(dot, 4);
                     dot += __shfl_xor(dot, 8);
                     if ((lane & 15) == 0) den[my_row + 4 * j] = dot;
-                    *reinterpret_cast<u32x4 *>(bufQ + wr_off + 4 * j * kCoopRow) = ROPE ? st.rot.rotate(s, j, pq) : pq;
+                    *reinterpret_cast<u32x4 *>(bufQ + wr_off + 4 * j * kCoopRow) = st.rot.rotate_with(pq, cs[j]);
                 }
             }
             st.request(s, i0 + s + DEPTH);   // refill this stage: DEPTH steps ahead

@@ -78,6 +78,8 @@ struct Rotator<kRopeNone, STEPS, DEPTH> {
     __device__ __forceinline__ void request(int, bool, int) {}
     __device__ __forceinline__ void begin_tile(int) {}
     __device__ __forceinline__ u32x4 rotate(int, int, u32x4 w) const { return w; }
+    __device__ __forceinline__ void fetch(int, int, f32x2 (&)[4]) const {}
+    __device__ __forceinline__ u32x4 rotate_with(u32x4 w, const f32x2 (&)[4]) const { return w; }
 };
 
 template <int STEPS, int DEPTH>
@@ -109,6 +111,18 @@ struct Rotator<kRopeTable, STEPS, DEPTH> {
     __device__ __forceinline__ u32x4 rotate(int s, int j, u32x4 w) const
     {
         return rope_rotate_bf16x8(w, cs[s][j][0], cs[s][j][1]);
+    }
+    __device__ __forceinline__ void fetch(int s, int j, f32x2 (&e)[4]) const
+    {
+        e[0] = f32x2{cs[s][j][0].x, cs[s][j][0].y};
+        e[1] = f32x2{cs[s][j][0].z, cs[s][j][0].w};
+        e[2] = f32x2{cs[s][j][1].x, cs[s][j][1].y};
+        e[3] = f32x2{cs[s][j][1].z, cs[s][j][1].w};
+    }
+    __device__ __forceinline__ u32x4 rotate_with(u32x4 w, const f32x2 (&e)[4]) const
+    {
+        return u32x4{rope_rotate_pair(w.x, e[0].x, e[0].y), rope_rotate_pair(w.y, e[1].x, e[1].y),
+                     rope_rotate_pair(w.z, e[2].x, e[2].y), rope_rotate_pair(w.w, e[3].x, e[3].y)};
     }
 };
 
@@ -194,18 +208,29 @@ struct Rotator<kRope3D, STEPS, DEPTH> {
         }
     }
 
-    __device__ __forceinline__ u32x4 rotate(int /*s*/, int j, u32x4 w) const
+    // The (cos, sin) entries of the lane's four pairs of chunk j: four LDS reads.  Split from the
+    // arithmetic so that a caller can issue the reads of a whole tile first and do other work
+    // while they are in flight.
+    __device__ __forceinline__ void fetch(int /*s*/, int j, f32x2 (&e)[4]) const
     {
-        uint32_t word[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             // 24-bit multiplies run at full rate (32-bit ones at a quarter); positions and strides are far below 2^24
             const uint32_t addr = base[q] + __umul24((uint32_t)f[j], mul_f[q]) + __umul24((uint32_t)r[j], mul_r[q]) +
                                   __umul24((uint32_t)c[j], mul_c[q]);
-            const f32x2 cs = *reinterpret_cast<const f32x2 *>(tab + addr);
-            word[q] = rope_rotate_pair(word[q], cs.x, cs.y);
+            e[q] = *reinterpret_cast<const f32x2 *>(tab + addr);
         }
-        return u32x4{word[0], word[1], word[2], word[3]};
+    }
+    __device__ __forceinline__ u32x4 rotate_with(u32x4 w, const f32x2 (&e)[4]) const
+    {
+        return u32x4{rope_rotate_pair(w.x, e[0].x, e[0].y), rope_rotate_pair(w.y, e[1].x, e[1].y),
+                     rope_rotate_pair(w.z, e[2].x, e[2].y), rope_rotate_pair(w.w, e[3].x, e[3].y)};
+    }
+    __device__ __forceinline__ u32x4 rotate(int s, int j, u32x4 w) const
+    {
+        f32x2 e[4];
+        fetch(s, j, e);
+        return rotate_with(w, e);
     }
 };
 

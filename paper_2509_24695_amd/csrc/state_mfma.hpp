@@ -238,6 +238,10 @@ __device__ __forceinline__ void state_accumulate(StateStream<TILE, DEPTH, ROPE> 
             __builtin_amdgcn_sched_barrier(0);
             // phi(K) on the packed pairs
             st.rot.begin_tile(st.walk.template token<TILE>(i0 + s));
+            // the table lookups of the tile go out first; ReLU and key sums fill their latency
+            f32x2 cs[TILE / 8][4];
+#pragma unroll
+            for (int i = 0; i < TILE / 8; ++i) st.rot.fetch(s, i, cs[i]);
 #pragma unroll
             for (int i = 0; i < TILE / 8; ++i) {
                 const u32x4 kk = relu_bf16x8(st.k[s][i]);
@@ -248,8 +252,10 @@ __device__ __forceinline__ void state_accumulate(StateStream<TILE, DEPTH, ROPE> 
                     acc.z[4] += bf16_lo(kk.z);  acc.z[5] += bf16_hi(kk.z);
                     acc.z[6] += bf16_lo(kk.w);  acc.z[7] += bf16_hi(kk.w);
                 }
-                st.k[s][i] = st.rot.rotate(s, i, kk);
+                st.k[s][i] = kk;
             }
+#pragma unroll
+            for (int i = 0; i < TILE / 8; ++i) st.k[s][i] = st.rot.rotate_with(st.k[s][i], cs[i]);
             wave_lds_fence();   // earlier reads of the tile buffer are done before it is overwritten
 #pragma unroll
             for (int i = 0; i < TILE / 8; ++i) {

@@ -110,14 +110,23 @@ __device__ __forceinline__ void wide_state_accumulate(WideStateStream<DEPTH, ROP
         for (int s = 0; s < DEPTH; ++s) {
             __builtin_amdgcn_sched_barrier(0);   // stages stay in program order
             st.rot.begin_tile(st.walk.template token<kWideTile>(i0 + s));
+            // two chunks at a time: their eight table lookups go out first, ReLU and key sums fill the latency
 #pragma unroll
-            for (int j = 0; j < NLD; ++j) {
-                const u32x4 kk = relu_bf16x8(st.k[s][j]);
-                acc.z[0] += bf16_lo(kk.x);  acc.z[1] += bf16_hi(kk.x);
-                acc.z[2] += bf16_lo(kk.y);  acc.z[3] += bf16_hi(kk.y);
-                acc.z[4] += bf16_lo(kk.z);  acc.z[5] += bf16_hi(kk.z);
-                acc.z[6] += bf16_lo(kk.w);  acc.z[7] += bf16_hi(kk.w);
-                st.k[s][j] = st.rot.rotate(s, j, kk);
+            for (int j0 = 0; j0 < NLD; j0 += 2) {
+                f32x2 cs[2][4];
+#pragma unroll
+                for (int j = 0; j < 2; ++j) st.rot.fetch(s, j0 + j, cs[j]);
+#pragma unroll
+                for (int j = j0; j < j0 + 2; ++j) {
+                    const u32x4 kk = relu_bf16x8(st.k[s][j]);
+                    acc.z[0] += bf16_lo(kk.x);  acc.z[1] += bf16_hi(kk.x);
+                    acc.z[2] += bf16_lo(kk.y);  acc.z[3] += bf16_hi(kk.y);
+                    acc.z[4] += bf16_lo(kk.z);  acc.z[5] += bf16_hi(kk.z);
+                    acc.z[6] += bf16_lo(kk.w);  acc.z[7] += bf16_hi(kk.w);
+                    st.k[s][j] = kk;
+                }
+#pragma unroll
+                for (int j = 0; j < 2; ++j) st.k[s][j0 + j] = st.rot.rotate_with(st.k[s][j0 + j], cs[j]);
             }
             wave_lds_fence();   // earlier reads of the tile buffers are done before they are overwritten
 #pragma unroll
