@@ -97,37 +97,49 @@ __device__ __forceinline__ void wide_state_prefetch(WideStateStream<DEPTH, ROPE>
     }
 }
 
+// ReLU, key sums and rotation of the tile in stage s, in the registers it was loaded into; the
+// rotator has been told the tile (begin_tile).  Straight-line code, so that it can share a
+// scheduling region with MFMAs.  Two chunks at a time: their eight table lookups go out first,
+// ReLU and key sums fill the latency.
+template <int DEPTH, int ROPE>
+__device__ __forceinline__ void wide_state_prepare(WideStateStream<DEPTH, ROPE> &st, int s, WideAcc &acc)
+{
+    constexpr int NLD = WideStateStream<DEPTH, ROPE>::NLD;
+#pragma unroll
+    for (int j0 = 0; j0 < NLD; j0 += 2) {
+        f32x2 cs[2][4];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) st.rot.fetch(s, j0 + j, cs[j]);
+#pragma unroll
+        for (int j = j0; j < j0 + 2; ++j) {
+            const u32x4 kk = relu_bf16x8(st.k[s][j]);
+            acc.z[0] += bf16_lo(kk.x);  acc.z[1] += bf16_hi(kk.x);
+            acc.z[2] += bf16_lo(kk.y);  acc.z[3] += bf16_hi(kk.y);
+            acc.z[4] += bf16_lo(kk.z);  acc.z[5] += bf16_hi(kk.z);
+            acc.z[6] += bf16_lo(kk.w);  acc.z[7] += bf16_hi(kk.w);
+            st.k[s][j] = kk;
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) st.k[s][j0 + j] = st.rot.rotate_with(st.k[s][j0 + j], cs[j]);
+    }
+}
+
 // Accumulates the wave's share (its first DEPTH tiles are requested).  Stages past the share and
 // tokens past t1 hold zeros and add nothing.  tileK, tileV: the wave's private LDS tiles.
+// Software-pipelined by one tile: with one wave per SIMD nothing else fills the matrix core's
+// shadow, so the vector work of tile i + 1 is issued between the MFMAs of tile i.
 template <int DEPTH, int ROPE>
 __device__ __forceinline__ void wide_state_accumulate(WideStateStream<DEPTH, ROPE> &st, unsigned char *tileK,
                                                       unsigned char *tileV, int lane, WideAcc &acc)
 {
     constexpr int NLD = WideStateStream<DEPTH, ROPE>::NLD;
     const int wr_off = (lane >> 4) * kWideRow + (lane & 15) * 16;
+    st.rot.begin_tile(__builtin_amdgcn_readfirstlane(st.walk.template token<kWideTile>(0)));
+    wide_state_prepare(st, 0, acc);
     for (int i0 = 0; i0 < st.walk.count; i0 += DEPTH) {
 #pragma unroll
         for (int s = 0; s < DEPTH; ++s) {
             __builtin_amdgcn_sched_barrier(0);   // stages stay in program order
-            st.rot.begin_tile(st.walk.template token<kWideTile>(i0 + s));
-            // two chunks at a time: their eight table lookups go out first, ReLU and key sums fill the latency
-#pragma unroll
-            for (int j0 = 0; j0 < NLD; j0 += 2) {
-                f32x2 cs[2][4];
-#pragma unroll
-                for (int j = 0; j < 2; ++j) st.rot.fetch(s, j0 + j, cs[j]);
-#pragma unroll
-                for (int j = j0; j < j0 + 2; ++j) {
-                    const u32x4 kk = relu_bf16x8(st.k[s][j]);
-                    acc.z[0] += bf16_lo(kk.x);  acc.z[1] += bf16_hi(kk.x);
-                    acc.z[2] += bf16_lo(kk.y);  acc.z[3] += bf16_hi(kk.y);
-                    acc.z[4] += bf16_lo(kk.z);  acc.z[5] += bf16_hi(kk.z);
-                    acc.z[6] += bf16_lo(kk.w);  acc.z[7] += bf16_hi(kk.w);
-                    st.k[s][j] = kk;
-                }
-#pragma unroll
-                for (int j = 0; j < 2; ++j) st.k[s][j0 + j] = st.rot.rotate_with(st.k[s][j0 + j], cs[j]);
-            }
             wave_lds_fence();   // earlier reads of the tile buffers are done before they are overwritten
 #pragma unroll
             for (int j = 0; j < NLD; ++j) {
@@ -136,6 +148,9 @@ __device__ __forceinline__ void wide_state_accumulate(WideStateStream<DEPTH, ROP
             }
             st.request(s, i0 + s + DEPTH);   // refill this stage: DEPTH tiles ahead
             __builtin_amdgcn_sched_barrier(0);
+            // the next tile's position (has branches: kept out of the MFMA region)
+            st.rot.begin_tile(__builtin_amdgcn_readfirstlane(st.walk.template token<kWideTile>(i0 + s + 1)));
+            __builtin_amdgcn_sched_barrier(0);
             wave_lds_fence();
             bf16x8 a[4], b[4];
 #pragma unroll
@@ -143,11 +158,19 @@ __device__ __forceinline__ void wide_state_accumulate(WideStateStream<DEPTH, ROP
                 a[q] = lds_tr_operand<kWideRow>(tileK, 0, 32 * q, lane);
                 b[q] = lds_tr_operand<kWideRow>(tileV, 0, 32 * q, lane);
             }
+            __builtin_amdgcn_sched_barrier(0);
+            wide_state_prepare(st, (s + 1) % DEPTH, acc);
 #pragma unroll
             for (int rb = 0; rb < 4; ++rb)
 #pragma unroll
                 for (int cb = 0; cb < 4; ++cb)
                     acc.s[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rb], b[cb], acc.s[rb][cb], 0, 0, 0);
+            // one MFMA, then a share of the other instructions, sixteen times over
+#pragma unroll
+            for (int m = 0; m < 16; ++m) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x106, ROPE == kRopeNone ? 6 : 17, 0);
+            }
         }
     }
 }
