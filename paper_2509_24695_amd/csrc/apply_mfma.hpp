@@ -175,7 +175,7 @@ __device__ __forceinline__ void apply_tiles(ApplyStream<DEPTH, ROPE> &st, unsign
             const uint32_t out_off = st.walk.template offset<kApplyTile>(i0 + s, st.row_bytes);
             if (valid) {
                 wave_lds_fence();
-                st.rot.begin_tile(st.walk.template token<kApplyTile>(i0 + s));
+                st.rot.template begin_tile<kApplyTile>(st.walk, i0 + s);
                 // the table lookups of the tile go out first; the ReLU and the plain tile fill their latency
                 f32x2 cs[kApplyTile / 8][4];
 #pragma unroll

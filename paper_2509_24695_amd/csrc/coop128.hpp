@@ -108,7 +108,7 @@ __device__ __forceinline__ void state_accumulate_coop(CoopStateStream<DEPTH, ROP
         unsigned char *bufK = lds + (s & 1) * kCoopTile, *bufV = lds + (2 + (s & 1)) * kCoopTile;
         unsigned char *bufP = lds + (4 + (s & 1)) * kCoopTile;   // un-rotated phi(K), ROPE only
         if (i < count) {
-            st.rot.begin_tile(st.walk.template token<32>(i));
+            st.rot.template begin_tile<32>(st.walk, i);
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const u32x4 kk = relu_bf16x8(st.k[s][j]);
@@ -242,7 +242,7 @@ __device__ __forceinline__ void apply_tiles_coop(CoopApplyStream<DEPTH, ROPE, WA
             const bool valid = i0 + s < st.walk.count;
             const uint32_t out_off = st.valid ? st.walk.template offset<STEP>(i0 + s, st.row_bytes) : kOutOfRange;
             if (valid) {
-                st.rot.begin_tile(st.walk.template token<STEP>(i0 + s));
+                st.rot.template begin_tile<STEP>(st.walk, i0 + s);
                 // the table lookups of the step go out first; ReLU and denominators fill their latency
                 f32x2 cs[NLD][4];
 #pragma unroll

@@ -76,7 +76,7 @@ template <int STEPS, int DEPTH>
 struct Rotator<kRopeNone, STEPS, DEPTH> {
     __device__ __forceinline__ Rotator(const RopeArg &, int, int, int, int, int, int, const unsigned char *) {}
     __device__ __forceinline__ void request(int, bool, int) {}
-    __device__ __forceinline__ void begin_tile(int) {}
+    template <int TILE> __device__ __forceinline__ void begin_tile(const TileWalk &, int) {}
     __device__ __forceinline__ u32x4 rotate(int, int, u32x4 w) const { return w; }
     __device__ __forceinline__ void fetch(int, int, f32x2 (&)[4]) const {}
     __device__ __forceinline__ u32x4 rotate_with(u32x4 w, const f32x2 (&)[4]) const { return w; }
@@ -107,7 +107,7 @@ struct Rotator<kRopeTable, STEPS, DEPTH> {
             cs[s][j][1] = load_cached16(rT, off0 + lane_off + (uint32_t)j * step_bytes + 16u);
         }
     }
-    __device__ __forceinline__ void begin_tile(int) {}
+    template <int TILE> __device__ __forceinline__ void begin_tile(const TileWalk &, int) {}
     __device__ __forceinline__ u32x4 rotate(int s, int j, u32x4 w) const
     {
         return rope_rotate_bf16x8(w, cs[s][j][0], cs[s][j][1]);
@@ -132,14 +132,14 @@ struct Rotator<kRope3D, STEPS, DEPTH> {
     uint32_t base[4], mul_f[4], mul_r[4], mul_c[4];   // entry address of pair q = base + f*mul_f + r*mul_r + c*mul_c
     int rows, cols, rc, frames_m1, row0, rows_per_step;
     float inv_rows, inv_cols;
-    int last_tok, stride, f0, r0, c0, sf, sr, sc;   // wave-uniform: position of the tile in work, and of one stride
+    int sf, sr, sc;                    // wave-uniform: one stride of the walk as (frames, rows, columns)
     int f[STEPS], r[STEPS], c[STEPS];  // position of the lane's rows of the tile in work
 
     __device__ __forceinline__ Rotator(const RopeArg &a, int /*t1*/, int d, int row0_, int rows_per_step_, int pair0,
                                        int /*lane_valid*/, const unsigned char *lds_tab)
         : tab(lds_tab), rows(a.r3.rows), cols(a.r3.cols), rc(a.r3.rows * a.r3.cols), frames_m1(a.r3.frames - 1),
           row0(row0_), rows_per_step(rows_per_step_), inv_rows(1.0f / (float)a.r3.rows),
-          inv_cols(1.0f / (float)a.r3.cols), last_tok(-1), stride(0), f0(0), r0(0), c0(0), sf(0), sr(0), sc(0)
+          inv_cols(1.0f / (float)a.r3.cols), sf(0), sr(0), sc(0)
     {
         const Rope3D &R = a.r3;
         const uint32_t off_h = (uint32_t)(R.frames * R.n_t) * 8u, off_w = off_h + (uint32_t)(R.rows * R.n_h) * 8u;
@@ -163,48 +163,52 @@ struct Rotator<kRope3D, STEPS, DEPTH> {
 
     __device__ __forceinline__ void request(int, bool, int) {}
 
-    // Positions of the lane's rows of the tile that starts at token tok0 (wave-uniform).  A
-    // walk visits tiles a constant stride apart (except where it wraps around), so the
-    // tile's own position is normally the previous one plus the stride's, with two carries;
-    // integer divisions (long instruction sequences on this hardware) are left to the first
-    // tile, the first stride and the wrap.  The rows inside the tile are then reached with
-    // small carries done in floating point: (x + 0.5) / n is at least 0.5 / n away from an
-    // integer and x stays far below 2^20, so the truncated product with the rounded
-    // reciprocal is the exact quotient.
-    __device__ __forceinline__ void begin_tile(int tok0)
+    // Positions of the lane's rows of the i-th tile of the walk; call for i = 0, 1, 2, ... in turn.
+    // A walk visits tiles a constant stride apart except where its cyclic order wraps around, so
+    // normally every row is the same row of the previous tile plus the stride's (frames, rows,
+    // columns), with two carries: ten integer instructions per row and one scalar comparison.
+    // Integer divisions (long instruction sequences on this hardware) are left to the first tile
+    // and the wrap; there the rows inside the tile are reached from the tile's own position
+    // with small carries done in floating point: (x + 0.5) / n is at least 0.5 / n away from
+    // an integer and x stays far below 2^20, so the truncated product with the rounded
+    // reciprocal is the exact quotient.  A frame index is capped at the last frame: that
+    // happens to rows past the last token only (they hold zeros, any entry will do), and a
+    // row past the end stays past the end until the walk wraps.
+    template <int TILE> __device__ __forceinline__ void begin_tile(const TileWalk &w, int i)
     {
-        if (last_tok >= 0 && stride > 0 && tok0 == last_tok + stride) {
-            c0 += sc;
-            const int cr = c0 >= cols;
-            c0 -= cr ? cols : 0;
-            r0 += sr + cr;
-            const int cf = r0 >= rows;
-            r0 -= cf ? rows : 0;
-            f0 += sf + cf;
-        } else {
-            if (last_tok >= 0 && tok0 > last_tok) {       // learn the stride
-                stride = tok0 - last_tok;
+        if (i == 0 || i + w.rot == w.count) {
+            if (i == 0) {                                  // one stride as (frames, rows, columns)
+                const int stride = w.step * TILE;
                 sf = stride / rc;
                 const int srem = stride - sf * rc;
                 sr = srem / cols;
                 sc = srem - sr * cols;
             }
-            f0 = tok0 / rc;
-            const int rem = tok0 - f0 * rc;
-            r0 = rem / cols;
-            c0 = rem - r0 * cols;
-        }
-        last_tok = tok0;
+            const int tok0 = w.template token<TILE>(i);
+            const int f0 = tok0 / rc, rem = tok0 - f0 * rc, r0 = rem / cols, c0 = rem - r0 * cols;
 #pragma unroll
-        for (int j = 0; j < STEPS; ++j) {
-            const int c1 = c0 + row0 + j * rows_per_step;
-            const int dr = (int)(((float)c1 + 0.5f) * inv_cols);
-            const int r1 = r0 + dr;
-            const int df = (int)(((float)r1 + 0.5f) * inv_rows);
-            c[j] = c1 - __mul24(dr, cols);
-            r[j] = r1 - __mul24(df, rows);
-            const int ff = f0 + df;
-            f[j] = ff < frames_m1 ? ff : frames_m1;      // rows past the last token hold zeros: any entry will do
+            for (int j = 0; j < STEPS; ++j) {
+                const int c1 = c0 + row0 + j * rows_per_step;
+                const int dr = (int)(((float)c1 + 0.5f) * inv_cols);
+                const int r1 = r0 + dr;
+                const int df = (int)(((float)r1 + 0.5f) * inv_rows);
+                c[j] = c1 - __mul24(dr, cols);
+                r[j] = r1 - __mul24(df, rows);
+                const int ff = f0 + df;
+                f[j] = ff < frames_m1 ? ff : frames_m1;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < STEPS; ++j) {
+                const int cc = c[j] + sc;
+                const bool cr = cc >= cols;
+                c[j] = cr ? cc - cols : cc;
+                const int rr = r[j] + sr + (cr ? 1 : 0);
+                const bool cf = rr >= rows;
+                r[j] = cf ? rr - rows : rr;
+                const int ff = f[j] + sf + (cf ? 1 : 0);
+                f[j] = ff < frames_m1 ? ff : frames_m1;
+            }
         }
     }
 

@@ -237,7 +237,7 @@ __device__ __forceinline__ void state_accumulate(StateStream<TILE, DEPTH, ROPE> 
             // waited for) before this stage has been refilled
             __builtin_amdgcn_sched_barrier(0);
             // phi(K) on the packed pairs
-            st.rot.begin_tile(st.walk.template token<TILE>(i0 + s));
+            st.rot.template begin_tile<TILE>(st.walk, i0 + s);
             // the table lookups of the tile go out first; ReLU and key sums fill their latency
             f32x2 cs[TILE / 8][4];
 #pragma unroll

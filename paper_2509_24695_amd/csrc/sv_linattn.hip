@@ -30,7 +30,9 @@ constexpr int kVersion = 500;   // 0.5.0
 constexpr int kStateTile = 32, kStateWaves = 4, kApplyWaves = 4;
 constexpr int kCoopApplyWaves = 4, kCoopApplyNB = 1;   // d = 112/128 apply: one 128 x 32 panel of S per wave, two workgroups per compute unit
 constexpr int kStateDepth = 2, kApplyDepth = 2;
-constexpr int kWideStateDepth = 3;            // 16-token tiles of the wave-private d = 112/128 state kernel
+// 16-token tiles in flight per wave of the wave-private d = 112/128 state kernel: three, or two with the
+// factored rotation tables (that form is bound by its arithmetic and needs the registers)
+constexpr int kWideStateDepth = 3, kWideStateDepth3D = 2;
 constexpr int kCoopStateDepth = 4;            // 32-token tiles of the shared-tile d = 112/128 state kernel (full-table RoPE)
 constexpr int kFusedStateDepth[3] = {2, 2, 2};   // one-launch block step (d = 64), by RoPE mode
 constexpr int kFusedApplyDepth[3] = {6, 2, 6};   // Q tiles held in registers across the in-kernel waits
@@ -79,7 +81,7 @@ template <int ROPE> struct Kernels<128, ROPE> {
     // the wave-private kernel spends on the whole 128 x 128 state (then: one tile shared by the four waves).
     static constexpr bool kWideState = ROPE != kRopeTable;
     template <bool FINALIZE> static constexpr auto pick_state() {
-        if constexpr (kWideState) return &state_mfma_wide<kWideStateDepth, FINALIZE, ROPE>;
+        if constexpr (kWideState) return &state_mfma_wide<(ROPE == kRope3D ? kWideStateDepth3D : kWideStateDepth), FINALIZE, ROPE>;
         else return &state_mfma_d128<kCoopStateDepth, FINALIZE, ROPE>;
     }
     static constexpr auto state = pick_state<true>();

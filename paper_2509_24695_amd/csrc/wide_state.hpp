@@ -134,7 +134,7 @@ __device__ __forceinline__ void wide_state_accumulate(WideStateStream<DEPTH, ROP
 {
     constexpr int NLD = WideStateStream<DEPTH, ROPE>::NLD;
     const int wr_off = (lane >> 4) * kWideRow + (lane & 15) * 16;
-    st.rot.begin_tile(__builtin_amdgcn_readfirstlane(st.walk.template token<kWideTile>(0)));
+    st.rot.template begin_tile<kWideTile>(st.walk, 0);
     wide_state_prepare(st, 0, acc);
     for (int i0 = 0; i0 < st.walk.count; i0 += DEPTH) {
 #pragma unroll
@@ -149,7 +149,7 @@ __device__ __forceinline__ void wide_state_accumulate(WideStateStream<DEPTH, ROP
             st.request(s, i0 + s + DEPTH);   // refill this stage: DEPTH tiles ahead
             __builtin_amdgcn_sched_barrier(0);
             // the next tile's position (has branches: kept out of the MFMA region)
-            st.rot.begin_tile(__builtin_amdgcn_readfirstlane(st.walk.template token<kWideTile>(i0 + s + 1)));
+            st.rot.template begin_tile<kWideTile>(st.walk, i0 + s + 1);
             __builtin_amdgcn_sched_barrier(0);
             wave_lds_fence();
             bf16x8 a[4], b[4];
