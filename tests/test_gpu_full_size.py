@@ -169,3 +169,53 @@ def test_rope_h20d112_full_size_sampled():
         sv.sv_block_linattn_step_rope(qd, kd, vd, sv.desc_of(qd), torch.from_numpy(tables[m]).cuda(), S, z, wb.eps, o, ws)
         torch.cuda.synchronize()
         metrics.check(to_host(o), refs[m][0], "bf16", f"rope block {m}")
+
+
+@pytest.mark.parametrize("name", ["bidir_480p", "bidir_480p_h20d112"])
+def test_rope3d_full_size_sampled(name):
+    """The factored-table entry points at the size and in the launch configuration bench.py times:
+    long tile walks (many strides per wave, staggered starts, the cyclic wrap), state in full against
+    the oracle on the expanded table, O on sampled ranges; then three blocks of the block-causal stream
+    with the time axis continuing."""
+    import torch
+    w = wl.workload(name)
+    say(f"rope3d {w.name} full size B={w.B} H={w.H} N={w.N} d={w.d}")
+    Q, K, V = wl.draw_qkv(w)
+    T = wl.rope_table_3d(*w.grid, w.d)
+    R = sv.Rope3D.from_tensors(*(torch.from_numpy(t).cuda() for t in wl.rope_tables_3d_factored(*w.grid, w.d)))
+    Qd, Kd, Vd = to_dev(Q), to_dev(K), to_dev(V)
+    S, z = new_state(w.B, w.H, w.d)
+    ws = new_workspace(w.B, w.H, w.N, w.d)
+    O = torch.empty_like(Qd)
+    dsc = sv.desc_of(Qd)
+    sv.sv_linattn_state_rope3d(Kd, Vd, dsc, R, 0, w.N, 0, S, z, ws)
+    sv.sv_linattn_apply_rope3d(Qd, dsc, R, 0, w.N, S, z, w.eps, O)
+    torch.cuda.synchronize()
+    S_ref, z_ref = orc.state(K, V, rope=T)
+    assert metrics.rel_l2(to_host(S), S_ref) <= 3e-3          # rotated keys are rounded to bf16 once more
+    assert metrics.rel_l2(to_host(z), z_ref) <= STATE_TOL and metrics.max_rel(to_host(z), z_ref) <= STATE_TOL
+    Oh = to_host(O)
+    assert np.isfinite(Oh).all()
+    for (a, b) in _ranges(w.N, 78):
+        metrics.check(Oh[:, :, a:b], orc.apply(Q, S_ref, z_ref, w.eps, a, b, rope=T), "bf16", f"tokens [{a},{b})")
+    # an apply over a range that starts and ends inside tiles: other rows stay untouched
+    O2 = torch.full_like(Qd, 7.0)
+    a, b = 4681, 23457
+    sv.sv_linattn_apply_rope3d(Qd, dsc, R, a, b, S, z, w.eps, O2)
+    torch.cuda.synchronize()
+    assert torch.equal(O2[:, :, a:b], O[:, :, a:b])
+    assert bool((O2[:, :, :a] == 7.0).all()) and bool((O2[:, :, b:] == 7.0).all())
+    # block stream
+    wb = wl.workload("block_480p" if w.d == 64 else "block_480p_h20d112")
+    S, z = new_state(wb.B, wb.H, wb.d)
+    blocks = [tuple(np.ascontiguousarray(t[:, :, m * wb.N:(m + 1) * wb.N]) for t in (Q, K, V)) for m in range(3)]
+    tables = [wl.rope_table_3d(*wb.grid, wb.d, t0=m * wb.grid[0]) for m in range(3)]
+    refs = list(orc.block_stream(blocks, wb.eps, ropes=tables))
+    for m, (q, k, v) in enumerate(blocks):
+        qd, kd, vd = to_dev(q), to_dev(k), to_dev(v)
+        o = torch.empty_like(qd)
+        Rm = sv.Rope3D.from_tensors(*(torch.from_numpy(t).cuda()
+                                      for t in wl.rope_tables_3d_factored(*wb.grid, wb.d, t0=m * wb.grid[0])))
+        sv.sv_block_linattn_step_rope3d(qd, kd, vd, sv.desc_of(qd), Rm, S, z, wb.eps, o, ws)
+        torch.cuda.synchronize()
+        metrics.check(to_host(o), refs[m][0], "bf16", f"rope3d block {m}")
