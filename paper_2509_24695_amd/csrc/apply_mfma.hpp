@@ -56,6 +56,56 @@ struct ApplyOperands {
     bf16x8 s[NS][NB][KS];          // [hi/lo][row block][k-step]
     bf16x8 zrow[ZROWS ? KS : 1];   // [k-step]
 
+    // The same operands (DP = 64, value block 0), fetched once per workgroup instead of once per wave:
+    // wave w converts k-step w of S and hands it round through `stage` (16 KB of LDS, free again
+    // when this returns); the two z rows are cheap enough for every wave to take itself.  Must be
+    // called by all four waves.
+    __device__ __forceinline__ void load_shared(const float *__restrict__ Sh, const float *__restrict__ zh, int wave,
+                                                int lane, unsigned char *stage)
+    {
+        static_assert(DP == 64 && ZROWS, "the d = 64 apply kernel");
+        bf16x8 *st = reinterpret_cast<bf16x8 *>(stage);       // [hi/lo][row block][k-step][lane]
+        const int m = lane & 31, g = lane >> 5;
+#pragma unroll
+        for (int rb = 0; rb < NB; ++rb) {
+            const int F = 16 * NB * ((m >> 2) & 1) + 16 * rb + 4 * (m >> 3) + (m & 3);
+            uint32_t hi[4], lo[4];
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const int k = 16 * wave + 8 * g + 2 * p;
+                const float a = Sh[k * 64 + F], b = Sh[(k + 1) * 64 + F];
+                hi[p] = pack_bf16x2(a, b);
+                lo[p] = pack_bf16x2(a - bf16_lo(hi[p]), b - bf16_hi(hi[p]));
+            }
+            const u32x4 h4 = {hi[0], hi[1], hi[2], hi[3]}, l4 = {lo[0], lo[1], lo[2], lo[3]};
+            st[((0 * NB + rb) * KS + wave) * 64 + lane] = __builtin_bit_cast(bf16x8, h4);
+            st[((1 * NB + rb) * KS + wave) * 64 + lane] = __builtin_bit_cast(bf16x8, l4);
+        }
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            uint32_t w[4];
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const int k = 16 * ks + 8 * g + 2 * p;
+                const float a = zh[k], b = zh[k + 1];
+                const uint32_t hi = pack_bf16x2(a, b);
+                const uint32_t lo = pack_bf16x2(a - bf16_lo(hi), b - bf16_hi(hi));
+                w[p] = m == 0 ? hi : (m == 1 ? lo : 0u);
+            }
+            const u32x4 w4 = {w[0], w[1], w[2], w[3]};
+            zrow[ks] = __builtin_bit_cast(bf16x8, w4);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int rb = 0; rb < NB; ++rb) {
+                s[0][rb][ks] = st[((0 * NB + rb) * KS + ks) * 64 + lane];
+                if (HILO) s[NS - 1][rb][ks] = st[((1 * NB + rb) * KS + ks) * 64 + lane];
+            }
+        __syncthreads();                        // `stage` may be written again
+    }
+
     // COHERENT: the state was written by another workgroup of this same kernel.
     template <bool COHERENT>
     __device__ __forceinline__ void load(const float *__restrict__ Sh, const float *__restrict__ zh, int d, int vb,
@@ -261,7 +311,11 @@ __host__ __device__ constexpr int apply_lds_bytes() { return WAVES * apply_wave_
 
 // grid = (C, B*H), block = 64*WAVES.  Wave w of workgroup c owns tiles
 // WAVES*c + w + WAVES*C*i (i = 0, 1, ...) of the T = ceil((t1-t0)/32) tiles,
-// the same round-robin deal as the state kernel.
+// the same round-robin deal as the state kernel.  Without RoPE the host launches eight times as
+// many workgroups as fit the device at once (four tiles per wave at 32 760 tokens and 32 heads):
+// short-lived workgroups handed out in order by the dispatcher stream better than 256 that loop
+// (pure copies show the same: 45 against 49 us), and what made them too expensive before - every
+// wave fetching and converting all of S - is now done once per workgroup.
 // HILO = false drops the low half of S (one MFMA pass instead of two).
 // ROPE (kRopeNone/Table/3D); with kRope3D the dynamic LDS carries kRope3dLdsBytes more.
 template <bool HILO, int WAVES, int DEPTH, int ROPE>
@@ -286,7 +340,8 @@ __global__ __launch_bounds__(64 * WAVES, 1) void apply_mfma_d64(
         __syncthreads();
     }
     ApplyOperands<64, HILO> A;
-    A.template load<false>(S + (size_t)bh * 64 * 64, z + (size_t)bh * 64, 64, 0, lane);
+    static_assert(apply_lds_bytes<WAVES, ROPE>() >= 2 * 2 * 4 * 64 * 16 && WAVES == 4, "the tiles can stage S for load_shared");
+    A.load_shared(S + (size_t)bh * 64 * 64, z + (size_t)bh * 64, wave, lane, lds);   // through the tiles, not yet in use
     apply_tiles<HILO>(stream, lds + wave * apply_wave_lds_bytes<ROPE>(), lane, A, eps);
 }
 

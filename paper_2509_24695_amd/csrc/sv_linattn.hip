@@ -72,7 +72,10 @@ template <int ROPE> struct Kernels<64, ROPE> {
     static constexpr int state_wg_tokens = kStateTile * kStateWaves;
     static constexpr int fused_wg_tokens = state_wg_tokens;
     static constexpr int apply_wg_tokens = kApplyTile * kApplyWaves;
-    static constexpr int apply_threads = 64 * kApplyWaves, apply_wgs_per_cu = 1;
+    static constexpr int apply_threads = 64 * kApplyWaves;
+    // workgroups launched per compute unit: the plain kernel's are short-lived and queue up (see apply_mfma_d64);
+    // the RoPE kernels hold more registers and, with factored tables, fill their tables per workgroup
+    static constexpr int apply_wgs_per_cu = ROPE == kRopeNone ? 8 : 1;
 };
 template <int ROPE> struct Kernels<128, ROPE> {
     static constexpr int W = 1;
