@@ -94,7 +94,10 @@ template <int ROPE> struct Kernels<128, ROPE> {
     static constexpr int apply_lds = coop_apply_lds_bytes<kCoopApplyWaves, kCoopApplyNB>() + kTab;
     static constexpr int state_wg_tokens = kWideState ? 4 * kWideTile : 32;   // four private tiles, or one shared
     static constexpr int apply_wg_tokens = 8 * kCoopApplyWaves * kCoopApplyNB;   // the waves of a workgroup share its tiles
-    static constexpr int apply_threads = 64 * kCoopApplyWaves, apply_wgs_per_cu = 8 / (kCoopApplyWaves * kCoopApplyNB);
+    static constexpr int apply_threads = 64 * kCoopApplyWaves;
+    // workgroups per compute unit: with one 128 x 32 panel per wave (136-164 registers, 17-50 KB of LDS) three are
+    // resident; with a full rotation table two (three measured 98 against 89 us: its rows crowd the caches)
+    static constexpr int apply_wgs_per_cu = kCoopApplyNB != 1 ? 8 / (kCoopApplyWaves * kCoopApplyNB) : ROPE == kRopeTable ? 2 : 3;
 };
 
 template <int DP, int ROPE> void init_kernels(Device &d)
