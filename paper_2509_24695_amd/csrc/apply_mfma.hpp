@@ -59,7 +59,8 @@ struct ApplyOperands {
     // The same operands (DP = 64, value block 0), fetched once per workgroup instead of once per wave:
     // wave w converts k-step w of S and hands it round through `stage` (16 KB of LDS, free again
     // when this returns); the two z rows are cheap enough for every wave to take itself.  Must be
-    // called by all four waves.
+    // called by all four waves.  COHERENT: the state was written by another workgroup of this same kernel.
+    template <bool COHERENT>
     __device__ __forceinline__ void load_shared(const float *__restrict__ Sh, const float *__restrict__ zh, int wave,
                                                 int lane, unsigned char *stage)
     {
@@ -73,7 +74,8 @@ struct ApplyOperands {
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
                 const int k = 16 * wave + 8 * g + 2 * p;
-                const float a = Sh[k * 64 + F], b = Sh[(k + 1) * 64 + F];
+                const float a = COHERENT ? load_coherent1(Sh + k * 64 + F) : Sh[k * 64 + F];
+                const float b = COHERENT ? load_coherent1(Sh + (k + 1) * 64 + F) : Sh[(k + 1) * 64 + F];
                 hi[p] = pack_bf16x2(a, b);
                 lo[p] = pack_bf16x2(a - bf16_lo(hi[p]), b - bf16_hi(hi[p]));
             }
@@ -87,7 +89,8 @@ struct ApplyOperands {
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
                 const int k = 16 * ks + 8 * g + 2 * p;
-                const float a = zh[k], b = zh[k + 1];
+                const float a = COHERENT ? load_coherent1(zh + k) : zh[k];
+                const float b = COHERENT ? load_coherent1(zh + k + 1) : zh[k + 1];
                 const uint32_t hi = pack_bf16x2(a, b);
                 const uint32_t lo = pack_bf16x2(a - bf16_lo(hi), b - bf16_hi(hi));
                 w[p] = m == 0 ? hi : (m == 1 ? lo : 0u);
@@ -341,7 +344,7 @@ __global__ __launch_bounds__(64 * WAVES, 1) void apply_mfma_d64(
     }
     ApplyOperands<64, HILO> A;
     static_assert(apply_lds_bytes<WAVES, ROPE>() >= 2 * 2 * 4 * 64 * 16 && WAVES == 4, "the tiles can stage S for load_shared");
-    A.load_shared(S + (size_t)bh * 64 * 64, z + (size_t)bh * 64, wave, lane, lds);   // through the tiles, not yet in use
+    A.template load_shared<false>(S + (size_t)bh * 64 * 64, z + (size_t)bh * 64, wave, lane, lds);   // through the tiles, not yet in use
     apply_tiles<HILO>(stream, lds + wave * apply_wave_lds_bytes<ROPE>(), lane, A, eps);
 }
 

@@ -100,7 +100,8 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
 
     // ---- apply the updated state to this workgroup's share of Q_b --------------------------------
     ApplyOperands<64, HILO> A;
-    A.template load<true>(Sh, zh, 64, 0, lane);
+    static_assert(WAVES == 4 && block_step_lds_bytes<TILE, WAVES, ROPE>() >= 2 * 2 * 4 * 64 * 16, "LDS can stage S for load_shared");
+    A.template load_shared<true>(Sh, zh, wave, lane, lds);   // through LDS that the state phase has left and the apply phase not yet taken
     apply_tiles<HILO>(qstream, lds + wave * apply_wave_lds_bytes<ROPE>(), lane, A, eps);
 }
 
