@@ -36,10 +36,10 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix rate, published
 # 128-byte requests these kernels and the copy issue as 64 bytes; WRITE_SIZE x 1.0000).  Source:
 # profiles/traffic_pmc_bench_kernels.txt.  Algorithmic bytes per launch are 268 369 920.
 MEASURED_TRAFFIC_BYTES = {
-    ("apply", "bidir_480p"): int((67679.9 * 1.99964 + 131040.0) * 1024),
-    ("state", "bidir_480p"): int((133374.0 * 1.99964 + 4688.0) * 1024),
-    ("apply", "bidir_480p_h20d112"): int((75719.1 * 1.99964 + 143325.0) * 1024),
-    ("state", "bidir_480p_h20d112"): int((149563.7 * 1.99964 + 12861.2) * 1024),
+    ("apply", "bidir_480p"): int((67669.6 * 1.99963 + 131050.4) * 1024),
+    ("state", "bidir_480p"): int((133374.3 * 1.99963 + 4688.0) * 1024),
+    ("apply", "bidir_480p_h20d112"): int((75719.1 * 1.99963 + 143325.1) * 1024),
+    ("state", "bidir_480p_h20d112"): int((149565.8 * 1.99963 + 12861.2) * 1024),
 }
 
 
