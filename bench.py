@@ -349,10 +349,16 @@ def cpu_baseline(w, sets, torch):
         dt = time.perf_counter() - t0
         best = dt if best is None else min(best, dt)
         passes += 1
+    cpu_model = ""
+    try:
+        with open("/proc/cpuinfo") as f:
+            cpu_model = next((l.split(":", 1)[1].strip() for l in f if l.startswith("model name")), "")
+    except OSError:
+        pass
     return {"value": w.B * w.N / best, "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle",
             "sample": f"full {w.name} workload (B={w.B}, H={w.H}, N={w.N}, d={w.d}), best of {passes} passes, "
                       f"{best:.3f} s per pass, float64",
-            "seconds_per_pass": best}
+            "seconds_per_pass": best, "cpu_model": cpu_model}
 
 
 def main():
