@@ -8,12 +8,12 @@
 // reduces its round-robin share of the block's keys and values to a partial
 // state and publishes it with an epoch-tagged flag; when all partials of its
 // head are there it folds one slice of them into the carried S, z in chunk
-// order, publishes again, and waits for the other slices, with its first Q
-// tiles already in flight.  Every wait polls a bounded number of times, so
-// every wave always reaches the end of the kernel.  Then all workgroups apply
-// the new state to their share of Q_b.  The dependency
-// "all of the block's keys before any of its outputs" is per head, not grid
-// wide, so heads drift past each other and reads overlap writes.
+// order, publishes again, and waits for the other slices (one wave does this,
+// the others have their first Q tiles in flight meanwhile).  Every wait polls a
+// bounded number of times, so every wave always reaches the end of the kernel.
+// Then all workgroups apply the new state to their share of Q_b.  The
+// dependency "all of the block's keys before any of its outputs" is per head,
+// not grid wide, so heads drift past each other and reads overlap writes.
 #pragma once
 
 #include "apply_mfma.hpp"
@@ -41,7 +41,6 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
     unsigned long long epoch, uint32_t spin_limit)
 {
     static_assert(TILE == kApplyTile, "both phases walk tiles of the same size");
-    constexpr int THREADS = 64 * WAVES;
     constexpr int kTileBytes = TILE * kRowBytes;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
@@ -62,16 +61,6 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
     // kRope3D: the tables sit behind everything else in LDS and live through both phases
     const unsigned char *lds_tab = lds + block_step_lds_bytes<TILE, WAVES, ROPE>();
 
-    // Once all partials of the head are there, fold this workgroup's slice into S, z, then wait for
-    // the other slices.
-    auto agree_on_state = [&]() __attribute__((always_inline)) {
-        epoch = es.resolve(reinterpret_cast<unsigned long long *>(
-            lds + block_step_lds_bytes<TILE, WAVES, ROPE>() - kEpochLdsBytes));
-        state_publish_and_wait(ws, BH, elems, bh, c, C, 0, epoch, spin_limit, lane);
-        state_finalize_slice<THREADS, true>(partials, c, C, d, Sc, zc, Sh, zh);
-        state_publish_and_wait(ws, BH, elems, bh, c, C, 1, epoch, spin_limit, lane);
-    };
-
     // ---- this wave's first two tiles of Q_b are requested right away: they arrive during the
     //      state phase and make no later load wait behind them --------------------------------
     constexpr int kEarly = DEPTH_A < 2 ? DEPTH_A : 2;
@@ -91,17 +80,37 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
             __syncthreads();
         }
         state_accumulate(kvstream, tileK, tileK + kTileBytes, lane, acc);
-        // the rest of this wave's Q prefetch streams in while the head's state is being agreed on
-        apply_prefetch<kEarly, DEPTH_A>(qstream);
         state_wg_reduce_store<WAVES, ROPE != kRopeNone>(acc, reinterpret_cast<float *>(lds), wave, lane,
                                            partials + (size_t)c * elems);
     }
-    agree_on_state();
+    // ---- the head agrees on its new state ------------------------------------------------------
+    // Wave 0 alone waits for the head's partials, folds this workgroup's slice into S, z, publishes
+    // it and waits for the other slices: a chain of memory round trips.  The other waves request the
+    // rest of their Q prefetch meanwhile (wave 0 after the chain).  Memory operations of a wave
+    // complete in order, so a wave with tiles in flight would see each answer of the chain only after
+    // its tiles, and the chain and the prefetch would take turns instead of overlapping.
+    epoch = es.resolve(reinterpret_cast<unsigned long long *>(
+        lds + block_step_lds_bytes<TILE, WAVES, ROPE>() - kEpochLdsBytes));
+    const StateSlice sl(c, C, d);
+    f32x2 carry[5];
+    if (wave == 0) state_slice_carry<kWave>(sl, Sc, zc, lane, carry);
+    state_publish(ws, BH, elems, bh, c, 0, epoch);
+    if (wave != 0) {
+        apply_prefetch<kEarly, DEPTH_A>(qstream);
+    } else {
+        state_wait(ws, BH, elems, bh, C, 0, epoch, spin_limit, lane);
+        state_finalize_slice<kWave, true, 5, 8>(partials, sl, C, Sc, zc, Sh, zh, lane, carry);
+        coherent_stores_done();
+        if (lane == 0) flag_publish(ws_flags(ws, BH, elems, bh, 1) + c, epoch);
+        state_wait(ws, BH, elems, bh, C, 1, epoch, spin_limit, lane);
+    }
+    __syncthreads();
 
     // ---- apply the updated state to this workgroup's share of Q_b --------------------------------
     ApplyOperands<64, HILO> A;
     static_assert(WAVES == 4 && block_step_lds_bytes<TILE, WAVES, ROPE>() >= 2 * 2 * 4 * 64 * 16, "LDS can stage S for load_shared");
     A.template load_shared<true>(Sh, zh, wave, lane, lds);   // through LDS that the state phase has left and the apply phase not yet taken
+    if (wave == 0) apply_prefetch<kEarly, DEPTH_A>(qstream);
     apply_tiles<HILO>(qstream, lds + wave * apply_wave_lds_bytes<ROPE>(), lane, A, eps);
 }
 

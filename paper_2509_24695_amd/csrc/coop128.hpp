@@ -365,9 +365,13 @@ __global__ __launch_bounds__(256, 1) void state_mfma_d128(
     state_wg_quadrant_store(acc, reinterpret_cast<float *>(lds), wave, lane, d, partials + (size_t)c * elems);
     if (FINALIZE) {
         epoch = es.resolve(reinterpret_cast<unsigned long long *>(lds + state_d128_lds_bytes<ROPE>() - kEpochLdsBytes));
+        const float *Sc = S_in ? S_in + (size_t)bh * d * d : nullptr, *zc = z_in + (size_t)bh * d;
+        const StateSlice sl(c, C, d);
+        f32x2 carry[3];
+        state_slice_carry<256>(sl, Sc, zc, (int)threadIdx.x, carry);
         state_publish_and_wait(ws, BH, elems, bh, c, C, 0, epoch, spin_limit, lane);
-        state_finalize_slice<256, false>(partials, c, C, d, S_in ? S_in + (size_t)bh * d * d : nullptr,
-                                         z_in + (size_t)bh * d, S_out + (size_t)bh * d * d, z_out + (size_t)bh * d);
+        state_finalize_slice<256, false>(partials, sl, C, Sc, zc, S_out + (size_t)bh * d * d, z_out + (size_t)bh * d,
+                                         (int)threadIdx.x, carry);
     }
 }
 

@@ -369,41 +369,73 @@ __device__ __forceinline__ void state_wg_quadrant_store(StateAcc &acc, float *sl
     }
 }
 
-// Slice c of the head's state (8-byte units [c*per, (c+1)*per) of the
-// d*d + d values, per = ceil(units / C)):
-//   S_out, z_out = (S_in, z_in or 0) + partial[0] + partial[1] + ... + partial[C-1], in that order.
-// S_in may be null (no carried state) or equal to S_out (update in place).
-// Partials come in through coherent loads, up to eight chunks in flight.
-// COHERENT_OUT: also store the result coherently (other workgroups of this
-// kernel are going to read it).
-template <int THREADS, bool COHERENT_OUT>
-__device__ __forceinline__ void state_finalize_slice(const float *__restrict__ partials, int c, int C, int d,
-                                                     const float *S_in, const float *z_in, float *S_out,
-                                                     float *z_out)
+// Slice c of the head's state: 8-byte units [c*per, (c+1)*per) of the d*d + d values,
+// per = ceil(units / C).  A thread works on UNITS units at once, THREADS apart.
+struct StateSlice {
+    int s_units, units, lo, hi;
+    __device__ __forceinline__ StateSlice(int c, int C, int d)
+    {
+        s_units = d * d / 2;
+        units = s_units + d / 2;
+        const int per = (units + C - 1) / C;
+        lo = c * per;
+        hi = lo + per < units ? lo + per : units;
+    }
+};
+
+// The carried values (S_in, z_in; zeros if S_in is null) of the units a thread folds first.  They do
+// not depend on the other workgroups, so they are fetched before the wait for the partials, off
+// the chain of round trips that follows it.
+template <int THREADS, int UNITS>
+__device__ __forceinline__ void state_slice_carry(const StateSlice &sl, const float *S_in, const float *z_in, int tid,
+                                                  f32x2 (&x)[UNITS])
 {
-    constexpr int GROUP = 16;                                    // chunks in flight per unit
-    constexpr int UNITS = 3;                                     // units a thread works on at once: the loads of a
-                                                                 // round trip of ~1 us are all issued before any is used
-    const int s_units = d * d / 2, units = s_units + d / 2, elems = 2 * units;
-    const int per = (units + C - 1) / C;
-    const int lo = c * per, hi = lo + per < units ? lo + per : units;
-    for (int v0 = lo + (int)threadIdx.x; v0 < hi; v0 += THREADS * UNITS) {
-        f32x2 x[UNITS];
+#pragma unroll
+    for (int u = 0; u < UNITS; ++u) x[u] = f32x2{0.f, 0.f};
+    if (S_in) {
 #pragma unroll
         for (int u = 0; u < UNITS; ++u) {
-            const int v = v0 + u * THREADS;
-            x[u] = f32x2{0.f, 0.f};
-            if (S_in && v < hi) x[u] = *reinterpret_cast<const f32x2 *>(v < s_units ? S_in + 2 * v : z_in + 2 * (v - s_units));
+            int v = sl.lo + tid + u * THREADS;               // beyond the slice: any valid unit, the value is not used
+            v = v < sl.units ? v : sl.units - 1;
+            x[u] = *reinterpret_cast<const f32x2 *>(v < sl.s_units ? S_in + 2 * v : z_in + 2 * (v - sl.s_units));
+        }
+    }
+}
+
+//   S_out, z_out = (S_in, z_in or 0) + partial[0] + partial[1] + ... + partial[C-1], in that order,
+// for the slice.  S_in may be null (no carried state) or equal to S_out (update in place); `carry`
+// holds what state_slice_carry fetched.  Partials come in through coherent loads, GROUP chunks in
+// flight per unit: the loads of a round trip of ~1 us are all issued before any is used.
+// COHERENT_OUT: also store the result coherently (other workgroups of this kernel are going to
+// read it).  Called by THREADS threads numbered tid = 0 .. THREADS - 1 (a workgroup, or one wave).
+template <int THREADS, bool COHERENT_OUT, int UNITS = 3, int GROUP = 16>
+__device__ __forceinline__ void state_finalize_slice(const float *__restrict__ partials, const StateSlice &sl, int C,
+                                                     const float *S_in, const float *z_in, float *S_out,
+                                                     float *z_out, int tid, const f32x2 (&carry)[UNITS])
+{
+    const int s_units = sl.s_units, elems = 2 * sl.units, hi = sl.hi;
+    for (int v0 = sl.lo + tid; v0 < hi; v0 += THREADS * UNITS) {
+        f32x2 x[UNITS];
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) x[u] = carry[u];
+        if (v0 != sl.lo + tid) {                                 // slices longer than one round: fetched here
+#pragma unroll
+            for (int u = 0; u < UNITS; ++u) {
+                const int v = v0 + u * THREADS;
+                x[u] = f32x2{0.f, 0.f};
+                if (S_in && v < hi) x[u] = *reinterpret_cast<const f32x2 *>(v < s_units ? S_in + 2 * v : z_in + 2 * (v - s_units));
+            }
         }
         for (int c0 = 0; c0 < C; c0 += GROUP) {
             f32x2 p[UNITS][GROUP];
 #pragma unroll
             for (int u = 0; u < UNITS; ++u) {
-                const int v = v0 + u * THREADS;
+                int v = v0 + u * THREADS;                        // beyond the slice: any valid unit, the sum is not stored
+                v = v < sl.units ? v : sl.units - 1;
 #pragma unroll
                 for (int cc = 0; cc < GROUP; ++cc) {
                     p[u][cc] = f32x2{0.f, 0.f};
-                    if (c0 + cc < C && v < hi) p[u][cc] = load_coherent(partials + (size_t)(c0 + cc) * elems + 2 * v);
+                    if (c0 + cc < C) p[u][cc] = load_coherent(partials + (size_t)(c0 + cc) * elems + 2 * v);
                 }
             }
 #pragma unroll
@@ -506,10 +538,13 @@ __global__ __launch_bounds__(64 * WAVES, 1) void state_mfma_d64(
                                                     partials + (size_t)c * kStateElems);
     if (FINALIZE) {
         epoch = es.resolve(reinterpret_cast<unsigned long long *>(lds + state_lds_bytes<TILE, WAVES>() - kEpochLdsBytes));
+        const float *Sc = S_in ? S_in + (size_t)bh * 64 * 64 : nullptr, *zc = z_in + (size_t)bh * 64;
+        const StateSlice sl(c, C, 64);
+        f32x2 carry[3];
+        state_slice_carry<THREADS>(sl, Sc, zc, tid, carry);
         state_publish_and_wait(ws, BH, kStateElems, bh, c, C, 0, epoch, spin_limit, lane);
-        state_finalize_slice<THREADS, false>(partials, c, C, 64, S_in ? S_in + (size_t)bh * 64 * 64 : nullptr,
-                                             z_in + (size_t)bh * 64, S_out + (size_t)bh * 64 * 64,
-                                             z_out + (size_t)bh * 64);
+        state_finalize_slice<THREADS, false>(partials, sl, C, Sc, zc, S_out + (size_t)bh * 64 * 64,
+                                             z_out + (size_t)bh * 64, tid, carry);
     }
 }
 
