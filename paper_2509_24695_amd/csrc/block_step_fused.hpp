@@ -64,7 +64,11 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
     // ---- this wave's first two tiles of Q_b are requested right away: they arrive during the
     //      state phase and make no later load wait behind them --------------------------------
     constexpr int kEarly = DEPTH_A < 2 ? DEPTH_A : 2;
-    const TileWalk walk(0, WAVES * c + wave, WAVES * C, n_tiles, bh);
+    // Shares are dealt to the workgroups starting at a different one in each head: when the tiles do not
+    // divide evenly the longer shares fall on low share numbers, and workgroup c of every head runs on
+    // the same die (consecutive workgroup ids go round the dies).
+    const int share = (c + bh) % C;
+    const TileWalk walk(0, WAVES * share + wave, WAVES * C, n_tiles, bh);
     ApplyStream<DEPTH_A, ROPE> qstream(Q + head_off, O + head_off, rope, lds_tab, st.n, N, lane, walk);
     apply_prefetch<0, kEarly>(qstream);
 
@@ -81,7 +85,7 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
         }
         state_accumulate(kvstream, tileK, tileK + kTileBytes, lane, acc);
         state_wg_reduce_store<WAVES, ROPE != kRopeNone>(acc, reinterpret_cast<float *>(lds), wave, lane,
-                                           partials + (size_t)c * elems);
+                                           partials + (size_t)share * elems);   // slot = share: the fold adds the shares in tile order
     }
     // ---- the head agrees on its new state ------------------------------------------------------
     // Wave 0 alone waits for the head's partials, folds this workgroup's slice into S, z, publishes
