@@ -67,7 +67,7 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
     // Shares are dealt to the workgroups starting at a different one in each head: when the tiles do not
     // divide evenly the longer shares fall on low share numbers, and workgroup c of every head runs on
     // the same die (consecutive workgroup ids go round the dies).
-    const int share = (c + bh) % C;
+    const int share = block_step_share(c, bh, C);
     const TileWalk walk(0, WAVES * share + wave, WAVES * C, n_tiles, bh);
     ApplyStream<DEPTH_A, ROPE> qstream(Q + head_off, O + head_off, rope, lds_tab, st.n, N, lane, walk);
     apply_prefetch<0, kEarly>(qstream);

@@ -369,20 +369,6 @@ __device__ __forceinline__ void state_wg_quadrant_store(StateAcc &acc, float *sl
     }
 }
 
-// Slice c of the head's state: 8-byte units [c*per, (c+1)*per) of the d*d + d values,
-// per = ceil(units / C).  A thread works on UNITS units at once, THREADS apart.
-struct StateSlice {
-    int s_units, units, lo, hi;
-    __device__ __forceinline__ StateSlice(int c, int C, int d)
-    {
-        s_units = d * d / 2;
-        units = s_units + d / 2;
-        const int per = (units + C - 1) / C;
-        lo = c * per;
-        hi = lo + per < units ? lo + per : units;
-    }
-};
-
 // The carried values (S_in, z_in; zeros if S_in is null) of the units a thread folds first.  They do
 // not depend on the other workgroups, so they are fetched before the wait for the partials, off
 // the chain of round trips that follows it.

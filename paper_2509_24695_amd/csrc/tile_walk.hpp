@@ -45,4 +45,21 @@ struct TileWalk {
     }
 };
 
+// Slice c of a head's state when C workgroups fold it together: 8-byte units [lo, hi) of the
+// d*d/2 + d/2 units that S (d x d floats) and z (d floats) make, per = ceil(units / C) each; late
+// slices may be short or empty.
+struct StateSlice {
+    int s_units, units, lo, hi;
+    SV_HOST_DEVICE inline StateSlice(int c, int C, int d) : s_units(d * d / 2), units(d * d / 2 + d / 2), lo(0), hi(0)
+    {
+        const int per = (units + C - 1) / C;
+        lo = c * per < units ? c * per : units;
+        hi = lo + per < units ? lo + per : units;
+    }
+};
+
+// The share of the token tiles that workgroup c of head bh takes in the one-launch block step:
+// dealt from a different start in each head (see block_step_mfma).
+SV_HOST_DEVICE inline int block_step_share(int c, int bh, int C) { return (c + bh) % C; }
+
 }  // namespace sv
