@@ -217,6 +217,20 @@ def test_block_stream_small(dtype, d):
     _check_state(S, z, S_ref, z_ref, "final state")
 
 
+def test_block_stream_few_heads_many_chunks():
+    """Two heads only: each head's tokens go to the largest number of workgroups the library uses (32),
+    so the fold of the carried state runs over several groups of partials."""
+    B, H, d = 1, 2, 64
+    sizes = [6000, 4500, 4100]
+    say(f"block_stream_few_heads sizes={sizes}")
+    blocks = [_draw(7550 + i, B, H, n, d, "bf16") for i, n in enumerate(sizes)]
+    outs, S, z = _gpu_stream(blocks, 1e-6, B, H, d)
+    S_ref = z_ref = None
+    for i, (O_ref, S_ref, z_ref) in enumerate(orc.block_stream(blocks, 1e-6)):
+        metrics.check(outs[i], O_ref, "bf16", f"block {i}")
+    _check_state(S, z, S_ref, z_ref, "final state")
+
+
 def test_single_block_equals_bidirectional_bitwise():
     """One block from the empty cache is the bidirectional layer (same kernels, same order)."""
     import torch
