@@ -90,13 +90,14 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
     // ---- the head agrees on its new state ------------------------------------------------------
     // Wave 0 alone waits for the head's partials, folds this workgroup's slice into S, z, publishes
     // it and waits for the other slices: a chain of memory round trips.  The other waves request the
-    // rest of their Q prefetch meanwhile (wave 0 after the chain).  Memory operations of a wave
-    // complete in order, so a wave with tiles in flight would see each answer of the chain only after
-    // its tiles, and the chain and the prefetch would take turns instead of overlapping.
+    // rest of their Q prefetch meanwhile (wave 0 after the chain): memory operations of a wave
+    // complete in order, so the chain's wave keeps its own queue empty, and one wave per workgroup
+    // polling is a quarter of the flag traffic.  The carried values of the slice are fetched before
+    // the wait; they do not depend on the other workgroups.
     epoch = es.resolve(reinterpret_cast<unsigned long long *>(
         lds + block_step_lds_bytes<TILE, WAVES, ROPE>() - kEpochLdsBytes));
     const StateSlice sl(c, C, d);
-    f32x2 carry[5];
+    f32x2 carry[5] = {};
     if (wave == 0) state_slice_carry<kWave>(sl, Sc, zc, lane, carry);
     state_publish(ws, BH, elems, bh, c, 0, epoch);
     if (wave != 0) {
