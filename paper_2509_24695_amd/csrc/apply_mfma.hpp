@@ -337,9 +337,11 @@ __global__ __launch_bounds__(64 * WAVES, 1) void apply_mfma_d64(
 
     ApplyStream<DEPTH, ROPE> stream(Qh, Oh, rope, lds + apply_lds_bytes<WAVES, ROPE>(), st.n, t1, lane,
                                     TileWalk(t0, WAVES * c + wave, WAVES * C, n_tiles, bh));
+    Rope3dFill tabs;
+    if (ROPE == kRope3D) rope3d_lds_fill_begin(rope.r3, tabs);   // the first loads of the kernel
     apply_prefetch<0, DEPTH>(stream);   // in flight while S is fetched
     if (ROPE == kRope3D) {
-        rope3d_lds_fill(lds + apply_lds_bytes<WAVES, ROPE>(), rope.r3);
+        rope3d_lds_fill_end(lds + apply_lds_bytes<WAVES, ROPE>(), rope.r3, tabs);
         __syncthreads();
     }
     ApplyOperands<64, HILO> A;

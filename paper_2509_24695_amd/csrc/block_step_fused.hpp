@@ -70,6 +70,8 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
     const int share = block_step_share(c, bh, C);
     const TileWalk walk(0, WAVES * share + wave, WAVES * C, n_tiles, bh);
     ApplyStream<DEPTH_A, ROPE> qstream(Q + head_off, O + head_off, rope, lds_tab, st.n, N, lane, walk);
+    Rope3dFill tabs;
+    if (ROPE == kRope3D) rope3d_lds_fill_begin(rope.r3, tabs);   // the first loads of the kernel
     apply_prefetch<0, kEarly>(qstream);
 
     // ---- fold this workgroup's share of K_b, V_b ----------------------------------------------
@@ -80,7 +82,7 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
         unsigned char *tileK = lds + wave * 2 * kTileBytes;
         state_prefetch(kvstream);
         if (ROPE == kRope3D) {
-            rope3d_lds_fill(lds + block_step_lds_bytes<TILE, WAVES, ROPE>(), rope.r3);
+            rope3d_lds_fill_end(lds + block_step_lds_bytes<TILE, WAVES, ROPE>(), rope.r3, tabs);
             __syncthreads();
         }
         state_accumulate(kvstream, tileK, tileK + kTileBytes, lane, acc);

@@ -354,9 +354,11 @@ __global__ __launch_bounds__(256, 1) void state_mfma_d128(
     acc.clear();
     CoopStateStream<DEPTH, ROPE> stream(Kh, Vh, rope, lds + state_d128_lds_bytes<ROPE>(), st.n, t1, d, wave, lane,
                                         TileWalk(t0, c, C, n_tiles, bh));
+    Rope3dFill tabs;
+    if (ROPE == kRope3D) rope3d_lds_fill_begin(rope.r3, tabs);   // the first loads of the kernel
     coop_state_prefetch(stream);
     if (ROPE == kRope3D) {
-        rope3d_lds_fill(lds + state_d128_lds_bytes<ROPE>(), rope.r3);
+        rope3d_lds_fill_end(lds + state_d128_lds_bytes<ROPE>(), rope.r3, tabs);
         __syncthreads();
     }
     state_accumulate_coop(stream, lds, wave, lane, wave & 1, wave >> 1, acc);
@@ -397,9 +399,11 @@ __global__ __launch_bounds__(64 * WAVES, NB == 1 ? 2 : 1) void apply_mfma_d128(
 
     CoopApplyStream<DEPTH, ROPE, WAVES, NB> stream(Qh, Oh, rope, lds + coop_apply_lds_bytes<WAVES, NB>(), st.n, t1,
                                                    d, wave, lane, TileWalk(t0, c, C, n_steps, bh));
+    Rope3dFill tabs;
+    if (ROPE == kRope3D) rope3d_lds_fill_begin(rope.r3, tabs);   // the first loads of the kernel
     coop_apply_prefetch<0, DEPTH>(stream);   // in flight while S is fetched
     if (ROPE == kRope3D) {
-        rope3d_lds_fill(lds + coop_apply_lds_bytes<WAVES, NB>(), rope.r3);
+        rope3d_lds_fill_end(lds + coop_apply_lds_bytes<WAVES, NB>(), rope.r3, tabs);
         __syncthreads();
     }
     ApplyOperands<128, HILO, NB, false> A;

@@ -45,15 +45,44 @@ __host__ __device__ constexpr int rope3d_entries(int frames, int rows, int cols,
     return frames * n_t + rows * n_h + cols * n_w;
 }
 
-// Copies the three tables to LDS, frame table first.  All threads of the workgroup
-// call; the caller places a workgroup barrier between this and the first lookup.
-__device__ __forceinline__ void rope3d_lds_fill(unsigned char *lds_tab, const Rope3D &R)
+// Copies the three tables to LDS, frame table first, in two parts so that the table reads can be
+// the first memory operations of a kernel: _begin issues the loads of the first kRope3dFillBatch
+// entries per thread (all of them, for tables of up to 16 KB and 256 threads) without waiting,
+// the caller then requests its first token tiles, and _end stores to LDS (and copies whatever
+// is left).  Memory operations return in order, so the tables are there before the tiles and the
+// copy costs no round trip of its own.  All threads of the workgroup call both; the caller places
+// a workgroup barrier between _end and the first lookup.
+constexpr int kRope3dFillBatch = 8;
+struct Rope3dFill {
+    f32x2 v[kRope3dFillBatch];
+};
+// Entry e (clamped into range) of the three tables laid end to end.
+__device__ __forceinline__ f32x2 rope3d_entry_flat(const Rope3D &R, int nt, int nh, int total, int e)
+{
+    e = e < total ? e : total - 1;
+    const f32x2 *src = e < nt ? reinterpret_cast<const f32x2 *>(R.cs_t) + e
+                              : (e < nt + nh ? reinterpret_cast<const f32x2 *>(R.cs_h) + (e - nt)
+                                             : reinterpret_cast<const f32x2 *>(R.cs_w) + (e - nt - nh));
+    return *src;
+}
+__device__ __forceinline__ void rope3d_lds_fill_begin(const Rope3D &R, Rope3dFill &f)
+{
+    const int nt = R.frames * R.n_t, nh = R.rows * R.n_h, total = nt + nh + R.cols * R.n_w;
+#pragma unroll
+    for (int j = 0; j < kRope3dFillBatch; ++j)
+        f.v[j] = rope3d_entry_flat(R, nt, nh, total, (int)threadIdx.x + j * (int)blockDim.x);
+}
+__device__ __forceinline__ void rope3d_lds_fill_end(unsigned char *lds_tab, const Rope3D &R, const Rope3dFill &f)
 {
     f32x2 *dst = reinterpret_cast<f32x2 *>(lds_tab);
-    const int nt = R.frames * R.n_t, nh = R.rows * R.n_h, nw = R.cols * R.n_w;
-    for (int e = threadIdx.x; e < nt; e += blockDim.x) dst[e] = reinterpret_cast<const f32x2 *>(R.cs_t)[e];
-    for (int e = threadIdx.x; e < nh; e += blockDim.x) dst[nt + e] = reinterpret_cast<const f32x2 *>(R.cs_h)[e];
-    for (int e = threadIdx.x; e < nw; e += blockDim.x) dst[nt + nh + e] = reinterpret_cast<const f32x2 *>(R.cs_w)[e];
+    const int nt = R.frames * R.n_t, nh = R.rows * R.n_h, total = nt + nh + R.cols * R.n_w;
+#pragma unroll
+    for (int j = 0; j < kRope3dFillBatch; ++j) {
+        const int e = (int)threadIdx.x + j * (int)blockDim.x;
+        if (e < total) dst[e] = f.v[j];
+    }
+    for (int e = (int)threadIdx.x + kRope3dFillBatch * (int)blockDim.x; e < total; e += (int)blockDim.x)
+        dst[e] = rope3d_entry_flat(R, nt, nh, total, e);
 }
 
 // One (cos, sin) entry straight from global memory (plain-FMA kernels).

@@ -512,9 +512,11 @@ __global__ __launch_bounds__(64 * WAVES, 1) void state_mfma_d64(
     StateStream<TILE, DEPTH, ROPE> stream(Kh, Vh, rope, lds_tab, st.n, t1, lane,
                                           TileWalk(t0, WAVES * c + wave, WAVES * C, n_tiles, bh));
     unsigned char *tileK = lds + wave * 2 * kTileBytes;
+    Rope3dFill tabs;
+    if (ROPE == kRope3D) rope3d_lds_fill_begin(rope.r3, tabs);   // the first loads of the kernel
     state_prefetch(stream);
     if (ROPE == kRope3D) {
-        rope3d_lds_fill(lds + state_lds_bytes<TILE, WAVES>(), rope.r3);
+        rope3d_lds_fill_end(lds + state_lds_bytes<TILE, WAVES>(), rope.r3, tabs);
         __syncthreads();
     }
     state_accumulate(stream, tileK, tileK + kTileBytes, lane, acc);

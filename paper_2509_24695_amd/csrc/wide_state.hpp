@@ -261,9 +261,11 @@ __global__ __launch_bounds__(256, 1) void state_mfma_wide(
     acc.clear();
     WideStateStream<DEPTH, ROPE> stream(Kh, Vh, rope, lds + kWideTabOffset, st.n, t1, d, lane,
                                         TileWalk(t0, 4 * c + wave, 4 * C, n_tiles, bh));
+    Rope3dFill tabs;
+    if (ROPE == kRope3D) rope3d_lds_fill_begin(rope.r3, tabs);   // the first loads of the kernel
     wide_state_prefetch(stream);
     if (ROPE == kRope3D) {
-        rope3d_lds_fill(lds + kWideTabOffset, rope.r3);
+        rope3d_lds_fill_end(lds + kWideTabOffset, rope.r3, tabs);
         __syncthreads();
     }
     unsigned char *tileK = lds + wave * 2 * kWideTileBytes, *tileV = tileK + kWideTileBytes;
