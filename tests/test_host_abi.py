@@ -207,3 +207,29 @@ def test_stream_yardsticks_check_arguments():
     assert status(sv.sv_stream_copy, A, A + 512, 1024, 64) == 2          # overlapping buffers
     sv.sv_stream_read(A, 0, B, 64)                                        # nothing to do: no launch, no error
     sv.sv_stream_copy(A, B, 0, 64)
+
+
+def test_build_rejects_kernels_that_use_scratch_memory():
+    """build() reads hipcc's per-kernel resource remarks and refuses a library in which a kernel keeps data in
+    scratch memory (such a kernel passes every parity test and runs many times slower)."""
+    from paper_2509_24695_amd import build as b
+
+    def remarks(name, scratch, spill):
+        tag = "[-Rpass-analysis=kernel-resource-usage]"
+        rows = [f"Function Name: {name}", "    VGPRs: 512", "    AGPRs: 256", f"    ScratchSize [bytes/lane]: {scratch}",
+                "    Dynamic Stack: False", "    Occupancy [waves/SIMD]: 1", "    SGPRs Spill: 0", f"    VGPRs Spill: {spill}",
+                "    LDS Size [bytes/block]: 0"]
+        return "\n".join(f"x.hip:1:1: remark: {r} {tag}\n    1 | {{\n      | ^" for r in rows)
+
+    good = b.kernel_resources(remarks("_ZN2sv1aEv", 0, 0) + "\n" + remarks("_ZN2sv1bEv", 0, 0))
+    assert set(good) == {"_ZN2sv1aEv", "_ZN2sv1bEv"} and good["_ZN2sv1aEv"]["ScratchSize"] == "0"
+    assert good["_ZN2sv1aEv"]["VGPRs"] == "512" and good["_ZN2sv1bEv"]["Occupancy"] == "1"
+    b.check_resources(good)
+    for scratch, spill in ((448, 0), (0, 3)):
+        bad = b.kernel_resources(remarks("_ZN2sv1aEv", 0, 0) + "\n" + remarks("_ZN2sv1cEv", scratch, spill))
+        with pytest.raises(RuntimeError, match="_ZN2sv1cEv"):
+            b.check_resources(bad)
+    # the library built in-tree went through the same check; its record says so
+    if os.path.exists(b.RESOURCES):
+        lines = open(b.RESOURCES).read().splitlines()
+        assert len(lines) >= 40 and all(" scratch=0 " in l for l in lines)
