@@ -8,12 +8,16 @@ once.  Inputs are synthetic (i.i.d. Gaussian times 0.5, bf16), generated on the
 device and resident in HBM before the timed region starts; buffer sets rotate
 so that repeats are not served from the 256 MB Infinity Cache.
 
-Prints ONE JSON line.  `value` is tokens/s of the layer (B*N / time per step).
+Prints ONE JSON line.  `value` is tokens/s of the layer (B*N / time per step) on
+the headline workload: the 720p-like bidirectional layer (B = 2, 64 heads of
+75 600 tokens), the largest configuration of the method that one call covers.
 `roofline` refers to the slower of the two kernels of a step (state or apply),
 timed with HIP events on the launch stream over a second pass of the same steps
 (events between kernels cost a few microseconds, so they stay out of `value`).
 `cpu_baseline` is the float64 oracle timed on the host cores on the same
-workload.  Block-causal workloads are reported under `block_stream`.
+workload.  The 480p-like layer is reported under `secondary`, the block-causal
+workloads under `block_stream` (with the latency and the device memory of every
+block), the paper's head geometry under `geometry_h20d112`.
 """
 from __future__ import annotations
 
@@ -31,16 +35,37 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix rate, published
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of this file, each counter
-# scaled by what it reads for a plain device copy of known size (FETCH_SIZE x 1.9997: it books the
-# 128-byte requests these kernels and the copy issue as 64 bytes; WRITE_SIZE x 1.0000).  Source:
-# profiles/traffic_pmc_bench_kernels.txt.  Algorithmic bytes per launch are 268 369 920.
-MEASURED_TRAFFIC_BYTES = {
-    ("apply", "bidir_480p"): int((67669.6 * 1.99963 + 131050.4) * 1024),
-    ("state", "bidir_480p"): int((133374.3 * 1.99963 + 4688.0) * 1024),
-    ("apply", "bidir_480p_h20d112"): int((75719.1 * 1.99963 + 143325.1) * 1024),
-    ("state", "bidir_480p_h20d112"): int((149565.8 * 1.99963 + 12861.2) * 1024),
-}
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "traffic_table.txt")
+
+
+def measured_traffic():
+    """HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of this file, read from
+    profiles/traffic_table.txt: one line per (kernel, workload) with the two counters in KiB per dispatch, the
+    factors that scale them to bytes moved (what the same counters read for a plain device copy of known
+    size) and the fingerprint of the kernel sources the run was made on.  Returns
+    {(kernel, workload): (bytes, fingerprint)}."""
+    table = {}
+    try:
+        with open(TRAFFIC_TABLE) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) != 7 or line.lstrip().startswith("#"):
+                    continue
+                kernel, workload, fetch, write, fs, wsc, fp = parts
+                table[(kernel, workload)] = (int((float(fetch) * float(fs) + float(write) * float(wsc)) * 1024), fp)
+    except OSError:
+        pass
+    return table
+
+
+def traffic_of(table, kernel, workload, fingerprint):
+    """(bytes or None, note): counters taken on other kernel sources than the ones now built say nothing."""
+    if (kernel, workload) not in table:
+        return None, "no counter run kept for this kernel and workload"
+    nbytes, fp = table[(kernel, workload)]
+    if fp != fingerprint:
+        return None, f"counter run was made on kernel sources {fp}, this build is {fingerprint}"
+    return nbytes, "profiles/traffic_table.txt"
 
 
 def _parse():
@@ -48,7 +73,8 @@ def _parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="bidir_480p", choices=["bidir_480p", "bidir_720p", "bidir_480p_h20d112"])
+    ap.add_argument("--workload", default="bidir_720p", choices=["bidir_480p", "bidir_720p", "bidir_480p_h20d112"])
+    ap.add_argument("--no-secondary", action="store_true", help="skip the 480p-like bidirectional layer")
     ap.add_argument("--sets", type=int, default=0, help="rotating buffer sets (0 = enough for > 1.5 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-block-stream", action="store_true")
@@ -148,6 +174,8 @@ def bench_bidirectional(w, steps, warmup, n_sets, sv, torch, rope=None, sets=Non
     wall_ev = time.perf_counter() - t1
     t_state = [e[0].elapsed_time(e[1]) for e in events]      # ms
     t_apply = [e[1].elapsed_time(e[2]) for e in events]
+    if sv.sv_linattn_workspace_status(ws, B, H, d) != 0:
+        raise RuntimeError("an in-kernel wait timed out during the benchmark: its figures mean nothing")
     return {
         "ms_per_step": wall / steps * 1e3, "ms_per_step_with_events": wall_ev / steps * 1e3,
         "ms_state": statistics.mean(t_state), "ms_apply": statistics.mean(t_apply),
@@ -155,7 +183,7 @@ def bench_bidirectional(w, steps, warmup, n_sets, sv, torch, rope=None, sets=Non
     }
 
 
-def bench_block_stream(w, n_blocks, sv, torch, rope=False):
+def bench_block_stream(w, n_blocks, sv, torch, rope=False, ceiling=False):
     """Whole stream enqueued back to back, one event pair per block; no host sync inside.
     `rope`: False, "table" (sv_block_linattn_step_rope, one full table per block) or "3d"
     (sv_block_linattn_step_rope3d, per-axis tables; the frame table of each block continues the
@@ -222,6 +250,19 @@ def bench_block_stream(w, n_blocks, sv, torch, rope=False):
     torch.cuda.synchronize()
     lat = [e[0].elapsed_time(e[1]) * 1e3 for e in events]            # us
     peak_extra = torch.cuda.max_memory_allocated() - mem_before
+    # pass 2b: device memory after every block (the block is waited for, so this pass is not timed): bytes
+    # this process holds through the allocator, and bytes in use on the whole device
+    mem_alloc, mem_device = [], []
+    S.zero_()
+    z.zero_()
+    for m in range(n_blocks):
+        one(m)
+        torch.cuda.synchronize()
+        free_b, total_b = torch.cuda.mem_get_info()
+        mem_alloc.append(int(torch.cuda.memory_allocated()))
+        mem_device.append(int(total_b - free_b))
+    if sv.sv_linattn_workspace_status(ws, B, H, d) != 0:
+        raise RuntimeError("an in-kernel wait timed out during the block stream: its figures mean nothing")
     # pass 3: the whole stream recorded once into a HIP graph and replayed (the workspace is switched
     # to device-side epochs for that)
     sv.sv_linattn_workspace_init(ws, B, H, d, stream=stream)
@@ -254,7 +295,7 @@ def bench_block_stream(w, n_blocks, sv, torch, rope=False):
     slope = (sum((x - mx) * (y - my) for x, y in zip(xs, tail)) / max(1e-30, sum((x - mx) ** 2 for x in xs))
              if len(tail) > 1 else 0.0)
     per_block_us = stream_ms * 1e3 / n_blocks
-    return {
+    out = {
         "workload": w.name, "rope": ("table" if rope is True else rope), "blocks": n_blocks, "tokens_per_block": N,
         "us_per_block_stream": per_block_us, "us_per_block_graph_replay": graph_us,
         "tokens_per_s": B * N / (per_block_us * 1e-6),
@@ -262,8 +303,22 @@ def bench_block_stream(w, n_blocks, sv, torch, rope=False):
         "hbm_frac": w.algorithmic_bytes / (per_block_us * 1e-6) / 1e9 / HBM_PEAK_GBPS,
         "latency_us": {"first": lat[0], "min": min(tail), "median": med, "max": max(tail),
                        "max_over_median": max(tail) / med, "slope_us_per_block": slope},
+        "latency_us_per_block": [round(x, 2) for x in lat],
         "library_bytes": lib_bytes, "peak_new_device_bytes_during_stream": int(peak_extra),
+        # after every block: bytes held through the allocator and bytes in use on the device (inputs and
+        # outputs of all blocks are resident from the start; the library itself holds library_bytes throughout)
+        "allocated_bytes_after_block": mem_alloc, "device_bytes_in_use_after_block": mem_device,
+        "memory_constant_over_stream": len(set(mem_alloc)) == 1,
     }
+    if ceiling:
+        # what the device gives two dependent passes that only move the block's bytes: a pure read of K_b, V_b,
+        # then a pure copy of Q_b's size into O_b's (kernels of include/sv_measure.h, timed like the blocks)
+        c = bench_stream_ceiling(w.algorithmic_bytes // 2, sv, torch)
+        floor_us = c["read"]["us"] + c["copy"]["us"]
+        out["stream_ceiling"] = {"read_us": c["read"]["us"], "copy_us": c["copy"]["us"], "bytes_each": c["read"]["bytes"],
+                                 "read_then_copy_us": floor_us}
+        out["frac_of_stream_ceiling"] = floor_us / per_block_us
+    return out
 
 
 def bench_stream_ceiling(nbytes, sv, torch, reps=12):
@@ -376,17 +431,37 @@ def main():
     sv.load_library()              # fails loudly when the HIP library is missing
     torch.cuda.set_device(0)
 
+    from paper_2509_24695_amd.build import source_fingerprint
+    fingerprint = source_fingerprint()
+    table = measured_traffic()
+
+    def headline_roofline(w, r, with_ceiling):
+        """`roofline` of the slower kernel of the bidirectional step."""
+        half = w.algorithmic_bytes / 2          # state reads K,V; apply reads Q and writes O
+        dom = "state" if r["ms_state"] >= r["ms_apply"] else "apply"
+        dom_ms_events = max(r["ms_state"], r["ms_apply"])
+        # An event between two kernels adds a marker packet (2-3 us per kernel here).  The step time of the
+        # timed region has no events inside it, so the event durations are scaled to add up to it: that is
+        # the kernel's average launch duration in the timed region (rocprofv3's kernel trace agrees within 1 us).
+        dom_ms = dom_ms_events * r["ms_per_step"] / (r["ms_state"] + r["ms_apply"])
+        achieved = half / (dom_ms * 1e-3) / 1e9
+        traffic, note = traffic_of(table, dom, w.name, fingerprint)
+        roof = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic, "traffic_source": note,
+                "algorithmic_bytes_per_launch": half, "avg_launch_ms": dom_ms,
+                "avg_launch_ms_between_events": dom_ms_events}
+        ceil = None
+        if with_ceiling:
+            ceil = bench_stream_ceiling(int(half), sv, torch)
+            ref = ceil["read"] if dom == "state" else ceil["copy"]   # the state kernel only reads; the apply kernel reads and writes
+            # both timed between events on the launch stream, the same way
+            roof["frac_of_stream_ceiling"] = ref["us"] / (dom_ms_events * 1e3)
+        return roof, ceil
+
     w = wl.workload(args.workload)
     r = bench_bidirectional(w, args.steps, args.warmup, args.sets, sv, torch)
     sec = r["ms_per_step"] * 1e-3
-    half = w.algorithmic_bytes / 2          # state reads K,V; apply reads Q and writes O
-    dom = "state" if r["ms_state"] >= r["ms_apply"] else "apply"
-    dom_ms_events = max(r["ms_state"], r["ms_apply"])
-    # An event between two kernels adds a marker packet (2-3 us per kernel here).  The step time of the
-    # timed region has no events inside it, so the event durations are scaled to add up to it: that is
-    # the kernel's average launch duration in the timed region (rocprofv3's kernel trace agrees within 1 us).
-    dom_ms = dom_ms_events * r["ms_per_step"] / (r["ms_state"] + r["ms_apply"])
-    achieved = half / (dom_ms * 1e-3) / 1e9
+    roof, ceil = headline_roofline(w, r, not args.no_stream_ceiling)
     out = {
         "metric": "linear-attention tokens/s per layer (fwd)",
         "value": w.B * w.N / sec, "unit": "tokens/s",
@@ -401,18 +476,10 @@ def main():
         "hbm_frac_step": w.algorithmic_bytes / sec / 1e9 / HBM_PEAK_GBPS,
         "kernels_ms": {"state": r["ms_state"], "apply": r["ms_apply"],
                        "step_with_events": r["ms_per_step_with_events"]},
-        "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((dom, w.name)),
-                     "algorithmic_bytes_per_launch": half, "avg_launch_ms": dom_ms,
-                     "avg_launch_ms_between_events": dom_ms_events},
+        "roofline": roof, "source_fingerprint": fingerprint,
     }
-    if not args.no_stream_ceiling:
-        c = bench_stream_ceiling(int(half), sv, torch)
-        out["stream_ceiling"] = c
-        ref = c["read"] if dom == "state" else c["copy"]     # the state kernel only reads; the apply kernel reads and writes
-        # both timed between events on the launch stream, the same way
-        out["roofline"]["frac_of_stream_ceiling"] = ref["us"] / (dom_ms_events * 1e3)
+    if ceil:
+        out["stream_ceiling"] = ceil
     if args.calibration_copy > 0:
         src = r["sets"][0][0]
         dst = torch.empty_like(src)
@@ -439,34 +506,49 @@ def main():
             "hbm_frac_step": w.algorithmic_bytes / (rr["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
             "kernels_ms": {"state": rr["ms_state"], "apply": rr["ms_apply"]},
         }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, r["sets"], torch)
+    del r
+    torch.cuda.empty_cache()
+    w480 = wl.workload("bidir_480p")
+    if not args.no_secondary and w.name != w480.name:
+        # the 480p-like layer (32 heads of 32 760 tokens), same protocol
+        r1 = bench_bidirectional(w480, args.steps, args.warmup, 0, sv, torch)
+        roof1, ceil1 = headline_roofline(w480, r1, not args.no_stream_ceiling)
+        sec1 = r1["ms_per_step"] * 1e-3
+        out["secondary"] = {
+            "workload": f"{w480.name}: B={w480.B} H={w480.H} N={w480.N} d={w480.d}", "ms_per_step": r1["ms_per_step"],
+            "tokens_per_s": w480.B * w480.N / sec1, "hbm_frac_step": w480.algorithmic_bytes / sec1 / 1e9 / HBM_PEAK_GBPS,
+            "kernels_ms": {"state": r1["ms_state"], "apply": r1["ms_apply"]}, "roofline": roof1,
+        }
+        if ceil1:
+            out["secondary"]["stream_ceiling"] = ceil1
+        del r1
+        torch.cuda.empty_cache()
     if not args.no_d112 and w.d == 64:
-        # the same token grid in the paper's own head geometry (model-configuration table): H = 20, d = 112
-        w2 = wl.workload(w.name + "_h20d112") if w.name == "bidir_480p" else None
-        if w2 is not None:
-            r2 = bench_bidirectional(w2, args.steps, args.warmup, 0, sv, torch)
-            g = {"workload": f"{w2.name}: B={w2.B} H={w2.H} N={w2.N} d={w2.d}", "ms_per_step": r2["ms_per_step"],
-                 "tokens_per_s": w2.B * w2.N / (r2["ms_per_step"] * 1e-3),
-                 "hbm_frac_step": w2.algorithmic_bytes / (r2["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                 "kernels_ms": {"state": r2["ms_state"], "apply": r2["ms_apply"]}}
-            if not args.no_rope:
-                r3 = bench_bidirectional(w2, args.steps, args.warmup, 0, sv, torch, rope=_rope_table(w2, torch),
-                                         sets=r2["sets"])
-                g["rope"] = {"ms_per_step": r3["ms_per_step"],
-                             "tokens_per_s": w2.B * w2.N / (r3["ms_per_step"] * 1e-3),
-                             "hbm_frac_step": w2.algorithmic_bytes / (r3["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                             "kernels_ms": {"state": r3["ms_state"], "apply": r3["ms_apply"]}}
-                r3 = bench_bidirectional(w2, args.steps, args.warmup, 0, sv, torch, rope=_rope_3d(w2, torch, sv),
-                                         sets=r2["sets"])
-                g["rope3d"] = {"ms_per_step": r3["ms_per_step"],
-                               "tokens_per_s": w2.B * w2.N / (r3["ms_per_step"] * 1e-3),
-                               "hbm_frac_step": w2.algorithmic_bytes / (r3["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                               "kernels_ms": {"state": r3["ms_state"], "apply": r3["ms_apply"]}}
-            del r2
-            out["geometry_h20d112"] = g
+        # the 480p token grid in the paper's own head geometry (model-configuration table): H = 20, d = 112
+        w2 = wl.workload("bidir_480p_h20d112")
+        r2 = bench_bidirectional(w2, args.steps, args.warmup, 0, sv, torch)
+        roof2, _ = headline_roofline(w2, r2, False)
+        g = {"workload": f"{w2.name}: B={w2.B} H={w2.H} N={w2.N} d={w2.d}", "ms_per_step": r2["ms_per_step"],
+             "tokens_per_s": w2.B * w2.N / (r2["ms_per_step"] * 1e-3),
+             "hbm_frac_step": w2.algorithmic_bytes / (r2["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+             "kernels_ms": {"state": r2["ms_state"], "apply": r2["ms_apply"]}, "roofline": roof2}
+        if not args.no_rope:
+            for key, rope in (("rope", _rope_table(w2, torch)), ("rope3d", _rope_3d(w2, torch, sv))):
+                r3 = bench_bidirectional(w2, args.steps, args.warmup, 0, sv, torch, rope=rope, sets=r2["sets"])
+                g[key] = {"ms_per_step": r3["ms_per_step"],
+                          "tokens_per_s": w2.B * w2.N / (r3["ms_per_step"] * 1e-3),
+                          "hbm_frac_step": w2.algorithmic_bytes / (r3["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                          "kernels_ms": {"state": r3["ms_state"], "apply": r3["ms_apply"]}}
+        del r2
+        torch.cuda.empty_cache()
+        out["geometry_h20d112"] = g
     if not args.no_block_stream:
+        cl = not args.no_stream_ceiling
         out["block_stream"] = [
-            bench_block_stream(wl.workload("block_480p"), 10, sv, torch),
-            bench_block_stream(wl.workload("stream_720p"), args.stream_blocks, sv, torch),
+            bench_block_stream(wl.workload("block_480p"), 10, sv, torch, ceiling=cl),
+            bench_block_stream(wl.workload("stream_720p"), args.stream_blocks, sv, torch, ceiling=cl),
         ]
         if not args.no_d112:
             out["block_stream"].append(bench_block_stream(wl.workload("block_480p_h20d112"), 10, sv, torch))
@@ -486,8 +568,6 @@ def main():
         # the other cached operator of the block-causal model (Sec. 3.3.1): dense, so bound by the matrix cores
         out["tconv"] = [bench_tconv(wl.TCONV_WORKLOADS["tconv_480p"], 5, sv, torch),
                         bench_tconv(wl.TCONV_WORKLOADS["tconv_block_480p"], 5, sv, torch)]
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, r["sets"], torch)
     print(json.dumps(out))
 
 

@@ -34,6 +34,27 @@
  *  - For fixed arguments the results are bit-reproducible: partial sums over
  *    token chunks are combined in a fixed order, never with float atomics.
  *  - Inputs must be finite; O must not alias Q, K or V.
+ *  - Workgroups that wait for each other.  sv_linattn_state and the block steps
+ *    split a head's tokens over several workgroups which, when the whole grid fits
+ *    the device at once (about one workgroup per compute unit; the library checks
+ *    this against the device's capacity and otherwise takes a path of two
+ *    launches without waits), exchange their partial sums INSIDE the kernel: each
+ *    publishes a flag in the workspace and polls for the others'.  That is only
+ *    live if all of a launch's workgroups get to run together, so such a call
+ *    needs the device's compute units to itself: do not run it concurrently with
+ *    kernels of other streams or processes that may hold compute units for long
+ *    (two of these calls on two streams, each with its own workspace, can starve
+ *    each other).  Every wait is bounded (2^24 polls, several seconds): no kernel
+ *    hangs.  A wait that runs out stores a mark in the workspace
+ *    (sv_linattn_workspace_status) and the workgroup stores nothing further - its
+ *    part of S, z keeps its old contents, its rows of O are not written - so S, z
+ *    and O of that call are then INVALID as a whole (other workgroups may have
+ *    stored their parts) and a carried state must be rebuilt or restored by the
+ *    caller.  Callers that cannot rule out contention check the status at their
+ *    synchronisation points.
+ *  - The first call on a device queries it and raises kernel LDS limits (function
+ *    attributes).  Make one call (sv_linattn_workspace_init will do) before
+ *    capturing a stream into a HIP graph; later calls only enqueue kernels.
  */
 #ifndef SV_LINATTN_H
 #define SV_LINATTN_H
@@ -48,7 +69,10 @@ extern "C" {
 typedef enum {
     SV_OK = 0,
     SV_ERR_NULL = 1,        /* a required pointer is NULL                           */
-    SV_ERR_SHAPE = 2,       /* B, H, N <= 0, stride_n < d, or overlapping strides    */
+    SV_ERR_SHAPE = 2,       /* B, H, N <= 0, stride_n < d, or strides under which two
+                               (batch, head, token) rows share memory: taken in
+                               ascending order, each stride of an axis longer than 1
+                               must be >= stride * extent of the axis below it     */
     SV_ERR_UNSUPPORTED = 3, /* d not in {32, 64, 112, 128} or unknown dtype          */
     SV_ERR_ALIGN = 4,       /* pointer or stride not a multiple of 16 bytes          */
     SV_ERR_RANGE = 5,       /* token range outside [0, N], or eps negative/non-finite */
@@ -84,12 +108,43 @@ size_t sv_linattn_workspace_bytes(int32_t B, int32_t H, int32_t n_tokens, int32_
  * tiny kernel on `stream`; it must have completed, in stream order, before the
  * workspace is used) the kernels draw their epochs from a counter inside the
  * workspace instead, so the same launches may be captured once and replayed any
- * number of times.  B, H, d as given to sv_linattn_workspace_bytes.  The
+ * number of times.  The call also clears every flag and the timeout mark of the
+ * workspace, so it may be repeated, and a workspace may be re-initialised after
+ * its memory served something else.  B, H, d as given to
+ * sv_linattn_workspace_bytes.  The
  * workspace must then serve one stream at a time (as always), and a graph must be
  * replayed with the workspace it was captured with.  Eager calls work with or
  * without initialisation. */
 sv_status sv_linattn_workspace_init(void *workspace, size_t workspace_bytes,
                                     int32_t B, int32_t H, int32_t d, void *stream);
+
+/* Where the workspace records that an in-kernel wait ran out (see "Workgroups
+ * that wait for each other" above; for callers that monitor the library, no
+ * passage of the paper): byte offset of an 8-byte word inside a workspace for
+ * B, H, d.  Pure host function; 0 for unsupported arguments.  The word holds
+ * 0x54494d454f555421 after a timeout and anything else otherwise (the contents of
+ * a fresh workspace are undefined and need not be cleared for this);
+ * sv_linattn_workspace_init resets it. */
+size_t sv_linattn_workspace_status_offset(int32_t B, int32_t H, int32_t d);
+
+/* Reads that word: *timed_out (HOST pointer) = 1 if a wait of any call that used
+ * this workspace has run out since the workspace was allocated or last
+ * initialised, else 0.  Unlike every other call this one SYNCHRONISES: it copies
+ * the word on `stream` and waits for the stream, so it sees all earlier work of
+ * that stream.  Errors: SV_ERR_NULL, SV_ERR_SHAPE, SV_ERR_UNSUPPORTED,
+ * SV_ERR_ALIGN, SV_ERR_WORKSPACE as for sv_linattn_workspace_init; SV_ERR_LAUNCH if
+ * the copy failed. */
+sv_status sv_linattn_workspace_status(const void *workspace, size_t workspace_bytes,
+                                      int32_t B, int32_t H, int32_t d, void *stream,
+                                      int32_t *timed_out);
+
+/* Bound of the in-kernel waits, in polls (roughly 100 ns each), for all later
+ * calls of this process: a negative value restores the default (2^24).  0 makes
+ * every wait fail at once, which is how the tests exercise the timeout path
+ * without a kernel that hangs: the kernels still run to their end, store the
+ * timeout mark and leave S, z and O alone.  (For tests and for callers that want
+ * a tighter bound; no passage of the paper.) */
+void sv_linattn_set_wait_limit(int64_t polls);
 
 /* State reduction (numerator and denominator brackets of the Sec. 3.2 equation;
  * S_j and the key sum of Sec. 3.3.1) over tokens [tok_begin, tok_end):

@@ -47,7 +47,8 @@ extern "C" {
  *             bf16 (nearest even).  SV_F32 returns SV_ERR_UNSUPPORTED.
  *
  * B, T, HW >= 1; D >= 8 and a multiple of 8; B*T*HW and 3*D*D below 2^31.  All
- * pointers 16-byte aligned.  y must not overlap x, W or cache_in.  Inputs must
+ * pointers 16-byte aligned.  y must not overlap x, W or cache_in; cache_out must not
+ * overlap x, W or y (SV_ERR_SHAPE).  Inputs must
  * be finite.  Arguments are checked on the host before anything is launched; an
  * error other than SV_ERR_LAUNCH means nothing was written.  Work is enqueued
  * on `stream` (hipStream_t as void*, NULL = default stream); the library

@@ -20,6 +20,7 @@ EXPORTS = (
     "sv_block_linattn_lookahead_rope", "sv_linattn_workspace_init",
     "sv_linattn_state_rope3d", "sv_linattn_apply_rope3d", "sv_block_linattn_step_rope3d",
     "sv_block_linattn_lookahead_rope3d", "sv_tconv_block_step", "sv_stream_read", "sv_stream_copy",
+    "sv_linattn_workspace_status_offset", "sv_linattn_workspace_status", "sv_linattn_set_wait_limit",
 )
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
@@ -109,6 +110,12 @@ def load_library():
     lib.sv_stream_copy.restype = ctypes.c_int
     lib.sv_linattn_workspace_init.argtypes = [vp, sz, i32, i32, i32, vp]
     lib.sv_linattn_workspace_init.restype = ctypes.c_int
+    lib.sv_linattn_workspace_status_offset.argtypes = [i32, i32, i32]
+    lib.sv_linattn_workspace_status_offset.restype = sz
+    lib.sv_linattn_workspace_status.argtypes = [vp, sz, i32, i32, i32, vp, ctypes.POINTER(ctypes.c_int32)]
+    lib.sv_linattn_workspace_status.restype = ctypes.c_int
+    lib.sv_linattn_set_wait_limit.argtypes = [ctypes.c_int64]
+    lib.sv_linattn_set_wait_limit.restype = None
     lib.sv_status_string.argtypes = [ctypes.c_int]
     lib.sv_status_string.restype = ctypes.c_char_p
     lib.sv_version.argtypes = []
@@ -244,6 +251,25 @@ def sv_linattn_workspace_init(workspace, B: int, H: int, d: int, workspace_bytes
     wb = _nbytes(workspace) if workspace_bytes is None else int(workspace_bytes)
     _check(load_library().sv_linattn_workspace_init(_ptr(workspace), wb, int(B), int(H), int(d), _stream(stream)),
            "sv_linattn_workspace_init")
+
+
+def sv_linattn_workspace_status_offset(B: int, H: int, d: int) -> int:
+    return int(load_library().sv_linattn_workspace_status_offset(int(B), int(H), int(d)))
+
+
+def sv_linattn_workspace_status(workspace, B: int, H: int, d: int, workspace_bytes: int | None = None,
+                                stream=None) -> int:
+    """1 if an in-kernel wait of a call on this workspace has timed out, else 0.  Synchronises `stream`."""
+    wb = _nbytes(workspace) if workspace_bytes is None else int(workspace_bytes)
+    out = ctypes.c_int32(-1)
+    _check(load_library().sv_linattn_workspace_status(_ptr(workspace), wb, int(B), int(H), int(d), _stream(stream),
+                                                      ctypes.byref(out)), "sv_linattn_workspace_status")
+    return int(out.value)
+
+
+def sv_linattn_set_wait_limit(polls: int) -> None:
+    """Bound of the in-kernel waits in polls; negative restores the default, 0 makes every wait fail."""
+    load_library().sv_linattn_set_wait_limit(int(polls))
 
 
 class _CRope3D(ctypes.Structure):

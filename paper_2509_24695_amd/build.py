@@ -21,6 +21,25 @@ HIPCC_FLAGS = [
 RESOURCES = os.path.join(PKG, "kernel_resources.txt")   # written by build(): one line per kernel
 
 
+def source_fingerprint() -> str:
+    """Short hash of the kernel sources with comments and white space taken out: measurements that were
+    made on one build (rocprofv3 counter runs kept as text) carry it, so a reader can tell whether the
+    kernels have changed since."""
+    import hashlib
+    import re
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(CSRC)):
+        if not name.endswith((".hip", ".hpp")):
+            continue
+        with open(os.path.join(CSRC, name)) as f:
+            text = f.read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        text = re.sub(r"//[^\n]*", "", text)
+        h.update(name.encode())
+        h.update("".join(text.split()).encode())
+    return h.hexdigest()[:16]
+
+
 def kernel_resources(compiler_output: str) -> dict:
     """{kernel name: {"VGPRs": n, "AGPRs": n, "ScratchSize": bytes per lane, "VGPRs Spill": n, ...}} from the
     kernel-resource-usage remarks in hipcc's output."""

@@ -96,8 +96,9 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
     // complete in order, so the chain's wave keeps its own queue empty, and one wave per workgroup
     // polling is a quarter of the flag traffic.  The carried values of the slice are fetched before
     // the wait; they do not depend on the other workgroups.
-    epoch = es.resolve(reinterpret_cast<unsigned long long *>(
-        lds + block_step_lds_bytes<TILE, WAVES, ROPE>() - kEpochLdsBytes));
+    unsigned char *epoch_lds = lds + block_step_lds_bytes<TILE, WAVES, ROPE>() - kEpochLdsBytes;
+    epoch = es.resolve(reinterpret_cast<unsigned long long *>(epoch_lds));
+    int *agreed = reinterpret_cast<int *>(epoch_lds + 8);          // did both waits end in time?
     const StateSlice sl(c, C, d);
     f32x2 carry[5] = {};
     if (wave == 0) state_slice_carry<kWave>(sl, Sc, zc, lane, carry);
@@ -105,13 +106,19 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
     if (wave != 0) {
         apply_prefetch<kEarly, DEPTH_A>(qstream);
     } else {
-        state_wait(ws, BH, elems, bh, C, 0, epoch, spin_limit, lane);
-        state_finalize_slice<kWave, true, 5, 8>(partials, sl, C, Sc, zc, Sh, zh, lane, carry);
-        coherent_stores_done();
-        if (lane == 0) flag_publish(ws_flags(ws, BH, elems, bh, 1) + c, epoch);
-        state_wait(ws, BH, elems, bh, C, 1, epoch, spin_limit, lane);
+        bool ok = state_wait(ws, BH, elems, bh, C, 0, epoch, spin_limit, lane);
+        if (ok) {
+            state_finalize_slice<kWave, true, 5, 8>(partials, sl, C, Sc, zc, Sh, zh, lane, carry);
+            coherent_stores_done();
+            if (lane == 0) flag_publish(ws_flags(ws, BH, elems, bh, 1) + c, epoch);
+            ok = state_wait(ws, BH, elems, bh, C, 1, epoch, spin_limit, lane);
+        }
+        if (lane == 0) *agreed = ok;
     }
     __syncthreads();
+    // A wait that ran out (recorded in the workspace): nothing more is stored, neither this workgroup's
+    // slice of S, z (if the first wait failed) nor any row of O_b.
+    if (!*agreed) return;
 
     // ---- apply the updated state to this workgroup's share of Q_b --------------------------------
     ApplyOperands<64, HILO> A;

@@ -41,7 +41,7 @@ constexpr int kStateElems = 64 * 64 + 64;            // S then z of one head, d 
 //   float  partial[BH][kMaxChunks][elems]
 //   float  lookahead[BH][elems]       S then z per head: the updated state of a step that does not commit
 //   u64    flags[BH][2][kMaxChunks]   epoch-tagged: [0] partial c stored, [1] slice c of the new state stored
-//   u64    error, magic, pad, pad     error: non-zero if a bounded wait ever timed out
+//   u64    error, magic, pad, pad     error: kWsTimeoutMark once a bounded wait has timed out
 //   u64    tickets[BH]                magic, tickets: device-side epochs (EpochSource), unused unless initialised
 __host__ __device__ constexpr size_t ws_partial_bytes(int BH, int elems) {
     return (size_t)BH * kMaxChunks * elems * sizeof(float);
@@ -60,8 +60,11 @@ __host__ __device__ __forceinline__ unsigned long long *ws_flag_base(void *ws, i
 __host__ __device__ __forceinline__ unsigned long long *ws_flags(void *ws, int BH, int elems, int bh, int phase) {
     return ws_flag_base(ws, BH, elems) + ((size_t)bh * 2 + phase) * kMaxChunks;
 }
+__host__ __device__ constexpr size_t ws_error_offset(int BH, int elems) {
+    return ws_partial_bytes(BH, elems) + ws_lookahead_bytes(BH, elems) + (size_t)BH * 2 * kMaxChunks * sizeof(unsigned long long);
+}
 __host__ __device__ __forceinline__ unsigned long long *ws_error(void *ws, int BH, int elems) {
-    return ws_flag_base(ws, BH, elems) + (size_t)BH * 2 * kMaxChunks;
+    return reinterpret_cast<unsigned long long *>(static_cast<unsigned char *>(ws) + ws_error_offset(BH, elems));
 }
 __host__ __device__ __forceinline__ unsigned long long *ws_magic(void *ws, int BH, int elems) {
     return ws_error(ws, BH, elems) + 1;
@@ -88,6 +91,9 @@ __host__ __device__ constexpr size_t ws_total_bytes(int BH, int elems) {
 // many workgroups each launch gave the head.  Nothing is ever reset.
 // Device epochs are even, host epochs odd: they never collide.
 constexpr unsigned long long kWsMagic = 0x73764c696e417474ull;
+// What the workspace's error word holds after a bounded wait has run out.  A fixed pattern, so that the
+// word means something in a workspace whose contents were never initialised (any other value: no timeout).
+constexpr unsigned long long kWsTimeoutMark = 0x54494d454f555421ull;
 constexpr unsigned long long kTicketQuantum = 1ull << 20;     // far more than a head ever has workgroups
 
 struct EpochSource {
@@ -454,12 +460,15 @@ __device__ __forceinline__ void state_publish(void *ws, int BH, int elems, int b
 }
 
 // Waits until all C workgroups of head `bh` have published `phase`.  Returns
-// false (and records it in the workspace) if the bounded wait ran out.
+// false (and records it in the workspace) if the bounded wait ran out: the caller
+// must then store nothing that depends on the other workgroups.  The result is
+// uniform over the calling wave.
 __device__ __forceinline__ bool state_wait(void *ws, int BH, int elems, int bh, int C, int phase,
                                            unsigned long long epoch, uint32_t spin_limit, int lane)
 {
     const bool ok = flags_wait_all(ws_flags(ws, BH, elems, bh, phase), C, epoch, spin_limit, lane);
-    if (!ok && threadIdx.x == 0) *ws_error(ws, BH, elems) = epoch;
+    if (!ok && lane == 0)
+        __hip_atomic_store(ws_error(ws, BH, elems), kWsTimeoutMark, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     return ok;
 }
 
@@ -530,7 +539,8 @@ __global__ __launch_bounds__(64 * WAVES, 1) void state_mfma_d64(
         const StateSlice sl(c, C, 64);
         f32x2 carry[3];
         state_slice_carry<THREADS>(sl, Sc, zc, tid, carry);
-        state_publish_and_wait(ws, BH, kStateElems, bh, c, C, 0, epoch, spin_limit, lane);
+        if (!state_publish_and_wait(ws, BH, kStateElems, bh, c, C, 0, epoch, spin_limit, lane))
+            return;                                     // timed out: this wave leaves its part of S, z as it was
         state_finalize_slice<THREADS, false>(partials, sl, C, Sc, zc, S_out + (size_t)bh * 64 * 64,
                                              z_out + (size_t)bh * 64, tid, carry);
     }

@@ -38,6 +38,8 @@ constexpr int kFusedStateDepth[3] = {2, 2, 2};   // one-launch block step (d = 6
 constexpr int kFusedApplyDepth[3] = {6, 2, 6};   // Q tiles held in registers across the in-kernel waits
 constexpr bool kApplyHiLo = true;
 constexpr uint32_t kSpinLimit = 1u << 24;      // polls of ~100 ns: far beyond any real wait
+std::atomic<uint32_t> g_spin_limit{kSpinLimit};  // sv_linattn_set_wait_limit
+uint32_t spin_limit() { return g_spin_limit.load(std::memory_order_relaxed); }
 
 struct Shape {
     int B, H, N, d, BH;
@@ -142,12 +144,17 @@ struct Rope {
     RopeArg arg{};
 };
 
-// Switches a workspace to device-side epochs (and clears its error word).
-__global__ void workspace_header_init(unsigned long long *error, unsigned long long *magic, unsigned long long *tickets,
-                                      int BH)
+// Switches a workspace to device-side epochs and clears its error word.  The ticket counters restart at
+// zero, so the epochs drawn from them repeat those of an earlier life of the same memory: every flag word
+// is cleared too (no device epoch is ever 0), or a flag left behind by that earlier life could pass for
+// one of the first launch after this.
+__global__ void workspace_header_init(unsigned long long *flags, size_t n_flags, unsigned long long *error,
+                                      unsigned long long *magic, unsigned long long *tickets, int BH)
 {
-    for (int i = threadIdx.x; i < BH; i += blockDim.x) tickets[i] = 0ull;
-    if (threadIdx.x == 0) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x, first = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (size_t i = first; i < n_flags; i += stride) flags[i] = 0ull;
+    for (size_t i = first; i < (size_t)BH; i += stride) tickets[i] = 0ull;
+    if (first == 0) {
         *error = 0ull;
         *magic = kWsMagic;
     }
@@ -244,6 +251,19 @@ sv_status check_desc(const sv_tensor_desc *t, Shape *s)
     s->elem_bytes = s->bf16 ? 2 : 4;
     const int64_t per16 = 16 / s->elem_bytes;
     if (t->stride_n % per16 || t->stride_b % per16 || t->stride_h % per16) return SV_ERR_ALIGN;
+    // No two (b, h, n) rows may share memory (O rows would overwrite each other): taken in order of
+    // ascending stride, every axis with more than one index must step over all that the axes below it span.
+    struct Axis { int64_t stride, extent; } ax[3] = {{t->stride_b, t->B}, {t->stride_h, t->H}, {t->stride_n, t->N}};
+    for (int i = 0; i < 3; ++i)
+        for (int j = i + 1; j < 3; ++j)
+            if (ax[j].stride < ax[i].stride) { const Axis x = ax[i]; ax[i] = ax[j]; ax[j] = x; }
+    int64_t span = t->d;                             // elements covered by the axes handled so far
+    for (const Axis &a : ax) {
+        if (a.extent <= 1) continue;
+        if (a.stride < span) return SV_ERR_SHAPE;
+        if (a.stride > INT64_MAX / a.extent) return SV_ERR_SHAPE;
+        span = a.stride * a.extent;
+    }
     return SV_OK;
 }
 
@@ -285,7 +305,7 @@ void launch_state_mfma(const uint16_t *k, const uint16_t *v, const Rope &rope, c
         if ((int64_t)C * s.BH <= dev.state_resident_wgs[KN::W][rope.mode]) {
             // the head's workgroups wait for each other inside the kernel: all must be resident
             KN::state<<<dim3(C, s.BH), 64 * kStateWaves, KN::state_lds, stream>>>(
-                k, v, rope.arg, s.st, s.H, s.d, t0, t1, C, S_in, z_in, S_out, z_out, ws, next_epoch(), kSpinLimit);
+                k, v, rope.arg, s.st, s.H, s.d, t0, t1, C, S_in, z_in, S_out, z_out, ws, next_epoch(), spin_limit());
         } else {
             KN::state_partial<<<dim3(C, s.BH), 64 * kStateWaves, KN::state_lds, stream>>>(
                 k, v, rope.arg, s.st, s.H, s.d, t0, t1, C, S_in, z_in, S_out, z_out, ws, 0ull, 0u);
@@ -474,7 +494,7 @@ sv_status do_block_step(const void *Qb, const void *Kb, const void *Vb, const sv
             KN::fused<<<dim3(C, s.BH), 64 * kStateWaves, KN::fused_lds, hs>>>(
                 static_cast<const uint16_t *>(Qb), static_cast<const uint16_t *>(Kb),
                 static_cast<const uint16_t *>(Vb), static_cast<uint16_t *>(Ob), rope.arg, s.st, s.H, s.N, C, S_in,
-                z_in, S_out, z_out, eps, workspace, next_epoch(), kSpinLimit);
+                z_in, S_out, z_out, eps, workspace, next_epoch(), spin_limit());
             launched = true;
         };
         if (rope.mode == kRope3D) launch(Kernels<64, kRope3D>{});
@@ -507,9 +527,44 @@ sv_status sv_linattn_workspace_init(void *workspace, size_t workspace_bytes_give
     if (!aligned16(workspace)) return SV_ERR_ALIGN;
     if (workspace_bytes_given < workspace_bytes(B * H, d)) return SV_ERR_WORKSPACE;
     const int BH = B * H, elems = d * d + d;
-    workspace_header_init<<<1, kThreads, 0, static_cast<hipStream_t>(stream)>>>(
-        ws_error(workspace, BH, elems), ws_magic(workspace, BH, elems), ws_tickets(workspace, BH, elems), BH);
+    const size_t n_flags = (size_t)BH * 2 * kMaxChunks;
+    const size_t wgs = (n_flags + kThreads - 1) / kThreads;
+    workspace_header_init<<<(unsigned)(wgs < 1024 ? wgs : 1024), kThreads, 0, static_cast<hipStream_t>(stream)>>>(
+        ws_flag_base(workspace, BH, elems), n_flags, ws_error(workspace, BH, elems), ws_magic(workspace, BH, elems),
+        ws_tickets(workspace, BH, elems), BH);
     return launch_status();
+}
+
+void sv_linattn_set_wait_limit(int64_t polls)
+{
+    g_spin_limit.store(polls < 0 ? kSpinLimit : polls > 0xffffffffll ? 0xffffffffu : (uint32_t)polls,
+                       std::memory_order_relaxed);
+}
+
+size_t sv_linattn_workspace_status_offset(int32_t B, int32_t H, int32_t d)
+{
+    if (B <= 0 || H <= 0 || (int64_t)B * H > 65535 || !head_dim_ok(d)) return 0;
+    return ws_error_offset(B * H, d * d + d);
+}
+
+sv_status sv_linattn_workspace_status(const void *workspace, size_t workspace_bytes_given, int32_t B, int32_t H,
+                                      int32_t d, void *stream, int32_t *timed_out)
+{
+    if (!workspace || !timed_out) return SV_ERR_NULL;
+    if (B <= 0 || H <= 0 || (int64_t)B * H > 65535) return SV_ERR_SHAPE;
+    if (!head_dim_ok(d)) return SV_ERR_UNSUPPORTED;
+    if (!aligned16(workspace)) return SV_ERR_ALIGN;
+    if (workspace_bytes_given < workspace_bytes(B * H, d)) return SV_ERR_WORKSPACE;
+    unsigned long long word = 0;
+    auto hs = static_cast<hipStream_t>(stream);
+    const unsigned char *src = static_cast<const unsigned char *>(workspace) + sv_linattn_workspace_status_offset(B, H, d);
+    if (hipMemcpyAsync(&word, src, sizeof word, hipMemcpyDeviceToHost, hs) != hipSuccess ||
+        hipStreamSynchronize(hs) != hipSuccess) {
+        (void)hipGetLastError();
+        return SV_ERR_LAUNCH;
+    }
+    *timed_out = word == kWsTimeoutMark ? 1 : 0;
+    return SV_OK;
 }
 
 sv_status sv_linattn_state(const void *K, const void *V, const sv_tensor_desc *kv, int32_t tok_begin,

@@ -53,6 +53,10 @@ extern "C" sv_status sv_tconv_block_step(const void *x, const void *W, const voi
     if (overlaps(y, tok_bytes, x, tok_bytes) || overlaps(y, tok_bytes, W, w_bytes) ||
         (cache_in && overlaps(y, tok_bytes, cache_in, cache_bytes)))
         return SV_ERR_SHAPE;
+    // the new cache is copied out of x after y is complete: it may replace cache_in, nothing else
+    if (cache_out && (overlaps(cache_out, cache_bytes, y, tok_bytes) || overlaps(cache_out, cache_bytes, x, tok_bytes) ||
+                      overlaps(cache_out, cache_bytes, W, w_bytes)))
+        return SV_ERR_SHAPE;
     if (!tconv_kernel_ready()) return SV_ERR_LAUNCH;
 
     TconvArgs a;

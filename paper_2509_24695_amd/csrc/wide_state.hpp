@@ -279,7 +279,8 @@ __global__ __launch_bounds__(256, 1) void state_mfma_wide(
         const StateSlice sl(c, C, d);
         f32x2 carry[3];
         state_slice_carry<256>(sl, Sc, zc, (int)threadIdx.x, carry);
-        state_publish_and_wait(ws, BH, elems, bh, c, C, 0, epoch, spin_limit, lane);
+        if (!state_publish_and_wait(ws, BH, elems, bh, c, C, 0, epoch, spin_limit, lane))
+            return;                                     // timed out: this wave leaves its part of S, z as it was
         state_finalize_slice<256, false>(partials, sl, C, Sc, zc, S_out + (size_t)bh * d * d, z_out + (size_t)bh * d,
                                          (int)threadIdx.x, carry);
     }

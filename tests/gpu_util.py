@@ -57,7 +57,7 @@ def gpu_bidirectional(Qd, Kd, Vd, eps, ws=None, poison=True):
         z.fill_(float("nan"))
     if ws is None:
         ws = new_workspace(B, H, N, d)
-    O = torch.empty_like(Qd)
+    O = torch.full_like(Qd, float("nan"))      # a row no kernel writes must not pass a comparison
     dsc = sv.desc_of(Kd)
     sv.sv_linattn_state(Kd, Vd, dsc, 0, N, 0, S, z, ws)
     sv.sv_linattn_apply(Qd, sv.desc_of(Qd), 0, N, S, z, eps, O)

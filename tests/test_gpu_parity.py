@@ -332,23 +332,86 @@ def test_many_heads_bidirectional_and_block(BH, d):
 
 @pytest.mark.parametrize("H,d", [(32, 64), (20, 112)])
 def test_bounded_waits_never_time_out(H, d):
-    """The workspace ends with [error, magic, pad, pad, tickets[B*H]] (8-byte words); the error word
-    records a timed-out wait and must stay clear."""
+    """The workspace records a timed-out wait; after many calls on a workspace that was never
+    initialised (undefined contents) the library's query must still say that none has."""
     import torch
     B, N = 1, 4680
     say("bounded_waits_never_time_out")
     Q, K, V = (to_dev(t) for t in _draw(7950, B, H, N, d, "bf16"))
     ws = new_workspace(B, H, N, d)
-    ws.zero_()
+    ws.fill_(0xA5)
     S, z = new_state(B, H, d)
     O = torch.empty_like(Q)
     dsc = sv.desc_of(Q)
     for _ in range(20):
         sv.sv_linattn_state(K, V, dsc, 0, N, 0, S, z, ws)
         sv.sv_block_linattn_step(Q, K, V, dsc, S, z, 1e-6, O, ws)
+    assert sv.sv_linattn_workspace_status(ws, B, H, d) == 0
+    # the word the query reads is where the header says it is
+    off = sv.sv_linattn_workspace_status_offset(B, H, d)
+    assert int(ws[off:off + 8].view(torch.int64)[0]) != 0x54494d454f555421
+
+
+@pytest.mark.parametrize("H,d", [(8, 64), (20, 112)])
+def test_timed_out_wait_stores_nothing_and_is_reported(H, d):
+    """With the wait bound set to zero polls every in-kernel wait fails at once (the kernels still run to
+    their end): the carried S, z and the rows of O must keep their contents, the workspace must report the
+    timeout, initialising the workspace must clear the report, and the next call must be right again."""
+    import torch
+    B, N = 1, 2000
+    say(f"timed_out_wait H={H} d={d}")
+    Q, K, V = _draw(7960, B, H, N, d, "bf16")
+    Qd, Kd, Vd = to_dev(Q), to_dev(K), to_dev(V)
+    dsc = sv.desc_of(Qd)
+    ws = new_workspace(B, H, N, d)
+    sv.sv_linattn_workspace_init(ws, B, H, d)
+    S, z = new_state(B, H, d)
+    S.fill_(3.0)
+    z.fill_(5.0)
+    O = torch.full_like(Qd, float("nan"))
+    try:
+        sv.sv_linattn_set_wait_limit(0)
+        sv.sv_linattn_state(Kd, Vd, dsc, 0, N, 1, S, z, ws)
+        sv.sv_block_linattn_step(Qd, Kd, Vd, dsc, S, z, 1e-6, O, ws)
+        torch.cuda.synchronize()
+    finally:
+        sv.sv_linattn_set_wait_limit(-1)
+    assert sv.sv_linattn_workspace_status(ws, B, H, d) == 1
+    assert bool((S == 3.0).all()) and bool((z == 5.0).all()), "a timed-out call changed the carried state"
+    if d == 64:                       # one launch: the apply phase is skipped too
+        assert bool(torch.isnan(O.float()).all()), "a timed-out block step wrote rows of O"
+    sv.sv_linattn_workspace_init(ws, B, H, d)
+    assert sv.sv_linattn_workspace_status(ws, B, H, d) == 0
+    S.zero_()
+    z.zero_()
+    sv.sv_block_linattn_step(Qd, Kd, Vd, dsc, S, z, 1e-6, O, ws)
     torch.cuda.synchronize()
-    err = ws.numel() - 32 - 8 * B * H
-    assert int(ws[err:err + 8].view(torch.int64)[0]) == 0
+    assert sv.sv_linattn_workspace_status(ws, B, H, d) == 0
+    O_ref, S_ref, z_ref = orc.bidirectional(Q, K, V, 1e-6)
+    _check_state(S, z, S_ref, z_ref, "after the timeout")
+    metrics.check(to_host(O), O_ref, "bf16", "O after the timeout")
+
+
+@pytest.mark.parametrize("H,d", [(32, 64), (20, 112)])
+def test_workspace_reinitialised_between_uses(H, d):
+    """Device-side epochs restart when a workspace is initialised again, so a flag left by the single
+    launch of its earlier life equals the first epoch of the new one: initialisation must clear the flags,
+    or the second call below folds partials that are not there yet."""
+    import torch
+    B, N = 1, 4680
+    say(f"workspace_reinitialised H={H} d={d}")
+    _, K0, V0 = _draw(7970, B, H, N, d, "bf16")
+    _, K1, V1 = _draw(7971, B, H, N, d, "bf16")
+    ws = new_workspace(B, H, N, d)
+    S, z = new_state(B, H, d)
+    for K, V in ((K0, V0), (K1, V1)):
+        Kd, Vd = to_dev(K), to_dev(V)
+        sv.sv_linattn_workspace_init(ws, B, H, d)
+        sv.sv_linattn_state(Kd, Vd, sv.desc_of(Kd), 0, N, 0, S, z, ws)
+        torch.cuda.synchronize()
+        S_ref, z_ref = orc.state(K, V)
+        _check_state(S, z, S_ref, z_ref, "state after (re)initialisation")
+    assert sv.sv_linattn_workspace_status(ws, B, H, d) == 0
 
 
 # ---- look-ahead step: the cache is used but not updated (noisy passes of Alg. 1) -------------------

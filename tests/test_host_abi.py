@@ -55,6 +55,9 @@ def _desc(**kw):
 @pytest.mark.parametrize("kwargs,status", [
     (dict(d=48), 3), (dict(dtype=5), 3), (dict(N=0), 2), (dict(B=0), 2), (dict(stride_n=32), 2),
     (dict(stride_n=68), 4), (dict(stride_h=128 * 64 + 4), 4),
+    # rows of different heads or batches on top of each other
+    (dict(stride_h=127 * 64), 2), (dict(stride_h=64), 2), (dict(B=2, stride_b=128 * 64), 2),
+    (dict(stride_h=64, stride_n=64 * 2 - 8), 2),           # [N][H][d] with rows shorter than the heads they hold
 ])
 def test_bad_descriptors(kwargs, status):
     with pytest.raises(sv.SvError) as e:
@@ -67,6 +70,44 @@ def test_bad_descriptors(kwargs, status):
         with pytest.raises(sv.SvError) as e:
             step(FAKE, FAKE, FAKE, _desc(**kwargs), FAKE, FAKE, 1e-6, FAKE, FAKE, workspace_bytes=1 << 30)
         assert e.value.status == status
+
+
+def test_interleaved_layouts_are_accepted_up_to_the_launch():
+    """[B][N][H][d] (heads interleaved inside a token row) and token slices of a longer tensor pass the
+    descriptor checks: the calls get as far as the workspace check."""
+    for kw in (dict(stride_h=64, stride_n=2 * 64, stride_b=128 * 2 * 64),
+               dict(stride_h=1000 * 64), dict(H=1, stride_h=0), dict(B=1, stride_b=0)):
+        with pytest.raises(sv.SvError) as e:
+            sv.sv_linattn_state(FAKE, FAKE, _desc(**kw), 0, 1, 0, FAKE, FAKE, FAKE, workspace_bytes=16)
+        assert e.value.status == 6, kw
+
+
+def test_workspace_status_word():
+    """The word that records a timed-out wait lies inside the workspace, behind the partials, the look-ahead
+    state and the flags, 8-byte aligned; the query checks its arguments like the other workspace calls."""
+    for (B, H, d) in ((1, 32, 64), (2, 32, 64), (1, 20, 112), (1, 7, 128), (1, 2, 32)):
+        off = sv.sv_linattn_workspace_status_offset(B, H, d)
+        total = sv.sv_linattn_workspace_bytes(B, H, 1, d)
+        assert off % 8 == 0 and 0 < off <= total - 8
+        assert off >= B * H * (32 + 1) * (d * d + d) * 4        # partials of 32 chunks + look-ahead state
+        assert total - off == (4 + B * H) * 8                    # [error, magic, pad, pad, tickets[B*H]]
+    assert sv.sv_linattn_workspace_status_offset(1, 2, 48) == 0
+    assert sv.sv_linattn_workspace_status_offset(0, 2, 64) == 0
+    big = 1 << 30
+    with pytest.raises(sv.SvError) as e:
+        sv.sv_linattn_workspace_status(None, 1, 2, 64, workspace_bytes=big)
+    assert e.value.status == 1
+    with pytest.raises(sv.SvError) as e:
+        sv.sv_linattn_workspace_status(FAKE, 1, 2, 48, workspace_bytes=big)
+    assert e.value.status == 3
+    with pytest.raises(sv.SvError) as e:
+        sv.sv_linattn_workspace_status(FAKE, 1, 2, 64, workspace_bytes=100)
+    assert e.value.status == 6
+    with pytest.raises(sv.SvError) as e:
+        sv.sv_linattn_workspace_status(FAKE + 8, 1, 2, 64, workspace_bytes=big)
+    assert e.value.status == 4
+    lib = sv.load_library()
+    assert lib.sv_linattn_workspace_status(ctypes.c_void_p(FAKE), big, 1, 2, 64, None, None) == 1   # no result pointer
 
 
 def test_null_range_alignment_workspace_eps():
@@ -190,6 +231,9 @@ def test_tconv_checks_arguments():
     assert call(y=FAKE) == 2                                # y on top of x
     assert call(y=FAKE + 64) == 2                           # y inside x
     assert call(cache_in=FAKE + (1 << 29) + 1024) == 2      # cache_in inside y
+    assert call(cache_out=FAKE + (1 << 29) + 2048) == 2     # cache_out inside y
+    assert call(cache_out=FAKE + 4096) == 2                 # cache_out inside x
+    assert call(cache_out=FAKE + (1 << 28)) == 2            # cache_out on top of W
 
 
 def test_stream_yardsticks_check_arguments():
