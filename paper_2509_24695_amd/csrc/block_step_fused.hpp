@@ -57,7 +57,7 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
     float *Sh = S_out + (size_t)bh * d * d, *zh = z_out + (size_t)bh * d;
     float *partials = static_cast<float *>(ws) + (size_t)bh * kMaxChunks * elems;
     EpochSource es;
-    es.begin(ws, BH, elems, epoch);
+    es.begin(ws, BH, elems, epoch, bh, c, C);
     // kRope3D: the tables sit behind everything else in LDS and live through both phases
     const unsigned char *lds_tab = lds + block_step_lds_bytes<TILE, WAVES, ROPE>();
 
@@ -75,6 +75,7 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
     apply_prefetch<0, kEarly>(qstream);
 
     // ---- fold this workgroup's share of K_b, V_b ----------------------------------------------
+    unsigned char *epoch_lds = lds + block_step_lds_bytes<TILE, WAVES, ROPE>() - kEpochLdsBytes;
     {
         StateAcc acc;
         acc.clear();
@@ -96,7 +97,6 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
     // complete in order, so the chain's wave keeps its own queue empty, and one wave per workgroup
     // polling is a quarter of the flag traffic.  The carried values of the slice are fetched before
     // the wait; they do not depend on the other workgroups.
-    unsigned char *epoch_lds = lds + block_step_lds_bytes<TILE, WAVES, ROPE>() - kEpochLdsBytes;
     epoch = es.resolve(reinterpret_cast<unsigned long long *>(epoch_lds));
     int *agreed = reinterpret_cast<int *>(epoch_lds + 8);          // did both waits end in time?
     const StateSlice sl(c, C, d);

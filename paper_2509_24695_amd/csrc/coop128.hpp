@@ -348,7 +348,7 @@ __global__ __launch_bounds__(256, 1) void state_mfma_d128(
     const uint16_t *Vh = V + b * st.b + h * st.h;
     const int n_tiles = (t1 - t0 + 31) / 32;
     EpochSource es;
-    if (FINALIZE) es.begin(ws, BH, elems, epoch);
+    if (FINALIZE) es.begin(ws, BH, elems, epoch, bh, c, C);
 
     StateAcc acc;
     acc.clear();

@@ -97,25 +97,23 @@ constexpr unsigned long long kWsTimeoutMark = 0x54494d454f555421ull;
 constexpr unsigned long long kTicketQuantum = 1ull << 20;     // far more than a head ever has workgroups
 
 struct EpochSource {
-    unsigned long long host, ticket;    // ticket is meaningful in thread 0 only
-    bool device;
+    unsigned long long host, ticket, magic;    // ticket and magic are meaningful in thread 0 only
 
-    // First thing in the kernel (grid = (C, B*H)): the memory operations return long
-    // before resolve() needs them.
-    __device__ __forceinline__ void begin(void *ws, int BH, int elems, unsigned long long host_epoch)
+    // First thing in the kernel, in workgroup c of the C workgroups of head bh.  Nothing here looks at
+    // what the two memory operations return, so the wave goes straight on to request its first tiles;
+    // they have long returned when resolve() needs them.  The ticket is drawn whether or not the
+    // workspace was initialised (the counters are reserved for this either way): deciding that first
+    // would cost the wave a memory round trip before its first load.
+    __device__ __forceinline__ void begin(void *ws, int BH, int elems, unsigned long long host_epoch, int bh, int c, int C)
     {
         host = host_epoch;
         ticket = 0;
-        device = false;
+        magic = 0;
         if (threadIdx.x == 0) {
-            const unsigned long long magic =
-                __hip_atomic_load(ws_magic(ws, BH, elems), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            device = magic == kWsMagic;
-            if (device) {
-                const unsigned long long w = blockIdx.x == 0 ? kTicketQuantum - (gridDim.x - 1) : 1ull;
-                ticket = __hip_atomic_fetch_add(ws_tickets(ws, BH, elems) + blockIdx.y, w, __ATOMIC_RELAXED,
-                                                __HIP_MEMORY_SCOPE_AGENT);
-            }
+            magic = __hip_atomic_load(ws_magic(ws, BH, elems), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const unsigned long long w = c == 0 ? kTicketQuantum - (unsigned long long)(C - 1) : 1ull;
+            ticket = __hip_atomic_fetch_add(ws_tickets(ws, BH, elems) + bh, w, __ATOMIC_RELAXED,
+                                            __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 
@@ -123,7 +121,10 @@ struct EpochSource {
     // (one barrier); `lds_word` is 8 bytes of LDS that nothing else uses.
     __device__ __forceinline__ unsigned long long resolve(unsigned long long *lds_word) const
     {
-        if (threadIdx.x == 0) *lds_word = device ? ((ticket / kTicketQuantum + 1) << 1) : host;
+        if (threadIdx.x == 0) {
+            const bool device = magic == kWsMagic;
+            *lds_word = device ? ((ticket / kTicketQuantum + 1) << 1) : host;
+        }
         __syncthreads();
         return *lds_word;
     }
@@ -513,7 +514,7 @@ __global__ __launch_bounds__(64 * WAVES, 1) void state_mfma_d64(
     const uint16_t *Vh = V + b * st.b + h * st.h;
     const int n_tiles = (t1 - t0 + TILE - 1) / TILE;
     EpochSource es;
-    if (FINALIZE) es.begin(ws, BH, kStateElems, epoch);
+    if (FINALIZE) es.begin(ws, BH, kStateElems, epoch, bh, c, C);
 
     StateAcc acc;
     acc.clear();

@@ -255,7 +255,7 @@ __global__ __launch_bounds__(256, 1) void state_mfma_wide(
     const uint16_t *Vh = V + b * st.b + h * st.h;
     const int n_tiles = (t1 - t0 + kWideTile - 1) / kWideTile;
     EpochSource es;
-    if (FINALIZE) es.begin(ws, BH, elems, epoch);
+    if (FINALIZE) es.begin(ws, BH, elems, epoch, bh, c, C);
 
     WideAcc acc;
     acc.clear();

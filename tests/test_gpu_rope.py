@@ -143,8 +143,8 @@ def test_rope_block_stream_with_3d_table(dtype, d, H):
     _check_state(S, z, refs[-1][1], refs[-1][2], dtype, "final state")
 
 
-def test_rope_480p_full_size_sampled():
-    """The 480p-like layer with its 21x30x52 3-D table: state in full, O on sampled ranges."""
+def test_rope_480p_full_size():
+    """The 480p-like layer with its 21x30x52 3-D table: S, z and every element of O."""
     import torch
     w = wl.workload("bidir_480p")
     say(f"rope {w.name} full size")
@@ -153,17 +153,11 @@ def test_rope_480p_full_size_sampled():
     Qd, Kd, Vd, Td = to_dev(Q), to_dev(K), to_dev(V), _dev_table(T)
     S, z = new_state(w.B, w.H, w.d)
     ws = new_workspace(w.B, w.H, w.N, w.d)
-    O = torch.empty_like(Qd)
+    O = torch.full_like(Qd, float("nan"))
     dsc = sv.desc_of(Qd)
     sv.sv_linattn_state_rope(Kd, Vd, dsc, Td, 0, w.N, 0, S, z, ws)
     sv.sv_linattn_apply_rope(Qd, dsc, Td, 0, w.N, S, z, w.eps, O)
     torch.cuda.synchronize()
-    S_ref, z_ref = orc.state(K, V, rope=T)
+    O_ref, S_ref, z_ref = orc.bidirectional(Q, K, V, w.eps, rope=T)
     _check_state(S, z, S_ref, z_ref, "bf16", w.name)
-    Oh = to_host(O)
-    assert np.isfinite(Oh).all()
-    rng = np.random.default_rng(5)
-    for a in [0, w.N - 100] + [int(x) for x in rng.integers(0, w.N - 200, size=5)]:
-        b = min(w.N, a + 200)
-        ref = orc.apply(Q, S_ref, z_ref, w.eps, a, b, rope=T)
-        metrics.check(Oh[:, :, a:b], ref, "bf16", f"tokens [{a},{b})")
+    metrics.check(to_host(O), O_ref, "bf16", f"rope {w.name}")

@@ -158,28 +158,3 @@ def test_rope3d_tables_too_large_for_lds():
     torch.cuda.synchronize()
     assert metrics.rel_l2(to_host(S), S_ref) <= 1e-5      # the plain-FMA path keeps rotated keys in fp32
     metrics.check(to_host(O), O_ref, "bf16", "O")
-
-
-def test_rope3d_480p_full_size_sampled():
-    import torch
-    w = wl.workload("bidir_480p")
-    say(f"rope3d {w.name} full size")
-    Q, K, V = wl.draw_qkv(w)
-    _, R, T = _tables(*w.grid, w.d)
-    Qd, Kd, Vd = to_dev(Q), to_dev(K), to_dev(V)
-    S, z = new_state(w.B, w.H, w.d)
-    ws = new_workspace(w.B, w.H, w.N, w.d)
-    O = torch.empty_like(Qd)
-    dsc = sv.desc_of(Qd)
-    sv.sv_linattn_state_rope3d(Kd, Vd, dsc, R, 0, w.N, 0, S, z, ws)
-    sv.sv_linattn_apply_rope3d(Qd, dsc, R, 0, w.N, S, z, w.eps, O)
-    torch.cuda.synchronize()
-    S_ref, z_ref = orc.state(K, V, rope=T)
-    assert metrics.rel_l2(to_host(S), S_ref) <= S_TOL["bf16"]
-    assert metrics.rel_l2(to_host(z), z_ref) <= 1e-5
-    Oh = to_host(O)
-    assert np.isfinite(Oh).all()
-    rng = np.random.default_rng(6)
-    for a in [0, w.N - 100] + [int(x) for x in rng.integers(0, w.N - 200, size=5)]:
-        b = min(w.N, a + 200)
-        metrics.check(Oh[:, :, a:b], orc.apply(Q, S_ref, z_ref, w.eps, a, b, rope=T), "bf16", f"tokens [{a},{b})")
