@@ -180,6 +180,35 @@ sv_status sv_block_linattn_step(const void *Qb, const void *Kb, const void *Vb,
                                 float *S, float *z, float eps, void *Ob,
                                 void *workspace, size_t workspace_bytes, void *stream);
 
+/* sv_block_linattn_step for callers that cannot allocate device memory at all -
+ * code inside a HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc - and so cannot bring a workspace: the same step, same kernels and
+ * same results (bit for bit), with the workspace taken from an array of
+ * SV_STATIC_SCRATCH_BYTES that is part of the library's device code.  Each GPU
+ * the library runs on holds that array from the moment the library is loaded on
+ * it until the process ends.  The call allocates and frees nothing; its first
+ * use on a device looks the array's address up (no allocation either).
+ *  - Limit: sv_linattn_workspace_bytes(B, H, N, d) must not exceed
+ *    SV_STATIC_SCRATCH_BYTES, else SV_ERR_WORKSPACE (checked before anything is
+ *    launched): B*H <= 91 at d = 64, <= 30 at d = 112, <= 23 at d = 128.
+ *  - All calls on one GPU share the one array, whichever stream they use: two
+ *    calls whose kernels overlap in time (different streams, or one stream and a
+ *    replaying graph) race on it and give wrong results.  Calls on one stream
+ *    are ordered and safe.  The array keeps what the last call left; nothing in it
+ *    has to start out as zero (flags are told apart by a fresh tag per call).
+ *  - A captured call replays with the tag of the capture, so a graph that holds
+ *    this call may be replayed only if no other use of the array, this entry
+ *    point included, ran in between.  Callers that replay graphs freely take
+ *    sv_block_linattn_step with a workspace prepared by sv_linattn_workspace_init.
+ *  - The timeout mark of the in-kernel waits cannot be read for this array; use
+ *    sv_block_linattn_step where that matters.
+ * Other arguments, checks and errors as sv_block_linattn_step; SV_ERR_LAUNCH also
+ * if the array's address cannot be obtained. */
+#define SV_STATIC_SCRATCH_BYTES (48u << 20)
+sv_status sv_block_linattn_step_static(const void *Qb, const void *Kb, const void *Vb,
+                                       const sv_tensor_desc *blk,
+                                       float *S, float *z, float eps, void *Ob, void *stream);
+
 /* The same block WITHOUT committing it (the noisy denoising passes of Alg. 1:
  * G(x; t_j, KV) attends to the cache plus the block itself, and only the final
  * pass at t = 0 updates the cache):

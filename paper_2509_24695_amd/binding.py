@@ -21,6 +21,7 @@ EXPORTS = (
     "sv_linattn_state_rope3d", "sv_linattn_apply_rope3d", "sv_block_linattn_step_rope3d",
     "sv_block_linattn_lookahead_rope3d", "sv_tconv_block_step", "sv_stream_read", "sv_stream_copy",
     "sv_linattn_workspace_status_offset", "sv_linattn_workspace_status", "sv_linattn_set_wait_limit",
+    "sv_block_linattn_step_static",
 )
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
@@ -85,6 +86,8 @@ def load_library():
     lib.sv_linattn_apply.restype = ctypes.c_int
     lib.sv_block_linattn_step.argtypes = [vp, vp, vp, dp, vp, vp, ctypes.c_float, vp, vp, sz, vp]
     lib.sv_block_linattn_step.restype = ctypes.c_int
+    lib.sv_block_linattn_step_static.argtypes = [vp, vp, vp, dp, vp, vp, ctypes.c_float, vp, vp]
+    lib.sv_block_linattn_step_static.restype = ctypes.c_int
     lib.sv_block_linattn_lookahead.argtypes = [vp, vp, vp, dp, vp, vp, ctypes.c_float, vp, vp, sz, vp]
     lib.sv_block_linattn_lookahead.restype = ctypes.c_int
     lib.sv_linattn_state_rope.argtypes = [vp, vp, dp, vp, i32, i32, ctypes.c_int, vp, vp, vp, sz, vp]
@@ -199,6 +202,14 @@ def sv_block_linattn_step(Qb, Kb, Vb, blk: TensorDesc, S, z, eps: float, Ob, wor
     _check(load_library().sv_block_linattn_step(_ptr(Qb), _ptr(Kb), _ptr(Vb), ctypes.byref(d) if d else None,
                                                 _ptr(S), _ptr(z), float(eps), _ptr(Ob), _ptr(workspace), wb,
                                                 _stream(stream)), "sv_block_linattn_step")
+
+
+def sv_block_linattn_step_static(Qb, Kb, Vb, blk: TensorDesc, S, z, eps: float, Ob, stream=None) -> None:
+    """sv_block_linattn_step on the library's own static workspace (no allocation anywhere)."""
+    d = blk._c() if blk is not None else None
+    _check(load_library().sv_block_linattn_step_static(_ptr(Qb), _ptr(Kb), _ptr(Vb), ctypes.byref(d) if d else None,
+                                                       _ptr(S), _ptr(z), float(eps), _ptr(Ob), _stream(stream)),
+           "sv_block_linattn_step_static")
 
 
 def sv_block_linattn_lookahead(Qb, Kb, Vb, blk: TensorDesc, S, z, eps: float, Ob, workspace,

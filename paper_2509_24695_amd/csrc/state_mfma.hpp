@@ -89,12 +89,15 @@ __host__ __device__ constexpr size_t ws_total_bytes(int BH, int elems) {
 // launches on a stream do not overlap, so all workgroups of the head's n-th
 // launch draw tickets in [n * quantum, (n + 1) * quantum) and agree on n, however
 // many workgroups each launch gave the head.  Nothing is ever reset.
-// Device epochs are even, host epochs odd: they never collide.
+// Device epochs are even, host epochs odd: they never collide.  A host epoch with its top bit set tells
+// the kernel not to look for kWsMagic at all (kHostEpochsOnly: the workspace is memory whose header
+// nobody can have initialised and whose contents, left by calls of other shapes, are arbitrary).
 constexpr unsigned long long kWsMagic = 0x73764c696e417474ull;
 // What the workspace's error word holds after a bounded wait has run out.  A fixed pattern, so that the
 // word means something in a workspace whose contents were never initialised (any other value: no timeout).
 constexpr unsigned long long kWsTimeoutMark = 0x54494d454f555421ull;
 constexpr unsigned long long kTicketQuantum = 1ull << 20;     // far more than a head ever has workgroups
+constexpr unsigned long long kHostEpochsOnly = 1ull << 63;
 
 struct EpochSource {
     unsigned long long host, ticket, magic;    // ticket and magic are meaningful in thread 0 only
@@ -122,7 +125,7 @@ struct EpochSource {
     __device__ __forceinline__ unsigned long long resolve(unsigned long long *lds_word) const
     {
         if (threadIdx.x == 0) {
-            const bool device = magic == kWsMagic;
+            const bool device = magic == kWsMagic && !(host & kHostEpochsOnly);
             *lds_word = device ? ((ticket / kTicketQuantum + 1) << 1) : host;
         }
         __syncthreads();

@@ -46,6 +46,7 @@ struct Shape {
     TokStrides st;
     bool bf16;
     int elem_bytes;
+    bool host_epochs_only = false;   // the workspace is the library's own static array (see next_epoch)
 };
 
 struct Device {
@@ -212,11 +213,13 @@ const Device &device_info()
 // Fresh 64-bit tag for the workspace's flags; unique per call within the process
 // and seeded from the clock so that stale workspace contents of an earlier
 // process do not look current.
-unsigned long long next_epoch()
+unsigned long long next_epoch(bool host_epochs_only = false)
 {
     static std::atomic<unsigned long long> ctr{
         (unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count() * 0x9E3779B97F4A7C15ull};
-    return (ctr.fetch_add(1, std::memory_order_relaxed) << 1) | 1ull;   // odd, never zero, never repeated
+    // odd, never zero, never repeated (2^62 calls apart); the top bit is the kernels' kHostEpochsOnly
+    const unsigned long long e = ((ctr.fetch_add(1, std::memory_order_relaxed) << 1) | 1ull) & ~kHostEpochsOnly;
+    return host_epochs_only ? e | kHostEpochsOnly : e;
 }
 
 // Token chunks (workgroups) per head: about one workgroup per compute unit over
@@ -305,7 +308,8 @@ void launch_state_mfma(const uint16_t *k, const uint16_t *v, const Rope &rope, c
         if ((int64_t)C * s.BH <= dev.state_resident_wgs[KN::W][rope.mode]) {
             // the head's workgroups wait for each other inside the kernel: all must be resident
             KN::state<<<dim3(C, s.BH), 64 * kStateWaves, KN::state_lds, stream>>>(
-                k, v, rope.arg, s.st, s.H, s.d, t0, t1, C, S_in, z_in, S_out, z_out, ws, next_epoch(), spin_limit());
+                k, v, rope.arg, s.st, s.H, s.d, t0, t1, C, S_in, z_in, S_out, z_out, ws, next_epoch(s.host_epochs_only),
+                spin_limit());
         } else {
             KN::state_partial<<<dim3(C, s.BH), 64 * kStateWaves, KN::state_lds, stream>>>(
                 k, v, rope.arg, s.st, s.H, s.d, t0, t1, C, S_in, z_in, S_out, z_out, ws, 0ull, 0u);
@@ -464,12 +468,13 @@ sv_status do_apply(const void *Q, const sv_tensor_desc *q, const RopeSpec &spec,
 sv_status do_block_step(const void *Qb, const void *Kb, const void *Vb, const sv_tensor_desc *blk,
                         const RopeSpec &spec, const float *S_in, const float *z_in, float *S_out, float *z_out,
                         bool lookahead, float eps, void *Ob, void *workspace, size_t workspace_bytes_given,
-                        void *stream)
+                        void *stream, bool static_workspace = false)
 {
     if (!Qb || !Kb || !Vb || !S_in || !z_in || !Ob || !workspace) return SV_ERR_NULL;
     Shape s;
     sv_status rc = check_desc(blk, &s);
     if (rc != SV_OK) return rc;
+    s.host_epochs_only = static_workspace;
     if (!eps_ok(eps)) return SV_ERR_RANGE;
     Rope rope;
     if ((rc = resolve_rope(spec, s, &rope)) != SV_OK) return rc;
@@ -494,7 +499,7 @@ sv_status do_block_step(const void *Qb, const void *Kb, const void *Vb, const sv
             KN::fused<<<dim3(C, s.BH), 64 * kStateWaves, KN::fused_lds, hs>>>(
                 static_cast<const uint16_t *>(Qb), static_cast<const uint16_t *>(Kb),
                 static_cast<const uint16_t *>(Vb), static_cast<uint16_t *>(Ob), rope.arg, s.st, s.H, s.N, C, S_in,
-                z_in, S_out, z_out, eps, workspace, next_epoch(), spin_limit());
+                z_in, S_out, z_out, eps, workspace, next_epoch(s.host_epochs_only), spin_limit());
             launched = true;
         };
         if (rope.mode == kRope3D) launch(Kernels<64, kRope3D>{});
@@ -505,6 +510,31 @@ sv_status do_block_step(const void *Qb, const void *Kb, const void *Vb, const sv
     rc = enqueue_state(Kb, Vb, rope, s, 0, s.N, S_in, z_in, S_out, z_out, workspace, hs);
     if (rc != SV_OK) return rc;
     return enqueue_apply(Qb, rope, s, 0, s.N, S_out, z_out, eps, Ob, hs);
+}
+
+// ---- the workspace of sv_block_linattn_step_static: a file-scope device array ----------------------------------
+// Every GPU that loads the library holds its own copy until the process ends.  In host code the array's
+// name is only a handle for hipGetSymbolAddress; the address that kernels and other HIP calls get is the
+// one that call returns, looked up once per device with that device current.
+constexpr size_t kStaticScratchBytes = SV_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+void *static_scratch()
+{
+    static void *ptrs[64] = {};
+    static std::mutex mu;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptrs[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        ptrs[dev] = p;
+    }
+    return ptrs[dev];
 }
 
 }  // namespace
@@ -587,6 +617,20 @@ sv_status sv_block_linattn_step(const void *Qb, const void *Kb, const void *Vb, 
 {
     return do_block_step(Qb, Kb, Vb, blk, kNoRope, S, z, S, z, false, eps, Ob, workspace,
                          workspace_bytes_given, stream);
+}
+
+sv_status sv_block_linattn_step_static(const void *Qb, const void *Kb, const void *Vb, const sv_tensor_desc *blk,
+                                       float *S, float *z, float eps, void *Ob, void *stream)
+{
+    // the size check needs the descriptor only and comes before the first HIP call
+    Shape s;
+    const sv_status rc = check_desc(blk, &s);
+    if (rc != SV_OK) return rc;
+    if (workspace_bytes(s.BH, s.d) > kStaticScratchBytes) return SV_ERR_WORKSPACE;
+    if (!Qb || !Kb || !Vb || !S || !z || !Ob) return SV_ERR_NULL;
+    void *ws = static_scratch();
+    if (!ws) return SV_ERR_LAUNCH;
+    return do_block_step(Qb, Kb, Vb, blk, kNoRope, S, z, S, z, false, eps, Ob, ws, kStaticScratchBytes, stream, true);
 }
 
 sv_status sv_block_linattn_lookahead(const void *Qb, const void *Kb, const void *Vb, const sv_tensor_desc *blk,
