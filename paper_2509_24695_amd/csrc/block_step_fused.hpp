@@ -33,12 +33,14 @@ __host__ __device__ constexpr int block_step_lds_bytes() {
 // the state and the apply kernel want different workgroup shapes, and one launch measured 2-8 us
 // slower at every block size.)
 // ROPE: keys and queries are rotated after the ReLU in the numerator path (table row = token of the block).
-template <int TILE, int WAVES, int DEPTH_S, bool HILO, int DEPTH_A, int ROPE>
+// LOCAL: grid = (C * B*H) with B*H a multiple of n_dies; all workgroups of a head run on one die and
+// exchange their partial states and the new state through that die's L2 (see store_coherent).
+template <int TILE, int WAVES, int DEPTH_S, bool HILO, int DEPTH_A, int ROPE, bool LOCAL = false>
 __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
     uint16_t *__restrict__ O, RopeArg rope, TokStrides st, int H, int N, int C,
     const float *S_in, const float *z_in, float *S_out, float *z_out, float eps, void *__restrict__ ws,
-    unsigned long long epoch, uint32_t spin_limit)
+    unsigned long long epoch, uint32_t spin_limit, int BH_local, int n_dies)
 {
     static_assert(TILE == kApplyTile, "both phases walk tiles of the same size");
     constexpr int kTileBytes = TILE * kRowBytes;
@@ -46,7 +48,16 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int c = blockIdx.x, bh = blockIdx.y, BH = gridDim.y;
+    int c = blockIdx.x, bh = blockIdx.y, BH = gridDim.y;
+    if (LOCAL) {
+        // consecutive workgroup ids go round the dies: die x gets ids x, x + n_dies, ..., and with them
+        // heads x, x + n_dies, ..., C workgroups each
+        const int die = (int)blockIdx.x % n_dies, slot = (int)blockIdx.x / n_dies;
+        BH = BH_local;
+        bh = die + n_dies * (slot / C);
+        c = slot % C;
+    }
+    const uint32_t my_die = LOCAL ? die_id() : 0u;
     const int b = bh / H, h = bh % H;
     constexpr int d = 64, elems = d * d + d;
     const int64_t head_off = b * st.b + h * st.h;
@@ -68,7 +79,8 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
     // divide evenly the longer shares fall on low share numbers, and workgroup c of every head runs on
     // the same die (consecutive workgroup ids go round the dies).
     const int share = block_step_share(c, bh, C);
-    const TileWalk walk(0, WAVES * share + wave, WAVES * C, n_tiles, bh);
+    const int phase_key = LOCAL ? die_local_phase_key(bh, n_dies, BH) : bh;   // heads start their walks at staggered phases
+    const TileWalk walk(0, WAVES * share + wave, WAVES * C, n_tiles, phase_key);
     ApplyStream<DEPTH_A, ROPE> qstream(Q + head_off, O + head_off, rope, lds_tab, st.n, N, lane, walk);
     Rope3dFill tabs;
     if (ROPE == kRope3D) rope3d_lds_fill_begin(rope.r3, tabs);   // the first loads of the kernel
@@ -87,7 +99,7 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
             __syncthreads();
         }
         state_accumulate(kvstream, tileK, tileK + kTileBytes, lane, acc);
-        state_wg_reduce_store<WAVES, ROPE != kRopeNone>(acc, reinterpret_cast<float *>(lds), wave, lane,
+        state_wg_reduce_store<WAVES, ROPE != kRopeNone, LOCAL>(acc, reinterpret_cast<float *>(lds), wave, lane,
                                            partials + (size_t)share * elems);   // slot = share: the fold adds the shares in tile order
     }
     // ---- the head agrees on its new state ------------------------------------------------------
@@ -102,17 +114,32 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
     const StateSlice sl(c, C, d);
     f32x2 carry[5] = {};
     if (wave == 0) state_slice_carry<kWave>(sl, Sc, zc, lane, carry);
-    state_publish(ws, BH, elems, bh, c, 0, epoch);
+    if (LOCAL) {
+        coherent_stores_done();
+        __syncthreads();
+        if (threadIdx.x == 0) flag_publish<true>(ws_flags(ws, BH, elems, bh, 0) + c, flag_with_die(epoch, my_die));
+    } else {
+        state_publish(ws, BH, elems, bh, c, 0, epoch);
+    }
     if (wave != 0) {
         apply_prefetch<kEarly, DEPTH_A>(qstream);
     } else {
-        bool ok = state_wait(ws, BH, elems, bh, C, 0, epoch, spin_limit, lane);
+        bool same_die = true;
+        bool ok = LOCAL ? flags_wait_all_local(ws_flags(ws, BH, elems, bh, 0), C, epoch, spin_limit, lane, my_die, &same_die)
+                        : state_wait(ws, BH, elems, bh, C, 0, epoch, spin_limit, lane);
+        ok = ok && same_die;
         if (ok) {
-            state_finalize_slice<kWave, true, 5, 8>(partials, sl, C, Sc, zc, Sh, zh, lane, carry);
+            state_finalize_slice<kWave, true, 5, 8, LOCAL>(partials, sl, C, Sc, zc, Sh, zh, lane, carry);
             coherent_stores_done();
-            if (lane == 0) flag_publish(ws_flags(ws, BH, elems, bh, 1) + c, epoch);
-            ok = state_wait(ws, BH, elems, bh, C, 1, epoch, spin_limit, lane);
+            if (lane == 0) {
+                if (LOCAL) flag_publish<true>(ws_flags(ws, BH, elems, bh, 1) + c, flag_with_die(epoch, my_die));
+                else flag_publish(ws_flags(ws, BH, elems, bh, 1) + c, epoch);
+            }
+            ok = LOCAL ? flags_wait_all_local(ws_flags(ws, BH, elems, bh, 1), C, epoch, spin_limit, lane, my_die, &same_die)
+                       : state_wait(ws, BH, elems, bh, C, 1, epoch, spin_limit, lane);
         }
+        if (LOCAL && !ok && lane == 0)
+            __hip_atomic_store(ws_error(ws, BH, elems), kWsTimeoutMark, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (lane == 0) *agreed = ok;
     }
     __syncthreads();

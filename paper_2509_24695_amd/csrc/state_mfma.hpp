@@ -335,7 +335,7 @@ __device__ __forceinline__ void state_acc_to_slot(StateAcc &acc, float *dst, int
 // barrier each thread adds the waves' slots for its share of the elements,
 // wave w absorbing wave w + h for h = WAVES/2, ..., 1.  Must be called by all
 // threads; the staging tiles are dead afterwards.  LDS: WAVES * kStateElems floats.
-template <int WAVES, bool ZVALU>
+template <int WAVES, bool ZVALU, bool LOCAL = false>
 __device__ __forceinline__ void state_wg_reduce_store(StateAcc &acc, float *slots, int wave, int lane,
                                                       float *__restrict__ out)
 {
@@ -351,7 +351,7 @@ __device__ __forceinline__ void state_wg_reduce_store(StateAcc &acc, float *slot
         for (int h = WAVES / 2; h >= 1; h /= 2)
 #pragma unroll
             for (int w = 0; w < h; ++w) x[w] += x[w + h];
-        store_coherent(out + 2 * v, x[0]);
+        store_coherent<LOCAL>(out + 2 * v, x[0]);
     }
 }
 
@@ -404,7 +404,7 @@ __device__ __forceinline__ void state_slice_carry(const StateSlice &sl, const fl
 // flight per unit: the loads of a round trip of ~1 us are all issued before any is used.
 // COHERENT_OUT: also store the result coherently (other workgroups of this kernel are going to
 // read it).  Called by THREADS threads numbered tid = 0 .. THREADS - 1 (a workgroup, or one wave).
-template <int THREADS, bool COHERENT_OUT, int UNITS = 3, int GROUP = 16>
+template <int THREADS, bool COHERENT_OUT, int UNITS = 3, int GROUP = 16, bool LOCAL = false>
 __device__ __forceinline__ void state_finalize_slice(const float *__restrict__ partials, const StateSlice &sl, int C,
                                                      const float *S_in, const float *z_in, float *S_out,
                                                      float *z_out, int tid, const f32x2 (&carry)[UNITS])
@@ -445,7 +445,7 @@ __device__ __forceinline__ void state_finalize_slice(const float *__restrict__ p
             const int v = v0 + u * THREADS;
             if (v < hi) {
                 float *dst = v < s_units ? S_out + 2 * v : z_out + 2 * (v - s_units);
-                if (COHERENT_OUT) store_coherent(dst, x[u]);
+                if (COHERENT_OUT) store_coherent<LOCAL>(dst, x[u]);
                 else *reinterpret_cast<f32x2 *>(dst) = x[u];
             }
         }

@@ -62,4 +62,15 @@ struct StateSlice {
 // dealt from a different start in each head (see block_step_mfma).
 SV_HOST_DEVICE inline int block_step_share(int c, int bh, int C) { return (c + bh) % C; }
 
+// Phase key (the `bh` argument of TileWalk) of head bh in the die-local forms of the kernels, where die x
+// holds heads x, x + n_dies, ...: keyed by the head index itself, heads of one die would share phases (two
+// distinct ones for four heads), so the sixteen phases are dealt die by die, the heads of a die as far apart
+// as their number allows.
+SV_HOST_DEVICE inline int die_local_phase_key(int bh, int n_dies, int BH)
+{
+    const int per_die = BH / n_dies > 0 ? BH / n_dies : 1;
+    const int stride = per_die < 16 ? 16 / per_die : 1;
+    return ((bh / n_dies) * stride + (bh % n_dies) % stride) & 15;
+}
+
 }  // namespace sv
