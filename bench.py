@@ -75,6 +75,8 @@ def _parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="bidir_720p", choices=["bidir_480p", "bidir_720p", "bidir_480p_h20d112"])
     ap.add_argument("--no-secondary", action="store_true", help="skip the 480p-like bidirectional layer")
+    ap.add_argument("--no-apply-variants", action="store_true",
+                    help="skip the A/B timings of the apply kernel's measurement variants")
     ap.add_argument("--sets", type=int, default=0, help="rotating buffer sets (0 = enough for > 1.5 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-block-stream", action="store_true")
@@ -183,7 +185,7 @@ def bench_bidirectional(w, steps, warmup, n_sets, sv, torch, rope=None, sets=Non
     }
 
 
-def bench_block_stream(w, n_blocks, sv, torch, rope=False, ceiling=False):
+def bench_block_stream(w, n_blocks, sv, torch, rope=False, ceiling=False, traffic=None):
     """Whole stream enqueued back to back, one event pair per block; no host sync inside.
     `rope`: False, "table" (sv_block_linattn_step_rope, one full table per block) or "3d"
     (sv_block_linattn_step_rope3d, per-axis tables; the frame table of each block continues the
@@ -317,6 +319,12 @@ def bench_block_stream(w, n_blocks, sv, torch, rope=False, ceiling=False):
         "allocated_bytes_after_block": mem_alloc, "device_bytes_in_use_after_block": mem_device,
         "memory_constant_over_stream": len(set(mem_alloc)) == 1,
     }
+    if traffic is not None:
+        nbytes, note = traffic
+        gbps = w.algorithmic_bytes / (per_block_us * 1e-6) / 1e9
+        out["roofline"] = {"bound": "hbm", "kernel": "block_step_mfma", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                           "frac": gbps / HBM_PEAK_GBPS, "traffic": nbytes, "traffic_source": note,
+                           "algorithmic_bytes_per_launch": w.algorithmic_bytes, "avg_launch_ms": per_block_us * 1e-3}
     if ceiling:
         # what the device gives two dependent passes that only move the block's bytes: a pure read of K_b, V_b,
         # then a pure copy of Q_b's size into O_b's (kernels of include/sv_measure.h, timed like the blocks)
@@ -393,6 +401,40 @@ def bench_tconv(w, iters, sv, torch):
             "roofline": {"bound": "mfma", "kernel": "tconv_mfma", "achieved": tflops, "peak": MFMA_BF16_PEAK_TFLOPS,
                          "unit": "TFLOP/s", "frac": tflops / MFMA_BF16_PEAK_TFLOPS,
                          "algorithmic_flops_per_launch": w.algorithmic_flops}}
+
+
+def bench_apply_variants(w, sets, steps, sv, torch):
+    """The d = 64 apply kernel in its four forms (include/sv_measure.h: S in registers or in LDS, denominators
+    through the matrix core or on the vector ALU), each timed between one event pair over `steps` launches on
+    rotating buffer sets: the A/B figures behind two choices of the kernel design."""
+    B, H, N, d = w.B, w.H, w.N, w.d
+    S = torch.randn((B, H, d, d), dtype=torch.float32, device="cuda")
+    z = torch.rand((B, H, d), dtype=torch.float32, device="cuda") * N * 0.2 + 1.0
+    dsc = sv.desc_of(sets[0][0])
+    stream = torch.cuda.current_stream()
+    names = ["S in registers, denominators on the matrix core (the library's kernel)", "S in LDS, denominators on the matrix core",
+             "S in registers, denominators on the vector ALU", "S in LDS, denominators on the vector ALU"]
+    times = {v: [] for v in range(4)}
+    for rnd in range(3):                                  # three rounds, the variants in a different order each
+        for variant in [(rnd + k) % 4 for k in range(4)]:
+            for i in range(3):
+                q, _, _, o = sets[i % len(sets)]
+                sv.sv_measure_apply_variant(variant, q, dsc, 0, N, S, z, w.eps, o, stream=stream)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            a.record(stream)
+            for i in range(steps):
+                q, _, _, o = sets[i % len(sets)]
+                sv.sv_measure_apply_variant(variant, q, dsc, 0, N, S, z, w.eps, o, stream=stream)
+            b.record(stream)
+            torch.cuda.synchronize()
+            times[variant].append(a.elapsed_time(b) * 1e3 / steps)
+    out = []
+    for variant in range(4):
+        us = statistics.median(times[variant])
+        out.append({"variant": variant, "what": names[variant], "us_per_launch": us,
+                    "hbm_frac": w.algorithmic_bytes / 2 / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS})
+    return out
 
 
 def cpu_baseline(w, sets, torch):
@@ -513,6 +555,8 @@ def main():
             "hbm_frac_step": w.algorithmic_bytes / (rr["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
             "kernels_ms": {"state": rr["ms_state"], "apply": rr["ms_apply"]},
         }
+    if not args.no_apply_variants and w.d == 64:
+        out["apply_variants"] = bench_apply_variants(w, r["sets"], args.steps, sv, torch)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, r["sets"], torch)
     del r
@@ -554,8 +598,10 @@ def main():
     if not args.no_block_stream:
         cl = not args.no_stream_ceiling
         out["block_stream"] = [
-            bench_block_stream(wl.workload("block_480p"), 10, sv, torch, ceiling=cl),
-            bench_block_stream(wl.workload("stream_720p"), args.stream_blocks, sv, torch, ceiling=cl),
+            bench_block_stream(wl.workload("block_480p"), 10, sv, torch, ceiling=cl,
+                               traffic=traffic_of(table, "block_step", "block_480p", fingerprint)),
+            bench_block_stream(wl.workload("stream_720p"), args.stream_blocks, sv, torch, ceiling=cl,
+                               traffic=traffic_of(table, "block_step", "stream_720p", fingerprint)),
         ]
         if not args.no_d112:
             out["block_stream"].append(bench_block_stream(wl.workload("block_480p_h20d112"), 10, sv, torch))

@@ -33,6 +33,24 @@ sv_status sv_stream_read(const void *src, size_t bytes, void *sink, int32_t wgs,
 /* dst[0, bytes) = src[0, bytes). */
 sv_status sv_stream_copy(const void *src, void *dst, size_t bytes, int32_t wgs, void *stream);
 
+/* sv_linattn_apply for bf16 tokens and d = 64 in four forms of its kernel, for A/B measurements of two
+ * design choices (same arguments, checks, launch shape and results to rounding as sv_linattn_apply; no
+ * passage of the paper of its own):
+ *   variant 0  the kernel sv_linattn_apply launches: the head's state S lives in each wave's registers as
+ *              matrix-core operands for the whole token range, and the denominators phi(Q_i).z come out of
+ *              the same matrix-core pass (z as two extra operand rows, one cross-lane exchange);
+ *   variant 1  S kept in LDS instead (one copy per workgroup) and read again for every 32-token tile,
+ *              denominators as in variant 0;
+ *   variant 2  S in registers, denominators on the vector ALU: per lane 32 multiply-adds against the key
+ *              sums, then the two half-waves exchange their partial sums (a wavefront-level reduction);
+ *   variant 3  S in LDS and denominators on the vector ALU.
+ * SV_ERR_RANGE for another variant, SV_ERR_UNSUPPORTED unless the descriptor is SV_BF16 with d = 64 and
+ * heads below 2 GiB.  The first call of a variant on a device sets a kernel attribute: not under graph
+ * capture. */
+sv_status sv_measure_apply_variant(int32_t variant, const void *Q, const sv_tensor_desc *q,
+                                   int32_t tok_begin, int32_t tok_end,
+                                   const float *S, const float *z, float eps, void *O, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

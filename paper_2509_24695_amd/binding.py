@@ -21,7 +21,7 @@ EXPORTS = (
     "sv_linattn_state_rope3d", "sv_linattn_apply_rope3d", "sv_block_linattn_step_rope3d",
     "sv_block_linattn_lookahead_rope3d", "sv_tconv_block_step", "sv_stream_read", "sv_stream_copy",
     "sv_linattn_workspace_status_offset", "sv_linattn_workspace_status", "sv_linattn_set_wait_limit",
-    "sv_block_linattn_step_static",
+    "sv_block_linattn_step_static", "sv_measure_apply_variant",
 )
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
@@ -107,6 +107,8 @@ def load_library():
         f.restype = ctypes.c_int
     lib.sv_tconv_block_step.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp]
     lib.sv_tconv_block_step.restype = ctypes.c_int
+    lib.sv_measure_apply_variant.argtypes = [i32, vp, dp, i32, i32, vp, vp, ctypes.c_float, vp, vp]
+    lib.sv_measure_apply_variant.restype = ctypes.c_int
     lib.sv_stream_read.argtypes = [vp, sz, vp, i32, vp]
     lib.sv_stream_read.restype = ctypes.c_int
     lib.sv_stream_copy.argtypes = [vp, vp, sz, i32, vp]
@@ -360,6 +362,15 @@ def sv_tconv_block_step(x, W, cache_in, y, cache_out, B: int, T: int, HW: int, D
                                             dtype, _stream(stream))
     if rc != 0:
         raise SvError(rc, "sv_tconv_block_step")
+
+
+def sv_measure_apply_variant(variant: int, Q, q: TensorDesc, tok_begin: int, tok_end: int, S, z, eps: float, O,
+                             stream=None) -> None:
+    """sv_linattn_apply (bf16, d = 64) in one of four kernel forms (include/sv_measure.h)."""
+    d = q._c() if q is not None else None
+    _check(load_library().sv_measure_apply_variant(int(variant), _ptr(Q), ctypes.byref(d) if d else None, tok_begin,
+                                                   tok_end, _ptr(S), _ptr(z), float(eps), _ptr(O), _stream(stream)),
+           "sv_measure_apply_variant")
 
 
 def sv_stream_read(src, nbytes: int, sink, wgs: int, stream=None) -> None:

@@ -14,7 +14,8 @@
 // registers for its whole token range.  The key sum z rides along as two extra
 // operand rows (hi and lo), so the denominator comes out of the same MFMA pass
 // in fp32 and only has to be handed to the lane that holds the token's other
-// 32 features (one cross-lane exchange).  phi(Q)^T is the B operand: a lane
+// 32 features (one cross-lane exchange); DEN_VALU takes it on the vector ALU
+// instead (a wavefront-level reduction), which measures level.  phi(Q)^T is the B operand: a lane
 // needs 8 consecutive features of one token, i.e. 16 contiguous bytes of the
 // token row.  Q tiles come in with coalesced non-temporal 16-byte loads and
 // pass through a wave-private LDS tile to reach that layout; O tiles go back
@@ -98,7 +99,7 @@ struct ApplyOperands {
             const u32x4 w4 = {w[0], w[1], w[2], w[3]};
             zrow[ks] = __builtin_bit_cast(bf16x8, w4);
         }
-        __syncthreads();
+        wg_barrier();
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
@@ -106,7 +107,7 @@ struct ApplyOperands {
                 s[0][rb][ks] = st[((0 * NB + rb) * KS + ks) * 64 + lane];
                 if (HILO) s[NS - 1][rb][ks] = st[((1 * NB + rb) * KS + ks) * 64 + lane];
             }
-        __syncthreads();                        // `stage` may be written again
+        wg_barrier();                        // `stage` may be written again
     }
 
     // COHERENT: the state was written by another workgroup of this same kernel.
@@ -161,6 +162,20 @@ struct ApplyOperands {
     }
 };
 
+// The key sums a lane needs when the denominators are taken on the vector ALU (DEN_VALU): those of the 32
+// features of a token that pass through the lane as B operands, zf[ks][e] = z[16 ks + 8 (lane / 32) + e].
+template <bool COHERENT>
+__device__ __forceinline__ void load_key_sums(const float *__restrict__ zh, int lane, float (&zf)[4][8])
+{
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float *p = zh + 16 * ks + 8 * (lane >> 5) + e;
+            zf[ks][e] = COHERENT ? load_coherent1(p) : *p;
+        }
+}
+
 // One wave's token stream (d = 64): buffer resources over the head's Q and O
 // rows below the end of the token range, the wave's tile walk (32 tokens per
 // tile), the register staging of DEPTH tiles in flight, and the rotation source.
@@ -209,9 +224,17 @@ __device__ __forceinline__ void apply_prefetch(ApplyStream<DEPTH, ROPE> &st)
 // ones).  Tiles are taken DEPTH at a time; every stage issues its loads and
 // stores whether or not it still has a tile (out of range they do nothing), only
 // the arithmetic is skipped.
-template <bool HILO, int DEPTH, int ROPE>
+//
+// Two measurement variants (sv_measure_apply_variant; the library's own calls use neither):
+//   S_LDS     the operands of S stay in LDS (`s_lds`: the layout load_shared stages them in, shared by the
+//             workgroup's waves) and are read again for every tile, instead of living in each wave's registers;
+//   DEN_VALU  the denominators are taken on the vector ALU - every lane multiplies the 32 features of its token
+//             that pass through it as B operands with their key sums (`zf`, [k-step][feature]) and the two
+//             half-waves exchange their halves - instead of riding through the matrix core as two operand rows.
+template <bool HILO, int DEPTH, int ROPE, bool S_LDS = false, bool DEN_VALU = false>
 __device__ __forceinline__ void apply_tiles(ApplyStream<DEPTH, ROPE> &st, unsigned char *tileQ, int lane,
-                                            const ApplyOperands<64, HILO> &A, float eps)
+                                            const ApplyOperands<64, HILO> &A, float eps,
+                                            const unsigned char *s_lds = nullptr, const float (*zf)[8] = nullptr)
 {
     constexpr int NS = HILO ? 2 : 1;
     constexpr int KS = 4;
@@ -251,8 +274,18 @@ __device__ __forceinline__ void apply_tiles(ApplyStream<DEPTH, ROPE> &st, unsign
             if (valid) {
                 wave_lds_fence();
                 f32x16 acc[2], accz;
+                float den_valu = 0.f;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) { acc[0][i] = 0.f; acc[1][i] = 0.f; accz[i] = 0.f; }
+                if (DEN_VALU) {
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) {
+                        const u32x4 w = *reinterpret_cast<const u32x4 *>(tileQ + n * kRow + (16 * ks + 8 * g) * 2);
+                        den_valu += bf16_lo(w.x) * zf[ks][0] + bf16_hi(w.x) * zf[ks][1] + bf16_lo(w.y) * zf[ks][2] +
+                                    bf16_hi(w.y) * zf[ks][3] + bf16_lo(w.z) * zf[ks][4] + bf16_hi(w.z) * zf[ks][5] +
+                                    bf16_lo(w.w) * zf[ks][6] + bf16_hi(w.w) * zf[ks][7];
+                    }
+                }
                 // B operands: features 16*ks + 8g .. +8 of token n (br: the rotated copy for the numerator)
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
@@ -260,18 +293,26 @@ __device__ __forceinline__ void apply_tiles(ApplyStream<DEPTH, ROPE> &st, unsign
                     const bf16x8 br = ROPE ? *reinterpret_cast<const bf16x8 *>(tileQ + kTileBytes + n * kRow +
                                                                                (16 * ks + 8 * g) * 2)
                                            : bq;
-                    accz = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.zrow[ks], bq, accz, 0, 0, 0);
+                    if (!DEN_VALU) accz = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.zrow[ks], bq, accz, 0, 0, 0);
 #pragma unroll
                     for (int p = NS - 1; p >= 0; --p) {      // small (lo) terms first
-                        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.s[p][0][ks], br, acc[0], 0, 0, 0);
-                        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.s[p][1][ks], br, acc[1], 0, 0, 0);
+                        const bf16x8 *sl = reinterpret_cast<const bf16x8 *>(s_lds);   // [hi/lo][row block][k-step][lane]
+                        const bf16x8 a0 = S_LDS ? sl[((p * 2 + 0) * KS + ks) * 64 + lane] : A.s[p][0][ks];
+                        const bf16x8 a1 = S_LDS ? sl[((p * 2 + 1) * KS + ks) * 64 + lane] : A.s[p][1][ks];
+                        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, br, acc[0], 0, 0, 0);
+                        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, br, acc[1], 0, 0, 0);
                     }
                 }
                 wave_lds_fence();
                 // denominator: rows 0 (hi) and 1 (lo) of the z block sit in registers 0 and 1 of
                 // the lanes of the lower half; the upper half fetches them across the wave
-                float den = accz[1] + accz[0];
-                den = __shfl(den, n);
+                float den;
+                if (DEN_VALU) {
+                    den = den_valu + __shfl_xor(den_valu, 32);   // the other half-wave holds the token's other 32 features
+                } else {
+                    den = accz[1] + accz[0];
+                    den = __shfl(den, n);
+                }
                 const float inv = 1.0f / (den + eps);
 #pragma unroll
                 for (int rb = 0; rb < 2; ++rb) {
@@ -321,7 +362,9 @@ __host__ __device__ constexpr int apply_lds_bytes() { return WAVES * apply_wave_
 // wave fetching and converting all of S - is now done once per workgroup.
 // HILO = false drops the low half of S (one MFMA pass instead of two).
 // ROPE (kRopeNone/Table/3D); with kRope3D the dynamic LDS carries kRope3dLdsBytes more.
-template <bool HILO, int WAVES, int DEPTH, int ROPE>
+// S_LDS, DEN_VALU: the measurement variants of apply_tiles; S_LDS needs kApplyStateLdsBytes more dynamic LDS.
+constexpr int kApplyStateLdsBytes = 2 * 2 * 4 * 64 * 16;
+template <bool HILO, int WAVES, int DEPTH, int ROPE, bool S_LDS = false, bool DEN_VALU = false>
 __global__ __launch_bounds__(64 * WAVES, 1) void apply_mfma_d64(
     const uint16_t *__restrict__ Q, uint16_t *__restrict__ O, RopeArg rope, TokStrides st, int H,
     int /* d: always 64; keeps the argument list of the d = 112/128 kernel */, int t0, int t1, int C, const float *__restrict__ S, const float *__restrict__ z, float eps)
@@ -342,12 +385,16 @@ __global__ __launch_bounds__(64 * WAVES, 1) void apply_mfma_d64(
     apply_prefetch<0, DEPTH>(stream);   // in flight while S is fetched
     if (ROPE == kRope3D) {
         rope3d_lds_fill_end(lds + apply_lds_bytes<WAVES, ROPE>(), rope.r3, tabs);
-        __syncthreads();
+        wg_barrier();
     }
     ApplyOperands<64, HILO> A;
     static_assert(apply_lds_bytes<WAVES, ROPE>() >= 2 * 2 * 4 * 64 * 16 && WAVES == 4, "the tiles can stage S for load_shared");
-    A.template load_shared<false>(S + (size_t)bh * 64 * 64, z + (size_t)bh * 64, wave, lane, lds);   // through the tiles, not yet in use
-    apply_tiles<HILO>(stream, lds + wave * apply_wave_lds_bytes<ROPE>(), lane, A, eps);
+    // through the tiles, not yet in use; S_LDS: into an area of their own behind the tiles (and the tables), to stay
+    unsigned char *stage = S_LDS ? lds + apply_lds_bytes<WAVES, ROPE>() + (ROPE == kRope3D ? kRope3dLdsBytes : 0) : lds;
+    A.template load_shared<false>(S + (size_t)bh * 64 * 64, z + (size_t)bh * 64, wave, lane, stage);
+    float zf[4][8];
+    if (DEN_VALU) load_key_sums<false>(z + (size_t)bh * 64, lane, zf);
+    apply_tiles<HILO, DEPTH, ROPE, S_LDS, DEN_VALU>(stream, lds + wave * apply_wave_lds_bytes<ROPE>(), lane, A, eps, stage, zf);
 }
 
 }  // namespace sv

@@ -35,7 +35,7 @@ __host__ __device__ constexpr int block_step_lds_bytes() {
 // ROPE: keys and queries are rotated after the ReLU in the numerator path (table row = token of the block).
 // LOCAL: grid = (C * B*H) with B*H a multiple of n_dies; all workgroups of a head run on one die and
 // exchange their partial states and the new state through that die's L2 (see store_coherent).
-template <int TILE, int WAVES, int DEPTH_S, bool HILO, int DEPTH_A, int ROPE, bool LOCAL = false>
+template <int TILE, int WAVES, int DEPTH_S, bool HILO, int DEPTH_A, int ROPE, bool LOCAL = false, bool DEN_VALU = false>
 __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
     uint16_t *__restrict__ O, RopeArg rope, TokStrides st, int H, int N, int C,
@@ -96,7 +96,7 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
         state_prefetch(kvstream);
         if (ROPE == kRope3D) {
             rope3d_lds_fill_end(lds + block_step_lds_bytes<TILE, WAVES, ROPE>(), rope.r3, tabs);
-            __syncthreads();
+            wg_barrier();
         }
         state_accumulate(kvstream, tileK, tileK + kTileBytes, lane, acc);
         state_wg_reduce_store<WAVES, ROPE != kRopeNone, LOCAL>(acc, reinterpret_cast<float *>(lds), wave, lane,
@@ -116,7 +116,7 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
     if (wave == 0) state_slice_carry<kWave>(sl, Sc, zc, lane, carry);
     if (LOCAL) {
         coherent_stores_done();
-        __syncthreads();
+        wg_barrier();
         if (threadIdx.x == 0) flag_publish<true>(ws_flags(ws, BH, elems, bh, 0) + c, flag_with_die(epoch, my_die));
     } else {
         state_publish(ws, BH, elems, bh, c, 0, epoch);
@@ -142,7 +142,7 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
             __hip_atomic_store(ws_error(ws, BH, elems), kWsTimeoutMark, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (lane == 0) *agreed = ok;
     }
-    __syncthreads();
+    wg_barrier();
     // A wait that ran out (recorded in the workspace): nothing more is stored, neither this workgroup's
     // slice of S, z (if the first wait failed) nor any row of O_b.
     if (!*agreed) return;
@@ -151,8 +151,10 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
     ApplyOperands<64, HILO> A;
     static_assert(WAVES == 4 && block_step_lds_bytes<TILE, WAVES, ROPE>() >= 2 * 2 * 4 * 64 * 16, "LDS can stage S for load_shared");
     A.template load_shared<true>(Sh, zh, wave, lane, lds);   // through LDS that the state phase has left and the apply phase not yet taken
+    float zf[4][8];
+    if (DEN_VALU) load_key_sums<true>(zh, lane, zf);
     if (wave == 0) apply_prefetch<kEarly, DEPTH_A>(qstream);
-    apply_tiles<HILO>(qstream, lds + wave * apply_wave_lds_bytes<ROPE>(), lane, A, eps);
+    apply_tiles<HILO, DEPTH_A, ROPE, false, DEN_VALU>(qstream, lds + wave * apply_wave_lds_bytes<ROPE>(), lane, A, eps, nullptr, zf);
 }
 
 }  // namespace sv

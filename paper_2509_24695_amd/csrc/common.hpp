@@ -134,6 +134,18 @@ __device__ __forceinline__ void wave_lds_fence() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Workgroup barrier for handing LDS over between waves.  __syncthreads() alone does not do: the compiler
+// has been seen to move LDS reads that stand before it to behind it (two barriers in a row, the reads
+// after both), where another wave, already past the barrier, may have overwritten the memory.  The
+// assembly statement is opaque to the compiler (no memory operation crosses it in either direction) and
+// waits for this wave's LDS traffic, reads included, before the waves meet; the fences keep the meaning
+// that __syncthreads() has for global memory.
+__device__ __forceinline__ void wg_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
 // All LDS traffic of this wave is done, then all waves of the workgroup meet.
 // Global memory traffic is not waited for.
 __device__ __forceinline__ void lds_barrier() {

@@ -359,7 +359,7 @@ __global__ __launch_bounds__(256, 1) void state_mfma_d128(
     coop_state_prefetch(stream);
     if (ROPE == kRope3D) {
         rope3d_lds_fill_end(lds + state_d128_lds_bytes<ROPE>(), rope.r3, tabs);
-        __syncthreads();
+        wg_barrier();
     }
     state_accumulate_coop(stream, lds, wave, lane, wave & 1, wave >> 1, acc);
 
@@ -405,7 +405,7 @@ __global__ __launch_bounds__(64 * WAVES, NB == 1 ? 2 : 1) void apply_mfma_d128(
     coop_apply_prefetch<0, DEPTH>(stream);   // in flight while S is fetched
     if (ROPE == kRope3D) {
         rope3d_lds_fill_end(lds + coop_apply_lds_bytes<WAVES, NB>(), rope.r3, tabs);
-        __syncthreads();
+        wg_barrier();
     }
     ApplyOperands<128, HILO, NB, false> A;
     A.template load<false>(S + (size_t)bh * d * d, z + (size_t)bh * d, d, wave % (4 / NB), lane);

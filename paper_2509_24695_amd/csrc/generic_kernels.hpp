@@ -78,7 +78,7 @@ __global__ __launch_bounds__(kThreads) void state_partial_generic(
             sV[j][2 * p] = va;
             sV[j][2 * p + 1] = vb;
         }
-        __syncthreads();
+        wg_barrier();
         if (owner) {
 #pragma unroll 4
             for (int j = 0; j < TT; ++j) {
@@ -88,7 +88,7 @@ __global__ __launch_bounds__(kThreads) void state_partial_generic(
                 for (int e = 0; e < EPT; ++e) acc[e] = fmaf(a, sV[j][v0 + e], acc[e]);
             }
         }
-        __syncthreads();
+        wg_barrier();
     }
 
     if (!owner) return;
@@ -162,7 +162,7 @@ __global__ __launch_bounds__(kThreads) void apply_generic(
 
     for (int tile = tile_lo; tile < tile_hi; ++tile) {
         const int tok0 = t0 + tile * TT;
-        __syncthreads();
+        wg_barrier();
         for (int idx = tid; idx < TT * D / 2; idx += kThreads) {
             const int jj = idx / (D / 2), p = idx % (D / 2);
             const int tok = tok0 + jj;
@@ -184,7 +184,7 @@ __global__ __launch_bounds__(kThreads) void apply_generic(
             sQ[jj][2 * p] = a * c - b * s;
             sQ[jj][2 * p + 1] = a * s + b * c;
         }
-        __syncthreads();
+        wg_barrier();
         float num[VPT] = {0.f, 0.f, 0.f, 0.f};
         float den = 0.f;
         if (worker) {

@@ -128,7 +128,7 @@ struct EpochSource {
             const bool device = magic == kWsMagic && !(host & kHostEpochsOnly);
             *lds_word = device ? ((ticket / kTicketQuantum + 1) << 1) : host;
         }
-        __syncthreads();
+        wg_barrier();
         return *lds_word;
     }
 };
@@ -340,9 +340,9 @@ __device__ __forceinline__ void state_wg_reduce_store(StateAcc &acc, float *slot
                                                       float *__restrict__ out)
 {
     constexpr int THREADS = 64 * WAVES;
-    __syncthreads();                                   // all waves are done with their staging tiles
+    wg_barrier();                                   // all waves are done with their staging tiles
     state_acc_to_slot<ZVALU>(acc, slots + wave * kStateElems, lane);
-    __syncthreads();
+    wg_barrier();
     for (int v = threadIdx.x; v < kStateElems / 2; v += THREADS) {
         f32x2 x[WAVES];
 #pragma unroll
@@ -362,9 +362,9 @@ __device__ __forceinline__ void state_wg_reduce_store(StateAcc &acc, float *slot
 __device__ __forceinline__ void state_wg_quadrant_store(StateAcc &acc, float *slots, int wave, int lane, int d,
                                                         float *__restrict__ out)
 {
-    __syncthreads();                                   // all waves are done with their staging tiles
+    wg_barrier();                                   // all waves are done with their staging tiles
     state_acc_to_slot<false>(acc, slots + wave * kStateElems, lane);
-    __syncthreads();
+    wg_barrier();
     const int s_units = d * d / 2, units = s_units + d / 2;
     for (int u = threadIdx.x; u < units; u += 4 * kWave) {
         const float *src;
@@ -459,7 +459,7 @@ __device__ __forceinline__ void state_publish(void *ws, int BH, int elems, int b
                                               unsigned long long epoch)
 {
     coherent_stores_done();                             // this wave's stores are performed
-    __syncthreads();
+    wg_barrier();
     if (threadIdx.x == 0) flag_publish(ws_flags(ws, BH, elems, bh, phase) + c, epoch);
 }
 
@@ -530,7 +530,7 @@ __global__ __launch_bounds__(64 * WAVES, 1) void state_mfma_d64(
     state_prefetch(stream);
     if (ROPE == kRope3D) {
         rope3d_lds_fill_end(lds + state_lds_bytes<TILE, WAVES>(), rope.r3, tabs);
-        __syncthreads();
+        wg_barrier();
     }
     state_accumulate(stream, tileK, tileK + kTileBytes, lane, acc);
 

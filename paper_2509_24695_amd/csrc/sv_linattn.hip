@@ -1,6 +1,7 @@
 // C ABI of the gfx950 linear-attention library: argument checks, launch plans,
 // kernel dispatch.  See include/sv_linattn.h for the contract of each call.
 #include "../../include/sv_linattn.h"
+#include "../../include/sv_measure.h"
 
 #include <hip/hip_runtime.h>
 #include <math.h>
@@ -37,6 +38,11 @@ constexpr int kCoopStateDepth = 4;            // 32-token tiles of the shared-ti
 constexpr int kFusedStateDepth[3] = {2, 2, 2};   // one-launch block step (d = 64), by RoPE mode
 constexpr int kFusedApplyDepth[3] = {6, 2, 6};   // Q tiles held in registers across the in-kernel waits
 constexpr bool kApplyHiLo = true;
+// d = 64: the denominators phi(Q_i).z ride through the matrix core as two more operand rows (false) or are taken on
+// the vector ALU with a wavefront-level reduction (true).  Measured level (within 1 % either way at 32 760 and
+// 75 600 tokens; the one-launch block step 0.5-1 us per block slower with the vector ALU form), so they stay on
+// the matrix core; sv_measure_apply_variant runs both forms side by side.
+constexpr bool kDenValu = false;
 constexpr int kDies = 8, kCusPerDie = 32;      // MI355X: 8 accelerator dies (XCDs) of 32 compute units, one L2 each
 constexpr uint32_t kSpinLimit = 1u << 24;      // polls of ~100 ns: far beyond any real wait
 std::atomic<uint32_t> g_spin_limit{kSpinLimit};  // sv_linattn_set_wait_limit
@@ -66,11 +72,11 @@ template <int ROPE> struct Kernels<64, ROPE> {
     static constexpr int W = 0;
     static constexpr auto state = state_mfma_d64<kStateTile, kStateWaves, kStateDepth, true, ROPE>;
     static constexpr auto state_partial = state_mfma_d64<kStateTile, kStateWaves, kStateDepth, false, ROPE>;
-    static constexpr auto apply = apply_mfma_d64<kApplyHiLo, kApplyWaves, kApplyDepth, ROPE>;
+    static constexpr auto apply = apply_mfma_d64<kApplyHiLo, kApplyWaves, kApplyDepth, ROPE, false, kDenValu>;
     static constexpr auto fused = block_step_mfma<kStateTile, kStateWaves, kFusedStateDepth[ROPE], kApplyHiLo,
-                                                  kFusedApplyDepth[ROPE], ROPE>;
+                                                  kFusedApplyDepth[ROPE], ROPE, false, kDenValu>;
     static constexpr auto fused_local = block_step_mfma<kStateTile, kStateWaves, kFusedStateDepth[ROPE], kApplyHiLo,
-                                                        kFusedApplyDepth[ROPE], ROPE, true>;
+                                                        kFusedApplyDepth[ROPE], ROPE, true, kDenValu>;
     static constexpr int state_lds = state_lds_bytes<kStateTile, kStateWaves>() + kTab;
     static constexpr int apply_lds = apply_lds_bytes<kApplyWaves, ROPE>() + kTab;
     static constexpr int fused_lds = block_step_lds_bytes<kStateTile, kStateWaves, ROPE>() + kTab;
@@ -717,6 +723,43 @@ sv_status sv_block_linattn_lookahead_rope3d(const void *Qb, const void *Kb, cons
 {
     return do_block_step(Qb, Kb, Vb, blk, RopeSpec{kRope3D, nullptr, rope}, S, z, nullptr, nullptr, true, eps, Ob,
                          workspace, workspace_bytes_given, stream);
+}
+
+sv_status sv_measure_apply_variant(int32_t variant, const void *Q, const sv_tensor_desc *q, int32_t tok_begin,
+                                   int32_t tok_end, const float *S, const float *z, float eps, void *O, void *stream)
+{
+    if (!Q || !S || !z || !O) return SV_ERR_NULL;
+    if (variant < 0 || variant > 3) return SV_ERR_RANGE;
+    Shape s;
+    sv_status rc = check_desc(q, &s);
+    if (rc != SV_OK) return rc;
+    if ((rc = check_range(s, tok_begin, tok_end)) != SV_OK) return rc;
+    if (!eps_ok(eps)) return SV_ERR_RANGE;
+    if (!aligned16(Q) || !aligned16(O) || !aligned16(S) || !aligned16(z)) return SV_ERR_ALIGN;
+    Rope none;
+    if (s.d != 64 || !mfma_path(s, none)) return SV_ERR_UNSUPPORTED;
+    const int n = tok_end - tok_begin;
+    if (n == 0) return SV_OK;
+    const Device &dev = device_info();
+    if (!dev.ok) return SV_ERR_LAUNCH;
+    using KN = Kernels<64, kRopeNone>;
+    int C = KN::apply_wgs_per_cu * dev.num_cu / s.BH;          // the launch shape of sv_linattn_apply
+    const int steps = (n + KN::apply_wg_tokens - 1) / KN::apply_wg_tokens;
+    if (C > steps) C = steps;
+    if (C < 1) C = 1;
+    auto launch = [&](auto kernel, int lds) {
+        static_cast<void>(hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+        kernel<<<dim3(C, s.BH), KN::apply_threads, lds, static_cast<hipStream_t>(stream)>>>(
+            static_cast<const uint16_t *>(Q), static_cast<uint16_t *>(O), none.arg, s.st, s.H, s.d, tok_begin, tok_end, C, S, z, eps);
+    };
+    constexpr int lds0 = KN::apply_lds, lds1 = KN::apply_lds + kApplyStateLdsBytes;
+    switch (variant) {
+    case 0: launch(apply_mfma_d64<kApplyHiLo, kApplyWaves, kApplyDepth, kRopeNone, false, false>, lds0); break;
+    case 1: launch(apply_mfma_d64<kApplyHiLo, kApplyWaves, kApplyDepth, kRopeNone, true, false>, lds1); break;
+    case 2: launch(apply_mfma_d64<kApplyHiLo, kApplyWaves, kApplyDepth, kRopeNone, false, true>, lds0); break;
+    default: launch(apply_mfma_d64<kApplyHiLo, kApplyWaves, kApplyDepth, kRopeNone, true, true>, lds1); break;
+    }
+    return launch_status();
 }
 
 const char *sv_status_string(int status)

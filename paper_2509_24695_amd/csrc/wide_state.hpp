@@ -193,7 +193,7 @@ __device__ __forceinline__ void wide_state_wg_reduce_store(WideAcc &acc, unsigne
         x += __shfl_xor(x, 32);
         acc.z[e] = x;
     }
-    __syncthreads();                                   // all waves are done with their tiles
+    wg_barrier();                                   // all waves are done with their tiles
     if (lane < 16) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) zs[wave * 128 + lane * 8 + e] = acc.z[e];
@@ -266,7 +266,7 @@ __global__ __launch_bounds__(256, 1) void state_mfma_wide(
     wide_state_prefetch(stream);
     if (ROPE == kRope3D) {
         rope3d_lds_fill_end(lds + kWideTabOffset, rope.r3, tabs);
-        __syncthreads();
+        wg_barrier();
     }
     unsigned char *tileK = lds + wave * 2 * kWideTileBytes, *tileV = tileK + kWideTileBytes;
     wide_state_accumulate(stream, tileK, tileV, lane, acc);

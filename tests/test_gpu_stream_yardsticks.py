@@ -32,3 +32,39 @@ def test_stream_read_runs():
         sv.sv_stream_read(src, src.numel() * 4, sink, wgs)
     torch.cuda.synchronize()
     assert torch.equal(src, keep)
+
+
+@pytest.mark.parametrize("B,H,N", [(1, 2, 100), (2, 3, 4681), (1, 32, 4680)])
+def test_apply_variants_match_the_oracle_and_each_other(B, H, N):
+    """sv_measure_apply_variant: the four forms of the d = 64 apply kernel (S in registers or in LDS,
+    denominators through the matrix core or on the vector ALU) against the float64 oracle to the bf16
+    tolerances; variant 0 is the kernel sv_linattn_apply runs, bit for bit; a sub-range leaves other rows alone."""
+    import numpy as np
+    import torch
+    import sv_workloads as wl
+    from oracle import linattn_oracle as orc
+    from sv_workloads import metrics
+    from tests.gpu_util import gpu_bidirectional, say, to_dev, to_host
+    say(f"apply variants B={B} H={H} N={N}")
+    Q, K, V = wl.draw_tensors(9900 + N, (B, H, N, 64), 0.5, "bf16")
+    Qd = to_dev(Q)
+    O0, S, z = gpu_bidirectional(Qd, to_dev(K), to_dev(V), 1e-6)
+    O_ref, _, _ = orc.bidirectional(Q, K, V, 1e-6)
+    dsc = sv.desc_of(Qd)
+    outs = []
+    for variant in range(4):
+        O = torch.full_like(Qd, float("nan"))
+        sv.sv_measure_apply_variant(variant, Qd, dsc, 0, N, S, z, 1e-6, O)
+        torch.cuda.synchronize()
+        metrics.check(to_host(O), O_ref, "bf16", f"variant {variant}")
+        outs.append(O)
+    assert torch.equal(outs[0].view(torch.int16), O0.view(torch.int16))
+    assert torch.equal(outs[1].view(torch.int16), outs[0].view(torch.int16))      # same operands, read from LDS
+    assert torch.equal(outs[3].view(torch.int16), outs[2].view(torch.int16))
+    assert metrics.rel_l2(to_host(outs[2]), to_host(O0)) <= 2e-3                  # denominators summed in another order
+    if N > 50:
+        O = torch.full_like(Qd, 5.0)
+        sv.sv_measure_apply_variant(3, Qd, dsc, 17, N - 9, S, z, 1e-6, O)
+        torch.cuda.synchronize()
+        assert torch.equal(O[:, :, 17:N - 9].view(torch.int16), outs[3][:, :, 17:N - 9].view(torch.int16))
+        assert bool((O[:, :, :17] == 5.0).all()) and bool((O[:, :, N - 9:] == 5.0).all())

@@ -253,6 +253,19 @@ def test_stream_yardsticks_check_arguments():
     sv.sv_stream_copy(A, B, 0, 64)
 
 
+def test_apply_variant_checks_arguments():
+    d = _desc()
+    def status(variant=0, Q=FAKE, dsc=d, t0=0, t1=1, S=FAKE, eps=1e-6):
+        with pytest.raises(sv.SvError) as e:
+            sv.sv_measure_apply_variant(variant, Q, dsc, t0, t1, S, FAKE, eps, FAKE)
+        return e.value.status
+    assert status(Q=None) == 1 and status(S=None) == 1 and status(dsc=None) == 1
+    assert status(variant=4) == 5 and status(variant=-1) == 5 and status(t1=129) == 5 and status(eps=-1.0) == 5
+    assert status(dsc=_desc(d=48)) == 3 and status(dsc=_desc(d=32)) == 3 and status(dsc=_desc(dtype=sv.SV_F32)) == 3
+    assert status(dsc=_desc(d=128, stride_n=128, stride_h=128 * 128, stride_b=2 * 128 * 128)) == 3
+    assert status(Q=FAKE + 8) == 4
+
+
 def test_build_rejects_kernels_that_use_scratch_memory():
     """build() reads hipcc's per-kernel resource remarks and refuses a library in which a kernel keeps data in
     scratch memory (such a kernel passes every parity test and runs many times slower)."""
