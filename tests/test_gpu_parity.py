@@ -449,3 +449,90 @@ def test_lookahead_leaves_state_untouched(dtype, d, H):
     metrics.check(to_host(O_look), O_ref, dtype, "lookahead O")
     _, S1r, z1r = orc.block_step(Q1, K1, V1, S0r, z0r, 1e-6, commit=True)
     _check_state(S, z, S1r, z1r, "state after the committing pass")
+
+
+# ---- guard words: nothing outside the buffers a call is given may change -------------------------------
+
+def _guarded(nbytes, dtype, pattern=0xC3):
+    """A device buffer of `nbytes` with 4 KiB of a byte pattern in front of it and behind it.
+    Returns (whole allocation, view of the payload reinterpreted as `dtype`)."""
+    import torch
+    pad = 4096
+    whole = torch.full((pad + nbytes + pad,), pattern, dtype=torch.uint8, device="cuda")
+    return whole, whole[pad:pad + nbytes].view(dtype)
+
+
+def _guards_intact(whole, nbytes, pattern=0xC3):
+    pad = 4096
+    return bool((whole[:pad] == pattern).all()) and bool((whole[pad + nbytes:] == pattern).all())
+
+
+@pytest.mark.parametrize("dtype,d,H,N", [("bf16", 64, 32, 4681), ("bf16", 64, 3, 333), ("bf16", 112, 20, 4680),
+                                         ("bf16", 128, 5, 1000), ("f32", 32, 2, 1024), ("bf16", 32, 4, 777)])
+def test_nothing_is_written_outside_the_buffers(dtype, d, H, N):
+    """S, z, O and the workspace each sit between guard areas; after a state + apply pair, a committing step
+    and a look-ahead step (on ragged lengths: the kernels' last tiles reach past the token range and rely on
+    the buffer resources' range checks) every guard byte must be as it was, and the results must be right."""
+    import torch
+    B = 1
+    say(f"guard words dtype={dtype} d={d} H={H} N={N}")
+    Q, K, V = _draw(8100 + N, B, H, N, d, dtype)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    esz = 2 if dtype == "bf16" else 4
+    tok_bytes = B * H * N * d * esz
+    bufs = {}
+    for name, src in (("Q", Q), ("K", K), ("V", V)):
+        whole, view = _guarded(tok_bytes, tdt)
+        view.view(B, H, N, d).copy_(to_dev(src))
+        bufs[name] = (whole, view.view(B, H, N, d))
+    O_w, O = _guarded(tok_bytes, tdt)
+    O = O.view(B, H, N, d)
+    S_w, S = _guarded(B * H * d * d * 4, torch.float32)
+    z_w, z = _guarded(B * H * d * 4, torch.float32)
+    ws_bytes = sv.sv_linattn_workspace_bytes(B, H, N, d)
+    ws_w, ws = _guarded(ws_bytes, torch.uint8)
+    S, z = S.view(B, H, d, d), z.view(B, H, d)
+    Qd, Kd, Vd = bufs["Q"][1], bufs["K"][1], bufs["V"][1]
+    dsc = sv.desc_of(Qd)
+    sv.sv_linattn_state(Kd, Vd, dsc, 0, N, 0, S, z, ws, workspace_bytes=ws_bytes)
+    sv.sv_linattn_apply(Qd, dsc, 0, N, S, z, 1e-6, O)
+    torch.cuda.synchronize()
+    O_ref, S_ref, z_ref = orc.bidirectional(Q, K, V, 1e-6)
+    _check_state(S, z, S_ref, z_ref, "guarded state")
+    metrics.check(to_host(O), O_ref, dtype, "guarded O")
+    sv.sv_block_linattn_lookahead(Qd, Kd, Vd, dsc, S, z, 1e-6, O, ws, workspace_bytes=ws_bytes)
+    sv.sv_block_linattn_step(Qd, Kd, Vd, dsc, S, z, 1e-6, O, ws, workspace_bytes=ws_bytes)
+    torch.cuda.synchronize()
+    O2_ref, S2_ref, z2_ref = orc.block_step(Q, K, V, S_ref, z_ref, 1e-6)
+    _check_state(S, z, S2_ref, z2_ref, "guarded state after the step")
+    metrics.check(to_host(O), O2_ref, dtype, "guarded O of the step")
+    for name, (whole, _) in bufs.items():
+        assert _guards_intact(whole, tok_bytes), f"guard of {name} changed"
+    assert _guards_intact(O_w, tok_bytes), "a kernel wrote outside O"
+    assert _guards_intact(S_w, B * H * d * d * 4), "a kernel wrote outside S"
+    assert _guards_intact(z_w, B * H * d * 4), "a kernel wrote outside z"
+    assert _guards_intact(ws_w, ws_bytes), "a kernel wrote outside the workspace"
+
+
+def test_long_stream_resumes_bit_identically():
+    """80 blocks with the state carried; the stream is cut after every 16th block (state copied to the host,
+    device buffers freed, a fresh workspace) and must continue bit for bit like the uncut run."""
+    import torch
+    B, H, d, N, n_blocks = 1, 8, 64, 300, 80
+    say("long stream resume")
+    blocks = [_draw(8200 + i, B, H, N, d, "bf16") for i in range(n_blocks)]
+    outs1, S1, z1 = _gpu_stream(blocks, 1e-6, B, H, d)
+    S, z = new_state(B, H, d)
+    ws = new_workspace(B, H, N, d)
+    for i, blk in enumerate(blocks):
+        if i and i % 16 == 0:
+            Sh, zh = S.cpu(), z.cpu()
+            del S, z, ws
+            torch.cuda.empty_cache()
+            S, z, ws = Sh.cuda(), zh.cuda(), new_workspace(B, H, N, d)
+        Qd, Kd, Vd = (to_dev(t) for t in blk)
+        O = torch.empty_like(Qd)
+        sv.sv_block_linattn_step(Qd, Kd, Vd, sv.desc_of(Qd), S, z, 1e-6, O, ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_host(O), outs1[i]), f"block {i}"
+    assert torch.equal(S, S1) and torch.equal(z, z1)

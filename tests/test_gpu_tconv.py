@@ -101,23 +101,23 @@ def test_repeatable_bits():
 
 
 @pytest.mark.parametrize("name", ["tconv_480p", "tconv_block_480p"])
-def test_full_size_sampled_rows(name):
-    """The benchmark's shapes in the benchmark's launch configuration; the oracle computes sampled
-    token rows one by one (all channels of each), among them the rows at every kind of boundary."""
+def test_full_size(name):
+    """The benchmark's shapes in the benchmark's launch configuration, every element of y against the oracle
+    (for the block workload: every block of the stream, the cache carried on the device), y pre-filled with
+    NaN; the new cache must be the block's last input frame bit for bit."""
+    import torch
     w = TCONV_WORKLOADS[name]
     xb, Wb = draw_tconv(w)
     Wd = to_dev(Wb)
-    rng = np.random.Generator(np.random.PCG64(w.seed + 1))
-    first = w.n_blocks - 1 if w.n_blocks > 1 else 0        # for streams: the last block, with a real cache
-    blk = np.ascontiguousarray(xb[:, first * w.T:(first + 1) * w.T])
-    cache = np.ascontiguousarray(xb[:, first * w.T - 1]) if first > 0 else None
-    say(f"tconv full size {name}: B={w.B} T={w.T} HW={w.HW} D={w.D} cache={'yes' if cache is not None else 'no'}")
-    y, cache_new = _run_block(to_dev(blk), Wd, None if cache is None else to_dev(cache), w.B, w.T, w.HW, w.D)
-    rows = [(0, 0, 0), (0, 0, w.HW - 1), (0, w.T - 1, 0), (w.B - 1, w.T - 1, w.HW - 1), (0, w.T // 2, 255), (0, w.T // 2, 256)]
-    rows += [(int(rng.integers(w.B)), int(rng.integers(w.T)), int(rng.integers(w.HW))) for _ in range(150)]
-    ref = orc.tconv_rows(blk, Wb, cache, rows)
-    yh = to_host(y).astype(np.float64)
-    got = np.stack([yh[b, t, p] for b, t, p in rows])
-    _check(got, ref, name)
-    assert np.isfinite(yh).all()
-    assert np.array_equal(to_host(cache_new), to_host(to_dev(np.ascontiguousarray(blk[:, -1]))))
+    say(f"tconv full size {name}: B={w.B} T={w.T} HW={w.HW} D={w.D}, {w.n_blocks} block(s)")
+    cache_d, cache_ref = None, None
+    for m in range(max(1, w.n_blocks)):
+        blk = np.ascontiguousarray(xb[:, m * w.T:(m + 1) * w.T])
+        y = torch.full((w.B, w.T, w.HW, w.D), float("nan"), dtype=torch.bfloat16, device="cuda")
+        new_cache = torch.empty((w.B, w.HW, w.D), dtype=torch.bfloat16, device="cuda")
+        sv.sv_tconv_block_step(to_dev(blk), Wd, cache_d, y, new_cache, w.B, w.T, w.HW, w.D)
+        torch.cuda.synchronize()
+        y_ref, cache_ref = orc.tconv_block(blk, Wb, cache_ref)
+        _check(to_host(y).astype(np.float64), y_ref, f"{name} block {m}")
+        assert np.array_equal(to_host(new_cache).astype(np.float64), cache_ref)
+        cache_d = new_cache
