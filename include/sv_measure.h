@@ -51,6 +51,15 @@ sv_status sv_measure_apply_variant(int32_t variant, const void *Q, const sv_tens
                                    int32_t tok_begin, int32_t tok_end,
                                    const float *S, const float *z, float eps, void *O, void *stream);
 
+/* For tests of a safety net, no passage of the paper.  On the 8-die part the one-launch block step places all
+ * workgroups of a head on one die (workgroup ids go round the dies) and lets them exchange their partial states
+ * through that die's L2; every workgroup publishes the die it really runs on, and a head found on more than one
+ * die stores nothing and sets the workspace's timeout mark (sv_linattn_workspace_status).  This call makes all
+ * later block steps of the process place heads as if the device had `dies` dies (1, 2 or 4: heads then do end up
+ * on several dies, so every such step must give up and report; any other value restores the real count).  The
+ * kernels run to their end either way. */
+void sv_measure_assume_dies(int32_t dies);
+
 #ifdef __cplusplus
 }
 #endif

@@ -47,6 +47,7 @@ constexpr int kDies = 8, kCusPerDie = 32;      // MI355X: 8 accelerator dies (XC
 constexpr uint32_t kSpinLimit = 1u << 24;      // polls of ~100 ns: far beyond any real wait
 std::atomic<uint32_t> g_spin_limit{kSpinLimit};  // sv_linattn_set_wait_limit
 uint32_t spin_limit() { return g_spin_limit.load(std::memory_order_relaxed); }
+std::atomic<int> g_assumed_dies{kDies};          // sv_measure_assume_dies
 
 struct Shape {
     int B, H, N, d, BH;
@@ -513,11 +514,12 @@ sv_status do_block_step(const void *Qb, const void *Kb, const void *Vb, const sv
             // that ran out); devices other than the 8 x 32 compute-unit part keep the general form.
             // A full rotation table stays with the general form: there die c reads chunk c of every head, so each
             // table row reaches one L2 only; with whole heads on a die all eight would fetch every row.
-            if (dev.num_cu == kDies * kCusPerDie && s.BH % kDies == 0 && rope.mode != kRopeTable)
+            const int dies = g_assumed_dies.load(std::memory_order_relaxed);
+            if (dev.num_cu == kDies * kCusPerDie && s.BH % dies == 0 && rope.mode != kRopeTable)
                 KN::fused_local<<<dim3(C * s.BH), 64 * kStateWaves, KN::fused_lds, hs>>>(
                     static_cast<const uint16_t *>(Qb), static_cast<const uint16_t *>(Kb),
                     static_cast<const uint16_t *>(Vb), static_cast<uint16_t *>(Ob), rope.arg, s.st, s.H, s.N, C, S_in,
-                    z_in, S_out, z_out, eps, workspace, next_epoch(s.host_epochs_only), spin_limit(), s.BH, kDies);
+                    z_in, S_out, z_out, eps, workspace, next_epoch(s.host_epochs_only), spin_limit(), s.BH, dies);
             else
                 KN::fused<<<dim3(C, s.BH), 64 * kStateWaves, KN::fused_lds, hs>>>(
                     static_cast<const uint16_t *>(Qb), static_cast<const uint16_t *>(Kb),
@@ -723,6 +725,11 @@ sv_status sv_block_linattn_lookahead_rope3d(const void *Qb, const void *Kb, cons
 {
     return do_block_step(Qb, Kb, Vb, blk, RopeSpec{kRope3D, nullptr, rope}, S, z, nullptr, nullptr, true, eps, Ob,
                          workspace, workspace_bytes_given, stream);
+}
+
+void sv_measure_assume_dies(int32_t dies)
+{
+    g_assumed_dies.store(dies == 1 || dies == 2 || dies == 4 ? dies : kDies, std::memory_order_relaxed);
 }
 
 sv_status sv_measure_apply_variant(int32_t variant, const void *Q, const sv_tensor_desc *q, int32_t tok_begin,

@@ -392,6 +392,42 @@ def test_timed_out_wait_stores_nothing_and_is_reported(H, d):
     metrics.check(to_host(O), O_ref, "bf16", "O after the timeout")
 
 
+def test_head_spread_over_dies_gives_up_and_is_reported():
+    """The die-local block step checks where its workgroups really run.  Told to place heads as if the device
+    had four dies, every head ends up on two: the step must store nothing (S, z, O as they were), set the
+    mark that the status query reads, and work again once the real die count is back."""
+    import torch
+    B, H, N, d = 1, 32, 4680, 64
+    say("head spread over dies")
+    Q, K, V = _draw(7980, B, H, N, d, "bf16")
+    Qd, Kd, Vd = to_dev(Q), to_dev(K), to_dev(V)
+    dsc = sv.desc_of(Qd)
+    ws = new_workspace(B, H, N, d)
+    sv.sv_linattn_workspace_init(ws, B, H, d)
+    S, z = new_state(B, H, d)
+    S.fill_(3.0)
+    z.fill_(5.0)
+    O = torch.full_like(Qd, float("nan"))
+    try:
+        sv.sv_measure_assume_dies(4)
+        sv.sv_block_linattn_step(Qd, Kd, Vd, dsc, S, z, 1e-6, O, ws)
+        torch.cuda.synchronize()
+    finally:
+        sv.sv_measure_assume_dies(8)
+    if sv.sv_linattn_workspace_status(ws, B, H, d) == 0:
+        pytest.skip("this device did not take the die-local form (not the 8 x 32 compute-unit part)")
+    assert bool((S == 3.0).all()) and bool((z == 5.0).all()) and bool(torch.isnan(O.float()).all())
+    sv.sv_linattn_workspace_init(ws, B, H, d)
+    S.zero_()
+    z.zero_()
+    sv.sv_block_linattn_step(Qd, Kd, Vd, dsc, S, z, 1e-6, O, ws)
+    torch.cuda.synchronize()
+    assert sv.sv_linattn_workspace_status(ws, B, H, d) == 0
+    O_ref, S_ref, z_ref = orc.bidirectional(Q, K, V, 1e-6)
+    _check_state(S, z, S_ref, z_ref, "after the refused step")
+    metrics.check(to_host(O), O_ref, "bf16", "O after the refused step")
+
+
 @pytest.mark.parametrize("H,d", [(32, 64), (20, 112)])
 def test_workspace_reinitialised_between_uses(H, d):
     """Device-side epochs restart when a workspace is initialised again, so a flag left by the single
