@@ -396,11 +396,38 @@ def bench_tconv(w, iters, sv, torch):
     torch.cuda.synchronize()
     us = a.elapsed_time(b) * 1e3 / (iters * w.n_blocks)
     tflops = w.algorithmic_flops / us / 1e6
+
+    # The same matrix-core instruction stream with nothing around it (sv_mfma_stream): as many workgroups as the
+    # convolution has 256 x 256 tiles, each with the tile's K-steps; and 8 workgroups alone, for the clock an
+    # almost idle device gives the same stream.
+    tiles = -(-(w.B * w.T * w.HW) // 256) * -(-w.D // 256)
+    k_steps = -(-3 * w.D // 32)
+    sink = torch.zeros(4, dtype=torch.float32, device="cuda")
+
+    def stream_us(wgs):
+        sv.sv_mfma_stream(wgs, k_steps, sink, stream=stream)
+        torch.cuda.synchronize()
+        a.record(stream)
+        for _ in range(iters):
+            sv.sv_mfma_stream(wgs, k_steps, sink, stream=stream)
+        b.record(stream)
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e3 / iters
+
+    full_us, few_us = stream_us(tiles), stream_us(8)
+    wg_flops = k_steps * 4 * 32 * 2 * 32 * 32 * 16
     return {"workload": f"{w.name}: B={w.B} T={w.T} HW={w.HW} D={w.D}, {w.n_blocks} block(s)", "us_per_block": us,
             "tokens_per_s": w.tokens / (us * 1e-6), "dtype": "bf16",
             "roofline": {"bound": "mfma", "kernel": "tconv_mfma", "achieved": tflops, "peak": MFMA_BF16_PEAK_TFLOPS,
                          "unit": "TFLOP/s", "frac": tflops / MFMA_BF16_PEAK_TFLOPS,
-                         "algorithmic_flops_per_launch": w.algorithmic_flops}}
+                         "algorithmic_flops_per_launch": w.algorithmic_flops},
+            "mfma_stream": {"what": "the tile loop's MFMAs alone, operands in registers, no LDS or memory traffic "
+                                    "(sv_mfma_stream): one workgroup per tile, and 8 workgroups on an otherwise idle device",
+                            "tiles": tiles, "k_steps": k_steps, "us": full_us,
+                            "TFLOPs": tiles * wg_flops / full_us / 1e6,
+                            "us_8_workgroups": few_us,
+                            "us_per_tile_on_a_full_device": full_us / -(-tiles // 256), "us_per_tile_on_an_idle_device": few_us},
+            "frac_of_mfma_stream": full_us / us}
 
 
 def bench_apply_variants(w, sets, steps, sv, torch):

@@ -1,12 +1,13 @@
 /*
- * sv_measure.h - streaming yardsticks (MI355X, gfx950; part of libsvlinattn.so).
+ * sv_measure.h - yardsticks (MI355X, gfx950; part of libsvlinattn.so).
  *
  * Not part of the method of the paper: two kernels that do nothing but move
  * bytes, for callers that want to know what this device gives a pure stream of
  * a given size - the ceiling the attention kernels (all of them bound by memory
- * traffic) are measured against beside the published peak.
+ * traffic) are measured against beside the published peak - and one that does
+ * nothing but issue matrix-core instructions (sv_mfma_stream, below).
  *
- * Both take device pointers, work on `stream` (hipStream_t passed as void*,
+ * The two streaming calls take device pointers, work on `stream` (hipStream_t passed as void*,
  * NULL = default stream), return after enqueueing, allocate nothing and keep
  * nothing.  `wgs` workgroups of 256 threads each walk a contiguous share of the
  * buffer with 16-byte accesses, eight in flight per thread.
@@ -32,6 +33,16 @@ sv_status sv_stream_read(const void *src, size_t bytes, void *sink, int32_t wgs,
 
 /* dst[0, bytes) = src[0, bytes). */
 sv_status sv_stream_copy(const void *src, void *dst, size_t bytes, int32_t wgs, void *stream);
+
+/* The matrix-core instruction stream of the temporal convolution (sv_tconv.h) with everything else taken
+ * away: `wgs` workgroups of four waves, each wave issuing 32 * steps v_mfma_f32_32x32x16_bf16 on a 4 x 4 grid
+ * of accumulators from operands that stay in registers (one 256 x 256 output tile of the convolution is
+ * steps = 3 * D / 32; a workgroup does steps * 4 194 304 flop).  What this device gives that stream at a given
+ * number of busy compute units is the ceiling of any kernel built on it.  `sink` is 4 bytes of device memory,
+ * 4-byte aligned, that the kernel may write (for one value of its sums; the store keeps the products alive).
+ * Enqueues on `stream` and returns; allocates nothing.  SV_ERR_NULL / SV_ERR_ALIGN for sink, SV_ERR_SHAPE if
+ * wgs is outside [1, 1048576] or steps outside [0, 1048576]; steps == 0 launches nothing. */
+sv_status sv_mfma_stream(int32_t wgs, int32_t steps, void *sink, void *stream);
 
 /* sv_linattn_apply for bf16 tokens and d = 64 in four forms of its kernel, for A/B measurements of two
  * design choices (same arguments, checks, launch shape and results to rounding as sv_linattn_apply; no

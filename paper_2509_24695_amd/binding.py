@@ -22,7 +22,7 @@ EXPORTS = (
     "sv_block_linattn_lookahead_rope3d", "sv_tconv_block_step", "sv_stream_read", "sv_stream_copy",
     "sv_linattn_workspace_status_offset", "sv_linattn_workspace_status", "sv_linattn_set_wait_limit",
     "sv_block_linattn_step_static", "sv_measure_apply_variant",
-    "sv_measure_assume_dies",
+    "sv_measure_assume_dies", "sv_mfma_stream",
 )
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
@@ -112,6 +112,8 @@ def load_library():
     lib.sv_measure_apply_variant.restype = ctypes.c_int
     lib.sv_measure_assume_dies.argtypes = [i32]
     lib.sv_measure_assume_dies.restype = None
+    lib.sv_mfma_stream.argtypes = [i32, i32, vp, vp]
+    lib.sv_mfma_stream.restype = ctypes.c_int
     lib.sv_stream_read.argtypes = [vp, sz, vp, i32, vp]
     lib.sv_stream_read.restype = ctypes.c_int
     lib.sv_stream_copy.argtypes = [vp, vp, sz, i32, vp]
@@ -379,6 +381,11 @@ def sv_measure_apply_variant(variant: int, Q, q: TensorDesc, tok_begin: int, tok
 def sv_measure_assume_dies(dies: int) -> None:
     """Test hook (include/sv_measure.h): place heads as if the device had `dies` dies; 8 or 0 restores."""
     load_library().sv_measure_assume_dies(int(dies))
+
+
+def sv_mfma_stream(wgs: int, steps: int, sink, stream=None) -> None:
+    """Matrix-core yardstick (include/sv_measure.h): wgs workgroups x 4 waves x 32*steps bf16 MFMAs, no memory traffic."""
+    _check(load_library().sv_mfma_stream(int(wgs), int(steps), _ptr(sink), _stream(stream)), "sv_mfma_stream")
 
 
 def sv_stream_read(src, nbytes: int, sink, wgs: int, stream=None) -> None:

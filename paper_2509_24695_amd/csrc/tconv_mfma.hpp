@@ -188,16 +188,28 @@ __global__ __launch_bounds__(kThreads) void tconv_mfma(TconvArgs a)
             __builtin_amdgcn_sched_barrier(0);
         }
     }
-    // the repeated loads of the last steps must not land on the epilogue's staging
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-
     // ---- epilogue: y = bf16(x + acc), 32 token rows of the wave's quadrant at a time through LDS ----
-    // (nobody reads the operand ring any more; each wave uses its own region)
+    // (nobody reads the operand ring any more; each wave uses its own region).  The shortcut's x rows
+    // are requested one 32-row group ahead, so their latency is paid once per tile, not once per row.
     unsigned char *epi = lds + wave * (32 * kTcEpiPitch);
     const int er = lane >> 4, ec = lane & 15;                 // reader: row in a group of four, 8-channel chunk
     const int n = n0 + wn * 128 + ec * 8;
+    const bool col_ok = n < D;
+    const int n_ld = col_ok ? n : 0;                          // lanes past the last channel load a valid address
+    u32x4 xin[2][8];
+    auto load_x = [&](int buf, int i) {
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+            const int64_t g = (int64_t)m0 + wm * 128 + i * 32 + it * 4 + er;
+            xin[buf][it] = *reinterpret_cast<const u32x4 *>(a.x + (g < M ? g : (int64_t)M - 1) * D + n_ld);
+        }
+    };
+    load_x(0, 0);
+    // the repeated loads of the last steps must not land on the epilogue's staging
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
+        if (i + 1 < 4) load_x((i + 1) & 1, i + 1);
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -212,13 +224,13 @@ __global__ __launch_bounds__(kThreads) void tconv_mfma(TconvArgs a)
             const int64_t g = (int64_t)m0 + wm * 128 + i * 32 + row;
             const f32x4 lo = *reinterpret_cast<const f32x4 *>(epi + row * kTcEpiPitch + ec * 32);
             const f32x4 hi = *reinterpret_cast<const f32x4 *>(epi + row * kTcEpiPitch + ec * 32 + 16);
-            if (g < M && n < D) {
-                const u32x4 xin = *reinterpret_cast<const u32x4 *>(a.x + g * D + n);
+            if (g < M && col_ok) {
+                const u32x4 x4 = xin[i & 1][it];
                 u32x4 out;
-                out.x = pack_bf16x2(bf16_lo(xin.x) + lo.x, bf16_hi(xin.x) + lo.y);
-                out.y = pack_bf16x2(bf16_lo(xin.y) + lo.z, bf16_hi(xin.y) + lo.w);
-                out.z = pack_bf16x2(bf16_lo(xin.z) + hi.x, bf16_hi(xin.z) + hi.y);
-                out.w = pack_bf16x2(bf16_lo(xin.w) + hi.z, bf16_hi(xin.w) + hi.w);
+                out.x = pack_bf16x2(bf16_lo(x4.x) + lo.x, bf16_hi(x4.x) + lo.y);
+                out.y = pack_bf16x2(bf16_lo(x4.y) + lo.z, bf16_hi(x4.y) + lo.w);
+                out.z = pack_bf16x2(bf16_lo(x4.z) + hi.x, bf16_hi(x4.z) + hi.y);
+                out.w = pack_bf16x2(bf16_lo(x4.w) + hi.z, bf16_hi(x4.w) + hi.w);
                 *reinterpret_cast<u32x4 *>(a.y + g * D + n) = out;
             }
         }

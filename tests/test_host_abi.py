@@ -251,6 +251,10 @@ def test_stream_yardsticks_check_arguments():
     assert status(sv.sv_stream_copy, A, A + 512, 1024, 64) == 2          # overlapping buffers
     sv.sv_stream_read(A, 0, B, 64)                                        # nothing to do: no launch, no error
     sv.sv_stream_copy(A, B, 0, 64)
+    assert status(sv.sv_mfma_stream, 8, 10, None) == 1 and status(sv.sv_mfma_stream, 8, 10, A + 2) == 4
+    assert status(sv.sv_mfma_stream, 0, 10, A) == 2 and status(sv.sv_mfma_stream, 8, -1, A) == 2
+    assert status(sv.sv_mfma_stream, (1 << 20) + 1, 10, A) == 2 and status(sv.sv_mfma_stream, 8, (1 << 20) + 1, A) == 2
+    sv.sv_mfma_stream(8, 0, A)
 
 
 def test_apply_variant_checks_arguments():
