@@ -1,5 +1,6 @@
-"""The streaming yardsticks of include/sv_measure.h: the copy moves every byte (whole unrolled
-rounds, a ragged tail, more workgroups than vectors), the read runs and leaves its input alone."""
+"""The yardsticks of include/sv_measure.h: the copy moves every byte (whole unrolled rounds, a
+ragged tail, more workgroups than vectors), the read runs and leaves its input alone, the
+matrix-core stream runs, scales with its step count and writes nothing."""
 import pytest
 
 import paper_2509_24695_amd as sv
@@ -32,6 +33,31 @@ def test_stream_read_runs():
         sv.sv_stream_read(src, src.numel() * 4, sink, wgs)
     torch.cuda.synchronize()
     assert torch.equal(src, keep)
+
+
+def test_mfma_stream_runs_and_scales():
+    import torch
+    sink = torch.full((4,), 7.0, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def us(wgs, steps):
+        sv.sv_mfma_stream(wgs, steps, sink)
+        torch.cuda.synchronize()
+        a.record(stream)
+        for _ in range(5):
+            sv.sv_mfma_stream(wgs, steps, sink)
+        b.record(stream)
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e3 / 5
+
+    short, long = us(8, 210), us(8, 840)
+    assert bool((sink == 7.0).all())                     # the guarded store practically never happens
+    # 32 MFMAs of 32x32x16 per wave and step: a step cannot take less than 32 * 8 passes * 4 cycles at 2.4 GHz
+    assert short >= 210 * 32 * 32 / 2400.0 * 0.95, short
+    assert 3.0 < long / short < 4.5, (short, long)       # four times the steps: about four times the time
+    sv.sv_mfma_stream(1152, 1, sink)                     # many workgroups, one step
+    torch.cuda.synchronize()
 
 
 @pytest.mark.parametrize("B,H,N", [(1, 2, 100), (2, 3, 4681), (1, 32, 4680)])
