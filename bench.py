@@ -421,6 +421,23 @@ def bench_tconv(w, iters, sv, torch):
         return a.elapsed_time(b) * 1e3 / iters
 
     full_us, few_us = stream_us(tiles), stream_us(8)
+
+    # The tile kernel with parts of its loop left out (sv_measure_tconv_variant), on the stream's first block:
+    # what the loads into LDS and the operand reads from LDS cost on top of the matrix-core instructions.
+    def variant_us(variant):
+        for _ in range(2):
+            sv.sv_measure_tconv_variant(variant, xs[0], W, None, ys[0], w.B, w.T, w.HW, w.D, stream=stream)
+        a.record(stream)
+        for _ in range(iters):
+            sv.sv_measure_tconv_variant(variant, xs[0], W, None, ys[0], w.B, w.T, w.HW, w.D, stream=stream)
+        b.record(stream)
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e3 / iters
+
+    loop_variants = None
+    if w.D % 32 == 0:
+        names = ["library kernel", "without the loads into LDS", "without the operand reads from LDS", "without both"]
+        loop_variants = {names[v]: variant_us(v) for v in (0, 1, 2, 3, 0)}     # the library's kernel again at the end
     wg_flops = k_steps * 4 * 32 * 2 * 32 * 32 * 16
     return {"workload": f"{w.name}: B={w.B} T={w.T} HW={w.HW} D={w.D}, {w.n_blocks} block(s)", "us_per_block": us,
             "tokens_per_s": w.tokens / (us * 1e-6), "dtype": "bf16",
@@ -433,7 +450,8 @@ def bench_tconv(w, iters, sv, torch):
                             "TFLOPs": tiles * wg_flops / full_us / 1e6,
                             "us_8_workgroups": few_us,
                             "us_per_tile_on_a_full_device": full_us / -(-tiles // 256), "us_per_tile_on_an_idle_device": few_us},
-            "frac_of_mfma_stream": full_us / us}
+            "frac_of_mfma_stream": full_us / us,
+            "loop_variants_us": loop_variants}
 
 
 def bench_apply_variants(w, sets, steps, sv, torch):

@@ -62,6 +62,19 @@ sv_status sv_measure_apply_variant(int32_t variant, const void *Q, const sv_tens
                                    int32_t tok_begin, int32_t tok_end,
                                    const float *S, const float *z, float eps, void *O, void *stream);
 
+/* The tile kernel of sv_tconv_block_step (sv_tconv.h; same arguments without cache_out and dtype, same checks,
+ * same grid, bf16 only) with parts of its loop left out, to time what each part costs (no passage of the paper):
+ *   variant 0  the kernel sv_tconv_block_step launches;
+ *   variant 1  without the loads from memory into LDS inside the tile loop (the prologue's stay);
+ *   variant 2  without the operand reads from LDS inside the tile loop;
+ *   variant 3  without both: the matrix-core instructions, the barriers, prologue and epilogue.
+ * Variants 1-3 read the same memory and write every element of y, but what they write is not the convolution
+ * (finite values for finite inputs).  SV_ERR_RANGE for another variant, SV_ERR_UNSUPPORTED for variants 1-3
+ * unless D is a multiple of 32; otherwise the errors of sv_tconv_block_step.  The first call of a variant on a
+ * device sets a kernel attribute: not under graph capture. */
+sv_status sv_measure_tconv_variant(int32_t variant, const void *x, const void *W, const void *cache_in, void *y,
+                                   int32_t B, int32_t T, int32_t HW, int32_t D, void *stream);
+
 /* For tests of a safety net, no passage of the paper.  On the 8-die part the one-launch block step places all
  * workgroups of a head on one die (workgroup ids go round the dies) and lets them exchange their partial states
  * through that die's L2; every workgroup publishes the die it really runs on, and a head found on more than one

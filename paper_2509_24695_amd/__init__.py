@@ -12,5 +12,5 @@ from .binding import (  # noqa: F401
     Rope3D, sv_linattn_state_rope3d, sv_linattn_apply_rope3d, sv_block_linattn_step_rope3d,
     sv_block_linattn_lookahead_rope3d, sv_tconv_block_step, sv_stream_read, sv_stream_copy,
     sv_linattn_workspace_status, sv_linattn_workspace_status_offset, sv_linattn_set_wait_limit, sv_block_linattn_step_static, sv_measure_apply_variant, sv_measure_assume_dies,
-    sv_mfma_stream,
+    sv_mfma_stream, sv_measure_tconv_variant,
 )

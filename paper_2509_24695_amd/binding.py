@@ -22,7 +22,7 @@ EXPORTS = (
     "sv_block_linattn_lookahead_rope3d", "sv_tconv_block_step", "sv_stream_read", "sv_stream_copy",
     "sv_linattn_workspace_status_offset", "sv_linattn_workspace_status", "sv_linattn_set_wait_limit",
     "sv_block_linattn_step_static", "sv_measure_apply_variant",
-    "sv_measure_assume_dies", "sv_mfma_stream",
+    "sv_measure_assume_dies", "sv_mfma_stream", "sv_measure_tconv_variant",
 )
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
@@ -113,6 +113,8 @@ def load_library():
     lib.sv_measure_assume_dies.argtypes = [i32]
     lib.sv_measure_assume_dies.restype = None
     lib.sv_mfma_stream.argtypes = [i32, i32, vp, vp]
+    lib.sv_measure_tconv_variant.argtypes = [i32, vp, vp, vp, vp, i32, i32, i32, i32, vp]
+    lib.sv_measure_tconv_variant.restype = ctypes.c_int
     lib.sv_mfma_stream.restype = ctypes.c_int
     lib.sv_stream_read.argtypes = [vp, sz, vp, i32, vp]
     lib.sv_stream_read.restype = ctypes.c_int
@@ -381,6 +383,12 @@ def sv_measure_apply_variant(variant: int, Q, q: TensorDesc, tok_begin: int, tok
 def sv_measure_assume_dies(dies: int) -> None:
     """Test hook (include/sv_measure.h): place heads as if the device had `dies` dies; 8 or 0 restores."""
     load_library().sv_measure_assume_dies(int(dies))
+
+
+def sv_measure_tconv_variant(variant: int, x, W, cache_in, y, B: int, T: int, HW: int, D: int, stream=None) -> None:
+    """Measurement variants of the temporal-convolution kernel (include/sv_measure.h); 0 is the library's kernel."""
+    _check(load_library().sv_measure_tconv_variant(int(variant), _ptr(x), _ptr(W), _ptr(cache_in), _ptr(y), int(B), int(T),
+                                                   int(HW), int(D), _stream(stream)), "sv_measure_tconv_variant")
 
 
 def sv_mfma_stream(wgs: int, steps: int, sink, stream=None) -> None:

@@ -1,5 +1,6 @@
 // C ABI of the temporal convolution (include/sv_tconv.h): argument checks and launches.
 #include "../../include/sv_tconv.h"
+#include "../../include/sv_measure.h"
 
 #include <mutex>
 
@@ -36,10 +37,35 @@ bool tconv_kernel_ready()
     return true;
 }
 
-}  // namespace
+// The tile kernel for a measurement variant (0 = the library's own), readied once per device.
+using TconvKernel = void (*)(TconvArgs);
+TconvKernel variant_kernel(int variant)
+{
+    switch (variant) {
+    case 1: return tconv_mfma<false, 1>;
+    case 2: return tconv_mfma<false, 2>;
+    case 3: return tconv_mfma<false, 3>;
+    default: return tconv_mfma<false, 0>;
+    }
+}
+bool variant_kernel_ready(int variant)
+{
+    static bool ready[64][4] = {};
+    static std::mutex mu;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return false;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ready[dev][variant]) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(variant_kernel(variant)),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kTcLdsBytes) != hipSuccess)
+            return false;
+        ready[dev][variant] = true;
+    }
+    return true;
+}
 
-extern "C" sv_status sv_tconv_block_step(const void *x, const void *W, const void *cache_in, void *y, void *cache_out,
-                                         int32_t B, int32_t T, int32_t HW, int32_t D, int32_t dtype, void *stream)
+sv_status tconv_enqueue(int variant, const void *x, const void *W, const void *cache_in, void *y, void *cache_out,
+                        int32_t B, int32_t T, int32_t HW, int32_t D, int32_t dtype, void *stream)
 {
     if (!x || !W || !y) return SV_ERR_NULL;
     if (B <= 0 || T <= 0 || HW <= 0 || D <= 0) return SV_ERR_SHAPE;
@@ -57,7 +83,8 @@ extern "C" sv_status sv_tconv_block_step(const void *x, const void *W, const voi
     if (cache_out && (overlaps(cache_out, cache_bytes, y, tok_bytes) || overlaps(cache_out, cache_bytes, x, tok_bytes) ||
                       overlaps(cache_out, cache_bytes, W, w_bytes)))
         return SV_ERR_SHAPE;
-    if (!tconv_kernel_ready()) return SV_ERR_LAUNCH;
+    if (variant != 0 && D % kTcBK != 0) return SV_ERR_UNSUPPORTED;
+    if (!(variant == 0 ? tconv_kernel_ready() : variant_kernel_ready(variant))) return SV_ERR_LAUNCH;
 
     TconvArgs a;
     a.x = static_cast<const uint16_t *>(x);
@@ -70,7 +97,8 @@ extern "C" sv_status sv_tconv_block_step(const void *x, const void *W, const voi
     const int64_t wgs = tc_grid_size((int64_t)a.tiles_m * a.tiles_n);
     if (wgs >= (int64_t)1 << 31) return SV_ERR_SHAPE;
     auto hs = static_cast<hipStream_t>(stream);
-    if (D % kTcBK == 0) tconv_mfma<false><<<dim3((unsigned)wgs), kThreads, kTcLdsBytes, hs>>>(a);
+    if (variant != 0) variant_kernel(variant)<<<dim3((unsigned)wgs), kThreads, kTcLdsBytes, hs>>>(a);
+    else if (D % kTcBK == 0) tconv_mfma<false><<<dim3((unsigned)wgs), kThreads, kTcLdsBytes, hs>>>(a);
     else tconv_mfma<true><<<dim3((unsigned)wgs), kThreads, kTcLdsBytes, hs>>>(a);
     if (hipGetLastError() != hipSuccess) return SV_ERR_LAUNCH;
     if (cache_out) {
@@ -80,4 +108,19 @@ extern "C" sv_status sv_tconv_block_step(const void *x, const void *W, const voi
         if (hipGetLastError() != hipSuccess) return SV_ERR_LAUNCH;
     }
     return SV_OK;
+}
+
+}  // namespace
+
+extern "C" sv_status sv_tconv_block_step(const void *x, const void *W, const void *cache_in, void *y, void *cache_out,
+                                         int32_t B, int32_t T, int32_t HW, int32_t D, int32_t dtype, void *stream)
+{
+    return tconv_enqueue(0, x, W, cache_in, y, cache_out, B, T, HW, D, dtype, stream);
+}
+
+extern "C" sv_status sv_measure_tconv_variant(int32_t variant, const void *x, const void *W, const void *cache_in, void *y,
+                                              int32_t B, int32_t T, int32_t HW, int32_t D, void *stream)
+{
+    if (variant < 0 || variant > 3) return SV_ERR_RANGE;
+    return tconv_enqueue(variant, x, W, cache_in, y, nullptr, B, T, HW, D, SV_BF16, stream);
 }

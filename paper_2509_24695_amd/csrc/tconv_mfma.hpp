@@ -68,7 +68,10 @@ __device__ __forceinline__ void tc_load_to_lds(const uint16_t *src, unsigned cha
 }
 
 // KTAIL: D is not a multiple of the K-step, the last K-step of a tap has chunks past the row end.
-template <bool KTAIL>
+// SKIP: measurement variants (sv_measure_tconv_variant; the library's own calls use 0): bit 0 leaves the
+// loads into LDS out of the tile loop, bit 1 the operand reads from LDS.  Such a launch touches the same
+// memory and writes every element of y, but what it writes is not the convolution.
+template <bool KTAIL, int SKIP = 0>
 __global__ __launch_bounds__(kThreads) void tconv_mfma(TconvArgs a)
 {
     extern __shared__ __align__(16) unsigned char lds[];
@@ -158,9 +161,18 @@ __global__ __launch_bounds__(kThreads) void tconv_mfma(TconvArgs a)
     }
 #pragma unroll
     for (int m = 0; m < 4; ++m) request_one(kTcStages - 1, m);
+    if (SKIP & 1) {                    // no loads in the loop: the ring is filled here, once, and read over and over
+#pragma unroll
+        for (int m = 4; m < 8; ++m) request_one(kTcStages - 1, m);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
     asm volatile("s_waitcnt vmcnt(20)\n\ts_barrier" ::: "memory");
 #pragma unroll
     for (int m = 0; m < 8; ++m) op[0][m] = operand(0, 0, m);
+    if (SKIP & 2) {
+#pragma unroll
+        for (int m = 0; m < 8; ++m) op[1][m] = operand(0, 1, m);
+    }
 
     // A load instruction keeps the wave from issuing for longer than one MFMA runs, so the eight
     // loads of a step are spread out: one after every second MFMA of the second half of one step
@@ -171,8 +183,8 @@ __global__ __launch_bounds__(kThreads) void tconv_mfma(TconvArgs a)
         for (int m = 0; m < 16; ++m) {
             acc[m >> 2][m & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[0][m >> 2], op[0][4 + (m & 3)],
                                                                           acc[m >> 2][m & 3], 0, 0, 0);
-            if (m < 8) op[1][m] = operand(cur, 1, m);
-            if (m >= 8 && (m & 1)) request_one(prv, 4 + ((m - 8) >> 1));     // B rows of step s+3
+            if (!(SKIP & 2) && m < 8) op[1][m] = operand(cur, 1, m);
+            if (!(SKIP & 1) && m >= 8 && (m & 1)) request_one(prv, 4 + ((m - 8) >> 1));     // B rows of step s+3
             __builtin_amdgcn_sched_barrier(0);
         }
         advance();
@@ -183,8 +195,8 @@ __global__ __launch_bounds__(kThreads) void tconv_mfma(TconvArgs a)
         for (int m = 0; m < 16; ++m) {
             acc[m >> 2][m & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[1][m >> 2], op[1][4 + (m & 3)],
                                                                           acc[m >> 2][m & 3], 0, 0, 0);
-            if (m < 8) op[0][m] = operand(nxt, 0, m);
-            if (m >= 8 && (m & 1)) request_one(cur, (m - 8) >> 1);           // A rows of step s+4
+            if (!(SKIP & 2) && m < 8) op[0][m] = operand(nxt, 0, m);
+            if (!(SKIP & 1) && m >= 8 && (m & 1)) request_one(cur, (m - 8) >> 1);           // A rows of step s+4
             __builtin_amdgcn_sched_barrier(0);
         }
     }

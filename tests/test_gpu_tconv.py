@@ -121,3 +121,28 @@ def test_full_size(name):
         _check(to_host(y).astype(np.float64), y_ref, f"{name} block {m}")
         assert np.array_equal(to_host(new_cache).astype(np.float64), cache_ref)
         cache_d = new_cache
+
+
+def test_measurement_variants_write_all_of_y_and_variant_0_is_the_library_kernel():
+    """sv_measure_tconv_variant: variant 0 is sv_tconv_block_step's kernel bit for bit; variants 1-3 (parts of
+    the tile loop left out, for timing) touch nothing but y and leave no element of it unwritten."""
+    import torch
+    B, T, HW, D = 1, 3, 300, 320                       # two token tiles, two channel tiles, ten K-steps per tap
+    rng = np.random.default_rng(77)
+    x = (rng.standard_normal((B, T, HW, D)) * 0.5).astype(np.float32)
+    Wt = (rng.standard_normal((3, D, D)) * 0.05).astype(np.float32)
+    cache = (rng.standard_normal((B, HW, D)) * 0.5).astype(np.float32)
+    xd, Wd, cd = (torch.from_numpy(t).to(torch.bfloat16).cuda() for t in (x, Wt, cache))
+    keep = [t.clone() for t in (xd, Wd, cd)]
+    y_lib = torch.empty_like(xd)
+    sv.sv_tconv_block_step(xd, Wd, cd, y_lib, None, B, T, HW, D)
+    say("tconv measurement variants")
+    for variant in range(4):
+        y = torch.full_like(xd, float("nan"))
+        sv.sv_measure_tconv_variant(variant, xd, Wd, cd, y, B, T, HW, D)
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(y.float()).all()), variant
+        if variant == 0:
+            assert torch.equal(y.view(torch.int16), y_lib.view(torch.int16))
+        for t, k in zip((xd, Wd, cd), keep):
+            assert torch.equal(t.view(torch.int16), k.view(torch.int16))

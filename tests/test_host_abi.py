@@ -236,6 +236,17 @@ def test_tconv_checks_arguments():
     assert call(cache_out=FAKE + (1 << 28)) == 2            # cache_out on top of W
 
 
+def test_tconv_variant_checks_arguments():
+    def call(variant=1, x=FAKE, W=FAKE + (1 << 28), cache_in=None, y=FAKE + (1 << 29), B=1, T=3, HW=100, D=64):
+        with pytest.raises(sv.SvError) as e:
+            sv.sv_measure_tconv_variant(variant, x, W, cache_in, y, B, T, HW, D)
+        return e.value.status
+
+    assert call(variant=-1) == 5 and call(variant=4) == 5      # SV_ERR_RANGE
+    assert call(x=None) == 1 and call(y=None) == 1 and call(T=0) == 2 and call(y=FAKE + 64) == 2
+    assert call(variant=2, D=40) == 3                       # variants 1-3 need whole K-steps
+
+
 def test_stream_yardsticks_check_arguments():
     def status(fn, *args):
         with pytest.raises(sv.SvError) as e:
