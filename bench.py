@@ -437,7 +437,8 @@ def bench_tconv(w, iters, sv, torch):
     loop_variants = None
     if w.D % 32 == 0:
         names = ["library kernel", "without the loads into LDS", "without the operand reads from LDS", "without both"]
-        loop_variants = {names[v]: variant_us(v) for v in (0, 1, 2, 3, 0)}     # the library's kernel again at the end
+        loop_variants = {names[v]: variant_us(v) for v in range(4)}
+        loop_variants["library kernel, timed again"] = variant_us(0)
     wg_flops = k_steps * 4 * 32 * 2 * 32 * 32 * 16
     return {"workload": f"{w.name}: B={w.B} T={w.T} HW={w.HW} D={w.D}, {w.n_blocks} block(s)", "us_per_block": us,
             "tokens_per_s": w.tokens / (us * 1e-6), "dtype": "bf16",
