@@ -15,6 +15,10 @@ HIPCC_FLAGS = [
     "-Wall", "-Wextra", "-Wno-unused-parameter",
     # packed-fp32 VALU forms stay off (device-side feature; the host pass ignores it)
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # The epoch ticket (EpochSource::begin) is one lane's fetch-and-add whose result is needed much later.  The
+    # compiler's atomic optimizer would turn it into a wave-wide reduction that needs the result at once, and
+    # the wave would wait for the atomic's round trip before its first load.
+    "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
     # per-kernel register, scratch and LDS use as compiler remarks (parsed below)
     "-Rpass-analysis=kernel-resource-usage",
 ]

@@ -125,8 +125,14 @@ struct EpochSource {
     __device__ __forceinline__ unsigned long long resolve(unsigned long long *lds_word) const
     {
         if (threadIdx.x == 0) {
-            const bool device = magic == kWsMagic && !(host & kHostEpochsOnly);
-            *lds_word = device ? ((ticket / kTicketQuantum + 1) << 1) : host;
+            // What begin() fetched is looked at here and not before: without the two empty statements the
+            // compiler moves this arithmetic up into begin()'s branch (same condition), and the wave then
+            // waits for a device-scope atomic's round trip before it requests its first tile.
+            unsigned long long m = magic, t = ticket;
+            asm volatile("" : "+v"(m));
+            asm volatile("" : "+v"(t));
+            const bool device = m == kWsMagic && !(host & kHostEpochsOnly);
+            *lds_word = device ? ((t / kTicketQuantum + 1) << 1) : host;
         }
         wg_barrier();
         return *lds_word;
