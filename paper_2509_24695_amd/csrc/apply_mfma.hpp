@@ -68,15 +68,32 @@ struct ApplyOperands {
         static_assert(DP == 64 && ZROWS, "the d = 64 apply kernel");
         bf16x8 *st = reinterpret_cast<bf16x8 *>(stage);       // [hi/lo][row block][k-step][lane]
         const int m = lane & 31, g = lane >> 5;
+        // every load of the function goes out before the first value is looked at: one memory round trip, not one
+        // per row block and one for the key sums (the compiler keeps coherent loads in program order)
+        float sa[NB][8];
 #pragma unroll
         for (int rb = 0; rb < NB; ++rb) {
             const int F = 16 * NB * ((m >> 2) & 1) + 16 * rb + 4 * (m >> 3) + (m & 3);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int k = 16 * wave + 8 * g + i;
+                sa[rb][i] = COHERENT ? load_coherent1(Sh + k * 64 + F) : Sh[k * 64 + F];
+            }
+        }
+        float zv[KS][8];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int k = 16 * ks + 8 * g + i;
+                zv[ks][i] = COHERENT ? load_coherent1(zh + k) : zh[k];
+            }
+#pragma unroll
+        for (int rb = 0; rb < NB; ++rb) {
             uint32_t hi[4], lo[4];
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
-                const int k = 16 * wave + 8 * g + 2 * p;
-                const float a = COHERENT ? load_coherent1(Sh + k * 64 + F) : Sh[k * 64 + F];
-                const float b = COHERENT ? load_coherent1(Sh + (k + 1) * 64 + F) : Sh[(k + 1) * 64 + F];
+                const float a = sa[rb][2 * p], b = sa[rb][2 * p + 1];
                 hi[p] = pack_bf16x2(a, b);
                 lo[p] = pack_bf16x2(a - bf16_lo(hi[p]), b - bf16_hi(hi[p]));
             }
@@ -84,21 +101,26 @@ struct ApplyOperands {
             st[((0 * NB + rb) * KS + wave) * 64 + lane] = __builtin_bit_cast(bf16x8, h4);
             st[((1 * NB + rb) * KS + wave) * 64 + lane] = __builtin_bit_cast(bf16x8, l4);
         }
+        u32x4 zw[KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             uint32_t w[4];
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
-                const int k = 16 * ks + 8 * g + 2 * p;
-                const float a = COHERENT ? load_coherent1(zh + k) : zh[k];
-                const float b = COHERENT ? load_coherent1(zh + k + 1) : zh[k + 1];
+                const float a = zv[ks][2 * p], b = zv[ks][2 * p + 1];
                 const uint32_t hi = pack_bf16x2(a, b);
                 const uint32_t lo = pack_bf16x2(a - bf16_lo(hi), b - bf16_hi(hi));
                 w[p] = m == 0 ? hi : (m == 1 ? lo : 0u);
             }
-            const u32x4 w4 = {w[0], w[1], w[2], w[3]};
-            zrow[ks] = __builtin_bit_cast(bf16x8, w4);
+            zw[ks] = u32x4{w[0], w[1], w[2], w[3]};
         }
+        // The z rows are made here, before the barrier.  Left to itself the compiler sinks this arithmetic to
+        // the first use, behind whatever loads the caller issues after this function, and the wait for the
+        // key sums then becomes a wait for those loads as well (memory operations complete in order).
+        static_assert(KS == 4, "four k-steps");
+        asm volatile("" : "+v"(zw[0]), "+v"(zw[1]), "+v"(zw[2]), "+v"(zw[3]));
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) zrow[ks] = __builtin_bit_cast(bf16x8, zw[ks]);
         wg_barrier();
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
