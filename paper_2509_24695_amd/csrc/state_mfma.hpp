@@ -308,16 +308,23 @@ template <bool ZVALU>
 __device__ __forceinline__ void state_acc_to_slot(StateAcc &acc, float *dst, int lane)
 {
     // 32x32 accumulator layout: register i of lane l is row 8*(i/4) + 4*(l/32) + i%4, column l%32.
+    // (one base address per lane and compile-time offsets from it: the 96 LDS writes then need no address arithmetic)
     const int n = lane & 31, g = lane >> 5;
+    float *row0 = dst + (4 * g) * 64 + n, *z0 = dst + 64 * 64 + 4 * g;
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            const int k = 32 * rb + 8 * (i >> 2) + 4 * g + (i & 3);
-            dst[k * 64 + n] = acc.s[rb][0][i];
-            dst[k * 64 + 32 + n] = acc.s[rb][1][i];
-            if (!ZVALU && n == 0) dst[64 * 64 + k] = acc.zm[rb][i];   // every column of zm holds the key sums
+            const int kc = 32 * rb + 8 * (i >> 2) + (i & 3);   // k = kc + 4 g
+            row0[kc * 64] = acc.s[rb][0][i];
+            row0[kc * 64 + 32] = acc.s[rb][1][i];
         }
+    if (!ZVALU && n == 0) {                                  // every column of zm holds the key sums
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) z0[32 * rb + 8 * (i >> 2) + (i & 3)] = acc.zm[rb][i];
+    }
     if (ZVALU) {
         // lanes with equal lane%8 hold the same 8 features (wavefront-level reduction)
 #pragma unroll
@@ -428,17 +435,23 @@ __device__ __forceinline__ void state_finalize_slice(const float *__restrict__ p
                 if (S_in && v < hi) x[u] = *reinterpret_cast<const f32x2 *>(v < s_units ? S_in + 2 * v : z_in + 2 * (v - s_units));
             }
         }
+        // Straight-line loads: a wave-uniform base per partial plus one 32-bit offset per unit, no branch (a group
+        // that reaches past C re-reads the last partial and leaves it out of the sum).  This runs on the chain of
+        // round trips by which a head agrees on its state, where every instruction counts.
+        uint32_t off[UNITS];
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) {
+            int v = v0 + u * THREADS;                            // beyond the slice: any valid unit, the sum is not stored
+            v = v < sl.units ? v : sl.units - 1;
+            off[u] = 2u * (uint32_t)v;
+        }
         for (int c0 = 0; c0 < C; c0 += GROUP) {
             f32x2 p[UNITS][GROUP];
 #pragma unroll
-            for (int u = 0; u < UNITS; ++u) {
-                int v = v0 + u * THREADS;                        // beyond the slice: any valid unit, the sum is not stored
-                v = v < sl.units ? v : sl.units - 1;
+            for (int cc = 0; cc < GROUP; ++cc) {
+                const float *part = partials + (size_t)(c0 + cc < C ? c0 + cc : C - 1) * elems;
 #pragma unroll
-                for (int cc = 0; cc < GROUP; ++cc) {
-                    p[u][cc] = f32x2{0.f, 0.f};
-                    if (c0 + cc < C) p[u][cc] = load_coherent(partials + (size_t)(c0 + cc) * elems + 2 * v);
-                }
+                for (int u = 0; u < UNITS; ++u) p[u][cc] = load_coherent(part + off[u]);
             }
 #pragma unroll
             for (int u = 0; u < UNITS; ++u)
