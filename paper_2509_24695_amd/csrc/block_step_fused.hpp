@@ -43,6 +43,11 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
     unsigned long long epoch, uint32_t spin_limit, int BH_local, int n_dies)
 {
     static_assert(TILE == kApplyTile, "both phases walk tiles of the same size");
+    // Every argument is fetched with the first batch of scalar loads.  Left alone the compiler fetches
+    // some of them where they are first used - K and V right before the first tile request, the state pointers in
+    // the middle of the agreement chain - and each such fetch is a round trip nobody can hide.
+    asm volatile("" ::"s"(Q), "s"(K), "s"(V), "s"(O), "s"(S_in), "s"(z_in), "s"(S_out), "s"(z_out), "s"(ws), "s"(epoch),
+                 "s"(eps), "s"(spin_limit));
     constexpr int kTileBytes = TILE * kRowBytes;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
