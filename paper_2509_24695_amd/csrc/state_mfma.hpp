@@ -356,15 +356,25 @@ __device__ __forceinline__ void state_wg_reduce_store(StateAcc &acc, float *slot
     wg_barrier();                                   // all waves are done with their staging tiles
     state_acc_to_slot<ZVALU>(acc, slots + wave * kStateElems, lane);
     wg_barrier();
-    for (int v = threadIdx.x; v < kStateElems / 2; v += THREADS) {
-        f32x2 x[WAVES];
+    // a fixed number of rounds, all LDS reads of the workgroup's share issued before the first sum: this sits on
+    // the chain of round trips by which a head agrees on its state
+    constexpr int kUnits = kStateElems / 2, kRounds = (kUnits + THREADS - 1) / THREADS;
+    f32x2 x[kRounds][WAVES];
 #pragma unroll
-        for (int w = 0; w < WAVES; ++w) x[w] = *reinterpret_cast<const f32x2 *>(slots + w * kStateElems + 2 * v);
+    for (int r = 0; r < kRounds; ++r) {
+        int v = (int)threadIdx.x + r * THREADS;
+        v = v < kUnits ? v : kUnits - 1;                 // past the end: any valid unit, the sum is not stored
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) x[r][w] = *reinterpret_cast<const f32x2 *>(slots + w * kStateElems + 2 * v);
+    }
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
 #pragma unroll
         for (int h = WAVES / 2; h >= 1; h /= 2)
 #pragma unroll
-            for (int w = 0; w < h; ++w) x[w] += x[w + h];
-        store_coherent<LOCAL>(out + 2 * v, x[0]);
+            for (int w = 0; w < h; ++w) x[r][w] += x[r][w + h];
+        const int v = (int)threadIdx.x + r * THREADS;
+        if (v < kUnits) store_coherent<LOCAL>(out + 2 * v, x[r][0]);
     }
 }
 
