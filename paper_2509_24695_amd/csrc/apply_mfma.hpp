@@ -57,10 +57,12 @@ struct ApplyOperands {
     bf16x8 s[NS][NB][KS];          // [hi/lo][row block][k-step]
     bf16x8 zrow[ZROWS ? KS : 1];   // [k-step]
 
+    // LDS that load_shared stages through: the operand words of S, then the hi and lo words of the z rows.
+    static constexpr int kSharedStateBytes = 2 * NB * KS * 64 * 16, kSharedBytes = kSharedStateBytes + KS * 2 * 2 * 16;
+
     // The same operands (DP = 64, value block 0), fetched once per workgroup instead of once per wave:
-    // wave w converts k-step w of S and hands it round through `stage` (16 KB of LDS, free again
-    // when this returns); the two z rows are cheap enough for every wave to take itself.  Must be
-    // called by all four waves.  COHERENT: the state was written by another workgroup of this same kernel.
+    // wave w converts k-step w of S and of the two z rows and hands them round through `stage`
+    // (kSharedBytes of LDS, free again when this returns).  Must be called by all four waves.  COHERENT: the state was written by another workgroup of this same kernel.
     template <bool COHERENT>
     __device__ __forceinline__ void load_shared(const float *__restrict__ Sh, const float *__restrict__ zh, int wave,
                                                 int lane, unsigned char *stage)
@@ -80,14 +82,9 @@ struct ApplyOperands {
                 sa[rb][i] = COHERENT ? load_coherent1(Sh + k * 64 + F) : Sh[k * 64 + F];
             }
         }
-        float zv[KS][8];
+        float zv[8];                                          // the key sums of k-step `wave`
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int k = 16 * ks + 8 * g + i;
-                zv[ks][i] = COHERENT ? load_coherent1(zh + k) : zh[k];
-            }
+        for (int i = 0; i < 8; ++i) zv[i] = COHERENT ? load_coherent1(zh + 16 * wave + 8 * g + i) : zh[16 * wave + 8 * g + i];
 #pragma unroll
         for (int rb = 0; rb < NB; ++rb) {
             uint32_t hi[4], lo[4];
@@ -101,34 +98,32 @@ struct ApplyOperands {
             st[((0 * NB + rb) * KS + wave) * 64 + lane] = __builtin_bit_cast(bf16x8, h4);
             st[((1 * NB + rb) * KS + wave) * 64 + lane] = __builtin_bit_cast(bf16x8, l4);
         }
-        u32x4 zw[KS];
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            uint32_t w[4];
+        // z rows: the hi and lo words of k-step `wave`, once per half wave: [k-step][g][hi/lo] behind the S words
+        u32x4 *zst = reinterpret_cast<u32x4 *>(stage + kSharedStateBytes);
+        {
+            uint32_t hi[4], lo[4];
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
-                const float a = zv[ks][2 * p], b = zv[ks][2 * p + 1];
-                const uint32_t hi = pack_bf16x2(a, b);
-                const uint32_t lo = pack_bf16x2(a - bf16_lo(hi), b - bf16_hi(hi));
-                w[p] = m == 0 ? hi : (m == 1 ? lo : 0u);
+                const float a = zv[2 * p], b = zv[2 * p + 1];
+                hi[p] = pack_bf16x2(a, b);
+                lo[p] = pack_bf16x2(a - bf16_lo(hi[p]), b - bf16_hi(hi[p]));
             }
-            zw[ks] = u32x4{w[0], w[1], w[2], w[3]};
+            if (m == 0) {
+                zst[(wave * 2 + g) * 2 + 0] = u32x4{hi[0], hi[1], hi[2], hi[3]};
+                zst[(wave * 2 + g) * 2 + 1] = u32x4{lo[0], lo[1], lo[2], lo[3]};
+            }
         }
-        // The z rows are made here, before the barrier.  Left to itself the compiler sinks this arithmetic to
-        // the first use, behind whatever loads the caller issues after this function, and the wait for the
-        // key sums then becomes a wait for those loads as well (memory operations complete in order).
-        static_assert(KS == 4, "four k-steps");
-        asm volatile("" : "+v"(zw[0]), "+v"(zw[1]), "+v"(zw[2]), "+v"(zw[3]));
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) zrow[ks] = __builtin_bit_cast(bf16x8, zw[ks]);
         wg_barrier();
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
+        for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll
             for (int rb = 0; rb < NB; ++rb) {
                 s[0][rb][ks] = st[((0 * NB + rb) * KS + ks) * 64 + lane];
                 if (HILO) s[NS - 1][rb][ks] = st[((1 * NB + rb) * KS + ks) * 64 + lane];
             }
+            const u32x4 w4 = zst[(ks * 2 + g) * 2 + (m & 1)];            // row 0 = hi(z), row 1 = lo(z), the rest 0
+            zrow[ks] = __builtin_bit_cast(bf16x8, m < 2 ? w4 : u32x4{0u, 0u, 0u, 0u});
+        }
         wg_barrier();                        // `stage` may be written again
     }
 
@@ -385,7 +380,7 @@ __host__ __device__ constexpr int apply_lds_bytes() { return WAVES * apply_wave_
 // HILO = false drops the low half of S (one MFMA pass instead of two).
 // ROPE (kRopeNone/Table/3D); with kRope3D the dynamic LDS carries kRope3dLdsBytes more.
 // S_LDS, DEN_VALU: the measurement variants of apply_tiles; S_LDS needs kApplyStateLdsBytes more dynamic LDS.
-constexpr int kApplyStateLdsBytes = 2 * 2 * 4 * 64 * 16;
+constexpr int kApplyStateLdsBytes = ApplyOperands<64, true>::kSharedBytes;
 template <bool HILO, int WAVES, int DEPTH, int ROPE, bool S_LDS = false, bool DEN_VALU = false>
 __global__ __launch_bounds__(64 * WAVES, 1) void apply_mfma_d64(
     const uint16_t *__restrict__ Q, uint16_t *__restrict__ O, RopeArg rope, TokStrides st, int H,
@@ -410,7 +405,7 @@ __global__ __launch_bounds__(64 * WAVES, 1) void apply_mfma_d64(
         wg_barrier();
     }
     ApplyOperands<64, HILO> A;
-    static_assert(apply_lds_bytes<WAVES, ROPE>() >= 2 * 2 * 4 * 64 * 16 && WAVES == 4, "the tiles can stage S for load_shared");
+    static_assert(apply_lds_bytes<WAVES, ROPE>() >= ApplyOperands<64, HILO>::kSharedBytes && WAVES == 4, "the tiles can stage S for load_shared");
     // through the tiles, not yet in use; S_LDS: into an area of their own behind the tiles (and the tables), to stay
     unsigned char *stage = S_LDS ? lds + apply_lds_bytes<WAVES, ROPE>() + (ROPE == kRope3D ? kRope3dLdsBytes : 0) : lds;
     A.template load_shared<false>(S + (size_t)bh * 64 * 64, z + (size_t)bh * 64, wave, lane, stage);

@@ -154,7 +154,8 @@ __global__ __launch_bounds__(64 * WAVES, 1) void block_step_mfma(
 
     // ---- apply the updated state to this workgroup's share of Q_b --------------------------------
     ApplyOperands<64, HILO> A;
-    static_assert(WAVES == 4 && block_step_lds_bytes<TILE, WAVES, ROPE>() >= 2 * 2 * 4 * 64 * 16, "LDS can stage S for load_shared");
+    static_assert(WAVES == 4 && block_step_lds_bytes<TILE, WAVES, ROPE>() >= ApplyOperands<64, HILO>::kSharedBytes + kEpochLdsBytes,
+                  "LDS can stage S for load_shared");
     A.template load_shared<true>(Sh, zh, wave, lane, lds);   // through LDS that the state phase has left and the apply phase not yet taken
     float zf[4][8];
     if (DEN_VALU) load_key_sums<true>(zh, lane, zf);
