@@ -138,13 +138,17 @@ struct ApplyOperands {
             const int F = 32 * NB * vb + 16 * NB * ((m >> 2) & 1) + 16 * rb + 4 * (m >> 3) + (m & 3);
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
+                // every lane loads (a valid address where its element does not exist) and the value is dropped
+                // afterwards: a load under a condition becomes a branch, and the compiler then waits for each
+                // load before the next branch - eight dependent round trips instead of one
                 float sv_[8];
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
                     const int k = 16 * ks + 8 * g + i;
-                    const float *p = Sh + k * d + F;
-                    sv_[i] = 0.f;
-                    if (DP == 64 || (k < d && F < d)) sv_[i] = COHERENT ? load_coherent1(p) : *p;
+                    const bool exists = DP == 64 || (k < d && F < d);
+                    const float *p = Sh + (exists ? k * d + F : 0);
+                    const float x = COHERENT ? load_coherent1(p) : *p;
+                    sv_[i] = exists ? x : 0.f;
                 }
                 uint32_t hi[4], lo[4];
 #pragma unroll
@@ -164,11 +168,12 @@ struct ApplyOperands {
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
                 const int k = 16 * ks + 8 * g + 2 * p;
-                float a = 0.f, b = 0.f;
-                if (DP == 64 || k < d) {       // d is even: k and k + 1 exist together
-                    a = COHERENT ? load_coherent1(zh + k) : zh[k];
-                    b = COHERENT ? load_coherent1(zh + k + 1) : zh[k + 1];
-                }
+                const bool exists = DP == 64 || k < d;       // d is even: k and k + 1 exist together
+                const float *pz = zh + (exists ? k : 0);
+                float a = COHERENT ? load_coherent1(pz) : pz[0];
+                float b = COHERENT ? load_coherent1(pz + 1) : pz[1];
+                a = exists ? a : 0.f;
+                b = exists ? b : 0.f;
                 const uint32_t hi = pack_bf16x2(a, b);
                 const uint32_t lo = pack_bf16x2(a - bf16_lo(hi), b - bf16_hi(hi));
                 w[p] = m == 0 ? hi : (m == 1 ? lo : 0u);

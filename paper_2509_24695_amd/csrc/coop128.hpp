@@ -413,7 +413,8 @@ __global__ __launch_bounds__(64 * WAVES, NB == 1 ? 2 : 1) void apply_mfma_d128(
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         const int k = 8 * (lane & 15) + e;
-        zr[e] = k < d ? z[(size_t)bh * d + k] : 0.f;
+        const float x = z[(size_t)bh * d + (k < d ? k : 0)];   // loaded by every lane: a load under a condition is a branch
+        zr[e] = k < d ? x : 0.f;
     }
     apply_tiles_coop<HILO>(stream, lds, wave, lane, A, zr, eps);
 }
