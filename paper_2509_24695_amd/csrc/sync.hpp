@@ -28,6 +28,11 @@ __device__ __forceinline__ void store_coherent(float *p, f32x2 v) {
     else __hip_atomic_store(reinterpret_cast<unsigned long long *>(p), __builtin_bit_cast(unsigned long long, v),
                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// Device-coherent 4-byte store through a buffer resource: the same cache policy as store_coherent,
+// and byte offsets at or past the resource's size are dropped.
+__device__ __forceinline__ void store_coherent4(rsrc_t r, uint32_t off, float v) {
+    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, v), r, off, 0, 16 /* sc1 */);
+}
 __device__ __forceinline__ f32x2 load_coherent(const float *p) {
     return __builtin_bit_cast(f32x2, __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p),
                                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));

@@ -16,8 +16,8 @@
 // the rotation, waits, the barrier itself - are paid per 64 tokens of a compute unit's work
 // instead of per 32 and never hold up the other waves.
 //
-// At the end the four waves' states are added in a fixed order through LDS, a band of 32 key
-// features at a time, and stored as the workgroup's partial.
+// At the end the four waves' states are added in a fixed order, exchanged through LDS in the
+// accumulators' own layout, and stored as the workgroup's partial.
 #pragma once
 
 #include "state_mfma.hpp"
@@ -32,16 +32,21 @@ constexpr int kWideTile = 16;                       // tokens per tile: one MFMA
 constexpr int kWideRow = 128 * 2 + 64;
 constexpr int kWideTileBytes = kWideTile * kWideRow;
 
-// LDS map (bytes): [0, 64 KB) the reduction bands (4 waves x 32 rows x 128 floats), over the dead K/V
-// tiles (8 tiles from 0); then the rotation tables, the waves' key sums and the epoch word.
-constexpr int kWideTabOffset = 4 * 32 * 128 * 4;
-constexpr int kWideZOffset = kWideTabOffset + kRope3dLdsBytes;
+// LDS map (bytes): the K/V tiles (8 tiles from 0) and, from 64 KB, the rotation tables; once the token
+// loop is over, [0, 128 KB) are the four waves' parcels of the final reduction; then the waves' key
+// sums and the epoch word.
+constexpr int kWideTabOffset = 64 * 1024;
+constexpr int kWideParcelBytes = 8 * 16 * kWave * 4;     // eight accumulator blocks
+constexpr int kWideZOffset = 4 * kWideParcelBytes;
 constexpr int kWideEpochOffset = kWideZOffset + 4 * 128 * 4;
 constexpr int kWideLdsBytes = kWideEpochOffset + kEpochLdsBytes;
-static_assert(8 * kWideTileBytes <= kWideTabOffset, "the tiles fit under the reduction bands");
+static_assert(8 * kWideTileBytes <= kWideTabOffset, "the tiles end where the tables begin");
+static_assert(kWideTabOffset + kRope3dLdsBytes <= kWideZOffset, "the tables end where the key sums begin");
 
 struct WideAcc {
-    f32x16 s[4][4];   // [key feature block][value feature block]
+    // [r][value feature block]; in wave w, r is key feature block r ^ w: the final reduction then sends
+    // and keeps the same registers in every wave
+    f32x16 s[4][4];
     float z[8];       // features 8 * (lane % 16) + e of the tokens this lane loaded
     __device__ __forceinline__ void clear() {
 #pragma unroll
@@ -130,7 +135,7 @@ __device__ __forceinline__ void wide_state_prepare(WideStateStream<DEPTH, ROPE> 
 // shadow, so the vector work of tile i + 1 is issued between the MFMAs of tile i.
 template <int DEPTH, int ROPE>
 __device__ __forceinline__ void wide_state_accumulate(WideStateStream<DEPTH, ROPE> &st, unsigned char *tileK,
-                                                      unsigned char *tileV, int lane, WideAcc &acc)
+                                                      unsigned char *tileV, int wave, int lane, WideAcc &acc)
 {
     constexpr int NLD = WideStateStream<DEPTH, ROPE>::NLD;
     const int wr_off = (lane >> 4) * kWideRow + (lane & 15) * 16;
@@ -155,7 +160,7 @@ __device__ __forceinline__ void wide_state_accumulate(WideStateStream<DEPTH, ROP
             bf16x8 a[4], b[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                a[q] = lds_tr_operand<kWideRow>(tileK, 0, 32 * q, lane);
+                a[q] = lds_tr_operand<kWideRow>(tileK, 0, 32 * (q ^ wave), lane);
                 b[q] = lds_tr_operand<kWideRow>(tileV, 0, 32 * q, lane);
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -175,15 +180,66 @@ __device__ __forceinline__ void wide_state_accumulate(WideStateStream<DEPTH, ROP
     }
 }
 
+// Accumulator blocks travel between waves through LDS as each lane's own registers: block `slot` of a
+// transfer is four 16-byte words per lane, lane-contiguous (1 KB per instruction, no bank conflicts),
+// and the partner's lane of the same number holds the same elements of S.
+__device__ __forceinline__ void wide_send(unsigned char *region, int slot, const f32x16 &a, int lane)
+{
+    f32x4 *p = reinterpret_cast<f32x4 *>(region) + slot * 4 * kWave + lane;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        f32x4 x;
+        x.x = a[4 * q];  x.y = a[4 * q + 1];  x.z = a[4 * q + 2];  x.w = a[4 * q + 3];
+        p[q * kWave] = x;
+    }
+}
+// out(b) = own(b) + block b of the parcel at `region`, b < N.  The LDS reads run one block ahead of
+// the additions and no further: left to itself the compiler requests the whole parcel at once and
+// spills the state to make room for it.
+template <int N, class OwnFn, class OutFn>
+__device__ __forceinline__ void wide_recv_add(const unsigned char *region, int lane, OwnFn own, OutFn out)
+{
+    const f32x4 *p = reinterpret_cast<const f32x4 *>(region) + lane;
+    f32x4 x[2][4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) x[0][q] = p[q * kWave];
+#pragma unroll
+    for (int b = 0; b < N; ++b) {
+        if (b + 1 < N) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) x[(b + 1) & 1][q] = p[((b + 1) * 4 + q) * kWave];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        const f32x16 &o = own(b);
+        f32x16 r;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const f32x4 y = x[b & 1][q];
+            r[4 * q] = o[4 * q] + y.x;          r[4 * q + 1] = o[4 * q + 1] + y.y;
+            r[4 * q + 2] = o[4 * q + 2] + y.z;  r[4 * q + 3] = o[4 * q + 3] + y.w;
+        }
+        out(b) = r;
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
 // Adds the four waves' states in the fixed order (w0 + w2) + (w1 + w3) and stores the workgroup's
 // partial (d x d, row length d, then the d key sums) to `out` with coherent stores.  Must be called
-// by all threads; the tiles in LDS are dead afterwards.  The accumulators are only read: one band
-// of 32 key features at a time, every wave lays its four blocks out in [k][v] order (16 KB each),
-// then all threads add the four copies and store the band.
+// by all threads; the tiles and tables in LDS are dead afterwards.
+//
+// Two exchanges in the registers' own layout, each halving what a wave still owns: waves w and w ^ 2
+// swap the halves of S the other one keeps (32 KB each way) and add, then w and w ^ 1 swap one band
+// of 32 key features (16 KB).  Wave w ends with band w of the sum and stores it straight from its
+// accumulators, 32 consecutive floats of two rows per instruction.  Because block r of wave w holds
+// key block r ^ w (see WideAcc), the blocks that go out are blocks 2, 3 and then block 1 in every
+// wave, and a parcel's block meets the same key features at the receiver: one code path, whose only
+// dependence on the wave is in addresses.  192 KB go through LDS in 16-byte words; laying all four
+// states out row-major and re-reading them (256 KB of 4-byte writes, which move 64 bytes a clock, and
+// as much again in reads) took 4.8 us of a 22 us kernel.
+// A wave's second parcel goes where it read its first (nobody else touches that region any more),
+// so the exchanges need one barrier each.
 __device__ __forceinline__ void wide_state_wg_reduce_store(WideAcc &acc, unsigned char *lds, int wave, int lane, int d,
                                                            float *__restrict__ out)
 {
-    float *band = reinterpret_cast<float *>(lds);               // [wave][32 rows][128 columns]
     float *zs = reinterpret_cast<float *>(lds + kWideZOffset);  // [wave][128]
     // key sums: lanes with equal lane % 16 hold the same eight features
 #pragma unroll
@@ -198,34 +254,36 @@ __device__ __forceinline__ void wide_state_wg_reduce_store(WideAcc &acc, unsigne
 #pragma unroll
         for (int e = 0; e < 8; ++e) zs[wave * 128 + lane * 8 + e] = acc.z[e];
     }
+    unsigned char *mine = lds + wave * kWideParcelBytes, *theirs = lds + (wave ^ 2) * kWideParcelBytes;
+    const unsigned char *from = lds + (wave ^ 3) * kWideParcelBytes;   // where wave ^ 1 read its first parcel
+    // with wave ^ 2: blocks 2, 3 go out; what comes in belongs to blocks 0, 1
+#pragma unroll
+    for (int rr = 0; rr < 2; ++rr)
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb) wide_send(mine, 4 * rr + cb, acc.s[2 + rr][cb], lane);
+    lds_barrier();                                  // LDS only
+    f32x16 h[2][4], fin[4];
+    wide_recv_add<8>(theirs, lane, [&](int b) -> const f32x16 & { return acc.s[b >> 2][b & 3]; },
+                     [&](int b) -> f32x16 & { return h[b >> 2][b & 3]; });
+    // with wave ^ 1: block 1 goes out (`theirs` is this wave's to overwrite now), block 0 is band `wave`
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb) wide_send(theirs, cb, h[1][cb], lane);
+    lds_barrier();
+    wide_recv_add<4>(from, lane, [&](int b) -> const f32x16 & { return h[0][b]; },
+                     [&](int b) -> f32x16 & { return fin[b]; });
+    // element i of block cb: row 32 wave + 8 (i / 4) + 4 (lane / 32) + i % 4, column 32 cb + lane % 32.
+    // Rows past d lie past the resource's end, columns past d are sent there: both are dropped.
     const int n = lane & 31, g = lane >> 5;
-    const int half = d / 2;                            // 8-byte units per row of S
+    const rsrc_t rS = make_rsrc(out, (uint32_t)d * (uint32_t)d * 4u);
+    const uint32_t base = ((uint32_t)(32 * wave + 4 * g) * (uint32_t)d + (uint32_t)n) * 4u;
 #pragma unroll
-    for (int rb = 0; rb < 4; ++rb) {
-        float *mine = band + wave * (32 * 128);
+    for (int cb = 0; cb < 4; ++cb) {
+        const uint32_t col = 32 * cb + n < d ? base + 128u * cb : kOutOfRange;
 #pragma unroll
-        for (int cb = 0; cb < 4; ++cb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i)
-                mine[(8 * (i >> 2) + 4 * g + (i & 3)) * 128 + 32 * cb + n] = acc.s[rb][cb][i];
-        lds_barrier();                                 // LDS only: the stores of earlier bands stay in flight
-        // thread t: 8-byte unit t % 64 of rows t / 64 + 4 j of the band (no divisions; a wave stores whole rows)
-        const int cu = threadIdx.x & 63, r0 = threadIdx.x >> 6;
-        if (cu < half) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int k = r0 + 4 * j;
-                if (32 * rb + k < d) {
-                    const float *p = band + k * 128 + 2 * cu;
-                    const f32x2 x0 = *reinterpret_cast<const f32x2 *>(p), x1 = *reinterpret_cast<const f32x2 *>(p + 32 * 128),
-                                x2 = *reinterpret_cast<const f32x2 *>(p + 2 * 32 * 128),
-                                x3 = *reinterpret_cast<const f32x2 *>(p + 3 * 32 * 128);
-                    store_coherent(out + (size_t)(32 * rb + k) * d + 2 * cu, (x0 + x2) + (x1 + x3));
-                }
-            }
-        }
-        lds_barrier();                                 // the band is read before the next one is laid out
+        for (int i = 0; i < 16; ++i)
+            store_coherent4(rS, col + (uint32_t)(8 * (i >> 2) + (i & 3)) * (uint32_t)d * 4u, fin[cb][i]);
     }
+    const int half = d / 2;
     for (int u = threadIdx.x; u < half; u += 4 * kWave) {
         const int k = 2 * u;
         f32x2 x;
@@ -269,7 +327,7 @@ __global__ __launch_bounds__(256, 1) void state_mfma_wide(
         wg_barrier();
     }
     unsigned char *tileK = lds + wave * 2 * kWideTileBytes, *tileV = tileK + kWideTileBytes;
-    wide_state_accumulate(stream, tileK, tileV, lane, acc);
+    wide_state_accumulate(stream, tileK, tileV, wave, lane, acc);
 
     float *partials = static_cast<float *>(ws) + (size_t)bh * kMaxChunks * elems;
     wide_state_wg_reduce_store(acc, lds, wave, lane, d, partials + (size_t)c * elems);
