@@ -89,6 +89,7 @@ template <int ROPE> struct Kernels<64, ROPE> {
     // workgroups launched per compute unit: the plain kernel's are short-lived and queue up (see apply_mfma_d64);
     // the RoPE kernels hold more registers and, with factored tables, fill their tables per workgroup
     static constexpr int apply_wgs_per_cu = ROPE == kRopeNone ? 8 : 1;
+    static constexpr int apply_wgs_per_cu_short = apply_wgs_per_cu, apply_short_steps = 0;   // no other form for short ranges
 };
 template <int ROPE> struct Kernels<128, ROPE> {
     static constexpr int W = 1;
@@ -111,6 +112,8 @@ template <int ROPE> struct Kernels<128, ROPE> {
     // workgroups per compute unit: with one 128 x 32 panel per wave (136-164 registers, 17-50 KB of LDS) three are
     // resident; with a full rotation table two (three measured 98 against 89 us: its rows crowd the caches)
     static constexpr int apply_wgs_per_cu = kCoopApplyNB != 1 ? 8 / (kCoopApplyWaves * kCoopApplyNB) : ROPE == kRopeTable ? 2 : 3;
+    // ranges of fewer than apply_short_steps steps per workgroup: two per compute unit (see enqueue_apply)
+    static constexpr int apply_wgs_per_cu_short = apply_wgs_per_cu < 2 ? apply_wgs_per_cu : 2, apply_short_steps = 6;
 };
 
 template <int DP, int ROPE> void init_kernels(Device &d)
@@ -383,6 +386,11 @@ sv_status enqueue_apply(const void *Q, const Rope &rope, const Shape &s, int t0,
             using KN = decltype(kn);
             int C = KN::apply_wgs_per_cu * dev.num_cu / s.BH;
             const int steps = (n + KN::apply_wg_tokens - 1) / KN::apply_wg_tokens;
+            // Short ranges: every workgroup starts by fetching its panels of S, so with only a few steps each,
+            // fewer and longer ones win (d = 112, 20 heads, 4 680 tokens: two per compute unit 15.1 against
+            // 15.8-16.2 us with three; level at 10 800 tokens, three ahead from there on).
+            if (KN::apply_wgs_per_cu_short < KN::apply_wgs_per_cu && steps < KN::apply_short_steps * C)
+                C = KN::apply_wgs_per_cu_short * dev.num_cu / s.BH;
             if (C > steps) C = steps;
             // Full rotation table: consecutive workgroup ids go round the dies, so with a multiple of the die
             // count per head, workgroup c of every head runs on die c mod 8 and the table rows of its tiles
